@@ -1,0 +1,149 @@
+/*
+ * libdlf — fused-layer CNN inference on one MI355X (gfx950).
+ *
+ * A network is given as a linear layer list; dlf_plan() partitions it into contiguous fusion
+ * groups and gives each group a workgroup budget; dlf_run() executes the plan with one kernel
+ * launch per group, intermediate feature maps of a group staying on-chip (LDS).
+ *
+ * This is the execution model the paper tunes (Sec. II-A.2: the two knobs "number of cores" and
+ * "layer fusion"; Sec. III-B: a fused block keeps intermediates on chip and pays for it with
+ * halo recomputation; Algorithm 1: inputs = layer list, number of layers, OpCount_critical,
+ * outputs = fusion_partition_index[], mp_of_fusionblock[]).  Here "cores" are persistent
+ * workgroups of the GPU.
+ *
+ * Conventions
+ *   - Every call returns a dlf_status; out-parameters are written only on DLF_OK.  Nothing
+ *     throws or aborts across this boundary.  dlf_last_error() gives a thread-local message.
+ *   - Activations are NHWC fp16, [batch][H][W][C], in DEVICE memory owned by the caller.
+ *   - Weights/biases passed to dlf_net_create are HOST pointers, borrowed only for the duration
+ *     of the call (the library repacks them into its own device buffers).
+ *   - dlf_run is asynchronous on the given HIP stream and never synchronises or allocates.
+ */
+#ifndef DLF_H
+#define DLF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DLF_OK = 0,
+    DLF_ERR_INVALID_ARG = 1,  /* null pointer, negative size, bad enum value                  */
+    DLF_ERR_SHAPE = 2,        /* layer list does not shape-check                               */
+    DLF_ERR_UNSUPPORTED = 3,  /* valid network, but no kernel implements this layer            */
+    DLF_ERR_INFEASIBLE = 4,   /* a requested fusion group does not fit on-chip memory          */
+    DLF_ERR_OOM = 5,          /* host or device allocation failed, or workspace too small      */
+    DLF_ERR_HIP = 6,          /* a HIP runtime call failed (see dlf_last_error)                */
+    DLF_ERR_NO_WEIGHTS = 7    /* dlf_run on a shape-only network                               */
+} dlf_status;
+
+typedef enum { DLF_CONV = 0, DLF_DWCONV = 1, DLF_FC = 2, DLF_MAXPOOL = 3, DLF_GLOBAL_AVGPOOL = 4 } dlf_op;
+typedef enum { DLF_ACT_NONE = 0, DLF_ACT_RELU = 1, DLF_ACT_RELU6 = 2 } dlf_act;
+
+/* One layer.  Convolution is cross-correlation with zero padding; the operation count of a
+ * layer is Eq. 1 (convolution: 2*Hout*Wout*Hk*Wk*Cin*Cout) or Eq. 2 (FC: 2*M*K*N, M = batch). */
+typedef struct {
+    int32_t op;            /* dlf_op                                                            */
+    int32_t cin, cout;     /* channels (pooling: cin == cout; depthwise: cin == cout)           */
+    int32_t kh, kw;        /* kernel size (FC, global avgpool: 1)                               */
+    int32_t stride, pad;   /* spatial stride; symmetric padding (0 for conv, -inf for maxpool)  */
+    int32_t has_bias;      /* 1: add bias[cout] (a folded batch-norm shift)                     */
+    int32_t act;           /* dlf_act; applied after the residual add if there is one           */
+    int32_t input_from;    /* -1: previous layer (net input for layer 0); else a layer index    */
+    int32_t residual_from; /* -1: none; else index of the layer whose output is added           */
+    const void* weight;    /* HOST fp16 [cout][kh][kw][cin] (depthwise: [cout][kh][kw][1];      */
+                           /* FC: [cout][cin], cin flattened in h,w,c order); NULL => shape-only */
+    const float* bias;     /* HOST fp32 [cout], or NULL                                         */
+} dlf_layer_desc;
+
+typedef struct dlf_net_s dlf_net_t;
+typedef struct dlf_plan_s dlf_plan_t;
+
+/* Tuner modes. */
+enum { DLF_TUNER_DP = 0,      /* exact minimum of the additive cost model over all plans        */
+       DLF_TUNER_GREEDY = 1,  /* Algorithm 1 (greedy O(n) pass), then split of infeasible blocks */
+       DLF_TUNER_MANUAL = 2   /* caller gives group_last[] and budget[]                          */ };
+
+typedef struct {
+    int32_t mode;                     /* DLF_TUNER_*                                             */
+    const int32_t* budgets;           /* allowed workgroup budgets; NULL => {32,64,128,256}      */
+    int32_t n_budgets;
+    double opcount_critical;          /* Algorithm 1: operations per workgroup at which a block  */
+                                      /* is closed; <= 0 => library default                      */
+    double alpha, beta;               /* Eq. 5 weights of log2(C) and log2(OpCount); both 0 =>   */
+                                      /* the paper's 0.316 / 0.659                               */
+    double mp_scale, mp_offset;       /* Eq. 5 is a proportionality: MP = scale*score + offset;  */
+                                      /* both 0 => library default                               */
+    const int32_t* manual_group_last; /* DLF_TUNER_MANUAL: index of the last layer of each group */
+    const int32_t* manual_budget;     /* DLF_TUNER_MANUAL: budget of each group                  */
+    int32_t manual_n;                 /* number of manual groups                                 */
+    int32_t max_lds_bytes;            /* on-chip memory one workgroup may use; <= 0 => 160 KiB   */
+} dlf_tuner_opts;
+
+/* Builds a network from `n` layers on an in_h x in_w x in_c input.  Validates and infers
+ * shapes.  If every conv/depthwise/FC layer has a weight pointer, weights are repacked and
+ * uploaded to the current HIP device (needs a GPU); if all weight pointers are NULL the result
+ * is a shape-only network that can be planned but not run (works without a GPU). */
+dlf_status dlf_net_create(const dlf_layer_desc* layers, int32_t n, int32_t in_h, int32_t in_w,
+                          int32_t in_c, dlf_net_t** out);
+void dlf_net_destroy(dlf_net_t* net);
+int32_t dlf_net_num_layers(const dlf_net_t* net);
+/* Output shape and operation count (Eq. 1 / Eq. 2 at batch 1; 0 for pooling) of layer i. */
+dlf_status dlf_net_layer_info(const dlf_net_t* net, int32_t i, int32_t* out_h, int32_t* out_w,
+                              int32_t* out_c, uint64_t* op_count);
+
+/* Chooses fusion groups and budgets for `batch` images (Algorithm 1's outputs
+ * fusion_partition_index[] and mp_of_fusionblock[]); opts == NULL => DLF_TUNER_DP defaults. */
+dlf_status dlf_plan(const dlf_net_t* net, int32_t batch, const dlf_tuner_opts* opts,
+                    dlf_plan_t** out);
+void dlf_plan_destroy(dlf_plan_t* plan);
+int32_t dlf_plan_num_groups(const dlf_plan_t* plan);
+/* Group g covers layers [*first, *last]; *budget workgroups; tile_h x tile_w output pixels per
+ * workgroup step; model_cost in picoseconds of the cost model. Any out pointer may be NULL. */
+dlf_status dlf_plan_group(const dlf_plan_t* plan, int32_t g, int32_t* first, int32_t* last,
+                          int32_t* budget, int32_t* tile_h, int32_t* tile_w, uint64_t* model_cost);
+/* Cost-model value (picoseconds) of running layers [first,last] as one group with `budget`
+ * workgroups at the plan's batch; DLF_ERR_INFEASIBLE if the group cannot be executed. */
+dlf_status dlf_group_cost(const dlf_net_t* net, int32_t batch, int32_t first, int32_t last,
+                          int32_t budget, int32_t max_lds_bytes, uint64_t* cost);
+/* Device bytes needed for the activations that cross group boundaries. */
+size_t dlf_plan_workspace_bytes(const dlf_plan_t* plan);
+/* Gives the plan its workspace (DEVICE pointer, caller-owned, 256-byte aligned, must outlive the
+ * plan's runs).  A plan runs on one stream at a time per workspace. */
+dlf_status dlf_plan_bind_workspace(dlf_plan_t* plan, void* dev_ptr, size_t bytes);
+/* Runs the whole plan: in_dev [batch][in_h][in_w][in_c] fp16, out_dev = output of the last layer,
+ * both DEVICE pointers that must not alias; hip_stream is a hipStream_t (NULL = default stream).
+ * Asynchronous; reports launch errors only. */
+dlf_status dlf_run(const dlf_plan_t* plan, const void* in_dev, void* out_dev, void* hip_stream);
+/* Runs only group g: in_dev = the group's input tensor, out_dev = its output tensor; a residual
+ * operand produced outside the group is read from res_dev (may be NULL if the group has none). */
+dlf_status dlf_run_group(const dlf_plan_t* plan, int32_t g, const void* in_dev, const void* res_dev,
+                         void* out_dev, void* hip_stream);
+/* Device address inside the bound workspace of the output of layer i, or NULL if that tensor is
+ * never materialised (it lives only on-chip) or is the network output. */
+const void* dlf_plan_layer_output(const dlf_plan_t* plan, int32_t layer);
+
+/* Kernel configuration chosen for group g: kind (0 fused-group kernel, 1 FC, 2 global avgpool),
+ * register-tile variant, channel slices, channels per slice, whether stage 0 streams its input,
+ * LDS bytes per workgroup.  Any out pointer may be NULL. */
+dlf_status dlf_plan_group_config(const dlf_plan_t* plan, int32_t g, int32_t* kind, int32_t* variant,
+                                 int32_t* nslices, int32_t* slice_c, int32_t* stream0,
+                                 int32_t* lds_bytes);
+/* Testing hook: th > 0 forces tile th x tw, register-tile variant, channel slicing and streaming
+ * for every group planned afterwards (groups it does not fit become infeasible); th = 0 restores
+ * the automatic choice.  Process-wide, not thread-safe. */
+void dlf_debug_force_config(int32_t th, int32_t tw, int32_t variant, int32_t nslices,
+                            int32_t slice_c, int32_t stream0);
+
+const char* dlf_status_string(dlf_status s);
+const char* dlf_last_error(void);
+/* Version of the cost-model definition implemented by dlf_group_cost. */
+int32_t dlf_cost_model_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DLF_H */

@@ -1,0 +1,1029 @@
+// Host side of libdlf: network object, weight repacking, fusion-group construction, cost model,
+// tuner (exact DP, Algorithm-1 greedy, manual) and the launch loop.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/dlf.h"
+#include "dlf_internal.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+dlf_status fail(dlf_status s, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return s;
+}
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline int round_up(int a, int b) { return ceil_div(a, b) * b; }
+
+struct Layer {
+    dlf_layer_desc d;
+    int in_h, in_w, in_c;     // input tensor shape
+    int out_h, out_w, out_c;  // output tensor shape
+    int src;                  // producer of the input (-1 = net input)
+    uint64_t macs;            // multiply-accumulates at batch 1
+    // packed parameters (device)
+    void* d_w = nullptr;
+    float* d_bias = nullptr;
+    int kc = 0, cin_pad = 0, ncb = 0, nsteps = 0;
+};
+
+}  // namespace
+
+struct dlf_net_s {
+    std::vector<Layer> L;
+    int in_h, in_w, in_c;
+    bool has_weights;
+};
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// Weight repacking
+// ------------------------------------------------------------------------------------------
+
+// MFMA "A" fragments for v_mfma_f32_32x32x16_f16: for output-channel block cb (32 channels) and
+// K step t, lane l holds W[cb*32 + l%32][k(t) + (l/32)*8 + j], j = 0..7.  Steps run in the
+// order the kernel consumes them: input-channel chunk (kc channels) -> filter tap -> 16-channel
+// sub-step inside the chunk.
+void pack_conv_weights(const uint16_t* w, int cout, int taps, int cin, int kc, int cin_pad,
+                       std::vector<uint16_t>& out)
+{
+    const int ncb = ceil_div(cout, 32), nchunks = cin_pad / kc, nks = kc / 16;
+    const size_t nsteps = (size_t)nchunks * taps * nks;
+    out.assign((ncb * nsteps + 2) * 512, 0);
+    for (int cb = 0; cb < ncb; ++cb)
+        for (int chunk = 0; chunk < nchunks; ++chunk)
+            for (int tap = 0; tap < taps; ++tap)
+                for (int ks = 0; ks < nks; ++ks) {
+                    const size_t step = ((size_t)chunk * taps + tap) * nks + ks;
+                    uint16_t* dst = &out[(cb * nsteps + step) * 512];
+                    for (int lane = 0; lane < 64; ++lane) {
+                        const int co = cb * 32 + (lane & 31);
+                        if (co >= cout) continue;
+                        const int ci0 = chunk * kc + ks * 16 + (lane >> 5) * 8;
+                        const uint16_t* src = w + ((size_t)co * taps + tap) * cin;
+                        for (int j = 0; j < 8; ++j)
+                            if (ci0 + j < cin) dst[lane * 8 + j] = src[ci0 + j];
+                    }
+                }
+}
+
+dlf_status upload(const void* host, size_t bytes, void** dev)
+{
+    hipError_t e = hipMalloc(dev, bytes);
+    if (e != hipSuccess) return fail(DLF_ERR_OOM, "hipMalloc(%zu): %s", bytes, hipGetErrorString(e));
+    e = hipMemcpy(*dev, host, bytes, hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail(DLF_ERR_HIP, "hipMemcpy: %s", hipGetErrorString(e));
+    return DLF_OK;
+}
+
+bool g_kernels_ready = false;
+
+dlf_status pack_and_upload(Layer& L)
+{
+    const dlf_layer_desc& d = L.d;
+    if (d.op == DLF_CONV || d.op == DLF_FC) {
+        std::vector<uint16_t> packed;
+        const int taps = d.kh * d.kw;
+        pack_conv_weights((const uint16_t*)d.weight, d.cout, taps, d.cin, L.kc, L.cin_pad, packed);
+        dlf_status s = upload(packed.data(), packed.size() * 2, &L.d_w);
+        if (s != DLF_OK) return s;
+        std::vector<float> b((size_t)L.ncb * 32, 0.0f);
+        if (d.has_bias && d.bias) std::copy(d.bias, d.bias + d.cout, b.begin());
+        return upload(b.data(), b.size() * 4, (void**)&L.d_bias);
+    }
+    if (d.op == DLF_DWCONV) {
+        const int taps = d.kh * d.kw, cp = L.cin_pad;
+        std::vector<uint16_t> w((size_t)taps * cp, 0);
+        const uint16_t* src = (const uint16_t*)d.weight;
+        for (int c = 0; c < d.cout; ++c)
+            for (int t = 0; t < taps; ++t) w[(size_t)t * cp + c] = src[(size_t)c * taps + t];
+        dlf_status s = upload(w.data(), w.size() * 2, &L.d_w);
+        if (s != DLF_OK) return s;
+        std::vector<float> b((size_t)cp, 0.0f);
+        if (d.has_bias && d.bias) std::copy(d.bias, d.bias + d.cout, b.begin());
+        return upload(b.data(), b.size() * 4, (void**)&L.d_bias);
+    }
+    return DLF_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Fusion groups
+// ------------------------------------------------------------------------------------------
+
+enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2 };
+
+struct TileCfg {
+    int th, tw;      // tile of the group's final output tensor
+    int variant;     // register tile of CONV stages
+    int nslices, slice_c;
+    int stream0;
+};
+
+struct GroupPlan {
+    int first = 0, last = 0, budget = 0;
+    int kind = GK_GROUP;
+    int variant = 0, lds_bytes = 0, grid = 0;
+    int th = 0, tw = 0;
+    uint64_t cost = 0;
+    int in_layer = -1;   // producer of the group's input (-1 = net input)
+    int res_layer = -2;  // producer of a residual operand read from HBM (-2 = none)
+    int res_stage = -1;
+    DlfGroupArgs ga;
+    DlfFcArgs fa;
+    DlfGapArgs pa;
+};
+
+const int VAR_FC[5] = {2, 2, 1, 1, 4};
+const int VAR_FP[5] = {4, 2, 4, 2, 2};
+
+// Hardware constants of the cost model (MI355X: 256 CUs, 2.4 GHz, HBM 8 TB/s).
+const int64_t PS_PER_CYCLE = 417;
+const int64_t HBM_BYTES_PER_CYCLE = 3333;   // 8 TB/s at 2.4 GHz, whole chip
+const int64_t WG_BYTES_PER_CYCLE = 48;      // what one workgroup can pull from HBM / L2
+const int64_t L2_BYTES_PER_CYCLE = 8192;    // aggregate L2 -> CU bandwidth
+const int64_t LAUNCH_CYCLES = 9600;         // 4 us per kernel launch
+const int64_t TILE_CYCLES = 1500;           // per-tile fixed overhead (address setup, drain)
+const int64_t STAGE_CYCLES = 600;           // per-stage barrier / pipeline fill
+const int64_t MFMA_CYCLES = 32;             // one 32x32x16 MFMA on one SIMD
+const int64_t VALU_ITEM_CYCLES = 10;        // cycles per (pixel, 8 channels, tap) work item / 64 lanes
+
+struct StageSpec {   // one stage, before tiling
+    int layer;
+    int kind;
+    int pool2;
+    int pool_layer;  // layer index of the folded pool, or -1
+};
+
+bool is_pool2(const dlf_layer_desc& d)
+{
+    return d.op == DLF_MAXPOOL && d.kh == 2 && d.kw == 2 && d.stride == 2 && d.pad == 0;
+}
+
+// Can layers [first,last] form one group?  Returns the stage list.
+bool group_stages(const dlf_net_s& net, int first, int last, std::vector<StageSpec>& st, int& kind,
+                  std::string& why)
+{
+    st.clear();
+    const Layer& L0 = net.L[first];
+    if (L0.d.op == DLF_FC || L0.d.op == DLF_GLOBAL_AVGPOOL) {
+        if (first != last) { why = "FC / global pooling layers run as their own group"; return false; }
+        kind = (L0.d.op == DLF_FC) ? GK_FC : GK_GAP;
+        return true;
+    }
+    kind = GK_GROUP;
+    for (int i = first; i <= last; ++i) {
+        const Layer& L = net.L[i];
+        const dlf_layer_desc& d = L.d;
+        if (d.op == DLF_FC || d.op == DLF_GLOBAL_AVGPOOL) { why = "FC / global pooling inside a group"; return false; }
+        if (i > first && L.src != i - 1) { why = "layer input is not the previous layer of the group"; return false; }
+        if (d.residual_from >= first && d.residual_from <= last) { why = "residual operand produced inside the group"; return false; }
+        if (d.residual_from >= 0 && d.op != DLF_CONV) { why = "residual add on a non-convolution layer"; return false; }
+        // a tensor produced inside the group (except the last) must not be used outside it
+        if (i < last) {
+            for (size_t j = 0; j < net.L.size(); ++j) {
+                if ((int)j == i + 1) {
+                    if (net.L[j].d.residual_from == i) { why = "intermediate used as residual"; return false; }
+                    continue;
+                }
+                if (net.L[j].src == i || net.L[j].d.residual_from == i) { why = "intermediate tensor is used outside the group"; return false; }
+            }
+        }
+        StageSpec s;
+        s.layer = i;
+        s.pool2 = 0;
+        s.pool_layer = -1;
+        if (d.op == DLF_CONV) {
+            s.kind = DLF_ST_CONV;
+            if (d.cout % 4 != 0) { why = "convolution output channels must be a multiple of 4"; return false; }
+            if (i + 1 <= last && is_pool2(net.L[i + 1].d) && (L.out_h % 2 == 0) && (L.out_w % 2 == 0)
+                && d.residual_from < 0) {
+                // the pooled tensor replaces the convolution output: that output must be unused
+                bool used = false;
+                for (size_t j = 0; j < net.L.size(); ++j)
+                    if ((int)j != i + 1 && (net.L[j].src == i || net.L[j].d.residual_from == i)) used = true;
+                if (net.L[i + 1].src == i && !used) {
+                    s.pool2 = 1;
+                    s.pool_layer = i + 1;
+                }
+            }
+        } else if (d.op == DLF_DWCONV) {
+            s.kind = DLF_ST_DW;
+            if (d.cin % 8 != 0) { why = "depthwise channels must be a multiple of 8"; return false; }
+        } else {
+            s.kind = DLF_ST_MAXPOOL;
+            if (d.cin % 8 != 0) { why = "pooling channels must be a multiple of 8"; return false; }
+            if (d.pad >= d.kh) { why = "pooling pad must be smaller than the window"; return false; }
+        }
+        st.push_back(s);
+        if (s.pool2) ++i;
+    }
+    if ((int)st.size() > DLF_MAX_STAGES) { why = "too many stages"; return false; }
+    // a CONV stage after stage 0 needs all its input channels in LDS: VALU producers must
+    // write a multiple of the consumer's chunk size
+    for (size_t k = 1; k < st.size(); ++k) {
+        if (st[k].kind == DLF_ST_CONV && st[k - 1].kind != DLF_ST_CONV) {
+            const Layer& C = net.L[st[k].layer];
+            if (C.d.cin % C.kc != 0) { why = "channel count not a multiple of the K chunk"; return false; }
+        }
+    }
+    return true;
+}
+
+struct Built {
+    bool ok = false;
+    int lds_bytes = 0;
+    int ntiles = 0;
+    int64_t tile_cycles = 0;      // modelled cycles one workgroup spends per tile (compute side)
+    int64_t tile_hbm_bytes = 0;   // activation bytes per tile (HBM side)
+    int64_t tile_l2_bytes = 0;    // weight bytes per tile (L2 side)
+    DlfGroupArgs ga;
+};
+
+// Builds the kernel arguments of a group for one tiling choice; ok=false if it does not fit.
+Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int batch,
+                  const TileCfg& tc, int max_lds)
+{
+    Built b;
+    DlfGroupArgs& ga = b.ga;
+    memset(&ga, 0, sizeof ga);
+    const int ns = (int)specs.size();
+    const Layer& Lfirst = net.L[specs[0].layer];
+    const StageSpec& slast = specs[ns - 1];
+    const Layer& Llast = net.L[slast.pool2 ? slast.pool_layer : slast.layer];
+    const int FCv = VAR_FC[tc.variant], FPv = VAR_FP[tc.variant];
+    ga.nstages = ns;
+    ga.stream0 = tc.stream0;
+    ga.batch = batch;
+    ga.in_h = Lfirst.in_h; ga.in_w = Lfirst.in_w; ga.in_c = Lfirst.in_c;
+    ga.out_h = Llast.out_h; ga.out_w = Llast.out_w; ga.out_c = Llast.out_c;
+    ga.th = tc.th; ga.tw = tc.tw;
+    ga.tiles_y = ceil_div(ga.out_h, tc.th);
+    ga.tiles_x = ceil_div(ga.out_w, tc.tw);
+    ga.nslices = tc.nslices;
+    ga.slice_c = tc.slice_c;
+    ga.ntiles = batch * ga.tiles_y * ga.tiles_x * tc.nslices;
+    b.ntiles = ga.ntiles;
+
+    // backward region propagation
+    int my = 1, oy = 0, mx = 1, ox = 0, h = tc.th, w = tc.tw;
+    for (int s = ns - 1; s >= 0; --s) {
+        const Layer& L = net.L[specs[s].layer];
+        DlfStage& st = ga.st[s];
+        st.kind = specs[s].kind;
+        st.pool2 = specs[s].pool2;
+        if (st.pool2) { my *= 2; oy *= 2; mx *= 2; ox *= 2; h *= 2; w *= 2; }
+        st.cin = L.d.cin; st.cout = L.d.cout;
+        st.kh = L.d.kh; st.kw = L.d.kw; st.stride = L.d.stride; st.pad = L.d.pad; st.act = L.d.act;
+        st.in_h = L.in_h; st.in_w = L.in_w; st.out_h = L.out_h; st.out_w = L.out_w;
+        st.rh = h; st.rw = w;
+        st.oy_mul = my; st.oy_off = oy; st.ox_mul = mx; st.ox_off = ox;
+        st.ih = (h - 1) * st.stride + st.kh;
+        st.iw = (w - 1) * st.stride + st.kw;
+        my *= st.stride; oy = oy * st.stride - st.pad;
+        mx *= st.stride; ox = ox * st.stride - st.pad;
+        h = st.ih; w = st.iw;
+        st.w = L.d_w; st.bias = L.d_bias; st.res = nullptr;
+        if (st.kind == DLF_ST_CONV) {
+            st.kc = L.kc; st.cin_pad = L.cin_pad; st.ncb = L.ncb; st.nsteps = L.nsteps;
+        } else {
+            st.kc = 8; st.cin_pad = round_up(L.d.cin, 8); st.ncb = 0; st.nsteps = 0;
+        }
+    }
+    ga.iy_mul = my; ga.iy_off = oy; ga.ix_mul = mx; ga.ix_off = ox;
+
+    // slicing rules
+    if (tc.nslices > 1) {
+        for (int s = 1; s < ns; ++s)
+            if (ga.st[s].kind == DLF_ST_CONV) return b;  // later CONV stages need every channel
+        if (ga.st[0].kind == DLF_ST_CONV && (tc.slice_c % 32) != 0) return b;
+        if ((tc.slice_c % 8) != 0) return b;
+        const int cslice = ga.st[0].kind == DLF_ST_CONV ? ga.st[0].cout : ga.st[0].cin;
+        if ((int64_t)tc.nslices * tc.slice_c < cslice) return b;   // slices must cover every channel
+    }
+    if ((int64_t)batch * ga.in_h * ga.in_w * ga.in_c >= (int64_t)1 << 31) return b;   // 32-bit offsets
+    const int chan_local = (tc.nslices > 1) ? tc.slice_c : 0;   // 0 = all channels
+
+    // LDS layout: stage s reads buffer s, writes buffer s+1; even buffers share one area,
+    // odd buffers the other.
+    int64_t area[2] = {0, 0};
+    std::vector<int64_t> bufsz(ns + 1, 0);
+    for (int s = 0; s < ns; ++s) {
+        DlfStage& st = ga.st[s];
+        int cs;
+        if (st.kind == DLF_ST_CONV) {
+            cs = (s == 0 && tc.stream0) ? st.kc + DLF_CPAD : st.cin_pad + DLF_CPAD;
+        } else {
+            const int c = chan_local ? chan_local : st.cin;
+            cs = round_up(c, 8) + DLF_CPAD;
+        }
+        st.in_cs = cs;
+        if (s > 0) ga.st[s - 1].out_cs = cs;
+        int64_t sz = (int64_t)st.ih * st.iw * cs;
+        if (s == 0 && tc.stream0) {
+            st.stream_buf = (int)sz;
+            sz *= 2;
+            if ((int64_t)st.ih * st.iw * (st.kc / 8) > (int64_t)DLF_STAGE_VECS * DLF_WG_THREADS) return b;
+        }
+        bufsz[s] = sz;
+        area[s & 1] = std::max(area[s & 1], sz);
+    }
+    // consistency: what stage s writes must be what stage s+1 reads
+    for (int s = 0; s + 1 < ns; ++s) {
+        const DlfStage& p = ga.st[s];
+        const DlfStage& c = ga.st[s + 1];
+        const int ph = p.pool2 ? p.rh / 2 : p.rh, pw = p.pool2 ? p.rw / 2 : p.rw;
+        if (ph != c.ih || pw != c.iw) return b;
+        if (p.pool2 && ((p.oy_off & 1) || (p.ox_off & 1) || (p.rh & 1) || (p.rw & 1))) return b;
+    }
+    if (ga.st[ns - 1].pool2 && ((tc.th * 2 != ga.st[ns - 1].rh))) return b;
+    for (int s = 0; s < ns; ++s) {
+        ga.st[s].in_off = (s & 1) ? (int)area[0] : 0;
+        ga.st[s].out_off = ((s + 1) & 1) ? (int)area[0] : 0;
+    }
+    const int64_t lds_halfs = area[0] + area[1];
+    if (lds_halfs * 2 > max_lds) return b;
+    b.lds_bytes = (int)(lds_halfs * 2);
+
+    // work per tile
+    int64_t mfma = 0, valu = 0, l2 = 0;
+    for (int s = 0; s < ns; ++s) {
+        const DlfStage& st = ga.st[s];
+        const int npix = st.rh * st.rw;
+        if (st.kind == DLF_ST_CONV) {
+            const int npb = ceil_div(npix, 32), n_pg = ceil_div(npb, FPv);
+            int cbs = st.ncb;
+            if (tc.nslices > 1) cbs = std::min(st.ncb, tc.slice_c / 32);
+            const int n_cg = ceil_div(cbs, FCv);
+            const int nitems = n_pg * n_cg;
+            if (s == 0 && tc.stream0 && nitems > DLF_WAVES) return b;
+            const int64_t steps = st.nsteps;
+            mfma += (int64_t)ceil_div(nitems, DLF_WAVES) * steps * FCv * FPv * MFMA_CYCLES;
+            l2 += (int64_t)nitems * FCv * steps * 1024;
+        } else {
+            const int c = chan_local ? chan_local : st.cout;
+            const int64_t items = (int64_t)npix * ceil_div(c, 8);
+            valu += ceil_div((int)std::min<int64_t>(items, 1 << 30), 64) * (int64_t)(st.kh * st.kw)
+                    * VALU_ITEM_CYCLES / DLF_WAVES;
+        }
+    }
+    const DlfStage& s0 = ga.st[0];
+    const int cin0 = (s0.kind != DLF_ST_CONV && chan_local) ? chan_local : s0.cin;
+    const int cout_l = chan_local ? std::min(chan_local, ga.out_c) : ga.out_c;
+    b.tile_hbm_bytes = (int64_t)s0.ih * s0.iw * cin0 * 2 + (int64_t)tc.th * tc.tw * cout_l * 2;
+    b.tile_l2_bytes = l2;
+    b.tile_cycles = mfma + valu + TILE_CYCLES + (int64_t)ns * STAGE_CYCLES;
+    b.ok = true;
+    return b;
+}
+
+// Cost-model time of a built group with `budget` workgroups, in picoseconds.
+uint64_t group_cost_ps(const Built& b, int budget)
+{
+    const int64_t nwg = std::min<int64_t>(budget, b.ntiles);
+    const int64_t rounds = ceil_div(b.ntiles, (int)nwg);
+    const int64_t hbm_bw = std::min<int64_t>(WG_BYTES_PER_CYCLE, std::max<int64_t>(1, HBM_BYTES_PER_CYCLE / nwg));
+    const int64_t l2_bw = std::min<int64_t>(WG_BYTES_PER_CYCLE, std::max<int64_t>(1, L2_BYTES_PER_CYCLE / nwg));
+    const int64_t mem = b.tile_hbm_bytes / hbm_bw + b.tile_l2_bytes / l2_bw;
+    const int64_t tile = std::max(b.tile_cycles, mem + TILE_CYCLES);
+    return (uint64_t)((LAUNCH_CYCLES + rounds * tile) * PS_PER_CYCLE);
+}
+
+// Testing hook: when th > 0 every group is built with exactly this configuration.
+TileCfg g_force = {0, 0, 0, 1, 0, 0};
+
+const int TILE_H[] = {2, 4, 7, 8, 14, 16};
+const int TILE_W[] = {4, 7, 8, 14, 16, 28, 32};
+
+// Chooses tile / register tile / slicing for a group at a given budget: minimum modelled cost;
+// ties go to the earlier candidate in enumeration order.
+bool choose_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int batch, int budget,
+                  int max_lds, Built& best, TileCfg& best_tc, uint64_t& best_cost)
+{
+    bool found = false;
+    const int ns = (int)specs.size();
+    if (g_force.th > 0) {
+        Built b = build_group(net, specs, batch, g_force, max_lds);
+        if (!b.ok) return false;
+        best = b;
+        best_tc = g_force;
+        best_cost = group_cost_ps(b, budget);
+        return true;
+    }
+    const Layer& Llast = net.L[specs[ns - 1].pool2 ? specs[ns - 1].pool_layer : specs[ns - 1].layer];
+    const Layer& L0 = net.L[specs[0].layer];
+    const bool conv0 = specs[0].kind == DLF_ST_CONV;
+    bool later_conv = false, any_conv = conv0;
+    for (int s = 1; s < ns; ++s)
+        if (specs[s].kind == DLF_ST_CONV) { later_conv = true; any_conv = true; }
+    for (int th : TILE_H) {
+        if (th > Llast.out_h && th != TILE_H[0] && (th - Llast.out_h) >= 4) continue;
+        for (int tw : TILE_W) {
+            if (tw > Llast.out_w && tw != TILE_W[0] && (tw - Llast.out_w) >= 4) continue;
+            if (th * tw > 512) continue;
+            for (int variant = 0; variant < 5; ++variant) {
+                if (!any_conv && variant != 0) continue;
+                std::vector<TileCfg> cands;
+                if (conv0) {
+                    // slicing over output channels: only if no later CONV stage
+                    const int ncb = L0.ncb, FCv = VAR_FC[variant];
+                    for (int stream0 = 1; stream0 >= 0; --stream0) {
+                        TileCfg t{th, tw, variant, 1, 0, stream0};
+                        cands.push_back(t);
+                        if (!later_conv && stream0) {
+                            for (int cg = 1; cg <= 4; cg *= 2) {
+                                const int sc = FCv * cg * 32;
+                                if (sc >= ncb * 32) continue;
+                                TileCfg u{th, tw, variant, ceil_div(ncb * 32, sc), sc, 1};
+                                cands.push_back(u);
+                            }
+                        }
+                    }
+                } else {
+                    TileCfg t{th, tw, variant, 1, 0, 0};
+                    cands.push_back(t);
+                    if (!later_conv) {
+                        for (int sc = 32; sc < L0.d.cin; sc *= 2) {
+                            TileCfg u{th, tw, variant, ceil_div(L0.d.cin, sc), sc, 0};
+                            cands.push_back(u);
+                        }
+                    }
+                }
+                for (const TileCfg& tc : cands) {
+                    Built b = build_group(net, specs, batch, tc, max_lds);
+                    if (!b.ok) continue;
+                    const uint64_t c = group_cost_ps(b, budget);
+                    if (!found || c < best_cost) {
+                        found = true;
+                        best = b;
+                        best_tc = tc;
+                        best_cost = c;
+                    }
+                }
+            }
+        }
+    }
+    return found;
+}
+
+dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int budget, int max_lds,
+                      GroupPlan& g)
+{
+    if (first < 0 || last >= (int)net.L.size() || first > last || budget <= 0)
+        return fail(DLF_ERR_INVALID_ARG, "bad group [%d,%d] budget %d", first, last, budget);
+    std::vector<StageSpec> specs;
+    std::string why;
+    int kind;
+    if (!group_stages(net, first, last, specs, kind, why))
+        return fail(DLF_ERR_INFEASIBLE, "layers [%d,%d] cannot form a group: %s", first, last, why.c_str());
+    g = GroupPlan();
+    g.first = first; g.last = last; g.budget = budget; g.kind = kind;
+    const Layer& L0 = net.L[first];
+    g.in_layer = L0.src;
+    if (kind == GK_FC) {
+        DlfFcArgs& fa = g.fa;
+        memset(&fa, 0, sizeof fa);
+        fa.w = L0.d_w; fa.bias = L0.d_bias;
+        fa.batch = batch; fa.k = L0.d.cin; fa.cout = L0.d.cout; fa.ncb = L0.ncb;
+        fa.nsteps = L0.nsteps; fa.act = L0.d.act;
+        const int64_t wbytes = (int64_t)L0.ncb * L0.nsteps * 1024 * ceil_div(batch, 32);
+        const int64_t nwg = std::min<int64_t>(L0.ncb, 256);
+        const int64_t bw = std::min<int64_t>(HBM_BYTES_PER_CYCLE, nwg * WG_BYTES_PER_CYCLE);
+        g.cost = (uint64_t)((LAUNCH_CYCLES + TILE_CYCLES + wbytes / bw) * PS_PER_CYCLE);
+        g.grid = L0.ncb;
+        g.th = g.tw = 1;
+        return DLF_OK;
+    }
+    if (kind == GK_GAP) {
+        DlfGapArgs& pa = g.pa;
+        memset(&pa, 0, sizeof pa);
+        pa.batch = batch; pa.hw = L0.in_h * L0.in_w; pa.c = L0.d.cin;
+        const int64_t bytes = (int64_t)batch * pa.hw * pa.c * 2;
+        g.cost = (uint64_t)((LAUNCH_CYCLES + TILE_CYCLES + bytes / 1024) * PS_PER_CYCLE);
+        g.grid = ceil_div(batch * pa.c, 256);
+        g.th = L0.in_h; g.tw = L0.in_w;
+        return DLF_OK;
+    }
+    Built b;
+    TileCfg tc;
+    uint64_t cost;
+    if (!choose_group(net, specs, batch, budget, max_lds, b, tc, cost))
+        return fail(DLF_ERR_INFEASIBLE, "layers [%d,%d] do not fit on-chip memory as one group", first, last);
+    g.ga = b.ga;
+    g.variant = tc.variant;
+    g.lds_bytes = b.lds_bytes;
+    g.grid = std::min(budget, b.ntiles);
+    g.th = tc.th; g.tw = tc.tw;
+    g.cost = cost;
+    for (size_t s = 0; s < specs.size(); ++s) {
+        const int rf = net.L[specs[s].layer].d.residual_from;
+        if (rf >= 0) { g.res_layer = rf; g.res_stage = (int)s; }
+    }
+    return DLF_OK;
+}
+
+}  // namespace
+
+struct dlf_plan_s {
+    const dlf_net_s* net;
+    int batch;
+    std::vector<GroupPlan> G;
+    std::vector<size_t> layer_off;   // workspace offset of each layer's output, or SIZE_MAX
+    size_t ws_bytes = 0;
+    char* ws = nullptr;
+};
+
+namespace {
+
+const int DEFAULT_BUDGETS[4] = {32, 64, 128, 256};
+
+// Algorithm 1 of the paper (greedy joint fusion + MP pass); see the design doc for the readings.
+void algorithm1(const dlf_net_s& net, int batch, double crit, double alpha, double beta, double k,
+                double b, const std::vector<int>& allowed, std::vector<int>& part, std::vector<int>& mps)
+{
+    const int n = (int)net.L.size();
+    const int max_mp = *std::max_element(allowed.begin(), allowed.end());
+    auto conv_like = [&](int i) {
+        const int op = net.L[i].d.op;
+        return op == DLF_CONV || op == DLF_DWCONV || op == DLF_FC;
+    };
+    auto round_mp = [&](double avg) {
+        const int p = 1 << (int)std::floor(std::log2(avg));
+        int best = -1;
+        for (int a : allowed) if (a <= p && a > best) best = a;
+        if (best < 0) best = *std::min_element(allowed.begin(), allowed.end());
+        return best;
+    };
+    double sum_op = 0, sum_mp = 0;
+    int block = 0;
+    for (int i = 0; i < n; ++i) {
+        if (conv_like(i)) {
+            const Layer& L = net.L[i];
+            const double ops = 2.0 * (double)L.macs * batch;
+            const double score = alpha * std::log2((double)std::min(L.d.cin, L.d.cout)) + beta * std::log2(ops);
+            sum_mp += std::min((double)max_mp, std::max(1.0, k * score + b));
+            sum_op += ops;
+            ++block;
+        }
+        if (block > 0) {
+            const double avg = sum_mp / block;
+            if (sum_op / avg >= crit) {
+                while (i + 1 < n && !conv_like(i + 1)) ++i;
+                part.push_back(i);
+                mps.push_back(round_mp(avg));
+                sum_op = sum_mp = 0;
+                block = 0;
+            }
+        }
+    }
+    const int covered = part.empty() ? 0 : part.back() + 1;
+    if (covered < n) {
+        if (block > 0) {
+            part.push_back(n - 1);
+            mps.push_back(round_mp(sum_mp / block));
+        } else if (!part.empty()) {
+            part.back() = n - 1;
+        } else {
+            part.push_back(n - 1);
+            mps.push_back(*std::min_element(allowed.begin(), allowed.end()));
+        }
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dlf_status_string(dlf_status s)
+{
+    switch (s) {
+    case DLF_OK: return "ok";
+    case DLF_ERR_INVALID_ARG: return "invalid argument";
+    case DLF_ERR_SHAPE: return "shape mismatch";
+    case DLF_ERR_UNSUPPORTED: return "unsupported layer";
+    case DLF_ERR_INFEASIBLE: return "fusion group infeasible";
+    case DLF_ERR_OOM: return "out of memory";
+    case DLF_ERR_HIP: return "HIP error";
+    case DLF_ERR_NO_WEIGHTS: return "network has no weights";
+    }
+    return "unknown status";
+}
+
+const char* dlf_last_error(void) { return g_err.c_str(); }
+
+int32_t dlf_cost_model_version(void) { return 1; }
+
+dlf_status dlf_net_create(const dlf_layer_desc* layers, int32_t n, int32_t in_h, int32_t in_w,
+                          int32_t in_c, dlf_net_t** out)
+{
+    if (!layers || !out || n <= 0 || in_h <= 0 || in_w <= 0 || in_c <= 0)
+        return fail(DLF_ERR_INVALID_ARG, "dlf_net_create: null or non-positive argument");
+    dlf_net_s* net = new (std::nothrow) dlf_net_s;
+    if (!net) return fail(DLF_ERR_OOM, "host allocation failed");
+    net->in_h = in_h; net->in_w = in_w; net->in_c = in_c;
+    net->L.resize(n);
+    int with_w = 0, need_w = 0;
+    for (int i = 0; i < n; ++i) {
+        Layer& L = net->L[i];
+        L.d = layers[i];
+        const dlf_layer_desc& d = L.d;
+        auto bad = [&](dlf_status s, const char* msg) {
+            delete net;
+            return fail(s, "layer %d: %s", i, msg);
+        };
+        if (d.op < DLF_CONV || d.op > DLF_GLOBAL_AVGPOOL) return bad(DLF_ERR_INVALID_ARG, "bad op");
+        if (d.act < DLF_ACT_NONE || d.act > DLF_ACT_RELU6) return bad(DLF_ERR_INVALID_ARG, "bad activation");
+        if (d.cin <= 0 || d.cout <= 0 || d.kh <= 0 || d.kw <= 0 || d.stride <= 0 || d.pad < 0)
+            return bad(DLF_ERR_INVALID_ARG, "non-positive size");
+        if (d.input_from < -1 || d.input_from >= i) return bad(DLF_ERR_INVALID_ARG, "input_from must name an earlier layer");
+        if (d.residual_from < -1 || d.residual_from >= i) return bad(DLF_ERR_INVALID_ARG, "residual_from must name an earlier layer");
+        L.src = d.input_from >= 0 ? d.input_from : i - 1;
+        if (L.src < 0) { L.in_h = in_h; L.in_w = in_w; L.in_c = in_c; }
+        else { L.in_h = net->L[L.src].out_h; L.in_w = net->L[L.src].out_w; L.in_c = net->L[L.src].out_c; }
+        L.macs = 0;
+        switch (d.op) {
+        case DLF_CONV: case DLF_DWCONV: case DLF_MAXPOOL:
+            if (d.cin != L.in_c) return bad(DLF_ERR_SHAPE, "cin does not match the input tensor");
+            if (d.op != DLF_CONV && d.cin != d.cout) return bad(DLF_ERR_SHAPE, "cin must equal cout");
+            if (L.in_h + 2 * d.pad < d.kh || L.in_w + 2 * d.pad < d.kw) return bad(DLF_ERR_SHAPE, "kernel larger than padded input");
+            L.out_h = (L.in_h + 2 * d.pad - d.kh) / d.stride + 1;
+            L.out_w = (L.in_w + 2 * d.pad - d.kw) / d.stride + 1;
+            L.out_c = d.cout;
+            if (d.op == DLF_CONV) L.macs = (uint64_t)L.out_h * L.out_w * d.kh * d.kw * d.cin * d.cout;
+            if (d.op == DLF_DWCONV) L.macs = (uint64_t)L.out_h * L.out_w * d.kh * d.kw * d.cout;
+            if (d.op == DLF_MAXPOOL && d.has_bias) return bad(DLF_ERR_INVALID_ARG, "pooling has no bias");
+            break;
+        case DLF_FC:
+            if (d.cin != L.in_h * L.in_w * L.in_c) return bad(DLF_ERR_SHAPE, "FC cin must equal H*W*C of its input");
+            if (d.kh != 1 || d.kw != 1) return bad(DLF_ERR_INVALID_ARG, "FC kernel must be 1x1");
+            L.out_h = L.out_w = 1; L.out_c = d.cout;
+            L.macs = (uint64_t)d.cin * d.cout;
+            break;
+        case DLF_GLOBAL_AVGPOOL:
+            if (d.cin != L.in_c || d.cout != d.cin) return bad(DLF_ERR_SHAPE, "channel mismatch");
+            L.out_h = L.out_w = 1; L.out_c = d.cout;
+            break;
+        }
+        if (d.residual_from >= 0) {
+            const Layer& R = net->L[d.residual_from];
+            if (R.out_h != L.out_h || R.out_w != L.out_w || R.out_c != L.out_c)
+                return bad(DLF_ERR_SHAPE, "residual operand shape differs from the layer output");
+        }
+        if (d.op == DLF_CONV && (d.cin % 8) != 0 && d.cin > 32)
+            return bad(DLF_ERR_UNSUPPORTED, "convolution with more than 32 input channels needs cin % 8 == 0");
+        if (d.op == DLF_CONV && (d.cout % 4) != 0)
+            return bad(DLF_ERR_UNSUPPORTED, "convolution needs cout % 4 == 0");
+        if (d.op == DLF_FC && (d.cin % 8) != 0)
+            return bad(DLF_ERR_UNSUPPORTED, "FC needs cin % 8 == 0");
+        if ((d.op == DLF_DWCONV || d.op == DLF_MAXPOOL) && (d.cin % 8) != 0)
+            return bad(DLF_ERR_UNSUPPORTED, "depthwise / pooling layers need channels % 8 == 0");
+        if (d.op == DLF_MAXPOOL && d.pad >= d.kh)
+            return bad(DLF_ERR_UNSUPPORTED, "pooling pad must be smaller than the window");
+        if (d.op == DLF_CONV || d.op == DLF_FC) {
+            L.kc = d.cin <= 16 ? 16 : 32;
+            L.cin_pad = round_up(d.cin, L.kc);
+            L.ncb = ceil_div(d.cout, 32);
+            L.nsteps = (L.cin_pad / L.kc) * d.kh * d.kw * (L.kc / 16);
+        } else if (d.op == DLF_DWCONV) {
+            L.kc = 8; L.cin_pad = round_up(d.cin, 8);
+        }
+        if (d.op == DLF_CONV || d.op == DLF_FC || d.op == DLF_DWCONV) {
+            ++need_w;
+            if (d.weight) ++with_w;
+        }
+    }
+    if (with_w != 0 && with_w != need_w) {
+        delete net;
+        return fail(DLF_ERR_INVALID_ARG, "either all or none of the weighted layers must have weights");
+    }
+    net->has_weights = (with_w == need_w) && (with_w > 0 || need_w == 0);
+    if (net->has_weights && need_w > 0) {
+        for (int i = 0; i < n; ++i) {
+            dlf_status s = pack_and_upload(net->L[i]);
+            if (s != DLF_OK) { dlf_net_destroy(net); return s; }
+        }
+    }
+    for (int i = 0; i < n; ++i) { net->L[i].d.weight = nullptr; net->L[i].d.bias = nullptr; }
+    *out = net;
+    return DLF_OK;
+}
+
+void dlf_net_destroy(dlf_net_t* net)
+{
+    if (!net) return;
+    for (Layer& L : net->L) {
+        if (L.d_w) (void)hipFree(L.d_w);
+        if (L.d_bias) (void)hipFree(L.d_bias);
+    }
+    delete net;
+}
+
+int32_t dlf_net_num_layers(const dlf_net_t* net) { return net ? (int32_t)net->L.size() : 0; }
+
+dlf_status dlf_net_layer_info(const dlf_net_t* net, int32_t i, int32_t* out_h, int32_t* out_w,
+                              int32_t* out_c, uint64_t* op_count)
+{
+    if (!net || i < 0 || i >= (int)net->L.size()) return fail(DLF_ERR_INVALID_ARG, "bad layer index");
+    const Layer& L = net->L[i];
+    if (out_h) *out_h = L.out_h;
+    if (out_w) *out_w = L.out_w;
+    if (out_c) *out_c = L.out_c;
+    if (op_count) *op_count = 2 * L.macs;
+    return DLF_OK;
+}
+
+dlf_status dlf_group_cost(const dlf_net_t* net, int32_t batch, int32_t first, int32_t last,
+                          int32_t budget, int32_t max_lds_bytes, uint64_t* cost)
+{
+    if (!net || !cost || batch <= 0) return fail(DLF_ERR_INVALID_ARG, "dlf_group_cost: bad argument");
+    GroupPlan g;
+    dlf_status s = make_group(*net, batch, first, last, budget, max_lds_bytes > 0 ? max_lds_bytes : 160 * 1024, g);
+    if (s != DLF_OK) return s;
+    *cost = g.cost;
+    return DLF_OK;
+}
+
+dlf_status dlf_plan(const dlf_net_t* net, int32_t batch, const dlf_tuner_opts* opts, dlf_plan_t** out)
+{
+    if (!net || !out || batch <= 0) return fail(DLF_ERR_INVALID_ARG, "dlf_plan: bad argument");
+    dlf_tuner_opts o;
+    memset(&o, 0, sizeof o);
+    if (opts) o = *opts;
+    const int n = (int)net->L.size();
+    const int max_lds = o.max_lds_bytes > 0 ? o.max_lds_bytes : 160 * 1024;
+    std::vector<int> budgets;
+    if (o.budgets && o.n_budgets > 0) budgets.assign(o.budgets, o.budgets + o.n_budgets);
+    else budgets.assign(DEFAULT_BUDGETS, DEFAULT_BUDGETS + 4);
+    for (int b : budgets) if (b <= 0) return fail(DLF_ERR_INVALID_ARG, "budgets must be positive");
+
+    std::vector<GroupPlan> groups;
+    if (o.mode == DLF_TUNER_MANUAL) {
+        if (!o.manual_group_last || !o.manual_budget || o.manual_n <= 0)
+            return fail(DLF_ERR_INVALID_ARG, "manual plan needs group_last[], budget[] and a count");
+        int first = 0;
+        for (int g = 0; g < o.manual_n; ++g) {
+            const int last = o.manual_group_last[g];
+            if (last < first || last >= n) return fail(DLF_ERR_INVALID_ARG, "manual group_last[] must be increasing and < n");
+            GroupPlan gp;
+            dlf_status s = make_group(*net, batch, first, last, o.manual_budget[g], max_lds, gp);
+            if (s != DLF_OK) return s;
+            groups.push_back(gp);
+            first = last + 1;
+        }
+        if (first != n) return fail(DLF_ERR_INVALID_ARG, "manual groups must cover every layer");
+    } else if (o.mode == DLF_TUNER_DP) {
+        // cost[f][l][b] for every contiguous range and budget; infeasible = no entry
+        const uint64_t INF = std::numeric_limits<uint64_t>::max();
+        const int nb = (int)budgets.size();
+        std::vector<GroupPlan> table((size_t)n * n * nb);
+        std::vector<char> ok((size_t)n * n * nb, 0);
+        auto idx = [&](int f, int l, int b) { return ((size_t)f * n + l) * nb + b; };
+        for (int f = 0; f < n; ++f)
+            for (int l = f; l < n; ++l) {
+                bool any = false;
+                for (int b = 0; b < nb; ++b) {
+                    GroupPlan gp;
+                    if (make_group(*net, batch, f, l, budgets[b], max_lds, gp) == DLF_OK) {
+                        table[idx(f, l, b)] = gp;
+                        ok[idx(f, l, b)] = 1;
+                        any = true;
+                    }
+                }
+                if (!any && l > f) {
+                    // a range that cannot be a group: longer ranges starting at f may still be
+                    // (e.g. conv + pool + conv), so keep scanning
+                }
+            }
+        // best[i] = best plan for the suffix starting at layer i under the total order
+        // (cost, number of groups, group_last lexicographic, budgets lexicographic)
+        struct Sfx { uint64_t cost; int ngroups; std::vector<int> lasts, buds; bool valid; };
+        std::vector<Sfx> best(n + 1);
+        best[n] = Sfx{0, 0, {}, {}, true};
+        for (int i = n - 1; i >= 0; --i) {
+            Sfx bs{INF, 0, {}, {}, false};
+            for (int l = i; l < n; ++l) {
+                if (!best[l + 1].valid) continue;
+                for (int b = 0; b < nb; ++b) {
+                    if (!ok[idx(i, l, b)]) continue;
+                    Sfx c;
+                    c.valid = true;
+                    c.cost = table[idx(i, l, b)].cost + best[l + 1].cost;
+                    c.ngroups = 1 + best[l + 1].ngroups;
+                    c.lasts.push_back(l);
+                    c.lasts.insert(c.lasts.end(), best[l + 1].lasts.begin(), best[l + 1].lasts.end());
+                    c.buds.push_back(budgets[b]);
+                    c.buds.insert(c.buds.end(), best[l + 1].buds.begin(), best[l + 1].buds.end());
+                    bool better = !bs.valid;
+                    if (!better) {
+                        if (c.cost != bs.cost) better = c.cost < bs.cost;
+                        else if (c.ngroups != bs.ngroups) better = c.ngroups < bs.ngroups;
+                        else if (c.lasts != bs.lasts) better = c.lasts < bs.lasts;
+                        else better = c.buds < bs.buds;
+                    }
+                    if (better) bs = c;
+                }
+            }
+            best[i] = bs;
+        }
+        if (!best[0].valid) return fail(DLF_ERR_INFEASIBLE, "no feasible plan");
+        int first = 0;
+        for (size_t g = 0; g < best[0].lasts.size(); ++g) {
+            const int last = best[0].lasts[g];
+            int bi = 0;
+            for (int b = 0; b < nb; ++b) if (budgets[b] == best[0].buds[g]) { bi = b; break; }
+            groups.push_back(table[idx(first, last, bi)]);
+            first = last + 1;
+        }
+    } else if (o.mode == DLF_TUNER_GREEDY) {
+        const double alpha = (o.alpha == 0 && o.beta == 0) ? 0.316 : o.alpha;
+        const double beta = (o.alpha == 0 && o.beta == 0) ? 0.659 : o.beta;
+        const double k = (o.mp_scale == 0 && o.mp_offset == 0) ? 16.0 : o.mp_scale;
+        const double b0 = (o.mp_scale == 0 && o.mp_offset == 0) ? -256.0 : o.mp_offset;
+        const double crit = o.opcount_critical > 0 ? o.opcount_critical : 2.0e7;
+        std::vector<int> part, mps;
+        algorithm1(*net, batch, crit, alpha, beta, k, b0, budgets, part, mps);
+        // legalisation: a block the kernels cannot run as one group is split left to right into
+        // maximal feasible groups, all with the block's budget
+        int first = 0;
+        for (size_t g = 0; g < part.size(); ++g) {
+            const int blk_last = part[g];
+            while (first <= blk_last) {
+                int l = blk_last;
+                GroupPlan gp;
+                dlf_status s = DLF_ERR_INFEASIBLE;
+                for (; l >= first; --l) {
+                    s = make_group(*net, batch, first, l, mps[g], max_lds, gp);
+                    if (s == DLF_OK) break;
+                }
+                if (s != DLF_OK) return s;
+                groups.push_back(gp);
+                first = l + 1;
+            }
+        }
+    } else {
+        return fail(DLF_ERR_INVALID_ARG, "unknown tuner mode %d", o.mode);
+    }
+
+    dlf_plan_s* plan = new (std::nothrow) dlf_plan_s;
+    if (!plan) return fail(DLF_ERR_OOM, "host allocation failed");
+    plan->net = net;
+    plan->batch = batch;
+    plan->G = groups;
+    // workspace: the output of each group except the last, 256-byte aligned slots
+    plan->layer_off.assign(n, (size_t)-1);
+    size_t off = 0;
+    for (size_t g = 0; g + 1 < groups.size(); ++g) {
+        const Layer& L = net->L[groups[g].last];
+        const size_t bytes = (size_t)batch * L.out_h * L.out_w * L.out_c * 2;
+        plan->layer_off[groups[g].last] = off;
+        off += (bytes + 255) & ~(size_t)255;
+    }
+    plan->ws_bytes = off;
+    for (const GroupPlan& G : groups) {
+        const bool in_ok = G.in_layer < 0 || plan->layer_off[G.in_layer] != (size_t)-1;
+        const bool res_ok = G.res_stage < 0 || plan->layer_off[G.res_layer] != (size_t)-1;
+        if (!in_ok || !res_ok) {
+            delete plan;
+            return fail(DLF_ERR_INFEASIBLE, "group [%d,%d] reads a tensor that is not the output of an earlier group",
+                        G.first, G.last);
+        }
+    }
+    *out = plan;
+    return DLF_OK;
+}
+
+void dlf_plan_destroy(dlf_plan_t* plan) { delete plan; }
+
+int32_t dlf_plan_num_groups(const dlf_plan_t* plan) { return plan ? (int32_t)plan->G.size() : 0; }
+
+dlf_status dlf_plan_group(const dlf_plan_t* plan, int32_t g, int32_t* first, int32_t* last,
+                          int32_t* budget, int32_t* tile_h, int32_t* tile_w, uint64_t* model_cost)
+{
+    if (!plan || g < 0 || g >= (int)plan->G.size()) return fail(DLF_ERR_INVALID_ARG, "bad group index");
+    const GroupPlan& G = plan->G[g];
+    if (first) *first = G.first;
+    if (last) *last = G.last;
+    if (budget) *budget = G.budget;
+    if (tile_h) *tile_h = G.th;
+    if (tile_w) *tile_w = G.tw;
+    if (model_cost) *model_cost = G.cost;
+    return DLF_OK;
+}
+
+dlf_status dlf_plan_group_config(const dlf_plan_t* plan, int32_t g, int32_t* kind, int32_t* variant,
+                                 int32_t* nslices, int32_t* slice_c, int32_t* stream0, int32_t* lds_bytes)
+{
+    if (!plan || g < 0 || g >= (int)plan->G.size()) return fail(DLF_ERR_INVALID_ARG, "bad group index");
+    const GroupPlan& G = plan->G[g];
+    if (kind) *kind = G.kind;
+    if (variant) *variant = G.variant;
+    if (nslices) *nslices = G.kind == GK_GROUP ? G.ga.nslices : 1;
+    if (slice_c) *slice_c = G.kind == GK_GROUP ? G.ga.slice_c : 0;
+    if (stream0) *stream0 = G.kind == GK_GROUP ? G.ga.stream0 : 0;
+    if (lds_bytes) *lds_bytes = G.lds_bytes;
+    return DLF_OK;
+}
+
+void dlf_debug_force_config(int32_t th, int32_t tw, int32_t variant, int32_t nslices, int32_t slice_c,
+                            int32_t stream0)
+{
+    g_force = TileCfg{th, tw, variant, nslices < 1 ? 1 : nslices, slice_c, stream0};
+}
+
+size_t dlf_plan_workspace_bytes(const dlf_plan_t* plan) { return plan ? plan->ws_bytes : 0; }
+
+dlf_status dlf_plan_bind_workspace(dlf_plan_t* plan, void* dev_ptr, size_t bytes)
+{
+    if (!plan) return fail(DLF_ERR_INVALID_ARG, "null plan");
+    if (bytes < plan->ws_bytes) return fail(DLF_ERR_OOM, "workspace too small: %zu < %zu", bytes, plan->ws_bytes);
+    if (plan->ws_bytes > 0 && (!dev_ptr || ((uintptr_t)dev_ptr & 255) != 0))
+        return fail(DLF_ERR_INVALID_ARG, "workspace must be a 256-byte aligned device pointer");
+    plan->ws = (char*)dev_ptr;
+    return DLF_OK;
+}
+
+const void* dlf_plan_layer_output(const dlf_plan_t* plan, int32_t layer)
+{
+    if (!plan || layer < 0 || layer >= (int)plan->layer_off.size()) return nullptr;
+    if (plan->layer_off[layer] == (size_t)-1 || !plan->ws) return nullptr;
+    return plan->ws + plan->layer_off[layer];
+}
+
+static dlf_status launch_one(const dlf_plan_s* plan, const GroupPlan& G, const void* in, const void* res,
+                             void* out, void* stream)
+{
+    int e = 0;
+    if (!g_kernels_ready) {
+        e = dlf_kernels_init();
+        if (e != 0) return fail(DLF_ERR_HIP, "kernel setup failed: %s", hipGetErrorString((hipError_t)e));
+        g_kernels_ready = true;
+    }
+    if (G.kind == GK_FC) {
+        DlfFcArgs fa = G.fa;
+        fa.x = in; fa.y = out;
+        e = dlf_launch_fc(&fa, stream);
+    } else if (G.kind == GK_GAP) {
+        DlfGapArgs pa = G.pa;
+        pa.x = in; pa.y = out;
+        e = dlf_launch_gap(&pa, stream);
+    } else {
+        DlfGroupArgs ga = G.ga;
+        ga.in = in; ga.out = out;
+        if (G.res_stage >= 0) {
+            if (!res) return fail(DLF_ERR_INVALID_ARG, "group [%d,%d] needs its residual operand", G.first, G.last);
+            ga.st[G.res_stage].res = res;
+        }
+        e = dlf_launch_group(&ga, G.variant, G.grid, G.lds_bytes, stream);
+    }
+    if (e != 0) return fail(DLF_ERR_HIP, "launch of group [%d,%d] failed: %s", G.first, G.last,
+                            hipGetErrorString((hipError_t)e));
+    (void)plan;
+    return DLF_OK;
+}
+
+dlf_status dlf_run_group(const dlf_plan_t* plan, int32_t g, const void* in_dev, const void* res_dev,
+                         void* out_dev, void* hip_stream)
+{
+    if (!plan || g < 0 || g >= (int)plan->G.size() || !in_dev || !out_dev)
+        return fail(DLF_ERR_INVALID_ARG, "dlf_run_group: bad argument");
+    if (!plan->net->has_weights) return fail(DLF_ERR_NO_WEIGHTS, "network was created without weights");
+    return launch_one(plan, plan->G[g], in_dev, res_dev, out_dev, hip_stream);
+}
+
+dlf_status dlf_run(const dlf_plan_t* plan, const void* in_dev, void* out_dev, void* hip_stream)
+{
+    if (!plan || !in_dev || !out_dev) return fail(DLF_ERR_INVALID_ARG, "dlf_run: null argument");
+    if (!plan->net->has_weights) return fail(DLF_ERR_NO_WEIGHTS, "network was created without weights");
+    if (plan->ws_bytes > 0 && !plan->ws) return fail(DLF_ERR_INVALID_ARG, "no workspace bound");
+    const size_t ng = plan->G.size();
+    for (size_t g = 0; g < ng; ++g) {
+        const GroupPlan& G = plan->G[g];
+        const void* in = G.in_layer < 0 ? in_dev : plan->ws + plan->layer_off[G.in_layer];
+        const void* res = nullptr;
+        if (G.res_stage >= 0) res = plan->ws + plan->layer_off[G.res_layer];
+        void* out = (g + 1 == ng) ? out_dev : (void*)(plan->ws + plan->layer_off[G.last]);
+        dlf_status s = launch_one(plan, G, in, res, out, hip_stream);
+        if (s != DLF_OK) return s;
+    }
+    return DLF_OK;
+}
+
+}  // extern "C"

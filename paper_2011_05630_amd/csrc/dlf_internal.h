@@ -1,0 +1,85 @@
+// Shared between the host planner and the gfx950 kernels: the "group program" one workgroup
+// interprets.  A fusion group (Sec. III-B of the paper: consecutive layers executed as one block
+// with on-chip intermediates) is a short list of stages; each stage reads a region of its input
+// feature map from LDS (stage 0 may stream its input from HBM instead) and writes its output
+// region to LDS, or to HBM if it is the last stage.
+#pragma once
+#include <stdint.h>
+
+#define DLF_MAX_STAGES 8
+#define DLF_WG_THREADS 256
+#define DLF_WAVES 4
+#define DLF_CPAD 8          // halfs of padding per LDS pixel row: makes the row stride an odd
+                            // multiple of 16 bytes, so 16-byte LDS accesses spread over all banks
+#define DLF_STAGE_VECS 8    // 16-byte vectors each thread can hold while prefetching a streamed chunk
+
+enum { DLF_ST_CONV = 0, DLF_ST_MAXPOOL = 1, DLF_ST_DW = 2 };
+
+struct DlfStage {
+    int32_t kind;
+    int32_t cin;          // true input channels
+    int32_t cin_pad;      // input channels padded to a multiple of kc (zero weights beyond cin)
+    int32_t kc;           // channels per K-chunk: 16 or 32
+    int32_t cout;         // true output channels
+    int32_t ncb;          // CONV: number of 32-wide output-channel blocks = ceil(cout/32)
+    int32_t kh, kw, stride, pad, act;
+    int32_t pool2;        // CONV: fused 2x2 stride-2 max pooling in the epilogue
+    int32_t in_h, in_w;   // true size of the input feature map
+    int32_t out_h, out_w; // true size of the output feature map (before the fused pool)
+    int32_t rh, rw;       // output region this stage computes per tile (before the fused pool)
+    int32_t ih, iw;       // input region = (rh-1)*stride+kh by (rw-1)*stride+kw
+    int32_t oy_mul, oy_off, ox_mul, ox_off; // output region origin = tile origin * mul + off
+    int32_t in_cs;        // halfs per pixel of the input LDS buffer
+    int32_t out_cs;       // halfs per pixel of the output LDS buffer (if not last)
+    int32_t in_off;       // LDS offset (halfs) of the input buffer (stream: first of two buffers)
+    int32_t out_off;      // LDS offset (halfs) of the output buffer
+    int32_t stream_buf;   // stream mode: halfs per chunk buffer
+    int32_t nsteps;       // CONV: 16-wide K steps per output-channel block
+    const void* w;        // CONV: packed fragments; DW: [kh][kw][c] fp16
+    const float* bias;    // padded with zeros to ncb*32 (CONV) / c rounded up to 8 (DW)
+    const void* res;      // residual operand in HBM, NHWC with this stage's output shape, or null
+};
+
+struct DlfGroupArgs {
+    const void* in;       // group input tensor (HBM)
+    void* out;            // group output tensor (HBM)
+    int32_t nstages;
+    int32_t stream0;      // stage 0 is a CONV that streams its input in K-chunks
+    int32_t batch;
+    int32_t in_h, in_w, in_c;         // group input tensor shape
+    int32_t iy_mul, iy_off, ix_mul, ix_off; // group input region origin = tile origin*mul + off
+    int32_t th, tw;       // tile of the last stage's output region (before its fused pool)
+    int32_t tiles_y, tiles_x;
+    int32_t nslices;      // channel slices (grid over output channels / channels)
+    int32_t slice_c;      // channels per slice (multiple of 32 for CONV, of 8 otherwise)
+    int32_t ntiles;       // batch * tiles_y * tiles_x * nslices
+    int32_t out_h, out_w, out_c;      // group output tensor shape
+    DlfStage st[DLF_MAX_STAGES];
+};
+
+struct DlfFcArgs {
+    const void* x;        // [batch][k] fp16
+    void* y;              // [batch][cout] fp16
+    const void* w;        // packed fragments
+    const float* bias;
+    int32_t batch, k, cout, ncb, nsteps, act;
+};
+
+struct DlfGapArgs {
+    const void* x;        // [batch][hw][c]
+    void* y;              // [batch][c]
+    int32_t batch, hw, c;
+};
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+// Launchers (defined with the kernels).  `variant` selects the per-wave register tile of CONV
+// stages: 0 = 64 channels x 128 pixels, 1 = 64 x 64, 2 = 32 x 128, 3 = 32 x 64.
+int dlf_launch_group(const DlfGroupArgs* a, int variant, int grid, int lds_bytes, void* stream);
+int dlf_launch_fc(const DlfFcArgs* a, void* stream);
+int dlf_launch_gap(const DlfGapArgs* a, void* stream);
+int dlf_kernels_init(void);
+#ifdef __cplusplus
+}
+#endif

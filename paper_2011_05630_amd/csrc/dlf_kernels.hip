@@ -1,0 +1,548 @@
+// gfx950 (CDNA4) kernels of libdlf.
+//
+// k_group: one workgroup executes a fusion group (paper Sec. III-B: consecutive layers run as one
+// block, intermediates on chip, halo recomputed per tile) on one tile at a time, looping over
+// tiles persistently (grid size = the group's workgroup budget, the analogue of the paper's MP).
+//
+// Convolution stages are implicit GEMMs on v_mfma_f32_32x32x16_f16:
+//     D[co][pixel] += W[co][k] * X[k][pixel],   k = (kh, kw, ci)
+// The weights are the MFMA "A" operand (32 output channels x 16 k), pre-packed on the host in
+// exactly the register layout, so a wave fetches one 1 KiB fragment with one coalesced 16-byte
+// load per lane, straight from L2 into registers.  The activations are the "B" operand
+// (16 k x 32 pixels), read from LDS where a pixel's channels are contiguous (NHWC), so the
+// im2col gather is just an address offset per filter tap.  With this orientation each lane ends
+// up holding 4 consecutive output channels of one pixel, which is what an NHWC store wants.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "dlf_internal.h"
+
+typedef _Float16 half_t;
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+typedef float f4v __attribute__((ext_vector_type(4)));
+
+extern __shared__ __attribute__((aligned(16))) half_t lds[];
+
+__device__ __forceinline__ float apply_act(float v, int act)
+{
+    if (act >= 1) v = fmaxf(v, 0.0f);
+    if (act == 2) v = fminf(v, 6.0f);
+    return v;
+}
+
+// Region pixel index -> (row, col).  With `quad` the 4 pixels of a 2x2 pooling window are
+// consecutive indices, so they sit in 4 adjacent lanes of the MFMA result.
+__device__ __forceinline__ void pix_to_rc(int p, int rw, int quad, int& ry, int& rx)
+{
+    if (quad) {
+        const int q = p >> 2, d = p & 3, hw = rw >> 1;
+        const int qy = q / hw, qx = q - qy * hw;
+        ry = 2 * qy + (d >> 1);
+        rx = 2 * qx + (d & 1);
+    } else {
+        ry = p / rw;
+        rx = p - ry * rw;
+    }
+}
+
+__device__ __forceinline__ float quad_max(float v)
+{
+    // max over the 4 lanes of a quad with two DPP quad permutes: [1,0,3,2] then [2,3,0,1]
+    int x = __builtin_bit_cast(int, v);
+    float o = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(x, 0xB1, 0xF, 0xF, true));
+    v = fmaxf(v, o);
+    x = __builtin_bit_cast(int, v);
+    o = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(x, 0x4E, 0xF, 0xF, true));
+    return fmaxf(v, o);
+}
+
+// Loads 8 channels [c, c+8) of input pixel (n, gy, gx); zero outside the image or beyond c_end.
+__device__ __forceinline__ h8 load_px8(const half_t* in, int n, int gy, int gx, int H, int W,
+                                       int C, int c, int c_end)
+{
+    h8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (gy >= 0 && gy < H && gx >= 0 && gx < W && c < c_end) {
+        const half_t* p = in + (((size_t)n * H + gy) * W + gx) * C + c;
+        if ((C & 7) == 0 && c + 8 <= c_end) {
+            v = *(const h8*)p;
+        } else {
+            for (int j = 0; j < 8; ++j)
+                if (c + j < c_end) v[j] = p[j];
+        }
+    }
+    return v;
+}
+
+// Copies the input region [iy0, iy0+ih) x [ix0, ix0+iw), channels [c0, c0+cfill), into LDS as
+// [pixel][cs]; zero padding outside the image and beyond channel c_end.
+__device__ __forceinline__ void stage_region(const half_t* in, int n, int H, int W, int C,
+                                             int iy0, int ix0, int ih, int iw, int c0, int cfill,
+                                             int c_end, int cs, half_t* dst)
+{
+    const int nvec = cfill >> 3;
+    const int total = ih * iw * nvec;
+    for (int v = threadIdx.x; v < total; v += DLF_WG_THREADS) {
+        const int pix = v / nvec, part = v - pix * nvec;
+        const int ry = pix / iw, rx = pix - ry * iw;
+        const h8 val = load_px8(in, n, iy0 + ry, ix0 + rx, H, W, C, c0 + part * 8, c_end);
+        *(h8*)(dst + pix * cs + part * 8) = val;
+    }
+}
+
+template <int FC, int FP, bool STREAM>
+__device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage& st, bool last,
+                                           int n, int ty0, int tx0, int slice)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int npix = st.rh * st.rw;
+    const int npb = (npix + 31) >> 5;
+    const int n_pg = (npb + FP - 1) / FP;
+    int cb_begin = 0, cb_end = st.ncb;
+    if (a.nslices > 1) {
+        cb_begin = slice * (a.slice_c >> 5);
+        cb_end = min(st.ncb, cb_begin + (a.slice_c >> 5));
+    }
+    const int n_cg = (cb_end - cb_begin + FC - 1) / FC;
+    const int nitems = n_pg * n_cg;
+    const int ry0 = ty0 * st.oy_mul + st.oy_off, rx0 = tx0 * st.ox_mul + st.ox_off;
+    const int nchunks = st.cin_pad / st.kc;
+    const int nks = st.kc >> 4;
+    const int cs = st.in_cs;
+    const half_t* in = (const half_t*)a.in;
+
+    // ---- stream mode: per-thread addresses of the vectors this thread stages per chunk ----
+    int s_goff[DLF_STAGE_VECS];   // element offset into `in` for chunk 0, or -1 (zero fill)
+    int s_loff[DLF_STAGE_VECS];   // LDS offset (halfs) inside a chunk buffer, or -1 (nothing)
+    h8 s_reg[DLF_STAGE_VECS];
+    if (STREAM) {
+        const int iy0 = ty0 * a.iy_mul + a.iy_off, ix0 = tx0 * a.ix_mul + a.ix_off;
+        const int nvec = st.kc >> 3;
+        const int total = st.ih * st.iw * nvec;
+        if ((st.cin & 7) != 0) {
+            // narrow inputs (e.g. 3 channels): one chunk, element-wise copy, no prefetch
+            stage_region(in, n, a.in_h, a.in_w, a.in_c, iy0, ix0, st.ih, st.iw, 0, st.kc, st.cin,
+                         cs, lds + st.in_off);
+#pragma unroll
+            for (int i = 0; i < DLF_STAGE_VECS; ++i) { s_goff[i] = -1; s_loff[i] = -1; }
+        } else {
+#pragma unroll
+            for (int i = 0; i < DLF_STAGE_VECS; ++i) {
+                const int v = tid + i * DLF_WG_THREADS;
+                s_goff[i] = -1;
+                s_loff[i] = -1;
+                if (v < total) {
+                    const int pix = v / nvec, part = v - pix * nvec;
+                    const int ry = pix / st.iw, rx = pix - ry * st.iw;
+                    const int gy = iy0 + ry, gx = ix0 + rx;
+                    s_loff[i] = pix * cs + part * 8;
+                    if (gy >= 0 && gy < a.in_h && gx >= 0 && gx < a.in_w)
+                        s_goff[i] = ((n * a.in_h + gy) * a.in_w + gx) * a.in_c + part * 8;
+                }
+            }
+            // chunk 0
+#pragma unroll
+            for (int i = 0; i < DLF_STAGE_VECS; ++i) {
+                h8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+                const int part8 = ((tid + i * DLF_WG_THREADS) & (nvec - 1)) * 8;
+                if (s_goff[i] >= 0 && part8 < st.cin) v = *(const h8*)(in + s_goff[i]);
+                if (s_loff[i] >= 0) *(h8*)(lds + st.in_off + s_loff[i]) = v;
+            }
+        }
+        __syncthreads();
+    }
+
+    for (int item0 = 0; item0 < nitems; item0 += DLF_WAVES) {
+        const int item = item0 + wave;
+        const bool active = item < nitems;
+        if (!STREAM && !active) continue;
+        const int itc = active ? item : 0;
+        const int cg = itc / n_pg, pg = itc - cg * n_pg;
+
+        int pbase[FP];
+#pragma unroll
+        for (int p = 0; p < FP; ++p) {
+            const int pix = (pg * FP + p) * 32 + l32;
+            int ry, rx;
+            pix_to_rc(pix < npix ? pix : 0, st.rw, st.pool2, ry, rx);
+            pbase[p] = ((ry * st.stride) * st.iw + rx * st.stride) * cs + lhi * 8;
+        }
+        const h8* wp[FC];
+#pragma unroll
+        for (int f = 0; f < FC; ++f) {
+            const int cb = min(cb_begin + cg * FC + f, cb_end - 1);
+            wp[f] = (const h8*)st.w + (size_t)cb * st.nsteps * 64 + lane;
+        }
+        f16v acc[FC][FP];
+#pragma unroll
+        for (int f = 0; f < FC; ++f)
+#pragma unroll
+            for (int p = 0; p < FP; ++p)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[f][p][i] = 0.0f;
+
+        h8 a_cur[2][FC], a_nxt[2][FC];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int f = 0; f < FC; ++f) a_cur[ks][f] = wp[f][(ks < nks ? ks : 0) * 64];
+#pragma unroll
+        for (int f = 0; f < FC; ++f) wp[f] += nks * 64;
+
+        for (int chunk = 0; chunk < nchunks; ++chunk) {
+            const half_t* src;
+            if (STREAM) {
+                src = lds + st.in_off + (chunk & 1) * st.stream_buf;
+                if (chunk + 1 < nchunks) {
+                    const int coff = (chunk + 1) * st.kc;
+#pragma unroll
+                    for (int i = 0; i < DLF_STAGE_VECS; ++i) {
+                        h8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+                        const int part8 = ((tid + i * DLF_WG_THREADS) & ((st.kc >> 3) - 1)) * 8;
+                        if (s_goff[i] >= 0 && coff + part8 < st.cin)
+                            v = *(const h8*)(in + s_goff[i] + coff);
+                        s_reg[i] = v;
+                    }
+                }
+            } else {
+                src = lds + st.in_off + chunk * st.kc;
+            }
+            if (active) {
+                for (int kh = 0; kh < st.kh; ++kh) {
+                    for (int kw = 0; kw < st.kw; ++kw) {
+                        const int tapoff = (kh * st.iw + kw) * cs;
+                        // fetch the next tap's weight fragments while this tap is multiplied
+#pragma unroll
+                        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                            for (int f = 0; f < FC; ++f)
+                                a_nxt[ks][f] = wp[f][(ks < nks ? ks : 0) * 64];
+#pragma unroll
+                        for (int f = 0; f < FC; ++f) wp[f] += nks * 64;
+#pragma unroll
+                        for (int ks = 0; ks < 2; ++ks) {
+                            if (ks < nks) {
+                                h8 b[FP];
+#pragma unroll
+                                for (int p = 0; p < FP; ++p)
+                                    b[p] = *(const h8*)(src + pbase[p] + tapoff + ks * 16);
+#pragma unroll
+                                for (int f = 0; f < FC; ++f)
+#pragma unroll
+                                    for (int p = 0; p < FP; ++p)
+                                        acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                                            a_cur[ks][f], b[p], acc[f][p], 0, 0, 0);
+                            }
+                        }
+#pragma unroll
+                        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                            for (int f = 0; f < FC; ++f) a_cur[ks][f] = a_nxt[ks][f];
+                    }
+                }
+            }
+            if (STREAM) {
+                if (chunk + 1 < nchunks) {
+                    half_t* dst = lds + st.in_off + ((chunk + 1) & 1) * st.stream_buf;
+#pragma unroll
+                    for (int i = 0; i < DLF_STAGE_VECS; ++i)
+                        if (s_loff[i] >= 0) *(h8*)(dst + s_loff[i]) = s_reg[i];
+                }
+                __syncthreads();
+            }
+        }
+
+        // ---- epilogue: bias, residual, activation, (pool), fp16, store ----
+        if (!active) continue;
+        half_t* outp = (half_t*)a.out;
+        const half_t* resp = (const half_t*)st.res;
+#pragma unroll
+        for (int f = 0; f < FC; ++f) {
+            const int cb = cb_begin + cg * FC + f;
+            if (cb >= cb_end) continue;
+#pragma unroll
+            for (int p = 0; p < FP; ++p) {
+                const int pix = (pg * FP + p) * 32 + l32;
+                const bool valid = pix < npix;
+                int ry, rx;
+                pix_to_rc(valid ? pix : 0, st.rw, st.pool2, ry, rx);
+                const int gy = ry0 + ry, gx = rx0 + rx;
+                const bool inimg = valid && gy >= 0 && gy < st.out_h && gx >= 0 && gx < st.out_w;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int co = cb * 32 + q * 8 + lhi * 4;
+                    const f4v bv = *(const f4v*)(st.bias + co);
+                    float v[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[r] = acc[f][p][q * 4 + r] + bv[r];
+                    if (resp != nullptr && inimg && co < st.cout) {
+                        const h4 rv = *(const h4*)(resp + (((size_t)n * st.out_h + gy) * st.out_w
+                                                           + gx) * st.cout + co);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] += (float)rv[r];
+                    }
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[r] = apply_act(v[r], st.act);
+                    if (st.pool2) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] = quad_max(v[r]);
+                    }
+                    h4 hv;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) hv[r] = (half_t)v[r];
+                    if (last) {
+                        if (co < st.cout) {
+                            if (!st.pool2) {
+                                if (inimg)
+                                    *(h4*)(outp + (((size_t)n * a.out_h + gy) * a.out_w + gx)
+                                                      * a.out_c + co) = hv;
+                            } else {
+                                const int py = gy >> 1, px = gx >> 1;
+                                if (valid && (l32 & 3) == 0 && gy >= 0 && gx >= 0 && py < a.out_h
+                                    && px < a.out_w)
+                                    *(h4*)(outp + (((size_t)n * a.out_h + py) * a.out_w + px)
+                                                      * a.out_c + co) = hv;
+                            }
+                        }
+                    } else {
+                        const int lc = co - cb_begin * 32;
+                        if (lc < st.out_cs - DLF_CPAD) {
+                            const h4 z = {0, 0, 0, 0};
+                            if (!st.pool2) {
+                                if (valid)
+                                    *(h4*)(lds + st.out_off + pix * st.out_cs + lc) = inimg ? hv : z;
+                            } else {
+                                const int py = gy >> 1, px = gx >> 1;
+                                const bool pin = gy >= 0 && gx >= 0 && py < (st.out_h >> 1)
+                                                 && px < (st.out_w >> 1);
+                                if (valid && (l32 & 3) == 0)
+                                    *(h4*)(lds + st.out_off + (pix >> 2) * st.out_cs + lc)
+                                        = pin ? hv : z;
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+// Max pooling and depthwise convolution on the vector ALUs: one work item = one output pixel x
+// 8 channels, input read from LDS (16 bytes per tap), fp32 arithmetic.
+__device__ __forceinline__ void valu_stage(const DlfGroupArgs& a, const DlfStage& st, bool last,
+                                           int n, int ty0, int tx0, int slice)
+{
+    const int npix = st.rh * st.rw;
+    int c0 = 0, ccnt = st.cout;
+    if (a.nslices > 1) {
+        c0 = slice * a.slice_c;
+        ccnt = min(a.slice_c, st.cout - c0);
+    }
+    const int ncg = (ccnt + 7) >> 3;
+    const int ry0 = ty0 * st.oy_mul + st.oy_off, rx0 = tx0 * st.ox_mul + st.ox_off;
+    const half_t* wdw = (const half_t*)st.w;
+    half_t* outp = (half_t*)a.out;
+    for (int it = threadIdx.x; it < npix * ncg; it += DLF_WG_THREADS) {
+        const int pix = it / ncg, g = it - pix * ncg;
+        const int ry = pix / st.rw, rx = pix - ry * st.rw;
+        const int gy = ry0 + ry, gx = rx0 + rx;
+        const bool inimg = gy >= 0 && gy < st.out_h && gx >= 0 && gx < st.out_w;
+        const int lc = g * 8;
+        float v[8];
+        if (st.kind == DLF_ST_MAXPOOL) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = -INFINITY;
+            for (int kh = 0; kh < st.kh; ++kh) {
+                const int iy = gy * st.stride - st.pad + kh;
+                if (iy < 0 || iy >= st.in_h) continue;
+                for (int kw = 0; kw < st.kw; ++kw) {
+                    const int ix = gx * st.stride - st.pad + kw;
+                    if (ix < 0 || ix >= st.in_w) continue;
+                    const h8 x = *(const h8*)(lds + st.in_off
+                                              + ((ry * st.stride + kh) * st.iw + rx * st.stride + kw)
+                                                    * st.in_cs + lc);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) v[j] = fmaxf(v[j], (float)x[j]);
+                }
+            }
+        } else {
+            const f4v b0 = *(const f4v*)(st.bias + c0 + lc);
+            const f4v b1 = *(const f4v*)(st.bias + c0 + lc + 4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { v[j] = b0[j]; v[j + 4] = b1[j]; }
+            for (int kh = 0; kh < st.kh; ++kh) {
+                for (int kw = 0; kw < st.kw; ++kw) {
+                    const h8 x = *(const h8*)(lds + st.in_off
+                                              + ((ry * st.stride + kh) * st.iw + rx * st.stride + kw)
+                                                    * st.in_cs + lc);
+                    const h8 w = *(const h8*)(wdw + (kh * st.kw + kw) * st.cin_pad + c0 + lc);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) v[j] = fmaf((float)x[j], (float)w[j], v[j]);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = apply_act(v[j], st.act);
+        }
+        h8 hv;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) hv[j] = (half_t)v[j];
+        if (last) {
+            if (inimg) {
+                half_t* o = outp + (((size_t)n * a.out_h + gy) * a.out_w + gx) * a.out_c + c0 + lc;
+                if (lc + 8 <= ccnt) {
+                    *(h8*)o = hv;
+                } else {
+                    for (int j = 0; j < 8; ++j)
+                        if (lc + j < ccnt) o[j] = hv[j];
+                }
+            }
+        } else {
+            const h8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+            *(h8*)(lds + st.out_off + pix * st.out_cs + lc) = inimg ? hv : z;
+        }
+    }
+}
+
+template <int FC, int FP>
+__global__ __launch_bounds__(DLF_WG_THREADS) void k_group(const DlfGroupArgs a)
+{
+    for (int t = blockIdx.x; t < a.ntiles; t += gridDim.x) {
+        int r = t;
+        const int slice = r % a.nslices;
+        r /= a.nslices;
+        const int tx = r % a.tiles_x;
+        r /= a.tiles_x;
+        const int ty = r % a.tiles_y;
+        const int n = r / a.tiles_y;
+        const int ty0 = ty * a.th, tx0 = tx * a.tw;
+        if (!a.stream0) {
+            const DlfStage& s0 = a.st[0];
+            int c0 = 0, cfill = s0.cin_pad, cend = s0.cin;
+            if (a.nslices > 1 && s0.kind != DLF_ST_CONV) {
+                c0 = slice * a.slice_c;
+                cend = min(s0.cin, c0 + a.slice_c);
+                cfill = (cend - c0 + 7) & ~7;
+            }
+            stage_region((const half_t*)a.in, n, a.in_h, a.in_w, a.in_c,
+                         ty0 * a.iy_mul + a.iy_off, tx0 * a.ix_mul + a.ix_off, s0.ih, s0.iw, c0,
+                         cfill, cend, s0.in_cs, lds + s0.in_off);
+            __syncthreads();
+        }
+        for (int s = 0; s < a.nstages; ++s) {
+            const DlfStage& st = a.st[s];
+            const bool last = (s == a.nstages - 1);
+            if (st.kind == DLF_ST_CONV) {
+                if (s == 0 && a.stream0)
+                    conv_stage<FC, FP, true>(a, st, last, n, ty0, tx0, slice);
+                else
+                    conv_stage<FC, FP, false>(a, st, last, n, ty0, tx0, slice);
+            } else {
+                valu_stage(a, st, last, n, ty0, tx0, slice);
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// Fully connected layer (Eq. 2 with M = batch): y[n][co] = act(bias[co] + sum_k x[n][k] w[co][k]).
+// One workgroup per 32 output channels; its 8 waves split K, each streaming its share of the
+// packed weight fragments from HBM exactly once; partial sums meet in LDS.
+#define DLF_FC_WAVES 8
+__global__ __launch_bounds__(DLF_FC_WAVES * 64) void k_fc(const DlfFcArgs a)
+{
+    __shared__ float red[DLF_FC_WAVES][16][64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int cb = blockIdx.x;
+    const half_t* x = (const half_t*)a.x;
+    half_t* y = (half_t*)a.y;
+    const h8* wbase = (const h8*)a.w + (size_t)cb * a.nsteps * 64 + lane;
+    for (int nb = 0; nb < a.batch; nb += 32) {
+        const int img = min(nb + l32, a.batch - 1);
+        const half_t* xr = x + (size_t)img * a.k + lhi * 8;
+        f16v acc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+#pragma unroll 4
+        for (int t = wave; t < a.nsteps; t += DLF_FC_WAVES) {
+            const h8 av = wbase[(size_t)t * 64];
+            h8 bv = {0, 0, 0, 0, 0, 0, 0, 0};
+            const int k = t * 16 + lhi * 8;
+            if (k + 8 <= a.k) bv = *(const h8*)(xr + t * 16);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv, acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) red[wave][i][lane] = acc[i];
+        __syncthreads();
+        for (int e = tid; e < 16 * 64; e += DLF_FC_WAVES * 64) {
+            const int i = e >> 6, ln = e & 63;
+            float s = 0.0f;
+#pragma unroll
+            for (int w = 0; w < DLF_FC_WAVES; ++w) s += red[w][i][ln];
+            const int co = cb * 32 + (i >> 2) * 8 + (ln >> 5) * 4 + (i & 3);
+            const int im = nb + (ln & 31);
+            if (co < a.cout && im < a.batch)
+                y[(size_t)im * a.cout + co] = (half_t)apply_act(s + a.bias[co], a.act);
+        }
+        __syncthreads();
+    }
+}
+
+// Global average pooling: fp32 sum over H*W, mean, fp16.
+__global__ __launch_bounds__(256) void k_gap(const DlfGapArgs a)
+{
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= a.batch * a.c) return;
+    const int n = idx / a.c, c = idx - n * a.c;
+    const half_t* p = (const half_t*)a.x + (size_t)n * a.hw * a.c + c;
+    float s = 0.0f;
+    for (int i = 0; i < a.hw; ++i) s += (float)p[(size_t)i * a.c];
+    ((half_t*)a.y)[idx] = (half_t)(s / (float)a.hw);
+}
+
+typedef void (*group_kernel_t)(const DlfGroupArgs);
+static group_kernel_t group_kernel(int variant)
+{
+    switch (variant) {
+    case 0: return k_group<2, 4>;
+    case 1: return k_group<2, 2>;
+    case 2: return k_group<1, 4>;
+    case 3: return k_group<1, 2>;
+    case 4: return k_group<4, 2>;
+    default: return nullptr;
+    }
+}
+
+extern "C" int dlf_kernels_init(void)
+{
+    for (int v = 0; v < 5; ++v) {
+        hipError_t e = hipFuncSetAttribute((const void*)group_kernel(v),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return (int)e;
+    }
+    return 0;
+}
+
+extern "C" int dlf_launch_group(const DlfGroupArgs* a, int variant, int grid, int lds_bytes,
+                                void* stream)
+{
+    group_kernel_t k = group_kernel(variant);
+    if (k == nullptr || grid <= 0) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(k, dim3(grid), dim3(DLF_WG_THREADS), (size_t)lds_bytes, (hipStream_t)stream,
+                       *a);
+    return (int)hipGetLastError();
+}
+
+extern "C" int dlf_launch_fc(const DlfFcArgs* a, void* stream)
+{
+    hipLaunchKernelGGL(k_fc, dim3(a->ncb), dim3(DLF_FC_WAVES * 64), 0, (hipStream_t)stream, *a);
+    return (int)hipGetLastError();
+}
+
+extern "C" int dlf_launch_gap(const DlfGapArgs* a, void* stream)
+{
+    const int total = a->batch * a->c;
+    hipLaunchKernelGGL(k_gap, dim3((total + 255) / 256), dim3(256), 0, (hipStream_t)stream, *a);
+    return (int)hipGetLastError();
+}

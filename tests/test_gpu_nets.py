@@ -1,0 +1,187 @@
+"""GPU parity of the five synthetic workloads against the CPU oracle, through the C ABI.
+
+Small batches are compared element by element on the whole output.  At the large batch of a
+workload the oracle is run on sampled images only (images are independent, so each sampled
+image's output is computed exactly as in a full run), in the same launch configuration the
+benchmark times.  Every fusion group of the tuned plan is also checked on its own, the oracle
+being fed the GPU's own group input, so errors cannot hide behind later layers."""
+import numpy as np
+import pytest
+import torch
+
+from synth import nets, gen
+from gpu_util import compare, announce
+
+pytestmark = pytest.mark.gpu
+
+
+def _session(net, batch, ws, bs, **plan):
+    from paper_2011_05630_amd.runner import Session
+    return Session(net, batch, ws, bs, **plan)
+
+
+def _manual(lasts, budget):
+    from paper_2011_05630_amd import binding as B
+    return dict(mode=B.TUNER_MANUAL, group_last=list(lasts), group_budget=[budget] * len(lasts))
+
+
+def _check_groups(s, net, x, ws, bs):
+    """Each group's output vs the oracle applied to the GPU's own input of that group."""
+    from oracle import oracle as o
+    n = len(net["layers"])
+    outs = {-1: x.astype(np.float32)}
+    for i in range(n):
+        t = s.layer_output(i)
+        if t is not None:
+            outs[i] = t.float().cpu().numpy()
+    for g in s.groups:
+        if g["last"] == n - 1:
+            continue
+        given = {k: v for k, v in outs.items() if k < g["first"]}
+        ref = o.run_net(net, None, ws, bs, first=g["first"], last=g["last"], given=given)
+        compare(outs[g["last"]], ref, "  group [%d,%d]" % (g["first"], g["last"]))
+
+
+def test_config1_two_layer_block_fused_vs_unfused():
+    from oracle import oracle as o
+    net = nets.two_layer_block()
+    x, ws, bs = gen.make_params(net, 1)
+    ref = o.run_net(net, x, ws, bs)
+    res = {}
+    for name, lasts in (("fused", [1]), ("unfused", [0, 1])):
+        for budget in (32, 64, 128, 256):
+            announce("config1", name, budget)
+            s = _session(net, 1, ws, bs, **_manual(lasts, budget))
+            got = s.run_numpy(x)
+            s.close()
+            compare(got, ref, "config1 %s budget %d" % (name, budget))
+            res[(name, budget)] = got
+    # the budget never changes the arithmetic
+    for name in ("fused", "unfused"):
+        for budget in (64, 128, 256):
+            assert np.array_equal(res[(name, budget)], res[(name, 32)])
+
+
+PARTITIONS = {1: [0, 1, 2, 3], 2: [1, 3], 3: [2, 3], 4: [3]}
+
+
+@pytest.mark.parametrize("c", [16, 32, 64, 128, 256])
+@pytest.mark.parametrize("batch", [1, 8])
+def test_config2_layer_sweep(c, batch):
+    from oracle import oracle as o
+    from paper_2011_05630_amd.binding import DlfError, DLF_ERR_INFEASIBLE
+    net = nets.chain4(c)
+    x, ws, bs = gen.make_params(net, batch)
+    ref = o.run_net(net, x, ws, bs)
+    ran = 0
+    for depth, lasts in PARTITIONS.items():
+        for budget in (32, 64, 128, 256):
+            announce("config2 C", c, "batch", batch, "depth", depth, "budget", budget)
+            try:
+                s = _session(net, batch, ws, bs, **_manual(lasts, budget))
+            except DlfError as e:
+                assert e.status == DLF_ERR_INFEASIBLE, e
+                print("  infeasible (on-chip memory):", e)
+                continue
+            got = s.run_numpy(x)
+            s.close()
+            compare(got, ref, "config2 C=%d b=%d depth=%d budget=%d" % (c, batch, depth, budget))
+            ran += 1
+    assert ran >= 4          # depth 1 is always feasible
+
+
+def _net_case(net, batch, sample, check_groups, plans):
+    from oracle import oracle as o
+    x, ws, bs = gen.make_params(net, batch)
+    xs = x[sample]
+    ref = o.run_net(net, xs, ws, bs)
+    for pname, plan in plans:
+        announce(net["name"], "batch", batch, "plan", pname)
+        s = _session(net, batch, ws, bs, **plan)
+        print("  groups:", [(g["first"], g["last"], g["budget"]) for g in s.groups])
+        got = s.run_numpy(x)
+        compare(got[sample], ref, "%s b=%d %s" % (net["name"], batch, pname))
+        if check_groups:
+            _check_groups(s, net, x, ws, bs)
+        s.close()
+
+
+def _plans(net):
+    from paper_2011_05630_amd import binding as B
+    n = len(net["layers"])
+    return [("dp", dict(mode=B.TUNER_DP)), ("greedy", dict(mode=B.TUNER_GREEDY)),
+            ("unfused", _manual(list(range(n)), 256))]
+
+
+def test_config3_vgg16_batch1():
+    net = nets.vgg16()
+    _net_case(net, 1, [0], True, _plans(net))
+
+
+def test_config3_vgg16_batch16_sampled():
+    net = nets.vgg16()
+    _net_case(net, 16, [0, 15], False, _plans(net)[:1])
+
+
+def test_config4_resnet50_batch1():
+    net = nets.resnet50()
+    _net_case(net, 1, [0], True, _plans(net))
+
+
+def test_config4_resnet50_batch32_sampled():
+    net = nets.resnet50()
+    _net_case(net, 32, [0, 17, 31], False, _plans(net)[:1])
+
+
+def test_config5_mobilenet_batch1():
+    net = nets.mobilenet_v1()
+    _net_case(net, 1, [0], True, _plans(net))
+
+
+def test_config5_mobilenet_batch64_sampled():
+    net = nets.mobilenet_v1()
+    _net_case(net, 64, [0, 33, 63], False, _plans(net)[:1])
+
+
+def test_other_evaluated_networks_small_batch():
+    # shapes of the paper's other evaluation networks (Table "Networks description")
+    for net in (nets.resnet18(), nets.alexnet(), nets.vgg19(in_hw=64)):
+        _net_case(net, 2, [0, 1], False, _plans(net)[:1])
+
+
+def test_run_is_repeatable_and_async_on_a_side_stream():
+    from oracle import oracle as o
+    net = nets.chain4(32, 28)
+    x, ws, bs = gen.make_params(net, 2)
+    s = _session(net, 2, ws, bs)
+    xt = torch.from_numpy(x).cuda()
+    y0 = s.run(xt).clone()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        y1 = s.run(xt)
+        y2 = s.run(xt)
+    st.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1) and torch.equal(y1, y2)
+    compare(y0.cpu().numpy(), o.run_net(net, x, ws, bs), "chain4 c32 28x28")
+    s.close()
+
+
+def test_error_paths_return_status_not_crash():
+    from paper_2011_05630_amd import binding as B
+    net = nets.chain4(256)
+    h = B.dlf_net_create(net["layers"], 56, 56, 256)          # shape-only
+    with pytest.raises(B.DlfError) as e:
+        B.dlf_plan(h, 1, mode=B.TUNER_MANUAL, group_last=[3], group_budget=[64],
+                   max_lds_bytes=16 * 1024)
+    assert e.value.status == B.DLF_ERR_INFEASIBLE
+    p = B.dlf_plan(h, 1)
+    x = torch.zeros(1, 56, 56, 256, dtype=torch.float16, device="cuda")
+    y = torch.zeros_like(x)
+    ws = torch.empty(max(B.dlf_plan_workspace_bytes(p), 256), dtype=torch.uint8, device="cuda")
+    B.dlf_plan_bind_workspace(p, ws.data_ptr(), ws.numel())
+    with pytest.raises(B.DlfError) as e:
+        B.dlf_run(p, x.data_ptr(), y.data_ptr(), None)
+    assert e.value.status == 7                                  # no weights
+    B.dlf_plan_destroy(p)
+    B.dlf_net_destroy(h)
