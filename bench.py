@@ -1,0 +1,236 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused-layer CNN executor on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--batch B]
+                    [--plan dp|greedy|unfused] [--table] [--no-cpu]
+
+A step is one pass of the whole hot path (every fusion group of the plan) over one batch of
+synthetic input that is already resident in HBM.  Prints ONE JSON line: images/s, the roofline
+figures of the dominant kernel (measured with HIP events on the launch stream) and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_FP16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA
+RIDGE = MFMA_FP16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # FLOP per byte
+
+VARIANT_NAME = {0: "k_group<2,4>", 1: "k_group<2,2>", 2: "k_group<1,4>", 3: "k_group<1,2>",
+                4: "k_group<4,2>"}
+
+
+def workloads():
+    from synth import nets
+    w = {
+        "block2": (nets.two_layer_block, 1),
+        "vgg16": (nets.vgg16, 16),
+        "resnet50": (nets.resnet50, 32),
+        "mobilenet_v1": (nets.mobilenet_v1, 64),
+    }
+    for c in (16, 32, 64, 128, 256):
+        w["chain4_c%d" % c] = ((lambda c=c: nets.chain4(c)), 8)
+    return w
+
+
+def layer_bytes_flops(net, batch):
+    """Algorithmic MACs, weight bytes and tensor bytes per layer (Eq. 1/2; fp16 tensors)."""
+    from synth import nets
+    shapes = nets.infer_shapes(net)
+    rows = []
+    for L, (hin, hout) in zip(net["layers"], shapes):
+        if L["op"] == "conv":
+            mac = hout[0] * hout[1] * L["kh"] * L["kw"] * L["cin"] * L["cout"]
+            wb = L["cout"] * L["kh"] * L["kw"] * L["cin"] * 2 + 4 * L["cout"]
+        elif L["op"] == "dwconv":
+            mac = hout[0] * hout[1] * L["kh"] * L["kw"] * L["cout"]
+            wb = L["cout"] * L["kh"] * L["kw"] * 2 + 4 * L["cout"]
+        elif L["op"] == "fc":
+            mac = L["cin"] * L["cout"]
+            wb = L["cin"] * L["cout"] * 2 + 4 * L["cout"]
+        else:
+            mac, wb = 0, 0
+        rows.append(dict(mac=mac * batch, wbytes=wb,
+                         in_bytes=batch * hin[0] * hin[1] * hin[2] * 2,
+                         out_bytes=batch * hout[0] * hout[1] * hout[2] * 2))
+    return rows
+
+
+def group_accounting(net, batch, session):
+    """Per fusion group: algorithmic FLOPs and the bytes fusion must move (group input + output +
+    weights + residual operand)."""
+    from paper_2011_05630_amd import binding as B
+    rows = layer_bytes_flops(net, batch)
+    out = []
+    for g, info in enumerate(session.groups):
+        f, l = info["first"], info["last"]
+        flops = 2 * sum(rows[i]["mac"] for i in range(f, l + 1))
+        wbytes = sum(rows[i]["wbytes"] for i in range(f, l + 1))
+        in_layer, res_layer = B.dlf_plan_group_io(session.plan, g)
+        byts = rows[f]["in_bytes"] + rows[l]["out_bytes"] + wbytes
+        if res_layer >= -1:
+            byts += rows[l]["out_bytes"] if res_layer < 0 else rows[res_layer]["out_bytes"]
+        cfg = B.dlf_plan_group_config(session.plan, g)
+        if cfg["kind"] == 1:
+            kname = "k_fc"
+        elif cfg["kind"] == 2:
+            kname = "k_gap"
+        else:
+            kname = VARIANT_NAME[cfg["variant"]]
+        out.append(dict(first=f, last=l, budget=info["budget"], flops=flops, bytes=byts,
+                        kernel=kname, tile=(info["tile_h"], info["tile_w"]), cfg=cfg,
+                        model_us=info["model_cost"] / 1e6))
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="resnet50")
+    ap.add_argument("--batch", type=int, default=0)
+    ap.add_argument("--plan", default="dp", choices=["dp", "greedy", "unfused"])
+    ap.add_argument("--budget", type=int, default=256, help="budget of every group of --plan unfused")
+    ap.add_argument("--table", action="store_true", help="per-group table on stderr")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from synth import gen
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+
+    wl = workloads()
+    if args.workload not in wl:
+        print("unknown workload %s (have: %s)" % (args.workload, ", ".join(sorted(wl))),
+              file=sys.stderr)
+        sys.exit(2)
+    builder, default_batch = wl[args.workload]
+    batch = args.batch or default_batch
+    net = builder()
+    x, ws, bs = gen.make_params(net, batch)
+    n = len(net["layers"])
+    if args.plan == "dp":
+        plan = dict(mode=B.TUNER_DP)
+    elif args.plan == "greedy":
+        plan = dict(mode=B.TUNER_GREEDY)
+    else:
+        plan = dict(mode=B.TUNER_MANUAL, group_last=list(range(n)), group_budget=[args.budget] * n)
+    s = Session(net, batch, ws, bs, **plan)
+    xt = torch.from_numpy(x).cuda()
+    out = torch.empty(s.out_shape, dtype=torch.float16, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+
+    for _ in range(args.warmup):
+        B.dlf_run(s.plan, xt.data_ptr(), out.data_ptr(), stream)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        B.dlf_run(s.plan, xt.data_ptr(), out.data_ptr(), stream)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps   # wall clock, sync on both sides
+    event_ms_per_step = e0.elapsed_time(e1) / args.steps
+    images_per_s = batch / (ms_per_step * 1e-3)
+
+    # per-group durations: HIP event pair around every group launch, on the launch stream
+    reps = max(5, min(50, args.steps))
+    gms = B.dlf_run_profiled(s.plan, xt.data_ptr(), out.data_ptr(), stream, reps)
+    acct = group_accounting(net, batch, s)
+    by_kernel = {}
+    for a, ms in zip(acct, gms):
+        a["ms"] = ms
+        k = by_kernel.setdefault(a["kernel"], dict(ms=0.0, flops=0, bytes=0, launches=0))
+        k["ms"] += ms
+        k["flops"] += a["flops"]
+        k["bytes"] += a["bytes"]
+        k["launches"] += 1
+    dom = max(by_kernel, key=lambda k: by_kernel[k]["ms"])
+    d = by_kernel[dom]
+    ai = d["flops"] / max(d["bytes"], 1)
+    avg_ms = d["ms"] / d["launches"]
+    if ai >= RIDGE:
+        ach = d["flops"] / d["launches"] / (avg_ms * 1e-3) / 1e12
+        roof = dict(bound="mfma", achieved=ach, peak=MFMA_FP16_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=ach / MFMA_FP16_PEAK_TFLOPS)
+    else:
+        ach = d["bytes"] / d["launches"] / (avg_ms * 1e-3) / 1e9
+        roof = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=ach / HBM_PEAK_GBS)
+    roof.update(traffic=None, kernel=dom, launches_per_step=d["launches"],
+                avg_launch_us=avg_ms * 1e3, flops_per_launch=d["flops"] / d["launches"],
+                bytes_per_launch=d["bytes"] / d["launches"],
+                share_of_step=d["ms"] / max(sum(gms), 1e-9))
+
+    if args.table:
+        print("%-10s %-13s %6s %-7s %9s %9s %9s %8s %8s %7s %8s" % (
+            "layers", "kernel", "budget", "tile", "us", "model_us", "GFLOP", "MB", "TFLOP/s",
+            "GB/s", "roof%"), file=sys.stderr)
+        for a in acct:
+            t = a["ms"] * 1e-3
+            tf = a["flops"] / t / 1e12
+            gb = a["bytes"] / t / 1e9
+            aig = a["flops"] / max(a["bytes"], 1)
+            frac = tf / MFMA_FP16_PEAK_TFLOPS if aig >= RIDGE else gb / HBM_PEAK_GBS
+            print("%-10s %-13s %6d %-7s %9.2f %9.2f %9.3f %8.2f %8.1f %7.0f %7.1f%s  s%d x%d lds%dk" % (
+                "%d-%d" % (a["first"], a["last"]), a["kernel"], a["budget"],
+                "%dx%d" % a["tile"], a["ms"] * 1e3, a["model_us"], a["flops"] / 1e9,
+                a["bytes"] / 1e6, tf, gb, 100 * frac, "M" if aig >= RIDGE else "H",
+                a["cfg"]["stream0"], a["cfg"]["nslices"], a["cfg"]["lds_bytes"] // 1024),
+                file=sys.stderr)
+        print("sum of groups %.1f us; step %.1f us" % (sum(gms) * 1e3, ms_per_step * 1e3),
+              file=sys.stderr)
+
+    cpu = None
+    if not args.no_cpu:
+        from oracle import oracle as o
+        nsample = 1
+        t = time.perf_counter()
+        o.run_net(net, x[:1], ws, bs)
+        dt1 = time.perf_counter() - t
+        if dt1 < 5.0:
+            nsample = int(max(1, min(batch, 15.0 // max(dt1, 1e-3))))
+            t = time.perf_counter()
+            o.run_net(net, x[:nsample], ws, bs)
+            dt = time.perf_counter() - t
+        else:
+            dt = dt1
+        cpu = dict(value=nsample / dt, unit="images/s", cores=o.num_threads(), kind="oracle",
+                   sample="%d image(s) of the same seeded batch, whole network, fp32 nested loops"
+                          % nsample)
+
+    total_flops = sum(a["flops"] for a in acct)
+    res = {
+        "metric": "images_per_sec", "value": images_per_s, "unit": "images/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": "%s_b%d" % (net["name"], batch), "batch": batch,
+                   "plan": args.plan, "groups": len(s.groups), "layers": n,
+                   "input": "%dx%dx%d" % (net["in_h"], net["in_w"], net["in_c"])},
+        "event_ms_per_step": event_ms_per_step,
+        "algorithmic_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
+        "roofline": roof, "cpu_baseline": cpu,
+    }
+    s.close()
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -118,6 +118,12 @@ dlf_status dlf_plan_bind_workspace(dlf_plan_t* plan, void* dev_ptr, size_t bytes
  * both DEVICE pointers that must not alias; hip_stream is a hipStream_t (NULL = default stream).
  * Asynchronous; reports launch errors only. */
 dlf_status dlf_run(const dlf_plan_t* plan, const void* in_dev, void* out_dev, void* hip_stream);
+/* Profiling variant of dlf_run: runs the plan `reps` times with a HIP event pair around every
+ * group launch on hip_stream, waits for the stream, and writes the mean duration of each group
+ * in milliseconds to group_ms[dlf_plan_num_groups] (HOST array).  Creates and destroys events,
+ * synchronises: not for the serving path. */
+dlf_status dlf_run_profiled(const dlf_plan_t* plan, const void* in_dev, void* out_dev,
+                            void* hip_stream, int32_t reps, float* group_ms);
 /* Runs only group g: in_dev = the group's input tensor, out_dev = its output tensor; a residual
  * operand produced outside the group is read from res_dev (may be NULL if the group has none). */
 dlf_status dlf_run_group(const dlf_plan_t* plan, int32_t g, const void* in_dev, const void* res_dev,
@@ -132,11 +138,15 @@ const void* dlf_plan_layer_output(const dlf_plan_t* plan, int32_t layer);
 dlf_status dlf_plan_group_config(const dlf_plan_t* plan, int32_t g, int32_t* kind, int32_t* variant,
                                  int32_t* nslices, int32_t* slice_c, int32_t* stream0,
                                  int32_t* lds_bytes);
-/* Testing hook: th > 0 forces tile th x tw, register-tile variant, channel slicing and streaming
- * for every group planned afterwards (groups it does not fit become infeasible); th = 0 restores
- * the automatic choice.  Process-wide, not thread-safe. */
+/* Tensors group g reads from HBM: *in_layer = layer whose output is the group input (-1 = the
+ * network input); *res_layer = layer whose output is added as a residual (-2 = none). */
+dlf_status dlf_plan_group_io(const dlf_plan_t* plan, int32_t g, int32_t* in_layer, int32_t* res_layer);
+/* Testing hook: th > 0 forces tile th x tw, register-tile variant, channel slicing, streaming and
+ * channels per streaming round (kc: 32, 64 or 128; 0 = 32) for every group planned afterwards
+ * (groups it does not fit become infeasible); th = 0 restores the automatic choice.
+ * Process-wide, not thread-safe. */
 void dlf_debug_force_config(int32_t th, int32_t tw, int32_t variant, int32_t nslices,
-                            int32_t slice_c, int32_t stream0);
+                            int32_t slice_c, int32_t stream0, int32_t kc);
 
 const char* dlf_status_string(dlf_status s);
 const char* dlf_last_error(void);

@@ -23,6 +23,19 @@
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Threads the loops below will use (reported next to oracle timings). */
+int orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 #define ORC_DEFINE_CONV(NAME, ACC)                                                              \
 void NAME(const float* in, int N, int H, int W, int Cin, const float* w, const float* bias,     \

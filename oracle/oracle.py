@@ -44,6 +44,12 @@ def lib():
     return _lib
 
 
+def num_threads():
+    """Host threads the C loops run on."""
+    lib().orc_num_threads.restype = ctypes.c_int
+    return int(lib().orc_num_threads())
+
+
 def _f32(a):
     return np.ascontiguousarray(a, dtype=np.float32)
 

@@ -92,10 +92,14 @@ def lib():
     L.dlf_last_error.restype = ctypes.c_char_p
     L.dlf_cost_model_version.argtypes = []
     L.dlf_cost_model_version.restype = i32
-    L.dlf_debug_force_config.argtypes = [i32, i32, i32, i32, i32, i32]
+    L.dlf_debug_force_config.argtypes = [i32, i32, i32, i32, i32, i32, i32]
     L.dlf_debug_force_config.restype = None
     L.dlf_plan_group_config.argtypes = [vp, i32, i32p, i32p, i32p, i32p, i32p, i32p]
     L.dlf_plan_group_config.restype = i32
+    L.dlf_run_profiled.argtypes = [vp, vp, vp, vp, i32, ctypes.POINTER(ctypes.c_float)]
+    L.dlf_run_profiled.restype = i32
+    L.dlf_plan_group_io.argtypes = [vp, i32, i32p, i32p]
+    L.dlf_plan_group_io.restype = i32
     _lib = L
     return L
 
@@ -191,6 +195,14 @@ def dlf_plan_group_config(plan, g):
                 stream0=v[4].value, lds_bytes=v[5].value)
 
 
+def dlf_plan_group_io(plan, g):
+    """-> (in_layer, res_layer): producers of the group's input (-1 = net input) and residual
+    operand (-2 = none)."""
+    a, b = ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().dlf_plan_group_io(plan, g, ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
+
+
 def dlf_plan_groups(plan):
     return [dlf_plan_group(plan, g) for g in range(dlf_plan_num_groups(plan))]
 
@@ -217,6 +229,14 @@ def dlf_run(plan, in_ptr, out_ptr, stream=None):
     _check(lib().dlf_run(plan, in_ptr, out_ptr, stream))
 
 
+def dlf_run_profiled(plan, in_ptr, out_ptr, stream, reps):
+    """-> list of mean per-group durations in milliseconds (HIP events on `stream`)."""
+    n = dlf_plan_num_groups(plan)
+    ms = (ctypes.c_float * n)()
+    _check(lib().dlf_run_profiled(plan, in_ptr, out_ptr, stream, reps, ms))
+    return list(ms)
+
+
 def dlf_run_group(plan, g, in_ptr, res_ptr, out_ptr, stream=None):
     _check(lib().dlf_run_group(plan, g, in_ptr, res_ptr, out_ptr, stream))
 
@@ -229,7 +249,7 @@ def dlf_cost_model_version():
     return lib().dlf_cost_model_version()
 
 
-def dlf_debug_force_config(th=0, tw=0, variant=0, nslices=1, slice_c=0, stream0=0):
+def dlf_debug_force_config(th=0, tw=0, variant=0, nslices=1, slice_c=0, stream0=0, kc=0):
     """Testing hook: th > 0 forces the tile/register-tile/slicing of every group planned
     afterwards (th = 0 restores automatic choice)."""
-    lib().dlf_debug_force_config(th, tw, variant, nslices, slice_c, stream0)
+    lib().dlf_debug_force_config(th, tw, variant, nslices, slice_c, stream0, kc)

@@ -136,6 +136,7 @@ struct TileCfg {
     int variant;     // register tile of CONV stages
     int nslices, slice_c;
     int stream0;
+    int kc;          // stream0: channels per streaming round (32, 64 or 128)
 };
 
 struct GroupPlan {
@@ -242,7 +243,7 @@ bool group_stages(const dlf_net_s& net, int first, int last, std::vector<StageSp
     for (size_t k = 1; k < st.size(); ++k) {
         if (st[k].kind == DLF_ST_CONV && st[k - 1].kind != DLF_ST_CONV) {
             const Layer& C = net.L[st[k].layer];
-            if (C.d.cin % C.kc != 0) { why = "channel count not a multiple of the K chunk"; return false; }
+            if (C.d.cin % 32 != 0) { why = "channel count not a multiple of the K chunk"; return false; }
         }
     }
     return true;
@@ -303,9 +304,14 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
         h = st.ih; w = st.iw;
         st.w = L.d_w; st.bias = L.d_bias; st.res = nullptr;
         if (st.kind == DLF_ST_CONV) {
-            st.kc = L.kc; st.cin_pad = L.cin_pad; st.ncb = L.ncb; st.nsteps = L.nsteps;
+            st.kc = (s == 0 && tc.stream0) ? tc.kc : 32;
+            st.kc_shift = st.kc == 128 ? 4 : (st.kc == 64 ? 3 : 2);
+            st.cin_pad = L.cin_pad; st.ncb = L.ncb; st.nsteps = L.nsteps;
+            if (st.kc != 32 && st.kc != 64 && st.kc != 128) return b;
+            if (L.cin_pad % st.kc != 0) return b;
+            if (st.kc != 32 && (L.d.kh * L.d.kw != 1 || (L.d.cin & 7) != 0)) return b;
         } else {
-            st.kc = 8; st.cin_pad = round_up(L.d.cin, 8); st.ncb = 0; st.nsteps = 0;
+            st.kc = 8; st.kc_shift = 0; st.cin_pad = round_up(L.d.cin, 8); st.ncb = 0; st.nsteps = 0;
         }
     }
     ga.iy_mul = my; ga.iy_off = oy; ga.ix_mul = mx; ga.ix_off = ox;
@@ -408,7 +414,7 @@ uint64_t group_cost_ps(const Built& b, int budget)
 }
 
 // Testing hook: when th > 0 every group is built with exactly this configuration.
-TileCfg g_force = {0, 0, 0, 1, 0, 0};
+TileCfg g_force = {0, 0, 0, 1, 0, 0, 32};
 
 const int TILE_H[] = {2, 4, 7, 8, 14, 16};
 const int TILE_W[] = {4, 7, 8, 14, 16, 28, 32};
@@ -445,24 +451,28 @@ bool choose_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
                 if (conv0) {
                     // slicing over output channels: only if no later CONV stage
                     const int ncb = L0.ncb, FCv = VAR_FC[variant];
+                    const bool pointwise = L0.d.kh * L0.d.kw == 1 && (L0.d.cin & 7) == 0;
                     for (int stream0 = 1; stream0 >= 0; --stream0) {
-                        TileCfg t{th, tw, variant, 1, 0, stream0};
-                        cands.push_back(t);
-                        if (!later_conv && stream0) {
-                            for (int cg = 1; cg <= 4; cg *= 2) {
-                                const int sc = FCv * cg * 32;
-                                if (sc >= ncb * 32) continue;
-                                TileCfg u{th, tw, variant, ceil_div(ncb * 32, sc), sc, 1};
-                                cands.push_back(u);
+                        for (int kc = 32; kc <= (stream0 && pointwise ? 128 : 32); kc *= 2) {
+                            if (L0.cin_pad % kc != 0) continue;
+                            TileCfg t{th, tw, variant, 1, 0, stream0, kc};
+                            cands.push_back(t);
+                            if (!later_conv && stream0) {
+                                for (int cg = 1; cg <= 4; cg *= 2) {
+                                    const int sc = FCv * cg * 32;
+                                    if (sc >= ncb * 32) continue;
+                                    TileCfg u{th, tw, variant, ceil_div(ncb * 32, sc), sc, 1, kc};
+                                    cands.push_back(u);
+                                }
                             }
                         }
                     }
                 } else {
-                    TileCfg t{th, tw, variant, 1, 0, 0};
+                    TileCfg t{th, tw, variant, 1, 0, 0, 32};
                     cands.push_back(t);
                     if (!later_conv) {
                         for (int sc = 32; sc < L0.d.cin; sc *= 2) {
-                            TileCfg u{th, tw, variant, ceil_div(L0.d.cin, sc), sc, 0};
+                            TileCfg u{th, tw, variant, ceil_div(L0.d.cin, sc), sc, 0, 32};
                             cands.push_back(u);
                         }
                     }
@@ -698,7 +708,7 @@ dlf_status dlf_net_create(const dlf_layer_desc* layers, int32_t n, int32_t in_h,
         if (d.op == DLF_MAXPOOL && d.pad >= d.kh)
             return bad(DLF_ERR_UNSUPPORTED, "pooling pad must be smaller than the window");
         if (d.op == DLF_CONV || d.op == DLF_FC) {
-            L.kc = d.cin <= 16 ? 16 : 32;
+            L.kc = 32;
             L.cin_pad = round_up(d.cin, L.kc);
             L.ncb = ceil_div(d.cout, 32);
             L.nsteps = (L.cin_pad / L.kc) * d.kh * d.kw * (L.kc / 16);
@@ -942,10 +952,19 @@ dlf_status dlf_plan_group_config(const dlf_plan_t* plan, int32_t g, int32_t* kin
     return DLF_OK;
 }
 
-void dlf_debug_force_config(int32_t th, int32_t tw, int32_t variant, int32_t nslices, int32_t slice_c,
-                            int32_t stream0)
+dlf_status dlf_plan_group_io(const dlf_plan_t* plan, int32_t g, int32_t* in_layer, int32_t* res_layer)
 {
-    g_force = TileCfg{th, tw, variant, nslices < 1 ? 1 : nslices, slice_c, stream0};
+    if (!plan || g < 0 || g >= (int)plan->G.size()) return fail(DLF_ERR_INVALID_ARG, "bad group index");
+    const GroupPlan& G = plan->G[g];
+    if (in_layer) *in_layer = G.in_layer;
+    if (res_layer) *res_layer = G.res_stage >= 0 ? G.res_layer : -2;
+    return DLF_OK;
+}
+
+void dlf_debug_force_config(int32_t th, int32_t tw, int32_t variant, int32_t nslices, int32_t slice_c,
+                            int32_t stream0, int32_t kc)
+{
+    g_force = TileCfg{th, tw, variant, nslices < 1 ? 1 : nslices, slice_c, stream0, kc > 0 ? kc : 32};
 }
 
 size_t dlf_plan_workspace_bytes(const dlf_plan_t* plan) { return plan ? plan->ws_bytes : 0; }
@@ -1006,6 +1025,54 @@ dlf_status dlf_run_group(const dlf_plan_t* plan, int32_t g, const void* in_dev, 
         return fail(DLF_ERR_INVALID_ARG, "dlf_run_group: bad argument");
     if (!plan->net->has_weights) return fail(DLF_ERR_NO_WEIGHTS, "network was created without weights");
     return launch_one(plan, plan->G[g], in_dev, res_dev, out_dev, hip_stream);
+}
+
+static void group_pointers(const dlf_plan_s* plan, size_t g, const void* in_dev, void* out_dev,
+                           const void** in, const void** res, void** out)
+{
+    const GroupPlan& G = plan->G[g];
+    *in = G.in_layer < 0 ? in_dev : plan->ws + plan->layer_off[G.in_layer];
+    *res = G.res_stage >= 0 ? plan->ws + plan->layer_off[G.res_layer] : nullptr;
+    *out = (g + 1 == plan->G.size()) ? out_dev : (void*)(plan->ws + plan->layer_off[G.last]);
+}
+
+dlf_status dlf_run_profiled(const dlf_plan_t* plan, const void* in_dev, void* out_dev, void* hip_stream,
+                            int32_t reps, float* group_ms)
+{
+    if (!plan || !in_dev || !out_dev || !group_ms || reps <= 0)
+        return fail(DLF_ERR_INVALID_ARG, "dlf_run_profiled: bad argument");
+    if (!plan->net->has_weights) return fail(DLF_ERR_NO_WEIGHTS, "network was created without weights");
+    if (plan->ws_bytes > 0 && !plan->ws) return fail(DLF_ERR_INVALID_ARG, "no workspace bound");
+    const size_t ng = plan->G.size();
+    hipStream_t st = (hipStream_t)hip_stream;
+    std::vector<hipEvent_t> ev(2 * ng * reps);
+    for (hipEvent_t& e : ev)
+        if (hipEventCreate(&e) != hipSuccess) return fail(DLF_ERR_HIP, "hipEventCreate failed");
+    dlf_status rs = DLF_OK;
+    for (int r = 0; r < reps && rs == DLF_OK; ++r)
+        for (size_t g = 0; g < ng; ++g) {
+            const void *in, *res;
+            void* out;
+            group_pointers(plan, g, in_dev, out_dev, &in, &res, &out);
+            (void)hipEventRecord(ev[2 * (r * ng + g)], st);
+            rs = launch_one(plan, plan->G[g], in, res, out, hip_stream);
+            (void)hipEventRecord(ev[2 * (r * ng + g) + 1], st);
+            if (rs != DLF_OK) break;
+        }
+    if (hipStreamSynchronize(st) != hipSuccess && rs == DLF_OK) rs = fail(DLF_ERR_HIP, "stream synchronise failed");
+    if (rs == DLF_OK) {
+        for (size_t g = 0; g < ng; ++g) {
+            double sum = 0;
+            for (int r = 0; r < reps; ++r) {
+                float ms = 0;
+                (void)hipEventElapsedTime(&ms, ev[2 * (r * ng + g)], ev[2 * (r * ng + g) + 1]);
+                sum += ms;
+            }
+            group_ms[g] = (float)(sum / reps);
+        }
+    }
+    for (hipEvent_t& e : ev) (void)hipEventDestroy(e);
+    return rs;
 }
 
 dlf_status dlf_run(const dlf_plan_t* plan, const void* in_dev, void* out_dev, void* hip_stream)

@@ -18,8 +18,9 @@ enum { DLF_ST_CONV = 0, DLF_ST_MAXPOOL = 1, DLF_ST_DW = 2 };
 struct DlfStage {
     int32_t kind;
     int32_t cin;          // true input channels
-    int32_t cin_pad;      // input channels padded to a multiple of kc (zero weights beyond cin)
-    int32_t kc;           // channels per K-chunk: 16 or 32
+    int32_t cin_pad;      // input channels padded to a multiple of 32 (zero weights beyond cin)
+    int32_t kc;           // CONV streaming: channels brought in per round (32, 64 or 128)
+    int32_t kc_shift;     // log2(kc / 8) = log2 of the 16-byte vectors per pixel per round
     int32_t cout;         // true output channels
     int32_t ncb;          // CONV: number of 32-wide output-channel blocks = ceil(cout/32)
     int32_t kh, kw, stride, pad, act;

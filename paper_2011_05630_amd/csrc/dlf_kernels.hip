@@ -67,8 +67,8 @@ __device__ __forceinline__ h8 load_px8(const half_t* in, int n, int gy, int gx, 
         if ((C & 7) == 0 && c + 8 <= c_end) {
             v = *(const h8*)p;
         } else {
-            for (int j = 0; j < 8; ++j)
-                if (c + j < c_end) v[j] = p[j];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = (c + j < c_end) ? p[j] : (half_t)0;
         }
     }
     return v;
@@ -90,7 +90,91 @@ __device__ __forceinline__ void stage_region(const half_t* in, int n, int H, int
     }
 }
 
-template <int FC, int FP, bool STREAM>
+// One 32-channel K chunk of a convolution stage: every filter tap, two 16-channel MFMA steps per
+// tap.  TAPS = 9 (3x3) and TAPS = 1 (1x1) are fully unrolled so that the compiler can place the
+// waits of the interleaved LDS / global loads exactly; TAPS = 0 is the loop for any other filter.
+//   b0/b1: activation fragments of the two K steps of a tap; each is loaded from LDS while the
+//          other is being multiplied.
+//   a0/a1: weight fragments of the two K steps; each is re-fetched (for the next tap, which is
+//          simply the next 2 KiB of the packed stream) right after its MFMAs were issued.
+template <int FC, int FP, int TAPS>
+__device__ __forceinline__ void mma_chunk(const half_t* src, const int (&pbase)[FP],
+                                          const h8* (&wp)[FC], h8 (&a0)[FC], h8 (&a1)[FC],
+                                          f16v (&acc)[FC][FP], int cs, int iw, int kw, int ntaps)
+{
+    h8 b0[FP], b1[FP];
+    // Per-tap LDS addresses are formed right before each load; the empty asm keeps the compiler
+    // from precomputing all of them outside the chunk loop, which would cost TAPS x FP registers.
+    int pb[FP];
+#pragma unroll
+    for (int p = 0; p < FP; ++p) {
+        pb[p] = pbase[p];
+        asm volatile("" : "+v"(pb[p]));
+    }
+#pragma unroll
+    for (int p = 0; p < FP; ++p) b0[p] = *(const h8*)(src + pb[p]);
+    if (TAPS > 0) {
+        constexpr int KW = (TAPS == 9) ? 3 : 1;
+#pragma unroll
+        for (int t = 0; t < TAPS; ++t) {
+            const int tapoff = ((t / KW) * iw + (t % KW)) * cs;
+#pragma unroll
+            for (int p = 0; p < FP; ++p) b1[p] = *(const h8*)(src + pb[p] + tapoff + 16);
+#pragma unroll
+            for (int f = 0; f < FC; ++f)
+#pragma unroll
+                for (int p = 0; p < FP; ++p)
+                    acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0[f], b0[p], acc[f][p], 0, 0, 0);
+#pragma unroll
+            for (int f = 0; f < FC; ++f) a0[f] = wp[f][0];
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + 1 < TAPS) {
+                const int nextoff = (((t + 1) / KW) * iw + ((t + 1) % KW)) * cs;
+#pragma unroll
+                for (int p = 0; p < FP; ++p) b0[p] = *(const h8*)(src + pb[p] + nextoff);
+            }
+#pragma unroll
+            for (int f = 0; f < FC; ++f)
+#pragma unroll
+                for (int p = 0; p < FP; ++p)
+                    acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1[f], b1[p], acc[f][p], 0, 0, 0);
+#pragma unroll
+            for (int f = 0; f < FC; ++f) { a1[f] = wp[f][64]; wp[f] += 128; }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {
+        const int rowskip = (iw - kw) * cs;
+        int tapoff = 0, kwc = 0;
+        for (int t = 0; t < ntaps; ++t) {
+#pragma unroll
+            for (int p = 0; p < FP; ++p) b1[p] = *(const h8*)(src + pb[p] + tapoff + 16);
+#pragma unroll
+            for (int f = 0; f < FC; ++f)
+#pragma unroll
+                for (int p = 0; p < FP; ++p)
+                    acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0[f], b0[p], acc[f][p], 0, 0, 0);
+#pragma unroll
+            for (int f = 0; f < FC; ++f) a0[f] = wp[f][0];
+            tapoff += cs;
+            if (++kwc == kw) { kwc = 0; tapoff += rowskip; }
+            if (t + 1 < ntaps) {
+#pragma unroll
+                for (int p = 0; p < FP; ++p) b0[p] = *(const h8*)(src + pb[p] + tapoff);
+            }
+#pragma unroll
+            for (int f = 0; f < FC; ++f)
+#pragma unroll
+                for (int p = 0; p < FP; ++p)
+                    acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1[f], b1[p], acc[f][p], 0, 0, 0);
+#pragma unroll
+            for (int f = 0; f < FC; ++f) { a1[f] = wp[f][64]; wp[f] += 128; }
+        }
+    }
+}
+
+// A convolution stage.  STREAM: the input is not resident; it is brought from HBM in rounds of
+// st.kc channels (a multiple of 32) into two alternating LDS buffers.
+template <int FC, int FP, bool STREAM, int TAPS>
 __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage& st, bool last,
                                            int n, int ty0, int tx0, int slice)
 {
@@ -107,47 +191,45 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
     const int n_cg = (cb_end - cb_begin + FC - 1) / FC;
     const int nitems = n_pg * n_cg;
     const int ry0 = ty0 * st.oy_mul + st.oy_off, rx0 = tx0 * st.ox_mul + st.ox_off;
-    const int nchunks = st.cin_pad / st.kc;
-    const int nks = st.kc >> 4;
+    const int kc = STREAM ? st.kc : 32;         // channels per round
+    const int cpr = kc >> 5;                    // 32-channel chunks per round
+    const int nrounds = st.cin_pad / kc;
     const int cs = st.in_cs;
+    const int ntaps = st.kh * st.kw;
     const half_t* in = (const half_t*)a.in;
 
-    // ---- stream mode: per-thread addresses of the vectors this thread stages per chunk ----
-    int s_goff[DLF_STAGE_VECS];   // element offset into `in` for chunk 0, or -1 (zero fill)
-    int s_loff[DLF_STAGE_VECS];   // LDS offset (halfs) inside a chunk buffer, or -1 (nothing)
-    h8 s_reg[DLF_STAGE_VECS];
+    // ---- stream mode: per-thread addresses of the vectors this thread stages per round ----
+    int s_goff[DLF_STAGE_VECS];   // element offset into `in` for round 0, or -1 (zero fill)
+    const int vshift = st.kc_shift;              // log2(16-byte vectors per pixel per round)
+    const int s_total = (st.ih * st.iw) << vshift;
     if (STREAM) {
         const int iy0 = ty0 * a.iy_mul + a.iy_off, ix0 = tx0 * a.ix_mul + a.ix_off;
-        const int nvec = st.kc >> 3;
-        const int total = st.ih * st.iw * nvec;
         if ((st.cin & 7) != 0) {
-            // narrow inputs (e.g. 3 channels): one chunk, element-wise copy, no prefetch
-            stage_region(in, n, a.in_h, a.in_w, a.in_c, iy0, ix0, st.ih, st.iw, 0, st.kc, st.cin,
+            // narrow inputs (e.g. 3 channels): one round, element-wise copy
+            stage_region(in, n, a.in_h, a.in_w, a.in_c, iy0, ix0, st.ih, st.iw, 0, kc, st.cin,
                          cs, lds + st.in_off);
 #pragma unroll
-            for (int i = 0; i < DLF_STAGE_VECS; ++i) { s_goff[i] = -1; s_loff[i] = -1; }
+            for (int i = 0; i < DLF_STAGE_VECS; ++i) s_goff[i] = -1;
         } else {
 #pragma unroll
             for (int i = 0; i < DLF_STAGE_VECS; ++i) {
                 const int v = tid + i * DLF_WG_THREADS;
                 s_goff[i] = -1;
-                s_loff[i] = -1;
-                if (v < total) {
-                    const int pix = v / nvec, part = v - pix * nvec;
+                if (v < s_total) {
+                    const int pix = v >> vshift, part = v & ((1 << vshift) - 1);
                     const int ry = pix / st.iw, rx = pix - ry * st.iw;
                     const int gy = iy0 + ry, gx = ix0 + rx;
-                    s_loff[i] = pix * cs + part * 8;
                     if (gy >= 0 && gy < a.in_h && gx >= 0 && gx < a.in_w)
                         s_goff[i] = ((n * a.in_h + gy) * a.in_w + gx) * a.in_c + part * 8;
                 }
             }
-            // chunk 0
 #pragma unroll
             for (int i = 0; i < DLF_STAGE_VECS; ++i) {
+                const int vi = tid + i * DLF_WG_THREADS;
+                const int part8 = (vi & ((1 << vshift) - 1)) * 8;
                 h8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-                const int part8 = ((tid + i * DLF_WG_THREADS) & (nvec - 1)) * 8;
                 if (s_goff[i] >= 0 && part8 < st.cin) v = *(const h8*)(in + s_goff[i]);
-                if (s_loff[i] >= 0) *(h8*)(lds + st.in_off + s_loff[i]) = v;
+                if (vi < s_total) *(h8*)(lds + st.in_off + (vi >> vshift) * cs + part8) = v;
             }
         }
         __syncthreads();
@@ -182,72 +264,50 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[f][p][i] = 0.0f;
 
-        h8 a_cur[2][FC], a_nxt[2][FC];
+        h8 a0[FC], a1[FC];
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int f = 0; f < FC; ++f) a_cur[ks][f] = wp[f][(ks < nks ? ks : 0) * 64];
-#pragma unroll
-        for (int f = 0; f < FC; ++f) wp[f] += nks * 64;
+        for (int f = 0; f < FC; ++f) { a0[f] = wp[f][0]; a1[f] = wp[f][64]; wp[f] += 128; }
 
-        for (int chunk = 0; chunk < nchunks; ++chunk) {
-            const half_t* src;
+        for (int round = 0; round < nrounds; ++round) {
+            const half_t* src = STREAM ? lds + st.in_off + (round & 1) * st.stream_buf
+                                       : lds + st.in_off + round * 32;
+            if (active) {
+                if (TAPS == 1) {
+                    int j = 0;
+                    for (; j + 1 < cpr; j += 2) {
+                        mma_chunk<FC, FP, 1>(src + j * 32, pbase, wp, a0, a1, acc, cs, st.iw, 1, 1);
+                        mma_chunk<FC, FP, 1>(src + j * 32 + 32, pbase, wp, a0, a1, acc, cs, st.iw, 1, 1);
+                    }
+                    if (j < cpr)
+                        mma_chunk<FC, FP, 1>(src + j * 32, pbase, wp, a0, a1, acc, cs, st.iw, 1, 1);
+                } else {
+                    for (int j = 0; j < cpr; ++j)
+                        mma_chunk<FC, FP, TAPS>(src + j * 32, pbase, wp, a0, a1, acc, cs, st.iw, st.kw,
+                                                ntaps);
+                }
+            }
             if (STREAM) {
-                src = lds + st.in_off + (chunk & 1) * st.stream_buf;
-                if (chunk + 1 < nchunks) {
-                    const int coff = (chunk + 1) * st.kc;
+                // next round: HBM -> registers -> the other LDS buffer.  The loads are issued after
+                // this round's MFMAs so that no staging register is live across them; the second
+                // workgroup resident on the CU computes meanwhile.
+                if (round + 1 < nrounds) {
+                    const int coff = (round + 1) * kc;
+                    half_t* dst = lds + st.in_off + ((round + 1) & 1) * st.stream_buf;
+                    h8 s_reg[DLF_STAGE_VECS];
 #pragma unroll
                     for (int i = 0; i < DLF_STAGE_VECS; ++i) {
                         h8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-                        const int part8 = ((tid + i * DLF_WG_THREADS) & ((st.kc >> 3) - 1)) * 8;
+                        const int part8 = ((tid + i * DLF_WG_THREADS) & ((1 << vshift) - 1)) * 8;
                         if (s_goff[i] >= 0 && coff + part8 < st.cin)
                             v = *(const h8*)(in + s_goff[i] + coff);
                         s_reg[i] = v;
                     }
-                }
-            } else {
-                src = lds + st.in_off + chunk * st.kc;
-            }
-            if (active) {
-                for (int kh = 0; kh < st.kh; ++kh) {
-                    for (int kw = 0; kw < st.kw; ++kw) {
-                        const int tapoff = (kh * st.iw + kw) * cs;
-                        // fetch the next tap's weight fragments while this tap is multiplied
 #pragma unroll
-                        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                            for (int f = 0; f < FC; ++f)
-                                a_nxt[ks][f] = wp[f][(ks < nks ? ks : 0) * 64];
-#pragma unroll
-                        for (int f = 0; f < FC; ++f) wp[f] += nks * 64;
-#pragma unroll
-                        for (int ks = 0; ks < 2; ++ks) {
-                            if (ks < nks) {
-                                h8 b[FP];
-#pragma unroll
-                                for (int p = 0; p < FP; ++p)
-                                    b[p] = *(const h8*)(src + pbase[p] + tapoff + ks * 16);
-#pragma unroll
-                                for (int f = 0; f < FC; ++f)
-#pragma unroll
-                                    for (int p = 0; p < FP; ++p)
-                                        acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                                            a_cur[ks][f], b[p], acc[f][p], 0, 0, 0);
-                            }
-                        }
-#pragma unroll
-                        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                            for (int f = 0; f < FC; ++f) a_cur[ks][f] = a_nxt[ks][f];
+                    for (int i = 0; i < DLF_STAGE_VECS; ++i) {
+                        const int vi = tid + i * DLF_WG_THREADS;
+                        if (vi < s_total)
+                            *(h8*)(dst + (vi >> vshift) * cs + (vi & ((1 << vshift) - 1)) * 8) = s_reg[i];
                     }
-                }
-            }
-            if (STREAM) {
-                if (chunk + 1 < nchunks) {
-                    half_t* dst = lds + st.in_off + ((chunk + 1) & 1) * st.stream_buf;
-#pragma unroll
-                    for (int i = 0; i < DLF_STAGE_VECS; ++i)
-                        if (s_loff[i] >= 0) *(h8*)(dst + s_loff[i]) = s_reg[i];
                 }
                 __syncthreads();
             }
@@ -405,7 +465,7 @@ __device__ __forceinline__ void valu_stage(const DlfGroupArgs& a, const DlfStage
 }
 
 template <int FC, int FP>
-__global__ __launch_bounds__(DLF_WG_THREADS) void k_group(const DlfGroupArgs a)
+__global__ __launch_bounds__(DLF_WG_THREADS, 2) void k_group(const DlfGroupArgs a)
 {
     for (int t = blockIdx.x; t < a.ntiles; t += gridDim.x) {
         int r = t;
@@ -433,10 +493,17 @@ __global__ __launch_bounds__(DLF_WG_THREADS) void k_group(const DlfGroupArgs a)
             const DlfStage& st = a.st[s];
             const bool last = (s == a.nstages - 1);
             if (st.kind == DLF_ST_CONV) {
-                if (s == 0 && a.stream0)
-                    conv_stage<FC, FP, true>(a, st, last, n, ty0, tx0, slice);
-                else
-                    conv_stage<FC, FP, false>(a, st, last, n, ty0, tx0, slice);
+                const int taps = st.kh * st.kw;
+                const int kind = (taps == 9 && st.kw == 3) ? 9 : (taps == 1 ? 1 : 0);
+                if (s == 0 && a.stream0) {
+                    if (kind == 9) conv_stage<FC, FP, true, 9>(a, st, last, n, ty0, tx0, slice);
+                    else if (kind == 1) conv_stage<FC, FP, true, 1>(a, st, last, n, ty0, tx0, slice);
+                    else conv_stage<FC, FP, true, 0>(a, st, last, n, ty0, tx0, slice);
+                } else {
+                    if (kind == 9) conv_stage<FC, FP, false, 9>(a, st, last, n, ty0, tx0, slice);
+                    else if (kind == 1) conv_stage<FC, FP, false, 1>(a, st, last, n, ty0, tx0, slice);
+                    else conv_stage<FC, FP, false, 0>(a, st, last, n, ty0, tx0, slice);
+                }
             } else {
                 valu_stage(a, st, last, n, ty0, tx0, slice);
             }
