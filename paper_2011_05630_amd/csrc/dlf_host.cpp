@@ -309,7 +309,7 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
             st.cin_pad = L.cin_pad; st.ncb = L.ncb; st.nsteps = L.nsteps;
             if (st.kc != 32 && st.kc != 64 && st.kc != 128) return b;
             if (L.cin_pad % st.kc != 0) return b;
-            if (st.kc != 32 && (L.d.kh * L.d.kw != 1 || (L.d.cin & 7) != 0)) return b;
+            if (st.kc != 32 && (L.d.cin & 7) != 0) return b;
         } else {
             st.kc = 8; st.kc_shift = 0; st.cin_pad = round_up(L.d.cin, 8); st.ncb = 0; st.nsteps = 0;
         }
@@ -347,10 +347,18 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
         if (s == 0 && tc.stream0) {
             st.stream_buf = (int)sz;
             sz *= 2;
-            if ((int64_t)st.ih * st.iw * (st.kc / 8) > (int64_t)DLF_STAGE_VECS * DLF_WG_THREADS) return b;
+            if ((int64_t)st.ih * st.iw * (st.kc / 8) > (int64_t)DLF_STAGE_VECS * DLF_LOAD_THREADS) return b;
         }
         bufsz[s] = sz;
         area[s & 1] = std::max(area[s & 1], sz);
+    }
+    // the last CONV stage leaves its tile in LDS (buffer ns); store_tile copies it to HBM
+    if (ga.st[ns - 1].kind == DLF_ST_CONV) {
+        DlfStage& st = ga.st[ns - 1];
+        const int c = chan_local ? chan_local : st.cout;
+        st.out_cs = round_up(c, 8) + DLF_CPAD;
+        const int ph = st.pool2 ? st.rh / 2 : st.rh, pw = st.pool2 ? st.rw / 2 : st.rw;
+        area[ns & 1] = std::max(area[ns & 1], (int64_t)ph * pw * st.out_cs);
     }
     // consistency: what stage s writes must be what stage s+1 reads
     for (int s = 0; s + 1 < ns; ++s) {
@@ -380,9 +388,10 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
             if (tc.nslices > 1) cbs = std::min(st.ncb, tc.slice_c / 32);
             const int n_cg = ceil_div(cbs, FCv);
             const int nitems = n_pg * n_cg;
-            if (s == 0 && tc.stream0 && nitems > DLF_WAVES) return b;
+            const int mma_waves = (s == 0 && tc.stream0) ? DLF_MMA_WAVES : DLF_WAVES;
+            if (s == 0 && tc.stream0 && nitems > mma_waves) return b;
             const int64_t steps = st.nsteps;
-            mfma += (int64_t)ceil_div(nitems, DLF_WAVES) * steps * FCv * FPv * MFMA_CYCLES;
+            mfma += (int64_t)ceil_div(nitems, mma_waves) * steps * FCv * FPv * MFMA_CYCLES;
             l2 += (int64_t)nitems * FCv * steps * 1024;
         } else {
             const int c = chan_local ? chan_local : st.cout;
@@ -451,7 +460,7 @@ bool choose_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
                 if (conv0) {
                     // slicing over output channels: only if no later CONV stage
                     const int ncb = L0.ncb, FCv = VAR_FC[variant];
-                    const bool pointwise = L0.d.kh * L0.d.kw == 1 && (L0.d.cin & 7) == 0;
+                    const bool pointwise = (L0.d.cin & 7) == 0;   // any filter may stream 32..128 channels per round
                     for (int stream0 = 1; stream0 >= 0; --stream0) {
                         for (int kc = 32; kc <= (stream0 && pointwise ? 128 : 32); kc *= 2) {
                             if (L0.cin_pad % kc != 0) continue;

@@ -7,11 +7,13 @@
 #include <stdint.h>
 
 #define DLF_MAX_STAGES 8
-#define DLF_WG_THREADS 256
-#define DLF_WAVES 4
+#define DLF_WG_THREADS 512
+#define DLF_WAVES 8          // waves per workgroup
+#define DLF_MMA_WAVES 4      // streaming CONV stage: waves 0..3 multiply, the others move data
+#define DLF_LOAD_THREADS ((DLF_WAVES - DLF_MMA_WAVES) * 64)
 #define DLF_CPAD 8          // halfs of padding per LDS pixel row: makes the row stride an odd
                             // multiple of 16 bytes, so 16-byte LDS accesses spread over all banks
-#define DLF_STAGE_VECS 8    // 16-byte vectors each thread can hold while prefetching a streamed chunk
+#define DLF_STAGE_VECS 8    // 16-byte vectors a data-movement thread holds per streaming round
 
 enum { DLF_ST_CONV = 0, DLF_ST_MAXPOOL = 1, DLF_ST_DW = 2 };
 

@@ -172,11 +172,18 @@ __device__ __forceinline__ void mma_chunk(const half_t* src, const int (&pbase)[
     }
 }
 
-// A convolution stage.  STREAM: the input is not resident; it is brought from HBM in rounds of
-// st.kc channels (a multiple of 32) into two alternating LDS buffers.
+// A convolution stage.
+//
+// STREAM: the input is not resident; it is brought from HBM in rounds of st.kc channels (a
+// multiple of 32) into two alternating LDS buffers.  The workgroup is split by role: waves
+// 0..3 multiply (one work item each), waves 4..7 only move data (HBM -> registers -> LDS for the
+// next round).  The roles must be different waves because the hardware's load counter retires in
+// order: a wave that had both the long-latency activation loads and the just-in-time weight
+// fragment loads in flight would stall its MFMAs on the activation loads.
+// Resident (not STREAM): the input region is already in LDS and all 8 waves multiply.
 template <int FC, int FP, bool STREAM, int TAPS>
-__device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage& st, bool last,
-                                           int n, int ty0, int tx0, int slice)
+__device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage& st, int n,
+                                           int ty0, int tx0, int slice)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lhi = lane >> 5;
@@ -197,45 +204,67 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
     const int cs = st.in_cs;
     const int ntaps = st.kh * st.kw;
     const half_t* in = (const half_t*)a.in;
+    constexpr int MMA_WAVES = STREAM ? DLF_MMA_WAVES : DLF_WAVES;
 
-    // ---- stream mode: per-thread addresses of the vectors this thread stages per round ----
-    int s_goff[DLF_STAGE_VECS];   // element offset into `in` for round 0, or -1 (zero fill)
-    const int vshift = st.kc_shift;              // log2(16-byte vectors per pixel per round)
-    const int s_total = (st.ih * st.iw) << vshift;
-    if (STREAM) {
+    if (STREAM && wave >= DLF_MMA_WAVES) {
+        // ---------------- data-movement waves ----------------
+        const int lt = tid - DLF_MMA_WAVES * 64;                 // 0 .. DLF_LOAD_THREADS-1
+        const int vshift = st.kc_shift;              // log2(16-byte vectors per pixel per round)
+        const int vmask = (1 << vshift) - 1;
+        const int s_total = (st.ih * st.iw) << vshift;
         const int iy0 = ty0 * a.iy_mul + a.iy_off, ix0 = tx0 * a.ix_mul + a.ix_off;
+        int s_goff[DLF_STAGE_VECS];   // element offset into `in` for round 0, or -1 (zero fill)
         if ((st.cin & 7) != 0) {
             // narrow inputs (e.g. 3 channels): one round, element-wise copy
-            stage_region(in, n, a.in_h, a.in_w, a.in_c, iy0, ix0, st.ih, st.iw, 0, kc, st.cin,
-                         cs, lds + st.in_off);
-#pragma unroll
-            for (int i = 0; i < DLF_STAGE_VECS; ++i) s_goff[i] = -1;
-        } else {
-#pragma unroll
-            for (int i = 0; i < DLF_STAGE_VECS; ++i) {
-                const int v = tid + i * DLF_WG_THREADS;
-                s_goff[i] = -1;
-                if (v < s_total) {
-                    const int pix = v >> vshift, part = v & ((1 << vshift) - 1);
-                    const int ry = pix / st.iw, rx = pix - ry * st.iw;
-                    const int gy = iy0 + ry, gx = ix0 + rx;
-                    if (gy >= 0 && gy < a.in_h && gx >= 0 && gx < a.in_w)
-                        s_goff[i] = ((n * a.in_h + gy) * a.in_w + gx) * a.in_c + part * 8;
-                }
+            for (int v = lt; v < s_total; v += DLF_LOAD_THREADS) {
+                const int pix = v >> vshift, part = v & vmask;
+                const int ry = pix / st.iw, rx = pix - ry * st.iw;
+                *(h8*)(lds + st.in_off + pix * cs + part * 8) =
+                    load_px8(in, n, iy0 + ry, ix0 + rx, a.in_h, a.in_w, a.in_c, part * 8, st.cin);
             }
+            __syncthreads();
+            for (int round = 0; round < nrounds; ++round) __syncthreads();
+            return;
+        }
 #pragma unroll
-            for (int i = 0; i < DLF_STAGE_VECS; ++i) {
-                const int vi = tid + i * DLF_WG_THREADS;
-                const int part8 = (vi & ((1 << vshift) - 1)) * 8;
-                h8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-                if (s_goff[i] >= 0 && part8 < st.cin) v = *(const h8*)(in + s_goff[i]);
-                if (vi < s_total) *(h8*)(lds + st.in_off + (vi >> vshift) * cs + part8) = v;
+        for (int i = 0; i < DLF_STAGE_VECS; ++i) {
+            const int v = lt + i * DLF_LOAD_THREADS;
+            s_goff[i] = -1;
+            if (v < s_total) {
+                const int pix = v >> vshift, part = v & vmask;
+                const int ry = pix / st.iw, rx = pix - ry * st.iw;
+                const int gy = iy0 + ry, gx = ix0 + rx;
+                if (gy >= 0 && gy < a.in_h && gx >= 0 && gx < a.in_w)
+                    s_goff[i] = ((n * a.in_h + gy) * a.in_w + gx) * a.in_c + part * 8;
             }
         }
-        __syncthreads();
+        for (int round = 0; round <= nrounds; ++round) {
+            // round r of this loop fills the buffer that the multiplying waves read in round r
+            if (round < nrounds) {
+                const int coff = round * kc;
+                half_t* dst = lds + st.in_off + (round & 1) * st.stream_buf;
+                h8 s_reg[DLF_STAGE_VECS];
+#pragma unroll
+                for (int i = 0; i < DLF_STAGE_VECS; ++i) {
+                    h8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+                    const int part8 = ((lt + i * DLF_LOAD_THREADS) & vmask) * 8;
+                    if (s_goff[i] >= 0 && coff + part8 < st.cin)
+                        v = *(const h8*)(in + s_goff[i] + coff);
+                    s_reg[i] = v;
+                }
+#pragma unroll
+                for (int i = 0; i < DLF_STAGE_VECS; ++i) {
+                    const int vi = lt + i * DLF_LOAD_THREADS;
+                    if (vi < s_total) *(h8*)(dst + (vi >> vshift) * cs + (vi & vmask) * 8) = s_reg[i];
+                }
+            }
+            __syncthreads();
+        }
+        return;
     }
 
-    for (int item0 = 0; item0 < nitems; item0 += DLF_WAVES) {
+    bool first_pass = true;
+    for (int item0 = 0; item0 < nitems; item0 += MMA_WAVES) {
         const int item = item0 + wave;
         const bool active = item < nitems;
         if (!STREAM && !active) continue;
@@ -268,6 +297,10 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
 #pragma unroll
         for (int f = 0; f < FC; ++f) { a0[f] = wp[f][0]; a1[f] = wp[f][64]; wp[f] += 128; }
 
+        if (STREAM && first_pass) {
+            __syncthreads();          // round 0 is in LDS
+            first_pass = false;
+        }
         for (int round = 0; round < nrounds; ++round) {
             const half_t* src = STREAM ? lds + st.in_off + (round & 1) * st.stream_buf
                                        : lds + st.in_off + round * 32;
@@ -286,36 +319,12 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
                                                 ntaps);
                 }
             }
-            if (STREAM) {
-                // next round: HBM -> registers -> the other LDS buffer.  The loads are issued after
-                // this round's MFMAs so that no staging register is live across them; the second
-                // workgroup resident on the CU computes meanwhile.
-                if (round + 1 < nrounds) {
-                    const int coff = (round + 1) * kc;
-                    half_t* dst = lds + st.in_off + ((round + 1) & 1) * st.stream_buf;
-                    h8 s_reg[DLF_STAGE_VECS];
-#pragma unroll
-                    for (int i = 0; i < DLF_STAGE_VECS; ++i) {
-                        h8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-                        const int part8 = ((tid + i * DLF_WG_THREADS) & ((1 << vshift) - 1)) * 8;
-                        if (s_goff[i] >= 0 && coff + part8 < st.cin)
-                            v = *(const h8*)(in + s_goff[i] + coff);
-                        s_reg[i] = v;
-                    }
-#pragma unroll
-                    for (int i = 0; i < DLF_STAGE_VECS; ++i) {
-                        const int vi = tid + i * DLF_WG_THREADS;
-                        if (vi < s_total)
-                            *(h8*)(dst + (vi >> vshift) * cs + (vi & ((1 << vshift) - 1)) * 8) = s_reg[i];
-                    }
-                }
-                __syncthreads();
-            }
+            if (STREAM) __syncthreads();
         }
 
-        // ---- epilogue: bias, residual, activation, (pool), fp16, store ----
+        // ---- epilogue: bias, residual, activation, (pool), fp16 -> LDS tile [pixel][channel] ----
+        // (the last stage's tile is then written to HBM by store_tile with full-line stores)
         if (!active) continue;
-        half_t* outp = (half_t*)a.out;
         const half_t* resp = (const half_t*)st.res;
 #pragma unroll
         for (int f = 0; f < FC; ++f) {
@@ -351,21 +360,7 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
                     h4 hv;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) hv[r] = (half_t)v[r];
-                    if (last) {
-                        if (co < st.cout) {
-                            if (!st.pool2) {
-                                if (inimg)
-                                    *(h4*)(outp + (((size_t)n * a.out_h + gy) * a.out_w + gx)
-                                                      * a.out_c + co) = hv;
-                            } else {
-                                const int py = gy >> 1, px = gx >> 1;
-                                if (valid && (l32 & 3) == 0 && gy >= 0 && gx >= 0 && py < a.out_h
-                                    && px < a.out_w)
-                                    *(h4*)(outp + (((size_t)n * a.out_h + py) * a.out_w + px)
-                                                      * a.out_c + co) = hv;
-                            }
-                        }
-                    } else {
+                    {
                         const int lc = co - cb_begin * 32;
                         if (lc < st.out_cs - DLF_CPAD) {
                             const h4 z = {0, 0, 0, 0};
@@ -384,6 +379,44 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
                     }
                 }
             }
+        }
+    }
+}
+
+// Writes the finished output tile of a CONV stage from LDS to HBM: consecutive threads write
+// consecutive 16-byte pieces of a pixel's channels, so every store instruction covers whole
+// cache lines (the MFMA result layout itself would give 8-byte pieces 2*Cout bytes apart).
+__device__ __forceinline__ void store_tile(const DlfGroupArgs& a, const DlfStage& st, int n, int ty0,
+                                           int tx0, int slice)
+{
+    const int ph = st.pool2 ? st.rh >> 1 : st.rh, pw = st.pool2 ? st.rw >> 1 : st.rw;
+    int oy = ty0 * st.oy_mul + st.oy_off, ox = tx0 * st.ox_mul + st.ox_off;
+    if (st.pool2) { oy >>= 1; ox >>= 1; }
+    int c0 = 0, ccnt = st.cout;
+    if (a.nslices > 1) {
+        c0 = slice * a.slice_c;
+        ccnt = min(a.slice_c, st.cout - c0);
+    }
+    half_t* outp = (half_t*)a.out;
+    if ((st.cout & 7) == 0) {
+        const int nvec = ccnt >> 3;
+        for (int v = threadIdx.x; v < ph * pw * nvec; v += DLF_WG_THREADS) {
+            const int pix = v / nvec, part = v - pix * nvec;
+            const int y = pix / pw, x = pix - y * pw;
+            const int gy = oy + y, gx = ox + x;
+            if (gy < a.out_h && gx < a.out_w)
+                *(h8*)(outp + (((size_t)n * a.out_h + gy) * a.out_w + gx) * a.out_c + c0 + part * 8) =
+                    *(const h8*)(lds + st.out_off + pix * st.out_cs + part * 8);
+        }
+    } else {
+        const int nvec = ccnt >> 2;
+        for (int v = threadIdx.x; v < ph * pw * nvec; v += DLF_WG_THREADS) {
+            const int pix = v / nvec, part = v - pix * nvec;
+            const int y = pix / pw, x = pix - y * pw;
+            const int gy = oy + y, gx = ox + x;
+            if (gy < a.out_h && gx < a.out_w)
+                *(h4*)(outp + (((size_t)n * a.out_h + gy) * a.out_w + gx) * a.out_c + c0 + part * 4) =
+                    *(const h4*)(lds + st.out_off + pix * st.out_cs + part * 4);
         }
     }
 }
@@ -465,7 +498,7 @@ __device__ __forceinline__ void valu_stage(const DlfGroupArgs& a, const DlfStage
 }
 
 template <int FC, int FP>
-__global__ __launch_bounds__(DLF_WG_THREADS, 2) void k_group(const DlfGroupArgs a)
+__global__ __launch_bounds__(DLF_WG_THREADS) void k_group(const DlfGroupArgs a)
 {
     for (int t = blockIdx.x; t < a.ntiles; t += gridDim.x) {
         int r = t;
@@ -496,13 +529,17 @@ __global__ __launch_bounds__(DLF_WG_THREADS, 2) void k_group(const DlfGroupArgs 
                 const int taps = st.kh * st.kw;
                 const int kind = (taps == 9 && st.kw == 3) ? 9 : (taps == 1 ? 1 : 0);
                 if (s == 0 && a.stream0) {
-                    if (kind == 9) conv_stage<FC, FP, true, 9>(a, st, last, n, ty0, tx0, slice);
-                    else if (kind == 1) conv_stage<FC, FP, true, 1>(a, st, last, n, ty0, tx0, slice);
-                    else conv_stage<FC, FP, true, 0>(a, st, last, n, ty0, tx0, slice);
+                    if (kind == 9) conv_stage<FC, FP, true, 9>(a, st, n, ty0, tx0, slice);
+                    else if (kind == 1) conv_stage<FC, FP, true, 1>(a, st, n, ty0, tx0, slice);
+                    else conv_stage<FC, FP, true, 0>(a, st, n, ty0, tx0, slice);
                 } else {
-                    if (kind == 9) conv_stage<FC, FP, false, 9>(a, st, last, n, ty0, tx0, slice);
-                    else if (kind == 1) conv_stage<FC, FP, false, 1>(a, st, last, n, ty0, tx0, slice);
-                    else conv_stage<FC, FP, false, 0>(a, st, last, n, ty0, tx0, slice);
+                    if (kind == 9) conv_stage<FC, FP, false, 9>(a, st, n, ty0, tx0, slice);
+                    else if (kind == 1) conv_stage<FC, FP, false, 1>(a, st, n, ty0, tx0, slice);
+                    else conv_stage<FC, FP, false, 0>(a, st, n, ty0, tx0, slice);
+                }
+                if (last) {
+                    __syncthreads();
+                    store_tile(a, st, n, ty0, tx0, slice);
                 }
             } else {
                 valu_stage(a, st, last, n, ty0, tx0, slice);
@@ -564,6 +601,7 @@ __global__ __launch_bounds__(256) void k_gap(const DlfGapArgs a)
     const int n = idx / a.c, c = idx - n * a.c;
     const half_t* p = (const half_t*)a.x + (size_t)n * a.hw * a.c + c;
     float s = 0.0f;
+#pragma unroll 7
     for (int i = 0; i < a.hw; ++i) s += (float)p[(size_t)i * a.c];
     ((half_t*)a.y)[idx] = (half_t)(s / (float)a.hw);
 }
