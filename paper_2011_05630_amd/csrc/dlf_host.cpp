@@ -68,7 +68,7 @@ void pack_conv_weights(const uint16_t* w, int cout, int taps, int cin, int kc, i
 {
     const int ncb = ceil_div(cout, 32), nchunks = cin_pad / kc, nks = kc / 16;
     const size_t nsteps = (size_t)nchunks * taps * nks;
-    out.assign((ncb * nsteps + 2) * 512, 0);
+    out.assign((ncb * nsteps + 8) * 512, 0);   // 8 steps of zeros: the kernels prefetch ahead
     for (int cb = 0; cb < ncb; ++cb)
         for (int chunk = 0; chunk < nchunks; ++chunk)
             for (int tap = 0; tap < taps; ++tap)
@@ -153,8 +153,8 @@ struct GroupPlan {
     DlfGapArgs pa;
 };
 
-const int VAR_FC[5] = {2, 2, 1, 1, 4};
-const int VAR_FP[5] = {4, 2, 4, 2, 2};
+const int VAR_FC[DLF_NUM_VARIANTS] = {2, 1, 1};
+const int VAR_FP[DLF_NUM_VARIANTS] = {2, 4, 2};
 
 // Hardware constants of the cost model (MI355X: 256 CUs, 2.4 GHz, HBM 8 TB/s).
 const int64_t PS_PER_CYCLE = 417;
@@ -454,7 +454,7 @@ bool choose_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
         for (int tw : TILE_W) {
             if (tw > Llast.out_w && tw != TILE_W[0] && (tw - Llast.out_w) >= 4) continue;
             if (th * tw > 512) continue;
-            for (int variant = 0; variant < 5; ++variant) {
+            for (int variant = 0; variant < DLF_NUM_VARIANTS; ++variant) {
                 if (!any_conv && variant != 0) continue;
                 std::vector<TileCfg> cands;
                 if (conv0) {

@@ -78,7 +78,8 @@ struct DlfGapArgs {
 extern "C" {
 #endif
 // Launchers (defined with the kernels).  `variant` selects the per-wave register tile of CONV
-// stages: 0 = 64 channels x 128 pixels, 1 = 64 x 64, 2 = 32 x 128, 3 = 32 x 64.
+// stages: 0 = 64 channels x 64 pixels, 1 = 32 x 128, 2 = 32 x 64.
+#define DLF_NUM_VARIANTS 3
 int dlf_launch_group(const DlfGroupArgs* a, int variant, int grid, int lds_bytes, void* stream);
 int dlf_launch_fc(const DlfFcArgs* a, void* stream);
 int dlf_launch_gap(const DlfGapArgs* a, void* stream);

@@ -91,18 +91,27 @@ __device__ __forceinline__ void stage_region(const half_t* in, int n, int H, int
 }
 
 // One 32-channel K chunk of a convolution stage: every filter tap, two 16-channel MFMA steps per
-// tap.  TAPS = 9 (3x3) and TAPS = 1 (1x1) are fully unrolled so that the compiler can place the
-// waits of the interleaved LDS / global loads exactly; TAPS = 0 is the loop for any other filter.
-//   b0/b1: activation fragments of the two K steps of a tap; each is loaded from LDS while the
-//          other is being multiplied.
-//   a0/a1: weight fragments of the two K steps; each is re-fetched (for the next tap, which is
-//          simply the next 2 KiB of the packed stream) right after its MFMAs were issued.
+// tap.  A "step" is one K step of 16 channels; the packed weight stream holds one 1 KiB fragment
+// per output-channel block per step, in exactly the order the steps run.
+//
+// Weights: ring `ar` of RA steps.  Right after the MFMAs of step s were issued, ar[s % RA] is
+// re-fetched with step s + RA, so every weight fragment is requested RA steps (several hundred
+// cycles, an L2 round trip) before it is used, and one wave alone keeps the MFMA pipe busy.
+// Activations (3x3 path): both K steps of the next tap are read from LDS while the current tap
+// is multiplied.
+// TAPS = 9 (3x3, RA = 6) is fully unrolled so that every ring index is static and the compiler
+// places each wait exactly; TAPS = 1 (1x1) and TAPS = 0 (any other filter, a loop) use RA = 2.
+// (register tiles with 128 accumulator registers have no room for the deep ring)
+template <int TAPS, int FC, int FP> struct RingSize {
+    static constexpr int value = (TAPS == 9 && FC * FP < 8) ? 6 : 2;
+};
+
 template <int FC, int FP, int TAPS>
 __device__ __forceinline__ void mma_chunk(const half_t* src, const int (&pbase)[FP],
-                                          const h8* (&wp)[FC], h8 (&a0)[FC], h8 (&a1)[FC],
+                                          const h8* (&wp)[FC], h8 (&ar)[RingSize<TAPS, FC, FP>::value][FC],
                                           f16v (&acc)[FC][FP], int cs, int iw, int kw, int ntaps)
 {
-    h8 b0[FP], b1[FP];
+    constexpr int RA = RingSize<TAPS, FC, FP>::value;
     // Per-tap LDS addresses are formed right before each load; the empty asm keeps the compiler
     // from precomputing all of them outside the chunk loop, which would cost TAPS x FP registers.
     int pb[FP];
@@ -111,53 +120,63 @@ __device__ __forceinline__ void mma_chunk(const half_t* src, const int (&pbase)[
         pb[p] = pbase[p];
         asm volatile("" : "+v"(pb[p]));
     }
+    if constexpr (RA == 6) {
+        h8 b[2][2][FP];
 #pragma unroll
-    for (int p = 0; p < FP; ++p) b0[p] = *(const h8*)(src + pb[p]);
-    if (TAPS > 0) {
-        constexpr int KW = (TAPS == 9) ? 3 : 1;
-#pragma unroll
-        for (int t = 0; t < TAPS; ++t) {
-            const int tapoff = ((t / KW) * iw + (t % KW)) * cs;
-#pragma unroll
-            for (int p = 0; p < FP; ++p) b1[p] = *(const h8*)(src + pb[p] + tapoff + 16);
-#pragma unroll
-            for (int f = 0; f < FC; ++f)
-#pragma unroll
-                for (int p = 0; p < FP; ++p)
-                    acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0[f], b0[p], acc[f][p], 0, 0, 0);
-#pragma unroll
-            for (int f = 0; f < FC; ++f) a0[f] = wp[f][0];
-            __builtin_amdgcn_sched_barrier(0);
-            if (t + 1 < TAPS) {
-                const int nextoff = (((t + 1) / KW) * iw + ((t + 1) % KW)) * cs;
-#pragma unroll
-                for (int p = 0; p < FP; ++p) b0[p] = *(const h8*)(src + pb[p] + nextoff);
-            }
-#pragma unroll
-            for (int f = 0; f < FC; ++f)
-#pragma unroll
-                for (int p = 0; p < FP; ++p)
-                    acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1[f], b1[p], acc[f][p], 0, 0, 0);
-#pragma unroll
-            for (int f = 0; f < FC; ++f) { a1[f] = wp[f][64]; wp[f] += 128; }
-            __builtin_amdgcn_sched_barrier(0);
+        for (int p = 0; p < FP; ++p) {
+            b[0][0][p] = *(const h8*)(src + pb[p]);
+            b[0][1][p] = *(const h8*)(src + pb[p] + 16);
         }
+        // A wave issues in order, so a load placed between two MFMAs is issued while the first
+        // one still occupies the matrix pipe: one LDS read (and, at the end of a step, the weight
+        // refills) follows each MFMA, and scheduling barriers keep exactly this order.
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const int nextoff = (((t + 1) / 3) * iw + ((t + 1) % 3)) * cs;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const int sidx = (2 * t + ks) % RA;
+#pragma unroll
+                for (int f = 0; f < FC; ++f)
+#pragma unroll
+                    for (int p = 0; p < FP; ++p) {
+                        acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[sidx][f], b[t & 1][ks][p],
+                                                                           acc[f][p], 0, 0, 0);
+                        const int li = (ks * FC + f) * FP + p;     // loads so far in this tap
+                        if (t + 1 < 9 && li < 2 * FP)
+                            b[(t + 1) & 1][li / FP][li % FP] =
+                                *(const h8*)(src + pb[li % FP] + nextoff + (li / FP) * 16);
+                        if (f == FC - 1 && p == FP - 1) {
+#pragma unroll
+                            for (int f2 = 0; f2 < FC; ++f2)
+                                ar[sidx][f2] = wp[f2][(2 * t + ks + RA) * 64];
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+            }
+        }
+#pragma unroll
+        for (int f = 0; f < FC; ++f) wp[f] += 18 * 64;
     } else {
+        h8 b0[FP], b1[FP];
+#pragma unroll
+        for (int p = 0; p < FP; ++p) b0[p] = *(const h8*)(src + pb[p]);
+        const int nt = (TAPS == 1) ? 1 : ntaps;
         const int rowskip = (iw - kw) * cs;
         int tapoff = 0, kwc = 0;
-        for (int t = 0; t < ntaps; ++t) {
+        for (int t = 0; t < nt; ++t) {
 #pragma unroll
             for (int p = 0; p < FP; ++p) b1[p] = *(const h8*)(src + pb[p] + tapoff + 16);
 #pragma unroll
             for (int f = 0; f < FC; ++f)
 #pragma unroll
                 for (int p = 0; p < FP; ++p)
-                    acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0[f], b0[p], acc[f][p], 0, 0, 0);
+                    acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[0][f], b0[p], acc[f][p], 0, 0, 0);
 #pragma unroll
-            for (int f = 0; f < FC; ++f) a0[f] = wp[f][0];
+            for (int f = 0; f < FC; ++f) ar[0][f] = wp[f][128];
             tapoff += cs;
             if (++kwc == kw) { kwc = 0; tapoff += rowskip; }
-            if (t + 1 < ntaps) {
+            if (t + 1 < nt) {
 #pragma unroll
                 for (int p = 0; p < FP; ++p) b0[p] = *(const h8*)(src + pb[p] + tapoff);
             }
@@ -165,9 +184,9 @@ __device__ __forceinline__ void mma_chunk(const half_t* src, const int (&pbase)[
             for (int f = 0; f < FC; ++f)
 #pragma unroll
                 for (int p = 0; p < FP; ++p)
-                    acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1[f], b1[p], acc[f][p], 0, 0, 0);
+                    acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[1][f], b1[p], acc[f][p], 0, 0, 0);
 #pragma unroll
-            for (int f = 0; f < FC; ++f) { a1[f] = wp[f][64]; wp[f] += 128; }
+            for (int f = 0; f < FC; ++f) { ar[1][f] = wp[f][192]; wp[f] += 128; }
         }
     }
 }
@@ -183,7 +202,7 @@ __device__ __forceinline__ void mma_chunk(const half_t* src, const int (&pbase)[
 // Resident (not STREAM): the input region is already in LDS and all 8 waves multiply.
 template <int FC, int FP, bool STREAM, int TAPS>
 __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage& st, int n,
-                                           int ty0, int tx0, int slice)
+                                           int ty0, int tx0, int slice, bool defer_res)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lhi = lane >> 5;
@@ -285,17 +304,27 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
             const int cb = min(cb_begin + cg * FC + f, cb_end - 1);
             wp[f] = (const h8*)st.w + (size_t)cb * st.nsteps * 64 + lane;
         }
+        // accumulators start at the bias of their output channel
         f16v acc[FC][FP];
 #pragma unroll
-        for (int f = 0; f < FC; ++f)
+        for (int f = 0; f < FC; ++f) {
+            const int cb = min(cb_begin + cg * FC + f, cb_end - 1);
 #pragma unroll
-            for (int p = 0; p < FP; ++p)
+            for (int q = 0; q < 4; ++q) {
+                const f4v bv = *(const f4v*)(st.bias + cb * 32 + q * 8 + lhi * 4);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[f][p][i] = 0.0f;
+                for (int p = 0; p < FP; ++p)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[f][p][q * 4 + r] = bv[r];
+            }
+        }
 
-        h8 a0[FC], a1[FC];
+        constexpr int RA = RingSize<TAPS, FC, FP>::value;
+        h8 ar[RA][FC];
 #pragma unroll
-        for (int f = 0; f < FC; ++f) { a0[f] = wp[f][0]; a1[f] = wp[f][64]; wp[f] += 128; }
+        for (int i = 0; i < RA; ++i)
+#pragma unroll
+            for (int f = 0; f < FC; ++f) ar[i][f] = wp[f][i * 64];
 
         if (STREAM && first_pass) {
             __syncthreads();          // round 0 is in LDS
@@ -305,17 +334,17 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
             const half_t* src = STREAM ? lds + st.in_off + (round & 1) * st.stream_buf
                                        : lds + st.in_off + round * 32;
             if (active) {
-                if (TAPS == 1) {
+                if constexpr (TAPS == 1) {
                     int j = 0;
                     for (; j + 1 < cpr; j += 2) {
-                        mma_chunk<FC, FP, 1>(src + j * 32, pbase, wp, a0, a1, acc, cs, st.iw, 1, 1);
-                        mma_chunk<FC, FP, 1>(src + j * 32 + 32, pbase, wp, a0, a1, acc, cs, st.iw, 1, 1);
+                        mma_chunk<FC, FP, 1>(src + j * 32, pbase, wp, ar, acc, cs, st.iw, 1, 1);
+                        mma_chunk<FC, FP, 1>(src + j * 32 + 32, pbase, wp, ar, acc, cs, st.iw, 1, 1);
                     }
                     if (j < cpr)
-                        mma_chunk<FC, FP, 1>(src + j * 32, pbase, wp, a0, a1, acc, cs, st.iw, 1, 1);
+                        mma_chunk<FC, FP, 1>(src + j * 32, pbase, wp, ar, acc, cs, st.iw, 1, 1);
                 } else {
                     for (int j = 0; j < cpr; ++j)
-                        mma_chunk<FC, FP, TAPS>(src + j * 32, pbase, wp, a0, a1, acc, cs, st.iw, st.kw,
+                        mma_chunk<FC, FP, TAPS>(src + j * 32, pbase, wp, ar, acc, cs, st.iw, st.kw,
                                                 ntaps);
                 }
             }
@@ -325,7 +354,9 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
         // ---- epilogue: bias, residual, activation, (pool), fp16 -> LDS tile [pixel][channel] ----
         // (the last stage's tile is then written to HBM by store_tile with full-line stores)
         if (!active) continue;
-        const half_t* resp = (const half_t*)st.res;
+        // a residual operand of the group's last stage is added by store_tile instead
+        const half_t* resp = defer_res ? nullptr : (const half_t*)st.res;
+        const int act = (defer_res && st.res != nullptr) ? 0 : st.act;
 #pragma unroll
         for (int f = 0; f < FC; ++f) {
             const int cb = cb_begin + cg * FC + f;
@@ -341,10 +372,9 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int co = cb * 32 + q * 8 + lhi * 4;
-                    const f4v bv = *(const f4v*)(st.bias + co);
                     float v[4];
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) v[r] = acc[f][p][q * 4 + r] + bv[r];
+                    for (int r = 0; r < 4; ++r) v[r] = acc[f][p][q * 4 + r];
                     if (resp != nullptr && inimg && co < st.cout) {
                         const h4 rv = *(const h4*)(resp + (((size_t)n * st.out_h + gy) * st.out_w
                                                            + gx) * st.cout + co);
@@ -352,7 +382,7 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
                         for (int r = 0; r < 4; ++r) v[r] += (float)rv[r];
                     }
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) v[r] = apply_act(v[r], st.act);
+                    for (int r = 0; r < 4; ++r) v[r] = apply_act(v[r], act);
                     if (st.pool2) {
 #pragma unroll
                         for (int r = 0; r < 4; ++r) v[r] = quad_max(v[r]);
@@ -398,15 +428,24 @@ __device__ __forceinline__ void store_tile(const DlfGroupArgs& a, const DlfStage
         ccnt = min(a.slice_c, st.cout - c0);
     }
     half_t* outp = (half_t*)a.out;
+    const half_t* resp = (const half_t*)st.res;   // same shape as the output; added, then activation
     if ((st.cout & 7) == 0) {
         const int nvec = ccnt >> 3;
         for (int v = threadIdx.x; v < ph * pw * nvec; v += DLF_WG_THREADS) {
             const int pix = v / nvec, part = v - pix * nvec;
             const int y = pix / pw, x = pix - y * pw;
             const int gy = oy + y, gx = ox + x;
-            if (gy < a.out_h && gx < a.out_w)
-                *(h8*)(outp + (((size_t)n * a.out_h + gy) * a.out_w + gx) * a.out_c + c0 + part * 8) =
-                    *(const h8*)(lds + st.out_off + pix * st.out_cs + part * 8);
+            if (gy < a.out_h && gx < a.out_w) {
+                const size_t go = (((size_t)n * a.out_h + gy) * a.out_w + gx) * a.out_c + c0 + part * 8;
+                h8 val = *(const h8*)(lds + st.out_off + pix * st.out_cs + part * 8);
+                if (resp != nullptr) {
+                    const h8 rv = *(const h8*)(resp + go);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        val[j] = (half_t)apply_act((float)val[j] + (float)rv[j], st.act);
+                }
+                *(h8*)(outp + go) = val;
+            }
         }
     } else {
         const int nvec = ccnt >> 2;
@@ -414,9 +453,17 @@ __device__ __forceinline__ void store_tile(const DlfGroupArgs& a, const DlfStage
             const int pix = v / nvec, part = v - pix * nvec;
             const int y = pix / pw, x = pix - y * pw;
             const int gy = oy + y, gx = ox + x;
-            if (gy < a.out_h && gx < a.out_w)
-                *(h4*)(outp + (((size_t)n * a.out_h + gy) * a.out_w + gx) * a.out_c + c0 + part * 4) =
-                    *(const h4*)(lds + st.out_off + pix * st.out_cs + part * 4);
+            if (gy < a.out_h && gx < a.out_w) {
+                const size_t go = (((size_t)n * a.out_h + gy) * a.out_w + gx) * a.out_c + c0 + part * 4;
+                h4 val = *(const h4*)(lds + st.out_off + pix * st.out_cs + part * 4);
+                if (resp != nullptr) {
+                    const h4 rv = *(const h4*)(resp + go);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        val[j] = (half_t)apply_act((float)val[j] + (float)rv[j], st.act);
+                }
+                *(h4*)(outp + go) = val;
+            }
         }
     }
 }
@@ -529,13 +576,13 @@ __global__ __launch_bounds__(DLF_WG_THREADS) void k_group(const DlfGroupArgs a)
                 const int taps = st.kh * st.kw;
                 const int kind = (taps == 9 && st.kw == 3) ? 9 : (taps == 1 ? 1 : 0);
                 if (s == 0 && a.stream0) {
-                    if (kind == 9) conv_stage<FC, FP, true, 9>(a, st, n, ty0, tx0, slice);
-                    else if (kind == 1) conv_stage<FC, FP, true, 1>(a, st, n, ty0, tx0, slice);
-                    else conv_stage<FC, FP, true, 0>(a, st, n, ty0, tx0, slice);
+                    if (kind == 9) conv_stage<FC, FP, true, 9>(a, st, n, ty0, tx0, slice, last);
+                    else if (kind == 1) conv_stage<FC, FP, true, 1>(a, st, n, ty0, tx0, slice, last);
+                    else conv_stage<FC, FP, true, 0>(a, st, n, ty0, tx0, slice, last);
                 } else {
-                    if (kind == 9) conv_stage<FC, FP, false, 9>(a, st, n, ty0, tx0, slice);
-                    else if (kind == 1) conv_stage<FC, FP, false, 1>(a, st, n, ty0, tx0, slice);
-                    else conv_stage<FC, FP, false, 0>(a, st, n, ty0, tx0, slice);
+                    if (kind == 9) conv_stage<FC, FP, false, 9>(a, st, n, ty0, tx0, slice, last);
+                    else if (kind == 1) conv_stage<FC, FP, false, 1>(a, st, n, ty0, tx0, slice, last);
+                    else conv_stage<FC, FP, false, 0>(a, st, n, ty0, tx0, slice, last);
                 }
                 if (last) {
                     __syncthreads();
@@ -610,18 +657,16 @@ typedef void (*group_kernel_t)(const DlfGroupArgs);
 static group_kernel_t group_kernel(int variant)
 {
     switch (variant) {
-    case 0: return k_group<2, 4>;
-    case 1: return k_group<2, 2>;
-    case 2: return k_group<1, 4>;
-    case 3: return k_group<1, 2>;
-    case 4: return k_group<4, 2>;
+    case 0: return k_group<2, 2>;
+    case 1: return k_group<1, 4>;
+    case 2: return k_group<1, 2>;
     default: return nullptr;
     }
 }
 
 extern "C" int dlf_kernels_init(void)
 {
-    for (int v = 0; v < 5; ++v) {
+    for (int v = 0; v < DLF_NUM_VARIANTS; ++v) {
         hipError_t e = hipFuncSetAttribute((const void*)group_kernel(v),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return (int)e;

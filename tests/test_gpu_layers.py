@@ -41,8 +41,8 @@ def _manual(n_layers, lasts, budget=64):
 
 # (th, tw, variant, nslices, slice_c, stream0)
 FORCED = [
-    (8, 8, 3, 1, 0, 1), (8, 8, 3, 1, 0, 0), (8, 16, 1, 1, 0, 1), (16, 16, 0, 1, 0, 1),
-    (16, 16, 2, 1, 0, 0), (7, 14, 4, 1, 0, 1), (4, 28, 2, 1, 0, 1), (2, 4, 3, 1, 0, 1),
+    (8, 8, 2, 1, 0, 1), (8, 8, 2, 1, 0, 0), (8, 16, 0, 1, 0, 1), (16, 16, 1, 1, 0, 1),
+    (16, 16, 1, 1, 0, 0), (7, 14, 0, 1, 0, 1), (4, 28, 1, 1, 0, 1), (2, 4, 2, 1, 0, 1),
 ]
 
 
@@ -52,6 +52,15 @@ def test_conv3x3_single_layer_forced_configs(force):
     net = _mk([nets.conv(32, 64, 3, 1, 1, "relu")], 37, 29, 32)
     got, ref, _ = _run(net, 2, force=force, **_manual(1, [0]))
     compare(got, ref, "conv3x3 force=%s" % (force,))
+
+
+@pytest.mark.parametrize("k", [1, 3])
+@pytest.mark.parametrize("kc", [32, 64, 128])
+def test_conv_streaming_round_sizes(k, kc):
+    announce("conv stream round", k, kc)
+    net = _mk([nets.conv(128, 96, k, 1, k // 2, "relu")], 21, 18, 128, dist="normal")
+    got, ref, _ = _run(net, 2, force=(4, 8, 1, 1, 0, 1, kc), **_manual(1, [0]))
+    compare(got, ref, "conv k%d stream kc=%d" % (k, kc))
 
 
 @pytest.mark.parametrize("cin,cout", [(16, 16), (8, 24), (3, 32), (64, 128), (96, 40), (256, 64)])
@@ -72,8 +81,8 @@ def test_conv_kernel_stride_pad(k, stride, pad, cin, cout, hw):
     compare(got, ref, "conv k%d s%d p%d" % (k, stride, pad))
 
 
-@pytest.mark.parametrize("slices", [(8, 8, 1, 4, 64, 1), (8, 8, 0, 4, 64, 1), (7, 7, 4, 2, 128, 1),
-                                    (8, 8, 3, 8, 32, 1)])
+@pytest.mark.parametrize("slices", [(8, 8, 0, 4, 64, 1), (8, 8, 1, 2, 128, 1), (7, 7, 0, 2, 128, 1),
+                                    (8, 8, 2, 8, 32, 1), (8, 8, 1, 4, 64, 1, 64)])
 def test_conv_output_channel_slices(slices):
     announce("conv slices", slices)
     net = _mk([nets.conv(64, 256, 3, 1, 1, "relu")], 14, 14, 64)
@@ -132,7 +141,7 @@ def test_conv_with_fused_pool2():
     # sliced over output channels
     layers = [nets.conv(32, 128, 3, 1, 1, "relu"), nets.maxpool(128, 2, 2, 0)]
     net = _mk(layers, 16, 16, 32)
-    got, ref, g = _run(net, 1, force=(4, 4, 1, 2, 64, 1), **_manual(2, [1]))
+    got, ref, g = _run(net, 1, force=(4, 4, 0, 2, 64, 1), **_manual(2, [1]))
     compare(got, ref, "conv+pool fused, 2 slices")
 
 
@@ -181,7 +190,7 @@ def test_fused_chain_equals_oracle(depth, c, hw, tile):
     announce("fused chain", depth, c, hw, tile)
     net = nets.identical_chain(c, hw, depth)
     for stream0 in (1, 0):
-        for variant in (3, 1):
+        for variant in (2, 0, 1):
             try:
                 got, ref, g = _run(net, 2, force=(tile[0], tile[1], variant, 1, 0, stream0),
                                    **_manual(depth, [depth - 1]))
