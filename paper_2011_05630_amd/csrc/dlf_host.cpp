@@ -198,6 +198,7 @@ bool group_stages(const dlf_net_s& net, int first, int last, std::vector<StageSp
         if (i > first && L.src != i - 1) { why = "layer input is not the previous layer of the group"; return false; }
         if (d.residual_from >= first && d.residual_from <= last) { why = "residual operand produced inside the group"; return false; }
         if (d.residual_from >= 0 && d.op != DLF_CONV) { why = "residual add on a non-convolution layer"; return false; }
+        if (d.residual_from >= 0 && i != last) { why = "a residual add must be the last layer of its group"; return false; }
         // a tensor produced inside the group (except the last) must not be used outside it
         if (i < last) {
             for (size_t j = 0; j < net.L.size(); ++j) {

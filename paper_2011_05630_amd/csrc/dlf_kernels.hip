@@ -191,6 +191,66 @@ __device__ __forceinline__ void mma_chunk(const half_t* src, const int (&pbase)[
     }
 }
 
+// Keeps a wave-uniform value in a scalar register: without this the compiler prefers to re-load
+// kernel-argument fields from memory wherever they are used, and every such load is a stall.
+__device__ __forceinline__ int pin_s(int x)
+{
+    x = __builtin_amdgcn_readfirstlane(x);
+    asm volatile("" : "+s"(x));
+    return x;
+}
+
+// Epilogue of a convolution work item: activation, optional 2x2 max pooling across the 4 lanes
+// of a quad, fp16 rounding, store of 4 consecutive channels per lane into the LDS tile
+// [pixel][out_cs].  Pixels outside the true feature map are stored as zero (the padding value the
+// next convolution of the group must see).
+template <int FC, int FP, bool POOL>
+__device__ __forceinline__ void conv_epilogue(f16v (&acc)[FC][FP], int cbl, int ncbv, int pg,
+                                              int npix, int rw, int ry0, int rx0, int out_h,
+                                              int out_w, int act, int out_off, int out_cs)
+{
+    const int lane = threadIdx.x & 63, l32 = lane & 31, lhi = lane >> 5;
+    const int cmax = out_cs - DLF_CPAD;
+#pragma unroll
+    for (int p = 0; p < FP; ++p) {
+        const int pix = (pg * FP + p) * 32 + l32;
+        const bool valid = pix < npix;
+        int ry, rx;
+        pix_to_rc(valid ? pix : 0, rw, POOL ? 1 : 0, ry, rx);
+        const int gy = ry0 + ry, gx = rx0 + rx;
+        bool keep, store;
+        int row;
+        if (POOL) {
+            const int py = gy >> 1, px = gx >> 1;
+            keep = gy >= 0 && gx >= 0 && py < (out_h >> 1) && px < (out_w >> 1);
+            store = valid && (l32 & 3) == 0;
+            row = pix >> 2;
+        } else {
+            keep = gy >= 0 && gy < out_h && gx >= 0 && gx < out_w;
+            store = valid;
+            row = pix;
+        }
+        half_t* dst = lds + out_off + row * out_cs + lhi * 4;
+#pragma unroll
+        for (int f = 0; f < FC; ++f) {
+            if (f < ncbv) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int lc = (cbl + f) * 32 + q * 8;
+                    h4 hv;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float v = apply_act(acc[f][p][q * 4 + r], act);
+                        if (POOL) v = quad_max(v);
+                        hv[r] = keep ? (half_t)v : (half_t)0;
+                    }
+                    if (store && lc + lhi * 4 < cmax) *(h4*)(dst + lc) = hv;
+                }
+            }
+        }
+    }
+}
+
 // A convolution stage.
 //
 // STREAM: the input is not resident; it is brought from HBM in rounds of st.kc channels (a
@@ -202,7 +262,7 @@ __device__ __forceinline__ void mma_chunk(const half_t* src, const int (&pbase)[
 // Resident (not STREAM): the input region is already in LDS and all 8 waves multiply.
 template <int FC, int FP, bool STREAM, int TAPS>
 __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage& st, int n,
-                                           int ty0, int tx0, int slice, bool defer_res)
+                                           int ty0, int tx0, int slice, bool defer_act)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lhi = lane >> 5;
@@ -351,65 +411,21 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
             if (STREAM) __syncthreads();
         }
 
-        // ---- epilogue: bias, residual, activation, (pool), fp16 -> LDS tile [pixel][channel] ----
-        // (the last stage's tile is then written to HBM by store_tile with full-line stores)
+        // ---- epilogue: activation, (pool), fp16 -> LDS tile [pixel][channel] ----
+        // (the last stage's tile is then written to HBM by store_tile with full-line stores,
+        //  which also adds the residual operand and applies the activation after it)
         if (!active) continue;
-        // a residual operand of the group's last stage is added by store_tile instead
-        const half_t* resp = defer_res ? nullptr : (const half_t*)st.res;
-        const int act = (defer_res && st.res != nullptr) ? 0 : st.act;
-#pragma unroll
-        for (int f = 0; f < FC; ++f) {
-            const int cb = cb_begin + cg * FC + f;
-            if (cb >= cb_end) continue;
-#pragma unroll
-            for (int p = 0; p < FP; ++p) {
-                const int pix = (pg * FP + p) * 32 + l32;
-                const bool valid = pix < npix;
-                int ry, rx;
-                pix_to_rc(valid ? pix : 0, st.rw, st.pool2, ry, rx);
-                const int gy = ry0 + ry, gx = rx0 + rx;
-                const bool inimg = valid && gy >= 0 && gy < st.out_h && gx >= 0 && gx < st.out_w;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int co = cb * 32 + q * 8 + lhi * 4;
-                    float v[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) v[r] = acc[f][p][q * 4 + r];
-                    if (resp != nullptr && inimg && co < st.cout) {
-                        const h4 rv = *(const h4*)(resp + (((size_t)n * st.out_h + gy) * st.out_w
-                                                           + gx) * st.cout + co);
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) v[r] += (float)rv[r];
-                    }
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) v[r] = apply_act(v[r], act);
-                    if (st.pool2) {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) v[r] = quad_max(v[r]);
-                    }
-                    h4 hv;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) hv[r] = (half_t)v[r];
-                    {
-                        const int lc = co - cb_begin * 32;
-                        if (lc < st.out_cs - DLF_CPAD) {
-                            const h4 z = {0, 0, 0, 0};
-                            if (!st.pool2) {
-                                if (valid)
-                                    *(h4*)(lds + st.out_off + pix * st.out_cs + lc) = inimg ? hv : z;
-                            } else {
-                                const int py = gy >> 1, px = gx >> 1;
-                                const bool pin = gy >= 0 && gx >= 0 && py < (st.out_h >> 1)
-                                                 && px < (st.out_w >> 1);
-                                if (valid && (l32 & 3) == 0)
-                                    *(h4*)(lds + st.out_off + (pix >> 2) * st.out_cs + lc)
-                                        = pin ? hv : z;
-                            }
-                        }
-                    }
-                }
-            }
-        }
+        const int act = (defer_act && st.res != nullptr) ? 0 : st.act;
+        const int cbl = cg * FC;                       // first local channel block of the item
+        const int ncbv = min(FC, cb_end - cb_begin - cbl);
+        if (st.pool2)
+            conv_epilogue<FC, FP, true>(acc, cbl, ncbv, pg, npix, pin_s(st.rw), ry0, rx0,
+                                        pin_s(st.out_h), pin_s(st.out_w), act, pin_s(st.out_off),
+                                        pin_s(st.out_cs));
+        else
+            conv_epilogue<FC, FP, false>(acc, cbl, ncbv, pg, npix, pin_s(st.rw), ry0, rx0,
+                                         pin_s(st.out_h), pin_s(st.out_w), act, pin_s(st.out_off),
+                                         pin_s(st.out_cs));
     }
 }
 
@@ -533,6 +549,7 @@ __device__ __forceinline__ void valu_stage(const DlfGroupArgs& a, const DlfStage
                 if (lc + 8 <= ccnt) {
                     *(h8*)o = hv;
                 } else {
+#pragma unroll
                     for (int j = 0; j < 8; ++j)
                         if (lc + j < ccnt) o[j] = hv[j];
                 }
