@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA
 RIDGE = MFMA_FP16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # FLOP per byte
 
-VARIANT_NAME = {0: "k_group<2,2>", 1: "k_group<1,4>", 2: "k_group<1,2>"}
+VARIANT_NAME = {0: "k_group<2,2,2>", 1: "k_group<1,4,2>", 2: "k_group<1,2,2>", 3: "k_group<1,2,4>"}
 
 
 def workloads():

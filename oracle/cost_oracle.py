@@ -1,0 +1,387 @@
+"""Independent implementation of the published cost function of the fusion-group tuner (TEST
+INFRASTRUCTURE ONLY; shares no code with the GPU library).
+
+The cost function is ours, not the paper's: the paper times every candidate on the hardware
+(Sec. V "Oracle Case": reduced brute force) and its greedy pass only uses operation count and
+channel size (Sec. IV).  Here a group's cost is an integer number of picoseconds computed from
+the tiling the library would use; it is defined in DESIGN.md ("Cost model, version 2") and
+implemented twice: in the library (C++) and here (Python), so that the library's exact tuner can
+be checked bit for bit against exhaustive enumeration (plan_oracle.best_plan_exhaustive).
+
+cost(first, last, budget) = min over the candidate tilings of the group of
+    (C_LAUNCH + max(compute, memory)) * PS_PER_CYCLE
+or None if the layers cannot run as one group / no candidate fits on-chip memory.
+"""
+
+# ---- constants ("Cost model, version 2") ----
+PS_PER_CYCLE = 465
+HBM_BYTES_PER_CYCLE = 3300
+CU_BYTES_PER_CYCLE = 12
+L2_BYTES_PER_CYCLE = 48
+C_LAUNCH = 9000
+C_TILE = 6000
+C_LAT = 5000
+C_STAGE_VEC = 120
+C_IM2COL = 150
+C_ROUND = 3800
+C_BARRIER = 500
+C_EPI = 900
+C_VALU = 100
+C_STAGE = 1200
+C_STORE_VEC = 80
+C_STORE = 1600
+MFMA_CYCLES = 32
+FC_BYTES_PER_CYCLE = 900
+GAP_BYTES_PER_CYCLE = 1000
+
+WG_THREADS = 512
+WAVES = 8
+MMA_WAVES = 4
+LOAD_THREADS = 256
+STAGE_VECS = 8
+CPAD = 8
+MAX_STAGES = 8
+LDS_PER_CU = 160 * 1024
+
+VAR_FC = (2, 1, 1, 1)
+VAR_FP = (2, 4, 2, 2)
+VAR_OCC = (1, 1, 1, 2)
+TILE_H = (2, 4, 7, 8, 14, 16)
+TILE_W = (4, 7, 8, 14, 16, 28, 32)
+
+CONV, POOL, DW = 0, 1, 2
+
+
+def cdiv(a, b):
+    return -(-a // b)
+
+
+def rup(a, b):
+    return cdiv(a, b) * b
+
+
+class NetInfo:
+    """Shapes and packing parameters of every layer (plain shape inference)."""
+
+    def __init__(self, net):
+        self.layers = net["layers"]
+        self.cache = {}
+        n = len(self.layers)
+        self.src, self.ish, self.osh = [0] * n, [None] * n, [None] * n
+        self.cin_pad, self.ncb, self.nsteps, self.im2col = [0] * n, [0] * n, [0] * n, [False] * n
+        for i, L in enumerate(self.layers):
+            s = L["input_from"] if L["input_from"] >= 0 else i - 1
+            self.src[i] = s
+            h, w, c = (net["in_h"], net["in_w"], net["in_c"]) if s < 0 else self.osh[s]
+            self.ish[i] = (h, w, c)
+            op = L["op"]
+            if op in ("conv", "dwconv", "maxpool"):
+                ho = (h + 2 * L["pad"] - L["kh"]) // L["stride"] + 1
+                wo = (w + 2 * L["pad"] - L["kw"]) // L["stride"] + 1
+                self.osh[i] = (ho, wo, L["cout"])
+            else:
+                self.osh[i] = (1, 1, L["cout"])
+            if op in ("conv", "fc"):
+                self.im2col[i] = op == "conv" and L["cin"] % 8 != 0
+                k = L["kh"] * L["kw"] * L["cin"] if self.im2col[i] else L["cin"]
+                self.cin_pad[i] = rup(k, 32)
+                self.ncb[i] = cdiv(L["cout"], 32)
+                if self.im2col[i]:
+                    self.nsteps[i] = self.cin_pad[i] // 16
+                else:
+                    self.nsteps[i] = (self.cin_pad[i] // 32) * L["kh"] * L["kw"] * 2
+            elif op == "dwconv":
+                self.cin_pad[i] = rup(L["cin"], 8)
+
+    def escapes(self, j):
+        """Is tensor j read by a layer other than j+1, or added as a residual by any layer?"""
+        for k, L in enumerate(self.layers):
+            if L["residual_from"] == j:
+                return True
+            if k != j + 1 and self.src[k] == j:
+                return True
+        return False
+
+
+def group_stages(ni, first, last):
+    """Stage list [(layer, kind, pool2, pool_layer)] of a legal group, 'fc' / 'gap' for the
+    single-layer special kernels, or None if layers [first, last] cannot form a group."""
+    Ls = ni.layers
+    if Ls[first]["op"] in ("fc", "gavgpool"):
+        if first != last:
+            return None
+        return "fc" if Ls[first]["op"] == "fc" else "gap"
+    st = []
+    i = first
+    while i <= last:
+        L = Ls[i]
+        op = L["op"]
+        if op in ("fc", "gavgpool"):
+            return None
+        if i > first and ni.src[i] != i - 1:
+            return None
+        rf = L["residual_from"]
+        if first <= rf <= last:
+            return None
+        if rf >= 0 and (op != "conv" or i != last):
+            return None
+        if i < last and ni.escapes(i):
+            return None
+        pool2, pool_layer = 0, -1
+        if op == "conv":
+            kind = CONV
+            if L["cout"] % 4:
+                return None
+            if i + 1 <= last:
+                P = Ls[i + 1]
+                if (P["op"] == "maxpool" and P["kh"] == 2 and P["kw"] == 2 and P["stride"] == 2
+                        and P["pad"] == 0 and ni.src[i + 1] == i and ni.osh[i][0] % 2 == 0
+                        and ni.osh[i][1] % 2 == 0 and rf < 0):
+                    if i + 1 < last and ni.escapes(i + 1):
+                        return None
+                    pool2, pool_layer = 1, i + 1
+        elif op == "dwconv":
+            kind = DW
+            if L["cin"] % 8:
+                return None
+        else:
+            kind = POOL
+            if L["cin"] % 8 or L["pad"] >= L["kh"]:
+                return None
+        st.append((i, kind, pool2, pool_layer))
+        i += 2 if pool2 else 1
+    if len(st) > MAX_STAGES:
+        return None
+    for k in range(1, len(st)):
+        if st[k][1] == CONV and st[k - 1][1] != CONV and Ls[st[k][0]]["cin"] % 32:
+            return None
+    return st
+
+
+def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc, max_lds):
+    """Per-tile quantities of one candidate tiling, or None if it does not fit.
+    Returns (ntiles, lds_bytes, tile_cycles, tile_hbm_bytes, tile_l2_bytes)."""
+    Ls = ni.layers
+    ns = len(specs)
+    FC, FP = VAR_FC[variant], VAR_FP[variant]
+    lfirst = specs[0][0]
+    llast = specs[-1][3] if specs[-1][2] else specs[-1][0]
+    in_h, in_w, in_c = ni.ish[lfirst]
+    out_h, out_w, out_c = ni.osh[llast]
+    ntiles = batch * cdiv(out_h, th) * cdiv(out_w, tw) * nslices
+    S = [dict() for _ in range(ns)]
+    my, oy, mx, ox, h, w = 1, 0, 1, 0, th, tw
+    for s in range(ns - 1, -1, -1):
+        li, kind, pool2, _ = specs[s]
+        L = Ls[li]
+        st = S[s]
+        st["kind"], st["pool2"] = kind, pool2
+        if pool2:
+            my, oy, mx, ox, h, w = my * 2, oy * 2, mx * 2, ox * 2, h * 2, w * 2
+        st["cin"], st["cout"] = L["cin"], L["cout"]
+        kh, kw, stride, pad = L["kh"], L["kw"], L["stride"], L["pad"]
+        st["rh"], st["rw"], st["oy_off"], st["ox_off"] = h, w, oy, ox
+        st["ih"], st["iw"] = (h - 1) * stride + kh, (w - 1) * stride + kw
+        my, oy = my * stride, oy * stride - pad
+        mx, ox = mx * stride, ox * stride - pad
+        h, w = st["ih"], st["iw"]
+        st["im2col"] = 0
+        st["kh"], st["kw"] = kh, kw
+        if kind == CONV and ni.im2col[li]:
+            if s != 0 or stream0:
+                return None
+            st.update(im2col=1, im_kh=kh, im_kw=kw, im_stride=stride, im_cin=L["cin"], kh=1, kw=1,
+                      ih=st["rh"], iw=st["rw"])
+        if kind == CONV:
+            st["kc"] = kc if (s == 0 and stream0) else 32
+            st["cin_pad"], st["ncb"], st["nsteps"] = ni.cin_pad[li], ni.ncb[li], ni.nsteps[li]
+            if st["kc"] not in (32, 64, 128):
+                return None
+            if st["cin_pad"] % st["kc"]:
+                return None
+            if st["kc"] != 32 and L["cin"] % 8:
+                return None
+        else:
+            st["kc"], st["cin_pad"], st["ncb"], st["nsteps"] = 8, rup(L["cin"], 8), 0, 0
+    if nslices > 1:
+        if any(S[s]["kind"] == CONV for s in range(1, ns)):
+            return None
+        if S[0]["kind"] == CONV and slice_c % 32:
+            return None
+        if slice_c % 8:
+            return None
+        cslice = S[0]["cout"] if S[0]["kind"] == CONV else S[0]["cin"]
+        if nslices * slice_c < cslice:
+            return None
+    if batch * in_h * in_w * in_c >= 1 << 31:
+        return None
+    chan_local = slice_c if nslices > 1 else 0
+    area = [0, 0]
+    for s in range(ns):
+        st = S[s]
+        if st["kind"] == CONV:
+            cs = st["kc"] + CPAD if (s == 0 and stream0) else st["cin_pad"] + CPAD
+        else:
+            cs = rup(chan_local if chan_local else st["cin"], 8) + CPAD
+        sz = st["ih"] * st["iw"] * cs
+        if s == 0 and stream0:
+            sz *= 2
+            if st["ih"] * st["iw"] * (st["kc"] // 8) > STAGE_VECS * LOAD_THREADS:
+                return None
+        area[s & 1] = max(area[s & 1], sz)
+    sl = S[ns - 1]
+    if sl["kind"] == CONV:
+        c = chan_local if chan_local else sl["cout"]
+        ph = sl["rh"] // 2 if sl["pool2"] else sl["rh"]
+        pw = sl["rw"] // 2 if sl["pool2"] else sl["rw"]
+        area[ns & 1] = max(area[ns & 1], ph * pw * (rup(c, 8) + CPAD))
+    for s in range(ns - 1):
+        p, c = S[s], S[s + 1]
+        ph = p["rh"] // 2 if p["pool2"] else p["rh"]
+        pw = p["rw"] // 2 if p["pool2"] else p["rw"]
+        if ph != c["ih"] or pw != c["iw"]:
+            return None
+        if p["pool2"] and ((p["oy_off"] & 1) or (p["ox_off"] & 1) or (p["rh"] & 1) or (p["rw"] & 1)):
+            return None
+    if sl["pool2"] and th * 2 != sl["rh"]:
+        return None
+    lds_bytes = (area[0] + area[1]) * 2
+    if lds_bytes > max_lds:
+        return None
+
+    # ---- cycles one workgroup spends on one tile ----
+    cyc, l2 = C_TILE, 0
+    s0 = S[0]
+    cin0 = chan_local if (s0["kind"] != CONV and chan_local) else s0["cin"]
+    if stream0:
+        cyc += C_LAT
+    elif s0["kind"] == CONV and s0["im2col"]:
+        cyc += C_LAT + cdiv(s0["rh"] * s0["rw"] * s0["im_kh"], WG_THREADS) * s0["im_kw"] * s0["im_cin"] * C_IM2COL
+    else:
+        cfill = s0["cin_pad"] if s0["kind"] == CONV else rup(cin0, 8)
+        cyc += C_LAT + cdiv(s0["ih"] * s0["iw"] * (cfill // 8), WG_THREADS) * C_STAGE_VEC
+    for s in range(ns):
+        st = S[s]
+        npix = st["rh"] * st["rw"]
+        if st["kind"] == CONV:
+            n_pg = cdiv(cdiv(npix, 32), FP)
+            cbs = min(st["ncb"], slice_c // 32) if nslices > 1 else st["ncb"]
+            nitems = n_pg * cdiv(cbs, FC)
+            streaming = s == 0 and stream0
+            mma_waves = MMA_WAVES if streaming else WAVES
+            if streaming and nitems > mma_waves:
+                return None
+            mma = cdiv(nitems, 4) * st["nsteps"] * FC * FP * MFMA_CYCLES * 2
+            if streaming:
+                nrounds = st["cin_pad"] // st["kc"]
+                mma = max(mma, nrounds * C_ROUND) + nrounds * C_BARRIER
+            cyc += mma + cdiv(nitems, mma_waves) * FC * FP * C_EPI
+            l2 += nitems * FC * st["nsteps"] * 1024
+        else:
+            c = chan_local if chan_local else st["cout"]
+            items = npix * cdiv(c, 8)
+            cyc += cdiv(items, WG_THREADS) * (st["kh"] * st["kw"]) * C_VALU + C_STAGE
+    cout_l = min(chan_local, out_c) if chan_local else out_c
+    has_res = 1 if Ls[specs[-1][0]]["residual_from"] >= 0 else 0
+    if sl["kind"] == CONV:
+        cyc += cdiv(th * tw * cdiv(cout_l, 8), WG_THREADS) * C_STORE_VEC + C_STORE + has_res * C_LAT
+    hbm = s0["ih"] * s0["iw"] * cin0 * 2 + th * tw * cout_l * 2 * (1 + has_res)
+    if s0["kind"] == CONV and s0["im2col"]:
+        hbm = s0["rh"] * s0["rw"] * s0["im_stride"] * s0["im_stride"] * s0["im_cin"] * 2 + th * tw * cout_l * 2
+    return ntiles, lds_bytes, cyc, hbm, l2
+
+
+def tiling_cost_ps(built, budget, variant):
+    ntiles, lds_bytes, cyc, hbm, l2 = built
+    occ = max(1, min(VAR_OCC[variant], LDS_PER_CU // max(lds_bytes, 1)))
+    cu = min(budget, ntiles)
+    wg = min(ntiles, budget * occ)
+    conc = cdiv(wg, cu)
+    tiles_cu = cdiv(ntiles, cu)
+    compute = tiles_cu * cyc
+    if conc >= 2:
+        compute = compute * 3 // 4
+    bw = min(CU_BYTES_PER_CYCLE, max(1, HBM_BYTES_PER_CYCLE // cu))
+    mem = tiles_cu * (hbm // bw + l2 // L2_BYTES_PER_CYCLE)
+    return (C_LAUNCH + max(compute, mem)) * PS_PER_CYCLE
+
+
+def candidates(ni, specs):
+    """Every tiling the tuner considers for a group: (th, tw, variant, nslices, slice_c,
+    stream0, kc)."""
+    Ls = ni.layers
+    llast = specs[-1][3] if specs[-1][2] else specs[-1][0]
+    out_h, out_w, _ = ni.osh[llast]
+    l0 = specs[0][0]
+    conv0 = specs[0][1] == CONV
+    later_conv = any(sp[1] == CONV for sp in specs[1:])
+    any_conv = conv0 or later_conv
+    for th in TILE_H:
+        if th > out_h and th != TILE_H[0] and th - out_h >= 4:
+            continue
+        for tw in TILE_W:
+            if tw > out_w and tw != TILE_W[0] and tw - out_w >= 4:
+                continue
+            if th * tw > 512:
+                continue
+            for variant in range(4):
+                if not any_conv and variant not in (0, 3):
+                    continue
+                if conv0:
+                    ncb, fc = ni.ncb[l0], VAR_FC[variant]
+                    wide = Ls[l0]["cin"] % 8 == 0
+                    for stream0 in (1, 0):
+                        kc = 32
+                        while kc <= (128 if (stream0 and wide) else 32):
+                            if ni.cin_pad[l0] % kc == 0:
+                                yield th, tw, variant, 1, 0, stream0, kc
+                                if not later_conv and stream0:
+                                    for cg in (1, 2, 4):
+                                        sc = fc * cg * 32
+                                        if sc < ncb * 32:
+                                            yield th, tw, variant, cdiv(ncb * 32, sc), sc, 1, kc
+                            kc *= 2
+                else:
+                    yield th, tw, variant, 1, 0, 0, 32
+                    if not later_conv:
+                        sc = 32
+                        while sc < Ls[l0]["cin"]:
+                            yield th, tw, variant, cdiv(Ls[l0]["cin"], sc), sc, 0, 32
+                            sc *= 2
+
+
+def group_cost(net, batch, first, last, budget, max_lds=LDS_PER_CU, ni=None):
+    """Cost in picoseconds of running layers [first, last] as one group on `budget` CUs, or None."""
+    ni = ni or NetInfo(net)
+    specs = group_stages(ni, first, last)
+    if specs is None:
+        return None
+    if specs == "fc":
+        wbytes = ni.ncb[first] * ni.nsteps[first] * 1024 * cdiv(batch, 32)
+        return (C_LAUNCH + C_LAT + wbytes // FC_BYTES_PER_CYCLE) * PS_PER_CYCLE
+    if specs == "gap":
+        h, w, c = ni.ish[first]
+        return (C_LAUNCH + C_LAT + batch * h * w * c * 2 // GAP_BYTES_PER_CYCLE) * PS_PER_CYCLE
+    key = (first, last, batch, max_lds)
+    built = ni.cache.get(key)
+    if built is None:
+        built = []
+        for cand in candidates(ni, specs):
+            b = build_group(ni, specs, batch, *cand, max_lds)
+            if b is not None:
+                built.append((b, cand[2]))
+        ni.cache[key] = built
+    best = None
+    for b, variant in built:
+        c = tiling_cost_ps(b, budget, variant)
+        if best is None or c < best:
+            best = c
+    return best
+
+
+def cost_table(net, batch, budgets, max_lds=LDS_PER_CU):
+    """cost[(first, last, budget)] for every contiguous range (None = cannot be a group)."""
+    ni = NetInfo(net)
+    n = len(net["layers"])
+    return {(f, l, b): group_cost(net, batch, f, l, b, max_lds, ni)
+            for f in range(n) for l in range(f, n) for b in budgets}

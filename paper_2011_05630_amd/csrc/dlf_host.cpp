@@ -43,6 +43,7 @@ struct Layer {
     void* d_w = nullptr;
     float* d_bias = nullptr;
     int kc = 0, cin_pad = 0, ncb = 0, nsteps = 0;
+    bool im2col = false;     // narrow-input convolution run as a 1x1 over gathered rows
 };
 
 }  // namespace
@@ -103,7 +104,10 @@ dlf_status pack_and_upload(Layer& L)
     if (d.op == DLF_CONV || d.op == DLF_FC) {
         std::vector<uint16_t> packed;
         const int taps = d.kh * d.kw;
-        pack_conv_weights((const uint16_t*)d.weight, d.cout, taps, d.cin, L.kc, L.cin_pad, packed);
+        if (L.im2col)   // [cout][kh][kw][cin] is already the gathered row order: a 1x1 over kh*kw*cin
+            pack_conv_weights((const uint16_t*)d.weight, d.cout, 1, taps * d.cin, L.kc, L.cin_pad, packed);
+        else
+            pack_conv_weights((const uint16_t*)d.weight, d.cout, taps, d.cin, L.kc, L.cin_pad, packed);
         dlf_status s = upload(packed.data(), packed.size() * 2, &L.d_w);
         if (s != DLF_OK) return s;
         std::vector<float> b((size_t)L.ncb * 32, 0.0f);
@@ -142,7 +146,7 @@ struct TileCfg {
 struct GroupPlan {
     int first = 0, last = 0, budget = 0;
     int kind = GK_GROUP;
-    int variant = 0, lds_bytes = 0, grid = 0;
+    int variant = 0, lds_bytes = 0, grid = 0, occ = 1;
     int th = 0, tw = 0;
     uint64_t cost = 0;
     int in_layer = -1;   // producer of the group's input (-1 = net input)
@@ -153,19 +157,32 @@ struct GroupPlan {
     DlfGapArgs pa;
 };
 
-const int VAR_FC[DLF_NUM_VARIANTS] = {2, 1, 1};
-const int VAR_FP[DLF_NUM_VARIANTS] = {2, 4, 2};
+const int VAR_FC[DLF_NUM_VARIANTS] = {2, 1, 1, 1};
+const int VAR_FP[DLF_NUM_VARIANTS] = {2, 4, 2, 2};
+const int VAR_OCC[DLF_NUM_VARIANTS] = {1, 1, 1, 2};   // workgroups per CU the registers allow
 
-// Hardware constants of the cost model (MI355X: 256 CUs, 2.4 GHz, HBM 8 TB/s).
-const int64_t PS_PER_CYCLE = 417;
-const int64_t HBM_BYTES_PER_CYCLE = 3333;   // 8 TB/s at 2.4 GHz, whole chip
-const int64_t WG_BYTES_PER_CYCLE = 48;      // what one workgroup can pull from HBM / L2
-const int64_t L2_BYTES_PER_CYCLE = 8192;    // aggregate L2 -> CU bandwidth
-const int64_t LAUNCH_CYCLES = 9600;         // 4 us per kernel launch
-const int64_t TILE_CYCLES = 1500;           // per-tile fixed overhead (address setup, drain)
-const int64_t STAGE_CYCLES = 600;           // per-stage barrier / pipeline fill
+// Constants of the cost model, in GPU cycles unless noted (MI355X: 256 CUs at about 2.15 GHz
+// under load, HBM about 3300 bytes per cycle for the whole chip).  All arithmetic is integer so
+// that an independent implementation reproduces every cost bit for bit.
+const int64_t PS_PER_CYCLE = 465;
+const int64_t HBM_BYTES_PER_CYCLE = 3300;   // whole chip
+const int64_t CU_BYTES_PER_CYCLE = 12;      // what the workgroups of one CU pull from HBM
+const int64_t L2_BYTES_PER_CYCLE = 48;      // weight fragments, L2 -> one CU
+const int64_t C_LAUNCH = 9000;              // kernel launch + drain
+const int64_t C_TILE = 6000;                // per tile: decode, address setup, barriers
+const int64_t C_LAT = 5000;                 // one exposed HBM/L2 round trip
+const int64_t C_STAGE_VEC = 120;             // per 512 staged 16-byte vectors
+const int64_t C_IM2COL = 150;                // per gathered element per 512 (pixel, row) pairs
+const int64_t C_ROUND = 3800;               // lower bound of a streaming round (loader latency)
+const int64_t C_BARRIER = 500;
+const int64_t C_EPI = 900;                  // epilogue per 32x32 accumulator block
+const int64_t C_VALU = 100;                  // per tap per 512 (pixel, 8 channels) items
+const int64_t C_STAGE = 1200;                // per VALU stage
+const int64_t C_STORE_VEC = 80;             // per 512 stored 16-byte vectors
+const int64_t C_STORE = 1600;
 const int64_t MFMA_CYCLES = 32;             // one 32x32x16 MFMA on one SIMD
-const int64_t VALU_ITEM_CYCLES = 10;        // cycles per (pixel, 8 channels, tap) work item / 64 lanes
+const int64_t FC_BYTES_PER_CYCLE = 900;     // weight streaming rate of the FC kernel
+const int64_t GAP_BYTES_PER_CYCLE = 1000;
 
 struct StageSpec {   // one stage, before tiling
     int layer;
@@ -191,6 +208,14 @@ bool group_stages(const dlf_net_s& net, int first, int last, std::vector<StageSp
         return true;
     }
     kind = GK_GROUP;
+    // does any layer other than j+1 read tensor j, or does j+1 add it as a residual?
+    auto escapes = [&](int j) {
+        for (size_t k = 0; k < net.L.size(); ++k) {
+            if (net.L[k].d.residual_from == j) return true;
+            if ((int)k != j + 1 && net.L[k].src == j) return true;
+        }
+        return false;
+    };
     for (int i = first; i <= last; ++i) {
         const Layer& L = net.L[i];
         const dlf_layer_desc& d = L.d;
@@ -200,15 +225,7 @@ bool group_stages(const dlf_net_s& net, int first, int last, std::vector<StageSp
         if (d.residual_from >= 0 && d.op != DLF_CONV) { why = "residual add on a non-convolution layer"; return false; }
         if (d.residual_from >= 0 && i != last) { why = "a residual add must be the last layer of its group"; return false; }
         // a tensor produced inside the group (except the last) must not be used outside it
-        if (i < last) {
-            for (size_t j = 0; j < net.L.size(); ++j) {
-                if ((int)j == i + 1) {
-                    if (net.L[j].d.residual_from == i) { why = "intermediate used as residual"; return false; }
-                    continue;
-                }
-                if (net.L[j].src == i || net.L[j].d.residual_from == i) { why = "intermediate tensor is used outside the group"; return false; }
-            }
-        }
+        if (i < last && escapes(i)) { why = "intermediate tensor is used outside the group"; return false; }
         StageSpec s;
         s.layer = i;
         s.pool2 = 0;
@@ -216,16 +233,13 @@ bool group_stages(const dlf_net_s& net, int first, int last, std::vector<StageSp
         if (d.op == DLF_CONV) {
             s.kind = DLF_ST_CONV;
             if (d.cout % 4 != 0) { why = "convolution output channels must be a multiple of 4"; return false; }
-            if (i + 1 <= last && is_pool2(net.L[i + 1].d) && (L.out_h % 2 == 0) && (L.out_w % 2 == 0)
-                && d.residual_from < 0) {
-                // the pooled tensor replaces the convolution output: that output must be unused
-                bool used = false;
-                for (size_t j = 0; j < net.L.size(); ++j)
-                    if ((int)j != i + 1 && (net.L[j].src == i || net.L[j].d.residual_from == i)) used = true;
-                if (net.L[i + 1].src == i && !used) {
-                    s.pool2 = 1;
-                    s.pool_layer = i + 1;
-                }
+            if (i + 1 <= last && is_pool2(net.L[i + 1].d) && net.L[i + 1].src == i && (L.out_h % 2 == 0)
+                && (L.out_w % 2 == 0) && d.residual_from < 0) {
+                // the pooled tensor replaces the convolution output (which nothing else reads:
+                // checked above); the pooled tensor in turn must stay inside unless it is last
+                if (i + 1 < last && escapes(i + 1)) { why = "intermediate tensor is used outside the group"; return false; }
+                s.pool2 = 1;
+                s.pool_layer = i + 1;
             }
         } else if (d.op == DLF_DWCONV) {
             s.kind = DLF_ST_DW;
@@ -303,6 +317,15 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
         my *= st.stride; oy = oy * st.stride - st.pad;
         mx *= st.stride; ox = ox * st.stride - st.pad;
         h = st.ih; w = st.iw;
+        st.im2col = 0;
+        if (st.kind == DLF_ST_CONV && L.im2col) {
+            if (s != 0 || tc.stream0) return b;      // gathered staging: resident stage 0 only
+            st.im2col = 1;
+            st.im_kh = st.kh; st.im_kw = st.kw; st.im_stride = st.stride; st.im_pad = st.pad;
+            st.im_cin = L.d.cin;
+            st.kh = st.kw = 1; st.stride = 1; st.pad = 0;   // what the MFMA loop sees
+            st.ih = st.rh; st.iw = st.rw;
+        }
         st.w = L.d_w; st.bias = L.d_bias; st.res = nullptr;
         if (st.kind == DLF_ST_CONV) {
             st.kc = (s == 0 && tc.stream0) ? tc.kc : 32;
@@ -378,8 +401,18 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
     if (lds_halfs * 2 > max_lds) return b;
     b.lds_bytes = (int)(lds_halfs * 2);
 
-    // work per tile
-    int64_t mfma = 0, valu = 0, l2 = 0;
+    // ---- cost model: cycles one workgroup spends on one tile ----
+    int64_t cyc = C_TILE, l2 = 0;
+    const DlfStage& s0 = ga.st[0];
+    const int cin0 = (s0.kind != DLF_ST_CONV && chan_local) ? chan_local : s0.cin;
+    if (tc.stream0) {
+        cyc += C_LAT;
+    } else if (s0.kind == DLF_ST_CONV && s0.im2col) {
+        cyc += C_LAT + (int64_t)ceil_div(s0.rh * s0.rw * s0.im_kh, DLF_WG_THREADS) * s0.im_kw * s0.im_cin * C_IM2COL;
+    } else {
+        const int cfill = s0.kind == DLF_ST_CONV ? s0.cin_pad : round_up(cin0, 8);
+        cyc += C_LAT + (int64_t)ceil_div(s0.ih * s0.iw * (cfill / 8), DLF_WG_THREADS) * C_STAGE_VEC;
+    }
     for (int s = 0; s < ns; ++s) {
         const DlfStage& st = ga.st[s];
         const int npix = st.rh * st.rw;
@@ -389,38 +422,52 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
             if (tc.nslices > 1) cbs = std::min(st.ncb, tc.slice_c / 32);
             const int n_cg = ceil_div(cbs, FCv);
             const int nitems = n_pg * n_cg;
-            const int mma_waves = (s == 0 && tc.stream0) ? DLF_MMA_WAVES : DLF_WAVES;
-            if (s == 0 && tc.stream0 && nitems > mma_waves) return b;
-            const int64_t steps = st.nsteps;
-            mfma += (int64_t)ceil_div(nitems, mma_waves) * steps * FCv * FPv * MFMA_CYCLES;
-            l2 += (int64_t)nitems * FCv * steps * 1024;
+            const bool streaming = (s == 0 && tc.stream0);
+            const int mma_waves = streaming ? DLF_MMA_WAVES : DLF_WAVES;
+            if (streaming && nitems > mma_waves) return b;
+            // items queue up on the 4 SIMDs; measured rounds run at about half the MFMA issue rate
+            int64_t mma = (int64_t)ceil_div(nitems, 4) * st.nsteps * FCv * FPv * MFMA_CYCLES * 2;
+            if (streaming) {
+                const int64_t nrounds = st.cin_pad / st.kc;
+                mma = std::max(mma, nrounds * C_ROUND) + nrounds * C_BARRIER;
+            }
+            cyc += mma + (int64_t)ceil_div(nitems, mma_waves) * FCv * FPv * C_EPI;
+            l2 += (int64_t)nitems * FCv * st.nsteps * 1024;
         } else {
             const int c = chan_local ? chan_local : st.cout;
             const int64_t items = (int64_t)npix * ceil_div(c, 8);
-            valu += ceil_div((int)std::min<int64_t>(items, 1 << 30), 64) * (int64_t)(st.kh * st.kw)
-                    * VALU_ITEM_CYCLES / DLF_WAVES;
+            cyc += (int64_t)ceil_div((int)items, DLF_WG_THREADS) * (st.kh * st.kw) * C_VALU + C_STAGE;
         }
     }
-    const DlfStage& s0 = ga.st[0];
-    const int cin0 = (s0.kind != DLF_ST_CONV && chan_local) ? chan_local : s0.cin;
+    const DlfStage& sl = ga.st[ns - 1];
     const int cout_l = chan_local ? std::min(chan_local, ga.out_c) : ga.out_c;
-    b.tile_hbm_bytes = (int64_t)s0.ih * s0.iw * cin0 * 2 + (int64_t)tc.th * tc.tw * cout_l * 2;
+    const int has_res = net.L[specs[ns - 1].layer].d.residual_from >= 0 ? 1 : 0;
+    if (sl.kind == DLF_ST_CONV)
+        cyc += (int64_t)ceil_div(tc.th * tc.tw * ceil_div(cout_l, 8), DLF_WG_THREADS) * C_STORE_VEC + C_STORE
+               + has_res * C_LAT;
+    b.tile_hbm_bytes = (int64_t)s0.ih * s0.iw * cin0 * 2 + (int64_t)tc.th * tc.tw * cout_l * 2 * (1 + has_res);
+    if (s0.kind == DLF_ST_CONV && s0.im2col)
+        b.tile_hbm_bytes = (int64_t)s0.rh * s0.rw * s0.im_stride * s0.im_stride * s0.im_cin * 2
+                           + (int64_t)tc.th * tc.tw * cout_l * 2;
     b.tile_l2_bytes = l2;
-    b.tile_cycles = mfma + valu + TILE_CYCLES + (int64_t)ns * STAGE_CYCLES;
+    b.tile_cycles = cyc;
     b.ok = true;
     return b;
 }
 
-// Cost-model time of a built group with `budget` workgroups, in picoseconds.
-uint64_t group_cost_ps(const Built& b, int budget)
+// Cost-model time of a built group on `budget` CUs, in picoseconds.
+uint64_t group_cost_ps(const Built& b, int budget, int variant)
 {
-    const int64_t nwg = std::min<int64_t>(budget, b.ntiles);
-    const int64_t rounds = ceil_div(b.ntiles, (int)nwg);
-    const int64_t hbm_bw = std::min<int64_t>(WG_BYTES_PER_CYCLE, std::max<int64_t>(1, HBM_BYTES_PER_CYCLE / nwg));
-    const int64_t l2_bw = std::min<int64_t>(WG_BYTES_PER_CYCLE, std::max<int64_t>(1, L2_BYTES_PER_CYCLE / nwg));
-    const int64_t mem = b.tile_hbm_bytes / hbm_bw + b.tile_l2_bytes / l2_bw;
-    const int64_t tile = std::max(b.tile_cycles, mem + TILE_CYCLES);
-    return (uint64_t)((LAUNCH_CYCLES + rounds * tile) * PS_PER_CYCLE);
+    const int occ = std::max(1, std::min(VAR_OCC[variant], (160 * 1024) / std::max(b.lds_bytes, 1)));
+    const int64_t cu = std::min<int64_t>(budget, b.ntiles);
+    const int64_t wg = std::min<int64_t>(b.ntiles, (int64_t)budget * occ);
+    const int64_t conc = (wg + cu - 1) / cu;              // workgroups sharing a CU
+    const int64_t tiles_cu = (b.ntiles + cu - 1) / cu;    // tiles one CU works through
+    int64_t compute = tiles_cu * b.tile_cycles;
+    if (conc >= 2) compute = compute * 3 / 4;             // phases of two workgroups overlap
+    const int64_t bw = std::min<int64_t>(CU_BYTES_PER_CYCLE, std::max<int64_t>(1, HBM_BYTES_PER_CYCLE / cu));
+    const int64_t mem = tiles_cu * (b.tile_hbm_bytes / bw + b.tile_l2_bytes / L2_BYTES_PER_CYCLE);
+    return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
 }
 
 // Testing hook: when th > 0 every group is built with exactly this configuration.
@@ -441,7 +488,7 @@ bool choose_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
         if (!b.ok) return false;
         best = b;
         best_tc = g_force;
-        best_cost = group_cost_ps(b, budget);
+        best_cost = group_cost_ps(b, budget, g_force.variant);
         return true;
     }
     const Layer& Llast = net.L[specs[ns - 1].pool2 ? specs[ns - 1].pool_layer : specs[ns - 1].layer];
@@ -456,7 +503,7 @@ bool choose_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
             if (tw > Llast.out_w && tw != TILE_W[0] && (tw - Llast.out_w) >= 4) continue;
             if (th * tw > 512) continue;
             for (int variant = 0; variant < DLF_NUM_VARIANTS; ++variant) {
-                if (!any_conv && variant != 0) continue;
+                if (!any_conv && variant != 0 && variant != 3) continue;   // only occupancy differs
                 std::vector<TileCfg> cands;
                 if (conv0) {
                     // slicing over output channels: only if no later CONV stage
@@ -490,7 +537,7 @@ bool choose_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
                 for (const TileCfg& tc : cands) {
                     Built b = build_group(net, specs, batch, tc, max_lds);
                     if (!b.ok) continue;
-                    const uint64_t c = group_cost_ps(b, budget);
+                    const uint64_t c = group_cost_ps(b, budget, tc.variant);
                     if (!found || c < best_cost) {
                         found = true;
                         best = b;
@@ -525,9 +572,7 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
         fa.batch = batch; fa.k = L0.d.cin; fa.cout = L0.d.cout; fa.ncb = L0.ncb;
         fa.nsteps = L0.nsteps; fa.act = L0.d.act;
         const int64_t wbytes = (int64_t)L0.ncb * L0.nsteps * 1024 * ceil_div(batch, 32);
-        const int64_t nwg = std::min<int64_t>(L0.ncb, 256);
-        const int64_t bw = std::min<int64_t>(HBM_BYTES_PER_CYCLE, nwg * WG_BYTES_PER_CYCLE);
-        g.cost = (uint64_t)((LAUNCH_CYCLES + TILE_CYCLES + wbytes / bw) * PS_PER_CYCLE);
+        g.cost = (uint64_t)((C_LAUNCH + C_LAT + wbytes / FC_BYTES_PER_CYCLE) * PS_PER_CYCLE);
         g.grid = L0.ncb;
         g.th = g.tw = 1;
         return DLF_OK;
@@ -537,7 +582,7 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
         memset(&pa, 0, sizeof pa);
         pa.batch = batch; pa.hw = L0.in_h * L0.in_w; pa.c = L0.d.cin;
         const int64_t bytes = (int64_t)batch * pa.hw * pa.c * 2;
-        g.cost = (uint64_t)((LAUNCH_CYCLES + TILE_CYCLES + bytes / 1024) * PS_PER_CYCLE);
+        g.cost = (uint64_t)((C_LAUNCH + C_LAT + bytes / GAP_BYTES_PER_CYCLE) * PS_PER_CYCLE);
         g.grid = ceil_div(batch * pa.c, 256);
         g.th = L0.in_h; g.tw = L0.in_w;
         return DLF_OK;
@@ -550,7 +595,9 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
     g.ga = b.ga;
     g.variant = tc.variant;
     g.lds_bytes = b.lds_bytes;
-    g.grid = std::min(budget, b.ntiles);
+    // the budget counts CUs; a CU holds as many workgroups as registers and LDS allow
+    g.occ = std::max(1, std::min(VAR_OCC[tc.variant], (160 * 1024) / std::max(b.lds_bytes, 1)));
+    g.grid = std::min(budget * g.occ, b.ntiles);
     g.th = tc.th; g.tw = tc.tw;
     g.cost = cost;
     for (size_t s = 0; s < specs.size(); ++s) {
@@ -649,7 +696,7 @@ const char* dlf_status_string(dlf_status s)
 
 const char* dlf_last_error(void) { return g_err.c_str(); }
 
-int32_t dlf_cost_model_version(void) { return 1; }
+int32_t dlf_cost_model_version(void) { return 2; }
 
 dlf_status dlf_net_create(const dlf_layer_desc* layers, int32_t n, int32_t in_h, int32_t in_w,
                           int32_t in_c, dlf_net_t** out)
@@ -707,8 +754,6 @@ dlf_status dlf_net_create(const dlf_layer_desc* layers, int32_t n, int32_t in_h,
             if (R.out_h != L.out_h || R.out_w != L.out_w || R.out_c != L.out_c)
                 return bad(DLF_ERR_SHAPE, "residual operand shape differs from the layer output");
         }
-        if (d.op == DLF_CONV && (d.cin % 8) != 0 && d.cin > 32)
-            return bad(DLF_ERR_UNSUPPORTED, "convolution with more than 32 input channels needs cin % 8 == 0");
         if (d.op == DLF_CONV && (d.cout % 4) != 0)
             return bad(DLF_ERR_UNSUPPORTED, "convolution needs cout % 4 == 0");
         if (d.op == DLF_FC && (d.cin % 8) != 0)
@@ -719,9 +764,14 @@ dlf_status dlf_net_create(const dlf_layer_desc* layers, int32_t n, int32_t in_h,
             return bad(DLF_ERR_UNSUPPORTED, "pooling pad must be smaller than the window");
         if (d.op == DLF_CONV || d.op == DLF_FC) {
             L.kc = 32;
-            L.cin_pad = round_up(d.cin, L.kc);
+            L.im2col = d.op == DLF_CONV && (d.cin % 8) != 0;
+            if (L.im2col && L.src >= 0)
+                return bad(DLF_ERR_UNSUPPORTED, "a convolution with cin % 8 != 0 must read the network input");
+            if (L.im2col && d.kh * d.kw * d.cin > 1024)
+                return bad(DLF_ERR_UNSUPPORTED, "narrow-input convolution too large");
+            L.cin_pad = round_up(L.im2col ? d.kh * d.kw * d.cin : d.cin, L.kc);
             L.ncb = ceil_div(d.cout, 32);
-            L.nsteps = (L.cin_pad / L.kc) * d.kh * d.kw * (L.kc / 16);
+            L.nsteps = L.im2col ? L.cin_pad / 16 : (L.cin_pad / L.kc) * d.kh * d.kw * (L.kc / 16);
         } else if (d.op == DLF_DWCONV) {
             L.kc = 8; L.cin_pad = round_up(d.cin, 8);
         }

@@ -38,6 +38,10 @@ struct DlfStage {
     int32_t out_off;      // LDS offset (halfs) of the output buffer
     int32_t stream_buf;   // stream mode: halfs per chunk buffer
     int32_t nsteps;       // CONV: 16-wide K steps per output-channel block
+    int32_t im2col;       // CONV stage 0 on a narrow input (cin % 8 != 0): the staging gathers each
+                          // output pixel's kh*kw*cin inputs into one LDS row and the stage then
+                          // runs as a 1x1 convolution over cin_pad = roundup(kh*kw*cin, 32) channels
+    int32_t im_kh, im_kw, im_stride, im_pad, im_cin; // the real filter geometry of an im2col stage
     const void* w;        // CONV: packed fragments; DW: [kh][kw][c] fp16
     const float* bias;    // padded with zeros to ncb*32 (CONV) / c rounded up to 8 (DW)
     const void* res;      // residual operand in HBM, NHWC with this stage's output shape, or null
@@ -78,8 +82,9 @@ struct DlfGapArgs {
 extern "C" {
 #endif
 // Launchers (defined with the kernels).  `variant` selects the per-wave register tile of CONV
-// stages: 0 = 64 channels x 64 pixels, 1 = 32 x 128, 2 = 32 x 64.
-#define DLF_NUM_VARIANTS 3
+// stages: 0 = 64 channels x 64 pixels, 1 = 32 x 128, 2 = 32 x 64, 3 = 32 x 64 compiled for 128
+// registers so that two workgroups share a CU.
+#define DLF_NUM_VARIANTS 4
 int dlf_launch_group(const DlfGroupArgs* a, int variant, int grid, int lds_bytes, void* stream);
 int dlf_launch_fc(const DlfFcArgs* a, void* stream);
 int dlf_launch_gap(const DlfGapArgs* a, void* stream);

@@ -82,11 +82,57 @@ __device__ __forceinline__ void stage_region(const half_t* in, int n, int H, int
 {
     const int nvec = cfill >> 3;
     const int total = ih * iw * nvec;
+    // batches of 8 loads per thread are issued before any is stored: the HBM latency is paid
+    // once per batch, not once per 16 bytes
+    constexpr int U = 8;
+    for (int v0 = threadIdx.x; v0 < total; v0 += DLF_WG_THREADS * U) {
+        h8 val[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int v = v0 + u * DLF_WG_THREADS;
+            if (v < total) {
+                const int pix = v / nvec, part = v - pix * nvec;
+                const int ry = pix / iw, rx = pix - ry * iw;
+                val[u] = load_px8(in, n, iy0 + ry, ix0 + rx, H, W, C, c0 + part * 8, c_end);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int v = v0 + u * DLF_WG_THREADS;
+            if (v < total) {
+                const int pix = v / nvec, part = v - pix * nvec;
+                *(h8*)(dst + pix * cs + part * 8) = val[u];
+            }
+        }
+    }
+}
+
+// im2col staging for a convolution on a narrow input (3 channels): LDS row p holds the
+// kh*kw*cin inputs of output pixel p in (kh, kw, ci) order, zero padded to kfill halfs, so that the
+// convolution becomes a 1x1 convolution over kfill channels: K = 27 -> 32 for a 3x3 filter on RGB
+// instead of 9 taps x 32 padded channels.
+__device__ __forceinline__ void stage_im2col(const half_t* in, int n, int H, int W, int C, int oy0,
+                                             int ox0, int rh, int rw, int kh, int kw, int stride,
+                                             int pad, int kfill, int cs, half_t* dst)
+{
+    const int rowlen = kw * C;                     // contiguous in NHWC
+    const int total = rh * rw * kh;
     for (int v = threadIdx.x; v < total; v += DLF_WG_THREADS) {
-        const int pix = v / nvec, part = v - pix * nvec;
-        const int ry = pix / iw, rx = pix - ry * iw;
-        const h8 val = load_px8(in, n, iy0 + ry, ix0 + rx, H, W, C, c0 + part * 8, c_end);
-        *(h8*)(dst + pix * cs + part * 8) = val;
+        const int pix = v / kh, r = v - pix * kh;
+        const int oy = pix / rw, ox = pix - oy * rw;
+        const int iy = (oy0 + oy) * stride - pad + r;
+        const int ix0 = (ox0 + ox) * stride - pad;
+        half_t* d = dst + pix * cs + r * rowlen;
+        const bool rowok = iy >= 0 && iy < H;
+        const half_t* src = in + (((size_t)n * H + (rowok ? iy : 0)) * W) * C;
+        for (int j = 0; j < rowlen; ++j) {
+            const int ix = ix0 + j / C;
+            half_t val = (half_t)0;
+            if (rowok && ix >= 0 && ix < W) val = src[ix0 * C + j];
+            d[j] = val;
+        }
+        if (r == kh - 1)
+            for (int j = kh * rowlen; j < kfill; ++j) dst[pix * cs + j] = (half_t)0;
     }
 }
 
@@ -447,20 +493,34 @@ __device__ __forceinline__ void store_tile(const DlfGroupArgs& a, const DlfStage
     const half_t* resp = (const half_t*)st.res;   // same shape as the output; added, then activation
     if ((st.cout & 7) == 0) {
         const int nvec = ccnt >> 3;
-        for (int v = threadIdx.x; v < ph * pw * nvec; v += DLF_WG_THREADS) {
-            const int pix = v / nvec, part = v - pix * nvec;
-            const int y = pix / pw, x = pix - y * pw;
-            const int gy = oy + y, gx = ox + x;
-            if (gy < a.out_h && gx < a.out_w) {
-                const size_t go = (((size_t)n * a.out_h + gy) * a.out_w + gx) * a.out_c + c0 + part * 8;
-                h8 val = *(const h8*)(lds + st.out_off + pix * st.out_cs + part * 8);
-                if (resp != nullptr) {
-                    const h8 rv = *(const h8*)(resp + go);
+        const int total = ph * pw * nvec;
+        constexpr int U = 4;     // residual loads of a batch are all in flight together
+        for (int v0 = threadIdx.x; v0 < total; v0 += DLF_WG_THREADS * U) {
+            size_t go[U];
+            h8 val[U], rv[U];
+            bool ok[U];
 #pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        val[j] = (half_t)apply_act((float)val[j] + (float)rv[j], st.act);
+            for (int u = 0; u < U; ++u) {
+                const int v = v0 + u * DLF_WG_THREADS;
+                const int vc = v < total ? v : 0;
+                const int pix = vc / nvec, part = vc - pix * nvec;
+                const int y = pix / pw, x = pix - y * pw;
+                const int gy = oy + y, gx = ox + x;
+                ok[u] = v < total && gy < a.out_h && gx < a.out_w;
+                go[u] = (((size_t)n * a.out_h + gy) * a.out_w + gx) * a.out_c + c0 + part * 8;
+                val[u] = *(const h8*)(lds + st.out_off + pix * st.out_cs + part * 8);
+                if (resp != nullptr && ok[u]) rv[u] = *(const h8*)(resp + go[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (ok[u]) {
+                    if (resp != nullptr) {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j)
+                            val[u][j] = (half_t)apply_act((float)val[u][j] + (float)rv[u][j], st.act);
+                    }
+                    *(h8*)(outp + go[u]) = val[u];
                 }
-                *(h8*)(outp + go) = val;
             }
         }
     } else {
@@ -561,8 +621,11 @@ __device__ __forceinline__ void valu_stage(const DlfGroupArgs& a, const DlfStage
     }
 }
 
-template <int FC, int FP>
-__global__ __launch_bounds__(DLF_WG_THREADS) void k_group(const DlfGroupArgs a)
+// MINW = minimum waves per SIMD the register allocation must allow: 2 (up to 256 registers, one
+// workgroup per CU) or 4 (128 registers, two workgroups per CU, for bandwidth-bound groups whose
+// load, multiply and store phases then overlap across workgroups).
+template <int FC, int FP, int MINW>
+__global__ __launch_bounds__(DLF_WG_THREADS, MINW) void k_group(const DlfGroupArgs a)
 {
     for (int t = blockIdx.x; t < a.ntiles; t += gridDim.x) {
         int r = t;
@@ -581,9 +644,15 @@ __global__ __launch_bounds__(DLF_WG_THREADS) void k_group(const DlfGroupArgs a)
                 cend = min(s0.cin, c0 + a.slice_c);
                 cfill = (cend - c0 + 7) & ~7;
             }
-            stage_region((const half_t*)a.in, n, a.in_h, a.in_w, a.in_c,
-                         ty0 * a.iy_mul + a.iy_off, tx0 * a.ix_mul + a.ix_off, s0.ih, s0.iw, c0,
-                         cfill, cend, s0.in_cs, lds + s0.in_off);
+            if (s0.kind == DLF_ST_CONV && s0.im2col)
+                stage_im2col((const half_t*)a.in, n, a.in_h, a.in_w, a.in_c,
+                             ty0 * s0.oy_mul + s0.oy_off, tx0 * s0.ox_mul + s0.ox_off, s0.rh, s0.rw,
+                             s0.im_kh, s0.im_kw, s0.im_stride, s0.im_pad, s0.cin_pad, s0.in_cs,
+                             lds + s0.in_off);
+            else
+                stage_region((const half_t*)a.in, n, a.in_h, a.in_w, a.in_c,
+                             ty0 * a.iy_mul + a.iy_off, tx0 * a.ix_mul + a.ix_off, s0.ih, s0.iw, c0,
+                             cfill, cend, s0.in_cs, lds + s0.in_off);
             __syncthreads();
         }
         for (int s = 0; s < a.nstages; ++s) {
@@ -674,9 +743,10 @@ typedef void (*group_kernel_t)(const DlfGroupArgs);
 static group_kernel_t group_kernel(int variant)
 {
     switch (variant) {
-    case 0: return k_group<2, 2>;
-    case 1: return k_group<1, 4>;
-    case 2: return k_group<1, 2>;
+    case 0: return k_group<2, 2, 2>;
+    case 1: return k_group<1, 4, 2>;
+    case 2: return k_group<1, 2, 2>;
+    case 3: return k_group<1, 2, 4>;
     default: return nullptr;
     }
 }

@@ -1,0 +1,334 @@
+"""Host-side checks that need no GPU: the library loads and exports its whole C ABI, its cost
+function equals the independent Python implementation bit for bit, its exact tuner returns the
+plan brute-force enumeration finds (Sec. V, "Oracle Case", on nets small enough to enumerate),
+its greedy mode follows Algorithm 1, and bad arguments are rejected with an error."""
+import os
+import random
+import re
+
+import pytest
+
+from synth import nets
+from oracle import cost_oracle as C
+from oracle import plan_oracle as P
+from paper_2011_05630_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+BUDGETS = (32, 64, 128, 256)
+
+
+def _net(layers, h, w, c, name="t"):
+    return dict(name=name, layers=layers, in_h=h, in_w=w, in_c=c, input_dist="uniform")
+
+
+def _handle(net):
+    return B.dlf_net_create(net["layers"], net["in_h"], net["in_w"], net["in_c"])
+
+
+def _sub(net, first, last):
+    """Layers [first, last] of a net as a net of their own (chains only)."""
+    ni = C.NetInfo(net)
+    h, w, c = ni.ish[first]
+    layers = []
+    for i in range(first, last + 1):
+        L = dict(net["layers"][i])
+        for key in ("input_from", "residual_from"):
+            if L[key] >= 0:
+                L[key] -= first
+                assert L[key] >= 0 or key == "input_from" and L[key] == -1
+        layers.append(L)
+    return _net(layers, h, w, c, "%s[%d:%d]" % (net["name"], first, last))
+
+
+def _random_net(rng):
+    """A legal random layer list: convolutions, depthwise, pooling, strides, one residual."""
+    c = rng.choice([8, 16, 32, 64])
+    hw = rng.choice([14, 20, 28, 33])
+    layers, shapes = [], []
+    h = w = hw
+    cin = c
+    n = rng.randint(3, 7)
+    for i in range(n):
+        kind = rng.choice(["c3", "c3", "c1", "dw", "pool", "c3s2"])
+        if kind == "pool" and (min(h, w) < 4 or i == 0):
+            kind = "c3"
+        if kind == "c3s2" and min(h, w) < 6:
+            kind = "c3"
+        if kind == "c3":
+            cout = rng.choice([16, 32, 64])
+            layers.append(nets.conv(cin, cout, 3, 1, 1, "relu"))
+        elif kind == "c3s2":
+            cout = rng.choice([32, 64])
+            layers.append(nets.conv(cin, cout, 3, 2, 1, "relu"))
+            h, w = (h - 1) // 2 + 1, (w - 1) // 2 + 1
+        elif kind == "c1":
+            cout = rng.choice([16, 32, 64, 128])
+            layers.append(nets.conv(cin, cout, 1, 1, 0, "relu6"))
+        elif kind == "dw":
+            cout = cin
+            layers.append(nets.dwconv(cin, 3, 1, "relu6"))
+        else:
+            cout = cin
+            k = rng.choice([2, 3])
+            layers.append(nets.maxpool(cin, k, 2, 0 if k == 2 else 1))
+            h, w = ((h - 2) // 2 + 1, (w - 2) // 2 + 1) if k == 2 else ((h - 1) // 2 + 1, (w - 1) // 2 + 1)
+        cin = cout
+        shapes.append((h, w, cout))
+    # a residual add onto the last layer from an earlier tensor of the same shape, if any
+    if layers[-1]["op"] == "conv":
+        same = [j for j in range(n - 1) if shapes[j] == shapes[-1]]
+        if same and rng.random() < 0.6:
+            layers[-1]["residual_from"] = rng.choice(same)
+    return _net(layers, hw, hw, c, "rand")
+
+
+def _small_nets():
+    out = [(nets.two_layer_block(), 1)]
+    for c in (16, 64, 256):
+        out.append((nets.chain4(c), 1))
+        out.append((nets.chain4(c), 8))
+    v = nets.vgg16()
+    out.append((_sub(v, 0, 6), 16))        # conv conv pool conv conv pool conv
+    out.append((_sub(v, 10, 17), 1))       # deep 512-channel stages with pools
+    r = nets.resnet50()
+    out.append((_sub(r, 0, 5), 32))        # stem, pool, first bottleneck with projection
+    out.append((_sub(r, 6, 11), 4))        # two identity bottlenecks
+    m = nets.mobilenet_v1()
+    out.append((_sub(m, 0, 6), 64))        # stem + three dw/pw pairs
+    out.append((_sub(m, len(m["layers"]) - 6, len(m["layers"]) - 1), 64))   # ... gap, fc
+    out.append((nets.alexnet(), 4))
+    rng = random.Random(5630)
+    for _ in range(8):
+        out.append((_random_net(rng), rng.choice([1, 2, 8])))
+    return out
+
+
+SMALL = _small_nets()
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "dlf.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    hdr = re.sub(r"//[^\n]*", "", hdr)
+    names = sorted(set(re.findall(r"\b(dlf_[a-z0-9_]+)\s*\(", hdr)))
+    assert len(names) >= 20, names
+    lib = B.lib()
+    missing = [n for n in names if not hasattr(lib, n)]
+    assert not missing, missing
+    # and the binding offers the same names
+    unbound = [n for n in names if not hasattr(B, n)]
+    assert not unbound, unbound
+    assert B.dlf_cost_model_version() == 2
+
+
+def test_layer_info_matches_eq1_eq2():
+    for net in (nets.vgg16(), nets.resnet50(), nets.mobilenet_v1()):
+        h = _handle(net)
+        ni = C.NetInfo(net)
+        for i, L in enumerate(net["layers"]):
+            oh, ow, oc, ops = B.dlf_net_layer_info(h, i)
+            assert (oh, ow, oc) == ni.osh[i]
+            assert ops == P.op_count(L, oh, ow)
+        B.dlf_net_destroy(h)
+
+
+@pytest.mark.parametrize("idx", range(len(SMALL)))
+def test_group_cost_equals_independent_model(idx):
+    net, batch = SMALL[idx]
+    h = _handle(net)
+    ni = C.NetInfo(net)
+    n = len(net["layers"])
+    feasible = 0
+    for f in range(n):
+        for l in range(f, n):
+            for b in (1, 7) + BUDGETS:
+                got = B.dlf_group_cost(h, batch, f, l, b)
+                want = C.group_cost(net, batch, f, l, b, ni=ni)
+                assert got == want, (net["name"], f, l, b, got, want)
+                feasible += got is not None
+    assert feasible >= n      # every single layer runs at least on its own
+    B.dlf_net_destroy(h)
+
+
+@pytest.mark.parametrize("name,batch,maxlen", [("vgg16", 16, 5), ("resnet50", 32, 5),
+                                               ("mobilenet_v1", 64, 5), ("resnet18", 8, 4),
+                                               ("vgg19", 2, 3)])
+def test_group_cost_on_full_networks(name, batch, maxlen):
+    net = getattr(nets, name)()
+    h = _handle(net)
+    ni = C.NetInfo(net)
+    n = len(net["layers"])
+    for f in range(n):
+        for l in range(f, min(n, f + maxlen)):
+            for b in BUDGETS:
+                assert B.dlf_group_cost(h, batch, f, l, b) == C.group_cost(net, batch, f, l, b, ni=ni), (f, l, b)
+    B.dlf_net_destroy(h)
+
+
+def test_group_cost_respects_lds_limit():
+    net = nets.chain4(64)
+    h = _handle(net)
+    ni = C.NetInfo(net)
+    seen = set()
+    for lds in (16 * 1024, 40 * 1024, 64 * 1024, 160 * 1024):
+        for l in range(4):
+            got = B.dlf_group_cost(h, 1, 0, l, 256, lds)
+            assert got == C.group_cost(net, 1, 0, l, 256, lds, ni=ni)
+            seen.add((lds, l, got is not None))
+    assert (16 * 1024, 3, False) in seen and (160 * 1024, 3, True) in seen
+    B.dlf_net_destroy(h)
+
+
+def _plan_tuple(h, batch, **kw):
+    p = B.dlf_plan(h, batch, **kw)
+    gs = B.dlf_plan_groups(p)
+    B.dlf_plan_destroy(p)
+    return (sum(g["model_cost"] for g in gs), tuple(g["last"] for g in gs),
+            tuple(g["budget"] for g in gs)), gs
+
+
+@pytest.mark.parametrize("idx", range(len(SMALL)))
+def test_dp_plan_equals_exhaustive_search(idx):
+    net, batch = SMALL[idx]
+    n = len(net["layers"])
+    budgets = BUDGETS if n <= 7 else (64, 256)
+    assert P.count_plans(n, len(budgets)) <= 400000
+    h = _handle(net)
+    ni = C.NetInfo(net)
+    cost, lasts, buds, visited = P.best_plan_exhaustive(
+        n, budgets, lambda f, l, b: C.group_cost(net, batch, f, l, b, ni=ni))
+    assert visited == P.count_plans(n, len(budgets))
+    got, gs = _plan_tuple(h, batch, mode=B.TUNER_DP, budgets=list(budgets))
+    assert got == (cost, lasts, buds), (net["name"], got, (cost, lasts, buds))
+    # groups tile the layer list
+    first = 0
+    for g in gs:
+        assert g["first"] == first
+        first = g["last"] + 1
+    assert first == n
+    B.dlf_net_destroy(h)
+
+
+def test_dp_plan_under_a_small_lds_limit():
+    net = nets.chain4(32)
+    h = _handle(net)
+    ni = C.NetInfo(net)
+    for lds in (24 * 1024, 64 * 1024):
+        cost, lasts, buds, _ = P.best_plan_exhaustive(
+            4, BUDGETS, lambda f, l, b: C.group_cost(net, 2, f, l, b, lds, ni=ni))
+        got, _ = _plan_tuple(h, 2, mode=B.TUNER_DP, budgets=list(BUDGETS), max_lds_bytes=lds)
+        assert got == (cost, lasts, buds)
+    B.dlf_net_destroy(h)
+
+
+def test_dp_fuses_where_the_model_says_so():
+    """Sanity of the plan itself: small feature maps fuse, and the fused plan's modelled cost is
+    below the all-separate plan's."""
+    net = nets.two_layer_block()
+    h = _handle(net)
+    (cost, lasts, buds), _ = _plan_tuple(h, 1)
+    sep = sum(B.dlf_group_cost(h, 1, i, i, 256) for i in range(2))
+    assert lasts == (1,) and cost < sep
+    B.dlf_net_destroy(h)
+
+
+def _legalise(net, batch, part, mps):
+    """Blocks of Algorithm 1 -> executable groups: each block is cut left to right into the
+    longest groups the kernels can run, all with the block's MP."""
+    ni = C.NetInfo(net)
+    out = []
+    first = 0
+    for blk_last, mp in zip(part, mps):
+        while first <= blk_last:
+            l = blk_last
+            while C.group_cost(net, batch, first, l, mp, ni=ni) is None:
+                l -= 1
+                assert l >= first
+            out.append((first, l, mp))
+            first = l + 1
+    return out
+
+
+@pytest.mark.parametrize("name,batch", [("two_layer_block", 1), ("vgg16", 1), ("vgg16", 16),
+                                        ("resnet50", 32), ("mobilenet_v1", 64), ("alexnet", 4),
+                                        ("resnet18", 8)])
+@pytest.mark.parametrize("crit,k,b", [(2.0e7, 16.0, -256.0), (5.0e8, 8.0, -100.0), (1.0e6, 1.0, 0.0)])
+def test_greedy_mode_follows_algorithm1(name, batch, crit, k, b):
+    net = getattr(nets, name)()
+    ni = C.NetInfo(net)
+    ops = [P.op_count(L, ni.osh[i][0], ni.osh[i][1], batch) for i, L in enumerate(net["layers"])]
+    part, mps = P.algorithm1(net["layers"], ops, crit, 0.316, 0.659, k, b, BUDGETS)
+    assert part[-1] == len(net["layers"]) - 1 and len(part) == len(mps)
+    want = _legalise(net, batch, part, mps)
+    h = _handle(net)
+    p = B.dlf_plan(h, batch, mode=B.TUNER_GREEDY, budgets=list(BUDGETS), opcount_critical=crit,
+                   alpha=0.316, beta=0.659, mp_scale=k, mp_offset=b)
+    got = [(g["first"], g["last"], g["budget"]) for g in B.dlf_plan_groups(p)]
+    B.dlf_plan_destroy(p)
+    B.dlf_net_destroy(h)
+    assert got == want
+
+
+def test_manual_plan_and_workspace():
+    net = nets.chain4(64)
+    h = _handle(net)
+    p = B.dlf_plan(h, 8, mode=B.TUNER_MANUAL, group_last=[1, 3], group_budget=[64, 256])
+    gs = B.dlf_plan_groups(p)
+    assert [(g["first"], g["last"], g["budget"]) for g in gs] == [(0, 1, 64), (2, 3, 256)]
+    assert gs[0]["model_cost"] == C.group_cost(net, 8, 0, 1, 64)
+    # one intermediate tensor (layer 1's output), 256-byte aligned
+    assert B.dlf_plan_workspace_bytes(p) == 8 * 56 * 56 * 64 * 2
+    assert B.dlf_plan_group_io(p, 0) == (-1, -2) and B.dlf_plan_group_io(p, 1) == (1, -2)
+    B.dlf_plan_destroy(p)
+    B.dlf_net_destroy(h)
+
+
+def test_residual_groups_read_their_operand_from_outside():
+    r = nets.resnet50()
+    net = _sub(r, 0, 5)
+    h = _handle(net)
+    p = B.dlf_plan(h, 2)
+    gs = B.dlf_plan_groups(p)
+    last = len(gs) - 1
+    assert gs[last]["last"] == 5
+    in_layer, res_layer = B.dlf_plan_group_io(p, last)
+    assert res_layer == net["layers"][5]["residual_from"]
+    assert not (gs[last]["first"] <= res_layer <= gs[last]["last"])
+    B.dlf_plan_destroy(p)
+    B.dlf_net_destroy(h)
+
+
+def _raises(status_substr, fn, *a, **kw):
+    with pytest.raises(B.DlfError) as e:
+        fn(*a, **kw)
+    assert status_substr in str(e.value).lower(), str(e.value)
+
+
+def test_error_paths_on_the_host():
+    good = nets.chain4(16)
+    h = _handle(good)
+    _raises("manual", B.dlf_plan, h, 1, mode=B.TUNER_MANUAL, group_last=[1], group_budget=[64])
+    _raises("manual", B.dlf_plan, h, 1, mode=B.TUNER_MANUAL, group_last=[2, 1, 3], group_budget=[64] * 3)
+    _raises("budget", B.dlf_plan, h, 1, budgets=[0, 64])
+    _raises("mode", B.dlf_plan, h, 1, mode=7)
+    _raises("argument", B.dlf_plan, h, 0)
+    _raises("group", B.dlf_plan, h, 1, mode=B.TUNER_MANUAL, group_last=[3], group_budget=[0])
+    assert B.dlf_group_cost(h, 1, 0, 3, 64, 8 * 1024) is None       # nothing fits 8 KiB
+    B.dlf_net_destroy(h)
+    bad = [dict(nets.conv(16, 16)), dict(nets.conv(32, 16))]        # cin mismatch
+    _raises("cin", B.dlf_net_create, bad, 8, 8, 16)
+    bad = [dict(nets.conv(16, 18))]                                   # cout % 4
+    _raises("cout", B.dlf_net_create, bad, 8, 8, 16)
+    bad = [dict(nets.conv(16, 16)), dict(nets.conv(16, 16, residual_from=1))]
+    _raises("earlier", B.dlf_net_create, bad, 8, 8, 16)
+    bad = [dict(nets.conv(16, 32)), dict(nets.conv(32, 16, residual_from=0))]
+    _raises("residual", B.dlf_net_create, bad, 8, 8, 16)
+    bad = [dict(nets.conv(16, 16, 5, 1, 0))]
+    _raises("kernel", B.dlf_net_create, bad, 3, 3, 16)
+    _raises("non-positive", B.dlf_net_create, [dict(nets.conv(16, 16))], 0, 8, 16)
+    # a net without weights plans but does not run
+    h = _handle(good)
+    p = B.dlf_plan(h, 1)
+    _raises("weight", B.dlf_run, p, 256, 256)
+    B.dlf_plan_destroy(p)
+    B.dlf_net_destroy(h)
