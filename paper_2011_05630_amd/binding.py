@@ -139,6 +139,18 @@ def dlf_net_destroy(net):
     lib().dlf_net_destroy(net)
 
 
+def dlf_net_num_layers(net):
+    return lib().dlf_net_num_layers(net)
+
+
+def dlf_status_string(status):
+    return lib().dlf_status_string(status).decode()
+
+
+def dlf_last_error():
+    return lib().dlf_last_error().decode()
+
+
 def dlf_net_layer_info(net, i):
     h, w, c = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
     ops = ctypes.c_uint64()

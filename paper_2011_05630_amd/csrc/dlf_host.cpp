@@ -622,7 +622,13 @@ namespace {
 
 const int DEFAULT_BUDGETS[4] = {32, 64, 128, 256};
 
-// Algorithm 1 of the paper (greedy joint fusion + MP pass); see the design doc for the readings.
+// Algorithm 1 of the paper (greedy joint fusion + MP pass).  Where the printed algorithm is silent
+// or inconsistent: the running mean of the per-layer MP is kept as a sum and a count; the threshold
+// test is skipped while the open block holds no convolution / FC layer; the walk covers every layer;
+// layers left over at the end form a last block; pooling layers ride with the block before them;
+// Eq. 5's proportionality is closed with a fitted scale and offset (MP = k * score + b, clamped),
+// with C = min(Cin, Cout); a block's MP is its mean MP floored to a power of two, then the largest
+// allowed budget not above it.
 void algorithm1(const dlf_net_s& net, int batch, double crit, double alpha, double beta, double k,
                 double b, const std::vector<int>& allowed, std::vector<int>& part, std::vector<int>& mps)
 {

@@ -92,7 +92,7 @@ def _small_nets():
     out.append((_sub(v, 10, 17), 1))       # deep 512-channel stages with pools
     r = nets.resnet50()
     out.append((_sub(r, 0, 5), 32))        # stem, pool, first bottleneck with projection
-    out.append((_sub(r, 6, 11), 4))        # two identity bottlenecks
+    out.append((_sub(r, 0, 8), 4))         # ... plus an identity bottleneck
     m = nets.mobilenet_v1()
     out.append((_sub(m, 0, 6), 64))        # stem + three dw/pw pairs
     out.append((_sub(m, len(m["layers"]) - 6, len(m["layers"]) - 1), 64))   # ... gap, fc
