@@ -2,14 +2,15 @@
  * libdlf — fused-layer CNN inference on one MI355X (gfx950).
  *
  * A network is given as a linear layer list; dlf_plan() partitions it into contiguous fusion
- * groups and gives each group a workgroup budget; dlf_run() executes the plan with one kernel
- * launch per group, intermediate feature maps of a group staying on-chip (LDS).
+ * groups and gives each group a budget of compute units (CUs); dlf_run() executes the plan with
+ * one kernel launch per group, intermediate feature maps of a group staying on-chip (LDS).
  *
  * This is the execution model the paper tunes (Sec. II-A.2: the two knobs "number of cores" and
  * "layer fusion"; Sec. III-B: a fused block keeps intermediates on chip and pays for it with
  * halo recomputation; Algorithm 1: inputs = layer list, number of layers, OpCount_critical,
- * outputs = fusion_partition_index[], mp_of_fusionblock[]).  Here "cores" are persistent
- * workgroups of the GPU.
+ * outputs = fusion_partition_index[], mp_of_fusionblock[]).  Here a "core" is a compute unit:
+ * a group with budget b is launched as min(tiles, b * occupancy) persistent workgroups, where
+ * occupancy (1 or 2 workgroups per CU) follows from the kernel variant's registers and LDS.
  *
  * Conventions
  *   - Every call returns a dlf_status; out-parameters are written only on DLF_OK.  Nothing
@@ -69,9 +70,9 @@ enum { DLF_TUNER_DP = 0,      /* exact minimum of the additive cost model over a
 
 typedef struct {
     int32_t mode;                     /* DLF_TUNER_*                                             */
-    const int32_t* budgets;           /* allowed workgroup budgets; NULL => {32,64,128,256}      */
+    const int32_t* budgets;           /* allowed CU budgets (the MP set); NULL => {32,64,128,256} */
     int32_t n_budgets;
-    double opcount_critical;          /* Algorithm 1: operations per workgroup at which a block  */
+    double opcount_critical;          /* Algorithm 1: operations per core at which a block       */
                                       /* is closed; <= 0 => library default                      */
     double alpha, beta;               /* Eq. 5 weights of log2(C) and log2(OpCount); both 0 =>   */
                                       /* the paper's 0.316 / 0.659                               */
@@ -101,12 +102,15 @@ dlf_status dlf_plan(const dlf_net_t* net, int32_t batch, const dlf_tuner_opts* o
                     dlf_plan_t** out);
 void dlf_plan_destroy(dlf_plan_t* plan);
 int32_t dlf_plan_num_groups(const dlf_plan_t* plan);
-/* Group g covers layers [*first, *last]; *budget workgroups; tile_h x tile_w output pixels per
+/* Group g covers layers [*first, *last] on *budget CUs; tile_h x tile_w output pixels per
  * workgroup step; model_cost in picoseconds of the cost model. Any out pointer may be NULL. */
 dlf_status dlf_plan_group(const dlf_plan_t* plan, int32_t g, int32_t* first, int32_t* last,
                           int32_t* budget, int32_t* tile_h, int32_t* tile_w, uint64_t* model_cost);
-/* Cost-model value (picoseconds) of running layers [first,last] as one group with `budget`
- * workgroups at the plan's batch; DLF_ERR_INFEASIBLE if the group cannot be executed. */
+/* Cost-model value (picoseconds) of running layers [first,last] as one group on `budget` CUs
+ * for `batch` images, minimised over the tilings the library can use; DLF_ERR_INFEASIBLE if the
+ * layers cannot be executed as one group (the paper times candidates on the device, Sec. V
+ * "Oracle Case"; here an integer model stands in, so that dlf_plan can be checked against
+ * exhaustive enumeration).  max_lds_bytes <= 0 => 160 KiB.  Works without a GPU. */
 dlf_status dlf_group_cost(const dlf_net_t* net, int32_t batch, int32_t first, int32_t last,
                           int32_t budget, int32_t max_lds_bytes, uint64_t* cost);
 /* Device bytes needed for the activations that cross group boundaries. */
@@ -133,8 +137,10 @@ dlf_status dlf_run_group(const dlf_plan_t* plan, int32_t g, const void* in_dev, 
 const void* dlf_plan_layer_output(const dlf_plan_t* plan, int32_t layer);
 
 /* Kernel configuration chosen for group g: kind (0 fused-group kernel, 1 FC, 2 global avgpool),
- * register-tile variant, channel slices, channels per slice, whether stage 0 streams its input,
- * LDS bytes per workgroup.  Any out pointer may be NULL. */
+ * register-tile variant (per-wave accumulator tile, output channels x pixels: 0 = 64x64,
+ * 1 = 32x128, 2 = 32x64, 3 = 32x64 built for two workgroups per CU), channel slices, channels
+ * per slice, whether stage 0 streams its input, LDS bytes per workgroup.  Any out pointer may be
+ * NULL. */
 dlf_status dlf_plan_group_config(const dlf_plan_t* plan, int32_t g, int32_t* kind, int32_t* variant,
                                  int32_t* nslices, int32_t* slice_c, int32_t* stream0,
                                  int32_t* lds_bytes);
