@@ -215,6 +215,8 @@ def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc
             return None
     if batch * in_h * in_w * in_c >= 1 << 31:
         return None
+    if batch * (out_h + 32) * (out_w + 32) * out_c >= 1 << 31:
+        return None
     chan_local = slice_c if nslices > 1 else 0
     area = [0, 0]
     for s in range(ns):

@@ -349,7 +349,9 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
         const int cslice = ga.st[0].kind == DLF_ST_CONV ? ga.st[0].cout : ga.st[0].cin;
         if ((int64_t)tc.nslices * tc.slice_c < cslice) return b;   // slices must cover every channel
     }
-    if ((int64_t)batch * ga.in_h * ga.in_w * ga.in_c >= (int64_t)1 << 31) return b;   // 32-bit offsets
+    // the kernels form element offsets into the input, output and residual tensors in 32 bits
+    if ((int64_t)batch * ga.in_h * ga.in_w * ga.in_c >= (int64_t)1 << 31) return b;
+    if ((int64_t)batch * (ga.out_h + 32) * (ga.out_w + 32) * ga.out_c >= (int64_t)1 << 31) return b;
     const int chan_local = (tc.nslices > 1) ? tc.slice_c : 0;   // 0 = all channels
 
     // LDS layout: stage s reads buffer s, writes buffer s+1; even buffers share one area,

@@ -21,6 +21,8 @@ typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 typedef float f4v __attribute__((ext_vector_type(4)));
+typedef unsigned u4v __attribute__((ext_vector_type(4)));
+typedef unsigned u2v __attribute__((ext_vector_type(2)));
 
 extern __shared__ __attribute__((aligned(16))) half_t lds[];
 
@@ -31,30 +33,72 @@ __device__ __forceinline__ float apply_act(float v, int act)
     return v;
 }
 
-// Region pixel index -> (row, col).  With `quad` the 4 pixels of a 2x2 pooling window are
-// consecutive indices, so they sit in 4 adjacent lanes of the MFMA result.
-__device__ __forceinline__ void pix_to_rc(int p, int rw, int quad, int& ry, int& rx)
+// Division of a small non-negative integer by a wave-uniform divisor d as one multiply:
+// q = (n * m) >> 32 with m = floor((2^32 - 1) / d) + 1, exact while n * d < 2^32 (d = 1 wraps m to
+// 0, which stands for "divide by one").  The general integer division costs some 40 vector
+// instructions; the address arithmetic of staging, epilogue and store phases is full of them.
+__device__ __forceinline__ unsigned div_magic(int d) { return 0xFFFFFFFFu / (unsigned)d + 1u; }
+__device__ __forceinline__ int div_by(int n, unsigned m)
+{
+    return m == 0 ? n : (int)__umulhi((unsigned)n, m);
+}
+
+// Region pixel index -> (row, col); rw_m = div_magic(rw), or div_magic(rw / 2) with `quad`.  With
+// `quad` the 4 pixels of a 2x2 pooling window are consecutive indices, so they sit in 4 adjacent
+// lanes of the MFMA result.
+__device__ __forceinline__ void pix_to_rc(int p, int rw, unsigned rw_m, int quad, int& ry, int& rx)
 {
     if (quad) {
         const int q = p >> 2, d = p & 3, hw = rw >> 1;
-        const int qy = q / hw, qx = q - qy * hw;
+        const int qy = div_by(q, rw_m), qx = q - qy * hw;
         ry = 2 * qy + (d >> 1);
         rx = 2 * qx + (d & 1);
     } else {
-        ry = p / rw;
+        ry = div_by(p, rw_m);
         rx = p - ry * rw;
     }
 }
 
-__device__ __forceinline__ float quad_max(float v)
+// Two packed fp16 values per 32-bit register: max / min / add on both halves at once.
+__device__ __forceinline__ unsigned pk_max(unsigned a, unsigned b)
+{
+    unsigned r;
+    asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ unsigned pk_min(unsigned a, unsigned b)
+{
+    unsigned r;
+    asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ unsigned pk_add(unsigned a, unsigned b)
+{
+    unsigned r;
+    asm("v_pk_add_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+// Rounds two fp32 values to fp16 (nearest even) into one register.
+__device__ __forceinline__ unsigned cvt_pk(float a, float b)
+{
+    typedef float f2v __attribute__((ext_vector_type(2)));
+    typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+    const f2v f = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f, h2v));
+}
+// The activation as a clamp on packed fp16: none = [-inf, +inf], ReLU = [0, +inf], ReLU6 = [0, 6].
+// Clamping after the rounding to fp16 gives the same result as before it: rounding is monotone
+// and 0 and 6 are exact in fp16.
+__device__ __forceinline__ unsigned act_lo(int act) { return act == 0 ? 0xFC00FC00u : 0u; }
+__device__ __forceinline__ unsigned act_hi(int act) { return act == 2 ? 0x46004600u : 0x7C007C00u; }
+
+__device__ __forceinline__ unsigned quad_max_pk(unsigned v)
 {
     // max over the 4 lanes of a quad with two DPP quad permutes: [1,0,3,2] then [2,3,0,1]
-    int x = __builtin_bit_cast(int, v);
-    float o = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(x, 0xB1, 0xF, 0xF, true));
-    v = fmaxf(v, o);
-    x = __builtin_bit_cast(int, v);
-    o = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(x, 0x4E, 0xF, 0xF, true));
-    return fmaxf(v, o);
+    unsigned o = (unsigned)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);
+    v = pk_max(v, o);
+    o = (unsigned)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true);
+    return pk_max(v, o);
 }
 
 // Loads 8 channels [c, c+8) of input pixel (n, gy, gx); zero outside the image or beyond c_end.
@@ -63,7 +107,8 @@ __device__ __forceinline__ h8 load_px8(const half_t* in, int n, int gy, int gx, 
 {
     h8 v = {0, 0, 0, 0, 0, 0, 0, 0};
     if (gy >= 0 && gy < H && gx >= 0 && gx < W && c < c_end) {
-        const half_t* p = in + (((size_t)n * H + gy) * W + gx) * C + c;
+        // the host rejects tensors of 2^31 elements or more, so offsets fit 32 bits
+        const half_t* p = in + (unsigned)(((n * H + gy) * W + gx) * C + c);
         if ((C & 7) == 0 && c + 8 <= c_end) {
             v = *(const h8*)p;
         } else {
@@ -82,27 +127,27 @@ __device__ __forceinline__ void stage_region(const half_t* in, int n, int H, int
 {
     const int nvec = cfill >> 3;
     const int total = ih * iw * nvec;
+    const unsigned nvec_m = div_magic(nvec), iw_m = div_magic(iw);
     // batches of 8 loads per thread are issued before any is stored: the HBM latency is paid
     // once per batch, not once per 16 bytes
     constexpr int U = 8;
     for (int v0 = threadIdx.x; v0 < total; v0 += DLF_WG_THREADS * U) {
         h8 val[U];
+        int doff[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int v = v0 + u * DLF_WG_THREADS;
             if (v < total) {
-                const int pix = v / nvec, part = v - pix * nvec;
-                const int ry = pix / iw, rx = pix - ry * iw;
+                const int pix = div_by(v, nvec_m), part = v - pix * nvec;
+                const int ry = div_by(pix, iw_m), rx = pix - ry * iw;
+                doff[u] = pix * cs + part * 8;
                 val[u] = load_px8(in, n, iy0 + ry, ix0 + rx, H, W, C, c0 + part * 8, c_end);
             }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int v = v0 + u * DLF_WG_THREADS;
-            if (v < total) {
-                const int pix = v / nvec, part = v - pix * nvec;
-                *(h8*)(dst + pix * cs + part * 8) = val[u];
-            }
+            if (v < total) *(h8*)(dst + doff[u]) = val[u];
         }
     }
 }
@@ -246,23 +291,24 @@ __device__ __forceinline__ int pin_s(int x)
     return x;
 }
 
-// Epilogue of a convolution work item: activation, optional 2x2 max pooling across the 4 lanes
-// of a quad, fp16 rounding, store of 4 consecutive channels per lane into the LDS tile
+// Epilogue of a convolution work item: fp16 rounding, optional 2x2 max pooling across the 4 lanes
+// of a quad, activation, store of 4 consecutive channels per lane into the LDS tile
 // [pixel][out_cs].  Pixels outside the true feature map are stored as zero (the padding value the
 // next convolution of the group must see).
 template <int FC, int FP, bool POOL>
 __device__ __forceinline__ void conv_epilogue(f16v (&acc)[FC][FP], int cbl, int ncbv, int pg,
-                                              int npix, int rw, int ry0, int rx0, int out_h,
-                                              int out_w, int act, int out_off, int out_cs)
+                                              int npix, int rw, unsigned rw_m, int ry0, int rx0,
+                                              int out_h, int out_w, int act, int out_off, int out_cs)
 {
     const int lane = threadIdx.x & 63, l32 = lane & 31, lhi = lane >> 5;
     const int cmax = out_cs - DLF_CPAD;
+    const unsigned lo_act = act_lo(act), hi_act = act_hi(act);
 #pragma unroll
     for (int p = 0; p < FP; ++p) {
         const int pix = (pg * FP + p) * 32 + l32;
         const bool valid = pix < npix;
         int ry, rx;
-        pix_to_rc(valid ? pix : 0, rw, POOL ? 1 : 0, ry, rx);
+        pix_to_rc(valid ? pix : 0, rw, rw_m, POOL ? 1 : 0, ry, rx);
         const int gy = ry0 + ry, gx = rx0 + rx;
         bool keep, store;
         int row;
@@ -276,6 +322,9 @@ __device__ __forceinline__ void conv_epilogue(f16v (&acc)[FC][FP], int cbl, int 
             store = valid;
             row = pix;
         }
+        // a pixel outside the feature map is clamped to [0, 0]: the zero padding the next
+        // convolution must see, at no extra instruction
+        const unsigned lo = keep ? lo_act : 0u, hi = keep ? hi_act : 0u;
         half_t* dst = lds + out_off + row * out_cs + lhi * 4;
 #pragma unroll
         for (int f = 0; f < FC; ++f) {
@@ -283,14 +332,18 @@ __device__ __forceinline__ void conv_epilogue(f16v (&acc)[FC][FP], int cbl, int 
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int lc = (cbl + f) * 32 + q * 8;
-                    h4 hv;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        float v = apply_act(acc[f][p][q * 4 + r], act);
-                        if (POOL) v = quad_max(v);
-                        hv[r] = keep ? (half_t)v : (half_t)0;
+                    unsigned u0 = cvt_pk(acc[f][p][q * 4 + 0], acc[f][p][q * 4 + 1]);
+                    unsigned u1 = cvt_pk(acc[f][p][q * 4 + 2], acc[f][p][q * 4 + 3]);
+                    if (POOL) {
+                        u0 = quad_max_pk(u0);
+                        u1 = quad_max_pk(u1);
                     }
-                    if (store && lc + lhi * 4 < cmax) *(h4*)(dst + lc) = hv;
+                    u0 = pk_min(pk_max(u0, lo), hi);
+                    u1 = pk_min(pk_max(u1, lo), hi);
+                    if (store && lc + lhi * 4 < cmax) {
+                        const u2v uu = {u0, u1};
+                        *(u2v*)(dst + lc) = uu;
+                    }
                 }
             }
         }
@@ -323,6 +376,7 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
     const int n_cg = (cb_end - cb_begin + FC - 1) / FC;
     const int nitems = n_pg * n_cg;
     const int ry0 = ty0 * st.oy_mul + st.oy_off, rx0 = tx0 * st.ox_mul + st.ox_off;
+    const unsigned rw_m = div_magic(st.pool2 ? st.rw >> 1 : st.rw);
     const int kc = STREAM ? st.kc : 32;         // channels per round
     const int cpr = kc >> 5;                    // 32-channel chunks per round
     const int nrounds = st.cin_pad / kc;
@@ -337,13 +391,14 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
         const int vshift = st.kc_shift;              // log2(16-byte vectors per pixel per round)
         const int vmask = (1 << vshift) - 1;
         const int s_total = (st.ih * st.iw) << vshift;
+        const unsigned iw_m = div_magic(st.iw);
         const int iy0 = ty0 * a.iy_mul + a.iy_off, ix0 = tx0 * a.ix_mul + a.ix_off;
         int s_goff[DLF_STAGE_VECS];   // element offset into `in` for round 0, or -1 (zero fill)
         if ((st.cin & 7) != 0) {
             // narrow inputs (e.g. 3 channels): one round, element-wise copy
             for (int v = lt; v < s_total; v += DLF_LOAD_THREADS) {
                 const int pix = v >> vshift, part = v & vmask;
-                const int ry = pix / st.iw, rx = pix - ry * st.iw;
+                const int ry = div_by(pix, iw_m), rx = pix - ry * st.iw;
                 *(h8*)(lds + st.in_off + pix * cs + part * 8) =
                     load_px8(in, n, iy0 + ry, ix0 + rx, a.in_h, a.in_w, a.in_c, part * 8, st.cin);
             }
@@ -357,7 +412,7 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
             s_goff[i] = -1;
             if (v < s_total) {
                 const int pix = v >> vshift, part = v & vmask;
-                const int ry = pix / st.iw, rx = pix - ry * st.iw;
+                const int ry = div_by(pix, iw_m), rx = pix - ry * st.iw;
                 const int gy = iy0 + ry, gx = ix0 + rx;
                 if (gy >= 0 && gy < a.in_h && gx >= 0 && gx < a.in_w)
                     s_goff[i] = ((n * a.in_h + gy) * a.in_w + gx) * a.in_c + part * 8;
@@ -401,7 +456,7 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
         for (int p = 0; p < FP; ++p) {
             const int pix = (pg * FP + p) * 32 + l32;
             int ry, rx;
-            pix_to_rc(pix < npix ? pix : 0, st.rw, st.pool2, ry, rx);
+            pix_to_rc(pix < npix ? pix : 0, st.rw, rw_m, st.pool2, ry, rx);
             pbase[p] = ((ry * st.stride) * st.iw + rx * st.stride) * cs + lhi * 8;
         }
         const h8* wp[FC];
@@ -465,11 +520,11 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
         const int cbl = cg * FC;                       // first local channel block of the item
         const int ncbv = min(FC, cb_end - cb_begin - cbl);
         if (st.pool2)
-            conv_epilogue<FC, FP, true>(acc, cbl, ncbv, pg, npix, pin_s(st.rw), ry0, rx0,
+            conv_epilogue<FC, FP, true>(acc, cbl, ncbv, pg, npix, pin_s(st.rw), rw_m, ry0, rx0,
                                         pin_s(st.out_h), pin_s(st.out_w), act, pin_s(st.out_off),
                                         pin_s(st.out_cs));
         else
-            conv_epilogue<FC, FP, false>(acc, cbl, ncbv, pg, npix, pin_s(st.rw), ry0, rx0,
+            conv_epilogue<FC, FP, false>(acc, cbl, ncbv, pg, npix, pin_s(st.rw), rw_m, ry0, rx0,
                                          pin_s(st.out_h), pin_s(st.out_w), act, pin_s(st.out_off),
                                          pin_s(st.out_cs));
     }
@@ -494,32 +549,36 @@ __device__ __forceinline__ void store_tile(const DlfGroupArgs& a, const DlfStage
     if ((st.cout & 7) == 0) {
         const int nvec = ccnt >> 3;
         const int total = ph * pw * nvec;
+        const unsigned nvec_m = div_magic(nvec), pw_m = div_magic(pw);
+        const unsigned lo = act_lo(st.act), hi = act_hi(st.act);
         constexpr int U = 4;     // residual loads of a batch are all in flight together
         for (int v0 = threadIdx.x; v0 < total; v0 += DLF_WG_THREADS * U) {
-            size_t go[U];
-            h8 val[U], rv[U];
+            unsigned go[U];      // element offsets fit 32 bits (checked on the host)
+            u4v val[U], rv[U];
             bool ok[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int v = v0 + u * DLF_WG_THREADS;
                 const int vc = v < total ? v : 0;
-                const int pix = vc / nvec, part = vc - pix * nvec;
-                const int y = pix / pw, x = pix - y * pw;
+                const int pix = div_by(vc, nvec_m), part = vc - pix * nvec;
+                const int y = div_by(pix, pw_m), x = pix - y * pw;
                 const int gy = oy + y, gx = ox + x;
                 ok[u] = v < total && gy < a.out_h && gx < a.out_w;
-                go[u] = (((size_t)n * a.out_h + gy) * a.out_w + gx) * a.out_c + c0 + part * 8;
-                val[u] = *(const h8*)(lds + st.out_off + pix * st.out_cs + part * 8);
-                if (resp != nullptr && ok[u]) rv[u] = *(const h8*)(resp + go[u]);
+                go[u] = (unsigned)(((n * a.out_h + gy) * a.out_w + gx) * a.out_c + c0 + part * 8);
+                if (resp != nullptr && ok[u]) rv[u] = *(const u4v*)(resp + go[u]);
+                val[u] = *(const u4v*)(lds + st.out_off + pix * st.out_cs + part * 8);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (ok[u]) {
                     if (resp != nullptr) {
-#pragma unroll
-                        for (int j = 0; j < 8; ++j)
-                            val[u][j] = (half_t)apply_act((float)val[u][j] + (float)rv[u][j], st.act);
+                        // fp16 + fp16 correctly rounded, then the activation as a clamp
+                        val[u].x = pk_min(pk_max(pk_add(val[u].x, rv[u].x), lo), hi);
+                        val[u].y = pk_min(pk_max(pk_add(val[u].y, rv[u].y), lo), hi);
+                        val[u].z = pk_min(pk_max(pk_add(val[u].z, rv[u].z), lo), hi);
+                        val[u].w = pk_min(pk_max(pk_add(val[u].w, rv[u].w), lo), hi);
                     }
-                    *(h8*)(outp + go[u]) = val[u];
+                    *(u4v*)(outp + go[u]) = val[u];
                 }
             }
         }
@@ -556,33 +615,37 @@ __device__ __forceinline__ void valu_stage(const DlfGroupArgs& a, const DlfStage
         ccnt = min(a.slice_c, st.cout - c0);
     }
     const int ncg = (ccnt + 7) >> 3;
+    const unsigned ncg_m = div_magic(ncg), rw_m = div_magic(st.rw);
     const int ry0 = ty0 * st.oy_mul + st.oy_off, rx0 = tx0 * st.ox_mul + st.ox_off;
     const half_t* wdw = (const half_t*)st.w;
     half_t* outp = (half_t*)a.out;
     for (int it = threadIdx.x; it < npix * ncg; it += DLF_WG_THREADS) {
-        const int pix = it / ncg, g = it - pix * ncg;
-        const int ry = pix / st.rw, rx = pix - ry * st.rw;
+        const int pix = div_by(it, ncg_m), g = it - pix * ncg;
+        const int ry = div_by(pix, rw_m), rx = pix - ry * st.rw;
         const int gy = ry0 + ry, gx = rx0 + rx;
         const bool inimg = gy >= 0 && gy < st.out_h && gx >= 0 && gx < st.out_w;
         const int lc = g * 8;
-        float v[8];
+        u4v hv;
         if (st.kind == DLF_ST_MAXPOOL) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = -INFINITY;
+            // max of fp16 values is exact: stay in packed fp16
+            hv = u4v{0xFC00FC00u, 0xFC00FC00u, 0xFC00FC00u, 0xFC00FC00u};   // -inf
             for (int kh = 0; kh < st.kh; ++kh) {
                 const int iy = gy * st.stride - st.pad + kh;
                 if (iy < 0 || iy >= st.in_h) continue;
                 for (int kw = 0; kw < st.kw; ++kw) {
                     const int ix = gx * st.stride - st.pad + kw;
                     if (ix < 0 || ix >= st.in_w) continue;
-                    const h8 x = *(const h8*)(lds + st.in_off
-                                              + ((ry * st.stride + kh) * st.iw + rx * st.stride + kw)
-                                                    * st.in_cs + lc);
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) v[j] = fmaxf(v[j], (float)x[j]);
+                    const u4v x = *(const u4v*)(lds + st.in_off
+                                                    + ((ry * st.stride + kh) * st.iw + rx * st.stride + kw)
+                                                          * st.in_cs + lc);
+                    hv.x = pk_max(hv.x, x.x);
+                    hv.y = pk_max(hv.y, x.y);
+                    hv.z = pk_max(hv.z, x.z);
+                    hv.w = pk_max(hv.w, x.w);
                 }
             }
         } else {
+            float v[8];
             const f4v b0 = *(const f4v*)(st.bias + c0 + lc);
             const f4v b1 = *(const f4v*)(st.bias + c0 + lc + 4);
 #pragma unroll
@@ -597,26 +660,27 @@ __device__ __forceinline__ void valu_stage(const DlfGroupArgs& a, const DlfStage
                     for (int j = 0; j < 8; ++j) v[j] = fmaf((float)x[j], (float)w[j], v[j]);
                 }
             }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = apply_act(v[j], st.act);
+            const unsigned lo = act_lo(st.act), hi = act_hi(st.act);
+            hv.x = pk_min(pk_max(cvt_pk(v[0], v[1]), lo), hi);
+            hv.y = pk_min(pk_max(cvt_pk(v[2], v[3]), lo), hi);
+            hv.z = pk_min(pk_max(cvt_pk(v[4], v[5]), lo), hi);
+            hv.w = pk_min(pk_max(cvt_pk(v[6], v[7]), lo), hi);
         }
-        h8 hv;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) hv[j] = (half_t)v[j];
         if (last) {
             if (inimg) {
-                half_t* o = outp + (((size_t)n * a.out_h + gy) * a.out_w + gx) * a.out_c + c0 + lc;
+                half_t* o = outp + (unsigned)(((n * a.out_h + gy) * a.out_w + gx) * a.out_c + c0 + lc);
                 if (lc + 8 <= ccnt) {
-                    *(h8*)o = hv;
+                    *(u4v*)o = hv;
                 } else {
+                    const h8 hh = __builtin_bit_cast(h8, hv);
 #pragma unroll
                     for (int j = 0; j < 8; ++j)
-                        if (lc + j < ccnt) o[j] = hv[j];
+                        if (lc + j < ccnt) o[j] = hh[j];
                 }
             }
         } else {
-            const h8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-            *(h8*)(lds + st.out_off + pix * st.out_cs + lc) = inimg ? hv : z;
+            const u4v z = {0, 0, 0, 0};
+            *(u4v*)(lds + st.out_off + pix * st.out_cs + lc) = inimg ? hv : z;
         }
     }
 }
