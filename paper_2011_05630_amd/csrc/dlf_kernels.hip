@@ -605,6 +605,9 @@ __device__ __forceinline__ void store_tile(const DlfGroupArgs& a, const DlfStage
 
 // Max pooling and depthwise convolution on the vector ALUs: one work item = one output pixel x
 // 8 channels, input read from LDS (16 bytes per tap), fp32 arithmetic.
+// HOIST: keep the 3x3 depthwise weights of the lane's channel group in registers across work
+// items (44 registers; not in the 128-register build, where they are re-read per item).
+template <bool HOIST>
 __device__ __forceinline__ void valu_stage(const DlfGroupArgs& a, const DlfStage& st, bool last,
                                            int n, int ty0, int tx0, int slice)
 {
@@ -619,6 +622,18 @@ __device__ __forceinline__ void valu_stage(const DlfGroupArgs& a, const DlfStage
     const int ry0 = ty0 * st.oy_mul + st.oy_off, rx0 = tx0 * st.ox_mul + st.ox_off;
     const half_t* wdw = (const half_t*)st.w;
     half_t* outp = (half_t*)a.out;
+    const bool k3 = st.kind == DLF_ST_DW && st.kh == 3 && st.kw == 3;
+    // a thread's channel group is it % ncg with it advancing by the workgroup size
+    const bool fixed_g = HOIST && (DLF_WG_THREADS % ncg) == 0;
+    h8 w3[9];
+    f4v b0, b1;
+    if (k3 && fixed_g) {
+        const int lc = (threadIdx.x % ncg) * 8;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) w3[t] = *(const h8*)(wdw + t * st.cin_pad + c0 + lc);
+        b0 = *(const f4v*)(st.bias + c0 + lc);
+        b1 = *(const f4v*)(st.bias + c0 + lc + 4);
+    }
     for (int it = threadIdx.x; it < npix * ncg; it += DLF_WG_THREADS) {
         const int pix = div_by(it, ncg_m), g = it - pix * ncg;
         const int ry = div_by(pix, rw_m), rx = pix - ry * st.rw;
@@ -646,18 +661,44 @@ __device__ __forceinline__ void valu_stage(const DlfGroupArgs& a, const DlfStage
             }
         } else {
             float v[8];
-            const f4v b0 = *(const f4v*)(st.bias + c0 + lc);
-            const f4v b1 = *(const f4v*)(st.bias + c0 + lc + 4);
+            if (k3) {
+                // 3x3: taps unrolled, the 9 weight vectors and the bias of the lane's channel
+                // group held in registers (loaded once when the group never changes)
+                if (!fixed_g) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { v[j] = b0[j]; v[j + 4] = b1[j]; }
-            for (int kh = 0; kh < st.kh; ++kh) {
-                for (int kw = 0; kw < st.kw; ++kw) {
-                    const h8 x = *(const h8*)(lds + st.in_off
-                                              + ((ry * st.stride + kh) * st.iw + rx * st.stride + kw)
-                                                    * st.in_cs + lc);
-                    const h8 w = *(const h8*)(wdw + (kh * st.kw + kw) * st.cin_pad + c0 + lc);
+                    for (int t = 0; t < 9; ++t) w3[t] = *(const h8*)(wdw + t * st.cin_pad + c0 + lc);
+                    b0 = *(const f4v*)(st.bias + c0 + lc);
+                    b1 = *(const f4v*)(st.bias + c0 + lc + 4);
+                }
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) v[j] = fmaf((float)x[j], (float)w[j], v[j]);
+                for (int j = 0; j < 4; ++j) { v[j] = b0[j]; v[j + 4] = b1[j]; }
+                const half_t* xp = lds + st.in_off + ((ry * st.stride) * st.iw + rx * st.stride) * st.in_cs + lc;
+                const int rowstep = st.iw * st.in_cs;
+#pragma unroll
+                for (int kh = 0; kh < 3; ++kh) {
+                    h8 x[3];
+#pragma unroll
+                    for (int kw = 0; kw < 3; ++kw) x[kw] = *(const h8*)(xp + kh * rowstep + kw * st.in_cs);
+#pragma unroll
+                    for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+                        for (int j = 0; j < 8; ++j)
+                            v[j] = fmaf((float)x[kw][j], (float)w3[kh * 3 + kw][j], v[j]);
+                }
+            } else {
+                const f4v c0v = *(const f4v*)(st.bias + c0 + lc);
+                const f4v c1v = *(const f4v*)(st.bias + c0 + lc + 4);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { v[j] = c0v[j]; v[j + 4] = c1v[j]; }
+                for (int kh = 0; kh < st.kh; ++kh) {
+                    for (int kw = 0; kw < st.kw; ++kw) {
+                        const h8 x = *(const h8*)(lds + st.in_off
+                                                  + ((ry * st.stride + kh) * st.iw + rx * st.stride + kw)
+                                                        * st.in_cs + lc);
+                        const h8 w = *(const h8*)(wdw + (kh * st.kw + kw) * st.cin_pad + c0 + lc);
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) v[j] = fmaf((float)x[j], (float)w[j], v[j]);
+                    }
                 }
             }
             const unsigned lo = act_lo(st.act), hi = act_hi(st.act);
@@ -739,7 +780,7 @@ __global__ __launch_bounds__(DLF_WG_THREADS, MINW) void k_group(const DlfGroupAr
                     store_tile(a, st, n, ty0, tx0, slice);
                 }
             } else {
-                valu_stage(a, st, last, n, ty0, tx0, slice);
+                valu_stage<(MINW < 4)>(a, st, last, n, ty0, tx0, slice);
             }
             __syncthreads();
         }
