@@ -23,6 +23,7 @@ C_TILE = 6000
 C_LAT = 5000
 C_STAGE_VEC = 120
 C_IM2COL = 150
+C_ROWFOLD = 400
 C_ROUND = 3800
 C_BARRIER = 500
 C_EPI = 900
@@ -69,6 +70,7 @@ class NetInfo:
         n = len(self.layers)
         self.src, self.ish, self.osh = [0] * n, [None] * n, [None] * n
         self.cin_pad, self.ncb, self.nsteps, self.im2col = [0] * n, [0] * n, [0] * n, [False] * n
+        self.rowfold = [False] * n
         for i, L in enumerate(self.layers):
             s = L["input_from"] if L["input_from"] >= 0 else i - 1
             self.src[i] = s
@@ -82,11 +84,17 @@ class NetInfo:
             else:
                 self.osh[i] = (1, 1, L["cout"])
             if op in ("conv", "fc"):
-                self.im2col[i] = op == "conv" and L["cin"] % 8 != 0
+                narrow = op == "conv" and L["cin"] % 8 != 0
+                self.rowfold[i] = narrow and L["cin"] <= 4 and L["stride"] % 2 == 0 and L["kw"] * 4 <= 128
+                self.im2col[i] = narrow and not self.rowfold[i]
                 k = L["kh"] * L["kw"] * L["cin"] if self.im2col[i] else L["cin"]
+                if self.rowfold[i]:
+                    k = L["kw"] * 4
                 self.cin_pad[i] = rup(k, 32)
                 self.ncb[i] = cdiv(L["cout"], 32)
-                if self.im2col[i]:
+                if self.rowfold[i]:
+                    self.nsteps[i] = (self.cin_pad[i] // 16) * L["kh"]
+                elif self.im2col[i]:
                     self.nsteps[i] = self.cin_pad[i] // 16
                 else:
                     self.nsteps[i] = (self.cin_pad[i] // 32) * L["kh"] * L["kw"] * 2
@@ -187,7 +195,12 @@ def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc
         h, w = st["ih"], st["iw"]
         st["im2col"] = 0
         st["kh"], st["kw"] = kh, kw
-        if kind == CONV and ni.im2col[li]:
+        if kind == CONV and ni.rowfold[li]:
+            if s != 0 or stream0:
+                return None
+            st.update(im2col=2, im_kh=kh, im_kw=kw, im_stride=stride, im_cin=L["cin"], kw=1,
+                      iw=rup(st["iw"], 2))
+        elif kind == CONV and ni.im2col[li]:
             if s != 0 or stream0:
                 return None
             st.update(im2col=1, im_kh=kh, im_kw=kw, im_stride=stride, im_cin=L["cin"], kh=1, kw=1,
@@ -221,11 +234,15 @@ def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc
     area = [0, 0]
     for s in range(ns):
         st = S[s]
-        if st["kind"] == CONV:
+        if st["kind"] == CONV and st["im2col"] == 2:
+            cs = 4
+        elif st["kind"] == CONV:
             cs = st["kc"] + CPAD if (s == 0 and stream0) else st["cin_pad"] + CPAD
         else:
             cs = rup(chan_local if chan_local else st["cin"], 8) + CPAD
         sz = st["ih"] * st["iw"] * cs
+        if st["kind"] == CONV and st["im2col"] == 2:
+            sz += 32
         if s == 0 and stream0:
             sz *= 2
             if st["ih"] * st["iw"] * (st["kc"] // 8) > STAGE_VECS * LOAD_THREADS:
@@ -257,6 +274,8 @@ def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc
     cin0 = chan_local if (s0["kind"] != CONV and chan_local) else s0["cin"]
     if stream0:
         cyc += C_LAT
+    elif s0["kind"] == CONV and s0["im2col"] == 2:
+        cyc += C_LAT + cdiv(s0["ih"] * s0["iw"], WG_THREADS) * C_ROWFOLD
     elif s0["kind"] == CONV and s0["im2col"]:
         cyc += C_LAT + cdiv(s0["rh"] * s0["rw"] * s0["im_kh"], WG_THREADS) * s0["im_kw"] * s0["im_cin"] * C_IM2COL
     else:
@@ -288,7 +307,9 @@ def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc
     if sl["kind"] == CONV:
         cyc += cdiv(th * tw * cdiv(cout_l, 8), WG_THREADS) * C_STORE_VEC + C_STORE + has_res * C_LAT
     hbm = s0["ih"] * s0["iw"] * cin0 * 2 + th * tw * cout_l * 2 * (1 + has_res)
-    if s0["kind"] == CONV and s0["im2col"]:
+    if s0["kind"] == CONV and s0["im2col"] == 2:
+        hbm = s0["ih"] * s0["iw"] * s0["im_cin"] * 2 + th * tw * cout_l * 2
+    elif s0["kind"] == CONV and s0["im2col"]:
         hbm = s0["rh"] * s0["rw"] * s0["im_stride"] * s0["im_stride"] * s0["im_cin"] * 2 + th * tw * cout_l * 2
     return ntiles, lds_bytes, cyc, hbm, l2
 

@@ -44,6 +44,9 @@ struct Layer {
     float* d_bias = nullptr;
     int kc = 0, cin_pad = 0, ncb = 0, nsteps = 0;
     bool im2col = false;     // narrow-input convolution run as a 1x1 over gathered rows
+    bool rowfold = false;    // narrow-input convolution (cin <= 4, even stride) whose filter columns are
+                             // folded into the channel dimension: input staged as 4-channel pixels,
+                             // one tap per filter row over round_up(4 * kw, 32) "channels"
 };
 
 }  // namespace
@@ -104,7 +107,18 @@ dlf_status pack_and_upload(Layer& L)
     if (d.op == DLF_CONV || d.op == DLF_FC) {
         std::vector<uint16_t> packed;
         const int taps = d.kh * d.kw;
-        if (L.im2col)   // [cout][kh][kw][cin] is already the gathered row order: a 1x1 over kh*kw*cin
+        if (L.rowfold) {
+            // repack [cout][kh][kw][cin] as [cout][kh][cin_pad] with column kw*4 + c, zero elsewhere
+            std::vector<uint16_t> w4((size_t)d.cout * d.kh * L.cin_pad, 0);
+            const uint16_t* src = (const uint16_t*)d.weight;
+            for (int co = 0; co < d.cout; ++co)
+                for (int r = 0; r < d.kh; ++r)
+                    for (int q = 0; q < d.kw; ++q)
+                        for (int c = 0; c < d.cin; ++c)
+                            w4[((size_t)co * d.kh + r) * L.cin_pad + q * 4 + c] =
+                                src[(((size_t)co * d.kh + r) * d.kw + q) * d.cin + c];
+            pack_conv_weights(w4.data(), d.cout, d.kh, L.cin_pad, L.kc, L.cin_pad, packed);
+        } else if (L.im2col)   // [cout][kh][kw][cin] is already the gathered row order: a 1x1 over kh*kw*cin
             pack_conv_weights((const uint16_t*)d.weight, d.cout, 1, taps * d.cin, L.kc, L.cin_pad, packed);
         else
             pack_conv_weights((const uint16_t*)d.weight, d.cout, taps, d.cin, L.kc, L.cin_pad, packed);
@@ -173,6 +187,7 @@ const int64_t C_TILE = 6000;                // per tile: decode, address setup, 
 const int64_t C_LAT = 5000;                 // one exposed HBM/L2 round trip
 const int64_t C_STAGE_VEC = 120;             // per 512 staged 16-byte vectors
 const int64_t C_IM2COL = 150;                // per gathered element per 512 (pixel, row) pairs
+const int64_t C_ROWFOLD = 400;               // per 512 staged narrow pixels (3 element loads, one 8-byte LDS write)
 const int64_t C_ROUND = 3800;               // lower bound of a streaming round (loader latency)
 const int64_t C_BARRIER = 500;
 const int64_t C_EPI = 900;                  // epilogue per 32x32 accumulator block
@@ -318,7 +333,14 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
         mx *= st.stride; ox = ox * st.stride - st.pad;
         h = st.ih; w = st.iw;
         st.im2col = 0;
-        if (st.kind == DLF_ST_CONV && L.im2col) {
+        if (st.kind == DLF_ST_CONV && L.rowfold) {
+            if (s != 0 || tc.stream0) return b;      // folded staging: resident stage 0 only
+            st.im2col = 2;
+            st.im_kh = st.kh; st.im_kw = st.kw; st.im_stride = st.stride; st.im_pad = st.pad;
+            st.im_cin = L.d.cin;
+            st.kw = 1;                                // what the MFMA loop sees: one tap per row
+            st.iw = round_up(st.iw, 2);               // keeps every 16-byte LDS read aligned
+        } else if (st.kind == DLF_ST_CONV && L.im2col) {
             if (s != 0 || tc.stream0) return b;      // gathered staging: resident stage 0 only
             st.im2col = 1;
             st.im_kh = st.kh; st.im_kw = st.kw; st.im_stride = st.stride; st.im_pad = st.pad;
@@ -361,7 +383,9 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
     for (int s = 0; s < ns; ++s) {
         DlfStage& st = ga.st[s];
         int cs;
-        if (st.kind == DLF_ST_CONV) {
+        if (st.kind == DLF_ST_CONV && st.im2col == 2) {
+            cs = 4;
+        } else if (st.kind == DLF_ST_CONV) {
             cs = (s == 0 && tc.stream0) ? st.kc + DLF_CPAD : st.cin_pad + DLF_CPAD;
         } else {
             const int c = chan_local ? chan_local : st.cin;
@@ -370,6 +394,7 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
         st.in_cs = cs;
         if (s > 0) ga.st[s - 1].out_cs = cs;
         int64_t sz = (int64_t)st.ih * st.iw * cs;
+        if (st.kind == DLF_ST_CONV && st.im2col == 2) sz += 32;   // zeroed slack behind the last pixel
         if (s == 0 && tc.stream0) {
             st.stream_buf = (int)sz;
             sz *= 2;
@@ -409,6 +434,8 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
     const int cin0 = (s0.kind != DLF_ST_CONV && chan_local) ? chan_local : s0.cin;
     if (tc.stream0) {
         cyc += C_LAT;
+    } else if (s0.kind == DLF_ST_CONV && s0.im2col == 2) {
+        cyc += C_LAT + (int64_t)ceil_div(s0.ih * s0.iw, DLF_WG_THREADS) * C_ROWFOLD;
     } else if (s0.kind == DLF_ST_CONV && s0.im2col) {
         cyc += C_LAT + (int64_t)ceil_div(s0.rh * s0.rw * s0.im_kh, DLF_WG_THREADS) * s0.im_kw * s0.im_cin * C_IM2COL;
     } else {
@@ -448,7 +475,9 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
         cyc += (int64_t)ceil_div(tc.th * tc.tw * ceil_div(cout_l, 8), DLF_WG_THREADS) * C_STORE_VEC + C_STORE
                + has_res * C_LAT;
     b.tile_hbm_bytes = (int64_t)s0.ih * s0.iw * cin0 * 2 + (int64_t)tc.th * tc.tw * cout_l * 2 * (1 + has_res);
-    if (s0.kind == DLF_ST_CONV && s0.im2col)
+    if (s0.kind == DLF_ST_CONV && s0.im2col == 2)
+        b.tile_hbm_bytes = (int64_t)s0.ih * s0.iw * s0.im_cin * 2 + (int64_t)tc.th * tc.tw * cout_l * 2;
+    else if (s0.kind == DLF_ST_CONV && s0.im2col)
         b.tile_hbm_bytes = (int64_t)s0.rh * s0.rw * s0.im_stride * s0.im_stride * s0.im_cin * 2
                            + (int64_t)tc.th * tc.tw * cout_l * 2;
     b.tile_l2_bytes = l2;
@@ -772,14 +801,19 @@ dlf_status dlf_net_create(const dlf_layer_desc* layers, int32_t n, int32_t in_h,
             return bad(DLF_ERR_UNSUPPORTED, "pooling pad must be smaller than the window");
         if (d.op == DLF_CONV || d.op == DLF_FC) {
             L.kc = 32;
-            L.im2col = d.op == DLF_CONV && (d.cin % 8) != 0;
+            const bool narrow = d.op == DLF_CONV && (d.cin % 8) != 0;
+            L.rowfold = narrow && d.cin <= 4 && (d.stride % 2) == 0 && d.kw * 4 <= 128;
+            L.im2col = narrow && !L.rowfold;
+            if (narrow && L.src >= 0)
+                return bad(DLF_ERR_UNSUPPORTED, "a convolution with cin % 8 != 0 must read the network input");
             if (L.im2col && L.src >= 0)
                 return bad(DLF_ERR_UNSUPPORTED, "a convolution with cin % 8 != 0 must read the network input");
             if (L.im2col && d.kh * d.kw * d.cin > 1024)
                 return bad(DLF_ERR_UNSUPPORTED, "narrow-input convolution too large");
-            L.cin_pad = round_up(L.im2col ? d.kh * d.kw * d.cin : d.cin, L.kc);
+            L.cin_pad = round_up(L.rowfold ? d.kw * 4 : (L.im2col ? d.kh * d.kw * d.cin : d.cin), L.kc);
             L.ncb = ceil_div(d.cout, 32);
-            L.nsteps = L.im2col ? L.cin_pad / 16 : (L.cin_pad / L.kc) * d.kh * d.kw * (L.kc / 16);
+            L.nsteps = L.rowfold ? (L.cin_pad / 16) * d.kh
+                                 : (L.im2col ? L.cin_pad / 16 : (L.cin_pad / L.kc) * d.kh * d.kw * (L.kc / 16));
         } else if (d.op == DLF_DWCONV) {
             L.kc = 8; L.cin_pad = round_up(d.cin, 8);
         }

@@ -38,9 +38,12 @@ struct DlfStage {
     int32_t out_off;      // LDS offset (halfs) of the output buffer
     int32_t stream_buf;   // stream mode: halfs per chunk buffer
     int32_t nsteps;       // CONV: 16-wide K steps per output-channel block
-    int32_t im2col;       // CONV stage 0 on a narrow input (cin % 8 != 0): the staging gathers each
+    int32_t im2col;       // CONV stage 0 on a narrow input (cin % 8 != 0).  1: the staging gathers each
                           // output pixel's kh*kw*cin inputs into one LDS row and the stage then
-                          // runs as a 1x1 convolution over cin_pad = roundup(kh*kw*cin, 32) channels
+                          // runs as a 1x1 convolution over cin_pad = roundup(kh*kw*cin, 32) channels.
+                          // 2 (cin <= 4, even stride): the input patch is staged as 4-channel pixels
+                          // and the stage runs with one tap per filter row over
+                          // cin_pad = roundup(4*kw, 32) channels, in_cs = 4, kw = 1
     int32_t im_kh, im_kw, im_stride, im_pad, im_cin; // the real filter geometry of an im2col stage
     const void* w;        // CONV: packed fragments; DW: [kh][kw][c] fp16
     const float* bias;    // padded with zeros to ncb*32 (CONV) / c rounded up to 8 (DW)

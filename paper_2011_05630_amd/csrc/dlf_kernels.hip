@@ -156,7 +156,7 @@ __device__ __forceinline__ void stage_region(const half_t* in, int n, int H, int
 // kh*kw*cin inputs of output pixel p in (kh, kw, ci) order, zero padded to kfill halfs, so that the
 // convolution becomes a 1x1 convolution over kfill channels: K = 27 -> 32 for a 3x3 filter on RGB
 // instead of 9 taps x 32 padded channels.
-__device__ __forceinline__ void stage_im2col(const half_t* in, int n, int H, int W, int C, int oy0,
+__device__ __attribute__((noinline)) void stage_im2col(const half_t* in, int n, int H, int W, int C, int oy0,
                                              int ox0, int rh, int rw, int kh, int kw, int stride,
                                              int pad, int kfill, int cs, half_t* dst)
 {
@@ -178,6 +178,51 @@ __device__ __forceinline__ void stage_im2col(const half_t* in, int n, int H, int
         }
         if (r == kh - 1)
             for (int j = kh * rowlen; j < kfill; ++j) dst[pix * cs + j] = (half_t)0;
+    }
+}
+
+// Staging for a convolution on a narrow input (cin <= 4) with an even stride: the input patch goes
+// to LDS as 4-channel pixels [ih][iw][4] (missing channels and pixels outside the image zero).
+// The convolution stage then treats a filter row as one tap over round_up(4 * kw, 32) "channels":
+// the 16-byte reads of a tap start at a pixel and run on over its right-hand neighbours, which are
+// exactly the filter columns; the columns beyond kw meet zero weights (so the 32 halfs behind the
+// last pixel only have to be finite: they are zeroed here).  No gather, K = kh * 32 per 7x7 row
+// set instead of kh * kw * cin copies per output pixel.
+__device__ __attribute__((noinline)) void stage_rowfold(const half_t* in, int n, int H, int W, int C, int iy0,
+                                              int ix0, int ih, int iw, half_t* dst)
+{
+    const int total = ih * iw;
+    const unsigned iw_m = div_magic(iw);
+    constexpr int U = 4;
+    for (int v0 = threadIdx.x; v0 < total; v0 += DLF_WG_THREADS * U) {
+        h4 val[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int v = v0 + u * DLF_WG_THREADS;
+            h4 px = {0, 0, 0, 0};
+            if (v < total) {
+                const int py = div_by(v, iw_m), pxx = v - py * iw;
+                const int gy = iy0 + py, gx = ix0 + pxx;
+                if (gy >= 0 && gy < H && gx >= 0 && gx < W) {
+                    const half_t* p = in + (unsigned)(((n * H + gy) * W + gx) * C);
+                    const half_t c0 = p[0];
+                    const half_t c1 = C > 1 ? p[1] : (half_t)0;
+                    const half_t c2 = C > 2 ? p[2] : (half_t)0;
+                    const half_t c3 = C > 3 ? p[3] : (half_t)0;
+                    px = h4{c0, c1, c2, c3};
+                }
+            }
+            val[u] = px;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int v = v0 + u * DLF_WG_THREADS;
+            if (v < total) *(h4*)(dst + v * 4) = val[u];
+        }
+    }
+    if (threadIdx.x < 4) {
+        const h8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+        *(h8*)(dst + total * 4 + threadIdx.x * 8) = z;
     }
 }
 
@@ -749,7 +794,10 @@ __global__ __launch_bounds__(DLF_WG_THREADS, MINW) void k_group(const DlfGroupAr
                 cend = min(s0.cin, c0 + a.slice_c);
                 cfill = (cend - c0 + 7) & ~7;
             }
-            if (s0.kind == DLF_ST_CONV && s0.im2col)
+            if (s0.kind == DLF_ST_CONV && s0.im2col == 2)
+                stage_rowfold((const half_t*)a.in, n, a.in_h, a.in_w, a.in_c, ty0 * a.iy_mul + a.iy_off,
+                              tx0 * a.ix_mul + a.ix_off, s0.ih, s0.iw, lds + s0.in_off);
+            else if (s0.kind == DLF_ST_CONV && s0.im2col)
                 stage_im2col((const half_t*)a.in, n, a.in_h, a.in_w, a.in_c,
                              ty0 * s0.oy_mul + s0.oy_off, tx0 * s0.ox_mul + s0.ox_off, s0.rh, s0.rw,
                              s0.im_kh, s0.im_kw, s0.im_stride, s0.im_pad, s0.cin_pad, s0.in_cs,

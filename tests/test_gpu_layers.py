@@ -81,6 +81,35 @@ def test_conv_kernel_stride_pad(k, stride, pad, cin, cout, hw):
     compare(got, ref, "conv k%d s%d p%d" % (k, stride, pad))
 
 
+@pytest.mark.parametrize("k,stride,pad,cin,cout,hw", [
+    (3, 2, 1, 3, 32, 33), (7, 2, 3, 3, 64, 61), (5, 2, 2, 4, 16, 30), (3, 2, 1, 1, 8, 21),
+    (11, 4, 2, 3, 64, 67), (3, 4, 0, 2, 32, 40), (7, 2, 3, 3, 64, 224)])
+def test_narrow_input_even_stride(k, stride, pad, cin, cout, hw):
+    """cin <= 4 with an even stride: filter columns folded into the channel dimension."""
+    announce("narrow conv", k, stride, pad, cin, cout, hw)
+    net = _mk([nets.conv(cin, cout, k, stride, pad, "relu")], hw, hw + 5, cin, dist="normal")
+    got, ref, _ = _run(net, 2, **_manual(1, [0]))
+    compare(got, ref, "narrow conv k%d s%d cin%d" % (k, stride, cin))
+    for force in ((4, 8, 2, 1, 0, 0), (7, 14, 0, 1, 0, 0), (8, 16, 1, 1, 0, 0)):
+        got, ref, _ = _run(net, 2, force=force, **_manual(1, [0]))
+        compare(got, ref, "narrow conv k%d s%d cin%d force %s" % (k, stride, cin, force))
+
+
+def test_narrow_input_stems_fused():
+    announce("fused stems")
+    layers = [nets.conv(3, 64, 7, 2, 3, "relu"), nets.maxpool(64, 3, 2, 1)]
+    net = _mk(layers, 99, 83, 3, dist="normal")
+    got, ref, g = _run(net, 2, **_manual(2, [1]))
+    assert len(g) == 1
+    compare(got, ref, "7x7 s2 stem + 3x3 s2 pool")
+    layers = [nets.conv(3, 32, 3, 2, 1, "relu6"), nets.dwconv(32, 3, 1, "relu6"),
+              nets.conv(32, 64, 1, 1, 0, "relu6"), nets.dwconv(64, 3, 2, "relu6")]
+    net = _mk(layers, 64, 72, 3, dist="normal")
+    got, ref, g = _run(net, 2, **_manual(4, [3]))
+    assert len(g) == 1
+    compare(got, ref, "3x3 s2 stem + dw + pw + dw s2")
+
+
 @pytest.mark.parametrize("slices", [(8, 8, 0, 4, 64, 1), (8, 8, 1, 2, 128, 1), (7, 7, 0, 2, 128, 1),
                                     (8, 8, 2, 8, 32, 1), (8, 8, 1, 4, 64, 1, 64)])
 def test_conv_output_channel_slices(slices):
