@@ -80,6 +80,8 @@ def group_accounting(net, batch, session):
         cfg = B.dlf_plan_group_config(session.plan, g)
         if cfg["kind"] == 1:
             kname = "k_fc"
+        elif cfg["kind"] == 3:
+            kname = "k_pw"
         elif cfg["kind"] == 2:
             kname = "k_gap"
         else:

@@ -136,7 +136,8 @@ dlf_status dlf_run_group(const dlf_plan_t* plan, int32_t g, const void* in_dev, 
  * never materialised (it lives only on-chip) or is the network output. */
 const void* dlf_plan_layer_output(const dlf_plan_t* plan, int32_t layer);
 
-/* Kernel configuration chosen for group g: kind (0 fused-group kernel, 1 FC, 2 global avgpool),
+/* Kernel configuration chosen for group g: kind (0 fused-group kernel, 1 FC, 2 global avgpool,
+ * 3 pointwise-convolution kernel: a single 1x1 layer run barrier-free, one wave per 64x64 item),
  * register-tile variant (per-wave accumulator tile, output channels x pixels: 0 = 64x64,
  * 1 = 32x128, 2 = 32x64, 3 = 32x64 built for two workgroups per CU), channel slices, channels
  * per slice, whether stage 0 streams its input, LDS bytes per workgroup.  Any out pointer may be
@@ -153,6 +154,12 @@ dlf_status dlf_plan_group_io(const dlf_plan_t* plan, int32_t g, int32_t* in_laye
  * Process-wide, not thread-safe. */
 void dlf_debug_force_config(int32_t th, int32_t tw, int32_t variant, int32_t nslices,
                             int32_t slice_c, int32_t stream0, int32_t kc);
+
+/* Testing hook: how single 1x1 convolutions choose between the fused-group kernel and the
+ * pointwise kernel: 0 = by modelled cost (default), 1 = pointwise wherever it applies, 2 = never,
+ * 3 / 4 = pointwise wherever it applies with 64x64 / 32x32 work items.
+ * Process-wide, not thread-safe. */
+void dlf_debug_pointwise_mode(int32_t mode);
 
 const char* dlf_status_string(dlf_status s);
 const char* dlf_last_error(void);

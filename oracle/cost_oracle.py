@@ -34,6 +34,12 @@ C_STORE = 1600
 MFMA_CYCLES = 32
 FC_BYTES_PER_CYCLE = 900
 GAP_BYTES_PER_CYCLE = 1000
+PW_SHAPES = ((2, 2, 4, 8), (1, 1, 8, 16))   # FC, FP, ring depth, waves per CU
+C_PW_ITEM = 3000
+C_PW_LAT = 2000
+C_PW_EPI = 400
+C_PW_RES = 1000
+PW_HBM_BYTES_PER_CYCLE = 2400
 
 WG_THREADS = 512
 WAVES = 8
@@ -373,6 +379,37 @@ def candidates(ni, specs):
                             sc *= 2
 
 
+def pw_cost(ni, i, batch, budget):
+    """Cost of a single 1x1 convolution on the barrier-free pointwise kernel, or None if it does
+    not apply (needs 1x1, no padding, cin % 32 == 0, cout % 8 == 0)."""
+    L = ni.layers[i]
+    if L["op"] != "conv" or L["kh"] != 1 or L["kw"] != 1 or L["pad"] != 0:
+        return None
+    if L["cin"] % 32 or L["cout"] % 8:
+        return None
+    ih, iw, ic = ni.ish[i]
+    oh, ow, oc = ni.osh[i]
+    if batch * ih * iw * ic >= 1 << 31 or batch * oh * ow * oc >= 1 << 31:
+        return None
+    m = batch * oh * ow
+    has_res = 1 if L["residual_from"] >= 0 else 0
+    nsteps = ni.nsteps[i]
+    nbytes = m * L["cin"] * 2 + m * L["cout"] * 2 * (1 + has_res) + ni.ncb[i] * nsteps * 1024
+    mem = nbytes // min(PW_HBM_BYTES_PER_CYCLE, budget * CU_BYTES_PER_CYCLE)
+    best = None
+    for fc, fp, depth, w in PW_SHAPES:
+        items = cdiv(m, 32 * fp) * cdiv(ni.ncb[i], fc)
+        items_cu = cdiv(items, budget)
+        vmem = items_cu * nsteps * (fc + fp) * 16
+        step = max(fc * fp * MFMA_CYCLES * (w // 4), C_PW_LAT // depth)
+        item = C_PW_ITEM + nsteps * step + fc * fp * C_PW_EPI + has_res * C_PW_RES
+        compute = max(vmem, cdiv(items_cu, w) * item)
+        c = (C_LAUNCH + max(compute, mem)) * PS_PER_CYCLE
+        if best is None or c < best:
+            best = c
+    return best
+
+
 def group_cost(net, batch, first, last, budget, max_lds=LDS_PER_CU, ni=None):
     """Cost in picoseconds of running layers [first, last] as one group on `budget` CUs, or None."""
     ni = ni or NetInfo(net)
@@ -399,6 +436,10 @@ def group_cost(net, batch, first, last, budget, max_lds=LDS_PER_CU, ni=None):
         c = tiling_cost_ps(b, budget, variant)
         if best is None or c < best:
             best = c
+    if first == last:
+        pc = pw_cost(ni, first, batch, budget)
+        if pc is not None and (best is None or pc < best):
+            best = pc
     return best
 
 

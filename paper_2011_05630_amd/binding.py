@@ -54,6 +54,10 @@ def lib():
     if not os.path.exists(LIB_PATH):
         raise RuntimeError("libdlf.so is not built: run `python -m paper_2011_05630_amd.build` "
                            "(or __graft_entry__.build()) first")
+    # PyTorch (the caller's source of device buffers and streams) ships its own HIP runtime.  It
+    # has to be in the process before libdlf.so is, so that the library binds to that same runtime:
+    # two HIP runtimes in one process cannot both open the device.
+    import torch  # noqa: F401
     L = ctypes.CDLL(LIB_PATH)
     vp, i32, u64p, i32p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_uint64), \
         ctypes.POINTER(ctypes.c_int32)
@@ -94,6 +98,8 @@ def lib():
     L.dlf_cost_model_version.restype = i32
     L.dlf_debug_force_config.argtypes = [i32, i32, i32, i32, i32, i32, i32]
     L.dlf_debug_force_config.restype = None
+    L.dlf_debug_pointwise_mode.argtypes = [i32]
+    L.dlf_debug_pointwise_mode.restype = None
     L.dlf_plan_group_config.argtypes = [vp, i32, i32p, i32p, i32p, i32p, i32p, i32p]
     L.dlf_plan_group_config.restype = i32
     L.dlf_run_profiled.argtypes = [vp, vp, vp, vp, i32, ctypes.POINTER(ctypes.c_float)]
@@ -259,6 +265,12 @@ def dlf_plan_layer_output(plan, layer):
 
 def dlf_cost_model_version():
     return lib().dlf_cost_model_version()
+
+
+def dlf_debug_pointwise_mode(mode=0):
+    """Testing hook: 0 = pointwise kernel chosen by modelled cost, 1 = wherever it applies, 2 = never,
+    3 / 4 = wherever it applies with 64x64 / 32x32 work items."""
+    lib().dlf_debug_pointwise_mode(mode)
 
 
 def dlf_debug_force_config(th=0, tw=0, variant=0, nslices=1, slice_c=0, stream0=0, kc=0):

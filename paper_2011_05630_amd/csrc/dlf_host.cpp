@@ -147,7 +147,7 @@ dlf_status pack_and_upload(Layer& L)
 // Fusion groups
 // ------------------------------------------------------------------------------------------
 
-enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2 };
+enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3 };
 
 struct TileCfg {
     int th, tw;      // tile of the group's final output tensor
@@ -169,6 +169,7 @@ struct GroupPlan {
     DlfGroupArgs ga;
     DlfFcArgs fa;
     DlfGapArgs pa;
+    DlfPwArgs wa;
 };
 
 const int VAR_FC[DLF_NUM_VARIANTS] = {2, 1, 1, 1};
@@ -198,6 +199,18 @@ const int64_t C_STORE = 1600;
 const int64_t MFMA_CYCLES = 32;             // one 32x32x16 MFMA on one SIMD
 const int64_t FC_BYTES_PER_CYCLE = 900;     // weight streaming rate of the FC kernel
 const int64_t GAP_BYTES_PER_CYCLE = 1000;
+// pointwise kernel, per item shape: register tile (FC x FP blocks of 32), operand ring depth,
+// independent waves per CU
+const int PW_SHAPES = 2;
+const int PW_FC[PW_SHAPES] = {2, 1};
+const int PW_FP[PW_SHAPES] = {2, 1};
+const int PW_DEPTH[PW_SHAPES] = {4, 8};
+const int PW_WAVES_PER_CU[PW_SHAPES] = {8, 16};
+const int64_t C_PW_ITEM = 3000;             // address setup, first operand round trip
+const int64_t C_PW_LAT = 2000;              // memory round trip a ring slot waits for
+const int64_t C_PW_EPI = 400;               // per 32x32 block: transpose through LDS, stores
+const int64_t C_PW_RES = 1000;              // residual loads
+const int64_t PW_HBM_BYTES_PER_CYCLE = 2400;
 
 struct StageSpec {   // one stage, before tiling
     int layer;
@@ -582,6 +595,50 @@ bool choose_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
     return found;
 }
 
+// Testing hook: 0 = the pointwise kernel competes with the fused-group kernel on modelled cost,
+// 1 = always where it applies, 2 = never, 3 / 4 = always, with item shape 0 / 1.
+int g_pw_mode = 0;
+
+// A convolution the pointwise kernel can run: 1x1, no padding, whole 32-channel K chunks.
+bool pw_eligible(const Layer& L, int batch)
+{
+    const dlf_layer_desc& d = L.d;
+    if (d.op != DLF_CONV || d.kh != 1 || d.kw != 1 || d.pad != 0) return false;
+    if ((d.cin % 32) != 0 || (d.cout % 8) != 0) return false;
+    if ((int64_t)batch * L.in_h * L.in_w * L.in_c >= (int64_t)1 << 31) return false;
+    if ((int64_t)batch * L.out_h * L.out_w * L.out_c >= (int64_t)1 << 31) return false;
+    return true;
+}
+
+uint64_t pw_shape_cost_ps(const Layer& L, int batch, int budget, int shape)
+{
+    const int64_t FCs = PW_FC[shape], FPs = PW_FP[shape], W = PW_WAVES_PER_CU[shape];
+    const int64_t m = (int64_t)batch * L.out_h * L.out_w;
+    const int64_t items = ((m + 32 * FPs - 1) / (32 * FPs)) * ((L.ncb + FCs - 1) / FCs);
+    const int64_t items_cu = (items + budget - 1) / budget;
+    const int64_t has_res = L.d.residual_from >= 0 ? 1 : 0;
+    // (FC + FP) KiB of operands per K step through the CU's 64-byte-per-cycle vector memory path
+    const int64_t vmem = items_cu * L.nsteps * (FCs + FPs) * 16;
+    const int64_t step = std::max<int64_t>(FCs * FPs * MFMA_CYCLES * (W / 4), C_PW_LAT / PW_DEPTH[shape]);
+    const int64_t item = C_PW_ITEM + L.nsteps * step + FCs * FPs * C_PW_EPI + has_res * C_PW_RES;
+    const int64_t compute = std::max(vmem, ((items_cu + W - 1) / W) * item);
+    const int64_t bytes = m * L.d.cin * 2 + m * L.d.cout * 2 * (1 + has_res) + (int64_t)L.ncb * L.nsteps * 1024;
+    const int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
+    return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
+}
+
+// Cheaper of the item shapes (ties: the larger tile).
+uint64_t pw_cost_ps(const Layer& L, int batch, int budget, int& shape)
+{
+    uint64_t best = 0;
+    shape = 0;
+    for (int sh = 0; sh < PW_SHAPES; ++sh) {
+        const uint64_t c = pw_shape_cost_ps(L, batch, budget, sh);
+        if (sh == 0 || c < best) { best = c; shape = sh; }
+    }
+    return best;
+}
+
 dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int budget, int max_lds,
                       GroupPlan& g)
 {
@@ -620,8 +677,39 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
     }
     Built b;
     TileCfg tc;
-    uint64_t cost;
-    if (!choose_group(net, specs, batch, budget, max_lds, b, tc, cost))
+    uint64_t cost = 0;
+    const bool tiled = choose_group(net, specs, batch, budget, max_lds, b, tc, cost);
+    const bool pw_ok = first == last && pw_eligible(L0, batch) && g_pw_mode != 2 &&
+                       (g_force.th <= 0 || g_pw_mode == 1 || g_pw_mode >= 3);
+    if (pw_ok) {
+        int shape = 0;
+        uint64_t pc = pw_cost_ps(L0, batch, budget, shape);
+        if (g_pw_mode >= 3) {
+            shape = g_pw_mode - 3;
+            pc = pw_shape_cost_ps(L0, batch, budget, shape);
+        }
+        if (!tiled || g_pw_mode == 1 || g_pw_mode >= 3 || pc < cost) {
+            DlfPwArgs& wa = g.wa;
+            memset(&wa, 0, sizeof wa);
+            wa.w = L0.d_w; wa.bias = L0.d_bias;
+            wa.m = batch * L0.out_h * L0.out_w;
+            wa.cin = L0.d.cin; wa.cout = L0.d.cout; wa.ncb = L0.ncb; wa.nsteps = L0.nsteps;
+            wa.act = L0.d.act; wa.stride = L0.d.stride;
+            wa.in_h = L0.in_h; wa.in_w = L0.in_w; wa.out_h = L0.out_h; wa.out_w = L0.out_w;
+            wa.n_pg = ceil_div(wa.m, 32 * PW_FP[shape]); wa.n_cg = ceil_div(L0.ncb, PW_FC[shape]);
+            wa.nitems = wa.n_pg * wa.n_cg;
+            g.kind = GK_PW;
+            g.cost = pc;
+            g.variant = shape;
+            g.occ = PW_WAVES_PER_CU[shape] / DLF_PW_WAVES;
+            g.grid = std::min(budget * g.occ, ceil_div(wa.nitems, DLF_PW_WAVES));
+            g.th = 1; g.tw = 32 * PW_FP[shape];
+            g.lds_bytes = DLF_PW_WAVES * 32 * PW_FP[shape] * (32 * PW_FC[shape] + 8) * 2;
+            if (L0.d.residual_from >= 0) { g.res_layer = L0.d.residual_from; g.res_stage = 0; }
+            return DLF_OK;
+        }
+    }
+    if (!tiled)
         return fail(DLF_ERR_INFEASIBLE, "layers [%d,%d] do not fit on-chip memory as one group", first, last);
     g.ga = b.ga;
     g.variant = tc.variant;
@@ -1063,6 +1151,8 @@ dlf_status dlf_plan_group_io(const dlf_plan_t* plan, int32_t g, int32_t* in_laye
     return DLF_OK;
 }
 
+void dlf_debug_pointwise_mode(int32_t mode) { g_pw_mode = (mode >= 0 && mode <= 4) ? mode : 0; }
+
 void dlf_debug_force_config(int32_t th, int32_t tw, int32_t variant, int32_t nslices, int32_t slice_c,
                             int32_t stream0, int32_t kc)
 {
@@ -1105,6 +1195,14 @@ static dlf_status launch_one(const dlf_plan_s* plan, const GroupPlan& G, const v
         DlfGapArgs pa = G.pa;
         pa.x = in; pa.y = out;
         e = dlf_launch_gap(&pa, stream);
+    } else if (G.kind == GK_PW) {
+        DlfPwArgs wa = G.wa;
+        wa.in = in; wa.out = out;
+        if (G.res_stage >= 0) {
+            if (!res) return fail(DLF_ERR_INVALID_ARG, "group [%d,%d] needs its residual operand", G.first, G.last);
+            wa.res = res;
+        }
+        e = dlf_launch_pw(&wa, G.variant, G.grid, stream);
     } else {
         DlfGroupArgs ga = G.ga;
         ga.in = in; ga.out = out;

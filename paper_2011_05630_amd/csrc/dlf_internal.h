@@ -75,6 +75,24 @@ struct DlfFcArgs {
     int32_t batch, k, cout, ncb, nsteps, act;
 };
 
+// Pointwise (1x1, pad 0) convolution run without tiles or barriers: every wave owns work items
+// of 64 x 64 (shape 0) or 32 x 32 (shape 1) output pixels x output channels, reads its activations
+// straight from HBM in the MFMA operand layout and writes its result through a wave-private LDS
+// transpose buffer.
+#define DLF_PW_WAVES 4               // waves per workgroup
+struct DlfPwArgs {
+    const void* in;       // [batch][in_h][in_w][cin] fp16
+    void* out;            // [batch][out_h][out_w][cout] fp16
+    const void* w;        // packed fragments (same stream as a CONV stage)
+    const float* bias;    // padded to ncb*32
+    const void* res;      // residual operand, output shape, or null
+    int32_t m;            // output pixels = batch * out_h * out_w
+    int32_t cin, cout, ncb, nsteps, act;
+    int32_t stride, in_h, in_w, out_h, out_w;
+    int32_t n_pg, n_cg;   // groups of 64 (32) pixels, groups of 64 (32) output channels
+    int32_t nitems;       // n_pg * n_cg
+};
+
 struct DlfGapArgs {
     const void* x;        // [batch][hw][c]
     void* y;              // [batch][c]
@@ -91,6 +109,7 @@ extern "C" {
 int dlf_launch_group(const DlfGroupArgs* a, int variant, int grid, int lds_bytes, void* stream);
 int dlf_launch_fc(const DlfFcArgs* a, void* stream);
 int dlf_launch_gap(const DlfGapArgs* a, void* stream);
+int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stream);
 int dlf_kernels_init(void);
 #ifdef __cplusplus
 }

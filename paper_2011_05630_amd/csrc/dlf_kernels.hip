@@ -835,6 +835,170 @@ __global__ __launch_bounds__(DLF_WG_THREADS, MINW) void k_group(const DlfGroupAr
     }
 }
 
+// Pointwise convolution, one wave per work item (32*FP output pixels x 32*FC output channels), no
+// workgroup barrier anywhere: the layers this serves are bound by HBM traffic or by the latency of
+// a long K loop, and eight to sixteen independent waves per CU, each with its own loads in
+// flight, hide the memory latency that a tile pipeline with barriers exposes phase by phase.
+//   B operand (activations): lane (pixel l%32, k half l/32) loads 16 bytes of its pixel's
+//     channels per K step directly from HBM/L2 -- the MFMA layout, no LDS staging;
+//   A operand (weights): packed fragments from L2, as in the fused-group kernel;
+//   both through D-deep register rings refilled right behind the MFMAs that used the slot; the
+//     first operands of the wave's next item are requested before the epilogue of the current one;
+//   result: fp16 into the wave's transpose buffer, read back 16 bytes per lane so that the
+//     stores (and the residual loads) cover whole runs of 64 * FC bytes.
+// Shapes: (2,2) with D = 4 for large layers (each operand byte feeds two MFMAs); (1,1) with D = 8
+// where the layer has too few 64 x 64 items to occupy the chip (small feature maps, long K).
+template <int FP>
+__device__ __forceinline__ void pw_item_setup(const DlfPwArgs& a, int item, int lane, const half_t* (&bp)[FP],
+                                              int& pg, int& cg)
+{
+    const int l32 = lane & 31, lhi = lane >> 5;
+    pg = item / a.n_cg;
+    cg = item - pg * a.n_cg;
+#pragma unroll
+    for (int p = 0; p < FP; ++p) {
+        int pix = (pg * FP + p) * 32 + l32;
+        pix = pix < a.m ? pix : a.m - 1;          // clamped lanes compute a result nobody stores
+        unsigned off;
+        if (a.stride == 1) {
+            off = (unsigned)pix * (unsigned)a.cin;
+        } else {
+            const int hw = a.out_h * a.out_w;
+            const int n = pix / hw, r = pix - n * hw;
+            const int oy = r / a.out_w, ox = r - oy * a.out_w;
+            off = (unsigned)(((n * a.in_h + oy * a.stride) * a.in_w + ox * a.stride) * a.cin);
+        }
+        bp[p] = (const half_t*)a.in + off + lhi * 8;
+    }
+}
+
+template <int FC, int FP, int D, int MINB>
+__global__ __launch_bounds__(DLF_PW_WAVES * 64, MINB) void k_pw(const DlfPwArgs a)
+{
+    constexpr int ROW = 32 * FC + 8;                 // halfs per pixel row of the transpose buffer
+    constexpr int LPP = 4 * FC;                      // lanes (16-byte vectors) per pixel
+    constexpr int NPASS = 2 * FC * FP;               // read-back passes of 64 vectors
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
+    half_t* tb = lds + wave * (32 * FP * ROW);
+    const half_t* resp = (const half_t*)a.res;
+    half_t* outp = (half_t*)a.out;
+    const int nwaves = gridDim.x * DLF_PW_WAVES;
+    const int nsteps = a.nsteps;
+    const int act_epi = resp != nullptr ? 0 : a.act;     // with a residual the activation comes after the add
+    const unsigned lo_e = act_lo(act_epi), hi_e = act_hi(act_epi);
+    const unsigned lo_r = act_lo(a.act), hi_r = act_hi(a.act);
+
+    int item = blockIdx.x * DLF_PW_WAVES + wave;
+    if (item >= a.nitems) return;
+    const half_t* bp[FP];
+    const h8* wp[FC];
+    int pg, cg;
+    h8 ar[D][FC], br[D][FP];
+    auto request_first = [&]() {
+        pw_item_setup<FP>(a, item, lane, bp, pg, cg);
+#pragma unroll
+        for (int f = 0; f < FC; ++f) {
+            const int cb = min(cg * FC + f, a.ncb - 1);
+            wp[f] = (const h8*)a.w + (size_t)cb * nsteps * 64 + lane;
+        }
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            if (j < nsteps) {
+#pragma unroll
+                for (int f = 0; f < FC; ++f) ar[j][f] = wp[f][j * 64];
+#pragma unroll
+                for (int p = 0; p < FP; ++p) br[j][p] = *(const h8*)(bp[p] + j * 16);
+            }
+        }
+    };
+    request_first();
+    for (;;) {
+        // the bias is needed only after the K loop: requested now, it arrives behind the ring
+        f4v bias[FC][4];
+#pragma unroll
+        for (int f = 0; f < FC; ++f) {
+            const int cb = min(cg * FC + f, a.ncb - 1);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) bias[f][q] = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
+        }
+        f16v acc[FC][FP];
+#pragma unroll
+        for (int f = 0; f < FC; ++f)
+#pragma unroll
+            for (int p = 0; p < FP; ++p)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[f][p][r] = 0.0f;
+        for (int s = 0; s < nsteps; s += D) {
+#pragma unroll
+            for (int j = 0; j < D; ++j) {
+                if (s + j < nsteps) {
+#pragma unroll
+                    for (int f = 0; f < FC; ++f)
+#pragma unroll
+                        for (int p = 0; p < FP; ++p)
+                            acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[j][f], br[j][p], acc[f][p], 0, 0, 0);
+                    if (s + j + D < nsteps) {       // never read activations beyond the pixel's channels
+#pragma unroll
+                        for (int f = 0; f < FC; ++f) ar[j][f] = wp[f][(s + j + D) * 64];
+#pragma unroll
+                        for (int p = 0; p < FP; ++p) br[j][p] = *(const h8*)(bp[p] + (s + j + D) * 16);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        const int cur_pg = pg, cur_cg = cg;
+        item += nwaves;
+        const bool more = item < a.nitems;
+        if (more) request_first();
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- result (+ bias) -> wave-private transpose buffer [pixel][channel] ----
+#pragma unroll
+        for (int p = 0; p < FP; ++p)
+#pragma unroll
+            for (int f = 0; f < FC; ++f)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    unsigned u0 = cvt_pk(acc[f][p][q * 4 + 0] + bias[f][q][0], acc[f][p][q * 4 + 1] + bias[f][q][1]);
+                    unsigned u1 = cvt_pk(acc[f][p][q * 4 + 2] + bias[f][q][2], acc[f][p][q * 4 + 3] + bias[f][q][3]);
+                    u0 = pk_min(pk_max(u0, lo_e), hi_e);
+                    u1 = pk_min(pk_max(u1, lo_e), hi_e);
+                    const u2v uu = {u0, u1};
+                    *(u2v*)(tb + (p * 32 + l32) * ROW + f * 32 + q * 8 + lhi * 4) = uu;
+                }
+        __builtin_amdgcn_wave_barrier();
+        // ---- 16 bytes per lane: LPP lanes cover the 32*FC channels of one pixel ----
+        const int part = lane % LPP;
+        const int c = cur_cg * (32 * FC) + part * 8;
+        u4v val[NPASS], rv[NPASS];
+        bool ok[NPASS];
+        unsigned go[NPASS];
+#pragma unroll
+        for (int i = 0; i < NPASS; ++i) {
+            const int px = i * (64 / LPP) + lane / LPP;
+            const int gpix = cur_pg * (32 * FP) + px;
+            ok[i] = gpix < a.m && c < a.cout;
+            go[i] = (unsigned)gpix * (unsigned)a.cout + (unsigned)c;
+            if (resp != nullptr && ok[i]) rv[i] = *(const u4v*)(resp + go[i]);
+            val[i] = *(const u4v*)(tb + px * ROW + part * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < NPASS; ++i) {
+            if (ok[i]) {
+                if (resp != nullptr) {
+                    val[i].x = pk_min(pk_max(pk_add(val[i].x, rv[i].x), lo_r), hi_r);
+                    val[i].y = pk_min(pk_max(pk_add(val[i].y, rv[i].y), lo_r), hi_r);
+                    val[i].z = pk_min(pk_max(pk_add(val[i].z, rv[i].z), lo_r), hi_r);
+                    val[i].w = pk_min(pk_max(pk_add(val[i].w, rv[i].w), lo_r), hi_r);
+                }
+                *(u4v*)(outp + go[i]) = val[i];
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (!more) break;
+    }
+}
+
 // Fully connected layer (Eq. 2 with M = batch): y[n][co] = act(bias[co] + sum_k x[n][k] w[co][k]).
 // One workgroup per 32 output channels; its 8 waves split K, each streaming its share of the
 // packed weight fragments from HBM exactly once; partial sums meet in LDS.
@@ -927,6 +1091,20 @@ extern "C" int dlf_launch_group(const DlfGroupArgs* a, int variant, int grid, in
 extern "C" int dlf_launch_fc(const DlfFcArgs* a, void* stream)
 {
     hipLaunchKernelGGL(k_fc, dim3(a->ncb), dim3(DLF_FC_WAVES * 64), 0, (hipStream_t)stream, *a);
+    return (int)hipGetLastError();
+}
+
+extern "C" int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stream)
+{
+    if (grid <= 0) return (int)hipErrorInvalidValue;
+    if (shape == 0)
+        hipLaunchKernelGGL((k_pw<2, 2, 4, 2>), dim3(grid), dim3(DLF_PW_WAVES * 64),
+                           (size_t)(DLF_PW_WAVES * 64 * (64 + 8) * 2), (hipStream_t)stream, *a);
+    else if (shape == 1)
+        hipLaunchKernelGGL((k_pw<1, 1, 8, 4>), dim3(grid), dim3(DLF_PW_WAVES * 64),
+                           (size_t)(DLF_PW_WAVES * 32 * (32 + 8) * 2), (hipStream_t)stream, *a);
+    else
+        return (int)hipErrorInvalidValue;
     return (int)hipGetLastError();
 }
 

@@ -119,6 +119,63 @@ def test_conv_output_channel_slices(slices):
     compare(got, ref, "conv slices %s" % (slices,))
 
 
+@pytest.mark.parametrize("cin,cout,hw,stride,act,batch", [
+    (64, 256, 28, 1, "relu", 2), (256, 64, 28, 1, "relu", 2), (32, 64, 33, 1, "relu6", 3),
+    (256, 512, 28, 2, "none", 2), (96, 40, 7, 1, "relu", 3), (64, 8, 9, 1, "relu", 1),
+    (1024, 256, 14, 1, "relu", 5), (128, 128, 15, 2, "relu6", 2), (32, 1000, 3, 1, "none", 7)])
+def test_pointwise_kernel(cin, cout, hw, stride, act, batch):
+    """1x1 convolutions on the barrier-free pointwise kernel (forced), ragged pixel and channel
+    counts included."""
+    announce("pointwise", cin, cout, hw, stride, act, batch)
+    from paper_2011_05630_amd import binding as B
+    net = _mk([nets.conv(cin, cout, 1, stride, 0, act)], hw, hw + 2, cin, dist="normal")
+    for mode in (3, 4):         # 64x64 and 32x32 work items
+        B.dlf_debug_pointwise_mode(mode)
+        try:
+            got, ref, g = _run(net, batch, **_manual(1, [0]))
+        finally:
+            B.dlf_debug_pointwise_mode(0)
+        compare(got, ref, "pointwise %d->%d s%d shape %d" % (cin, cout, stride, mode - 3))
+
+
+def test_pointwise_kernel_is_used_and_adds_residual():
+    announce("pointwise residual")
+    from oracle import oracle as o
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    layers = [nets.conv(64, 64, 3, 1, 1, "relu"), nets.conv(64, 256, 1, 1, 0, "relu"),
+              nets.conv(256, 64, 1, 1, 0, "relu"), nets.conv(64, 256, 1, 1, 0, "relu", residual_from=1)]
+    net = _mk(layers, 21, 19, 64, dist="normal")
+    x, ws, bs = gen.make_params(net, 3)
+    ref = o.run_net(net, x, ws, bs)
+    for mode in (1, 3, 4):
+        B.dlf_debug_pointwise_mode(mode)
+        try:
+            s = Session(net, 3, ws, bs, **_manual(4, [0, 1, 2, 3]))
+        finally:
+            B.dlf_debug_pointwise_mode(0)
+        try:
+            kinds = [B.dlf_plan_group_config(s.plan, i)["kind"] for i in range(4)]
+            got = s.run_numpy(x)
+        finally:
+            s.close()
+        assert kinds == [0, 3, 3, 3], kinds
+        compare(got, ref, "pointwise chain with residual, mode %d" % mode)
+    # never mode: same result from the fused-group kernel
+    B.dlf_debug_pointwise_mode(2)
+    try:
+        s = Session(net, 3, ws, bs, **_manual(4, [0, 1, 2, 3]))
+    finally:
+        B.dlf_debug_pointwise_mode(0)
+    try:
+        kinds = [B.dlf_plan_group_config(s.plan, i)["kind"] for i in range(4)]
+        got2 = s.run_numpy(x)
+    finally:
+        s.close()
+    assert kinds == [0, 0, 0, 0], kinds
+    compare(got2, ref, "same chain, fused-group kernel")
+
+
 @pytest.mark.parametrize("act", ["none", "relu", "relu6"])
 def test_activations_and_bias(act):
     announce("act", act)
