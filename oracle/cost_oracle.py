@@ -34,12 +34,10 @@ C_STORE = 1600
 MFMA_CYCLES = 32
 FC_BYTES_PER_CYCLE = 900
 GAP_BYTES_PER_CYCLE = 1000
-PW_SHAPES = ((2, 2, 4, 8), (1, 1, 8, 16))   # FC, FP, ring depth, waves per CU
-C_PW_ITEM = 3000
-C_PW_LAT = 2000
-C_PW_EPI = 400
+PW_SHAPES = ((2, 2, 8, 470), (1, 1, 16, 700))   # FC, FP, waves per CU, cycles per K step
+C_PW_ITEM = 2500
 C_PW_RES = 1000
-PW_HBM_BYTES_PER_CYCLE = 2400
+PW_HBM_BYTES_PER_CYCLE = 2000
 
 WG_THREADS = 512
 WAVES = 8
@@ -397,13 +395,11 @@ def pw_cost(ni, i, batch, budget):
     nbytes = m * L["cin"] * 2 + m * L["cout"] * 2 * (1 + has_res) + ni.ncb[i] * nsteps * 1024
     mem = nbytes // min(PW_HBM_BYTES_PER_CYCLE, budget * CU_BYTES_PER_CYCLE)
     best = None
-    for fc, fp, depth, w in PW_SHAPES:
+    for fc, fp, w, step in PW_SHAPES:
         items = cdiv(m, 32 * fp) * cdiv(ni.ncb[i], fc)
         items_cu = cdiv(items, budget)
-        vmem = items_cu * nsteps * (fc + fp) * 16
-        step = max(fc * fp * MFMA_CYCLES * (w // 4), C_PW_LAT // depth)
-        item = C_PW_ITEM + nsteps * step + fc * fp * C_PW_EPI + has_res * C_PW_RES
-        compute = max(vmem, cdiv(items_cu, w) * item)
+        item = C_PW_ITEM + nsteps * step + has_res * C_PW_RES
+        compute = cdiv(items_cu, w) * item
         c = (C_LAUNCH + max(compute, mem)) * PS_PER_CYCLE
         if best is None or c < best:
             best = c

@@ -204,13 +204,12 @@ const int64_t GAP_BYTES_PER_CYCLE = 1000;
 const int PW_SHAPES = 2;
 const int PW_FC[PW_SHAPES] = {2, 1};
 const int PW_FP[PW_SHAPES] = {2, 1};
-const int PW_DEPTH[PW_SHAPES] = {4, 8};
 const int PW_WAVES_PER_CU[PW_SHAPES] = {8, 16};
-const int64_t C_PW_ITEM = 3000;             // address setup, first operand round trip
-const int64_t C_PW_LAT = 2000;              // memory round trip a ring slot waits for
-const int64_t C_PW_EPI = 400;               // per 32x32 block: transpose through LDS, stores
+// fitted to per-launch HIP-event times of 1x1 layers of the ResNet-50 / MobileNet-v1 shapes
+const int64_t C_PW_ITEM = 2500;             // per work item: address setup, epilogue
+const int64_t C_PW_STEP[PW_SHAPES] = {470, 700};   // per K step of a latency-bound wave
 const int64_t C_PW_RES = 1000;              // residual loads
-const int64_t PW_HBM_BYTES_PER_CYCLE = 2400;
+const int64_t PW_HBM_BYTES_PER_CYCLE = 2000;
 
 struct StageSpec {   // one stage, before tiling
     int layer;
@@ -617,11 +616,8 @@ uint64_t pw_shape_cost_ps(const Layer& L, int batch, int budget, int shape)
     const int64_t items = ((m + 32 * FPs - 1) / (32 * FPs)) * ((L.ncb + FCs - 1) / FCs);
     const int64_t items_cu = (items + budget - 1) / budget;
     const int64_t has_res = L.d.residual_from >= 0 ? 1 : 0;
-    // (FC + FP) KiB of operands per K step through the CU's 64-byte-per-cycle vector memory path
-    const int64_t vmem = items_cu * L.nsteps * (FCs + FPs) * 16;
-    const int64_t step = std::max<int64_t>(FCs * FPs * MFMA_CYCLES * (W / 4), C_PW_LAT / PW_DEPTH[shape]);
-    const int64_t item = C_PW_ITEM + L.nsteps * step + FCs * FPs * C_PW_EPI + has_res * C_PW_RES;
-    const int64_t compute = std::max(vmem, ((items_cu + W - 1) / W) * item);
+    const int64_t item = C_PW_ITEM + L.nsteps * C_PW_STEP[shape] + has_res * C_PW_RES;
+    const int64_t compute = ((items_cu + W - 1) / W) * item;
     const int64_t bytes = m * L.d.cin * 2 + m * L.d.cout * 2 * (1 + has_res) + (int64_t)L.ncb * L.nsteps * 1024;
     const int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
     return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
