@@ -24,7 +24,8 @@ C_LAT = 5000
 C_STAGE_VEC = 120
 C_IM2COL = 150
 C_ROWFOLD = 400
-C_ROUND = 3800
+C_ROUND = 1500
+C_ROUND_VEC = 300
 C_BARRIER = 500
 C_EPI = 900
 C_VALU = 100
@@ -34,7 +35,7 @@ C_STORE = 1600
 MFMA_CYCLES = 32
 FC_BYTES_PER_CYCLE = 900
 GAP_BYTES_PER_CYCLE = 1000
-PW_SHAPES = ((2, 2, 8, 470), (1, 1, 16, 700))   # FC, FP, waves per CU, cycles per K step
+PW_SHAPES = ((2, 2, 8, 470, 64), (1, 1, 16, 300, 100))   # FC, FP, waves per CU, cycles per K step (alone, per wave sharing the CU)
 C_PW_ITEM = 2500
 C_PW_RES = 1000
 PW_HBM_BYTES_PER_CYCLE = 2000
@@ -299,7 +300,8 @@ def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc
             mma = cdiv(nitems, 4) * st["nsteps"] * FC * FP * MFMA_CYCLES * 2
             if streaming:
                 nrounds = st["cin_pad"] // st["kc"]
-                mma = max(mma, nrounds * C_ROUND) + nrounds * C_BARRIER
+                vecs = cdiv(st["ih"] * st["iw"] * (st["kc"] // 8), LOAD_THREADS)
+                mma = max(mma, nrounds * (C_ROUND + vecs * C_ROUND_VEC)) + nrounds * C_BARRIER
             cyc += mma + cdiv(nitems, mma_waves) * FC * FP * C_EPI
             l2 += nitems * FC * st["nsteps"] * 1024
         else:
@@ -395,9 +397,10 @@ def pw_cost(ni, i, batch, budget):
     nbytes = m * L["cin"] * 2 + m * L["cout"] * 2 * (1 + has_res) + ni.ncb[i] * nsteps * 1024
     mem = nbytes // min(PW_HBM_BYTES_PER_CYCLE, budget * CU_BYTES_PER_CYCLE)
     best = None
-    for fc, fp, w, step in PW_SHAPES:
+    for fc, fp, w, step0, step_wave in PW_SHAPES:
         items = cdiv(m, 32 * fp) * cdiv(ni.ncb[i], fc)
         items_cu = cdiv(items, budget)
+        step = max(step0, min(items_cu, w) * step_wave)
         item = C_PW_ITEM + nsteps * step + has_res * C_PW_RES
         compute = cdiv(items_cu, w) * item
         c = (C_LAUNCH + max(compute, mem)) * PS_PER_CYCLE

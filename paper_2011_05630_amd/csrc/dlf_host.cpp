@@ -189,7 +189,8 @@ const int64_t C_LAT = 5000;                 // one exposed HBM/L2 round trip
 const int64_t C_STAGE_VEC = 120;             // per 512 staged 16-byte vectors
 const int64_t C_IM2COL = 150;                // per gathered element per 512 (pixel, row) pairs
 const int64_t C_ROWFOLD = 400;               // per 512 staged narrow pixels (3 element loads, one 8-byte LDS write)
-const int64_t C_ROUND = 3800;               // lower bound of a streaming round (loader latency)
+const int64_t C_ROUND = 1500;               // lower bound of a streaming round: loader latency ...
+const int64_t C_ROUND_VEC = 300;            // ... plus this per 16-byte vector a data-movement thread brings in
 const int64_t C_BARRIER = 500;
 const int64_t C_EPI = 900;                  // epilogue per 32x32 accumulator block
 const int64_t C_VALU = 100;                  // per tap per 512 (pixel, 8 channels) items
@@ -207,7 +208,8 @@ const int PW_FP[PW_SHAPES] = {2, 1};
 const int PW_WAVES_PER_CU[PW_SHAPES] = {8, 16};
 // fitted to per-launch HIP-event times of 1x1 layers of the ResNet-50 / MobileNet-v1 shapes
 const int64_t C_PW_ITEM = 2500;             // per work item: address setup, epilogue
-const int64_t C_PW_STEP[PW_SHAPES] = {470, 700};   // per K step of a latency-bound wave
+const int64_t C_PW_STEP[PW_SHAPES] = {470, 300};   // per K step of a latency-bound wave ...
+const int64_t C_PW_STEP_WAVE[PW_SHAPES] = {64, 100};   // ... or of a CU whose waves share its vector-memory path
 const int64_t C_PW_RES = 1000;              // residual loads
 const int64_t PW_HBM_BYTES_PER_CYCLE = 2000;
 
@@ -470,7 +472,8 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
             int64_t mma = (int64_t)ceil_div(nitems, 4) * st.nsteps * FCv * FPv * MFMA_CYCLES * 2;
             if (streaming) {
                 const int64_t nrounds = st.cin_pad / st.kc;
-                mma = std::max(mma, nrounds * C_ROUND) + nrounds * C_BARRIER;
+                const int64_t vecs = ceil_div(st.ih * st.iw * (st.kc / 8), DLF_LOAD_THREADS);
+                mma = std::max(mma, nrounds * (C_ROUND + vecs * C_ROUND_VEC)) + nrounds * C_BARRIER;
             }
             cyc += mma + (int64_t)ceil_div(nitems, mma_waves) * FCv * FPv * C_EPI;
             l2 += (int64_t)nitems * FCv * st.nsteps * 1024;
@@ -616,7 +619,8 @@ uint64_t pw_shape_cost_ps(const Layer& L, int batch, int budget, int shape)
     const int64_t items = ((m + 32 * FPs - 1) / (32 * FPs)) * ((L.ncb + FCs - 1) / FCs);
     const int64_t items_cu = (items + budget - 1) / budget;
     const int64_t has_res = L.d.residual_from >= 0 ? 1 : 0;
-    const int64_t item = C_PW_ITEM + L.nsteps * C_PW_STEP[shape] + has_res * C_PW_RES;
+    const int64_t step = std::max(C_PW_STEP[shape], std::min(items_cu, W) * C_PW_STEP_WAVE[shape]);
+    const int64_t item = C_PW_ITEM + L.nsteps * step + has_res * C_PW_RES;
     const int64_t compute = ((items_cu + W - 1) / W) * item;
     const int64_t bytes = m * L.d.cin * 2 + m * L.d.cout * 2 * (1 + has_res) + (int64_t)L.ncb * L.nsteps * 1024;
     const int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
