@@ -103,6 +103,9 @@ def main():
     ap.add_argument("--budget", type=int, default=256, help="budget of every group of --plan unfused")
     ap.add_argument("--table", action="store_true", help="per-group table on stderr")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--calib-copy", type=int, default=0,
+                    help="run this many plain 256 MiB device copies first (reference dispatches of "
+                         "known size for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported" % args.gpus,
@@ -135,6 +138,13 @@ def main():
     out = torch.empty(s.out_shape, dtype=torch.float16, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
 
+    if args.calib_copy > 0:
+        src = torch.ones(128 * 1024 * 1024, dtype=torch.float16, device="cuda")     # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(args.calib_copy):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         B.dlf_run(s.plan, xt.data_ptr(), out.data_ptr(), stream)
     torch.cuda.synchronize()

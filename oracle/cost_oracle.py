@@ -33,7 +33,7 @@ C_STAGE = 1200
 C_STORE_VEC = 80
 C_STORE = 1600
 MFMA_CYCLES = 32
-FC_BYTES_PER_CYCLE = 900
+FC_BYTES_PER_CYCLE = 1400
 GAP_BYTES_PER_CYCLE = 1000
 PW_SHAPES = ((2, 2, 8, 470, 64), (1, 1, 16, 300, 100))   # FC, FP, waves per CU, cycles per K step (alone, per wave sharing the CU)
 C_PW_ITEM = 2500

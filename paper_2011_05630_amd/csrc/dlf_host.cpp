@@ -198,7 +198,7 @@ const int64_t C_STAGE = 1200;                // per VALU stage
 const int64_t C_STORE_VEC = 80;             // per 512 stored 16-byte vectors
 const int64_t C_STORE = 1600;
 const int64_t MFMA_CYCLES = 32;             // one 32x32x16 MFMA on one SIMD
-const int64_t FC_BYTES_PER_CYCLE = 900;     // weight streaming rate of the FC kernel
+const int64_t FC_BYTES_PER_CYCLE = 1400;    // weight streaming rate of the FC kernel
 const int64_t GAP_BYTES_PER_CYCLE = 1000;
 // pointwise kernel, per item shape: register tile (FC x FP blocks of 32), operand ring depth,
 // independent waves per CU

@@ -1000,8 +1000,8 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, MINB) void k_pw(const DlfPwArgs 
 }
 
 // Fully connected layer (Eq. 2 with M = batch): y[n][co] = act(bias[co] + sum_k x[n][k] w[co][k]).
-// One workgroup per 32 output channels; its 8 waves split K, each streaming its share of the
-// packed weight fragments from HBM exactly once; partial sums meet in LDS.
+// One workgroup per 32 output channels; its 8 waves split K, each streaming a contiguous share
+// of the packed weight fragments from HBM exactly once; partial sums meet in LDS.
 #define DLF_FC_WAVES 8
 __global__ __launch_bounds__(DLF_FC_WAVES * 64) void k_fc(const DlfFcArgs a)
 {
@@ -1018,13 +1018,37 @@ __global__ __launch_bounds__(DLF_FC_WAVES * 64) void k_fc(const DlfFcArgs a)
         f16v acc;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
-#pragma unroll 4
-        for (int t = wave; t < a.nsteps; t += DLF_FC_WAVES) {
-            const h8 av = wbase[(size_t)t * 64];
-            h8 bv = {0, 0, 0, 0, 0, 0, 0, 0};
-            const int k = t * 16 + lhi * 8;
-            if (k + 8 <= a.k) bv = *(const h8*)(xr + t * 16);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv, acc, 0, 0, 0);
+        // each wave streams a contiguous eighth of the K steps through an 8-deep operand ring:
+        // 8 KiB of weights in flight per wave, refilled right behind the MFMA that used the slot
+        const int per = (a.nsteps + DLF_FC_WAVES - 1) / DLF_FC_WAVES;
+        const int t0 = wave * per, t1 = min(a.nsteps, t0 + per);
+        h8 av[8], bv[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int t = t0 + j;
+            if (t < t1) {
+                av[j] = wbase[(size_t)t * 64];
+                h8 b = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (t * 16 + lhi * 8 + 8 <= a.k) b = *(const h8*)(xr + t * 16);
+                bv[j] = b;
+            }
+        }
+        for (int tb = t0; tb < t1; tb += 8) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int t = tb + j;
+                if (t < t1) {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[j], bv[j], acc, 0, 0, 0);
+                    const int tn = t + 8;
+                    if (tn < t1) {
+                        av[j] = wbase[(size_t)tn * 64];
+                        h8 b = {0, 0, 0, 0, 0, 0, 0, 0};
+                        if (tn * 16 + lhi * 8 + 8 <= a.k) b = *(const h8*)(xr + tn * 16);
+                        bv[j] = b;
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
         }
 #pragma unroll
         for (int i = 0; i < 16; ++i) red[wave][i][lane] = acc[i];
