@@ -1055,8 +1055,8 @@ dlf_status dlf_plan(const dlf_net_t* net, int32_t batch, const dlf_tuner_opts* o
     } else if (o.mode == DLF_TUNER_GREEDY) {
         const double alpha = (o.alpha == 0 && o.beta == 0) ? 0.316 : o.alpha;
         const double beta = (o.alpha == 0 && o.beta == 0) ? 0.659 : o.beta;
-        const double k = (o.mp_scale == 0 && o.mp_offset == 0) ? 16.0 : o.mp_scale;
-        const double b0 = (o.mp_scale == 0 && o.mp_offset == 0) ? -256.0 : o.mp_offset;
+        const double k = (o.mp_scale == 0 && o.mp_offset == 0) ? 64.0 : o.mp_scale;
+        const double b0 = (o.mp_scale == 0 && o.mp_offset == 0) ? -1056.0 : o.mp_offset;
         const double crit = o.opcount_critical > 0 ? o.opcount_critical : 2.0e7;
         std::vector<int> part, mps;
         algorithm1(*net, batch, crit, alpha, beta, k, b0, budgets, part, mps);

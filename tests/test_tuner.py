@@ -269,6 +269,20 @@ def test_greedy_mode_follows_algorithm1(name, batch, crit, k, b):
     assert got == want
 
 
+def test_greedy_defaults_are_the_documented_ones():
+    net = nets.resnet50()
+    h = _handle(net)
+    p = B.dlf_plan(h, 32, mode=B.TUNER_GREEDY)
+    a = [(g["first"], g["last"], g["budget"]) for g in B.dlf_plan_groups(p)]
+    B.dlf_plan_destroy(p)
+    p = B.dlf_plan(h, 32, mode=B.TUNER_GREEDY, budgets=list(BUDGETS), opcount_critical=2.0e7,
+                   alpha=0.316, beta=0.659, mp_scale=64.0, mp_offset=-1056.0)
+    b = [(g["first"], g["last"], g["budget"]) for g in B.dlf_plan_groups(p)]
+    B.dlf_plan_destroy(p)
+    B.dlf_net_destroy(h)
+    assert a == b
+
+
 def test_manual_plan_and_workspace():
     net = nets.chain4(64)
     h = _handle(net)
