@@ -24,6 +24,27 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA
 RIDGE = MFMA_FP16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # FLOP per byte
 
+# HBM bytes per launch of a workload's main kernels, from two `rocprofv3 --pmc` runs of this file
+# (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch; `--calib-copy 3` adds plain 256 MiB device copies
+# whose readings give the scale factors: 2.000 for FETCH_SIZE, 1.000 for WRITE_SIZE on this chip).
+# Valid only for the kernel sources they were taken with: `csrc_sha1` is checked at run time and
+# `traffic` is reported as null when the sources have changed since.
+TRAFFIC = {
+    "csrc_sha1": "",
+    "bytes_per_launch": {},
+}
+
+
+def csrc_sha1():
+    import hashlib
+    h = hashlib.sha1()
+    d = os.path.join(ROOT, "paper_2011_05630_amd", "csrc")
+    for f in sorted(os.listdir(d)):
+        with open(os.path.join(d, f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
 VARIANT_NAME = {0: "k_group<2,2,2>", 1: "k_group<1,4,2>", 2: "k_group<1,2,2>", 3: "k_group<1,2,4>"}
 
 
@@ -184,7 +205,10 @@ def main():
         ach = d["bytes"] / d["launches"] / (avg_ms * 1e-3) / 1e9
         roof = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=ach / HBM_PEAK_GBS)
-    roof.update(traffic=None, kernel=dom, launches_per_step=d["launches"],
+    traffic = None
+    if TRAFFIC["csrc_sha1"] == csrc_sha1():
+        traffic = TRAFFIC["bytes_per_launch"].get("%s_b%d" % (net["name"], batch), {}).get(dom)
+    roof.update(traffic=traffic, kernel=dom, launches_per_step=d["launches"],
                 avg_launch_us=avg_ms * 1e3, flops_per_launch=d["flops"] / d["launches"],
                 bytes_per_launch=d["bytes"] / d["launches"],
                 share_of_step=d["ms"] / max(sum(gms), 1e-9))

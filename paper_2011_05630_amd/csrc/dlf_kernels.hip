@@ -913,14 +913,6 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, MINB) void k_pw(const DlfPwArgs 
     };
     request_first();
     for (;;) {
-        // the bias is needed only after the K loop: requested now, it arrives behind the ring
-        f4v bias[FC][4];
-#pragma unroll
-        for (int f = 0; f < FC; ++f) {
-            const int cb = min(cg * FC + f, a.ncb - 1);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) bias[f][q] = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
-        }
         f16v acc[FC][FP];
 #pragma unroll
         for (int f = 0; f < FC; ++f)
@@ -947,6 +939,14 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, MINB) void k_pw(const DlfPwArgs 
                 }
             }
         }
+        // bias first, then the next item's operands: the epilogue waits for the bias only
+        f4v bias[FC][4];
+#pragma unroll
+        for (int f = 0; f < FC; ++f) {
+            const int cb = min(cg * FC + f, a.ncb - 1);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) bias[f][q] = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
+        }
         const int cur_pg = pg, cur_cg = cg;
         item += nwaves;
         const bool more = item < a.nitems;
@@ -970,28 +970,32 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, MINB) void k_pw(const DlfPwArgs 
         // ---- 16 bytes per lane: LPP lanes cover the 32*FC channels of one pixel ----
         const int part = lane % LPP;
         const int c = cur_cg * (32 * FC) + part * 8;
-        u4v val[NPASS], rv[NPASS];
-        bool ok[NPASS];
-        unsigned go[NPASS];
+        constexpr int HP = NPASS > 1 ? NPASS / 2 : 1;          // two rounds keep the register need down
 #pragma unroll
-        for (int i = 0; i < NPASS; ++i) {
-            const int px = i * (64 / LPP) + lane / LPP;
-            const int gpix = cur_pg * (32 * FP) + px;
-            ok[i] = gpix < a.m && c < a.cout;
-            go[i] = (unsigned)gpix * (unsigned)a.cout + (unsigned)c;
-            if (resp != nullptr && ok[i]) rv[i] = *(const u4v*)(resp + go[i]);
-            val[i] = *(const u4v*)(tb + px * ROW + part * 8);
-        }
+        for (int h = 0; h < NPASS / HP; ++h) {
+            u4v val[HP], rv[HP];
+            bool ok[HP];
+            unsigned go[HP];
 #pragma unroll
-        for (int i = 0; i < NPASS; ++i) {
-            if (ok[i]) {
-                if (resp != nullptr) {
-                    val[i].x = pk_min(pk_max(pk_add(val[i].x, rv[i].x), lo_r), hi_r);
-                    val[i].y = pk_min(pk_max(pk_add(val[i].y, rv[i].y), lo_r), hi_r);
-                    val[i].z = pk_min(pk_max(pk_add(val[i].z, rv[i].z), lo_r), hi_r);
-                    val[i].w = pk_min(pk_max(pk_add(val[i].w, rv[i].w), lo_r), hi_r);
+            for (int i = 0; i < HP; ++i) {
+                const int px = (h * HP + i) * (64 / LPP) + lane / LPP;
+                const int gpix = cur_pg * (32 * FP) + px;
+                ok[i] = gpix < a.m && c < a.cout;
+                go[i] = (unsigned)gpix * (unsigned)a.cout + (unsigned)c;
+                if (resp != nullptr && ok[i]) rv[i] = *(const u4v*)(resp + go[i]);
+                val[i] = *(const u4v*)(tb + px * ROW + part * 8);
+            }
+#pragma unroll
+            for (int i = 0; i < HP; ++i) {
+                if (ok[i]) {
+                    if (resp != nullptr) {
+                        val[i].x = pk_min(pk_max(pk_add(val[i].x, rv[i].x), lo_r), hi_r);
+                        val[i].y = pk_min(pk_max(pk_add(val[i].y, rv[i].y), lo_r), hi_r);
+                        val[i].z = pk_min(pk_max(pk_add(val[i].z, rv[i].z), lo_r), hi_r);
+                        val[i].w = pk_min(pk_max(pk_add(val[i].w, rv[i].w), lo_r), hi_r);
+                    }
+                    *(u4v*)(outp + go[i]) = val[i];
                 }
-                *(u4v*)(outp + go[i]) = val[i];
             }
         }
         __builtin_amdgcn_wave_barrier();
@@ -1122,7 +1126,7 @@ extern "C" int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stre
 {
     if (grid <= 0) return (int)hipErrorInvalidValue;
     if (shape == 0)
-        hipLaunchKernelGGL((k_pw<2, 2, 4, 2>), dim3(grid), dim3(DLF_PW_WAVES * 64),
+        hipLaunchKernelGGL((k_pw<2, 2, 6, 2>), dim3(grid), dim3(DLF_PW_WAVES * 64),
                            (size_t)(DLF_PW_WAVES * 64 * (64 + 8) * 2), (hipStream_t)stream, *a);
     else if (shape == 1)
         hipLaunchKernelGGL((k_pw<1, 1, 8, 4>), dim3(grid), dim3(DLF_PW_WAVES * 64),
