@@ -30,8 +30,8 @@ RIDGE = MFMA_FP16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # FLOP per byte
 # Valid only for the kernel sources they were taken with: `csrc_sha1` is checked at run time and
 # `traffic` is reported as null when the sources have changed since.
 TRAFFIC = {
-    "csrc_sha1": "",
-    "bytes_per_launch": {},
+    "csrc_sha1": "30d3b7c65ff3405f2d6af713673feca6fbb064e7",
+    "bytes_per_launch": {"resnet50_b32": {"k_pw": 45898326, "k_group<1,2,2>": 50171504, "k_group<1,2,4>": 29692647}},
 }
 
 
