@@ -35,7 +35,9 @@ C_STORE = 1600
 MFMA_CYCLES = 32
 FC_BYTES_PER_CYCLE = 1400
 GAP_BYTES_PER_CYCLE = 1000
-PW_SHAPES = ((2, 2, 8, 470, 64), (1, 1, 16, 300, 100))   # FC, FP, waves per CU, cycles per K step (alone, per wave sharing the CU)
+# FC, FP, items in flight per CU, cycles per K step (alone, per item sharing the CU), K split
+PW_SHAPES = ((2, 2, 8, 470, 64, 1), (1, 1, 16, 300, 100, 1), (2, 2, 2, 470, 256, 4))
+C_PW_SK = 12000
 C_PW_ITEM = 2500
 C_PW_RES = 1000
 PW_HBM_BYTES_PER_CYCLE = 2000
@@ -397,11 +399,13 @@ def pw_cost(ni, i, batch, budget):
     nbytes = m * L["cin"] * 2 + m * L["cout"] * 2 * (1 + has_res) + ni.ncb[i] * nsteps * 1024
     mem = nbytes // min(PW_HBM_BYTES_PER_CYCLE, budget * CU_BYTES_PER_CYCLE)
     best = None
-    for fc, fp, w, step0, step_wave in PW_SHAPES:
+    for fc, fp, w, step0, step_wave, ks in PW_SHAPES:
+        if ks > 1 and (nsteps % ks or nsteps < 16):
+            continue
         items = cdiv(m, 32 * fp) * cdiv(ni.ncb[i], fc)
         items_cu = cdiv(items, budget)
         step = max(step0, min(items_cu, w) * step_wave)
-        item = C_PW_ITEM + nsteps * step + has_res * C_PW_RES
+        item = C_PW_ITEM + (nsteps // ks) * step + (C_PW_SK if ks > 1 else 0) + has_res * C_PW_RES
         compute = cdiv(items_cu, w) * item
         c = (C_LAUNCH + max(compute, mem)) * PS_PER_CYCLE
         if best is None or c < best:

@@ -269,7 +269,7 @@ def dlf_cost_model_version():
 
 def dlf_debug_pointwise_mode(mode=0):
     """Testing hook: 0 = pointwise kernel chosen by modelled cost, 1 = wherever it applies, 2 = never,
-    3 / 4 = wherever it applies with 64x64 / 32x32 work items."""
+    3 / 4 / 5 = wherever it applies with 64x64 / 32x32 / split-K 64x64 work items."""
     lib().dlf_debug_pointwise_mode(mode)
 
 

@@ -202,14 +202,17 @@ const int64_t FC_BYTES_PER_CYCLE = 1400;    // weight streaming rate of the FC k
 const int64_t GAP_BYTES_PER_CYCLE = 1000;
 // pointwise kernel, per item shape: register tile (FC x FP blocks of 32), operand ring depth,
 // independent waves per CU
-const int PW_SHAPES = 2;
-const int PW_FC[PW_SHAPES] = {2, 1};
-const int PW_FP[PW_SHAPES] = {2, 1};
-const int PW_WAVES_PER_CU[PW_SHAPES] = {8, 16};
+// (shape 2: the split-K form, a 64 x 64 item per workgroup of four waves, two workgroups per CU)
+const int PW_SHAPES = 3;
+const int PW_FC[PW_SHAPES] = {2, 1, 2};
+const int PW_FP[PW_SHAPES] = {2, 1, 2};
+const int PW_WAVES_PER_CU[PW_SHAPES] = {8, 16, 2};     // items in flight per CU
+const int PW_KSPLIT[PW_SHAPES] = {1, 1, 4};
 // fitted to per-launch HIP-event times of 1x1 layers of the ResNet-50 / MobileNet-v1 shapes
 const int64_t C_PW_ITEM = 2500;             // per work item: address setup, epilogue
-const int64_t C_PW_STEP[PW_SHAPES] = {470, 300};   // per K step of a latency-bound wave ...
-const int64_t C_PW_STEP_WAVE[PW_SHAPES] = {64, 100};   // ... or of a CU whose waves share its vector-memory path
+const int64_t C_PW_STEP[PW_SHAPES] = {470, 300, 470};   // per K step of a latency-bound wave ...
+const int64_t C_PW_STEP_WAVE[PW_SHAPES] = {64, 100, 256};   // ... or of a CU whose waves share its vector-memory path
+const int64_t C_PW_SK = 12000;              // split-K: exchange of partial sums through LDS, idle waves of a second round
 const int64_t C_PW_RES = 1000;              // residual loads
 const int64_t PW_HBM_BYTES_PER_CYCLE = 2000;
 
@@ -598,7 +601,8 @@ bool choose_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
 }
 
 // Testing hook: 0 = the pointwise kernel competes with the fused-group kernel on modelled cost,
-// 1 = always where it applies, 2 = never, 3 / 4 = always, with item shape 0 / 1.
+// 1 = always where it applies, 2 = never, 3 / 4 / 5 = always, with item shape 0 / 1 / 2 (shape 2
+// falls back to 0 where K does not split in four).
 int g_pw_mode = 0;
 
 // A convolution the pointwise kernel can run: 1x1, no padding, whole 32-channel K chunks.
@@ -620,7 +624,8 @@ uint64_t pw_shape_cost_ps(const Layer& L, int batch, int budget, int shape)
     const int64_t items_cu = (items + budget - 1) / budget;
     const int64_t has_res = L.d.residual_from >= 0 ? 1 : 0;
     const int64_t step = std::max(C_PW_STEP[shape], std::min(items_cu, W) * C_PW_STEP_WAVE[shape]);
-    const int64_t item = C_PW_ITEM + L.nsteps * step + has_res * C_PW_RES;
+    const int64_t ks = PW_KSPLIT[shape];
+    const int64_t item = C_PW_ITEM + (L.nsteps / ks) * step + (ks > 1 ? C_PW_SK : 0) + has_res * C_PW_RES;
     const int64_t compute = ((items_cu + W - 1) / W) * item;
     const int64_t bytes = m * L.d.cin * 2 + m * L.d.cout * 2 * (1 + has_res) + (int64_t)L.ncb * L.nsteps * 1024;
     const int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
@@ -633,6 +638,7 @@ uint64_t pw_cost_ps(const Layer& L, int batch, int budget, int& shape)
     uint64_t best = 0;
     shape = 0;
     for (int sh = 0; sh < PW_SHAPES; ++sh) {
+        if (PW_KSPLIT[sh] > 1 && (L.nsteps % PW_KSPLIT[sh] != 0 || L.nsteps < 16)) continue;
         const uint64_t c = pw_shape_cost_ps(L, batch, budget, sh);
         if (sh == 0 || c < best) { best = c; shape = sh; }
     }
@@ -686,6 +692,7 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
         uint64_t pc = pw_cost_ps(L0, batch, budget, shape);
         if (g_pw_mode >= 3) {
             shape = g_pw_mode - 3;
+            if (PW_KSPLIT[shape] > 1 && (L0.nsteps % PW_KSPLIT[shape] != 0 || L0.nsteps < 16)) shape = 0;
             pc = pw_shape_cost_ps(L0, batch, budget, shape);
         }
         if (!tiled || g_pw_mode == 1 || g_pw_mode >= 3 || pc < cost) {
@@ -701,8 +708,9 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
             g.kind = GK_PW;
             g.cost = pc;
             g.variant = shape;
-            g.occ = PW_WAVES_PER_CU[shape] / DLF_PW_WAVES;
-            g.grid = std::min(budget * g.occ, ceil_div(wa.nitems, DLF_PW_WAVES));
+            g.occ = shape == 2 ? 2 : PW_WAVES_PER_CU[shape] / DLF_PW_WAVES;
+            g.grid = shape == 2 ? std::min(budget * 2, wa.nitems)
+                                : std::min(budget * g.occ, ceil_div(wa.nitems, DLF_PW_WAVES));
             g.th = 1; g.tw = 32 * PW_FP[shape];
             g.lds_bytes = DLF_PW_WAVES * 32 * PW_FP[shape] * (32 * PW_FC[shape] + 8) * 2;
             if (L0.d.residual_from >= 0) { g.res_layer = L0.d.residual_from; g.res_stage = 0; }
@@ -1151,7 +1159,7 @@ dlf_status dlf_plan_group_io(const dlf_plan_t* plan, int32_t g, int32_t* in_laye
     return DLF_OK;
 }
 
-void dlf_debug_pointwise_mode(int32_t mode) { g_pw_mode = (mode >= 0 && mode <= 4) ? mode : 0; }
+void dlf_debug_pointwise_mode(int32_t mode) { g_pw_mode = (mode >= 0 && mode <= 5) ? mode : 0; }
 
 void dlf_debug_force_config(int32_t th, int32_t tw, int32_t variant, int32_t nslices, int32_t slice_c,
                             int32_t stream0, int32_t kc)

@@ -76,10 +76,12 @@ struct DlfFcArgs {
 };
 
 // Pointwise (1x1, pad 0) convolution run without tiles or barriers: every wave owns work items
-// of 64 x 64 (shape 0) or 32 x 32 (shape 1) output pixels x output channels, reads its activations
+// of 64 x 64 (shape 0) or 32 x 32 (shape 1) output pixels x output channels (shape 2: a 64 x 64
+// item shared by the four waves of a workgroup, each running a quarter of K), reads its activations
 // straight from HBM in the MFMA operand layout and writes its result through a wave-private LDS
 // transpose buffer.
 #define DLF_PW_WAVES 4               // waves per workgroup
+#define DLF_PWSK_PART_BYTES (4 * 3 * 16 * 64 * 4)   // split-K form (shape 2): partial sums in LDS
 struct DlfPwArgs {
     const void* in;       // [batch][in_h][in_w][cin] fp16
     void* out;            // [batch][out_h][out_w][cout] fp16

@@ -1003,6 +1003,127 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, MINB) void k_pw(const DlfPwArgs 
     }
 }
 
+// Split-K form of the pointwise kernel, for layers with few work items and a long K loop (small
+// feature maps, many input channels), where one wave per item leaves most of the chip idle behind a
+// serial chain of operand round trips: the four waves of a workgroup share one 64 x 64 item, each
+// runs a quarter of the K steps, the partial sums meet in LDS and each wave finishes one of the
+// four 32 x 32 blocks (bias, activation, residual, store).
+__global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pw_sk(const DlfPwArgs a)
+{
+    constexpr int D = 6;
+    constexpr int ROW = 32 + 8;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
+    float* part = (float*)lds;                                  // [block][3 senders][16][64] fp32
+    half_t* tb = lds + DLF_PWSK_PART_BYTES / 2 + wave * (32 * ROW);
+    const half_t* resp = (const half_t*)a.res;
+    half_t* outp = (half_t*)a.out;
+    const int per = a.nsteps / DLF_PW_WAVES;                    // the host guarantees divisibility
+    const int s0 = wave * per;
+    const int act_epi = resp != nullptr ? 0 : a.act;
+    const unsigned lo_e = act_lo(act_epi), hi_e = act_hi(act_epi);
+    const unsigned lo_r = act_lo(a.act), hi_r = act_hi(a.act);
+    for (int item = blockIdx.x; item < a.nitems; item += gridDim.x) {
+        const half_t* bp[2];
+        const h8* wp[2];
+        int pg, cg;
+        pw_item_setup<2>(a, item, lane, bp, pg, cg);
+#pragma unroll
+        for (int p = 0; p < 2; ++p) bp[p] += s0 * 16;
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+            const int cb = min(cg * 2 + f, a.ncb - 1);
+            wp[f] = (const h8*)a.w + ((size_t)cb * a.nsteps + s0) * 64 + lane;
+        }
+        h8 ar[D][2], br[D][2];
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            if (j < per) {
+#pragma unroll
+                for (int f = 0; f < 2; ++f) ar[j][f] = wp[f][j * 64];
+#pragma unroll
+                for (int p = 0; p < 2; ++p) br[j][p] = *(const h8*)(bp[p] + j * 16);
+            }
+        }
+        f16v acc[2][2];
+#pragma unroll
+        for (int f = 0; f < 2; ++f)
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[f][p][r] = 0.0f;
+        for (int s = 0; s < per; s += D) {
+#pragma unroll
+            for (int j = 0; j < D; ++j) {
+                if (s + j < per) {
+#pragma unroll
+                    for (int f = 0; f < 2; ++f)
+#pragma unroll
+                        for (int p = 0; p < 2; ++p)
+                            acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[j][f], br[j][p], acc[f][p], 0, 0, 0);
+                    if (s + j + D < per) {          // stays inside this wave's share of the channels
+#pragma unroll
+                        for (int f = 0; f < 2; ++f) ar[j][f] = wp[f][(s + j + D) * 64];
+#pragma unroll
+                        for (int p = 0; p < 2; ++p) br[j][p] = *(const h8*)(bp[p] + (s + j + D) * 16);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        // ---- exchange: block b = 2 * f + p is finished by wave b; the others send their partials ----
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            if (b != wave) {
+                const int k = wave < b ? wave : wave - 1;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) part[((b * 3 + k) * 16 + r) * 64 + lane] = acc[b >> 1][b & 1][r];
+            }
+        }
+        __syncthreads();
+        f16v own = wave == 0 ? acc[0][0] : (wave == 1 ? acc[0][1] : (wave == 2 ? acc[1][0] : acc[1][1]));
+#pragma unroll
+        for (int k = 0; k < 3; ++k)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) own[r] += part[((wave * 3 + k) * 16 + r) * 64 + lane];
+        const int fo = wave >> 1, po = wave & 1;
+        const int cb = cg * 2 + fo;
+        if (cb < a.ncb) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f4v bv = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
+                unsigned u0 = cvt_pk(own[q * 4 + 0] + bv[0], own[q * 4 + 1] + bv[1]);
+                unsigned u1 = cvt_pk(own[q * 4 + 2] + bv[2], own[q * 4 + 3] + bv[3]);
+                u0 = pk_min(pk_max(u0, lo_e), hi_e);
+                u1 = pk_min(pk_max(u1, lo_e), hi_e);
+                const u2v uu = {u0, u1};
+                *(u2v*)(tb + l32 * ROW + q * 8 + lhi * 4) = uu;
+            }
+            __builtin_amdgcn_wave_barrier();
+            // 32 pixels x 4 vectors of 8 channels: two per lane
+            const int partv = lane & 3;
+            const int c = cb * 32 + partv * 8;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int px = i * 16 + (lane >> 2);
+                const int gpix = (pg * 2 + po) * 32 + px;
+                if (gpix < a.m && c < a.cout) {
+                    const unsigned go = (unsigned)gpix * (unsigned)a.cout + (unsigned)c;
+                    u4v val = *(const u4v*)(tb + px * ROW + partv * 8);
+                    if (resp != nullptr) {
+                        const u4v rv = *(const u4v*)(resp + go);
+                        val.x = pk_min(pk_max(pk_add(val.x, rv.x), lo_r), hi_r);
+                        val.y = pk_min(pk_max(pk_add(val.y, rv.y), lo_r), hi_r);
+                        val.z = pk_min(pk_max(pk_add(val.z, rv.z), lo_r), hi_r);
+                        val.w = pk_min(pk_max(pk_add(val.w, rv.w), lo_r), hi_r);
+                    }
+                    *(u4v*)(outp + go) = val;
+                }
+            }
+        }
+        __syncthreads();        // the partial-sum area is rewritten by the next item
+    }
+}
+
 // Fully connected layer (Eq. 2 with M = batch): y[n][co] = act(bias[co] + sum_k x[n][k] w[co][k]).
 // One workgroup per 32 output channels; its 8 waves split K, each streaming a contiguous share
 // of the packed weight fragments from HBM exactly once; partial sums meet in LDS.
@@ -1131,6 +1252,10 @@ extern "C" int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stre
     else if (shape == 1)
         hipLaunchKernelGGL((k_pw<1, 1, 8, 4>), dim3(grid), dim3(DLF_PW_WAVES * 64),
                            (size_t)(DLF_PW_WAVES * 32 * (32 + 8) * 2), (hipStream_t)stream, *a);
+    else if (shape == 2)
+        hipLaunchKernelGGL(k_pw_sk, dim3(grid), dim3(DLF_PW_WAVES * 64),
+                           (size_t)(DLF_PWSK_PART_BYTES + DLF_PW_WAVES * 32 * (32 + 8) * 2),
+                           (hipStream_t)stream, *a);
     else
         return (int)hipErrorInvalidValue;
     return (int)hipGetLastError();

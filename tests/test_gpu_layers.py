@@ -122,14 +122,15 @@ def test_conv_output_channel_slices(slices):
 @pytest.mark.parametrize("cin,cout,hw,stride,act,batch", [
     (64, 256, 28, 1, "relu", 2), (256, 64, 28, 1, "relu", 2), (32, 64, 33, 1, "relu6", 3),
     (256, 512, 28, 2, "none", 2), (96, 40, 7, 1, "relu", 3), (64, 8, 9, 1, "relu", 1),
-    (1024, 256, 14, 1, "relu", 5), (128, 128, 15, 2, "relu6", 2), (32, 1000, 3, 1, "none", 7)])
+    (1024, 256, 14, 1, "relu", 5), (128, 128, 15, 2, "relu6", 2), (32, 1000, 3, 1, "none", 7),
+    (2048, 512, 7, 1, "relu", 3), (512, 40, 7, 2, "relu", 2)])
 def test_pointwise_kernel(cin, cout, hw, stride, act, batch):
     """1x1 convolutions on the barrier-free pointwise kernel (forced), ragged pixel and channel
     counts included."""
     announce("pointwise", cin, cout, hw, stride, act, batch)
     from paper_2011_05630_amd import binding as B
     net = _mk([nets.conv(cin, cout, 1, stride, 0, act)], hw, hw + 2, cin, dist="normal")
-    for mode in (3, 4):         # 64x64 and 32x32 work items
+    for mode in (3, 4, 5):      # 64x64, 32x32 and split-K 64x64 work items
         B.dlf_debug_pointwise_mode(mode)
         try:
             got, ref, g = _run(net, batch, **_manual(1, [0]))
@@ -148,7 +149,7 @@ def test_pointwise_kernel_is_used_and_adds_residual():
     net = _mk(layers, 21, 19, 64, dist="normal")
     x, ws, bs = gen.make_params(net, 3)
     ref = o.run_net(net, x, ws, bs)
-    for mode in (1, 3, 4):
+    for mode in (1, 3, 4, 5):
         B.dlf_debug_pointwise_mode(mode)
         try:
             s = Session(net, 3, ws, bs, **_manual(4, [0, 1, 2, 3]))
@@ -174,6 +175,20 @@ def test_pointwise_kernel_is_used_and_adds_residual():
         s.close()
     assert kinds == [0, 0, 0, 0], kinds
     compare(got2, ref, "same chain, fused-group kernel")
+
+
+def test_pointwise_split_k_with_residual():
+    announce("pointwise split-K residual")
+    from paper_2011_05630_amd import binding as B
+    layers = [nets.conv(512, 256, 1, 1, 0, "relu"), nets.conv(256, 256, 1, 1, 0, "relu6"),
+              nets.conv(256, 256, 1, 1, 0, "relu", residual_from=0)]
+    net = _mk(layers, 9, 11, 512, dist="normal")
+    B.dlf_debug_pointwise_mode(5)
+    try:
+        got, ref, g = _run(net, 3, **_manual(3, [0, 1, 2]))
+    finally:
+        B.dlf_debug_pointwise_mode(0)
+    compare(got, ref, "split-K pointwise chain with residual")
 
 
 @pytest.mark.parametrize("act", ["none", "relu", "relu6"])
