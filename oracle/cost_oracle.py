@@ -8,6 +8,10 @@ the tiling the library would use ("cost model, version 2" in the project's desig
 implemented twice, in the library (C++) and here (Python), so that the library's exact tuner can
 be checked bit for bit against exhaustive enumeration (plan_oracle.best_plan_exhaustive).
 
+The paper prints no cost function, so nothing here can be pinned against it (parity unpinned): this
+module is the second, independent statement of our own definition, and what it checks is that the
+library's planner implements exactly that definition and minimises it exactly.
+
 cost(first, last, budget) = min over the candidate tilings of the group of
     (C_LAUNCH + max(compute, memory)) * PS_PER_CYCLE
 or None if the layers cannot run as one group / no candidate fits on-chip memory.

@@ -4,8 +4,8 @@ Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
 library never does, and nothing here imports the GPU library.  Each layer function forwards to
 the plain nested-loop C routine of the same name in dlf_oracle.c; `run_net` applies them layer by
 layer, unfused, which is the definition the fused execution must be equivalent to (paper, Sec. I:
-fusion patterns are "mathematically equivalent" rewrites; Sec. III-B: fusion only changes where
-intermediates live).
+fusion rewrites the computation without changing its result; Sec. III-B: fusion only changes
+where intermediates live).
 
 Pins (tests/test_oracle_*.py): tap-count closed form, delta/shift kernels, linearity, 1x1 conv and
 FC against numpy.matmul, single-channel conv against scipy.signal.correlate2d, stride-2 against
