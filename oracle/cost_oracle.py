@@ -264,7 +264,12 @@ def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc
         c = chan_local if chan_local else sl["cout"]
         ph = sl["rh"] // 2 if sl["pool2"] else sl["rh"]
         pw = sl["rw"] // 2 if sl["pool2"] else sl["rw"]
-        area[ns & 1] = max(area[ns & 1], ph * pw * (rup(c, 8) + CPAD))
+        # the output tile overwrites the last stage's input where no wave has a second work item
+        n_pg = cdiv(cdiv(sl["rh"] * sl["rw"], 32), FP)
+        cbs = min(sl["ncb"], slice_c // 32) if nslices > 1 else sl["ncb"]
+        alias = (ns == 1 and stream0) or n_pg * cdiv(cbs, FC) <= WAVES
+        a = (ns - 1 if alias else ns) & 1
+        area[a] = max(area[a], ph * pw * (rup(c, 8) + CPAD))
     for s in range(ns - 1):
         p, c = S[s], S[s + 1]
         ph = p["rh"] // 2 if p["pool2"] else p["rh"]
@@ -303,7 +308,7 @@ def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc
             mma_waves = MMA_WAVES if streaming else WAVES
             if streaming and nitems > mma_waves:
                 return None
-            mma = cdiv(nitems, 4) * st["nsteps"] * FC * FP * MFMA_CYCLES * 2
+            mma = cdiv(nitems, 4) * st["nsteps"] * FC * FP * MFMA_CYCLES * (16 if FP >= 4 else 20) // 10
             if streaming:
                 nrounds = st["cin_pad"] // st["kc"]
                 vecs = cdiv(st["ih"] * st["iw"] * (st["kc"] // 8), LOAD_THREADS)

@@ -420,13 +420,24 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
         bufsz[s] = sz;
         area[s & 1] = std::max(area[s & 1], sz);
     }
-    // the last CONV stage leaves its tile in LDS (buffer ns); store_tile copies it to HBM
+    // the last CONV stage leaves its tile in LDS (buffer ns); store_tile copies it to HBM.  Where
+    // every wave has at most one work item of that stage (or the stage streams, which ends with a
+    // barrier anyway), the tile may overwrite the stage's own input: one barrier between the
+    // last MFMA and the epilogue, and the group needs that much less LDS.
+    bool alias_out = false;
     if (ga.st[ns - 1].kind == DLF_ST_CONV) {
         DlfStage& st = ga.st[ns - 1];
         const int c = chan_local ? chan_local : st.cout;
         st.out_cs = round_up(c, 8) + DLF_CPAD;
         const int ph = st.pool2 ? st.rh / 2 : st.rh, pw = st.pool2 ? st.rw / 2 : st.rw;
-        area[ns & 1] = std::max(area[ns & 1], (int64_t)ph * pw * st.out_cs);
+        const int npb = ceil_div(st.rh * st.rw, 32), n_pg = ceil_div(npb, FPv);
+        const int cbs = tc.nslices > 1 ? std::min(st.ncb, tc.slice_c / 32) : st.ncb;
+        const int nitems = n_pg * ceil_div(cbs, FCv);
+        const bool streaming = (ns == 1 && tc.stream0);
+        alias_out = streaming || nitems <= DLF_WAVES;
+        st.alias_out = alias_out ? 1 : 0;
+        area[(alias_out ? ns - 1 : ns) & 1] =
+            std::max(area[(alias_out ? ns - 1 : ns) & 1], (int64_t)ph * pw * st.out_cs);
     }
     // consistency: what stage s writes must be what stage s+1 reads
     for (int s = 0; s + 1 < ns; ++s) {
@@ -441,6 +452,7 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
         ga.st[s].in_off = (s & 1) ? (int)area[0] : 0;
         ga.st[s].out_off = ((s + 1) & 1) ? (int)area[0] : 0;
     }
+    if (alias_out) ga.st[ns - 1].out_off = ga.st[ns - 1].in_off;
     const int64_t lds_halfs = area[0] + area[1];
     if (lds_halfs * 2 > max_lds) return b;
     b.lds_bytes = (int)(lds_halfs * 2);
@@ -472,7 +484,9 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
             const int mma_waves = streaming ? DLF_MMA_WAVES : DLF_WAVES;
             if (streaming && nitems > mma_waves) return b;
             // items queue up on the 4 SIMDs; measured rounds run at about half the MFMA issue rate
-            int64_t mma = (int64_t)ceil_div(nitems, 4) * st.nsteps * FCv * FPv * MFMA_CYCLES * 2;
+            // (a 32 x 128 register tile needs half the weight traffic per MFMA and runs closer to
+            //  the issue rate: 1.6 instead of 2)
+            int64_t mma = (int64_t)ceil_div(nitems, 4) * st.nsteps * FCv * FPv * MFMA_CYCLES * (FPv >= 4 ? 16 : 20) / 10;
             if (streaming) {
                 const int64_t nrounds = st.cin_pad / st.kc;
                 const int64_t vecs = ceil_div(st.ih * st.iw * (st.kc / 8), DLF_LOAD_THREADS);

@@ -38,6 +38,8 @@ struct DlfStage {
     int32_t out_off;      // LDS offset (halfs) of the output buffer
     int32_t stream_buf;   // stream mode: halfs per chunk buffer
     int32_t nsteps;       // CONV: 16-wide K steps per output-channel block
+    int32_t alias_out;    // last CONV stage: the output tile overwrites the stage's input in LDS; a
+                          // barrier separates the last MFMA from the epilogue
     int32_t im2col;       // CONV stage 0 on a narrow input (cin % 8 != 0).  1: the staging gathers each
                           // output pixel's kh*kw*cin inputs into one LDS row and the stage then
                           // runs as a 1x1 convolution over cin_pad = roundup(kh*kw*cin, 32) channels.

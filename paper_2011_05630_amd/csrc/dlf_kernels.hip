@@ -492,7 +492,10 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
     for (int item0 = 0; item0 < nitems; item0 += MMA_WAVES) {
         const int item = item0 + wave;
         const bool active = item < nitems;
-        if (!STREAM && !active) continue;
+        if (!STREAM && !active) {
+            if (st.alias_out) __syncthreads();     // the barrier in front of the other waves' epilogues
+            continue;
+        }
         const int itc = active ? item : 0;
         const int cg = itc / n_pg, pg = itc - cg * n_pg;
 
@@ -557,6 +560,9 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
             if (STREAM) __syncthreads();
         }
 
+        // the output tile may overwrite this stage's input: every wave must be done reading it
+        // (a streaming stage has just passed its last round's barrier)
+        if (!STREAM && st.alias_out) __syncthreads();
         // ---- epilogue: activation, (pool), fp16 -> LDS tile [pixel][channel] ----
         // (the last stage's tile is then written to HBM by store_tile with full-line stores,
         //  which also adds the residual operand and applies the activation after it)
