@@ -122,8 +122,10 @@ dlf_status dlf_plan_bind_workspace(dlf_plan_t* plan, void* dev_ptr, size_t bytes
  * both DEVICE pointers that must not alias; hip_stream is a hipStream_t (NULL = default stream).
  * Asynchronous; reports launch errors only. */
 dlf_status dlf_run(const dlf_plan_t* plan, const void* in_dev, void* out_dev, void* hip_stream);
-/* Profiling variant of dlf_run: runs the plan `reps` times with a HIP event pair around every
- * group launch on hip_stream, waits for the stream, and writes the mean duration of each group
+/* Profiling variant of dlf_run: runs the plan `reps` times with a HIP stop event attached to every
+ * group launch on hip_stream (stamped with the end of that dispatch; a group's duration is taken
+ * from the end of the previous dispatch to the end of its own), waits for the stream, and writes
+ * the mean duration of each group
  * in milliseconds to group_ms[dlf_plan_num_groups] (HOST array).  Creates and destroys events,
  * synchronises: not for the serving path. */
 dlf_status dlf_run_profiled(const dlf_plan_t* plan, const void* in_dev, void* out_dev,

@@ -115,6 +115,8 @@ int dlf_launch_fc(const DlfFcArgs* a, void* stream);
 int dlf_launch_gap(const DlfGapArgs* a, void* stream);
 int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stream);
 int dlf_kernels_init(void);
+// Attaches a start / stop event pair (hipEvent_t, either may be null) to this thread's next launch.
+void dlf_next_launch_events(void* start, void* stop);
 #ifdef __cplusplus
 }
 #endif

@@ -13,6 +13,7 @@
 // im2col gather is just an address offset per filter tap.  With this orientation each lane ends
 // up holding 4 consecutive output channels of one pixel, which is what an NHWC store wants.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include "dlf_internal.h"
 
@@ -1211,6 +1212,27 @@ __global__ __launch_bounds__(256) void k_gap(const DlfGapArgs a)
     ((half_t*)a.y)[idx] = (half_t)(s / (float)a.hw);
 }
 
+// Profiling: a start / stop event pair attached to the next launch of this thread.  The runtime
+// stamps such events with the dispatch's own begin and end, so their difference is the kernel's
+// duration (what a kernel trace reports), free of the gaps around events recorded on the stream.
+static thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
+extern "C" void dlf_next_launch_events(void* start, void* stop)
+{
+    g_ev_start = (hipEvent_t)start;
+    g_ev_stop = (hipEvent_t)stop;
+}
+
+template <typename K, typename A>
+static void launch(K k, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream, const A& a)
+{
+    if (g_ev_start != nullptr || g_ev_stop != nullptr) {
+        hipExtLaunchKernelGGL(k, grid, block, lds_bytes, stream, g_ev_start, g_ev_stop, 0, a);
+        g_ev_start = g_ev_stop = nullptr;
+    } else {
+        hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, a);
+    }
+}
+
 typedef void (*group_kernel_t)(const DlfGroupArgs);
 static group_kernel_t group_kernel(int variant)
 {
@@ -1238,14 +1260,13 @@ extern "C" int dlf_launch_group(const DlfGroupArgs* a, int variant, int grid, in
 {
     group_kernel_t k = group_kernel(variant);
     if (k == nullptr || grid <= 0) return (int)hipErrorInvalidValue;
-    hipLaunchKernelGGL(k, dim3(grid), dim3(DLF_WG_THREADS), (size_t)lds_bytes, (hipStream_t)stream,
-                       *a);
+    launch(k, dim3(grid), dim3(DLF_WG_THREADS), (size_t)lds_bytes, (hipStream_t)stream, *a);
     return (int)hipGetLastError();
 }
 
 extern "C" int dlf_launch_fc(const DlfFcArgs* a, void* stream)
 {
-    hipLaunchKernelGGL(k_fc, dim3(a->ncb), dim3(DLF_FC_WAVES * 64), 0, (hipStream_t)stream, *a);
+    launch(k_fc, dim3(a->ncb), dim3(DLF_FC_WAVES * 64), 0, (hipStream_t)stream, *a);
     return (int)hipGetLastError();
 }
 
@@ -1253,13 +1274,13 @@ extern "C" int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stre
 {
     if (grid <= 0) return (int)hipErrorInvalidValue;
     if (shape == 0)
-        hipLaunchKernelGGL((k_pw<2, 2, 6, 2>), dim3(grid), dim3(DLF_PW_WAVES * 64),
+        launch(k_pw<2, 2, 6, 2>, dim3(grid), dim3(DLF_PW_WAVES * 64),
                            (size_t)(DLF_PW_WAVES * 64 * (64 + 8) * 2), (hipStream_t)stream, *a);
     else if (shape == 1)
-        hipLaunchKernelGGL((k_pw<1, 1, 8, 4>), dim3(grid), dim3(DLF_PW_WAVES * 64),
+        launch(k_pw<1, 1, 8, 4>, dim3(grid), dim3(DLF_PW_WAVES * 64),
                            (size_t)(DLF_PW_WAVES * 32 * (32 + 8) * 2), (hipStream_t)stream, *a);
     else if (shape == 2)
-        hipLaunchKernelGGL(k_pw_sk, dim3(grid), dim3(DLF_PW_WAVES * 64),
+        launch(k_pw_sk, dim3(grid), dim3(DLF_PW_WAVES * 64),
                            (size_t)(DLF_PWSK_PART_BYTES + DLF_PW_WAVES * 32 * (32 + 8) * 2),
                            (hipStream_t)stream, *a);
     else
@@ -1270,6 +1291,6 @@ extern "C" int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stre
 extern "C" int dlf_launch_gap(const DlfGapArgs* a, void* stream)
 {
     const int total = a->batch * a->c;
-    hipLaunchKernelGGL(k_gap, dim3((total + 255) / 256), dim3(256), 0, (hipStream_t)stream, *a);
+    launch(k_gap, dim3((total + 255) / 256), dim3(256), 0, (hipStream_t)stream, *a);
     return (int)hipGetLastError();
 }
