@@ -46,6 +46,8 @@ def csrc_sha1():
 
 
 VARIANT_NAME = {0: "k_group<2,2,2>", 1: "k_group<1,4,2>", 2: "k_group<1,2,2>", 3: "k_group<1,2,4>"}
+# pointwise kernels by item shape
+PW_NAME = {0: "k_pw<2,2,6,2>", 1: "k_pw<1,1,8,4>", 2: "k_pw_sk", 3: "k_pwb<2,2>", 4: "k_pwb<1,4>"}
 
 
 def workloads():
@@ -102,7 +104,7 @@ def group_accounting(net, batch, session):
         if cfg["kind"] == 1:
             kname = "k_fc"
         elif cfg["kind"] == 3:
-            kname = "k_pw"
+            kname = PW_NAME[cfg["variant"]]
         elif cfg["kind"] == 2:
             kname = "k_gap"
         else:

@@ -159,8 +159,9 @@ void dlf_debug_force_config(int32_t th, int32_t tw, int32_t variant, int32_t nsl
 
 /* Testing hook: how single 1x1 convolutions choose between the fused-group kernel and the
  * pointwise kernel: 0 = by modelled cost (default), 1 = pointwise wherever it applies, 2 = never,
- * 3 / 4 / 5 = pointwise wherever it applies with 64x64 / 32x32 / split-K 64x64 work items.
- * Process-wide, not thread-safe. */
+ * 3 / 4 / 5 = pointwise wherever it applies with 64x64 / 32x32 / split-K 64x64 work items,
+ * 6 / 7 = with workgroup blocks of 128 channels x 128 pixels / 64 channels x 256 pixels whose
+ * operands are shared through LDS.  Process-wide, not thread-safe. */
 void dlf_debug_pointwise_mode(int32_t mode);
 
 const char* dlf_status_string(dlf_status s);

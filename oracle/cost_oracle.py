@@ -41,6 +41,10 @@ FC_BYTES_PER_CYCLE = 1400
 GAP_BYTES_PER_CYCLE = 1000
 # FC, FP, items in flight per CU, cycles per K step (alone, per item sharing the CU), K split
 PW_SHAPES = ((2, 2, 8, 470, 64, 1), (1, 1, 16, 300, 100, 1), (2, 2, 2, 470, 256, 4))
+# block forms: (32-channel blocks, 32-pixel blocks) of a workgroup's block, two blocks per CU
+PWB_SHAPES = ((4, 4), (2, 8))
+C_PWB_BLOCK = 4000
+PWB_BYTES_PER_CYCLE = 25
 C_PW_SK = 12000
 C_PW_ITEM = 2500
 C_PW_RES = 1000
@@ -415,7 +419,20 @@ def pw_cost(ni, i, batch, budget):
         items_cu = cdiv(items, budget)
         step = max(step0, min(items_cu, w) * step_wave)
         item = C_PW_ITEM + (nsteps // ks) * step + (C_PW_SK if ks > 1 else 0) + has_res * C_PW_RES
-        compute = cdiv(items_cu, w) * item
+        stream = items_cu * nsteps * (fc + fp) * 1024 // PWB_BYTES_PER_CYCLE
+        compute = max(cdiv(items_cu, w) * item, stream)
+        c = (C_LAUNCH + max(compute, mem)) * PS_PER_CYCLE
+        if best is None or c < best:
+            best = c
+    for k, (bc, bp) in enumerate(PWB_SHAPES):
+        # 128 x 128 blocks for more than 64 output channels, 64 x 256 otherwise
+        if (k == 0) != (ni.ncb[i] >= 3):
+            continue
+        items = cdiv(m, 32 * bp) * cdiv(ni.ncb[i], bc)
+        items_cu = cdiv(items, budget)
+        rounds = cdiv(items_cu, 2)
+        frag_bytes = items_cu * nsteps * (bc + bp) * 1024
+        compute = rounds * (C_PWB_BLOCK + has_res * C_PW_RES) + frag_bytes // PWB_BYTES_PER_CYCLE
         c = (C_LAUNCH + max(compute, mem)) * PS_PER_CYCLE
         if best is None or c < best:
             best = c

@@ -203,15 +203,20 @@ const int64_t GAP_BYTES_PER_CYCLE = 1000;
 // pointwise kernel, per item shape: register tile (FC x FP blocks of 32), operand ring depth,
 // independent waves per CU
 // (shape 2: the split-K form, a 64 x 64 item per workgroup of four waves, two workgroups per CU)
-const int PW_SHAPES = 3;
-const int PW_FC[PW_SHAPES] = {2, 1, 2};
-const int PW_FP[PW_SHAPES] = {2, 1, 2};
-const int PW_WAVES_PER_CU[PW_SHAPES] = {8, 16, 2};     // items in flight per CU
-const int PW_KSPLIT[PW_SHAPES] = {1, 1, 4};
+// (shapes 3, 4: the block form, four waves share a block of 128 x 128 or 64 channels x 256 pixels
+// through LDS, two workgroups per CU)
+const int PW_SHAPES = 5;
+const int PW_FC[PW_SHAPES] = {2, 1, 2, 4, 2};          // 32-channel blocks per item
+const int PW_FP[PW_SHAPES] = {2, 1, 2, 4, 8};          // 32-pixel blocks per item
+const int PW_WAVES_PER_CU[PW_SHAPES] = {8, 16, 2, 2, 2};     // items in flight per CU
+const int PW_KSPLIT[PW_SHAPES] = {1, 1, 4, 1, 1};
+const bool PW_BLOCK[PW_SHAPES] = {false, false, false, true, true};
 // fitted to per-launch HIP-event times of 1x1 layers of the ResNet-50 / MobileNet-v1 shapes
 const int64_t C_PW_ITEM = 2500;             // per work item: address setup, epilogue
-const int64_t C_PW_STEP[PW_SHAPES] = {470, 300, 470};   // per K step of a latency-bound wave ...
-const int64_t C_PW_STEP_WAVE[PW_SHAPES] = {64, 100, 256};   // ... or of a CU whose waves share its vector-memory path
+const int64_t C_PW_STEP[PW_SHAPES] = {470, 300, 470, 0, 0};   // per K step of a latency-bound wave ...
+const int64_t C_PW_STEP_WAVE[PW_SHAPES] = {64, 100, 256, 0, 0};   // ... or of a CU whose waves share its vector-memory path
+const int64_t C_PWB_BLOCK = 4000;           // block form, per round of two blocks on a CU: first operands, epilogue
+const int64_t PWB_BYTES_PER_CYCLE = 25;     // rate at which a CU takes operand fragments in (all pointwise forms)
 const int64_t C_PW_SK = 12000;              // split-K: exchange of partial sums through LDS, idle waves of a second round
 const int64_t C_PW_RES = 1000;              // residual loads
 const int64_t PW_HBM_BYTES_PER_CYCLE = 2000;
@@ -615,7 +620,7 @@ bool choose_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
 }
 
 // Testing hook: 0 = the pointwise kernel competes with the fused-group kernel on modelled cost,
-// 1 = always where it applies, 2 = never, 3 / 4 / 5 = always, with item shape 0 / 1 / 2 (shape 2
+// 1 = always where it applies, 2 = never, 3 .. 7 = always, with item shape 0 .. 4 (shape 2
 // falls back to 0 where K does not split in four).
 int g_pw_mode = 0;
 
@@ -637,24 +642,48 @@ uint64_t pw_shape_cost_ps(const Layer& L, int batch, int budget, int shape)
     const int64_t items = ((m + 32 * FPs - 1) / (32 * FPs)) * ((L.ncb + FCs - 1) / FCs);
     const int64_t items_cu = (items + budget - 1) / budget;
     const int64_t has_res = L.d.residual_from >= 0 ? 1 : 0;
+    if (PW_BLOCK[shape]) {
+        // a CU works through its blocks two at a time; what bounds a block is the stream of operand
+        // fragments into the CU (1 KiB per 32 channels or pixels of the block and K step)
+        const int64_t rounds = (items_cu + W - 1) / W;
+        const int64_t frag_bytes = items_cu * L.nsteps * (FCs + FPs) * 1024;
+        const int64_t compute = rounds * (C_PWB_BLOCK + has_res * C_PW_RES) + frag_bytes / PWB_BYTES_PER_CYCLE;
+        const int64_t bytes = m * L.d.cin * 2 + m * L.d.cout * 2 * (1 + has_res) + (int64_t)L.ncb * L.nsteps * 1024;
+        const int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
+        return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
+    }
     const int64_t step = std::max(C_PW_STEP[shape], std::min(items_cu, W) * C_PW_STEP_WAVE[shape]);
     const int64_t ks = PW_KSPLIT[shape];
     const int64_t item = C_PW_ITEM + (L.nsteps / ks) * step + (ks > 1 ? C_PW_SK : 0) + has_res * C_PW_RES;
-    const int64_t compute = ((items_cu + W - 1) / W) * item;
+    // ... and never faster than the CU takes in the operand fragments of its items
+    const int64_t stream = items_cu * L.nsteps * (FCs + FPs) * 1024 / PWB_BYTES_PER_CYCLE;
+    const int64_t compute = std::max(((items_cu + W - 1) / W) * item, stream);
     const int64_t bytes = m * L.d.cin * 2 + m * L.d.cout * 2 * (1 + has_res) + (int64_t)L.ncb * L.nsteps * 1024;
     const int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
     return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
 }
 
-// Cheaper of the item shapes (ties: the larger tile).
+// May the planner choose this shape for the layer?  Split-K needs K steps that divide by four; of
+// the block forms, 128 x 128 serves layers of more than 64 output channels, 64 x 256 the others.
+bool pw_shape_ok(const Layer& L, int shape)
+{
+    if (PW_KSPLIT[shape] > 1 && (L.nsteps % PW_KSPLIT[shape] != 0 || L.nsteps < 16)) return false;
+    if (shape == 3) return L.ncb >= 3;
+    if (shape == 4) return L.ncb <= 2;
+    return true;
+}
+
+// Cheapest of the shapes (ties: the block forms first, then the larger item).
 uint64_t pw_cost_ps(const Layer& L, int batch, int budget, int& shape)
 {
+    static const int order[PW_SHAPES] = {3, 4, 0, 1, 2};
     uint64_t best = 0;
-    shape = 0;
-    for (int sh = 0; sh < PW_SHAPES; ++sh) {
-        if (PW_KSPLIT[sh] > 1 && (L.nsteps % PW_KSPLIT[sh] != 0 || L.nsteps < 16)) continue;
+    shape = -1;
+    for (int k = 0; k < PW_SHAPES; ++k) {
+        const int sh = order[k];
+        if (!pw_shape_ok(L, sh)) continue;
         const uint64_t c = pw_shape_cost_ps(L, batch, budget, sh);
-        if (sh == 0 || c < best) { best = c; shape = sh; }
+        if (shape < 0 || c < best) { best = c; shape = sh; }
     }
     return best;
 }
@@ -706,7 +735,7 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
         uint64_t pc = pw_cost_ps(L0, batch, budget, shape);
         if (g_pw_mode >= 3) {
             shape = g_pw_mode - 3;
-            if (PW_KSPLIT[shape] > 1 && (L0.nsteps % PW_KSPLIT[shape] != 0 || L0.nsteps < 16)) shape = 0;
+            if (PW_KSPLIT[shape] > 1 && !pw_shape_ok(L0, shape)) shape = 0;
             pc = pw_shape_cost_ps(L0, batch, budget, shape);
         }
         if (!tiled || g_pw_mode == 1 || g_pw_mode >= 3 || pc < cost) {
@@ -722,11 +751,14 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
             g.kind = GK_PW;
             g.cost = pc;
             g.variant = shape;
-            g.occ = shape == 2 ? 2 : PW_WAVES_PER_CU[shape] / DLF_PW_WAVES;
-            g.grid = shape == 2 ? std::min(budget * 2, wa.nitems)
+            g.occ = (shape == 2 || PW_BLOCK[shape]) ? 2 : PW_WAVES_PER_CU[shape] / DLF_PW_WAVES;
+            g.grid = PW_BLOCK[shape] ? std::max(8, std::min(budget * 2, ceil_div(wa.nitems, 8) * 8) / 8 * 8)
+                     : shape == 2 ? std::min(budget * 2, wa.nitems)
                                 : std::min(budget * g.occ, ceil_div(wa.nitems, DLF_PW_WAVES));
             g.th = 1; g.tw = 32 * PW_FP[shape];
-            g.lds_bytes = DLF_PW_WAVES * 32 * PW_FP[shape] * (32 * PW_FC[shape] + 8) * 2;
+            g.lds_bytes = shape == 3   ? DLF_PWB_LDS_BYTES(2, 2)
+                          : shape == 4 ? DLF_PWB_LDS_BYTES(1, 4)
+                                       : DLF_PW_WAVES * 32 * PW_FP[shape] * (32 * PW_FC[shape] + 8) * 2;
             if (L0.d.residual_from >= 0) { g.res_layer = L0.d.residual_from; g.res_stage = 0; }
             return DLF_OK;
         }
@@ -1173,7 +1205,7 @@ dlf_status dlf_plan_group_io(const dlf_plan_t* plan, int32_t g, int32_t* in_laye
     return DLF_OK;
 }
 
-void dlf_debug_pointwise_mode(int32_t mode) { g_pw_mode = (mode >= 0 && mode <= 5) ? mode : 0; }
+void dlf_debug_pointwise_mode(int32_t mode) { g_pw_mode = (mode >= 0 && mode <= 7) ? mode : 0; }
 
 void dlf_debug_force_config(int32_t th, int32_t tw, int32_t variant, int32_t nslices, int32_t slice_c,
                             int32_t stream0, int32_t kc)

@@ -84,6 +84,18 @@ struct DlfFcArgs {
 // transpose buffer.
 #define DLF_PW_WAVES 4               // waves per workgroup
 #define DLF_PWSK_PART_BYTES (4 * 3 * 16 * 64 * 4)   // split-K form (shape 2): partial sums in LDS
+// block form of the pointwise kernel: K steps per LDS stage, stages in the ring; LDS = the ring
+// (1 KiB per fragment) or the four waves' transpose buffers, whichever is larger
+#ifndef DLF_PWB_KS
+#define DLF_PWB_KS 2
+#endif
+#ifndef DLF_PWB_STAGES
+#define DLF_PWB_STAGES 4
+#endif
+#define DLF_PWB_LDS_BYTES(WN, WM)                                                                   \
+    ((DLF_PWB_STAGES * (2 * (WN) + 2 * (WM)) * DLF_PWB_KS * 1024) > (DLF_PW_WAVES * 64 * 72 * 2)      \
+         ? (DLF_PWB_STAGES * (2 * (WN) + 2 * (WM)) * DLF_PWB_KS * 1024)                              \
+         : (DLF_PW_WAVES * 64 * 72 * 2))
 struct DlfPwArgs {
     const void* in;       // [batch][in_h][in_w][cin] fp16
     void* out;            // [batch][out_h][out_w][cout] fp16

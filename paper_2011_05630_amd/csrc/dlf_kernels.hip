@@ -1131,6 +1131,206 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pw_sk(const DlfPwArgs 
     }
 }
 
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Block form of the pointwise kernel, for layers whose operand traffic from L2 bounds the
+// one-wave-per-item form: a workgroup of four waves computes 64 * WN output channels x 64 * WM
+// pixels (2 x 2 or 1 x 4 waves, each a 64 x 64 part), and the block's operands pass through LDS, so
+// every byte fetched from L2 feeds WM (weights) or WN (activations) waves.
+//   Global -> LDS: 16-byte direct loads (no registers in between); a wave's 64 lanes deposit one
+//     1 KiB MFMA fragment, lane l at byte 16 l -- for weights the packed fragment as it lies in
+//     memory, for activations lane (pixel l % 32, K half l / 32) fetches its own 16 bytes.
+//   LDS is a ring of NST stages of KS K steps; stage t + NST - 1 is requested when stage t is
+//     about to be multiplied.  Loads retire in issue order: "at most n x loads-per-stage
+//     outstanding" means that all but the wave's last n requested stages have landed, and the
+//     barrier that follows extends that to all waves (and tells every wave that stage t - 1 has
+//     been read by all, so its slot may be refilled).
+//   The barrier is the bare instruction: the fence of __syncthreads() would wait for every load
+//     in flight and serialise the ring.
+//   Epilogue as in k_pw, through a wave-private transpose buffer that reuses the ring.
+// One block per workgroup; consecutive blocks (same pixels, next channels) are dealt to the same
+// XCD so that they meet in its L2.
+template <int WN, int WM>
+__global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
+{
+    constexpr int KS = DLF_PWB_KS, NST = DLF_PWB_STAGES;
+    constexpr int NA = 2 * WN * KS, NB = 2 * WM * KS, NF = NA + NB;   // fragments per stage
+    constexpr int LPW = NF / DLF_PW_WAVES;                            // loads per wave per stage
+    constexpr int STAGE = NF * 512;                                   // halfs per stage
+    static_assert(WN * WM == DLF_PW_WAVES && NA % DLF_PW_WAVES == 0 && NB % DLF_PW_WAVES == 0, "fragment roles are per wave");
+    static_assert(KS % 2 == 0 && NST >= 4, "two register sets alternate per K step; one stage is read ahead");
+    constexpr int ROW = 64 + 8;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
+    // blockIdx.x % 8 is the XCD: give each XCD a contiguous range of blocks (the grid is a
+    // multiple of 8; a workgroup takes every (gridDim.x / 8)-th block of its XCD's range)
+    const int per_xcd = (a.nitems + 7) >> 3;
+    bool again = false;
+    for (int li = blockIdx.x >> 3; li < per_xcd; li += gridDim.x >> 3) {
+    const int item = (blockIdx.x & 7) * per_xcd + li;
+    if (item >= a.nitems) break;
+    if (again) {
+        // the stores of the previous block must not be counted among the loads of the ring, and
+        // the transpose buffers of all waves must have been read before the ring is refilled
+        wait_vmcnt<0>();
+        asm volatile("s_barrier" ::: "memory");
+    }
+    again = true;
+    const int pg = item / a.n_cg, cg = item - pg * a.n_cg;
+    const int wn = WN == 1 ? 0 : (wave & (WN - 1)), wm = WN == 1 ? wave : wave / WN;
+    const int wcg = cg * WN + wn, wpg = pg * WM + wm;       // the wave's 64-channel / 64-pixel part
+    const half_t* resp = (const half_t*)a.res;
+    half_t* outp = (half_t*)a.out;
+    const int act_epi = resp != nullptr ? 0 : a.act;
+    const unsigned lo_e = act_lo(act_epi), hi_e = act_hi(act_epi);
+    const unsigned lo_r = act_lo(a.act), hi_r = act_hi(a.act);
+
+    // the oldest loads in flight: complete by the first wait of the ring
+    f4v bias[2][4];
+#pragma unroll
+    for (int f = 0; f < 2; ++f) {
+        const int cb = min(wcg * 2 + f, a.ncb - 1);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bias[f][q] = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
+    }
+
+    // this wave's loads of a stage: fragments wave, wave + 4, ...
+    const half_t* src[LPW];
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+        const int f = wave + DLF_PW_WAVES * i;
+        if (DLF_PW_WAVES * i < NA) {
+            const int cbl = f / KS, ks = f - cbl * KS;
+            const int cb = min(cg * (2 * WN) + cbl, a.ncb - 1);
+            src[i] = (const half_t*)a.w + ((size_t)cb * a.nsteps + ks) * 512 + lane * 8;
+        } else {
+            const int j = f - NA;
+            const int pbl = j / KS, ks = j - pbl * KS;
+            int pix = (pg * (2 * WM) + pbl) * 32 + l32;
+            pix = pix < a.m ? pix : a.m - 1;          // clamped lanes compute a result nobody stores
+            unsigned off;
+            if (a.stride == 1) {
+                off = (unsigned)pix * (unsigned)a.cin;
+            } else {
+                const int hw = a.out_h * a.out_w;
+                const int n = pix / hw, r = pix - n * hw;
+                const int oy = r / a.out_w, ox = r - oy * a.out_w;
+                off = (unsigned)(((n * a.in_h + oy * a.stride) * a.in_w + ox * a.stride) * a.cin);
+            }
+            src[i] = (const half_t*)a.in + off + ks * 16 + lhi * 8;
+        }
+    }
+    auto issue = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            half_t* dst = lds + slot * STAGE + (wave + DLF_PW_WAVES * i) * 512;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src[i],
+                                             (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+            src[i] += (DLF_PW_WAVES * i < NA) ? KS * 512 : KS * 16;
+        }
+    };
+    const int KT = a.nsteps / KS;
+#pragma unroll
+    for (int t = 0; t < NST - 1; ++t)
+        if (t < KT) issue(t);
+
+    f16v acc[2][2];
+#pragma unroll
+    for (int f = 0; f < 2; ++f)
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[f][p][r] = 0.0f;
+
+    // Stage t is multiplied while the fragments of the next K step -- the last one of a stage
+    // reads ahead into stage t + 1 -- are on their way from LDS, so stage t + 1 must be visible
+    // when iteration t starts: NST - 3 requested stages stay in flight behind it.
+    auto read_frags = [&](const half_t* sb, int ks, h8 (&af)[2], h8 (&bf)[2]) {
+#pragma unroll
+        for (int f = 0; f < 2; ++f) af[f] = *(const h8*)(sb + ((wn * 2 + f) * KS + ks) * 512);
+#pragma unroll
+        for (int p = 0; p < 2; ++p) bf[p] = *(const h8*)(sb + (NA + (wm * 2 + p) * KS + ks) * 512);
+    };
+    h8 af[2][2], bf[2][2];
+    if (KT > NST - 2) wait_vmcnt<(NST - 2) * LPW>(); else wait_vmcnt<0>();
+    asm volatile("s_barrier" ::: "memory");
+    read_frags(lds + lane * 8, 0, af[0], bf[0]);
+    int slot = 0;
+    for (int kt = 0; kt < KT; ++kt) {
+        const int nslot = slot + 1 == NST ? 0 : slot + 1;
+        if (kt + 1 < KT) {
+            if (kt + NST - 2 < KT) wait_vmcnt<(NST - 3) * LPW>();
+            else wait_vmcnt<0>();
+        }
+        asm volatile("s_barrier" ::: "memory");
+        if (kt + NST - 1 < KT) issue(slot == 0 ? NST - 1 : slot - 1);
+        const half_t* sb = lds + slot * STAGE + lane * 8;
+        const half_t* nb = lds + nslot * STAGE + lane * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks + 1 < KS) read_frags(sb, ks + 1, af[nxt], bf[nxt]);
+            else if (kt + 1 < KT) read_frags(nb, 0, af[nxt], bf[nxt]);
+#pragma unroll
+            for (int f = 0; f < 2; ++f)
+#pragma unroll
+                for (int p = 0; p < 2; ++p)
+                    acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][f], bf[cur][p], acc[f][p], 0, 0, 0);
+        }
+        slot = nslot;
+    }
+    // every wave is done with the ring (all loads were waited for above): reuse it
+    asm volatile("s_barrier" ::: "memory");
+    half_t* tb = lds + wave * (64 * ROW);
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int f = 0; f < 2; ++f)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                unsigned u0 = cvt_pk(acc[f][p][q * 4 + 0] + bias[f][q][0], acc[f][p][q * 4 + 1] + bias[f][q][1]);
+                unsigned u1 = cvt_pk(acc[f][p][q * 4 + 2] + bias[f][q][2], acc[f][p][q * 4 + 3] + bias[f][q][3]);
+                u0 = pk_min(pk_max(u0, lo_e), hi_e);
+                u1 = pk_min(pk_max(u1, lo_e), hi_e);
+                const u2v uu = {u0, u1};
+                *(u2v*)(tb + (p * 32 + l32) * ROW + f * 32 + q * 8 + lhi * 4) = uu;
+            }
+    __builtin_amdgcn_wave_barrier();
+    // 16 bytes per lane: 8 lanes cover the 64 channels of one pixel, 8 pixels per pass
+    const int part = lane & 7;
+    const int c = wcg * 64 + part * 8;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        u4v val[4], rv[4];
+        bool ok[4];
+        unsigned go[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int px = (h * 4 + i) * 8 + (lane >> 3);
+            const int gpix = wpg * 64 + px;
+            ok[i] = gpix < a.m && c < a.cout;
+            go[i] = (unsigned)gpix * (unsigned)a.cout + (unsigned)c;
+            if (resp != nullptr && ok[i]) rv[i] = *(const u4v*)(resp + go[i]);
+            val[i] = *(const u4v*)(tb + px * ROW + part * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (ok[i]) {
+                if (resp != nullptr) {
+                    val[i].x = pk_min(pk_max(pk_add(val[i].x, rv[i].x), lo_r), hi_r);
+                    val[i].y = pk_min(pk_max(pk_add(val[i].y, rv[i].y), lo_r), hi_r);
+                    val[i].z = pk_min(pk_max(pk_add(val[i].z, rv[i].z), lo_r), hi_r);
+                    val[i].w = pk_min(pk_max(pk_add(val[i].w, rv[i].w), lo_r), hi_r);
+                }
+                *(u4v*)(outp + go[i]) = val[i];
+            }
+        }
+    }
+    }
+}
+
 // Fully connected layer (Eq. 2 with M = batch): y[n][co] = act(bias[co] + sum_k x[n][k] w[co][k]).
 // One workgroup per 32 output channels; its 8 waves split K, each streaming a contiguous share
 // of the packed weight fragments from HBM exactly once; partial sums meet in LDS.
@@ -1283,6 +1483,12 @@ extern "C" int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stre
         launch(k_pw_sk, dim3(grid), dim3(DLF_PW_WAVES * 64),
                            (size_t)(DLF_PWSK_PART_BYTES + DLF_PW_WAVES * 32 * (32 + 8) * 2),
                            (hipStream_t)stream, *a);
+    else if (shape == 3)
+        launch(k_pwb<2, 2>, dim3(grid), dim3(DLF_PW_WAVES * 64), (size_t)DLF_PWB_LDS_BYTES(2, 2),
+               (hipStream_t)stream, *a);
+    else if (shape == 4)
+        launch(k_pwb<1, 4>, dim3(grid), dim3(DLF_PW_WAVES * 64), (size_t)DLF_PWB_LDS_BYTES(1, 4),
+               (hipStream_t)stream, *a);
     else
         return (int)hipErrorInvalidValue;
     return (int)hipGetLastError();

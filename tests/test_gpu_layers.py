@@ -130,7 +130,7 @@ def test_pointwise_kernel(cin, cout, hw, stride, act, batch):
     announce("pointwise", cin, cout, hw, stride, act, batch)
     from paper_2011_05630_amd import binding as B
     net = _mk([nets.conv(cin, cout, 1, stride, 0, act)], hw, hw + 2, cin, dist="normal")
-    for mode in (3, 4, 5):      # 64x64, 32x32 and split-K 64x64 work items
+    for mode in (3, 4, 5, 6, 7):      # 64x64, 32x32, split-K 64x64 items; 128x128 and 64x256 blocks
         B.dlf_debug_pointwise_mode(mode)
         try:
             got, ref, g = _run(net, batch, **_manual(1, [0]))
@@ -149,7 +149,7 @@ def test_pointwise_kernel_is_used_and_adds_residual():
     net = _mk(layers, 21, 19, 64, dist="normal")
     x, ws, bs = gen.make_params(net, 3)
     ref = o.run_net(net, x, ws, bs)
-    for mode in (1, 3, 4, 5):
+    for mode in (1, 3, 4, 5, 6, 7):
         B.dlf_debug_pointwise_mode(mode)
         try:
             s = Session(net, 3, ws, bs, **_manual(4, [0, 1, 2, 3]))
