@@ -124,6 +124,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--plan", default="dp", choices=["dp", "greedy", "unfused"])
     ap.add_argument("--budget", type=int, default=256, help="budget of every group of --plan unfused")
+    ap.add_argument("--refine", type=int, default=0,
+                    help="measured refinement of the plan before timing: candidates per group (0 = off)")
     ap.add_argument("--table", action="store_true", help="per-group table on stderr")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--calib-copy", type=int, default=0,
@@ -168,6 +170,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    refined = 0
+    if args.refine > 0:
+        refined = s.refine(xt, top_k=args.refine, reps=5)
     for _ in range(args.warmup):
         B.dlf_run(s.plan, xt.data_ptr(), out.data_ptr(), stream)
     torch.cuda.synchronize()
@@ -264,7 +269,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": "%s_b%d" % (net["name"], batch), "batch": batch,
-                   "plan": args.plan, "groups": len(s.groups), "layers": n,
+                   "plan": args.plan + ("+refine%d" % args.refine if args.refine > 0 else ""),
+                   "groups_refined": refined, "groups": len(s.groups), "layers": n,
                    "input": "%dx%dx%d" % (net["in_h"], net["in_w"], net["in_c"])},
         "event_ms_per_step": event_ms_per_step,
         "event_overhead_us_per_launch": ev_overhead_ms * 1e3,

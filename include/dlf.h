@@ -150,6 +150,19 @@ dlf_status dlf_plan_group_config(const dlf_plan_t* plan, int32_t g, int32_t* kin
 /* Tensors group g reads from HBM: *in_layer = layer whose output is the group input (-1 = the
  * network input); *res_layer = layer whose output is added as a residual (-2 = none). */
 dlf_status dlf_plan_group_io(const dlf_plan_t* plan, int32_t g, int32_t* in_layer, int32_t* res_layer);
+/* Measured refinement of a plan, after the paper's search procedure that times candidates on the
+ * hardware (Sec. V, the reduced brute-force search): for every fused group and every single 1x1
+ * layer, the top_k tilings by modelled cost (and each pointwise kernel form that applies) are run
+ * `reps` times on the group's real input (caches scrubbed, the input freshly written by the group
+ * in front) and the fastest replaces the planned configuration if it is at least 10 % faster.  The partition into groups and the budgets stay as planned.
+ * in_dev / out_dev: DEVICE, as for dlf_run; the workspace must be bound.  Runs the network once,
+ * then the candidates, on hip_stream, and waits for them (this call synchronises the stream).
+ * *changed (HOST, may be null): number of groups whose configuration changed.  The plan must
+ * not be in use by another thread.  dlf_plan_group and dlf_plan_group_config report the new
+ * configuration; model_cost is the modelled cost of that configuration. */
+dlf_status dlf_plan_refine(dlf_plan_t* plan, const void* in_dev, void* out_dev, void* hip_stream,
+                           int32_t top_k, int32_t reps, int32_t* changed);
+
 /* Testing hook: th > 0 forces tile th x tw, register-tile variant, channel slicing, streaming and
  * channels per streaming round (kc: 32, 64 or 128; 0 = 32) for every group planned afterwards
  * (groups it does not fit become infeasible); th = 0 restores the automatic choice.

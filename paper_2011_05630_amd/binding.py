@@ -104,6 +104,8 @@ def lib():
     L.dlf_plan_group_config.restype = i32
     L.dlf_run_profiled.argtypes = [vp, vp, vp, vp, i32, ctypes.POINTER(ctypes.c_float)]
     L.dlf_run_profiled.restype = i32
+    L.dlf_plan_refine.argtypes = [vp, vp, vp, vp, i32, i32, i32p]
+    L.dlf_plan_refine.restype = i32
     L.dlf_plan_group_io.argtypes = [vp, i32, i32p, i32p]
     L.dlf_plan_group_io.restype = i32
     _lib = L
@@ -255,6 +257,14 @@ def dlf_run_profiled(plan, in_ptr, out_ptr, stream, reps):
     return list(ms)
 
 
+def dlf_plan_refine(plan, in_ptr, out_ptr, stream, top_k=6, reps=5):
+    """Times the top_k modelled tilings (and pointwise forms) of every group on the GPU and keeps
+    the fastest; -> number of groups whose configuration changed."""
+    changed = ctypes.c_int32(0)
+    _check(lib().dlf_plan_refine(plan, in_ptr, out_ptr, stream, top_k, reps, ctypes.byref(changed)))
+    return changed.value
+
+
 def dlf_run_group(plan, g, in_ptr, res_ptr, out_ptr, stream=None):
     _check(lib().dlf_run_group(plan, g, in_ptr, res_ptr, out_ptr, stream))
 
@@ -269,7 +279,8 @@ def dlf_cost_model_version():
 
 def dlf_debug_pointwise_mode(mode=0):
     """Testing hook: 0 = pointwise kernel chosen by modelled cost, 1 = wherever it applies, 2 = never,
-    3 / 4 / 5 = wherever it applies with 64x64 / 32x32 / split-K 64x64 work items."""
+    3 / 4 / 5 = wherever it applies with 64x64 / 32x32 / split-K 64x64 work items, 6 / 7 = with
+    128x128 / 64x256 workgroup blocks."""
     lib().dlf_debug_pointwise_mode(mode)
 
 

@@ -547,16 +547,17 @@ const int TILE_W[] = {4, 7, 8, 14, 16, 28, 32};
 // Chooses tile / register tile / slicing for a group at a given budget: minimum modelled cost;
 // ties go to the earlier candidate in enumeration order.
 bool choose_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int batch, int budget,
-                  int max_lds, Built& best, TileCfg& best_tc, uint64_t& best_cost)
+                  int max_lds, Built& best, TileCfg& best_tc, uint64_t& best_cost,
+                  const TileCfg& force = g_force, std::vector<std::pair<uint64_t, TileCfg>>* all = nullptr)
 {
     bool found = false;
     const int ns = (int)specs.size();
-    if (g_force.th > 0) {
-        Built b = build_group(net, specs, batch, g_force, max_lds);
+    if (force.th > 0) {
+        Built b = build_group(net, specs, batch, force, max_lds);
         if (!b.ok) return false;
         best = b;
-        best_tc = g_force;
-        best_cost = group_cost_ps(b, budget, g_force.variant);
+        best_tc = force;
+        best_cost = group_cost_ps(b, budget, force.variant);
         return true;
     }
     const Layer& Llast = net.L[specs[ns - 1].pool2 ? specs[ns - 1].pool_layer : specs[ns - 1].layer];
@@ -606,6 +607,7 @@ bool choose_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
                     Built b = build_group(net, specs, batch, tc, max_lds);
                     if (!b.ok) continue;
                     const uint64_t c = group_cost_ps(b, budget, tc.variant);
+                    if (all) all->push_back(std::make_pair(c, tc));
                     if (!found || c < best_cost) {
                         found = true;
                         best = b;
@@ -688,9 +690,12 @@ uint64_t pw_cost_ps(const Layer& L, int batch, int budget, int& shape)
     return best;
 }
 
+// force_tc / pw_mode: explicit values for the two testing hooks (null / -1: the process-wide ones)
 dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int budget, int max_lds,
-                      GroupPlan& g)
+                      GroupPlan& g, const TileCfg* force_tc = nullptr, int pw_mode = -1)
 {
+    const TileCfg& force = force_tc ? *force_tc : g_force;
+    const int pwm = pw_mode >= 0 ? pw_mode : g_pw_mode;
     if (first < 0 || last >= (int)net.L.size() || first > last || budget <= 0)
         return fail(DLF_ERR_INVALID_ARG, "bad group [%d,%d] budget %d", first, last, budget);
     std::vector<StageSpec> specs;
@@ -727,18 +732,18 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
     Built b;
     TileCfg tc;
     uint64_t cost = 0;
-    const bool tiled = choose_group(net, specs, batch, budget, max_lds, b, tc, cost);
-    const bool pw_ok = first == last && pw_eligible(L0, batch) && g_pw_mode != 2 &&
-                       (g_force.th <= 0 || g_pw_mode == 1 || g_pw_mode >= 3);
+    const bool tiled = choose_group(net, specs, batch, budget, max_lds, b, tc, cost, force);
+    const bool pw_ok = first == last && pw_eligible(L0, batch) && pwm != 2 &&
+                       (force.th <= 0 || pwm == 1 || pwm >= 3);
     if (pw_ok) {
         int shape = 0;
         uint64_t pc = pw_cost_ps(L0, batch, budget, shape);
-        if (g_pw_mode >= 3) {
-            shape = g_pw_mode - 3;
+        if (pwm >= 3) {
+            shape = pwm - 3;
             if (PW_KSPLIT[shape] > 1 && !pw_shape_ok(L0, shape)) shape = 0;
             pc = pw_shape_cost_ps(L0, batch, budget, shape);
         }
-        if (!tiled || g_pw_mode == 1 || g_pw_mode >= 3 || pc < cost) {
+        if (!tiled || pwm == 1 || pwm >= 3 || pc < cost) {
             DlfPwArgs& wa = g.wa;
             memset(&wa, 0, sizeof wa);
             wa.w = L0.d_w; wa.bias = L0.d_bias;
@@ -789,6 +794,7 @@ struct dlf_plan_s {
     std::vector<size_t> layer_off;   // workspace offset of each layer's output, or SIZE_MAX
     size_t ws_bytes = 0;
     char* ws = nullptr;
+    int max_lds = 160 * 1024;
 };
 
 namespace {
@@ -1141,6 +1147,7 @@ dlf_status dlf_plan(const dlf_net_t* net, int32_t batch, const dlf_tuner_opts* o
     plan->net = net;
     plan->batch = batch;
     plan->G = groups;
+    plan->max_lds = max_lds;
     // workspace: the output of each group except the last, 256-byte aligned slots
     plan->layer_off.assign(n, (size_t)-1);
     size_t off = 0;
@@ -1288,6 +1295,125 @@ static void group_pointers(const dlf_plan_s* plan, size_t g, const void* in_dev,
     *in = G.in_layer < 0 ? in_dev : plan->ws + plan->layer_off[G.in_layer];
     *res = G.res_stage >= 0 ? plan->ws + plan->layer_off[G.res_layer] : nullptr;
     *out = (g + 1 == plan->G.size()) ? out_dev : (void*)(plan->ws + plan->layer_off[G.last]);
+}
+
+dlf_status dlf_plan_refine(dlf_plan_t* plan, const void* in_dev, void* out_dev, void* hip_stream,
+                           int32_t top_k, int32_t reps, int32_t* changed)
+{
+    if (!plan || !in_dev || !out_dev || top_k <= 0 || reps <= 0)
+        return fail(DLF_ERR_INVALID_ARG, "dlf_plan_refine: bad argument");
+    if (!plan->net->has_weights) return fail(DLF_ERR_NO_WEIGHTS, "network was created without weights");
+    if (plan->ws_bytes > 0 && !plan->ws) return fail(DLF_ERR_INVALID_ARG, "no workspace bound");
+    const dlf_net_s& net = *plan->net;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // every group's input must hold real data before groups are timed one by one
+    dlf_status rs = dlf_run(plan, in_dev, out_dev, hip_stream);
+    if (rs != DLF_OK) return rs;
+    if (hipStreamSynchronize(st) != hipSuccess) return fail(DLF_ERR_HIP, "stream synchronise failed");
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return fail(DLF_ERR_HIP, "hipEventCreate failed");
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(DLF_ERR_HIP, "hipEventCreate failed"); }
+    // A group is timed the way it runs inside the network: weights and everything else it reads
+    // are no longer in the caches (a scratch buffer larger than the last-level cache is rewritten
+    // first), except its input, which the group in front of it has just produced.
+    const size_t scrub_bytes = (size_t)320 << 20;
+    void* scrub = nullptr;
+    if (hipMalloc(&scrub, scrub_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        scrub = nullptr;                 // no room: time with warm caches
+    }
+    // candidates take turns, repetition by repetition, so that none of them profits from what the
+    // others left behind (page translations, clocks)
+    auto time_groups = [&](size_t g, const std::vector<GroupPlan>& list, const void* in, const void* res,
+                           void* out, std::vector<float>& ms) {
+        dlf_status r = DLF_OK;
+        std::vector<double> sum(list.size(), 0.0);
+        for (size_t i = 0; i < list.size() && r == DLF_OK; ++i)
+            r = launch_one(plan, list[i], in, res, out, hip_stream);          // warm-up
+        for (int rep = 0; rep < reps && r == DLF_OK; ++rep)
+            for (size_t i = 0; i < list.size() && r == DLF_OK; ++i) {
+                if (scrub) (void)hipMemsetAsync(scrub, rep, scrub_bytes, st);
+                if (g > 0) {
+                    const void *pin, *pres;
+                    void* pout;
+                    group_pointers(plan, g - 1, in_dev, out_dev, &pin, &pres, &pout);
+                    r = launch_one(plan, plan->G[g - 1], pin, pres, pout, hip_stream);
+                    if (r != DLF_OK) break;
+                }
+                (void)hipEventRecord(e0, st);
+                r = launch_one(plan, list[i], in, res, out, hip_stream);
+                (void)hipEventRecord(e1, st);
+                if (hipEventSynchronize(e1) != hipSuccess && r == DLF_OK)
+                    r = fail(DLF_ERR_HIP, "event synchronise failed");
+                float t = 0;
+                if (r == DLF_OK) { (void)hipEventElapsedTime(&t, e0, e1); sum[i] += t; }
+            }
+        ms.resize(list.size());
+        for (size_t i = 0; i < list.size(); ++i) ms[i] = (float)(sum[i] / reps);
+        return r;
+    };
+    TileCfg none{};
+    none.th = 0;
+    int nchanged = 0;
+    for (size_t g = 0; g < plan->G.size() && rs == DLF_OK; ++g) {
+        const GroupPlan cur = plan->G[g];
+        if (cur.kind == GK_FC || cur.kind == GK_GAP) continue;
+        const void *in, *res;
+        void* out;
+        group_pointers(plan, g, in_dev, out_dev, &in, &res, &out);
+        std::vector<GroupPlan> cands;
+        std::vector<StageSpec> specs;
+        std::string why;
+        int kind;
+        if (!group_stages(net, cur.first, cur.last, specs, kind, why)) continue;
+        {   // the top_k tilings by modelled cost
+            std::vector<std::pair<uint64_t, TileCfg>> all;
+            Built b;
+            TileCfg tc;
+            uint64_t c = 0;
+            choose_group(net, specs, plan->batch, cur.budget, plan->max_lds, b, tc, c, none, &all);
+            std::stable_sort(all.begin(), all.end(),
+                             [](const std::pair<uint64_t, TileCfg>& x, const std::pair<uint64_t, TileCfg>& y) {
+                                 return x.first < y.first;
+                             });
+            for (size_t i = 0; i < all.size() && (int)i < top_k; ++i) {
+                GroupPlan gp;
+                if (make_group(net, plan->batch, cur.first, cur.last, cur.budget, plan->max_lds, gp,
+                               &all[i].second, 2) == DLF_OK)
+                    cands.push_back(gp);
+            }
+        }
+        if (cur.first == cur.last && pw_eligible(net.L[cur.first], plan->batch)) {
+            for (int sh = 0; sh < PW_SHAPES; ++sh) {
+                if (!pw_shape_ok(net.L[cur.first], sh)) continue;
+                GroupPlan gp;
+                if (make_group(net, plan->batch, cur.first, cur.last, cur.budget, plan->max_lds, gp, &none,
+                               3 + sh) == DLF_OK)
+                    cands.push_back(gp);
+            }
+        }
+        cands.insert(cands.begin(), cur);
+        std::vector<float> ms;
+        rs = time_groups(g, cands, in, res, out, ms);
+        if (rs != DLF_OK) break;
+        const float cur_ms = ms[0];
+        float best_ms = cur_ms;
+        int best = -1;
+        for (size_t i = 1; i < cands.size(); ++i)
+            if (ms[i] < best_ms) { best_ms = ms[i]; best = (int)i; }
+        // A candidate replaces the planned configuration only if it is clearly faster: timed one
+        // by one, kernels of 15-20 us differ by a microsecond or two from how they run between
+        // their neighbours in the network, in either direction.
+        if (rs == DLF_OK && best >= 0 && best_ms < cur_ms * 0.90f) {
+            plan->G[g] = cands[best];
+            ++nchanged;
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (scrub) (void)hipFree(scrub);
+    if (rs == DLF_OK && changed) *changed = nchanged;
+    return rs;
 }
 
 dlf_status dlf_run_profiled(const dlf_plan_t* plan, const void* in_dev, void* out_dev, void* hip_stream,

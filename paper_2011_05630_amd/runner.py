@@ -34,6 +34,16 @@ class Session:
         B.dlf_plan_bind_workspace(self.plan, self.ws.data_ptr(), self.ws.numel())
         self.groups = B.dlf_plan_groups(self.plan)
 
+    def refine(self, x, top_k=6, reps=5):
+        """Measured refinement of the plan on the input tensor x; -> number of groups changed."""
+        assert x.is_cuda and x.dtype == torch.float16 and x.is_contiguous()
+        assert tuple(x.shape) == self.in_shape, (x.shape, self.in_shape)
+        out = torch.empty(self.out_shape, dtype=torch.float16, device=self.device)
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        n = B.dlf_plan_refine(self.plan, x.data_ptr(), out.data_ptr(), stream, top_k, reps)
+        self.groups = B.dlf_plan_groups(self.plan)
+        return n
+
     def layer_shape(self, i):
         if i < 0:
             return self.in_shape

@@ -167,6 +167,32 @@ def test_run_is_repeatable_and_async_on_a_side_stream():
     s.close()
 
 
+def test_measured_refinement_keeps_the_results():
+    """dlf_plan_refine times alternative tilings of every group and may swap them in: the partition
+    stays, and whatever it chose still computes the network."""
+    from oracle import oracle as o
+    layers = [nets.conv(3, 32, 3, 2, 1, "relu6"), nets.dwconv(32, 3, 1, "relu6"),
+              nets.conv(32, 64, 1, 1, 0, "relu6"), nets.dwconv(64, 3, 2, "relu6"),
+              nets.conv(64, 128, 1, 1, 0, "relu6"), nets.conv(128, 128, 3, 1, 1, "relu"),
+              nets.conv(128, 256, 1, 1, 0, "relu")]
+    net = dict(name="refine", layers=layers, in_h=64, in_w=64, in_c=3, input_dist="normal")
+    x, ws, bs = gen.make_params(net, 4)
+    ref = o.run_net(net, x, ws, bs)
+    s = _session(net, 4, ws, bs)
+    xt = torch.from_numpy(x).cuda()
+    before = [(g["first"], g["last"], g["budget"]) for g in s.groups]
+    y0 = s.run(xt).clone()
+    torch.cuda.synchronize()
+    changed = s.refine(xt, top_k=6, reps=2)
+    assert 0 <= changed <= len(before)
+    assert [(g["first"], g["last"], g["budget"]) for g in s.groups] == before
+    y1 = s.run(xt)
+    torch.cuda.synchronize()
+    compare(y0.cpu().numpy(), ref, "before refinement")
+    compare(y1.cpu().numpy(), ref, "after refinement")
+    s.close()
+
+
 def test_error_paths_return_status_not_crash():
     from paper_2011_05630_amd import binding as B
     net = nets.chain4(256)
