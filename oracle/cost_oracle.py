@@ -183,7 +183,7 @@ def group_stages(ni, first, last):
 
 def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc, max_lds):
     """Per-tile quantities of one candidate tiling, or None if it does not fit.
-    Returns (ntiles, lds_bytes, tile_cycles, tile_hbm_bytes, tile_l2_bytes)."""
+    Returns (ntiles, lds_bytes, tile_cycles, tile_hbm_bytes, tile_l2_bytes, tile_mma_cycles)."""
     Ls = ni.layers
     ns = len(specs)
     FC, FP = VAR_FC[variant], VAR_FP[variant]
@@ -289,7 +289,7 @@ def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc
         return None
 
     # ---- cycles one workgroup spends on one tile ----
-    cyc, l2 = C_TILE, 0
+    cyc, l2, mma_total = C_TILE, 0, 0
     s0 = S[0]
     cin0 = chan_local if (s0["kind"] != CONV and chan_local) else s0["cin"]
     if stream0:
@@ -312,11 +312,12 @@ def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc
             mma_waves = MMA_WAVES if streaming else WAVES
             if streaming and nitems > mma_waves:
                 return None
-            mma = cdiv(nitems, 4) * st["nsteps"] * FC * FP * MFMA_CYCLES * (16 if FP >= 4 else 20) // 10
+            mma = cdiv(nitems, 4) * st["nsteps"] * FC * FP * MFMA_CYCLES * (13 if FP >= 4 else 20) // 10
             if streaming:
                 nrounds = st["cin_pad"] // st["kc"]
                 vecs = cdiv(st["ih"] * st["iw"] * (st["kc"] // 8), LOAD_THREADS)
                 mma = max(mma, nrounds * (C_ROUND + vecs * C_ROUND_VEC)) + nrounds * C_BARRIER
+            mma_total += mma
             cyc += mma + cdiv(nitems, mma_waves) * FC * FP * C_EPI
             l2 += nitems * FC * st["nsteps"] * 1024
         else:
@@ -332,19 +333,20 @@ def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc
         hbm = s0["ih"] * s0["iw"] * s0["im_cin"] * 2 + th * tw * cout_l * 2
     elif s0["kind"] == CONV and s0["im2col"]:
         hbm = s0["rh"] * s0["rw"] * s0["im_stride"] * s0["im_stride"] * s0["im_cin"] * 2 + th * tw * cout_l * 2
-    return ntiles, lds_bytes, cyc, hbm, l2
+    return ntiles, lds_bytes, cyc, hbm, l2, mma_total
 
 
 def tiling_cost_ps(built, budget, variant):
-    ntiles, lds_bytes, cyc, hbm, l2 = built
+    ntiles, lds_bytes, cyc, hbm, l2, mma_total = built
     occ = max(1, min(VAR_OCC[variant], LDS_PER_CU // max(lds_bytes, 1)))
     cu = min(budget, ntiles)
     wg = min(ntiles, budget * occ)
     conc = cdiv(wg, cu)
     tiles_cu = cdiv(ntiles, cu)
-    compute = tiles_cu * cyc
-    if conc >= 2:
-        compute = compute * 3 // 4
+    # latency chains outside the MFMA loops: paid in full by a workgroup alone on its CU, filled in
+    # by a second workgroup down to the time the shared matrix pipes are busy
+    tile = mma_total + (cyc - mma_total) * 5 // 4
+    compute = tiles_cu * (max(mma_total, tile * 3 // 5) if conc >= 2 else tile)
     bw = min(CU_BYTES_PER_CYCLE, max(1, HBM_BYTES_PER_CYCLE // cu))
     mem = tiles_cu * (hbm // bw + l2 // L2_BYTES_PER_CYCLE)
     return (C_LAUNCH + max(compute, mem)) * PS_PER_CYCLE

@@ -306,6 +306,7 @@ struct Built {
     int lds_bytes = 0;
     int ntiles = 0;
     int64_t tile_cycles = 0;      // modelled cycles one workgroup spends per tile (compute side)
+    int64_t tile_mma_cycles = 0;  // the part of them that occupies the matrix pipes
     int64_t tile_hbm_bytes = 0;   // activation bytes per tile (HBM side)
     int64_t tile_l2_bytes = 0;    // weight bytes per tile (L2 side)
     DlfGroupArgs ga;
@@ -463,7 +464,7 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
     b.lds_bytes = (int)(lds_halfs * 2);
 
     // ---- cost model: cycles one workgroup spends on one tile ----
-    int64_t cyc = C_TILE, l2 = 0;
+    int64_t cyc = C_TILE, l2 = 0, mma_total = 0;
     const DlfStage& s0 = ga.st[0];
     const int cin0 = (s0.kind != DLF_ST_CONV && chan_local) ? chan_local : s0.cin;
     if (tc.stream0) {
@@ -491,12 +492,13 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
             // items queue up on the 4 SIMDs; measured rounds run at about half the MFMA issue rate
             // (a 32 x 128 register tile needs half the weight traffic per MFMA and runs closer to
             //  the issue rate: 1.6 instead of 2)
-            int64_t mma = (int64_t)ceil_div(nitems, 4) * st.nsteps * FCv * FPv * MFMA_CYCLES * (FPv >= 4 ? 16 : 20) / 10;
+            int64_t mma = (int64_t)ceil_div(nitems, 4) * st.nsteps * FCv * FPv * MFMA_CYCLES * (FPv >= 4 ? 13 : 20) / 10;
             if (streaming) {
                 const int64_t nrounds = st.cin_pad / st.kc;
                 const int64_t vecs = ceil_div(st.ih * st.iw * (st.kc / 8), DLF_LOAD_THREADS);
                 mma = std::max(mma, nrounds * (C_ROUND + vecs * C_ROUND_VEC)) + nrounds * C_BARRIER;
             }
+            mma_total += mma;
             cyc += mma + (int64_t)ceil_div(nitems, mma_waves) * FCv * FPv * C_EPI;
             l2 += (int64_t)nitems * FCv * st.nsteps * 1024;
         } else {
@@ -519,6 +521,7 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
                            + (int64_t)tc.th * tc.tw * cout_l * 2;
     b.tile_l2_bytes = l2;
     b.tile_cycles = cyc;
+    b.tile_mma_cycles = mma_total;
     b.ok = true;
     return b;
 }
@@ -531,8 +534,12 @@ uint64_t group_cost_ps(const Built& b, int budget, int variant)
     const int64_t wg = std::min<int64_t>(b.ntiles, (int64_t)budget * occ);
     const int64_t conc = (wg + cu - 1) / cu;              // workgroups sharing a CU
     const int64_t tiles_cu = (b.ntiles + cu - 1) / cu;    // tiles one CU works through
-    int64_t compute = tiles_cu * b.tile_cycles;
-    if (conc >= 2) compute = compute * 3 / 4;             // phases of two workgroups overlap
+    // Everything but the MFMA loops (staging, epilogues, VALU stages, stores, barriers) is a chain
+    // of latencies: a workgroup alone on its CU pays them in full (5/4 of the fitted terms); two
+    // workgroups fill each other's gaps (3/5 of the total), down to the time the matrix pipes
+    // they share are busy.
+    const int64_t tile = b.tile_mma_cycles + (b.tile_cycles - b.tile_mma_cycles) * 5 / 4;
+    int64_t compute = tiles_cu * (conc >= 2 ? std::max(b.tile_mma_cycles, tile * 3 / 5) : tile);
     const int64_t bw = std::min<int64_t>(CU_BYTES_PER_CYCLE, std::max<int64_t>(1, HBM_BYTES_PER_CYCLE / cu));
     const int64_t mem = tiles_cu * (b.tile_hbm_bytes / bw + b.tile_l2_bytes / L2_BYTES_PER_CYCLE);
     return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
