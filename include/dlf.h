@@ -159,13 +159,15 @@ dlf_status dlf_plan_group_io(const dlf_plan_t* plan, int32_t g, int32_t* in_laye
  * then the candidates, on hip_stream, and waits for them (this call synchronises the stream).
  * *changed (HOST, may be null): number of groups whose configuration changed.  The plan must
  * not be in use by another thread.  dlf_plan_group and dlf_plan_group_config report the new
- * configuration; model_cost is the modelled cost of that configuration. */
+ * configuration; model_cost is the modelled cost of that configuration.  With the environment
+ * variable DLF_DEBUG set, one line per group with the measured times goes to stderr. */
 dlf_status dlf_plan_refine(dlf_plan_t* plan, const void* in_dev, void* out_dev, void* hip_stream,
                            int32_t top_k, int32_t reps, int32_t* changed);
 
 /* Testing hook: th > 0 forces tile th x tw, register-tile variant, channel slicing, streaming and
  * channels per streaming round (kc: 32, 64 or 128; 0 = 32) for every group planned afterwards
- * (groups it does not fit become infeasible); th = 0 restores the automatic choice.
+ * (groups it does not fit become infeasible; for a fully connected layer nslices = 1, 2, 4 or 8
+ * is the number of K slices); th = 0 restores the automatic choice.
  * Process-wide, not thread-safe. */
 void dlf_debug_force_config(int32_t th, int32_t tw, int32_t variant, int32_t nslices,
                             int32_t slice_c, int32_t stream0, int32_t kc);

@@ -38,6 +38,7 @@ C_STORE_VEC = 80
 C_STORE = 1600
 MFMA_CYCLES = 32
 FC_BYTES_PER_CYCLE = 1400
+FC_SPLIT_HBM_BYTES_PER_CYCLE = 1900
 GAP_BYTES_PER_CYCLE = 1000
 # FC, FP, items in flight per CU, cycles per K step (alone, per item sharing the CU), K split
 PW_SHAPES = ((2, 2, 8, 470, 64, 1), (1, 1, 16, 300, 100, 1), (2, 2, 2, 470, 256, 4))
@@ -448,8 +449,17 @@ def group_cost(net, batch, first, last, budget, max_lds=LDS_PER_CU, ni=None):
     if specs is None:
         return None
     if specs == "fc":
-        wbytes = ni.ncb[first] * ni.nsteps[first] * 1024 * cdiv(batch, 32)
-        return (C_LAUNCH + C_LAT + wbytes // FC_BYTES_PER_CYCLE) * PS_PER_CYCLE
+        nbb = cdiv(batch, 32)
+        ncb, nsteps = ni.ncb[first], ni.nsteps[first]
+        best = (C_LAUNCH + C_LAT + ncb * nsteps * 1024 * nbb // FC_BYTES_PER_CYCLE) * PS_PER_CYCLE
+        # split-K form: pairs of channel blocks, K in 2 / 4 / 8 slices, a second launch adds them
+        for ks in (2, 4, 8):
+            if cdiv(ncb, 2) * ks > 256 or nsteps < 64 * ks:
+                continue
+            intake = 3 * cdiv(nsteps, ks) * 1024 * nbb // PWB_BYTES_PER_CYCLE
+            hbm = ncb * nsteps * 1024 * nbb // FC_SPLIT_HBM_BYTES_PER_CYCLE
+            best = min(best, (2 * C_LAUNCH + C_LAT + max(intake, hbm)) * PS_PER_CYCLE)
+        return best
     if specs == "gap":
         h, w, c = ni.ish[first]
         return (C_LAUNCH + C_LAT + batch * h * w * c * 2 // GAP_BYTES_PER_CYCLE) * PS_PER_CYCLE

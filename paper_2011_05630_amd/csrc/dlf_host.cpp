@@ -161,6 +161,7 @@ struct GroupPlan {
     int first = 0, last = 0, budget = 0;
     int kind = GK_GROUP;
     int variant = 0, lds_bytes = 0, grid = 0, occ = 1;
+    size_t scratch_bytes = 0, scratch_off = 0;   // device scratch in the workspace (split-K FC)
     int th = 0, tw = 0;
     uint64_t cost = 0;
     int in_layer = -1;   // producer of the group's input (-1 = net input)
@@ -199,6 +200,7 @@ const int64_t C_STORE_VEC = 80;             // per 512 stored 16-byte vectors
 const int64_t C_STORE = 1600;
 const int64_t MFMA_CYCLES = 32;             // one 32x32x16 MFMA on one SIMD
 const int64_t FC_BYTES_PER_CYCLE = 1400;    // weight streaming rate of the FC kernel
+const int64_t FC_SPLIT_HBM_BYTES_PER_CYCLE = 1900;   // the same with K split over all CUs
 const int64_t GAP_BYTES_PER_CYCLE = 1000;
 // pointwise kernel, per item shape: register tile (FC x FP blocks of 32), operand ring depth,
 // independent waves per CU
@@ -698,6 +700,25 @@ uint64_t pw_cost_ps(const Layer& L, int batch, int budget, int& shape)
 }
 
 // force_tc / pw_mode: explicit values for the two testing hooks (null / -1: the process-wide ones)
+// Fully connected layer: one workgroup per 32 output channels streaming all of K, or, where that is
+// cheaper, pairs of channel blocks with K split 2, 4 or 8 ways (at most 256 workgroups), a second
+// launch adding the slices: what a workgroup then takes in per K step is 3 KiB for two MFMAs.
+uint64_t fc_cost_ps(const Layer& L, int batch, int& ksplit)
+{
+    const int64_t nbb = ceil_div(batch, 32);
+    const int64_t wbytes = (int64_t)L.ncb * L.nsteps * 1024 * nbb;
+    uint64_t best = (uint64_t)((C_LAUNCH + C_LAT + wbytes / FC_BYTES_PER_CYCLE) * PS_PER_CYCLE);
+    ksplit = 1;
+    for (int ks = 2; ks <= 8; ks *= 2) {
+        if (ceil_div(L.ncb, 2) * ks > 256 || L.nsteps < 64 * ks) continue;
+        const int64_t intake = 3 * (int64_t)ceil_div(L.nsteps, ks) * 1024 * nbb / PWB_BYTES_PER_CYCLE;
+        const int64_t hbm = wbytes / FC_SPLIT_HBM_BYTES_PER_CYCLE;
+        const uint64_t c = (uint64_t)((2 * C_LAUNCH + C_LAT + std::max(intake, hbm)) * PS_PER_CYCLE);
+        if (c < best) { best = c; ksplit = ks; }
+    }
+    return best;
+}
+
 dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int budget, int max_lds,
                       GroupPlan& g, const TileCfg* force_tc = nullptr, int pw_mode = -1)
 {
@@ -720,8 +741,12 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
         fa.w = L0.d_w; fa.bias = L0.d_bias;
         fa.batch = batch; fa.k = L0.d.cin; fa.cout = L0.d.cout; fa.ncb = L0.ncb;
         fa.nsteps = L0.nsteps; fa.act = L0.d.act;
-        const int64_t wbytes = (int64_t)L0.ncb * L0.nsteps * 1024 * ceil_div(batch, 32);
-        g.cost = (uint64_t)((C_LAUNCH + C_LAT + wbytes / FC_BYTES_PER_CYCLE) * PS_PER_CYCLE);
+        int ksplit = 1;
+        g.cost = fc_cost_ps(L0, batch, ksplit);
+        if (force.th > 0 && (force.nslices == 1 || force.nslices == 2 || force.nslices == 4 || force.nslices == 8))
+            ksplit = force.nslices;                     // testing hook
+        fa.ksplit = ksplit;
+        g.scratch_bytes = ksplit > 1 ? (size_t)ksplit * ceil_div(batch, 32) * L0.ncb * 4096 : 0;
         g.grid = L0.ncb;
         g.th = g.tw = 1;
         return DLF_OK;
@@ -1164,6 +1189,11 @@ dlf_status dlf_plan(const dlf_net_t* net, int32_t batch, const dlf_tuner_opts* o
         plan->layer_off[groups[g].last] = off;
         off += (bytes + 255) & ~(size_t)255;
     }
+    for (GroupPlan& G : plan->G)
+        if (G.scratch_bytes > 0) {
+            G.scratch_off = off;
+            off += (G.scratch_bytes + 255) & ~(size_t)255;
+        }
     plan->ws_bytes = off;
     for (const GroupPlan& G : groups) {
         const bool in_ok = G.in_layer < 0 || plan->layer_off[G.in_layer] != (size_t)-1;
@@ -1258,6 +1288,10 @@ static dlf_status launch_one(const dlf_plan_s* plan, const GroupPlan& G, const v
     if (G.kind == GK_FC) {
         DlfFcArgs fa = G.fa;
         fa.x = in; fa.y = out;
+        if (fa.ksplit > 1) {
+            if (!plan->ws) return fail(DLF_ERR_INVALID_ARG, "no workspace bound");
+            fa.part = (float*)(plan->ws + G.scratch_off);
+        }
         e = dlf_launch_fc(&fa, stream);
     } else if (G.kind == GK_GAP) {
         DlfGapArgs pa = G.pa;
@@ -1408,6 +1442,12 @@ dlf_status dlf_plan_refine(dlf_plan_t* plan, const void* in_dev, void* out_dev, 
         int best = -1;
         for (size_t i = 1; i < cands.size(); ++i)
             if (ms[i] < best_ms) { best_ms = ms[i]; best = (int)i; }
+        if (getenv("DLF_DEBUG"))
+            fprintf(stderr, "dlf_plan_refine [%d,%d]: planned %.2f us (variant %d tile %dx%d), best of %zu: %.2f us (kind %d variant %d tile %dx%d lds %d)\n",
+                    cur.first, cur.last, cur_ms * 1e3, cur.variant, cur.th, cur.tw, cands.size() - 1, best_ms * 1e3,
+                    best >= 0 ? cands[best].kind : cur.kind, best >= 0 ? cands[best].variant : cur.variant,
+                    best >= 0 ? cands[best].th : cur.th, best >= 0 ? cands[best].tw : cur.tw,
+                    best >= 0 ? cands[best].lds_bytes : cur.lds_bytes);
         // A candidate replaces the planned configuration only if it is clearly faster: timed one
         // by one, kernels of 15-20 us differ by a microsecond or two from how they run between
         // their neighbours in the network, in either direction.

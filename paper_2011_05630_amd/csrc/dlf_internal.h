@@ -75,6 +75,8 @@ struct DlfFcArgs {
     const void* w;        // packed fragments
     const float* bias;
     int32_t batch, k, cout, ncb, nsteps, act;
+    int32_t ksplit;       // > 1: K is split over ksplit workgroups per pair of channel blocks ...
+    float* part;          // ... which leave fp32 partial sums here: [batch block][ksplit][ncb][16][64]
 };
 
 // Pointwise (1x1, pad 0) convolution run without tiles or barriers: every wave owns work items

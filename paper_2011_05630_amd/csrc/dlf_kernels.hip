@@ -1399,6 +1399,98 @@ __global__ __launch_bounds__(DLF_FC_WAVES * 64) void k_fc(const DlfFcArgs a)
     }
 }
 
+// Split-K form of the fully connected layer, for long K and few output channels per CU (VGG's
+// 25088 -> 4096): a workgroup takes two 32-channel blocks (the activation fragment of a K step
+// feeds two MFMAs) and one of `ksplit` slices of K, so that the operand bytes a CU has to take in
+// drop from 2 KiB to 0.75 KiB per MFMA and ksplit times as many CUs share them.  The partial sums
+// (fp32, in the MFMA accumulator layout) go to scratch memory; k_fc_fin adds the slices in a fixed
+// order, the bias and the activation.
+__global__ __launch_bounds__(DLF_FC_WAVES * 64) void k_fc_sk(const DlfFcArgs a)
+{
+    __shared__ float red[DLF_FC_WAVES][16][64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int ks = blockIdx.x % a.ksplit, cbp = blockIdx.x / a.ksplit;
+    const int cb0 = cbp * 2, cb1 = min(cb0 + 1, a.ncb - 1);
+    const half_t* x = (const half_t*)a.x;
+    const h8* w0 = (const h8*)a.w + (size_t)cb0 * a.nsteps * 64 + lane;
+    const h8* w1 = (const h8*)a.w + (size_t)cb1 * a.nsteps * 64 + lane;
+    const int per_ks = (a.nsteps + a.ksplit - 1) / a.ksplit;
+    const int s0 = ks * per_ks, s1 = min(a.nsteps, s0 + per_ks);
+    const int per = (max(s1 - s0, 0) + DLF_FC_WAVES - 1) / DLF_FC_WAVES;
+    const int t0 = s0 + wave * per, t1 = min(s1, t0 + per);
+    for (int nb = 0; nb < a.batch; nb += 32) {
+        const int img = min(nb + l32, a.batch - 1);
+        const half_t* xr = x + (size_t)img * a.k + lhi * 8;
+        f16v acc0, acc1;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { acc0[i] = 0.0f; acc1[i] = 0.0f; }
+        h8 av0[8], av1[8], bv[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int t = t0 + j;
+            if (t < t1) {
+                av0[j] = w0[(size_t)t * 64];
+                av1[j] = w1[(size_t)t * 64];
+                h8 b = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (t * 16 + lhi * 8 + 8 <= a.k) b = *(const h8*)(xr + t * 16);
+                bv[j] = b;
+            }
+        }
+        for (int tb = t0; tb < t1; tb += 8) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int t = tb + j;
+                if (t < t1) {
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(av0[j], bv[j], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(av1[j], bv[j], acc1, 0, 0, 0);
+                    const int tn = t + 8;
+                    if (tn < t1) {
+                        av0[j] = w0[(size_t)tn * 64];
+                        av1[j] = w1[(size_t)tn * 64];
+                        h8 b = {0, 0, 0, 0, 0, 0, 0, 0};
+                        if (tn * 16 + lhi * 8 + 8 <= a.k) b = *(const h8*)(xr + tn * 16);
+                        bv[j] = b;
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        float* pbase = a.part + (size_t)((nb >> 5) * a.ksplit + ks) * a.ncb * 1024;
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+            if (f == 1 && cb0 + 1 >= a.ncb) break;          // uniform: an odd number of blocks
+#pragma unroll
+            for (int i = 0; i < 16; ++i) red[wave][i][lane] = f == 0 ? acc0[i] : acc1[i];
+            __syncthreads();
+            for (int e = tid; e < 16 * 64; e += DLF_FC_WAVES * 64) {
+                const int i = e >> 6, ln = e & 63;
+                float sum = 0.0f;
+#pragma unroll
+                for (int w = 0; w < DLF_FC_WAVES; ++w) sum += red[w][i][ln];
+                pbase[(size_t)(cb0 + f) * 1024 + e] = sum;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_fc_fin(const DlfFcArgs a)
+{
+    const int cb = blockIdx.x % a.ncb, nbi = blockIdx.x / a.ncb;
+    half_t* y = (half_t*)a.y;
+    for (int e = threadIdx.x; e < 16 * 64; e += 256) {
+        const int i = e >> 6, ln = e & 63;
+        float s = 0.0f;
+        for (int ks = 0; ks < a.ksplit; ++ks)
+            s += a.part[((size_t)(nbi * a.ksplit + ks) * a.ncb + cb) * 1024 + e];
+        const int co = cb * 32 + (i >> 2) * 8 + (ln >> 5) * 4 + (i & 3);
+        const int im = nbi * 32 + (ln & 31);
+        if (co < a.cout && im < a.batch)
+            y[(size_t)im * a.cout + co] = (half_t)apply_act(s + a.bias[co], a.act);
+    }
+}
+
 // Global average pooling: fp32 sum over H*W, mean, fp16.
 __global__ __launch_bounds__(256) void k_gap(const DlfGapArgs a)
 {
@@ -1466,6 +1558,17 @@ extern "C" int dlf_launch_group(const DlfGroupArgs* a, int variant, int grid, in
 
 extern "C" int dlf_launch_fc(const DlfFcArgs* a, void* stream)
 {
+    if (a->ksplit > 1) {
+        if (a->part == nullptr) return (int)hipErrorInvalidValue;
+        // a stop event requested for "the next launch" belongs to the second of the two
+        hipEvent_t stop = g_ev_stop;
+        g_ev_stop = nullptr;
+        launch(k_fc_sk, dim3(((a->ncb + 1) / 2) * a->ksplit), dim3(DLF_FC_WAVES * 64), 0,
+               (hipStream_t)stream, *a);
+        g_ev_stop = stop;
+        launch(k_fc_fin, dim3(a->ncb * ((a->batch + 31) / 32)), dim3(256), 0, (hipStream_t)stream, *a);
+        return (int)hipGetLastError();
+    }
     launch(k_fc, dim3(a->ncb), dim3(DLF_FC_WAVES * 64), 0, (hipStream_t)stream, *a);
     return (int)hipGetLastError();
 }

@@ -284,6 +284,33 @@ def test_fc_and_global_avgpool():
     compare(got, ref, "fc-fc batch 37")
 
 
+@pytest.mark.parametrize("k_hw,k_c,cout,batch", [(8, 64, 1000, 3), (7, 96, 70, 40), (4, 512, 96, 16)])
+def test_fc_split_k(k_hw, k_c, cout, batch):
+    """Long K, few output channels: the planner splits K over workgroups (pairs of 32-channel
+    blocks, an odd number of blocks and two batch blocks included) and a second launch adds the
+    slices."""
+    announce("fc split-K", k_hw, k_c, cout, batch)
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    layers = [nets.fc(k_hw * k_hw * k_c, cout, "relu")]
+    net = _mk(layers, k_hw, k_hw, k_c, dist="normal")
+    x, ws, bs = gen.make_params(net, batch)
+    from oracle import oracle as o
+    ref = o.run_net(net, x, ws, bs)
+    for ksplit in (2, 4, 8):
+        B.dlf_debug_force_config(1, 1, 0, ksplit, 0, 0, 32)
+        try:
+            s = Session(net, batch, ws, bs)
+        finally:
+            B.dlf_debug_force_config(0, 0, 0, 1, 0, 0, 32)
+        try:
+            assert B.dlf_plan_workspace_bytes(s.plan) > 0, "the split-K form keeps partial sums in the workspace"
+            got = s.run_numpy(x)
+        finally:
+            s.close()
+        compare(got, ref, "fc %d->%d batch %d, K in %d slices" % (k_hw * k_hw * k_c, cout, batch, ksplit))
+
+
 @pytest.mark.parametrize("depth,c,hw,tile", [(2, 16, 32, (8, 8)), (3, 32, 21, (8, 8)),
                                              (4, 16, 19, (4, 8)), (2, 64, 30, (16, 16)),
                                              (4, 64, 56, (14, 14))])
