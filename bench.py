@@ -57,6 +57,10 @@ def workloads():
         "vgg16": (nets.vgg16, 16),
         "resnet50": (nets.resnet50, 32),
         "mobilenet_v1": (nets.mobilenet_v1, 64),
+        # the other networks of the paper's evaluation (Sec. V, table of networks)
+        "vgg19": (nets.vgg19, 16),
+        "resnet18": (nets.resnet18, 32),
+        "alexnet": (nets.alexnet, 32),
     }
     for c in (16, 32, 64, 128, 256):
         w["chain4_c%d" % c] = ((lambda c=c: nets.chain4(c)), 8)
@@ -122,8 +126,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet50")
     ap.add_argument("--batch", type=int, default=0)
-    ap.add_argument("--plan", default="dp", choices=["dp", "greedy", "unfused"])
+    ap.add_argument("--plan", default="dp", choices=["dp", "greedy", "unfused", "layerwise", "maxfuse"],
+                    help="dp: exact minimum of the cost model; greedy: Algorithm 1; unfused: every layer "
+                         "alone on --budget CUs; layerwise: every layer alone, budget by Eq. 5; "
+                         "maxfuse: longest runnable groups on the largest budget")
     ap.add_argument("--budget", type=int, default=256, help="budget of every group of --plan unfused")
+    ap.add_argument("--fixed-budget", type=int, default=0,
+                    help="one budget for all groups of --plan greedy / layerwise / maxfuse (0: the tuner's)")
     ap.add_argument("--refine", type=int, default=0,
                     help="measured refinement of the plan before timing: candidates per group (0 = off)")
     ap.add_argument("--table", action="store_true", help="per-group table on stderr")
@@ -155,7 +164,11 @@ def main():
     if args.plan == "dp":
         plan = dict(mode=B.TUNER_DP)
     elif args.plan == "greedy":
-        plan = dict(mode=B.TUNER_GREEDY)
+        plan = dict(mode=B.TUNER_GREEDY, fixed_budget=args.fixed_budget)
+    elif args.plan == "layerwise":
+        plan = dict(mode=B.TUNER_LAYERWISE, fixed_budget=args.fixed_budget)
+    elif args.plan == "maxfuse":
+        plan = dict(mode=B.TUNER_MAXFUSE, fixed_budget=args.fixed_budget)
     else:
         plan = dict(mode=B.TUNER_MANUAL, group_last=list(range(n)), group_budget=[args.budget] * n)
     s = Session(net, batch, ws, bs, **plan)
@@ -269,7 +282,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": "%s_b%d" % (net["name"], batch), "batch": batch,
-                   "plan": args.plan + ("+refine%d" % args.refine if args.refine > 0 else ""),
+                   "plan": args.plan + ("@%d" % args.fixed_budget if args.fixed_budget > 0 else "")
+                   + ("@%d" % args.budget if args.plan == "unfused" else "")
+                   + ("+refine%d" % args.refine if args.refine > 0 else ""),
                    "groups_refined": refined, "groups": len(s.groups), "layers": n,
                    "input": "%dx%dx%d" % (net["in_h"], net["in_w"], net["in_c"])},
         "event_ms_per_step": event_ms_per_step,

@@ -66,7 +66,12 @@ typedef struct dlf_plan_s dlf_plan_t;
 /* Tuner modes. */
 enum { DLF_TUNER_DP = 0,      /* exact minimum of the additive cost model over all plans        */
        DLF_TUNER_GREEDY = 1,  /* Algorithm 1 (greedy O(n) pass), then split of infeasible blocks */
-       DLF_TUNER_MANUAL = 2   /* caller gives group_last[] and budget[]                          */ };
+       DLF_TUNER_MANUAL = 2,  /* caller gives group_last[] and budget[]                          */
+       /* The comparison strategies of the paper's evaluation (Sec. V, table of strategies):      */
+       DLF_TUNER_LAYERWISE = 3, /* no fusion; each layer's budget from Eq. 5 (strategy 3), or      */
+                                /* fixed_budget for all (strategies 1 and 2)                       */
+       DLF_TUNER_MAXFUSE = 4    /* longest groups the kernels can run, left to right, on the       */
+                                /* largest allowed budget or fixed_budget (strategy 4)             */ };
 
 typedef struct {
     int32_t mode;                     /* DLF_TUNER_*                                             */
@@ -82,6 +87,8 @@ typedef struct {
     const int32_t* manual_budget;     /* DLF_TUNER_MANUAL: budget of each group                  */
     int32_t manual_n;                 /* number of manual groups                                 */
     int32_t max_lds_bytes;            /* on-chip memory one workgroup may use; <= 0 => 160 KiB   */
+    int32_t fixed_budget;             /* > 0: every group of a GREEDY / LAYERWISE / MAXFUSE plan  */
+                                      /* gets this budget (GREEDY: strategy 5 of the paper)      */
 } dlf_tuner_opts;
 
 /* Builds a network from `n` layers on an in_h x in_w x in_c input.  Validates and infers

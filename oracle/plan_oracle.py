@@ -165,3 +165,36 @@ def algorithm1(layers, ops, opcount_critical, alpha=0.316, beta=0.659, k=1.0, b=
             part.append(n - 1)
             mps.append(min(allowed))
     return part, mps
+
+
+def layerwise_budgets(layers, ops, alpha=0.316, beta=0.659, k=1.0, b=0.0, allowed=(1, 2, 4, 8, 16, 32),
+                      fixed_budget=0):
+    """The no-fusion strategies of the evaluation (Sec. V, table of strategies): every layer is a
+    block of its own.  Strategy 3 gives each convolution / FC layer the MP of Eq. 5 (rounded as a
+    block of one layer would be); strategies 1 and 2 use one MP for all (fixed_budget).  A layer
+    without Eq.-5 features (pooling) takes the MP of the convolution before it (the smallest
+    allowed MP if there is none).  Returns the per-layer MP list."""
+    out = []
+    cur = min(allowed)
+    for i, L in enumerate(layers):
+        if L["op"] in CONV_LIKE:
+            cur = round_block_mp(layer_mp(L, ops[i], alpha, beta, k, b, max(allowed)), allowed)
+        out.append(fixed_budget if fixed_budget > 0 else cur)
+    return out
+
+
+def max_fusion(n, feasible, budget):
+    """Strategy 4 ("all fusion, maximal MP") as far as the kernels allow: walking left to right,
+    each block is the longest range [first, last] that can run as one group (feasible(first, last)
+    is the caller's test), all on the same MP.  Returns [(first, last, budget), ...]."""
+    out = []
+    first = 0
+    while first < n:
+        last = n - 1
+        while not feasible(first, last):
+            last -= 1
+            assert last >= first, "a single layer must be feasible"
+        out.append((first, last, budget))
+        first = last + 1
+    return out
+

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(HERE, "libdlf.so")
 
 OP = {"conv": 0, "dwconv": 1, "fc": 2, "maxpool": 3, "gavgpool": 4}
 ACT = {"none": 0, "relu": 1, "relu6": 2}
-TUNER_DP, TUNER_GREEDY, TUNER_MANUAL = 0, 1, 2
+TUNER_DP, TUNER_GREEDY, TUNER_MANUAL, TUNER_LAYERWISE, TUNER_MAXFUSE = 0, 1, 2, 3, 4
 DLF_OK = 0
 DLF_ERR_INFEASIBLE = 4
 
@@ -40,7 +40,8 @@ class TunerOpts(ctypes.Structure):
                 ("mp_scale", ctypes.c_double), ("mp_offset", ctypes.c_double),
                 ("manual_group_last", ctypes.POINTER(ctypes.c_int32)),
                 ("manual_budget", ctypes.POINTER(ctypes.c_int32)),
-                ("manual_n", ctypes.c_int32), ("max_lds_bytes", ctypes.c_int32)]
+                ("manual_n", ctypes.c_int32), ("max_lds_bytes", ctypes.c_int32),
+                ("fixed_budget", ctypes.c_int32)]
 
 
 _lib = None
@@ -169,7 +170,7 @@ def dlf_net_layer_info(net, i):
 
 def dlf_plan(net, batch, mode=TUNER_DP, budgets=None, group_last=None, group_budget=None,
              opcount_critical=0.0, alpha=0.0, beta=0.0, mp_scale=0.0, mp_offset=0.0,
-             max_lds_bytes=0):
+             max_lds_bytes=0, fixed_budget=0):
     o = TunerOpts()
     o.mode = mode
     keep = []
@@ -185,6 +186,7 @@ def dlf_plan(net, batch, mode=TUNER_DP, budgets=None, group_last=None, group_bud
     o.opcount_critical, o.alpha, o.beta = opcount_critical, alpha, beta
     o.mp_scale, o.mp_offset = mp_scale, mp_offset
     o.max_lds_bytes = max_lds_bytes
+    o.fixed_budget = fixed_budget
     h = ctypes.c_void_p()
     _check(lib().dlf_plan(net, batch, ctypes.byref(o), ctypes.byref(h)))
     return h

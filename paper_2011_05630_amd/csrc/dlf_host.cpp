@@ -840,31 +840,44 @@ const int DEFAULT_BUDGETS[4] = {32, 64, 128, 256};
 // Eq. 5's proportionality is closed with a fitted scale and offset (MP = k * score + b, clamped),
 // with C = min(Cin, Cout); a block's MP is its mean MP floored to a power of two, then the largest
 // allowed budget not above it.
+bool conv_like(const dlf_net_s& net, int i)
+{
+    const int op = net.L[i].d.op;
+    return op == DLF_CONV || op == DLF_DWCONV || op == DLF_FC;
+}
+
+// Eq. 5 closed with a scale and an offset, clamped to [1, max_mp]
+double layer_mp(const Layer& L, int batch, double alpha, double beta, double k, double b, int max_mp)
+{
+    const double ops = 2.0 * (double)L.macs * batch;
+    const double score = alpha * std::log2((double)std::min(L.d.cin, L.d.cout)) + beta * std::log2(ops);
+    return std::min((double)max_mp, std::max(1.0, k * score + b));
+}
+
+// mean MP of a block -> power of two below it -> largest allowed budget not above that
+int round_mp(double avg, const std::vector<int>& allowed)
+{
+    const int p = 1 << (int)std::floor(std::log2(avg));
+    int best = -1;
+    for (int a : allowed) if (a <= p && a > best) best = a;
+    if (best < 0) best = *std::min_element(allowed.begin(), allowed.end());
+    return best;
+}
+
 void algorithm1(const dlf_net_s& net, int batch, double crit, double alpha, double beta, double k,
                 double b, const std::vector<int>& allowed, std::vector<int>& part, std::vector<int>& mps)
 {
     const int n = (int)net.L.size();
     const int max_mp = *std::max_element(allowed.begin(), allowed.end());
-    auto conv_like = [&](int i) {
-        const int op = net.L[i].d.op;
-        return op == DLF_CONV || op == DLF_DWCONV || op == DLF_FC;
-    };
-    auto round_mp = [&](double avg) {
-        const int p = 1 << (int)std::floor(std::log2(avg));
-        int best = -1;
-        for (int a : allowed) if (a <= p && a > best) best = a;
-        if (best < 0) best = *std::min_element(allowed.begin(), allowed.end());
-        return best;
-    };
+    auto conv_like = [&](int i) { return ::conv_like(net, i); };
+    auto round_mp = [&](double avg) { return ::round_mp(avg, allowed); };
     double sum_op = 0, sum_mp = 0;
     int block = 0;
     for (int i = 0; i < n; ++i) {
         if (conv_like(i)) {
             const Layer& L = net.L[i];
-            const double ops = 2.0 * (double)L.macs * batch;
-            const double score = alpha * std::log2((double)std::min(L.d.cin, L.d.cout)) + beta * std::log2(ops);
-            sum_mp += std::min((double)max_mp, std::max(1.0, k * score + b));
-            sum_op += ops;
+            sum_mp += layer_mp(L, batch, alpha, beta, k, b, max_mp);
+            sum_op += 2.0 * (double)L.macs * batch;
             ++block;
         }
         if (block > 0) {
@@ -1162,13 +1175,44 @@ dlf_status dlf_plan(const dlf_net_t* net, int32_t batch, const dlf_tuner_opts* o
                 GroupPlan gp;
                 dlf_status s = DLF_ERR_INFEASIBLE;
                 for (; l >= first; --l) {
-                    s = make_group(*net, batch, first, l, mps[g], max_lds, gp);
+                    s = make_group(*net, batch, first, l, o.fixed_budget > 0 ? o.fixed_budget : mps[g], max_lds, gp);
                     if (s == DLF_OK) break;
                 }
                 if (s != DLF_OK) return s;
                 groups.push_back(gp);
                 first = l + 1;
             }
+        }
+    } else if (o.mode == DLF_TUNER_LAYERWISE) {
+        // every layer a group of its own; a layer without Eq. 5 features (pooling) takes the
+        // budget of the convolution before it
+        const double alpha = (o.alpha == 0 && o.beta == 0) ? 0.316 : o.alpha;
+        const double beta = (o.alpha == 0 && o.beta == 0) ? 0.659 : o.beta;
+        const double k = (o.mp_scale == 0 && o.mp_offset == 0) ? 64.0 : o.mp_scale;
+        const double b0 = (o.mp_scale == 0 && o.mp_offset == 0) ? -1056.0 : o.mp_offset;
+        const int max_mp = *std::max_element(budgets.begin(), budgets.end());
+        int bud = *std::min_element(budgets.begin(), budgets.end());
+        for (int i = 0; i < n; ++i) {
+            if (conv_like(*net, i)) bud = round_mp(layer_mp(net->L[i], batch, alpha, beta, k, b0, max_mp), budgets);
+            GroupPlan gp;
+            dlf_status s = make_group(*net, batch, i, i, o.fixed_budget > 0 ? o.fixed_budget : bud, max_lds, gp);
+            if (s != DLF_OK) return s;
+            groups.push_back(gp);
+        }
+    } else if (o.mode == DLF_TUNER_MAXFUSE) {
+        const int bud = o.fixed_budget > 0 ? o.fixed_budget : *std::max_element(budgets.begin(), budgets.end());
+        int first = 0;
+        while (first < n) {
+            int l = n - 1;
+            GroupPlan gp;
+            dlf_status s = DLF_ERR_INFEASIBLE;
+            for (; l >= first; --l) {
+                s = make_group(*net, batch, first, l, bud, max_lds, gp);
+                if (s == DLF_OK) break;
+            }
+            if (s != DLF_OK) return s;
+            groups.push_back(gp);
+            first = l + 1;
         }
     } else {
         return fail(DLF_ERR_INVALID_ARG, "unknown tuner mode %d", o.mode);

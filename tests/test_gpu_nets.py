@@ -167,6 +167,24 @@ def test_run_is_repeatable_and_async_on_a_side_stream():
     s.close()
 
 
+def test_comparison_strategy_plans_compute_the_same_network():
+    """Plans of the paper's comparison strategies (no fusion with Eq. 5 budgets, maximal fusion,
+    Algorithm 1 with one budget) run through the same kernels and must give the same network."""
+    from oracle import oracle as o
+    from paper_2011_05630_amd import binding as B
+    net = nets.resnet18()
+    x, ws, bs = gen.make_params(net, 2)
+    ref = o.run_net(net, x, ws, bs)
+    for kw in (dict(mode=B.TUNER_LAYERWISE), dict(mode=B.TUNER_LAYERWISE, fixed_budget=32),
+               dict(mode=B.TUNER_MAXFUSE), dict(mode=B.TUNER_GREEDY, fixed_budget=64)):
+        s = _session(net, 2, ws, bs, **kw)
+        try:
+            got = s.run_numpy(x)
+        finally:
+            s.close()
+        compare(got, ref, "resnet18 %r" % (kw,))
+
+
 def test_measured_refinement_keeps_the_results():
     """dlf_plan_refine times alternative tilings of every group and may swap them in: the partition
     stays, and whatever it chose still computes the network."""

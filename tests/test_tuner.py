@@ -269,6 +269,36 @@ def test_greedy_mode_follows_algorithm1(name, batch, crit, k, b):
     assert got == want
 
 
+@pytest.mark.parametrize("name,batch", [("vgg16", 16), ("resnet50", 32), ("mobilenet_v1", 64),
+                                        ("alexnet", 4), ("two_layer_block", 1)])
+def test_comparison_strategies_of_the_evaluation(name, batch):
+    """The other rows of the paper's table of strategies: no fusion with one MP for all layers
+    (1, 2), no fusion with Eq. 5 per layer (3), maximal fusion on the largest MP (4), Algorithm 1
+    with one MP for all blocks (5)."""
+    net = getattr(nets, name)()
+    n = len(net["layers"])
+    ni = C.NetInfo(net)
+    ops = [P.op_count(L, ni.osh[i][0], ni.osh[i][1], batch) for i, L in enumerate(net["layers"])]
+    h = _handle(net)
+
+    def groups(**kw):
+        p = B.dlf_plan(h, batch, budgets=list(BUDGETS), **kw)
+        g = [(g["first"], g["last"], g["budget"]) for g in B.dlf_plan_groups(p)]
+        B.dlf_plan_destroy(p)
+        return g
+
+    k, b, crit = 16.0, -256.0, 2.0e7
+    want = P.layerwise_budgets(net["layers"], ops, 0.316, 0.659, k, b, BUDGETS)
+    assert groups(mode=B.TUNER_LAYERWISE, mp_scale=k, mp_offset=b) == [(i, i, want[i]) for i in range(n)]
+    assert groups(mode=B.TUNER_LAYERWISE, fixed_budget=64) == [(i, i, 64) for i in range(n)]
+    feasible = lambda f, l: C.group_cost(net, batch, f, l, max(BUDGETS), ni=ni) is not None
+    assert groups(mode=B.TUNER_MAXFUSE) == P.max_fusion(n, feasible, max(BUDGETS))
+    part, mps = P.algorithm1(net["layers"], ops, crit, 0.316, 0.659, k, b, BUDGETS)
+    assert groups(mode=B.TUNER_GREEDY, opcount_critical=crit, mp_scale=k, mp_offset=b, fixed_budget=128) == \
+        _legalise(net, batch, part, [128] * len(part))
+    B.dlf_net_destroy(h)
+
+
 def test_greedy_defaults_are_the_documented_ones():
     net = nets.resnet50()
     h = _handle(net)
