@@ -30,8 +30,8 @@ RIDGE = MFMA_FP16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # FLOP per byte
 # Valid only for the kernel sources they were taken with: `csrc_sha1` is checked at run time and
 # `traffic` is reported as null when the sources have changed since.
 TRAFFIC = {
-    "csrc_sha1": "4d2db5aef94f7a7504007f136c8bac7c09efa537",
-    "bytes_per_launch": {"resnet50_b32": {"k_group<1,4,2>": 65804290, "k_pwb<2,2>": 43007216, "k_pwb<1,4>": 64607468, "k_group<1,2,2>": 22403356, "k_pw_sk": 55585699, "k_gap": 6570370, "k_fc": 5398513}},
+    "csrc_sha1": "13243559fe5aaaefb7181d9d3f420ae5299fb2fe",
+    "bytes_per_launch": {"resnet50_b32": {"k_group<1,2,4>": 67713049, "k_pwb<2,2>": 43004110, "k_pwb<1,4>": 64613136, "k_group<1,2,2>": 22390330, "k_pw_sk": 55595277, "k_gap": 6584726, "k_fc": 5398519}},
 }
 
 
