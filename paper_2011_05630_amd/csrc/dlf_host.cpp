@@ -72,7 +72,7 @@ void pack_conv_weights(const uint16_t* w, int cout, int taps, int cin, int kc, i
 {
     const int ncb = ceil_div(cout, 32), nchunks = cin_pad / kc, nks = kc / 16;
     const size_t nsteps = (size_t)nchunks * taps * nks;
-    out.assign((ncb * nsteps + 8) * 512, 0);   // 8 steps of zeros: the kernels prefetch ahead
+    out.assign((ncb * nsteps + 24) * 512, 0);  // 24 steps of zeros: the kernels prefetch up to 18 steps ahead
     for (int cb = 0; cb < ncb; ++cb)
         for (int chunk = 0; chunk < nchunks; ++chunk)
             for (int tap = 0; tap < taps; ++tap)

@@ -236,19 +236,22 @@ __device__ __attribute__((noinline)) void stage_rowfold(const half_t* in, int n,
 // cycles, an L2 round trip) before it is used, and one wave alone keeps the MFMA pipe busy.
 // Activations (3x3 path): both K steps of the next tap are read from LDS while the current tap
 // is multiplied.
-// TAPS = 9 (3x3, RA = 6) is fully unrolled so that every ring index is static and the compiler
-// places each wait exactly; TAPS = 1 (1x1) and TAPS = 0 (any other filter, a loop) use RA = 2.
-// (register tiles with 128 accumulator registers have no room for the deep ring)
-template <int TAPS, int FC, int FP> struct RingSize {
-    static constexpr int value = (TAPS == 9 && FC * FP < 8) ? 6 : 2;
+// TAPS = 9 (3x3, RA = 6 or 18) is fully unrolled so that every ring index is static and the
+// compiler places each wait exactly; TAPS = 1 (1x1) and TAPS = 0 (any other filter, a loop) use
+// RA = 2.  A wave's weight stream is bound by (ring bytes) / (round trip): with 6 KiB in flight and
+// 0.5-1.3 us to L2 or HBM a wave gets 5-13 GB/s, which is what a layer with a long K and few
+// pixels (3x3 on 14 x 14 or 7 x 7 maps) then runs at; the 32 x 64 register tile has the registers
+// for a ring of a whole 18-step chunk (not in the build for 128 registers).
+template <int TAPS, int FC, int FP, bool LEAN> struct RingSize {
+    static constexpr int value = TAPS != 9 ? 2 : (FC * FP <= 2 && !LEAN) ? 18 : (FC * FP < 8 ? 6 : 2);
 };
 
-template <int FC, int FP, int TAPS>
+template <int FC, int FP, int TAPS, int RA>
 __device__ __forceinline__ void mma_chunk(const half_t* src, const int (&pbase)[FP],
-                                          const h8* (&wp)[FC], h8 (&ar)[RingSize<TAPS, FC, FP>::value][FC],
+                                          const h8* (&wp)[FC], h8 (&ar)[RA][FC],
                                           f16v (&acc)[FC][FP], int cs, int iw, int kw, int ntaps)
 {
-    constexpr int RA = RingSize<TAPS, FC, FP>::value;
+    static_assert(RA == 2 || (TAPS == 9 && 18 % RA == 0), "ring depths this loop is written for");
     // Per-tap LDS addresses are formed right before each load; the empty asm keeps the compiler
     // from precomputing all of them outside the chunk loop, which would cost TAPS x FP registers.
     int pb[FP];
@@ -257,7 +260,7 @@ __device__ __forceinline__ void mma_chunk(const half_t* src, const int (&pbase)[
         pb[p] = pbase[p];
         asm volatile("" : "+v"(pb[p]));
     }
-    if constexpr (RA == 6) {
+    if constexpr (RA > 2) {
         h8 b[2][2][FP];
 #pragma unroll
         for (int p = 0; p < FP; ++p) {
@@ -405,7 +408,7 @@ __device__ __forceinline__ void conv_epilogue(f16v (&acc)[FC][FP], int cbl, int 
 // order: a wave that had both the long-latency activation loads and the just-in-time weight
 // fragment loads in flight would stall its MFMAs on the activation loads.
 // Resident (not STREAM): the input region is already in LDS and all 8 waves multiply.
-template <int FC, int FP, bool STREAM, int TAPS>
+template <int FC, int FP, bool STREAM, int TAPS, bool LEAN>
 __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage& st, int n,
                                            int ty0, int tx0, int slice, bool defer_act)
 {
@@ -529,7 +532,7 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
             }
         }
 
-        constexpr int RA = RingSize<TAPS, FC, FP>::value;
+        constexpr int RA = RingSize<TAPS, FC, FP, LEAN>::value;
         h8 ar[RA][FC];
 #pragma unroll
         for (int i = 0; i < RA; ++i)
@@ -547,14 +550,14 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
                 if constexpr (TAPS == 1) {
                     int j = 0;
                     for (; j + 1 < cpr; j += 2) {
-                        mma_chunk<FC, FP, 1>(src + j * 32, pbase, wp, ar, acc, cs, st.iw, 1, 1);
-                        mma_chunk<FC, FP, 1>(src + j * 32 + 32, pbase, wp, ar, acc, cs, st.iw, 1, 1);
+                        mma_chunk<FC, FP, 1, RA>(src + j * 32, pbase, wp, ar, acc, cs, st.iw, 1, 1);
+                        mma_chunk<FC, FP, 1, RA>(src + j * 32 + 32, pbase, wp, ar, acc, cs, st.iw, 1, 1);
                     }
                     if (j < cpr)
-                        mma_chunk<FC, FP, 1>(src + j * 32, pbase, wp, ar, acc, cs, st.iw, 1, 1);
+                        mma_chunk<FC, FP, 1, RA>(src + j * 32, pbase, wp, ar, acc, cs, st.iw, 1, 1);
                 } else {
                     for (int j = 0; j < cpr; ++j)
-                        mma_chunk<FC, FP, TAPS>(src + j * 32, pbase, wp, ar, acc, cs, st.iw, st.kw,
+                        mma_chunk<FC, FP, TAPS, RA>(src + j * 32, pbase, wp, ar, acc, cs, st.iw, st.kw,
                                                 ntaps);
                 }
             }
@@ -822,13 +825,13 @@ __global__ __launch_bounds__(DLF_WG_THREADS, MINW) void k_group(const DlfGroupAr
                 const int taps = st.kh * st.kw;
                 const int kind = (taps == 9 && st.kw == 3) ? 9 : (taps == 1 ? 1 : 0);
                 if (s == 0 && a.stream0) {
-                    if (kind == 9) conv_stage<FC, FP, true, 9>(a, st, n, ty0, tx0, slice, last);
-                    else if (kind == 1) conv_stage<FC, FP, true, 1>(a, st, n, ty0, tx0, slice, last);
-                    else conv_stage<FC, FP, true, 0>(a, st, n, ty0, tx0, slice, last);
+                    if (kind == 9) conv_stage<FC, FP, true, 9, (MINW >= 4)>(a, st, n, ty0, tx0, slice, last);
+                    else if (kind == 1) conv_stage<FC, FP, true, 1, (MINW >= 4)>(a, st, n, ty0, tx0, slice, last);
+                    else conv_stage<FC, FP, true, 0, (MINW >= 4)>(a, st, n, ty0, tx0, slice, last);
                 } else {
-                    if (kind == 9) conv_stage<FC, FP, false, 9>(a, st, n, ty0, tx0, slice, last);
-                    else if (kind == 1) conv_stage<FC, FP, false, 1>(a, st, n, ty0, tx0, slice, last);
-                    else conv_stage<FC, FP, false, 0>(a, st, n, ty0, tx0, slice, last);
+                    if (kind == 9) conv_stage<FC, FP, false, 9, (MINW >= 4)>(a, st, n, ty0, tx0, slice, last);
+                    else if (kind == 1) conv_stage<FC, FP, false, 1, (MINW >= 4)>(a, st, n, ty0, tx0, slice, last);
+                    else conv_stage<FC, FP, false, 0, (MINW >= 4)>(a, st, n, ty0, tx0, slice, last);
                 }
                 if (last) {
                     __syncthreads();
