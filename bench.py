@@ -30,8 +30,8 @@ RIDGE = MFMA_FP16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # FLOP per byte
 # Valid only for the kernel sources they were taken with: `csrc_sha1` is checked at run time and
 # `traffic` is reported as null when the sources have changed since.
 TRAFFIC = {
-    "csrc_sha1": "13243559fe5aaaefb7181d9d3f420ae5299fb2fe",
-    "bytes_per_launch": {"resnet50_b32": {"k_group<1,2,4>": 67713049, "k_pwb<2,2>": 43004110, "k_pwb<1,4>": 64613136, "k_group<1,2,2>": 22390330, "k_pw_sk": 55595277, "k_gap": 6584726, "k_fc": 5398519}},
+    "csrc_sha1": "5c3d0034ad90415171a2c1529d0f059d493e76ef",
+    "bytes_per_launch": {"resnet50_b32": {"k_group<1,2,4>": 67710066, "k_pwb<2,2>": 43003053, "k_pwb<1,4>": 64619052, "k_group<1,2,2>": 22526052, "k_pw_sk": 55598327, "k_gap": 6584706, "k_fc": 5398514}},
 }
 
 
