@@ -4,7 +4,7 @@ INFRASTRUCTURE ONLY; shares no code with the GPU library).
 The cost function is ours, not the paper's: the paper times every candidate on the hardware
 (Sec. V "Oracle Case": reduced brute force) and its greedy pass only uses operation count and
 channel size (Sec. IV).  Here a group's cost is an integer number of picoseconds computed from
-the tiling the library would use ("cost model, version 2" in the project's design notes).  It is
+the tiling the library would use (cost model, version 3).  It is
 implemented twice, in the library (C++) and here (Python), so that the library's exact tuner can
 be checked bit for bit against exhaustive enumeration (plan_oracle.best_plan_exhaustive).
 
@@ -17,7 +17,7 @@ cost(first, last, budget) = min over the candidate tilings of the group of
 or None if the layers cannot run as one group / no candidate fits on-chip memory.
 """
 
-# ---- constants of cost model version 2 ----
+# ---- constants of cost model version 3 ----
 PS_PER_CYCLE = 465
 HBM_BYTES_PER_CYCLE = 3300
 CU_BYTES_PER_CYCLE = 12

@@ -926,7 +926,7 @@ const char* dlf_status_string(dlf_status s)
 
 const char* dlf_last_error(void) { return g_err.c_str(); }
 
-int32_t dlf_cost_model_version(void) { return 2; }
+int32_t dlf_cost_model_version(void) { return 3; }
 
 dlf_status dlf_net_create(const dlf_layer_desc* layers, int32_t n, int32_t in_h, int32_t in_w,
                           int32_t in_c, dlf_net_t** out)

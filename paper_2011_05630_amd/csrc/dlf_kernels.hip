@@ -699,6 +699,26 @@ __device__ __forceinline__ void valu_stage(const DlfGroupArgs& a, const DlfStage
         if (st.kind == DLF_ST_MAXPOOL) {
             // max of fp16 values is exact: stay in packed fp16
             hv = u4v{0xFC00FC00u, 0xFC00FC00u, 0xFC00FC00u, 0xFC00FC00u};   // -inf
+            if (st.kh == 3 && st.kw == 3) {
+                // 3x3: all nine reads are issued before the first maximum (one LDS round trip per
+                // work item instead of nine); taps outside the feature map count as -inf
+                const int iy = gy * st.stride - st.pad, ix = gx * st.stride - st.pad;
+                const half_t* xp = lds + st.in_off + ((ry * st.stride) * st.iw + rx * st.stride) * st.in_cs + lc;
+                const int rowstep = st.iw * st.in_cs;
+                u4v x[9];
+#pragma unroll
+                for (int t = 0; t < 9; ++t) x[t] = *(const u4v*)(xp + (t / 3) * rowstep + (t % 3) * st.in_cs);
+#pragma unroll
+                for (int t = 0; t < 9; ++t) {
+                    const int ty = iy + t / 3, tx = ix + t % 3;
+                    const bool ok = ty >= 0 && ty < st.in_h && tx >= 0 && tx < st.in_w;
+                    const unsigned m = ok ? 0u : 0xFC00FC00u;      // max(x, -inf) = x
+                    hv.x = pk_max(hv.x, ok ? x[t].x : m);
+                    hv.y = pk_max(hv.y, ok ? x[t].y : m);
+                    hv.z = pk_max(hv.z, ok ? x[t].z : m);
+                    hv.w = pk_max(hv.w, ok ? x[t].w : m);
+                }
+            } else
             for (int kh = 0; kh < st.kh; ++kh) {
                 const int iy = gy * st.stride - st.pad + kh;
                 if (iy < 0 || iy >= st.in_h) continue;

@@ -118,7 +118,7 @@ def test_library_exports_every_declared_symbol():
     # and the binding offers the same names
     unbound = [n for n in names if not hasattr(B, n)]
     assert not unbound, unbound
-    assert B.dlf_cost_model_version() == 2
+    assert B.dlf_cost_model_version() == 3
 
 
 def test_layer_info_matches_eq1_eq2():
