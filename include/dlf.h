@@ -178,6 +178,9 @@ dlf_status dlf_plan_refine(dlf_plan_t* plan, const void* in_dev, void* out_dev, 
  * Process-wide, not thread-safe. */
 void dlf_debug_force_config(int32_t th, int32_t tw, int32_t variant, int32_t nslices,
                             int32_t slice_c, int32_t stream0, int32_t kc);
+/* Testing hook, after dlf_debug_force_config (which resets it to 1): the forced tiling also splits K
+ * over `ksplit` waves per work item (2, 4 or 8; single resident convolution, 32x64 register tile). */
+void dlf_debug_force_ksplit(int32_t ksplit);
 
 /* Testing hook: how single 1x1 convolutions choose between the fused-group kernel and the
  * pointwise kernel: 0 = by modelled cost (default), 1 = pointwise wherever it applies, 2 = never,

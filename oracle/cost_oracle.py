@@ -32,6 +32,7 @@ C_ROUND = 1500
 C_ROUND_VEC = 300
 C_BARRIER = 500
 C_EPI = 900
+C_KSPLIT = 2500
 C_VALU = 100
 C_STAGE = 1200
 C_STORE_VEC = 80
@@ -182,7 +183,7 @@ def group_stages(ni, first, last):
     return st
 
 
-def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc, max_lds):
+def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc, ksplit, max_lds):
     """Per-tile quantities of one candidate tiling, or None if it does not fit.
     Returns (ntiles, lds_bytes, tile_cycles, tile_hbm_bytes, tile_l2_bytes, tile_mma_cycles)."""
     Ls = ni.layers
@@ -285,7 +286,22 @@ def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc
             return None
     if sl["pool2"] and th * 2 != sl["rh"]:
         return None
-    lds_bytes = (area[0] + area[1]) * 2
+    lds_halfs = area[0] + area[1]
+    if ksplit > 1:
+        # K of a single resident CONV stage split over `ksplit` waves per work item: register tile
+        # of at most 32 x 64, chunks divisible, one pass of work items, partial sums of all 8 waves
+        # in LDS (fp32)
+        st = S[0]
+        if ksplit not in (2, 4, 8) or ns != 1 or st["kind"] != CONV or stream0 or st["im2col"] or FC * FP > 2:
+            return None
+        if (st["cin_pad"] // 32) % ksplit:
+            return None
+        n_pg = cdiv(cdiv(st["rh"] * st["rw"], 32), FP)
+        cbs = min(st["ncb"], slice_c // 32) if nslices > 1 else st["ncb"]
+        if n_pg * cdiv(cbs, FC) * ksplit > WAVES:
+            return None
+        lds_halfs = rup(lds_halfs, 8) + WAVES * FC * FP * 16 * 64 * 2
+    lds_bytes = lds_halfs * 2
     if lds_bytes > max_lds:
         return None
 
@@ -308,19 +324,19 @@ def build_group(ni, specs, batch, th, tw, variant, nslices, slice_c, stream0, kc
         if st["kind"] == CONV:
             n_pg = cdiv(cdiv(npix, 32), FP)
             cbs = min(st["ncb"], slice_c // 32) if nslices > 1 else st["ncb"]
-            nitems = n_pg * cdiv(cbs, FC)
+            nitems = n_pg * cdiv(cbs, FC) * ksplit          # K slices run like work items
             streaming = s == 0 and stream0
             mma_waves = MMA_WAVES if streaming else WAVES
             if streaming and nitems > mma_waves:
                 return None
-            mma = cdiv(nitems, 4) * st["nsteps"] * FC * FP * MFMA_CYCLES * (13 if FP >= 4 else 20) // 10
+            mma = cdiv(nitems, 4) * (st["nsteps"] // ksplit) * FC * FP * MFMA_CYCLES * (13 if FP >= 4 else 20) // 10
             if streaming:
                 nrounds = st["cin_pad"] // st["kc"]
                 vecs = cdiv(st["ih"] * st["iw"] * (st["kc"] // 8), LOAD_THREADS)
                 mma = max(mma, nrounds * (C_ROUND + vecs * C_ROUND_VEC)) + nrounds * C_BARRIER
             mma_total += mma
-            cyc += mma + cdiv(nitems, mma_waves) * FC * FP * C_EPI
-            l2 += nitems * FC * st["nsteps"] * 1024
+            cyc += mma + cdiv(nitems, mma_waves) * FC * FP * C_EPI + (C_KSPLIT if ksplit > 1 else 0)
+            l2 += nitems * FC * (st["nsteps"] // ksplit) * 1024
         else:
             c = chan_local if chan_local else st["cout"]
             items = npix * cdiv(c, 8)
@@ -355,7 +371,7 @@ def tiling_cost_ps(built, budget, variant):
 
 def candidates(ni, specs):
     """Every tiling the tuner considers for a group: (th, tw, variant, nslices, slice_c,
-    stream0, kc)."""
+    stream0, kc, ksplit)."""
     Ls = ni.layers
     llast = specs[-1][3] if specs[-1][2] else specs[-1][0]
     out_h, out_w, _ = ni.osh[llast]
@@ -381,19 +397,26 @@ def candidates(ni, specs):
                         kc = 32
                         while kc <= (128 if (stream0 and wide) else 32):
                             if ni.cin_pad[l0] % kc == 0:
-                                yield th, tw, variant, 1, 0, stream0, kc
+                                yield th, tw, variant, 1, 0, stream0, kc, 1
+                                if not stream0 and len(specs) == 1 and fc * VAR_FP[variant] <= 2:
+                                    for ks in (2, 4, 8):
+                                        yield th, tw, variant, 1, 0, 0, 32, ks
+                                        for cg in (1, 2, 4):
+                                            sc = fc * cg * 32
+                                            if sc < ncb * 32:
+                                                yield th, tw, variant, cdiv(ncb * 32, sc), sc, 0, 32, ks
                                 if not later_conv and stream0:
                                     for cg in (1, 2, 4):
                                         sc = fc * cg * 32
                                         if sc < ncb * 32:
-                                            yield th, tw, variant, cdiv(ncb * 32, sc), sc, 1, kc
+                                            yield th, tw, variant, cdiv(ncb * 32, sc), sc, 1, kc, 1
                             kc *= 2
                 else:
-                    yield th, tw, variant, 1, 0, 0, 32
+                    yield th, tw, variant, 1, 0, 0, 32, 1
                     if not later_conv:
                         sc = 32
                         while sc < Ls[l0]["cin"]:
-                            yield th, tw, variant, cdiv(Ls[l0]["cin"], sc), sc, 0, 32
+                            yield th, tw, variant, cdiv(Ls[l0]["cin"], sc), sc, 0, 32, 1
                             sc *= 2
 
 

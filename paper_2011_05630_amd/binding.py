@@ -99,6 +99,8 @@ def lib():
     L.dlf_cost_model_version.restype = i32
     L.dlf_debug_force_config.argtypes = [i32, i32, i32, i32, i32, i32, i32]
     L.dlf_debug_force_config.restype = None
+    L.dlf_debug_force_ksplit.argtypes = [i32]
+    L.dlf_debug_force_ksplit.restype = None
     L.dlf_debug_pointwise_mode.argtypes = [i32]
     L.dlf_debug_pointwise_mode.restype = None
     L.dlf_plan_group_config.argtypes = [vp, i32, i32p, i32p, i32p, i32p, i32p, i32p]
@@ -277,6 +279,11 @@ def dlf_plan_layer_output(plan, layer):
 
 def dlf_cost_model_version():
     return lib().dlf_cost_model_version()
+
+
+def dlf_debug_force_ksplit(ksplit=1):
+    """Testing hook (after dlf_debug_force_config): K of the forced tiling split over `ksplit` waves."""
+    lib().dlf_debug_force_ksplit(ksplit)
 
 
 def dlf_debug_pointwise_mode(mode=0):

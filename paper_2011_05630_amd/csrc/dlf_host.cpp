@@ -155,6 +155,7 @@ struct TileCfg {
     int nslices, slice_c;
     int stream0;
     int kc;          // stream0: channels per streaming round (32, 64 or 128)
+    int ksplit = 1;  // resident single CONV stage: waves that share a work item's K
 };
 
 struct GroupPlan {
@@ -193,6 +194,7 @@ const int64_t C_ROWFOLD = 400;               // per 512 staged narrow pixels (3 
 const int64_t C_ROUND = 1500;               // lower bound of a streaming round: loader latency ...
 const int64_t C_ROUND_VEC = 300;            // ... plus this per 16-byte vector a data-movement thread brings in
 const int64_t C_BARRIER = 500;
+const int64_t C_KSPLIT = 2500;              // K split over waves: partial sums through LDS, a barrier
 const int64_t C_EPI = 900;                  // epilogue per 32x32 accumulator block
 const int64_t C_VALU = 100;                  // per tap per 512 (pixel, 8 channels) items
 const int64_t C_STAGE = 1200;                // per VALU stage
@@ -428,6 +430,18 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
         bufsz[s] = sz;
         area[s & 1] = std::max(area[s & 1], sz);
     }
+    // K split over waves: a single resident CONV stage on a register tile of at most 64 pixels x 32
+    // channels (the partial sums of 8 waves must fit LDS), chunks divisible, one pass of work items
+    for (int s = 0; s < ns; ++s) { ga.st[s].ksplit = 1; ga.st[s].ks_off = 0; }
+    if (tc.ksplit != 1) {
+        const DlfStage& st = ga.st[0];
+        if (tc.ksplit != 2 && tc.ksplit != 4 && tc.ksplit != 8) return b;
+        if (ns != 1 || st.kind != DLF_ST_CONV || tc.stream0 || st.im2col || FCv * FPv > 2) return b;
+        if ((st.cin_pad / 32) % tc.ksplit != 0) return b;
+        const int npb = ceil_div(st.rh * st.rw, 32), n_pg = ceil_div(npb, FPv);
+        const int cbs = tc.nslices > 1 ? std::min(st.ncb, tc.slice_c / 32) : st.ncb;
+        if (n_pg * ceil_div(cbs, FCv) * tc.ksplit > DLF_WAVES) return b;
+    }
     // the last CONV stage leaves its tile in LDS (buffer ns); store_tile copies it to HBM.  Where
     // every wave has at most one work item of that stage (or the stage streams, which ends with a
     // barrier anyway), the tile may overwrite the stage's own input: one barrier between the
@@ -461,7 +475,13 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
         ga.st[s].out_off = ((s + 1) & 1) ? (int)area[0] : 0;
     }
     if (alias_out) ga.st[ns - 1].out_off = ga.st[ns - 1].in_off;
-    const int64_t lds_halfs = area[0] + area[1];
+    int64_t lds_halfs = area[0] + area[1];
+    if (tc.ksplit > 1) {
+        ga.st[0].ksplit = tc.ksplit;
+        lds_halfs = round_up((int)lds_halfs, 8);
+        ga.st[0].ks_off = (int)lds_halfs;
+        lds_halfs += (int64_t)DLF_WAVES * FCv * FPv * 16 * 64 * 2;      // fp32 = 2 halfs
+    }
     if (lds_halfs * 2 > max_lds) return b;
     b.lds_bytes = (int)(lds_halfs * 2);
 
@@ -487,22 +507,22 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
             int cbs = st.ncb;
             if (tc.nslices > 1) cbs = std::min(st.ncb, tc.slice_c / 32);
             const int n_cg = ceil_div(cbs, FCv);
-            const int nitems = n_pg * n_cg;
+            const int nitems = n_pg * n_cg * tc.ksplit;           // K slices run like work items
             const bool streaming = (s == 0 && tc.stream0);
             const int mma_waves = streaming ? DLF_MMA_WAVES : DLF_WAVES;
             if (streaming && nitems > mma_waves) return b;
             // items queue up on the 4 SIMDs; measured rounds run at about half the MFMA issue rate
             // (a 32 x 128 register tile needs half the weight traffic per MFMA and runs closer to
             //  the issue rate: 1.6 instead of 2)
-            int64_t mma = (int64_t)ceil_div(nitems, 4) * st.nsteps * FCv * FPv * MFMA_CYCLES * (FPv >= 4 ? 13 : 20) / 10;
+            int64_t mma = (int64_t)ceil_div(nitems, 4) * (st.nsteps / tc.ksplit) * FCv * FPv * MFMA_CYCLES * (FPv >= 4 ? 13 : 20) / 10;
             if (streaming) {
                 const int64_t nrounds = st.cin_pad / st.kc;
                 const int64_t vecs = ceil_div(st.ih * st.iw * (st.kc / 8), DLF_LOAD_THREADS);
                 mma = std::max(mma, nrounds * (C_ROUND + vecs * C_ROUND_VEC)) + nrounds * C_BARRIER;
             }
             mma_total += mma;
-            cyc += mma + (int64_t)ceil_div(nitems, mma_waves) * FCv * FPv * C_EPI;
-            l2 += (int64_t)nitems * FCv * st.nsteps * 1024;
+            cyc += mma + (int64_t)ceil_div(nitems, mma_waves) * FCv * FPv * C_EPI + (tc.ksplit > 1 ? C_KSPLIT : 0);
+            l2 += (int64_t)nitems * FCv * (st.nsteps / tc.ksplit) * 1024;
         } else {
             const int c = chan_local ? chan_local : st.cout;
             const int64_t items = (int64_t)npix * ceil_div(c, 8);
@@ -592,6 +612,20 @@ bool choose_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
                             if (L0.cin_pad % kc != 0) continue;
                             TileCfg t{th, tw, variant, 1, 0, stream0, kc};
                             cands.push_back(t);
+                            if (!stream0 && ns == 1 && FCv * VAR_FP[variant] <= 2) {
+                                // a single resident CONV: K split over 2, 4 or 8 waves, whole or
+                                // sliced over the output channels
+                                for (int ks = 2; ks <= 8; ks *= 2) {
+                                    TileCfg k{th, tw, variant, 1, 0, 0, 32, ks};
+                                    cands.push_back(k);
+                                    for (int cg = 1; cg <= 4; cg *= 2) {
+                                        const int sc = FCv * cg * 32;
+                                        if (sc >= ncb * 32) continue;
+                                        TileCfg u{th, tw, variant, ceil_div(ncb * 32, sc), sc, 0, 32, ks};
+                                        cands.push_back(u);
+                                    }
+                                }
+                            }
                             if (!later_conv && stream0) {
                                 for (int cg = 1; cg <= 4; cg *= 2) {
                                     const int sc = FCv * cg * 32;
@@ -1294,6 +1328,8 @@ dlf_status dlf_plan_group_io(const dlf_plan_t* plan, int32_t g, int32_t* in_laye
 }
 
 void dlf_debug_pointwise_mode(int32_t mode) { g_pw_mode = (mode >= 0 && mode <= 7) ? mode : 0; }
+
+void dlf_debug_force_ksplit(int32_t ksplit) { g_force.ksplit = ksplit > 0 ? ksplit : 1; }
 
 void dlf_debug_force_config(int32_t th, int32_t tw, int32_t variant, int32_t nslices, int32_t slice_c,
                             int32_t stream0, int32_t kc)

@@ -50,6 +50,9 @@ struct DlfStage {
     const void* w;        // CONV: packed fragments; DW: [kh][kw][c] fp16
     const float* bias;    // padded with zeros to ncb*32 (CONV) / c rounded up to 8 (DW)
     const void* res;      // residual operand in HBM, NHWC with this stage's output shape, or null
+    int32_t ksplit;       // resident CONV stage: K (the 32-channel chunks) split over this many waves per
+                          // work item (1, 2, 4 or 8; work items x ksplit <= 8); the partial sums meet in
+    int32_t ks_off;       // an LDS area at this offset (halfs): [wave][FC * FP * 16][64] fp32
 };
 
 struct DlfGroupArgs {

@@ -408,7 +408,7 @@ __device__ __forceinline__ void conv_epilogue(f16v (&acc)[FC][FP], int cbl, int 
 // order: a wave that had both the long-latency activation loads and the just-in-time weight
 // fragment loads in flight would stall its MFMAs on the activation loads.
 // Resident (not STREAM): the input region is already in LDS and all 8 waves multiply.
-template <int FC, int FP, bool STREAM, int TAPS, bool LEAN>
+template <int FC, int FP, bool STREAM, int TAPS, bool LEAN, bool KSP>
 __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage& st, int n,
                                            int ty0, int tx0, int slice, bool defer_act)
 {
@@ -492,12 +492,23 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
         return;
     }
 
+    // K split over waves (resident stages with few work items and a long K, where a wave's weight
+    // stream, not the matrix pipe, sets the pace): ksplit waves share a work item, each runs a
+    // contiguous share of the 32-channel chunks, the partial sums meet in LDS and the first wave of
+    // the item finishes it.  The host guarantees work items x ksplit <= waves: one pass.  Only the
+    // KSP builds of the kernel carry this form; in the others ksplit is the constant 1.
+    const int ksplit = (KSP && !STREAM) ? max(st.ksplit, 1) : 1;    // a power of two
+    const int ks_shift = __builtin_ctz(ksplit);
+    const int kpart = wave & (ksplit - 1);
+    const int iwave = wave >> ks_shift;
+    const int items_per_pass = MMA_WAVES >> ks_shift;
     bool first_pass = true;
-    for (int item0 = 0; item0 < nitems; item0 += MMA_WAVES) {
-        const int item = item0 + wave;
+    for (int item0 = 0; item0 < nitems; item0 += items_per_pass) {
+        const int item = item0 + iwave;
         const bool active = item < nitems;
         if (!STREAM && !active) {
-            if (st.alias_out) __syncthreads();     // the barrier in front of the other waves' epilogues
+            // the barrier in front of the other waves' epilogues
+            if (st.alias_out || ksplit > 1) __syncthreads();
             continue;
         }
         const int itc = active ? item : 0;
@@ -511,20 +522,23 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
             pix_to_rc(pix < npix ? pix : 0, st.rw, rw_m, st.pool2, ry, rx);
             pbase[p] = ((ry * st.stride) * st.iw + rx * st.stride) * cs + lhi * 8;
         }
+        const int rounds_mine = nrounds / ksplit;           // the host guarantees divisibility
+        const int round_first = kpart * rounds_mine;
         const h8* wp[FC];
 #pragma unroll
         for (int f = 0; f < FC; ++f) {
             const int cb = min(cb_begin + cg * FC + f, cb_end - 1);
-            wp[f] = (const h8*)st.w + (size_t)cb * st.nsteps * 64 + lane;
+            wp[f] = (const h8*)st.w + ((size_t)cb * st.nsteps + (size_t)round_first * cpr * ntaps * 2) * 64 + lane;
         }
-        // accumulators start at the bias of their output channel
+        // accumulators start at the bias of their output channel (in the item's first wave)
         f16v acc[FC][FP];
 #pragma unroll
         for (int f = 0; f < FC; ++f) {
             const int cb = min(cb_begin + cg * FC + f, cb_end - 1);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const f4v bv = *(const f4v*)(st.bias + cb * 32 + q * 8 + lhi * 4);
+                f4v bv = *(const f4v*)(st.bias + cb * 32 + q * 8 + lhi * 4);
+                if (kpart != 0) bv = f4v{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                 for (int p = 0; p < FP; ++p)
 #pragma unroll
@@ -543,7 +557,7 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
             __syncthreads();          // round 0 is in LDS
             first_pass = false;
         }
-        for (int round = 0; round < nrounds; ++round) {
+        for (int round = round_first; round < round_first + rounds_mine; ++round) {
             const half_t* src = STREAM ? lds + st.in_off + (round & 1) * st.stream_buf
                                        : lds + st.in_off + round * 32;
             if (active) {
@@ -564,9 +578,31 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
             if (STREAM) __syncthreads();
         }
 
+        // partial sums of a split K: every wave but the item's first leaves its accumulators in LDS
+        if (!STREAM && ksplit > 1 && kpart != 0) {
+            float* sc = (float*)(lds + st.ks_off) + wave * (FC * FP * 16 * 64) + lane;
+#pragma unroll
+            for (int f = 0; f < FC; ++f)
+#pragma unroll
+                for (int p = 0; p < FP; ++p)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sc[((f * FP + p) * 16 + r) * 64] = acc[f][p][r];
+        }
         // the output tile may overwrite this stage's input: every wave must be done reading it
         // (a streaming stage has just passed its last round's barrier)
-        if (!STREAM && st.alias_out) __syncthreads();
+        if (!STREAM && (st.alias_out || ksplit > 1)) __syncthreads();
+        if (!STREAM && ksplit > 1) {
+            if (kpart != 0) continue;
+            for (int k = 1; k < ksplit; ++k) {
+                const float* sc = (const float*)(lds + st.ks_off) + (wave + k) * (FC * FP * 16 * 64) + lane;
+#pragma unroll
+                for (int f = 0; f < FC; ++f)
+#pragma unroll
+                    for (int p = 0; p < FP; ++p)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) acc[f][p][r] += sc[((f * FP + p) * 16 + r) * 64];
+            }
+        }
         // ---- epilogue: activation, (pool), fp16 -> LDS tile [pixel][channel] ----
         // (the last stage's tile is then written to HBM by store_tile with full-line stores,
         //  which also adds the residual operand and applies the activation after it)
@@ -804,7 +840,7 @@ __device__ __forceinline__ void valu_stage(const DlfGroupArgs& a, const DlfStage
 // MINW = minimum waves per SIMD the register allocation must allow: 2 (up to 256 registers, one
 // workgroup per CU) or 4 (128 registers, two workgroups per CU, for bandwidth-bound groups whose
 // load, multiply and store phases then overlap across workgroups).
-template <int FC, int FP, int MINW>
+template <int FC, int FP, int MINW, bool KSP = false>
 __global__ __launch_bounds__(DLF_WG_THREADS, MINW) void k_group(const DlfGroupArgs a)
 {
     for (int t = blockIdx.x; t < a.ntiles; t += gridDim.x) {
@@ -845,13 +881,13 @@ __global__ __launch_bounds__(DLF_WG_THREADS, MINW) void k_group(const DlfGroupAr
                 const int taps = st.kh * st.kw;
                 const int kind = (taps == 9 && st.kw == 3) ? 9 : (taps == 1 ? 1 : 0);
                 if (s == 0 && a.stream0) {
-                    if (kind == 9) conv_stage<FC, FP, true, 9, (MINW >= 4)>(a, st, n, ty0, tx0, slice, last);
-                    else if (kind == 1) conv_stage<FC, FP, true, 1, (MINW >= 4)>(a, st, n, ty0, tx0, slice, last);
-                    else conv_stage<FC, FP, true, 0, (MINW >= 4)>(a, st, n, ty0, tx0, slice, last);
+                    if (kind == 9) conv_stage<FC, FP, true, 9, (MINW >= 4), false>(a, st, n, ty0, tx0, slice, last);
+                    else if (kind == 1) conv_stage<FC, FP, true, 1, (MINW >= 4), false>(a, st, n, ty0, tx0, slice, last);
+                    else conv_stage<FC, FP, true, 0, (MINW >= 4), false>(a, st, n, ty0, tx0, slice, last);
                 } else {
-                    if (kind == 9) conv_stage<FC, FP, false, 9, (MINW >= 4)>(a, st, n, ty0, tx0, slice, last);
-                    else if (kind == 1) conv_stage<FC, FP, false, 1, (MINW >= 4)>(a, st, n, ty0, tx0, slice, last);
-                    else conv_stage<FC, FP, false, 0, (MINW >= 4)>(a, st, n, ty0, tx0, slice, last);
+                    if (kind == 9) conv_stage<FC, FP, false, 9, (MINW >= 4), KSP>(a, st, n, ty0, tx0, slice, last);
+                    else if (kind == 1) conv_stage<FC, FP, false, 1, (MINW >= 4), KSP>(a, st, n, ty0, tx0, slice, last);
+                    else conv_stage<FC, FP, false, 0, (MINW >= 4), KSP>(a, st, n, ty0, tx0, slice, last);
                 }
                 if (last) {
                     __syncthreads();
@@ -1549,22 +1585,24 @@ static void launch(K k, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t str
 }
 
 typedef void (*group_kernel_t)(const DlfGroupArgs);
-static group_kernel_t group_kernel(int variant)
+static group_kernel_t group_kernel(int variant, bool ksplit)
 {
     switch (variant) {
-    case 0: return k_group<2, 2, 2>;
-    case 1: return k_group<1, 4, 2>;
-    case 2: return k_group<1, 2, 2>;
-    case 3: return k_group<1, 2, 4>;
+    case 0: return ksplit ? nullptr : k_group<2, 2, 2>;
+    case 1: return ksplit ? nullptr : k_group<1, 4, 2>;
+    case 2: return ksplit ? k_group<1, 2, 2, true> : k_group<1, 2, 2>;
+    case 3: return ksplit ? k_group<1, 2, 4, true> : k_group<1, 2, 4>;
     default: return nullptr;
     }
 }
 
 extern "C" int dlf_kernels_init(void)
 {
-    for (int v = 0; v < DLF_NUM_VARIANTS; ++v) {
-        hipError_t e = hipFuncSetAttribute((const void*)group_kernel(v),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    for (int v = 0; v < 2 * DLF_NUM_VARIANTS; ++v) {
+        group_kernel_t k = group_kernel(v >> 1, (v & 1) != 0);
+        if (k == nullptr) continue;
+        hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           160 * 1024);
         if (e != hipSuccess) return (int)e;
     }
     return 0;
@@ -1573,7 +1611,8 @@ extern "C" int dlf_kernels_init(void)
 extern "C" int dlf_launch_group(const DlfGroupArgs* a, int variant, int grid, int lds_bytes,
                                 void* stream)
 {
-    group_kernel_t k = group_kernel(variant);
+    const bool ksplit = a->nstages == 1 && a->st[0].kind == DLF_ST_CONV && a->st[0].ksplit > 1;
+    group_kernel_t k = group_kernel(variant, ksplit);
     if (k == nullptr || grid <= 0) return (int)hipErrorInvalidValue;
     launch(k, dim3(grid), dim3(DLF_WG_THREADS), (size_t)lds_bytes, (hipStream_t)stream, *a);
     return (int)hipGetLastError();

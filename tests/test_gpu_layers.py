@@ -284,6 +284,38 @@ def test_fc_and_global_avgpool():
     compare(got, ref, "fc-fc batch 37")
 
 
+@pytest.mark.parametrize("cin,cout,hw,ks,tile,var,nsl,sc,kh,stride,act", [
+    (256, 64, 7, 4, (7, 7), 2, 1, 0, 3, 1, "relu"),      # two work items x 4 K slices
+    (512, 128, 7, 8, (7, 7), 2, 4, 32, 3, 1, "relu"),    # sliced channels, one item x 8
+    (128, 96, 14, 2, (4, 14), 3, 1, 0, 3, 1, "relu6"),   # 128-register build, ragged channel blocks
+    (256, 40, 9, 4, (4, 8), 2, 1, 0, 3, 2, "none"),      # stride 2, ragged tiles and channels
+    (512, 64, 5, 8, (7, 7), 2, 2, 32, 1, 1, "relu"),     # 1x1 filter, tile larger than the map
+    (64, 64, 8, 2, (8, 8), 2, 1, 0, 5, 1, "relu"),       # 5x5 filter (generic tap loop)
+])
+def test_conv_k_split_over_waves(cin, cout, hw, ks, tile, var, nsl, sc, kh, stride, act):
+    """A single resident convolution whose K is split over the waves of a workgroup (partial sums
+    through LDS), forced.  The form exists for one-stage groups only."""
+    announce("conv ksplit", cin, cout, hw, ks, tile, var, nsl, sc, kh, stride, act)
+    from oracle import oracle as o
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    nets_ = [_mk([nets.conv(cin, cout, kh, stride, kh // 2, act)], hw, hw + 1, cin, dist="normal")]
+    for net in nets_:
+        x, ws, bs = gen.make_params(net, 3)
+        ref = o.run_net(net, x, ws, bs)
+        B.dlf_debug_force_config(tile[0], tile[1], var, nsl, sc, 0, 32)
+        B.dlf_debug_force_ksplit(ks)
+        try:
+            s = Session(net, 3, ws, bs, **_manual(len(net["layers"]), [len(net["layers"]) - 1]))
+        finally:
+            B.dlf_debug_force_config(0)
+        try:
+            got = s.run_numpy(x)
+        finally:
+            s.close()
+        compare(got, ref, "conv %d->%d k%d s%d, K over %d waves" % (cin, cout, kh, stride, ks))
+
+
 @pytest.mark.parametrize("k_hw,k_c,cout,batch", [(8, 64, 1000, 3), (7, 96, 70, 40), (4, 512, 96, 16)])
 def test_fc_split_k(k_hw, k_c, cout, batch):
     """Long K, few output channels: the planner splits K over workgroups (pairs of 32-channel
