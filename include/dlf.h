@@ -189,6 +189,15 @@ void dlf_debug_force_ksplit(int32_t ksplit);
  * operands are shared through LDS.  Process-wide, not thread-safe. */
 void dlf_debug_pointwise_mode(int32_t mode);
 
+/* Testing hook: how a single 3x3 stride-1 pad-1 convolution (with the 2x2 max pool folded behind
+ * it, if any) chooses between the fused-group kernel and the block 3x3 kernel: mode 0 = by
+ * modelled cost (default), 1 = the block kernel wherever it applies, 2 = never.  shape >= 0 also
+ * fixes the block's shape and its th x tw pixel tile: shape 0 / 1 = 128 channels x up to 256
+ * pixels with activations brought in 32 / 64 input channels at a time, 2 / 3 = 64 channels x up to
+ * 512 pixels likewise; a shape that cannot be laid out falls back to the fused-group kernel.
+ * Process-wide, not thread-safe. */
+void dlf_debug_block3x3_mode(int32_t mode, int32_t shape, int32_t th, int32_t tw);
+
 const char* dlf_status_string(dlf_status s);
 const char* dlf_last_error(void);
 /* Version of the cost-model definition implemented by dlf_group_cost. */

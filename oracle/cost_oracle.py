@@ -51,6 +51,16 @@ C_PW_SK = 12000
 C_PW_ITEM = 2500
 C_PW_RES = 1000
 PW_HBM_BYTES_PER_CYCLE = 2000
+# block 3x3 kernel: (64-channel waves along the channels, input channels per activation block)
+C3_SHAPES = ((2, 32), (2, 64), (1, 32), (1, 64))
+C3_WAVES = 8
+C3_MAX_ACT_LOADS = 8
+C3_EPI_BYTES = C3_WAVES * 64 * 72 * 2
+C_C3_ITEM = 10000
+C_C3_SHORT_K = 6000
+C3_MMA_TENTHS = 16
+C3_BYTES_PER_CYCLE = 25
+C3_SHALLOW_RING = 300
 
 WG_THREADS = 512
 WAVES = 8
@@ -465,6 +475,60 @@ def pw_cost(ni, i, batch, budget):
     return best
 
 
+def c3_cost(ni, specs, batch, budget, max_lds):
+    """Cost of a single 3x3 stride-1 pad-1 convolution (with its folded 2x2 pool, if any) on the
+    block 3x3 kernel: cheapest of its shapes and pixel tiles, or None where it does not apply."""
+    if len(specs) != 1 or specs[0][1] != CONV:
+        return None
+    i, pool2 = specs[0][0], specs[0][2]
+    L = ni.layers[i]
+    if L["op"] != "conv" or L["kh"] != 3 or L["kw"] != 3 or L["stride"] != 1 or L["pad"] != 1:
+        return None
+    if L["cin"] % 32 or L["cout"] % 8:
+        return None
+    ih, iw, ic = ni.ish[i]
+    oh, ow, oc = ni.osh[i]
+    if batch * ih * iw * ic >= 1 << 31 or batch * oh * ow * oc >= 1 << 31:
+        return None
+    has_res = 1 if L["residual_from"] >= 0 else 0
+    m = batch * oh * ow
+    nbytes = m * L["cin"] * 2 + (m // 4 if pool2 else m) * L["cout"] * 2 * (1 + has_res) \
+        + ni.ncb[i] * ni.nsteps[i] * 1024
+    mem = nbytes // min(PW_HBM_BYTES_PER_CYCLE, budget * CU_BYTES_PER_CYCLE)
+    kt = L["cin"] // 16
+    best = None
+    for wc, ach in C3_SHAPES:
+        if L["cin"] % ach:
+            continue
+        for th in TILE_H:
+            if th > oh and th != TILE_H[0] and th - oh >= 4:
+                continue
+            for tw in TILE_W:
+                if tw > ow and tw != TILE_W[0] and tw - ow >= 4:
+                    continue
+                if th * tw > 64 * (C3_WAVES // wc) or (pool2 and ((th | tw) & 1)):
+                    continue
+                npxh = (th + 2) * (tw + 2)
+                na_i = cdiv(npxh, 512 // ach)
+                if cdiv(na_i, C3_WAVES) > C3_MAX_ACT_LOADS:
+                    continue
+                act, wstage = 2 * na_i * 1024, 9 * 2 * wc * 1024
+                nst = min(4, (max_lds - 1024 - act) // wstage)
+                if nst < 2 or max(act + nst * wstage + 1024, C3_EPI_BYTES) > max_lds:
+                    continue
+                items = batch * cdiv(oh, th) * cdiv(ow, tw) * cdiv(ni.ncb[i], 2 * wc)
+                items_cu = cdiv(items, budget)
+                stage = max(9 * 4 * MFMA_CYCLES * 2 * C3_MMA_TENTHS // 10,
+                            (wstage + npxh * 32) // C3_BYTES_PER_CYCLE)
+                if nst == 2:
+                    stage += C3_SHALLOW_RING
+                compute = items_cu * (C_C3_ITEM + (C_C3_SHORT_K if kt < 8 else 0) + has_res * C_PW_RES + kt * stage)
+                c = (C_LAUNCH + max(compute, mem)) * PS_PER_CYCLE
+                if best is None or c < best:
+                    best = c
+    return best
+
+
 def group_cost(net, batch, first, last, budget, max_lds=LDS_PER_CU, ni=None):
     """Cost in picoseconds of running layers [first, last] as one group on `budget` CUs, or None."""
     ni = ni or NetInfo(net)
@@ -504,6 +568,9 @@ def group_cost(net, batch, first, last, budget, max_lds=LDS_PER_CU, ni=None):
         pc = pw_cost(ni, first, batch, budget)
         if pc is not None and (best is None or pc < best):
             best = pc
+    cc = c3_cost(ni, specs, batch, budget, max_lds)
+    if cc is not None and (best is None or cc < best):
+        best = cc
     return best
 
 

@@ -103,6 +103,8 @@ def lib():
     L.dlf_debug_force_ksplit.restype = None
     L.dlf_debug_pointwise_mode.argtypes = [i32]
     L.dlf_debug_pointwise_mode.restype = None
+    L.dlf_debug_block3x3_mode.argtypes = [i32, i32, i32, i32]
+    L.dlf_debug_block3x3_mode.restype = None
     L.dlf_plan_group_config.argtypes = [vp, i32, i32p, i32p, i32p, i32p, i32p, i32p]
     L.dlf_plan_group_config.restype = i32
     L.dlf_run_profiled.argtypes = [vp, vp, vp, vp, i32, ctypes.POINTER(ctypes.c_float)]
@@ -291,6 +293,13 @@ def dlf_debug_pointwise_mode(mode=0):
     3 / 4 / 5 = wherever it applies with 64x64 / 32x32 / split-K 64x64 work items, 6 / 7 = with
     128x128 / 64x256 workgroup blocks."""
     lib().dlf_debug_pointwise_mode(mode)
+
+
+def dlf_debug_block3x3_mode(mode=0, shape=-1, th=0, tw=0):
+    """Testing hook: 0 = block 3x3 kernel chosen by modelled cost, 1 = wherever it applies, 2 = never;
+    shape >= 0 also fixes its shape (0 / 1: 128 channels x 256 pixels, activations 32 / 64 input
+    channels at a time; 2 / 3: 64 x 512 likewise) and pixel tile."""
+    lib().dlf_debug_block3x3_mode(mode, shape, th, tw)
 
 
 def dlf_debug_force_config(th=0, tw=0, variant=0, nslices=1, slice_c=0, stream0=0, kc=0):

@@ -147,7 +147,7 @@ dlf_status pack_and_upload(Layer& L)
 // Fusion groups
 // ------------------------------------------------------------------------------------------
 
-enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3 };
+enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3, GK_C3 = 4 };
 
 struct TileCfg {
     int th, tw;      // tile of the group's final output tensor
@@ -172,6 +172,7 @@ struct GroupPlan {
     DlfFcArgs fa;
     DlfGapArgs pa;
     DlfPwArgs wa;
+    DlfC3Args ca;
 };
 
 const int VAR_FC[DLF_NUM_VARIANTS] = {2, 1, 1, 1};
@@ -224,6 +225,13 @@ const int64_t PWB_BYTES_PER_CYCLE = 25;     // rate at which a CU takes operand 
 const int64_t C_PW_SK = 12000;              // split-K: exchange of partial sums through LDS, idle waves of a second round
 const int64_t C_PW_RES = 1000;              // residual loads
 const int64_t PW_HBM_BYTES_PER_CYCLE = 2000;
+// block 3x3 kernel: per work item (first stages of the ring, epilogue), per LDS stage of 16 input
+// channels (nine taps x four MFMAs on each of two waves per SIMD, in tenths), intake of a stage
+const int64_t C_C3_ITEM = 10000;
+const int64_t C_C3_SHORT_K = 6000;          // per item when K has fewer than 8 stages: the ring never reaches its steady state
+const int64_t C3_MMA_TENTHS = 16;
+const int64_t C3_BYTES_PER_CYCLE = 25;
+const int64_t C3_SHALLOW_RING = 300;        // per stage when the weight ring has two stages only
 
 struct StageSpec {   // one stage, before tiling
     int layer;
@@ -733,6 +741,87 @@ uint64_t pw_cost_ps(const Layer& L, int batch, int budget, int& shape)
     return best;
 }
 
+// ---- block 3x3 kernel (one 3x3 stride-1 pad-1 convolution, optionally with its folded 2x2 pool) ----
+
+// Testing hook: mode 0 = the block kernel competes with the fused-group kernel on modelled cost,
+// 1 = always where it applies, 2 = never; wc > 0 forces the shape (wc x th x tw).
+struct C3Force { int mode, shape, th, tw; };      // shape < 0: not forced
+C3Force g_c3_force = {0, -1, 0, 0};
+const int C3_WC[DLF_C3_SHAPES] = {2, 2, 1, 1};
+const int C3_ACH[DLF_C3_SHAPES] = {32, 64, 32, 64};
+
+struct C3Cfg { int shape, th, tw, nst, lds_bytes, npxh, na_i, lpw_a; };
+
+bool c3_eligible(const dlf_net_s& net, const std::vector<StageSpec>& specs, int batch)
+{
+    if (specs.size() != 1 || specs[0].kind != DLF_ST_CONV) return false;
+    const Layer& L = net.L[specs[0].layer];
+    const dlf_layer_desc& d = L.d;
+    if (d.op != DLF_CONV || d.kh != 3 || d.kw != 3 || d.stride != 1 || d.pad != 1) return false;
+    if (L.im2col || L.rowfold || (d.cin % 32) != 0 || (d.cout % 8) != 0) return false;
+    if ((int64_t)batch * L.in_h * L.in_w * L.in_c >= (int64_t)1 << 31) return false;
+    if ((int64_t)batch * L.out_h * L.out_w * L.out_c >= (int64_t)1 << 31) return false;
+    return true;
+}
+
+// Lays one shape out: wc waves along the channels (64 each), 8 / wc along the pixels (64 each);
+// two activation buffers of ACH channels, the rest of LDS (less a spare KiB) a ring of weight stages.
+bool c3_build(int pool2, int cin, int shape, int th, int tw, int max_lds, C3Cfg& c)
+{
+    if (shape < 0 || shape >= DLF_C3_SHAPES) return false;
+    const int wc = C3_WC[shape], ach = C3_ACH[shape];
+    if (th < 1 || tw < 1 || th * tw > 64 * (DLF_C3_WAVES / wc) || (cin % ach) != 0) return false;
+    if (pool2 && (((th | tw) & 1) != 0)) return false;
+    c.shape = shape; c.th = th; c.tw = tw;
+    c.npxh = (th + 2) * (tw + 2);
+    c.na_i = ceil_div(c.npxh, 512 / ach);
+    c.lpw_a = ceil_div(c.na_i, DLF_C3_WAVES);
+    if (c.lpw_a > DLF_C3_MAX_ACT_LOADS) return false;
+    const int act = 2 * c.na_i * 1024, wstage = 9 * 2 * wc * 1024;
+    c.nst = std::min(4, (max_lds - 1024 - act) / wstage);
+    if (c.nst < 2) return false;
+    c.lds_bytes = std::max(act + c.nst * wstage + 1024, (int)DLF_C3_EPI_BYTES);
+    return c.lds_bytes <= max_lds;
+}
+
+uint64_t c3_cost_ps(const Layer& L, int pool2, int batch, int budget, const C3Cfg& c)
+{
+    const int wc = C3_WC[c.shape];
+    const int64_t tiles = (int64_t)batch * ceil_div(L.out_h, c.th) * ceil_div(L.out_w, c.tw);
+    const int64_t items = tiles * ceil_div(L.ncb, 2 * wc);
+    const int64_t items_cu = (items + budget - 1) / budget;
+    const int64_t stage_bytes = (int64_t)9 * 2 * wc * 1024 + (int64_t)c.npxh * 32;
+    int64_t stage = std::max(9 * 4 * MFMA_CYCLES * 2 * C3_MMA_TENTHS / 10, stage_bytes / C3_BYTES_PER_CYCLE);
+    if (c.nst == 2) stage += C3_SHALLOW_RING;
+    const int64_t has_res = L.d.residual_from >= 0 ? 1 : 0;
+    const int64_t kt = L.d.cin / 16;
+    const int64_t compute = items_cu * (C_C3_ITEM + (kt < 8 ? C_C3_SHORT_K : 0) + has_res * C_PW_RES + kt * stage);
+    const int64_t m = (int64_t)batch * L.out_h * L.out_w;
+    const int64_t bytes = m * L.d.cin * 2 + (pool2 ? m / 4 : m) * L.d.cout * 2 * (1 + has_res) + (int64_t)L.ncb * L.nsteps * 1024;
+    const int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
+    return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
+}
+
+// Cheapest shape (ties: the first in the order of shapes; tile heights, tile widths ascending).
+bool c3_choose(const Layer& L, int pool2, int batch, int budget, int max_lds, C3Cfg& best, uint64_t& cost,
+               std::vector<std::pair<uint64_t, C3Cfg>>* all = nullptr)
+{
+    bool found = false;
+    for (int shape = 0; shape < DLF_C3_SHAPES; ++shape)
+        for (int th : TILE_H) {
+            if (th > L.out_h && th != TILE_H[0] && (th - L.out_h) >= 4) continue;
+            for (int tw : TILE_W) {
+                if (tw > L.out_w && tw != TILE_W[0] && (tw - L.out_w) >= 4) continue;
+                C3Cfg c;
+                if (!c3_build(pool2, L.d.cin, shape, th, tw, max_lds, c)) continue;
+                const uint64_t cc = c3_cost_ps(L, pool2, batch, budget, c);
+                if (all) all->push_back(std::make_pair(cc, c));
+                if (!found || cc < cost) { found = true; cost = cc; best = c; }
+            }
+        }
+    return found;
+}
+
 // force_tc / pw_mode: explicit values for the two testing hooks (null / -1: the process-wide ones)
 // Fully connected layer: one workgroup per 32 output channels streaming all of K, or, where that is
 // cheaper, pairs of channel blocks with K split 2, 4 or 8 ways (at most 256 workgroups), a second
@@ -754,10 +843,12 @@ uint64_t fc_cost_ps(const Layer& L, int batch, int& ksplit)
 }
 
 dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int budget, int max_lds,
-                      GroupPlan& g, const TileCfg* force_tc = nullptr, int pw_mode = -1)
+                      GroupPlan& g, const TileCfg* force_tc = nullptr, int pw_mode = -1,
+                      const C3Force* c3_force = nullptr)
 {
     const TileCfg& force = force_tc ? *force_tc : g_force;
     const int pwm = pw_mode >= 0 ? pw_mode : g_pw_mode;
+    const C3Force& c3f = c3_force ? *c3_force : g_c3_force;
     if (first < 0 || last >= (int)net.L.size() || first > last || budget <= 0)
         return fail(DLF_ERR_INVALID_ARG, "bad group [%d,%d] budget %d", first, last, budget);
     std::vector<StageSpec> specs;
@@ -830,6 +921,40 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
             g.lds_bytes = shape == 3   ? DLF_PWB_LDS_BYTES(2, 2)
                           : shape == 4 ? DLF_PWB_LDS_BYTES(1, 4)
                                        : DLF_PW_WAVES * 32 * PW_FP[shape] * (32 * PW_FC[shape] + 8) * 2;
+            if (L0.d.residual_from >= 0) { g.res_layer = L0.d.residual_from; g.res_stage = 0; }
+            return DLF_OK;
+        }
+    }
+    if (c3f.mode != 2 && (force.th <= 0 || c3f.mode == 1) && c3_eligible(net, specs, batch)) {
+        C3Cfg cc;
+        uint64_t c3c = 0;
+        const int pool2 = specs[0].pool2;
+        bool have;
+        if (c3f.shape >= 0) {
+            have = c3_build(pool2, L0.d.cin, c3f.shape, c3f.th, c3f.tw, max_lds, cc);
+            if (have) c3c = c3_cost_ps(L0, pool2, batch, budget, cc);
+        } else {
+            have = c3_choose(L0, pool2, batch, budget, max_lds, cc, c3c);
+        }
+        if (have && (!tiled || c3f.mode == 1 || c3c < cost)) {
+            DlfC3Args& ca = g.ca;
+            memset(&ca, 0, sizeof ca);
+            ca.w = L0.d_w; ca.bias = L0.d_bias;
+            ca.batch = batch; ca.h = L0.out_h; ca.w_ = L0.out_w; ca.cin = L0.d.cin; ca.cout = L0.d.cout;
+            ca.ncb = L0.ncb; ca.nsteps = L0.nsteps; ca.act = L0.d.act; ca.pool2 = pool2;
+            ca.th = cc.th; ca.tw = cc.tw;
+            ca.tiles_y = ceil_div(L0.out_h, cc.th); ca.tiles_x = ceil_div(L0.out_w, cc.tw);
+            ca.n_cg = ceil_div(L0.ncb, 2 * C3_WC[cc.shape]);
+            ca.ntiles = batch * ca.tiles_y * ca.tiles_x;
+            ca.nitems = ca.n_cg * ca.ntiles;
+            ca.npxh = cc.npxh; ca.na_i = cc.na_i; ca.lpw_a = cc.lpw_a; ca.nst = cc.nst;
+            g.kind = GK_C3;
+            g.cost = c3c;
+            g.variant = cc.shape;
+            g.occ = 1;
+            g.grid = std::max(8, std::min(budget, ceil_div(ca.nitems, 8) * 8) / 8 * 8);
+            g.th = cc.th; g.tw = cc.tw;
+            g.lds_bytes = cc.lds_bytes;
             if (L0.d.residual_from >= 0) { g.res_layer = L0.d.residual_from; g.res_stage = 0; }
             return DLF_OK;
         }
@@ -1329,6 +1454,11 @@ dlf_status dlf_plan_group_io(const dlf_plan_t* plan, int32_t g, int32_t* in_laye
 
 void dlf_debug_pointwise_mode(int32_t mode) { g_pw_mode = (mode >= 0 && mode <= 7) ? mode : 0; }
 
+void dlf_debug_block3x3_mode(int32_t mode, int32_t shape, int32_t th, int32_t tw)
+{
+    g_c3_force = C3Force{(mode >= 0 && mode <= 2) ? mode : 0, shape, th, tw};
+}
+
 void dlf_debug_force_ksplit(int32_t ksplit) { g_force.ksplit = ksplit > 0 ? ksplit : 1; }
 
 void dlf_debug_force_config(int32_t th, int32_t tw, int32_t variant, int32_t nslices, int32_t slice_c,
@@ -1385,6 +1515,14 @@ static dlf_status launch_one(const dlf_plan_s* plan, const GroupPlan& G, const v
             wa.res = res;
         }
         e = dlf_launch_pw(&wa, G.variant, G.grid, stream);
+    } else if (G.kind == GK_C3) {
+        DlfC3Args ca = G.ca;
+        ca.in = in; ca.out = out;
+        if (G.res_stage >= 0) {
+            if (!res) return fail(DLF_ERR_INVALID_ARG, "group [%d,%d] needs its residual operand", G.first, G.last);
+            ca.res = res;
+        }
+        e = dlf_launch_c3(&ca, G.variant, G.grid, G.lds_bytes, stream);
     } else {
         DlfGroupArgs ga = G.ga;
         ga.in = in; ga.out = out;
@@ -1499,8 +1637,26 @@ dlf_status dlf_plan_refine(dlf_plan_t* plan, const void* in_dev, void* out_dev, 
                              });
             for (size_t i = 0; i < all.size() && (int)i < top_k; ++i) {
                 GroupPlan gp;
+                const C3Force never = {2, -1, 0, 0};
                 if (make_group(net, plan->batch, cur.first, cur.last, cur.budget, plan->max_lds, gp,
-                               &all[i].second, 2) == DLF_OK)
+                               &all[i].second, 2, &never) == DLF_OK)
+                    cands.push_back(gp);
+            }
+        }
+        if (c3_eligible(net, specs, plan->batch)) {
+            std::vector<std::pair<uint64_t, C3Cfg>> all;
+            C3Cfg cc;
+            uint64_t c = 0;
+            c3_choose(net.L[cur.first], specs[0].pool2, plan->batch, cur.budget, plan->max_lds, cc, c, &all);
+            std::stable_sort(all.begin(), all.end(),
+                             [](const std::pair<uint64_t, C3Cfg>& x, const std::pair<uint64_t, C3Cfg>& y) {
+                                 return x.first < y.first;
+                             });
+            for (size_t i = 0; i < all.size() && (int)i < top_k; ++i) {
+                GroupPlan gp;
+                const C3Force f = {1, all[i].second.shape, all[i].second.th, all[i].second.tw};
+                if (make_group(net, plan->batch, cur.first, cur.last, cur.budget, plan->max_lds, gp, &none, 2,
+                               &f) == DLF_OK)
                     cands.push_back(gp);
             }
         }

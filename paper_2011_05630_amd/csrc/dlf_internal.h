@@ -114,6 +114,32 @@ struct DlfPwArgs {
     int32_t nitems;       // n_pg * n_cg
 };
 
+// 3x3 stride-1 pad-1 convolution as a block kernel (one layer, optionally with the 2x2 max pool
+// that follows it): a workgroup of eight waves computes 64 * WC output channels x 64 * (8 / WC)
+// pixels of a th x tw tile, K streamed through LDS: the weights of all nine taps for the block's
+// channels 16 input channels at a time (a ring of stages), the tile's halo region ACH input
+// channels at a time (two buffers).  Shapes (WC, ACH): 0 = (2, 32), 1 = (2, 64), 2 = (1, 32), 3 = (1, 64).
+#define DLF_C3_WAVES 8
+#define DLF_C3_SHAPES 4
+#define DLF_C3_MAX_ACT_LOADS 8       // activation loads per wave per block the kernel is built for
+#define DLF_C3_EPI_BYTES (DLF_C3_WAVES * 64 * 72 * 2)   // transpose buffers of the epilogue
+struct DlfC3Args {
+    const void* in;       // [batch][h][w][cin] fp16
+    void* out;            // [batch][h][w][cout] fp16 ([batch][h/2][w/2][cout] with pool2)
+    const void* w;        // packed fragments (same stream as a CONV stage), zero steps behind them
+    const float* bias;    // padded to ncb*32
+    const void* res;      // residual operand, output shape, or null
+    int32_t batch, h, w_, cin, cout, ncb, nsteps, act, pool2;
+    int32_t th, tw, tiles_y, tiles_x;
+    int32_t n_cg;         // groups of 64 * WC output channels
+    int32_t ntiles;       // batch * tiles_y * tiles_x
+    int32_t nitems;       // n_cg * ntiles (channel group slowest)
+    int32_t npxh;         // (th + 2) * (tw + 2): pixels of the halo region
+    int32_t na_i;         // ceil(npxh / (512 / ACH)): activation load instructions per block (1 KiB each)
+    int32_t lpw_a;        // ceil(na_i / 8): ... per wave
+    int32_t nst;          // stages in the weight ring (2 .. 4)
+};
+
 struct DlfGapArgs {
     const void* x;        // [batch][hw][c]
     void* y;              // [batch][c]
@@ -131,6 +157,7 @@ int dlf_launch_group(const DlfGroupArgs* a, int variant, int grid, int lds_bytes
 int dlf_launch_fc(const DlfFcArgs* a, void* stream);
 int dlf_launch_gap(const DlfGapArgs* a, void* stream);
 int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stream);
+int dlf_launch_c3(const DlfC3Args* a, int shape, int grid, int lds_bytes, void* stream);
 int dlf_kernels_init(void);
 // Attaches a start / stop event pair (hipEvent_t, either may be null) to this thread's next launch.
 void dlf_next_launch_events(void* start, void* stop);

@@ -1390,6 +1390,317 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
     }
 }
 
+// Waits until at most n of this wave's loads are outstanding, for a wave-uniform n known only at
+// run time (the count is an immediate of the instruction); counts above 32 wait for everything.
+__device__ __forceinline__ void wait_vmcnt_dyn(int n)
+{
+    switch (__builtin_amdgcn_readfirstlane(n)) {
+#define DLF_WAIT_CASE(N) case N: wait_vmcnt<N>(); break;
+    DLF_WAIT_CASE(1) DLF_WAIT_CASE(2) DLF_WAIT_CASE(3) DLF_WAIT_CASE(4) DLF_WAIT_CASE(5) DLF_WAIT_CASE(6)
+    DLF_WAIT_CASE(7) DLF_WAIT_CASE(8) DLF_WAIT_CASE(9) DLF_WAIT_CASE(10) DLF_WAIT_CASE(11) DLF_WAIT_CASE(12)
+    DLF_WAIT_CASE(13) DLF_WAIT_CASE(14) DLF_WAIT_CASE(15) DLF_WAIT_CASE(16) DLF_WAIT_CASE(17) DLF_WAIT_CASE(18)
+    DLF_WAIT_CASE(19) DLF_WAIT_CASE(20) DLF_WAIT_CASE(21) DLF_WAIT_CASE(22) DLF_WAIT_CASE(23) DLF_WAIT_CASE(24)
+    DLF_WAIT_CASE(25) DLF_WAIT_CASE(26) DLF_WAIT_CASE(27) DLF_WAIT_CASE(28) DLF_WAIT_CASE(29) DLF_WAIT_CASE(30)
+    DLF_WAIT_CASE(31) DLF_WAIT_CASE(32)
+#undef DLF_WAIT_CASE
+    default: wait_vmcnt<0>(); break;
+    }
+}
+
+// 3x3 convolution, stride 1, pad 1, as a block kernel: one layer (with the 2x2 max pool behind it
+// folded into the epilogue, or a residual operand added there), for layers where the fused-group
+// kernel is bound by the weight stream of its waves.  A workgroup of eight waves computes
+// 64 * WC output channels x a th x tw tile of up to 64 * (8 / WC) pixels, every wave a 64 x 64
+// part, and streams K through LDS:
+//   weights: a ring of 2 .. 4 stages, each the nine taps' fragments of the block's channels for 16
+//     input channels (9 * 2 * WC KiB, the packed fragments as they lie in memory);
+//   activations: two buffers, each the tile's halo region, (th + 2) x (tw + 2) pixels, for ACH
+//     input channels (ACH / 16 weight stages); block b + 1 is requested when block b is first used;
+//   global -> LDS by 16-byte direct loads, a wave's 64 lanes filling 1 KiB per instruction.  For
+//     activations ACH / 8 adjacent lanes fetch the ACH channels of one pixel, so that a request
+//     covers whole 64- or 128-byte runs of memory (16-byte pieces of different cache lines cost a
+//     CU several times their size in intake); lanes of pixels outside the image fetch from the
+//     zero steps behind the packed weights (the padding arrives as data); every wave issues the
+//     same number of loads (surplus ones go to a spare KiB), so one count of outstanding loads
+//     means the same for all of them;
+//   within a pixel's ACH channels the 16-byte parts are stored permuted, part q of halo pixel h at
+//     position q ^ f(h): an MFMA "B" fragment reads one part of 32 consecutive pixels, LDS serves
+//     16 lanes (256 bytes) per cycle, and with f(h) = (h / 2) % 8 (128 bytes per pixel) or
+//     (h / 4) % 4 (64 bytes) any 16 consecutive pixels land in 16 different 16-byte bank groups,
+//     whatever the filter tap's shift;
+//   one bare barrier per weight stage, as in k_pwb; fragments of tap t + 1 are read while tap t is
+//     multiplied.
+// Every byte from L2 feeds eight waves' worth of MFMAs: 128 channels x 256 pixels take in
+// 1 byte per ~200 FLOP, against ~50-100 for the per-wave weight streams of the fused-group kernel.
+// Work items: channel group slowest, so that the workgroups running at one time share weights; each
+// XCD gets a contiguous range of items.
+template <int WC, int ACH>
+__global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
+{
+    constexpr int NCBW = 2 * WC;                     // 32-channel blocks of the workgroup
+    constexpr int NWF = 9 * NCBW;                    // weight fragments per stage
+    constexpr int LPW_W = (NWF + DLF_C3_WAVES - 1) / DLF_C3_WAVES;
+    constexpr int W_HALFS = NWF * 512;
+    constexpr int LPP = ACH / 8;                     // lanes (16-byte parts) per pixel
+    constexpr int PPI = 64 / LPP;                    // pixels per load instruction
+    constexpr int SH = LPP == 8 ? 1 : 2;             // f(h) = (h >> SH) % LPP
+    constexpr int CPB = ACH / 16;                    // weight stages per activation block
+    constexpr int MAXA = DLF_C3_MAX_ACT_LOADS;
+    constexpr int ROW = 64 + 8;
+    static_assert(ACH == 32 || ACH == 64, "activation block: 64 or 128 bytes per pixel");
+    // the wave index as a scalar: everything derived from it (fragment numbers, LDS targets, weight
+    // addresses) then lives in scalar registers
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int wc = WC == 1 ? 0 : (wave & (WC - 1)), wp = WC == 1 ? wave : wave / WC;
+    const int pw = a.tw + 2;
+    const int npxh = a.npxh, na_i = a.na_i, lpa = a.lpw_a, nst = a.nst;
+    const int act_halfs = na_i * 512;
+    half_t* const wring = lds + 2 * act_halfs;
+    half_t* const trash = wring + nst * W_HALFS;
+    const int KT = a.cin >> 4, NB = a.cin / ACH;
+    const half_t* const inp = (const half_t*)a.in;
+    const half_t* const zsrc = (const half_t*)a.w + (size_t)a.ncb * a.nsteps * 512 + lane * 8;
+    const unsigned pw_m = div_magic(pw);
+    const unsigned tw_m = div_magic(a.pool2 ? a.tw >> 1 : a.tw);
+    const half_t* resp = (const half_t*)a.res;
+    half_t* outp = (half_t*)a.out;
+    const int act_epi = resp != nullptr ? 0 : a.act;
+    const unsigned lo_e = act_lo(act_epi), hi_e = act_hi(act_epi);
+    const unsigned lo_r = act_lo(a.act), hi_r = act_hi(a.act);
+    const int npix = a.th * a.tw;
+    const int per_xcd = (a.nitems + 7) >> 3;
+    bool again = false;
+    for (int li = blockIdx.x >> 3; li < per_xcd; li += gridDim.x >> 3) {
+        const int item = (blockIdx.x & 7) * per_xcd + li;
+        if (item >= a.nitems) break;
+        if (again) {
+            // the stores of the previous item must not be counted among the loads of the ring, and
+            // the transpose buffers of all waves must have been read before the ring is refilled
+            wait_vmcnt<0>();
+            asm volatile("s_barrier" ::: "memory");
+        }
+        again = true;
+        const int cg = item / a.ntiles;
+        int t = item - cg * a.ntiles;
+        const int tx = t % a.tiles_x;
+        t /= a.tiles_x;
+        const int ty = t % a.tiles_y;
+        const int n = t / a.tiles_y;
+        const int ty0 = ty * a.th, tx0 = tx * a.tw;
+
+        // the oldest loads in flight: complete by the first wait of the ring
+        f4v bias[2][4];
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+            const int cb = min(cg * NCBW + wc * 2 + f, a.ncb - 1);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) bias[f][q] = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
+        }
+
+        // this wave's weight loads of a stage: fragments wave, wave + 8, ... (tap-major)
+        const half_t* wsrc[LPW_W];
+#pragma unroll
+        for (int i = 0; i < LPW_W; ++i) {
+            const int fi = wave + DLF_C3_WAVES * i;
+            wsrc[i] = zsrc;
+            if (fi < NWF) {
+                const int tap = fi / NCBW, cbi = fi - tap * NCBW;
+                const int cb = min(cg * NCBW + cbi, a.ncb - 1);
+                wsrc[i] = (const half_t*)a.w + ((size_t)cb * a.nsteps + tap * 2) * 512 + lane * 8;
+            }
+        }
+        // ... and its activation loads of a block: instructions wave, wave + 8, ..., each PPI halo
+        // pixels x LPP parts; element offset of the lane's 16 bytes in block 0, or -1 for zeros
+        int aoff[MAXA];
+#pragma unroll
+        for (int i = 0; i < MAXA; ++i) {
+            aoff[i] = -1;
+            const int j = wave + DLF_C3_WAVES * i;
+            const int hpx = j * PPI + lane / LPP;
+            if (i < lpa && hpx < npxh) {
+                const int hy = div_by(hpx, pw_m), hx = hpx - hy * pw;
+                const int gy = ty0 - 1 + hy, gx = tx0 - 1 + hx;
+                if (gy >= 0 && gy < a.h && gx >= 0 && gx < a.w_) {
+                    const int q = (lane & (LPP - 1)) ^ ((hpx >> SH) & (LPP - 1));
+                    aoff[i] = ((n * a.h + gy) * a.w_ + gx) * a.cin + q * 8;
+                }
+            }
+        }
+        auto issue_w = [&](int c, int slot) {
+            half_t* sb = wring + slot * W_HALFS;
+            const int woff = ((c >> 1) * 18 + (c & 1)) * 512;    // stage c = 16-channel chunk c
+#pragma unroll
+            for (int i = 0; i < LPW_W; ++i) {
+                const int fi = wave + DLF_C3_WAVES * i;
+                half_t* dst = fi < NWF ? sb + fi * 512 : trash;
+                const half_t* src = fi < NWF ? wsrc[i] + woff : zsrc;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                                 (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+            }
+        };
+        auto issue_a = [&](int b) {
+            half_t* ab = lds + (b & 1) * act_halfs;
+#pragma unroll
+            for (int i = 0; i < MAXA; ++i) {
+                if (i < lpa) {
+                    const int j = wave + DLF_C3_WAVES * i;
+                    half_t* dst = j < na_i ? ab + j * 512 : trash;
+                    const half_t* src = aoff[i] >= 0 ? inp + (unsigned)(aoff[i] + b * ACH) : zsrc;
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                                     (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+                }
+            }
+        };
+        issue_a(0);
+        for (int c = 0; c < nst - 1; ++c)
+            if (c < KT) issue_w(c, c);
+
+        // the wave's two 32-pixel blocks: halo index of each lane's pixel under tap (0, 0)
+        int hp0[2];
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            int pix = wp * 64 + p * 32 + l32;
+            pix = pix < npix ? pix : 0;               // surplus lanes compute a result nobody stores
+            int ry, rx;
+            pix_to_rc(pix, a.tw, tw_m, a.pool2, ry, rx);
+            hp0[p] = ry * pw + rx;
+        }
+        f16v acc[2][2];
+#pragma unroll
+        for (int f = 0; f < 2; ++f)
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[f][p][r] = 0.0f;
+
+        // Loads retire in issue order: prologue A0 W0 .. W(nst-2), then iteration i issues
+        // W(i + nst - 1) and, when it starts block i / CPB, the next block behind it.  Iteration c
+        // needs W(c) and block c / CPB: it may leave outstanding exactly what was issued after both.
+        auto a_count = [&](int i) { return 1 + min(NB - 1, (i + CPB - 1) / CPB); };   // blocks issued before iteration i
+        int slot = 0;
+        for (int c = 0; c < KT; ++c) {
+            const int blk = c / CPB, kq = c - blk * CPB;
+            {
+                const int total = LPW_W * min(KT, c + nst - 1) + lpa * a_count(c);
+                const int pos_w = LPW_W * (c + 1) + lpa * a_count(max(0, c - nst + 1));
+                const int pos_a = blk == 0 ? lpa : lpa * (blk + 1) + LPW_W * min(KT, (blk - 1) * CPB + nst);
+                wait_vmcnt_dyn(total - max(pos_w, pos_a));
+            }
+            asm volatile("s_barrier" ::: "memory");
+            // every wave is done with stage c - 1 (and, at the start of a block, with the block
+            // before it): refill
+            if (c + nst - 1 < KT) issue_w(c + nst - 1, slot == 0 ? nst - 1 : slot - 1);
+            if (kq == 0 && blk + 1 < NB) issue_a(blk + 1);
+            const half_t* wf = wring + slot * W_HALFS + (wc * 2) * 512 + lane * 8;
+            const half_t* ab = lds + (blk & 1) * act_halfs;
+            const int q = 2 * kq + lhi;
+            // halo pixel h, part q: h * ACH halfs + 8 * (q ^ f(h))
+            auto b_at = [&](int h) { return ab + h * ACH + ((((h >> SH) & (LPP - 1)) ^ q) << 3); };
+            h8 af[2][2], bf[2][2];
+#pragma unroll
+            for (int f = 0; f < 2; ++f) af[0][f] = *(const h8*)(wf + f * 512);
+#pragma unroll
+            for (int p = 0; p < 2; ++p) bf[0][p] = *(const h8*)b_at(hp0[p]);
+            // A wave issues in order: each LDS read of the next tap's fragments is placed behind an
+            // MFMA of the current tap and is served while that MFMA occupies the matrix pipe; the
+            // scheduling barriers keep exactly this order.
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int tap = 0; tap < 9; ++tap) {
+                const int cur = tap & 1, nxt = cur ^ 1;
+                const int toff = ((tap + 1) / 3) * pw + ((tap + 1) % 3);
+                const half_t* nb0 = b_at(hp0[0] + toff);
+                const half_t* nb1 = b_at(hp0[1] + toff);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int f = 0; f < 2; ++f)
+#pragma unroll
+                    for (int p = 0; p < 2; ++p) {
+                        acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][f], bf[cur][p], acc[f][p], 0, 0, 0);
+                        if (tap + 1 < 9) {
+                            // behind the first three MFMAs, so that the last read has an MFMA's time
+                            const int k = f * 2 + p;
+                            if (k == 0) {
+                                af[nxt][0] = *(const h8*)(wf + ((tap + 1) * NCBW) * 512);
+                                bf[nxt][0] = *(const h8*)nb0;
+                            } else if (k == 1) {
+                                bf[nxt][1] = *(const h8*)nb1;
+                            } else if (k == 2) {
+                                af[nxt][1] = *(const h8*)(wf + ((tap + 1) * NCBW + 1) * 512);
+                            }
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+            }
+            slot = slot + 1 == nst ? 0 : slot + 1;
+        }
+        // every wave is done with the ring (all loads were waited for above): reuse it
+        asm volatile("s_barrier" ::: "memory");
+        half_t* tb = lds + wave * (64 * ROW);
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+#pragma unroll
+            for (int f = 0; f < 2; ++f)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    unsigned u0 = cvt_pk(acc[f][p][q * 4 + 0] + bias[f][q][0], acc[f][p][q * 4 + 1] + bias[f][q][1]);
+                    unsigned u1 = cvt_pk(acc[f][p][q * 4 + 2] + bias[f][q][2], acc[f][p][q * 4 + 3] + bias[f][q][3]);
+                    int row = p * 32 + l32;
+                    bool wr = true;
+                    if (a.pool2) {
+                        // the 2x2 window is the 4 lanes of a quad (monotone rounding and clamps
+                        // commute with the maximum)
+                        u0 = quad_max_pk(u0);
+                        u1 = quad_max_pk(u1);
+                        wr = (l32 & 3) == 0;
+                        row >>= 2;
+                    }
+                    u0 = pk_min(pk_max(u0, lo_e), hi_e);
+                    u1 = pk_min(pk_max(u1, lo_e), hi_e);
+                    const u2v uu = {u0, u1};
+                    if (wr) *(u2v*)(tb + row * ROW + f * 32 + q * 8 + lhi * 4) = uu;
+                }
+        __builtin_amdgcn_wave_barrier();
+        // 16 bytes per lane: 8 lanes cover the wave's 64 channels of one pixel, 8 pixels per pass
+        const int part = lane & 7;
+        const int cch = (cg * NCBW + wc * 2) * 32 + part * 8;
+        const int rows = a.pool2 ? 16 : 64;
+        const int oh = a.pool2 ? a.h >> 1 : a.h, ow = a.pool2 ? a.w_ >> 1 : a.w_;
+        const int otw = a.pool2 ? a.tw >> 1 : a.tw;
+        const int oy0 = a.pool2 ? ty0 >> 1 : ty0, ox0 = a.pool2 ? tx0 >> 1 : tx0;
+        const int onpix = a.pool2 ? npix >> 2 : npix;
+        for (int r0 = 0; r0 < rows; r0 += 32) {
+            u4v val[4], rv[4];
+            bool ok[4];
+            unsigned go[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = r0 + i * 8 + (lane >> 3);
+                const int opix = wp * rows + row;
+                const int ry = div_by(opix, tw_m), rx = opix - ry * otw;
+                const int gy = oy0 + ry, gx = ox0 + rx;
+                ok[i] = row < rows && opix < onpix && gy < oh && gx < ow && cch < a.cout;
+                go[i] = (unsigned)(((n * oh + gy) * ow + gx) * a.cout + cch);
+                if (resp != nullptr && ok[i]) rv[i] = *(const u4v*)(resp + go[i]);
+                val[i] = *(const u4v*)(tb + (row & 63) * ROW + part * 8);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (ok[i]) {
+                    if (resp != nullptr) {
+                        val[i].x = pk_min(pk_max(pk_add(val[i].x, rv[i].x), lo_r), hi_r);
+                        val[i].y = pk_min(pk_max(pk_add(val[i].y, rv[i].y), lo_r), hi_r);
+                        val[i].z = pk_min(pk_max(pk_add(val[i].z, rv[i].z), lo_r), hi_r);
+                        val[i].w = pk_min(pk_max(pk_add(val[i].w, rv[i].w), lo_r), hi_r);
+                    }
+                    *(u4v*)(outp + go[i]) = val[i];
+                }
+            }
+        }
+    }
+}
+
 // Fully connected layer (Eq. 2 with M = batch): y[n][co] = act(bias[co] + sum_k x[n][k] w[co][k]).
 // One workgroup per 32 output channels; its 8 waves split K, each streaming a contiguous share
 // of the packed weight fragments from HBM exactly once; partial sums meet in LDS.
@@ -1596,6 +1907,18 @@ static group_kernel_t group_kernel(int variant, bool ksplit)
     }
 }
 
+typedef void (*c3_kernel_t)(const DlfC3Args);
+static c3_kernel_t c3_kernel(int shape)
+{
+    switch (shape) {
+    case 0: return k_c3b<2, 32>;
+    case 1: return k_c3b<2, 64>;
+    case 2: return k_c3b<1, 32>;
+    case 3: return k_c3b<1, 64>;
+    default: return nullptr;
+    }
+}
+
 extern "C" int dlf_kernels_init(void)
 {
     for (int v = 0; v < 2 * DLF_NUM_VARIANTS; ++v) {
@@ -1605,7 +1928,20 @@ extern "C" int dlf_kernels_init(void)
                                            160 * 1024);
         if (e != hipSuccess) return (int)e;
     }
+    for (int sh = 0; sh < DLF_C3_SHAPES; ++sh) {
+        hipError_t e = hipFuncSetAttribute((const void*)c3_kernel(sh), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           160 * 1024);
+        if (e != hipSuccess) return (int)e;
+    }
     return 0;
+}
+
+extern "C" int dlf_launch_c3(const DlfC3Args* a, int shape, int grid, int lds_bytes, void* stream)
+{
+    c3_kernel_t k = c3_kernel(shape);
+    if (k == nullptr || grid < 8 || (grid & 7) != 0 || lds_bytes <= 0) return (int)hipErrorInvalidValue;
+    launch(k, dim3(grid), dim3(DLF_C3_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
+    return (int)hipGetLastError();
 }
 
 extern "C" int dlf_launch_group(const DlfGroupArgs* a, int variant, int grid, int lds_bytes,

@@ -316,6 +316,52 @@ def test_conv_k_split_over_waves(cin, cout, hw, ks, tile, var, nsl, sc, kh, stri
         compare(got, ref, "conv %d->%d k%d s%d, K over %d waves" % (cin, cout, kh, stride, ks))
 
 
+@pytest.mark.parametrize("cin,cout,h,w,batch,shape,th,tw,pool,act,res", [
+    (64, 128, 20, 24, 2, 1, 8, 32, 0, "relu", 0),      # ragged tiles in both directions, one activation block
+    (32, 64, 16, 16, 1, 2, 16, 32, 0, "none", 0),      # tile wider than the map, two weight stages only
+    (128, 72, 14, 14, 3, 0, 14, 16, 0, "relu6", 0),    # ragged channel group, 196 of 256 pixels
+    (64, 64, 12, 12, 2, 3, 8, 8, 1, "relu", 0),        # folded 2x2 pool, small tiles
+    (96, 200, 28, 28, 2, 0, 8, 28, 1, "relu", 0),      # folded pool, ragged channels and rows, three blocks
+    (64, 64, 30, 30, 2, 1, 16, 16, 0, "relu", 1),      # residual operand
+    (256, 256, 14, 14, 2, 2, 14, 32, 0, "relu", 1),    # long K: ring and buffers wrap many times
+    (256, 128, 14, 14, 2, 1, 8, 32, 0, "relu", 0),     # 64-channel blocks, four of them, two-stage ring
+    (192, 64, 9, 9, 1, 3, 4, 14, 0, "relu", 0),        # 64-channel blocks, three of them
+    (32, 32, 5, 5, 1, 0, 2, 4, 0, "relu", 0),          # tiny tiles: one activation load per block
+])
+def test_block3x3_kernel(cin, cout, h, w, batch, shape, th, tw, pool, act, res):
+    """The block 3x3 kernel, forced with a given shape, against the layer-by-layer oracle."""
+    announce("block 3x3", cin, cout, h, w, batch, shape, th, tw, pool, act, res)
+    from oracle import oracle as o
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    layers = []
+    if res:
+        layers.append(nets.conv(cin, cout, 1, 1, 0, "relu"))
+        layers.append(nets.conv(cout, cout, 3, 1, 1, act, residual_from=0))
+        lasts = [0, 1]
+    else:
+        layers.append(nets.conv(cin, cout, 3, 1, 1, act))
+        lasts = [0]
+        if pool:
+            layers.append(nets.maxpool(cout, 2, 2, 0))
+            lasts = [1]
+    net = _mk(layers, h, w, cin, dist="normal")
+    x, ws, bs = gen.make_params(net, batch, 5)
+    ref = o.run_net(net, x, ws, bs)
+    B.dlf_debug_block3x3_mode(1, shape, th, tw)
+    try:
+        s = Session(net, batch, ws, bs, **_manual(len(layers), lasts))
+    finally:
+        B.dlf_debug_block3x3_mode(0)
+    try:
+        cfg = B.dlf_plan_group_config(s.plan, len(lasts) - 1)
+        assert cfg["kind"] == 4 and cfg["variant"] == shape, "the block 3x3 kernel must be the one that runs"
+        got = s.run_numpy(x)
+    finally:
+        s.close()
+    compare(got, ref, "block 3x3 %d->%d %dx%d shape %d tile %dx%d" % (cin, cout, h, w, shape, th, tw))
+
+
 @pytest.mark.parametrize("k_hw,k_c,cout,batch", [(8, 64, 1000, 3), (7, 96, 70, 40), (4, 512, 96, 16)])
 def test_fc_split_k(k_hw, k_c, cout, batch):
     """Long K, few output channels: the planner splits K over workgroups (pairs of 32-channel
