@@ -1470,36 +1470,45 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
     const unsigned lo_r = act_lo(a.act), hi_r = act_hi(a.act);
     const int npix = a.th * a.tw;
     const int per_xcd = (a.nitems + 7) >> 3;
-    bool again = false;
-    for (int li = blockIdx.x >> 3; li < per_xcd; li += gridDim.x >> 3) {
-        const int item = (blockIdx.x & 7) * per_xcd + li;
-        if (item >= a.nitems) break;
-        if (again) {
-            // the stores of the previous item must not be counted among the loads of the ring, and
-            // the transpose buffers of all waves must have been read before the ring is refilled
-            wait_vmcnt<0>();
-            asm volatile("s_barrier" ::: "memory");
-        }
-        again = true;
-        const int cg = item / a.ntiles;
+    int li = blockIdx.x >> 3;
+    {
+        const int first = (blockIdx.x & 7) * per_xcd + li;
+        if (li >= per_xcd || first >= a.nitems) return;
+    }
+
+    // the wave's two 32-pixel blocks: halo index of each lane's pixel under tap (0, 0)
+    int hp0[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        int pix = wp * 64 + p * 32 + l32;
+        pix = pix < npix ? pix : 0;               // surplus lanes compute a result nobody stores
+        int ry, rx;
+        pix_to_rc(pix, a.tw, tw_m, a.pool2, ry, rx);
+        hp0[p] = ry * pw + rx;
+    }
+
+    // Load side: the item whose operands are being requested.  The first stages of item i + 1 are
+    // requested before the epilogue of item i, so that they arrive while it runs.
+    int cg = 0, n = 0, ty0 = 0, tx0 = 0;
+    f4v bias[2][4];
+    const half_t* wsrc[LPW_W];
+    int aoff[MAXA];
+    auto setup = [&](int item) {
+        cg = item / a.ntiles;
         int t = item - cg * a.ntiles;
         const int tx = t % a.tiles_x;
         t /= a.tiles_x;
         const int ty = t % a.tiles_y;
-        const int n = t / a.tiles_y;
-        const int ty0 = ty * a.th, tx0 = tx * a.tw;
-
-        // the oldest loads in flight: complete by the first wait of the ring
-        f4v bias[2][4];
+        n = t / a.tiles_y;
+        ty0 = ty * a.th;
+        tx0 = tx * a.tw;
 #pragma unroll
         for (int f = 0; f < 2; ++f) {
             const int cb = min(cg * NCBW + wc * 2 + f, a.ncb - 1);
 #pragma unroll
             for (int q = 0; q < 4; ++q) bias[f][q] = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
         }
-
         // this wave's weight loads of a stage: fragments wave, wave + 8, ... (tap-major)
-        const half_t* wsrc[LPW_W];
 #pragma unroll
         for (int i = 0; i < LPW_W; ++i) {
             const int fi = wave + DLF_C3_WAVES * i;
@@ -1512,7 +1521,6 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
         }
         // ... and its activation loads of a block: instructions wave, wave + 8, ..., each PPI halo
         // pixels x LPP parts; element offset of the lane's 16 bytes in block 0, or -1 for zeros
-        int aoff[MAXA];
 #pragma unroll
         for (int i = 0; i < MAXA; ++i) {
             aoff[i] = -1;
@@ -1527,81 +1535,92 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
                 }
             }
         }
-        auto issue_w = [&](int c, int slot) {
-            half_t* sb = wring + slot * W_HALFS;
-            const int woff = ((c >> 1) * 18 + (c & 1)) * 512;    // stage c = 16-channel chunk c
+    };
+    // one weight load (the wave's i-th of stage c, into ring slot `slot`) / one activation load
+    // (its i-th of block b)
+    auto issue_w1 = [&](int i, int c, int slot) {
+        const int fi = wave + DLF_C3_WAVES * i;
+        const int woff = ((c >> 1) * 18 + (c & 1)) * 512;    // stage c = 16-channel chunk c
+        half_t* dst = fi < NWF ? wring + slot * W_HALFS + fi * 512 : trash;
+        const half_t* src = fi < NWF ? wsrc[i] + woff : zsrc;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+    };
+    auto issue_a1 = [&](int i, int b) {
+        const int j = wave + DLF_C3_WAVES * i;
+        half_t* dst = j < na_i ? lds + (b & 1) * act_halfs + j * 512 : trash;
+        const half_t* src = aoff[i] >= 0 ? inp + (unsigned)(aoff[i] + b * ACH) : zsrc;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+    };
+    auto issue_w = [&](int c, int slot) {
 #pragma unroll
-            for (int i = 0; i < LPW_W; ++i) {
-                const int fi = wave + DLF_C3_WAVES * i;
-                half_t* dst = fi < NWF ? sb + fi * 512 : trash;
-                const half_t* src = fi < NWF ? wsrc[i] + woff : zsrc;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                                 (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
-            }
-        };
-        auto issue_a = [&](int b) {
-            half_t* ab = lds + (b & 1) * act_halfs;
+        for (int i = 0; i < LPW_W; ++i) issue_w1(i, c, slot);
+    };
+    auto issue_a = [&](int b) {
 #pragma unroll
-            for (int i = 0; i < MAXA; ++i) {
-                if (i < lpa) {
-                    const int j = wave + DLF_C3_WAVES * i;
-                    half_t* dst = j < na_i ? ab + j * 512 : trash;
-                    const half_t* src = aoff[i] >= 0 ? inp + (unsigned)(aoff[i] + b * ACH) : zsrc;
-                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                                     (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
-                }
-            }
-        };
+        for (int i = 0; i < MAXA; ++i)
+            if (i < lpa) issue_a1(i, b);
+    };
+    auto first_stages = [&]() {
         issue_a(0);
         for (int c = 0; c < nst - 1; ++c)
             if (c < KT) issue_w(c, c);
+    };
+    setup((blockIdx.x & 7) * per_xcd + li);
+    first_stages();
 
-        // the wave's two 32-pixel blocks: halo index of each lane's pixel under tap (0, 0)
-        int hp0[2];
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            int pix = wp * 64 + p * 32 + l32;
-            pix = pix < npix ? pix : 0;               // surplus lanes compute a result nobody stores
-            int ry, rx;
-            pix_to_rc(pix, a.tw, tw_m, a.pool2, ry, rx);
-            hp0[p] = ry * pw + rx;
-        }
+    for (;;) {
+        // accumulators start at the bias (requested with the item's first stages, so that it is not
+        // held in registers through the K loop)
         f16v acc[2][2];
 #pragma unroll
         for (int f = 0; f < 2; ++f)
 #pragma unroll
             for (int p = 0; p < 2; ++p)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[f][p][r] = 0.0f;
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[f][p][q * 4 + r] = bias[f][q][r];
 
-        // Loads retire in issue order: prologue A0 W0 .. W(nst-2), then iteration i issues
-        // W(i + nst - 1) and, when it starts block i / CPB, the next block behind it.  Iteration c
-        // needs W(c) and block c / CPB: it may leave outstanding exactly what was issued after both.
-        auto a_count = [&](int i) { return 1 + min(NB - 1, (i + CPB - 1) / CPB); };   // blocks issued before iteration i
+        // Loads retire in issue order: first A0 W0 .. W(nst-2); then iteration i requests W(i + nst - 1)
+        // and, when it starts block i / CPB, the next block, all at the top of the stage.  (A CU
+        // takes one such instruction per 16 cycles, so its eight waves spend about a thousand cycles
+        // there; requesting one load per filter tap instead, or half of the waves in mid-stage, was
+        // slower: the requests then have less time to land, and they already take two stages.)
+        // Iteration c needs W(c), requested in iteration c - nst + 1, and block c / CPB, requested in
+        // iteration (c / CPB - 1) * CPB: it may leave outstanding what was requested in the
+        // iterations after both of these.
+        auto w_thr = [&](int i) { return i >= 0 ? min(KT, i + nst) : min(KT, nst - 1); };     // stages requested through iteration i
+        auto a_thr = [&](int i) { return i >= 0 ? 1 + min(NB - 1, i / CPB + 1) : 1; };        // blocks
         int slot = 0;
         for (int c = 0; c < KT; ++c) {
             const int blk = c / CPB, kq = c - blk * CPB;
             {
-                const int total = LPW_W * min(KT, c + nst - 1) + lpa * a_count(c);
-                const int pos_w = LPW_W * (c + 1) + lpa * a_count(max(0, c - nst + 1));
-                const int pos_a = blk == 0 ? lpa : lpa * (blk + 1) + LPW_W * min(KT, (blk - 1) * CPB + nst);
-                wait_vmcnt_dyn(total - max(pos_w, pos_a));
+                const int need = max(max(c - nst + 1, (blk - 1) * CPB), -1);
+                wait_vmcnt_dyn(LPW_W * (w_thr(c - 1) - w_thr(need)) + lpa * (a_thr(c - 1) - a_thr(need)));
             }
             asm volatile("s_barrier" ::: "memory");
             // every wave is done with stage c - 1 (and, at the start of a block, with the block
-            // before it): refill
-            if (c + nst - 1 < KT) issue_w(c + nst - 1, slot == 0 ? nst - 1 : slot - 1);
-            if (kq == 0 && blk + 1 < NB) issue_a(blk + 1);
+            // before it; at c = 0, with the previous item's epilogue): their places may be refilled
+            const bool do_w = c + nst - 1 < KT, do_a = kq == 0 && blk + 1 < NB;
+            const int nslot = slot == 0 ? nst - 1 : slot - 1;
+            if (do_w) issue_w(c + nst - 1, nslot);
+            if (do_a) issue_a(blk + 1);
             const half_t* wf = wring + slot * W_HALFS + (wc * 2) * 512 + lane * 8;
             const half_t* ab = lds + (blk & 1) * act_halfs;
             const int q = 2 * kq + lhi;
             // halo pixel h, part q: h * ACH halfs + 8 * (q ^ f(h))
             auto b_at = [&](int h) { return ab + h * ACH + ((((h >> SH) & (LPP - 1)) ^ q) << 3); };
+            // (the empty asm keeps the compiler from precomputing the 18 tap addresses of a stage
+            // outside the K loop, which costs 36 registers)
+            int h0 = hp0[0], h1 = hp0[1];
+            asm volatile("" : "+v"(h0), "+v"(h1));
             h8 af[2][2], bf[2][2];
 #pragma unroll
             for (int f = 0; f < 2; ++f) af[0][f] = *(const h8*)(wf + f * 512);
-#pragma unroll
-            for (int p = 0; p < 2; ++p) bf[0][p] = *(const h8*)b_at(hp0[p]);
+            bf[0][0] = *(const h8*)b_at(h0);
+            bf[0][1] = *(const h8*)b_at(h1);
             // A wave issues in order: each LDS read of the next tap's fragments is placed behind an
             // MFMA of the current tap and is served while that MFMA occupies the matrix pipe; the
             // scheduling barriers keep exactly this order.
@@ -1610,8 +1629,8 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
             for (int tap = 0; tap < 9; ++tap) {
                 const int cur = tap & 1, nxt = cur ^ 1;
                 const int toff = ((tap + 1) / 3) * pw + ((tap + 1) % 3);
-                const half_t* nb0 = b_at(hp0[0] + toff);
-                const half_t* nb1 = b_at(hp0[1] + toff);
+                const half_t* nb0 = b_at(h0 + toff);
+                const half_t* nb1 = b_at(h1 + toff);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int f = 0; f < 2; ++f)
@@ -1635,69 +1654,91 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
             }
             slot = slot + 1 == nst ? 0 : slot + 1;
         }
-        // every wave is done with the ring (all loads were waited for above): reuse it
+        // every wave is done with the ring and the buffers (all loads were waited for above)
         asm volatile("s_barrier" ::: "memory");
-        half_t* tb = lds + wave * (64 * ROW);
-#pragma unroll
-        for (int p = 0; p < 2; ++p)
-#pragma unroll
-            for (int f = 0; f < 2; ++f)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    unsigned u0 = cvt_pk(acc[f][p][q * 4 + 0] + bias[f][q][0], acc[f][p][q * 4 + 1] + bias[f][q][1]);
-                    unsigned u1 = cvt_pk(acc[f][p][q * 4 + 2] + bias[f][q][2], acc[f][p][q * 4 + 3] + bias[f][q][3]);
-                    int row = p * 32 + l32;
-                    bool wr = true;
-                    if (a.pool2) {
-                        // the 2x2 window is the 4 lanes of a quad (monotone rounding and clamps
-                        // commute with the maximum)
-                        u0 = quad_max_pk(u0);
-                        u1 = quad_max_pk(u1);
-                        wr = (l32 & 3) == 0;
-                        row >>= 2;
-                    }
-                    u0 = pk_min(pk_max(u0, lo_e), hi_e);
-                    u1 = pk_min(pk_max(u1, lo_e), hi_e);
-                    const u2v uu = {u0, u1};
-                    if (wr) *(u2v*)(tb + row * ROW + f * 32 + q * 8 + lhi * 4) = uu;
-                }
-        __builtin_amdgcn_wave_barrier();
-        // 16 bytes per lane: 8 lanes cover the wave's 64 channels of one pixel, 8 pixels per pass
+        const int e_cg = cg, e_n = n, e_ty0 = ty0, e_tx0 = tx0;
+        li += gridDim.x >> 3;
+        const int next = (blockIdx.x & 7) * per_xcd + li;
+        const bool more = li < per_xcd && next < a.nitems;
+        if (more) {
+            setup(next);
+            first_stages();
+        }
+
+        // Epilogue, in passes of R pixels per wave through a transpose buffer in the last slot of
+        // the weight ring, which the first stages of the next item do not touch: fp16, (pool),
+        // activation; then 16 bytes per lane, 8 lanes covering the wave's 64 channels of a pixel.
+        constexpr int R = WC == 2 ? 32 : 16;
+        static_assert(DLF_C3_WAVES * R * ROW <= W_HALFS, "the transpose buffers fit one slot of the ring");
+        half_t* tb = wring + (nst - 1) * W_HALFS + wave * (R * ROW);
         const int part = lane & 7;
-        const int cch = (cg * NCBW + wc * 2) * 32 + part * 8;
-        const int rows = a.pool2 ? 16 : 64;
+        const int cch = (e_cg * NCBW + wc * 2) * 32 + part * 8;
+        const int rows_pass = a.pool2 ? R / 4 : R;
         const int oh = a.pool2 ? a.h >> 1 : a.h, ow = a.pool2 ? a.w_ >> 1 : a.w_;
         const int otw = a.pool2 ? a.tw >> 1 : a.tw;
-        const int oy0 = a.pool2 ? ty0 >> 1 : ty0, ox0 = a.pool2 ? tx0 >> 1 : tx0;
+        const int oy0 = a.pool2 ? e_ty0 >> 1 : e_ty0, ox0 = a.pool2 ? e_tx0 >> 1 : e_tx0;
         const int onpix = a.pool2 ? npix >> 2 : npix;
-        for (int r0 = 0; r0 < rows; r0 += 32) {
-            u4v val[4], rv[4];
-            bool ok[4];
-            unsigned go[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row = r0 + i * 8 + (lane >> 3);
-                const int opix = wp * rows + row;
-                const int ry = div_by(opix, tw_m), rx = opix - ry * otw;
-                const int gy = oy0 + ry, gx = ox0 + rx;
-                ok[i] = row < rows && opix < onpix && gy < oh && gx < ow && cch < a.cout;
-                go[i] = (unsigned)(((n * oh + gy) * ow + gx) * a.cout + cch);
-                if (resp != nullptr && ok[i]) rv[i] = *(const u4v*)(resp + go[i]);
-                val[i] = *(const u4v*)(tb + (row & 63) * ROW + part * 8);
-            }
+        for (int s = 0; s < 64 / R; ++s) {
+            const int p = s / (32 / R), sub = s % (32 / R);
+            if (l32 / R == sub) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (ok[i]) {
-                    if (resp != nullptr) {
-                        val[i].x = pk_min(pk_max(pk_add(val[i].x, rv[i].x), lo_r), hi_r);
-                        val[i].y = pk_min(pk_max(pk_add(val[i].y, rv[i].y), lo_r), hi_r);
-                        val[i].z = pk_min(pk_max(pk_add(val[i].z, rv[i].z), lo_r), hi_r);
-                        val[i].w = pk_min(pk_max(pk_add(val[i].w, rv[i].w), lo_r), hi_r);
+                for (int f = 0; f < 2; ++f)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        unsigned u0 = cvt_pk(acc[f][p][q * 4 + 0], acc[f][p][q * 4 + 1]);
+                        unsigned u1 = cvt_pk(acc[f][p][q * 4 + 2], acc[f][p][q * 4 + 3]);
+                        int row = l32 % R;
+                        bool wr = true;
+                        if (a.pool2) {
+                            // the 2x2 window is the 4 lanes of a quad (monotone rounding and clamps
+                            // commute with the maximum)
+                            u0 = quad_max_pk(u0);
+                            u1 = quad_max_pk(u1);
+                            wr = (l32 & 3) == 0;
+                            row >>= 2;
+                        }
+                        u0 = pk_min(pk_max(u0, lo_e), hi_e);
+                        u1 = pk_min(pk_max(u1, lo_e), hi_e);
+                        const u2v uu = {u0, u1};
+                        if (wr) *(u2v*)(tb + row * ROW + f * 32 + q * 8 + lhi * 4) = uu;
                     }
-                    *(u4v*)(outp + go[i]) = val[i];
+            }
+            __builtin_amdgcn_wave_barrier();
+            const int obase = wp * (a.pool2 ? 16 : 64) + (p * 32 + sub * R >> (a.pool2 ? 2 : 0));
+            for (int r0 = 0; r0 < rows_pass; r0 += 16) {
+                u4v val[2], rv[2];
+                bool ok[2];
+                unsigned go[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int row = r0 + i * 8 + (lane >> 3);
+                    const int opix = obase + row;
+                    const int ry = div_by(opix, tw_m), rx = opix - ry * otw;
+                    const int gy = oy0 + ry, gx = ox0 + rx;
+                    ok[i] = row < rows_pass && opix < onpix && gy < oh && gx < ow && cch < a.cout;
+                    go[i] = (unsigned)(((e_n * oh + gy) * ow + gx) * a.cout + cch);
+                    if (resp != nullptr && ok[i]) rv[i] = *(const u4v*)(resp + go[i]);
+                    val[i] = *(const u4v*)(tb + (row & (R - 1)) * ROW + part * 8);
+                }
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    if (ok[i]) {
+                        if (resp != nullptr) {
+                            val[i].x = pk_min(pk_max(pk_add(val[i].x, rv[i].x), lo_r), hi_r);
+                            val[i].y = pk_min(pk_max(pk_add(val[i].y, rv[i].y), lo_r), hi_r);
+                            val[i].z = pk_min(pk_max(pk_add(val[i].z, rv[i].z), lo_r), hi_r);
+                            val[i].w = pk_min(pk_max(pk_add(val[i].w, rv[i].w), lo_r), hi_r);
+                        }
+                        *(u4v*)(outp + go[i]) = val[i];
+                    }
                 }
             }
+            __builtin_amdgcn_wave_barrier();
         }
+        if (!more) break;
+        // this item's stores must not be counted among the loads of the next item's ring
+        wait_vmcnt<0>();
     }
 }
 
