@@ -54,7 +54,8 @@ PW_HBM_BYTES_PER_CYCLE = 2000
 # block 3x3 kernel: (64-channel waves along the channels, input channels per activation block)
 C3_SHAPES = ((2, 32), (2, 64), (1, 32), (1, 64))
 C3_WAVES = 8
-C3_MAX_ACT_LOADS = 8
+C3_LOAD_WAVES = 4
+C3_MAX_ACT_LOADS = 16
 C3_EPI_BYTES = C3_WAVES * 64 * 72 * 2
 C_C3_ITEM = 10000
 C_C3_SHORT_K = 6000
@@ -510,7 +511,7 @@ def c3_cost(ni, specs, batch, budget, max_lds):
                     continue
                 npxh = (th + 2) * (tw + 2)
                 na_i = cdiv(npxh, 512 // ach)
-                if cdiv(na_i, C3_WAVES) > C3_MAX_ACT_LOADS:
+                if cdiv(na_i, C3_LOAD_WAVES) > C3_MAX_ACT_LOADS:
                     continue
                 act, wstage = 2 * na_i * 1024, 9 * 2 * wc * 1024
                 nst = min(4, (max_lds - 1024 - act) // wstage)

@@ -775,7 +775,7 @@ bool c3_build(int pool2, int cin, int shape, int th, int tw, int max_lds, C3Cfg&
     c.shape = shape; c.th = th; c.tw = tw;
     c.npxh = (th + 2) * (tw + 2);
     c.na_i = ceil_div(c.npxh, 512 / ach);
-    c.lpw_a = ceil_div(c.na_i, DLF_C3_WAVES);
+    c.lpw_a = ceil_div(c.na_i, DLF_C3_LOAD_WAVES);
     if (c.lpw_a > DLF_C3_MAX_ACT_LOADS) return false;
     const int act = 2 * c.na_i * 1024, wstage = 9 * 2 * wc * 1024;
     c.nst = std::min(4, (max_lds - 1024 - act) / wstage);

@@ -121,7 +121,8 @@ struct DlfPwArgs {
 // channels at a time (two buffers).  Shapes (WC, ACH): 0 = (2, 32), 1 = (2, 64), 2 = (1, 32), 3 = (1, 64).
 #define DLF_C3_WAVES 8
 #define DLF_C3_SHAPES 4
-#define DLF_C3_MAX_ACT_LOADS 8       // activation loads per wave per block the kernel is built for
+#define DLF_C3_LOAD_WAVES 4          // waves 0 .. 3 request the operands of all eight
+#define DLF_C3_MAX_ACT_LOADS 16      // activation loads per requesting wave per block the kernel is built for
 #define DLF_C3_EPI_BYTES (DLF_C3_WAVES * 64 * 72 * 2)   // transpose buffers of the epilogue
 struct DlfC3Args {
     const void* in;       // [batch][h][w][cin] fp16
@@ -136,7 +137,7 @@ struct DlfC3Args {
     int32_t nitems;       // n_cg * ntiles (channel group slowest)
     int32_t npxh;         // (th + 2) * (tw + 2): pixels of the halo region
     int32_t na_i;         // ceil(npxh / (512 / ACH)): activation load instructions per block (1 KiB each)
-    int32_t lpw_a;        // ceil(na_i / 8): ... per wave
+    int32_t lpw_a;        // ceil(na_i / DLF_C3_LOAD_WAVES): ... per requesting wave
     int32_t nst;          // stages in the weight ring (2 .. 4)
 };
 

@@ -1391,7 +1391,7 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
 }
 
 // Waits until at most n of this wave's loads are outstanding, for a wave-uniform n known only at
-// run time (the count is an immediate of the instruction); counts above 32 wait for everything.
+// run time (the count is an immediate of the instruction); counts above 48 wait for everything.
 __device__ __forceinline__ void wait_vmcnt_dyn(int n)
 {
     switch (__builtin_amdgcn_readfirstlane(n)) {
@@ -1401,7 +1401,9 @@ __device__ __forceinline__ void wait_vmcnt_dyn(int n)
     DLF_WAIT_CASE(13) DLF_WAIT_CASE(14) DLF_WAIT_CASE(15) DLF_WAIT_CASE(16) DLF_WAIT_CASE(17) DLF_WAIT_CASE(18)
     DLF_WAIT_CASE(19) DLF_WAIT_CASE(20) DLF_WAIT_CASE(21) DLF_WAIT_CASE(22) DLF_WAIT_CASE(23) DLF_WAIT_CASE(24)
     DLF_WAIT_CASE(25) DLF_WAIT_CASE(26) DLF_WAIT_CASE(27) DLF_WAIT_CASE(28) DLF_WAIT_CASE(29) DLF_WAIT_CASE(30)
-    DLF_WAIT_CASE(31) DLF_WAIT_CASE(32)
+    DLF_WAIT_CASE(31) DLF_WAIT_CASE(32) DLF_WAIT_CASE(33) DLF_WAIT_CASE(34) DLF_WAIT_CASE(35) DLF_WAIT_CASE(36)
+    DLF_WAIT_CASE(37) DLF_WAIT_CASE(38) DLF_WAIT_CASE(39) DLF_WAIT_CASE(40) DLF_WAIT_CASE(41) DLF_WAIT_CASE(42)
+    DLF_WAIT_CASE(43) DLF_WAIT_CASE(44) DLF_WAIT_CASE(45) DLF_WAIT_CASE(46) DLF_WAIT_CASE(47) DLF_WAIT_CASE(48)
 #undef DLF_WAIT_CASE
     default: wait_vmcnt<0>(); break;
     }
@@ -1439,7 +1441,8 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
 {
     constexpr int NCBW = 2 * WC;                     // 32-channel blocks of the workgroup
     constexpr int NWF = 9 * NCBW;                    // weight fragments per stage
-    constexpr int LPW_W = (NWF + DLF_C3_WAVES - 1) / DLF_C3_WAVES;
+    constexpr int LW = DLF_C3_LOAD_WAVES;              // waves that request operands (one per SIMD)
+    constexpr int LPW_W = (NWF + LW - 1) / LW;
     constexpr int W_HALFS = NWF * 512;
     constexpr int LPP = ACH / 8;                     // lanes (16-byte parts) per pixel
     constexpr int PPI = 64 / LPP;                    // pixels per load instruction
@@ -1492,8 +1495,7 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
     int cg = 0, n = 0, ty0 = 0, tx0 = 0;
     f4v bias[2][4];
     const half_t* wsrc[LPW_W];
-    int aoff[MAXA];
-    auto setup = [&](int item) {
+    auto setup = [&](int item) __attribute__((always_inline)) {
         cg = item / a.ntiles;
         int t = item - cg * a.ntiles;
         const int tx = t % a.tiles_x;
@@ -1511,7 +1513,7 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
         // this wave's weight loads of a stage: fragments wave, wave + 8, ... (tap-major)
 #pragma unroll
         for (int i = 0; i < LPW_W; ++i) {
-            const int fi = wave + DLF_C3_WAVES * i;
+            const int fi = wave + LW * i;
             wsrc[i] = zsrc;
             if (fi < NWF) {
                 const int tap = fi / NCBW, cbi = fi - tap * NCBW;
@@ -1519,50 +1521,48 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
                 wsrc[i] = (const half_t*)a.w + ((size_t)cb * a.nsteps + tap * 2) * 512 + lane * 8;
             }
         }
-        // ... and its activation loads of a block: instructions wave, wave + 8, ..., each PPI halo
-        // pixels x LPP parts; element offset of the lane's 16 bytes in block 0, or -1 for zeros
-#pragma unroll
-        for (int i = 0; i < MAXA; ++i) {
-            aoff[i] = -1;
-            const int j = wave + DLF_C3_WAVES * i;
-            const int hpx = j * PPI + lane / LPP;
-            if (i < lpa && hpx < npxh) {
-                const int hy = div_by(hpx, pw_m), hx = hpx - hy * pw;
-                const int gy = ty0 - 1 + hy, gx = tx0 - 1 + hx;
-                if (gy >= 0 && gy < a.h && gx >= 0 && gx < a.w_) {
-                    const int q = (lane & (LPP - 1)) ^ ((hpx >> SH) & (LPP - 1));
-                    aoff[i] = ((n * a.h + gy) * a.w_ + gx) * a.cin + q * 8;
-                }
-            }
-        }
     };
     // one weight load (the wave's i-th of stage c, into ring slot `slot`) / one activation load
     // (its i-th of block b)
-    auto issue_w1 = [&](int i, int c, int slot) {
-        const int fi = wave + DLF_C3_WAVES * i;
+    auto issue_w1 = [&](int i, int c, int slot) __attribute__((always_inline)) {
+        const int fi = wave + LW * i;
         const int woff = ((c >> 1) * 18 + (c & 1)) * 512;    // stage c = 16-channel chunk c
         half_t* dst = fi < NWF ? wring + slot * W_HALFS + fi * 512 : trash;
         const half_t* src = fi < NWF ? wsrc[i] + woff : zsrc;
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                          (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
     };
-    auto issue_a1 = [&](int i, int b) {
-        const int j = wave + DLF_C3_WAVES * i;
+    // activation load i of the wave for block b: instruction j = wave + LW * i covers PPI halo
+    // pixels x LPP parts; the lane's 16 bytes, or zeros for a pixel outside the image (the offsets
+    // are formed anew each time: a wave that requests is waiting on the memory pipe anyway)
+    auto issue_a1 = [&](int i, int b) __attribute__((always_inline)) {
+        const int j = wave + LW * i;
         half_t* dst = j < na_i ? lds + (b & 1) * act_halfs + j * 512 : trash;
-        const half_t* src = aoff[i] >= 0 ? inp + (unsigned)(aoff[i] + b * ACH) : zsrc;
+        const half_t* src = zsrc;
+        const int hpx = j * PPI + lane / LPP;
+        if (hpx < npxh) {
+            const int hy = div_by(hpx, pw_m), hx = hpx - hy * pw;
+            const int gy = ty0 - 1 + hy, gx = tx0 - 1 + hx;
+            if (gy >= 0 && gy < a.h && gx >= 0 && gx < a.w_) {
+                const int q = (lane & (LPP - 1)) ^ ((hpx >> SH) & (LPP - 1));
+                src = inp + (unsigned)(((n * a.h + gy) * a.w_ + gx) * a.cin + q * 8 + b * ACH);
+            }
+        }
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                          (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
     };
-    auto issue_w = [&](int c, int slot) {
+    auto issue_w = [&](int c, int slot) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < LPW_W; ++i) issue_w1(i, c, slot);
     };
-    auto issue_a = [&](int b) {
+    auto issue_a = [&](int b) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < MAXA; ++i)
             if (i < lpa) issue_a1(i, b);
     };
-    auto first_stages = [&]() {
+    const bool loader = wave < LW;
+    auto first_stages = [&]() __attribute__((always_inline)) {
+        if (!loader) return;
         issue_a(0);
         for (int c = 0; c < nst - 1; ++c)
             if (c < KT) issue_w(c, c);
@@ -1584,19 +1584,22 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
                     for (int r = 0; r < 4; ++r) acc[f][p][q * 4 + r] = bias[f][q][r];
 
         // Loads retire in issue order: first A0 W0 .. W(nst-2); then iteration i requests W(i + nst - 1)
-        // and, when it starts block i / CPB, the next block, all at the top of the stage.  (A CU
-        // takes one such instruction per 16 cycles, so its eight waves spend about a thousand cycles
-        // there; requesting one load per filter tap instead, or half of the waves in mid-stage, was
-        // slower: the requests then have less time to land, and they already take two stages.)
+        // and, when it starts block i / CPB, the next block, all at the top of the stage.  A CU
+        // takes one such instruction per 16 cycles, so the requests of a stage keep the issuing
+        // waves, which issue in order, from their MFMAs for about a thousand cycles.  Only waves
+        // 0-3, one per SIMD, request operands: while such a wave waits, the other wave of its SIMD
+        // (4-7, which never touches memory in the K loop) has the matrix pipe to itself, and is
+        // waiting at the next barrier by the time the first catches up.  (Requesting one load per
+        // filter tap from every wave, or in mid-stage from half of them, was slower.)
         // Iteration c needs W(c), requested in iteration c - nst + 1, and block c / CPB, requested in
         // iteration (c / CPB - 1) * CPB: it may leave outstanding what was requested in the
         // iterations after both of these.
-        auto w_thr = [&](int i) { return i >= 0 ? min(KT, i + nst) : min(KT, nst - 1); };     // stages requested through iteration i
-        auto a_thr = [&](int i) { return i >= 0 ? 1 + min(NB - 1, i / CPB + 1) : 1; };        // blocks
+        auto w_thr = [&](int i) __attribute__((always_inline)) { return i >= 0 ? min(KT, i + nst) : min(KT, nst - 1); };     // stages requested through iteration i
+        auto a_thr = [&](int i) __attribute__((always_inline)) { return i >= 0 ? 1 + min(NB - 1, i / CPB + 1) : 1; };        // blocks
         int slot = 0;
         for (int c = 0; c < KT; ++c) {
             const int blk = c / CPB, kq = c - blk * CPB;
-            {
+            if (loader) {
                 const int need = max(max(c - nst + 1, (blk - 1) * CPB), -1);
                 wait_vmcnt_dyn(LPW_W * (w_thr(c - 1) - w_thr(need)) + lpa * (a_thr(c - 1) - a_thr(need)));
             }
@@ -1605,13 +1608,15 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
             // before it; at c = 0, with the previous item's epilogue): their places may be refilled
             const bool do_w = c + nst - 1 < KT, do_a = kq == 0 && blk + 1 < NB;
             const int nslot = slot == 0 ? nst - 1 : slot - 1;
-            if (do_w) issue_w(c + nst - 1, nslot);
-            if (do_a) issue_a(blk + 1);
+            if (loader) {
+                if (do_w) issue_w(c + nst - 1, nslot);
+                if (do_a) issue_a(blk + 1);
+            }
             const half_t* wf = wring + slot * W_HALFS + (wc * 2) * 512 + lane * 8;
             const half_t* ab = lds + (blk & 1) * act_halfs;
             const int q = 2 * kq + lhi;
             // halo pixel h, part q: h * ACH halfs + 8 * (q ^ f(h))
-            auto b_at = [&](int h) { return ab + h * ACH + ((((h >> SH) & (LPP - 1)) ^ q) << 3); };
+            auto b_at = [&](int h) __attribute__((always_inline)) { return ab + h * ACH + ((((h >> SH) & (LPP - 1)) ^ q) << 3); };
             // (the empty asm keeps the compiler from precomputing the 18 tap addresses of a stage
             // outside the K loop, which costs 36 registers)
             int h0 = hp0[0], h1 = hp0[1];
