@@ -30,8 +30,8 @@ RIDGE = MFMA_FP16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # FLOP per byte
 # Valid only for the kernel sources they were taken with: `csrc_sha1` is checked at run time and
 # `traffic` is reported as null when the sources have changed since.
 TRAFFIC = {
-    "csrc_sha1": "5c3d0034ad90415171a2c1529d0f059d493e76ef",
-    "bytes_per_launch": {"resnet50_b32": {"k_group<1,2,4>": 67710066, "k_pwb<2,2>": 43003053, "k_pwb<1,4>": 64619052, "k_group<1,2,2>": 22526052, "k_pw_sk": 55598327, "k_gap": 6584706, "k_fc": 5398514}},
+    "csrc_sha1": "d59d39133447d1d2ce8866740df2cb60290eede3",
+    "bytes_per_launch": {"resnet50_b32": {"k_group<1,2,4>": 67707065, "k_pwb<2,2>": 43005776, "k_pwb<1,4>": 64613196, "k_group<1,2,2>": 23319055, "k_pw_sk": 55595658, "k_group<1,2,2,true>": 19653961, "k_gap": 6584709, "k_fc": 5398517}},
 }
 
 
