@@ -136,6 +136,10 @@ def main():
     ap.add_argument("--budget", type=int, default=256, help="budget of every group of --plan unfused")
     ap.add_argument("--fixed-budget", type=int, default=0,
                     help="one budget for all groups of --plan greedy / layerwise / maxfuse (0: the tuner's)")
+    ap.add_argument("--eq5", default="",
+                    help="alpha,beta,scale,offset of Eq. 5 for --plan greedy / layerwise (default: the library's)")
+    ap.add_argument("--opcount-critical", type=float, default=0.0,
+                    help="Algorithm 1's operation count per CU at which a block is closed (0: the library's)")
     ap.add_argument("--refine", type=int, default=0,
                     help="measured refinement of the plan before timing: candidates per group (0 = off)")
     ap.add_argument("--table", action="store_true", help="per-group table on stderr")
@@ -174,6 +178,12 @@ def main():
         plan = dict(mode=B.TUNER_MAXFUSE, fixed_budget=args.fixed_budget)
     else:
         plan = dict(mode=B.TUNER_MANUAL, group_last=list(range(n)), group_budget=[args.budget] * n)
+    if args.plan in ("greedy", "layerwise"):
+        if args.eq5:
+            al, be, sc, of = (float(v) for v in args.eq5.split(","))
+            plan.update(alpha=al, beta=be, mp_scale=sc, mp_offset=of)
+        if args.opcount_critical > 0:
+            plan.update(opcount_critical=args.opcount_critical)
     s = Session(net, batch, ws, bs, **plan)
     xt = torch.from_numpy(x).cuda()
     out = torch.empty(s.out_shape, dtype=torch.float16, device="cuda")
@@ -286,6 +296,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s_b%d" % (net["name"], batch), "batch": batch,
                    "plan": args.plan + ("@%d" % args.fixed_budget if args.fixed_budget > 0 else "")
+                   + ("[eq5 %s]" % args.eq5 if args.eq5 and args.plan in ("greedy", "layerwise") else "")
+                   + ("[crit %g]" % args.opcount_critical if args.opcount_critical > 0 and args.plan == "greedy" else "")
                    + ("@%d" % args.budget if args.plan == "unfused" else "")
                    + ("+refine%d" % args.refine if args.refine > 0 else ""),
                    "groups_refined": refined, "groups": len(s.groups), "layers": n,
