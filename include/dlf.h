@@ -146,9 +146,13 @@ dlf_status dlf_run_group(const dlf_plan_t* plan, int32_t g, const void* in_dev, 
 const void* dlf_plan_layer_output(const dlf_plan_t* plan, int32_t layer);
 
 /* Kernel configuration chosen for group g: kind (0 fused-group kernel, 1 FC, 2 global avgpool,
- * 3 pointwise-convolution kernel: a single 1x1 layer run barrier-free, one wave per 64x64 item),
- * register-tile variant (per-wave accumulator tile, output channels x pixels: 0 = 64x64,
- * 1 = 32x128, 2 = 32x64, 3 = 32x64 built for two workgroups per CU), channel slices, channels
+ * 3 pointwise-convolution kernels: a single 1x1 layer, 4 block 3x3 kernel: a single 3x3 stride-1
+ * pad-1 layer, with its folded 2x2 pool or residual); variant: for kind 0 the register tile
+ * (per-wave accumulator tile, output channels x pixels: 0 = 64x64, 1 = 32x128, 2 = 32x64,
+ * 3 = 32x64 built for two workgroups per CU), for kind 3 the work-item form (0 = 64x64 and
+ * 1 = 32x32 per wave, 2 = 64x64 with K split over four waves, 3 = 128x128 and 4 = 64x256 blocks
+ * shared through LDS), for kind 4 the block shape (0 / 1 = 128 channels x 256 pixels, 2 / 3 =
+ * 64 x 512; odd: activations 64 input channels at a time, even: 32); channel slices, channels
  * per slice, whether stage 0 streams its input, LDS bytes per workgroup.  Any out pointer may be
  * NULL. */
 dlf_status dlf_plan_group_config(const dlf_plan_t* plan, int32_t g, int32_t* kind, int32_t* variant,
@@ -158,8 +162,9 @@ dlf_status dlf_plan_group_config(const dlf_plan_t* plan, int32_t g, int32_t* kin
  * network input); *res_layer = layer whose output is added as a residual (-2 = none). */
 dlf_status dlf_plan_group_io(const dlf_plan_t* plan, int32_t g, int32_t* in_layer, int32_t* res_layer);
 /* Measured refinement of a plan, after the paper's search procedure that times candidates on the
- * hardware (Sec. V, the reduced brute-force search): for every fused group and every single 1x1
- * layer, the top_k tilings by modelled cost (and each pointwise kernel form that applies) are run
+ * hardware (Sec. V, the reduced brute-force search): for every fused group and every single 1x1 or
+ * 3x3 layer, the top_k tilings by modelled cost (and each pointwise form, and the top_k block 3x3
+ * shapes, that apply) are run
  * `reps` times on the group's real input (caches scrubbed, the input freshly written by the group
  * in front) and the fastest replaces the planned configuration if it is at least 10 % faster.  The partition into groups and the budgets stay as planned.
  * in_dev / out_dev: DEVICE, as for dlf_run; the workspace must be bound.  Runs the network once,
