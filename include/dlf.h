@@ -129,6 +129,19 @@ dlf_status dlf_plan_bind_workspace(dlf_plan_t* plan, void* dev_ptr, size_t bytes
  * both DEVICE pointers that must not alias; hip_stream is a hipStream_t (NULL = default stream).
  * Asynchronous; reports launch errors only. */
 dlf_status dlf_run(const dlf_plan_t* plan, const void* in_dev, void* out_dev, void* hip_stream);
+/* Branches of the network (the layer graph of a residual network is not a chain): with on != 0 a
+ * group that does not read the output of the group in front of it -- the projection shortcut of a
+ * residual block, placed behind the block's first layers -- is launched by dlf_run on a second
+ * stream of the plan's own (default priority, created at the first such run), beside that group;
+ * events order it behind its producers and its consumers behind it, and hip_stream waits for the
+ * second stream before dlf_run returns, so the caller sees one stream.  Default off (every group
+ * on hip_stream, in order): measured on MI355X the hand-over between the two hardware queues costs
+ * more than the overlap gains (ResNet-18 batch 32: 313 -> 366 us per step).
+ * dlf_plan_group_stream: the stream group g runs on under the current setting, 0 = the caller's,
+ * 1 = the second one, -1 = bad argument.  dlf_run_profiled and dlf_plan_refine always run the
+ * groups in order on one stream. */
+dlf_status dlf_plan_set_overlap(dlf_plan_t* plan, int32_t on);
+int32_t dlf_plan_group_stream(const dlf_plan_t* plan, int32_t g);
 /* Profiling variant of dlf_run: runs the plan `reps` times with a HIP stop event attached to every
  * group launch on hip_stream (stamped with the end of that dispatch; a group's duration is taken
  * from the end of the previous dispatch to the end of its own), waits for the stream, and writes

@@ -105,6 +105,10 @@ def lib():
     L.dlf_debug_pointwise_mode.restype = None
     L.dlf_debug_block3x3_mode.argtypes = [i32, i32, i32, i32]
     L.dlf_debug_block3x3_mode.restype = None
+    L.dlf_plan_set_overlap.argtypes = [vp, i32]
+    L.dlf_plan_set_overlap.restype = i32
+    L.dlf_plan_group_stream.argtypes = [vp, i32]
+    L.dlf_plan_group_stream.restype = i32
     L.dlf_plan_group_config.argtypes = [vp, i32, i32p, i32p, i32p, i32p, i32p, i32p]
     L.dlf_plan_group_config.restype = i32
     L.dlf_run_profiled.argtypes = [vp, vp, vp, vp, i32, ctypes.POINTER(ctypes.c_float)]
@@ -293,6 +297,17 @@ def dlf_debug_pointwise_mode(mode=0):
     3 / 4 / 5 = wherever it applies with 64x64 / 32x32 / split-K 64x64 work items, 6 / 7 = with
     128x128 / 64x256 workgroup blocks."""
     lib().dlf_debug_pointwise_mode(mode)
+
+
+def dlf_plan_set_overlap(plan, on=True):
+    """on: groups that do not depend on the group in front of them run beside it on a second stream;
+    off (the default): every group on the caller's stream, in order."""
+    _check(lib().dlf_plan_set_overlap(plan, 1 if on else 0))
+
+
+def dlf_plan_group_stream(plan, g):
+    """0 = group g runs on the caller's stream, 1 = on the plan's second stream."""
+    return lib().dlf_plan_group_stream(plan, g)
 
 
 def dlf_debug_block3x3_mode(mode=0, shape=-1, th=0, tw=0):

@@ -986,6 +986,24 @@ struct dlf_plan_s {
     size_t ws_bytes = 0;
     char* ws = nullptr;
     int max_lds = 160 * 1024;
+    // Branches: a group that does not read the output of the group in front of it (the projection
+    // shortcut of a residual block beside the block's first layers) runs on a second stream, beside
+    // that group.  The streams meet through events: a group waits for each producer on the other
+    // stream, and the caller's stream waits for the second one at the end of dlf_run.  Off unless
+    // asked for: on this chip the hand-over between two hardware queues costs more than the
+    // overlap of two such layers gains.
+    bool overlap = false;
+    std::vector<int> on_side;        // per group: 1 = second stream
+    std::vector<int> dep_a, dep_b;   // per group: producer groups of its input / residual (-1: none)
+    mutable hipStream_t side = nullptr;
+    mutable std::vector<hipEvent_t> done;   // per group: recorded after it where another stream waits
+    mutable hipEvent_t side_end = nullptr;
+    ~dlf_plan_s()
+    {
+        for (hipEvent_t e : done) if (e) (void)hipEventDestroy(e);
+        if (side_end) (void)hipEventDestroy(side_end);
+        if (side) (void)hipStreamDestroy(side);
+    }
 };
 
 namespace {
@@ -1398,6 +1416,23 @@ dlf_status dlf_plan(const dlf_net_t* net, int32_t batch, const dlf_tuner_opts* o
             off += (G.scratch_bytes + 255) & ~(size_t)255;
         }
     plan->ws_bytes = off;
+    {
+        const size_t ng = groups.size();
+        std::vector<int> owner(n, -1);               // group that produces a layer's output
+        for (size_t g = 0; g < ng; ++g)
+            for (int l = groups[g].first; l <= groups[g].last; ++l) owner[l] = (int)g;
+        plan->on_side.assign(ng, 0);
+        plan->dep_a.assign(ng, -1);
+        plan->dep_b.assign(ng, -1);
+        for (size_t g = 0; g < ng; ++g) {
+            const GroupPlan& G = groups[g];
+            if (G.in_layer >= 0) plan->dep_a[g] = owner[G.in_layer];
+            if (G.res_stage >= 0 && G.res_layer >= 0) plan->dep_b[g] = owner[G.res_layer];
+            if (g >= 1 && g + 1 < ng && plan->on_side[g - 1] == 0 && plan->dep_a[g] != (int)g - 1 &&
+                plan->dep_b[g] != (int)g - 1)
+                plan->on_side[g] = 1;
+        }
+    }
     for (const GroupPlan& G : groups) {
         const bool in_ok = G.in_layer < 0 || plan->layer_off[G.in_layer] != (size_t)-1;
         const bool res_ok = G.res_stage < 0 || plan->layer_off[G.res_layer] != (size_t)-1;
@@ -1748,16 +1783,75 @@ dlf_status dlf_run(const dlf_plan_t* plan, const void* in_dev, void* out_dev, vo
     if (!plan->net->has_weights) return fail(DLF_ERR_NO_WEIGHTS, "network was created without weights");
     if (plan->ws_bytes > 0 && !plan->ws) return fail(DLF_ERR_INVALID_ARG, "no workspace bound");
     const size_t ng = plan->G.size();
+    bool any_side = false;
+    if (plan->overlap)
+        for (size_t g = 0; g < ng; ++g) any_side = any_side || plan->on_side[g] != 0;
+    if (any_side && plan->side == nullptr) {
+        // created on first use, with the default priority
+        if (hipStreamCreateWithFlags(&plan->side, hipStreamNonBlocking) != hipSuccess)
+            return fail(DLF_ERR_HIP, "hipStreamCreateWithFlags failed");
+        plan->done.assign(ng, nullptr);
+        for (size_t g = 0; g < ng; ++g) {
+            bool watched = false;      // does a group on the other stream read this group's output?
+            for (size_t c = g + 1; c < ng; ++c)
+                if ((plan->dep_a[c] == (int)g || plan->dep_b[c] == (int)g) && plan->on_side[c] != plan->on_side[g])
+                    watched = true;
+            if (watched && hipEventCreateWithFlags(&plan->done[g], hipEventDisableTiming) != hipSuccess)
+                return fail(DLF_ERR_HIP, "hipEventCreate failed");
+        }
+        if (hipEventCreateWithFlags(&plan->side_end, hipEventDisableTiming) != hipSuccess)
+            return fail(DLF_ERR_HIP, "hipEventCreate failed");
+    }
+    hipStream_t main_s = (hipStream_t)hip_stream;
+    if (any_side) {
+        // the second stream starts behind everything the caller's stream holds at this point (the
+        // producer of the network input, the previous run's readers of the buffers about to be
+        // rewritten), not behind the groups of this run
+        if (hipEventRecord(plan->side_end, main_s) != hipSuccess ||
+            hipStreamWaitEvent(plan->side, plan->side_end, 0) != hipSuccess)
+            return fail(DLF_ERR_HIP, "stream fork failed");
+    }
     for (size_t g = 0; g < ng; ++g) {
         const GroupPlan& G = plan->G[g];
         const void* in = G.in_layer < 0 ? in_dev : plan->ws + plan->layer_off[G.in_layer];
         const void* res = nullptr;
         if (G.res_stage >= 0) res = plan->ws + plan->layer_off[G.res_layer];
         void* out = (g + 1 == ng) ? out_dev : (void*)(plan->ws + plan->layer_off[G.last]);
-        dlf_status s = launch_one(plan, G, in, res, out, hip_stream);
+        hipStream_t st = main_s;
+        if (any_side) {
+            const int side = plan->on_side[g];
+            st = side ? plan->side : main_s;
+            const int deps[2] = {plan->dep_a[g], plan->dep_b[g]};
+            for (int d : deps)
+                if (d >= 0 && plan->on_side[d] != side && plan->done[d] != nullptr &&
+                    hipStreamWaitEvent(st, plan->done[d], 0) != hipSuccess)
+                    return fail(DLF_ERR_HIP, "hipStreamWaitEvent failed");
+        }
+        dlf_status s = launch_one(plan, G, in, res, out, (void*)st);
         if (s != DLF_OK) return s;
+        if (any_side && plan->done[g] != nullptr && hipEventRecord(plan->done[g], st) != hipSuccess)
+            return fail(DLF_ERR_HIP, "hipEventRecord failed");
+    }
+    if (any_side) {
+        // join: whatever follows on the caller's stream comes after the second stream's work
+        if (hipEventRecord(plan->side_end, plan->side) != hipSuccess ||
+            hipStreamWaitEvent(main_s, plan->side_end, 0) != hipSuccess)
+            return fail(DLF_ERR_HIP, "stream join failed");
     }
     return DLF_OK;
+}
+
+dlf_status dlf_plan_set_overlap(dlf_plan_t* plan, int32_t on)
+{
+    if (!plan) return fail(DLF_ERR_INVALID_ARG, "null plan");
+    plan->overlap = on != 0;
+    return DLF_OK;
+}
+
+int32_t dlf_plan_group_stream(const dlf_plan_t* plan, int32_t g)
+{
+    if (!plan || g < 0 || g >= (int)plan->G.size()) return -1;
+    return plan->overlap ? plan->on_side[g] : 0;
 }
 
 }  // extern "C"

@@ -229,3 +229,34 @@ def test_error_paths_return_status_not_crash():
     assert e.value.status == 7                                  # no weights
     B.dlf_plan_destroy(p)
     B.dlf_net_destroy(h)
+
+
+@pytest.mark.gpu
+def test_branches_on_a_second_stream_compute_the_same_network():
+    """dlf_plan_set_overlap: the projection shortcuts of a residual network on the plan's second
+    stream, several runs in a row (each run's buffers are rewritten by the next), against the
+    in-order run."""
+    import torch
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    net = nets.resnet18()
+    batch = 4
+    x, ws, bs = gen.make_params(net, batch, 3)
+    s = Session(net, batch, ws, bs)
+    try:
+        n_side = sum(B.dlf_plan_group_stream(s.plan, g) == 1 for g in range(len(s.groups)))
+        assert n_side == 0, "in order unless asked for"
+        want = s.run_numpy(x)
+        B.dlf_plan_set_overlap(s.plan, True)
+        n_side = sum(B.dlf_plan_group_stream(s.plan, g) == 1 for g in range(len(s.groups)))
+        assert n_side >= 3, "the three projection shortcuts of ResNet-18 do not depend on the layers in front of them"
+        xt = torch.from_numpy(x).cuda()
+        out = torch.empty(s.out_shape, dtype=torch.float16, device="cuda")
+        for _ in range(5):
+            s.run(xt, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), want)
+        B.dlf_plan_set_overlap(s.plan, False)
+        assert np.array_equal(s.run_numpy(x), want)
+    finally:
+        s.close()
