@@ -127,7 +127,10 @@ size_t dlf_plan_workspace_bytes(const dlf_plan_t* plan);
 dlf_status dlf_plan_bind_workspace(dlf_plan_t* plan, void* dev_ptr, size_t bytes);
 /* Runs the whole plan: in_dev [batch][in_h][in_w][in_c] fp16, out_dev = output of the last layer,
  * both DEVICE pointers that must not alias; hip_stream is a hipStream_t (NULL = default stream).
- * Asynchronous; reports launch errors only. */
+ * Asynchronous; reports launch errors only.  After its first call on a device (which sets kernel
+ * attributes once) it allocates nothing and records only kernel launches, so a call may be captured
+ * into a HIP graph (tested: replays equal the eager result; on MI355X a replay is no faster than
+ * the eager launches, the step being bound on the GPU side). */
 dlf_status dlf_run(const dlf_plan_t* plan, const void* in_dev, void* out_dev, void* hip_stream);
 /* Branches of the network (the layer graph of a residual network is not a chain): with on != 0 a
  * group that does not read the output of the group in front of it -- the projection shortcut of a

@@ -260,3 +260,37 @@ def test_branches_on_a_second_stream_compute_the_same_network():
         assert np.array_equal(s.run_numpy(x), want)
     finally:
         s.close()
+
+
+@pytest.mark.gpu
+def test_a_run_captured_in_a_hip_graph_replays_to_the_eager_result():
+    """dlf_run only launches kernels (after its first call on a device), so it can be captured;
+    every replay, with eager runs and synchronisations between them, must equal the eager result."""
+    from paper_2011_05630_amd.runner import Session
+    net = nets.mobilenet_v1()
+    batch = 2
+    x, ws, bs = gen.make_params(net, batch, 4)
+    s = Session(net, batch, ws, bs)
+    try:
+        xt = torch.from_numpy(x).cuda()
+        out = torch.empty(s.out_shape, dtype=torch.float16, device="cuda")
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            s.run(xt, out)                      # first run: one-time kernel set-up, outside the capture
+        torch.cuda.synchronize()
+        want = out.cpu().numpy().copy()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            s.run(xt, out)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            out.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy(), want)
+            s.run(xt, out)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy(), want)
+    finally:
+        s.close()
