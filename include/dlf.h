@@ -168,7 +168,7 @@ const void* dlf_plan_layer_output(const dlf_plan_t* plan, int32_t layer);
  * 3 = 32x64 built for two workgroups per CU), for kind 3 the work-item form (0 = 64x64 and
  * 1 = 32x32 per wave, 2 = 64x64 with K split over four waves, 3 = 128x128 and 4 = 64x256 blocks
  * shared through LDS), for kind 4 the block shape (0 / 1 = 128 channels x 256 pixels, 2 / 3 =
- * 64 x 512; odd: activations 64 input channels at a time, even: 32); channel slices, channels
+ * 64 x 512, odd: activations 64 input channels at a time, even: 32; 4 = 128 x 512); channel slices, channels
  * per slice, whether stage 0 streams its input, LDS bytes per workgroup.  Any out pointer may be
  * NULL. */
 dlf_status dlf_plan_group_config(const dlf_plan_t* plan, int32_t g, int32_t* kind, int32_t* variant,
@@ -215,7 +215,8 @@ void dlf_debug_pointwise_mode(int32_t mode);
  * modelled cost (default), 1 = the block kernel wherever it applies, 2 = never.  shape >= 0 also
  * fixes the block's shape and its th x tw pixel tile: shape 0 / 1 = 128 channels x up to 256
  * pixels with activations brought in 32 / 64 input channels at a time, 2 / 3 = 64 channels x up to
- * 512 pixels likewise; a shape that cannot be laid out falls back to the fused-group kernel.
+ * 512 pixels likewise, 4 = 128 channels x up to 512 pixels (32 input channels at a time); a shape
+ * that cannot be laid out falls back to the fused-group kernel.
  * Process-wide, not thread-safe. */
 void dlf_debug_block3x3_mode(int32_t mode, int32_t shape, int32_t th, int32_t tw);
 

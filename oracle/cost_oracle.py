@@ -51,8 +51,9 @@ C_PW_SK = 12000
 C_PW_ITEM = 2500
 C_PW_RES = 1000
 PW_HBM_BYTES_PER_CYCLE = 2000
-# block 3x3 kernel: (64-channel waves along the channels, input channels per activation block)
-C3_SHAPES = ((2, 32), (2, 64), (1, 32), (1, 64))
+# block 3x3 kernel: (64-channel waves along the channels, input channels per activation block,
+# 32-pixel blocks of a wave's part)
+C3_SHAPES = ((2, 32, 2), (2, 64, 2), (1, 32, 2), (1, 64, 2), (2, 32, 4))
 C3_WAVES = 8
 C3_LOAD_WAVES = 4
 C3_MAX_ACT_LOADS = 16
@@ -498,7 +499,7 @@ def c3_cost(ni, specs, batch, budget, max_lds):
     mem = nbytes // min(PW_HBM_BYTES_PER_CYCLE, budget * CU_BYTES_PER_CYCLE)
     kt = L["cin"] // 16
     best = None
-    for wc, ach in C3_SHAPES:
+    for wc, ach, fp in C3_SHAPES:
         if L["cin"] % ach:
             continue
         for th in TILE_H:
@@ -507,7 +508,7 @@ def c3_cost(ni, specs, batch, budget, max_lds):
             for tw in TILE_W:
                 if tw > ow and tw != TILE_W[0] and tw - ow >= 4:
                     continue
-                if th * tw > 64 * (C3_WAVES // wc) or (pool2 and ((th | tw) & 1)):
+                if th * tw > 32 * fp * (C3_WAVES // wc) or (pool2 and ((th | tw) & 1)):
                     continue
                 npxh = (th + 2) * (tw + 2)
                 na_i = cdiv(npxh, 512 // ach)
@@ -519,7 +520,7 @@ def c3_cost(ni, specs, batch, budget, max_lds):
                     continue
                 items = batch * cdiv(oh, th) * cdiv(ow, tw) * cdiv(ni.ncb[i], 2 * wc)
                 items_cu = cdiv(items, budget)
-                stage = max(9 * 4 * MFMA_CYCLES * 2 * C3_MMA_TENTHS // 10,
+                stage = max(9 * 2 * fp * MFMA_CYCLES * 2 * C3_MMA_TENTHS // 10,
                             (wstage + npxh * 32) // C3_BYTES_PER_CYCLE)
                 if nst == 2:
                     stage += C3_SHALLOW_RING

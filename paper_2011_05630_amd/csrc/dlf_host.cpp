@@ -747,8 +747,9 @@ uint64_t pw_cost_ps(const Layer& L, int batch, int budget, int& shape)
 // 1 = always where it applies, 2 = never; wc > 0 forces the shape (wc x th x tw).
 struct C3Force { int mode, shape, th, tw; };      // shape < 0: not forced
 C3Force g_c3_force = {0, -1, 0, 0};
-const int C3_WC[DLF_C3_SHAPES] = {2, 2, 1, 1};
-const int C3_ACH[DLF_C3_SHAPES] = {32, 64, 32, 64};
+const int C3_WC[DLF_C3_SHAPES] = {2, 2, 1, 1, 2};
+const int C3_ACH[DLF_C3_SHAPES] = {32, 64, 32, 64, 32};
+const int C3_FP[DLF_C3_SHAPES] = {2, 2, 2, 2, 4};      // 32-pixel blocks of a wave's part
 
 struct C3Cfg { int shape, th, tw, nst, lds_bytes, npxh, na_i, lpw_a; };
 
@@ -770,7 +771,7 @@ bool c3_build(int pool2, int cin, int shape, int th, int tw, int max_lds, C3Cfg&
 {
     if (shape < 0 || shape >= DLF_C3_SHAPES) return false;
     const int wc = C3_WC[shape], ach = C3_ACH[shape];
-    if (th < 1 || tw < 1 || th * tw > 64 * (DLF_C3_WAVES / wc) || (cin % ach) != 0) return false;
+    if (th < 1 || tw < 1 || th * tw > 32 * C3_FP[shape] * (DLF_C3_WAVES / wc) || (cin % ach) != 0) return false;
     if (pool2 && (((th | tw) & 1) != 0)) return false;
     c.shape = shape; c.th = th; c.tw = tw;
     c.npxh = (th + 2) * (tw + 2);
@@ -791,7 +792,7 @@ uint64_t c3_cost_ps(const Layer& L, int pool2, int batch, int budget, const C3Cf
     const int64_t items = tiles * ceil_div(L.ncb, 2 * wc);
     const int64_t items_cu = (items + budget - 1) / budget;
     const int64_t stage_bytes = (int64_t)9 * 2 * wc * 1024 + (int64_t)c.npxh * 32;
-    int64_t stage = std::max(9 * 4 * MFMA_CYCLES * 2 * C3_MMA_TENTHS / 10, stage_bytes / C3_BYTES_PER_CYCLE);
+    int64_t stage = std::max(9 * 2 * C3_FP[c.shape] * MFMA_CYCLES * 2 * C3_MMA_TENTHS / 10, stage_bytes / C3_BYTES_PER_CYCLE);
     if (c.nst == 2) stage += C3_SHALLOW_RING;
     const int64_t has_res = L.d.residual_from >= 0 ? 1 : 0;
     const int64_t kt = L.d.cin / 16;

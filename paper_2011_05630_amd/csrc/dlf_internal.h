@@ -118,9 +118,10 @@ struct DlfPwArgs {
 // that follows it): a workgroup of eight waves computes 64 * WC output channels x 64 * (8 / WC)
 // pixels of a th x tw tile, K streamed through LDS: the weights of all nine taps for the block's
 // channels 16 input channels at a time (a ring of stages), the tile's halo region ACH input
-// channels at a time (two buffers).  Shapes (WC, ACH): 0 = (2, 32), 1 = (2, 64), 2 = (1, 32), 3 = (1, 64).
+// channels at a time (two buffers).  A wave's part is 64 channels x 32 * FP pixels.
+// Shapes (WC, ACH, FP): 0 = (2, 32, 2), 1 = (2, 64, 2), 2 = (1, 32, 2), 3 = (1, 64, 2), 4 = (2, 32, 4).
 #define DLF_C3_WAVES 8
-#define DLF_C3_SHAPES 4
+#define DLF_C3_SHAPES 5
 #define DLF_C3_LOAD_WAVES 4          // waves 0 .. 3 request the operands of all eight
 #define DLF_C3_MAX_ACT_LOADS 16      // activation loads per requesting wave per block the kernel is built for
 #define DLF_C3_EPI_BYTES (DLF_C3_WAVES * 64 * 72 * 2)   // transpose buffers of the epilogue

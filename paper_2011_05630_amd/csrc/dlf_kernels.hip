@@ -1436,7 +1436,7 @@ __device__ __forceinline__ void wait_vmcnt_dyn(int n)
 // 1 byte per ~200 FLOP, against ~50-100 for the per-wave weight streams of the fused-group kernel.
 // Work items: channel group slowest, so that the workgroups running at one time share weights; each
 // XCD gets a contiguous range of items.
-template <int WC, int ACH>
+template <int WC, int ACH, int FP>
 __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
 {
     constexpr int NCBW = 2 * WC;                     // 32-channel blocks of the workgroup
@@ -1450,6 +1450,7 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
     constexpr int CPB = ACH / 16;                    // weight stages per activation block
     constexpr int MAXA = DLF_C3_MAX_ACT_LOADS;
     constexpr int ROW = 64 + 8;
+    static_assert(FP == 2 || FP == 4, "a wave's part: 64 channels x 32 * FP pixels");
     static_assert(ACH == 32 || ACH == 64, "activation block: 64 or 128 bytes per pixel");
     // the wave index as a scalar: everything derived from it (fragment numbers, LDS targets, weight
     // addresses) then lives in scalar registers
@@ -1479,11 +1480,11 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
         if (li >= per_xcd || first >= a.nitems) return;
     }
 
-    // the wave's two 32-pixel blocks: halo index of each lane's pixel under tap (0, 0)
-    int hp0[2];
+    // the wave's FP 32-pixel blocks: halo index of each lane's pixel under tap (0, 0)
+    int hp0[FP];
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
-        int pix = wp * 64 + p * 32 + l32;
+    for (int p = 0; p < FP; ++p) {
+        int pix = wp * (32 * FP) + p * 32 + l32;
         pix = pix < npix ? pix : 0;               // surplus lanes compute a result nobody stores
         int ry, rx;
         pix_to_rc(pix, a.tw, tw_m, a.pool2, ry, rx);
@@ -1493,7 +1494,6 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
     // Load side: the item whose operands are being requested.  The first stages of item i + 1 are
     // requested before the epilogue of item i, so that they arrive while it runs.
     int cg = 0, n = 0, ty0 = 0, tx0 = 0;
-    f4v bias[2][4];
     const half_t* wsrc[LPW_W];
     auto setup = [&](int item) __attribute__((always_inline)) {
         cg = item / a.ntiles;
@@ -1504,12 +1504,6 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
         n = t / a.tiles_y;
         ty0 = ty * a.th;
         tx0 = tx * a.tw;
-#pragma unroll
-        for (int f = 0; f < 2; ++f) {
-            const int cb = min(cg * NCBW + wc * 2 + f, a.ncb - 1);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) bias[f][q] = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
-        }
         // this wave's weight loads of a stage: fragments wave, wave + 8, ... (tap-major)
 #pragma unroll
         for (int i = 0; i < LPW_W; ++i) {
@@ -1556,9 +1550,10 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
         for (int i = 0; i < LPW_W; ++i) issue_w1(i, c, slot);
     };
     auto issue_a = [&](int b) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < MAXA; ++i)
-            if (i < lpa) issue_a1(i, b);
+        // a loop, not unrolled: the addresses are formed one load at a time (unrolled, the compiler
+        // forms all of them first, in registers the accumulators need)
+#pragma unroll 1
+        for (int i = 0; i < lpa; ++i) issue_a1(i, b);
     };
     const bool loader = wave < LW;
     auto first_stages = [&]() __attribute__((always_inline)) {
@@ -1571,17 +1566,20 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
     first_stages();
 
     for (;;) {
-        // accumulators start at the bias (requested with the item's first stages, so that it is not
-        // held in registers through the K loop)
-        f16v acc[2][2];
+        // accumulators start at the bias
+        f16v acc[2][FP];
 #pragma unroll
-        for (int f = 0; f < 2; ++f)
+        for (int f = 0; f < 2; ++f) {
+            const int cb = min(cg * NCBW + wc * 2 + f, a.ncb - 1);
 #pragma unroll
-            for (int p = 0; p < 2; ++p)
+            for (int q = 0; q < 4; ++q) {
+                const f4v bv = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
+                for (int p = 0; p < FP; ++p)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[f][p][q * 4 + r] = bias[f][q][r];
+                    for (int r = 0; r < 4; ++r) acc[f][p][q * 4 + r] = bv[r];
+            }
+        }
 
         // Loads retire in issue order: first A0 W0 .. W(nst-2); then iteration i requests W(i + nst - 1)
         // and, when it starts block i / CPB, the next block, all at the top of the stage.  A CU
@@ -1617,15 +1615,19 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
             const int q = 2 * kq + lhi;
             // halo pixel h, part q: h * ACH halfs + 8 * (q ^ f(h))
             auto b_at = [&](int h) __attribute__((always_inline)) { return ab + h * ACH + ((((h >> SH) & (LPP - 1)) ^ q) << 3); };
-            // (the empty asm keeps the compiler from precomputing the 18 tap addresses of a stage
-            // outside the K loop, which costs 36 registers)
-            int h0 = hp0[0], h1 = hp0[1];
-            asm volatile("" : "+v"(h0), "+v"(h1));
-            h8 af[2][2], bf[2][2];
+            // (the empty asm keeps the compiler from precomputing the tap addresses of a stage
+            // outside the K loop, which costs two registers per tap and pixel block)
+            int h[FP];
+#pragma unroll
+            for (int p = 0; p < FP; ++p) {
+                h[p] = hp0[p];
+                asm volatile("" : "+v"(h[p]));
+            }
+            h8 af[2][2], bf[2][FP];
 #pragma unroll
             for (int f = 0; f < 2; ++f) af[0][f] = *(const h8*)(wf + f * 512);
-            bf[0][0] = *(const h8*)b_at(h0);
-            bf[0][1] = *(const h8*)b_at(h1);
+#pragma unroll
+            for (int p = 0; p < FP; ++p) bf[0][p] = *(const h8*)b_at(h[p]);
             // A wave issues in order: each LDS read of the next tap's fragments is placed behind an
             // MFMA of the current tap and is served while that MFMA occupies the matrix pipe; the
             // scheduling barriers keep exactly this order.
@@ -1634,23 +1636,24 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
             for (int tap = 0; tap < 9; ++tap) {
                 const int cur = tap & 1, nxt = cur ^ 1;
                 const int toff = ((tap + 1) / 3) * pw + ((tap + 1) % 3);
-                const half_t* nb0 = b_at(h0 + toff);
-                const half_t* nb1 = b_at(h1 + toff);
+                const half_t* nb[FP];
+#pragma unroll
+                for (int p = 0; p < FP; ++p) nb[p] = b_at(h[p] + toff);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int f = 0; f < 2; ++f)
 #pragma unroll
-                    for (int p = 0; p < 2; ++p) {
+                    for (int p = 0; p < FP; ++p) {
                         acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][f], bf[cur][p], acc[f][p], 0, 0, 0);
                         if (tap + 1 < 9) {
-                            // behind the first three MFMAs, so that the last read has an MFMA's time
-                            const int k = f * 2 + p;
-                            if (k == 0) {
+                            // behind the first FP + 1 MFMAs, in the order the next tap needs them
+                            const int kk = f * FP + p;
+                            if (kk == 0) {
                                 af[nxt][0] = *(const h8*)(wf + ((tap + 1) * NCBW) * 512);
-                                bf[nxt][0] = *(const h8*)nb0;
-                            } else if (k == 1) {
-                                bf[nxt][1] = *(const h8*)nb1;
-                            } else if (k == 2) {
+                                bf[nxt][0] = *(const h8*)nb[0];
+                            } else if (kk < FP) {
+                                bf[nxt][kk] = *(const h8*)nb[kk];
+                            } else if (kk == FP) {
                                 af[nxt][1] = *(const h8*)(wf + ((tap + 1) * NCBW + 1) * 512);
                             }
                         }
@@ -1673,7 +1676,7 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
         // Epilogue, in passes of R pixels per wave through a transpose buffer in the last slot of
         // the weight ring, which the first stages of the next item do not touch: fp16, (pool),
         // activation; then 16 bytes per lane, 8 lanes covering the wave's 64 channels of a pixel.
-        constexpr int R = WC == 2 ? 32 : 16;
+        constexpr int R = (W_HALFS / (DLF_C3_WAVES * ROW)) >= 32 ? 32 : 16;
         static_assert(DLF_C3_WAVES * R * ROW <= W_HALFS, "the transpose buffers fit one slot of the ring");
         half_t* tb = wring + (nst - 1) * W_HALFS + wave * (R * ROW);
         const int part = lane & 7;
@@ -1684,7 +1687,7 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
         const int oy0 = a.pool2 ? e_ty0 >> 1 : e_ty0, ox0 = a.pool2 ? e_tx0 >> 1 : e_tx0;
         const int onpix = a.pool2 ? npix >> 2 : npix;
 #pragma unroll
-        for (int s = 0; s < 64 / R; ++s) {
+        for (int s = 0; s < 32 * FP / R; ++s) {
             const int p = s / (32 / R), sub = s % (32 / R);
             if (l32 / R == sub) {
 #pragma unroll
@@ -1710,7 +1713,7 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
                     }
             }
             __builtin_amdgcn_wave_barrier();
-            const int obase = wp * (a.pool2 ? 16 : 64) + (p * 32 + sub * R >> (a.pool2 ? 2 : 0));
+            const int obase = wp * (a.pool2 ? 8 * FP : 32 * FP) + (p * 32 + sub * R >> (a.pool2 ? 2 : 0));
             for (int r0 = 0; r0 < rows_pass; r0 += 16) {
                 u4v val[2], rv[2];
                 bool ok[2];
@@ -1957,10 +1960,11 @@ typedef void (*c3_kernel_t)(const DlfC3Args);
 static c3_kernel_t c3_kernel(int shape)
 {
     switch (shape) {
-    case 0: return k_c3b<2, 32>;
-    case 1: return k_c3b<2, 64>;
-    case 2: return k_c3b<1, 32>;
-    case 3: return k_c3b<1, 64>;
+    case 0: return k_c3b<2, 32, 2>;
+    case 1: return k_c3b<2, 64, 2>;
+    case 2: return k_c3b<1, 32, 2>;
+    case 3: return k_c3b<1, 64, 2>;
+    case 4: return k_c3b<2, 32, 4>;
     default: return nullptr;
     }
 }

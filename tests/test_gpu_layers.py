@@ -327,6 +327,9 @@ def test_conv_k_split_over_waves(cin, cout, hw, ks, tile, var, nsl, sc, kh, stri
     (256, 128, 14, 14, 2, 1, 8, 32, 0, "relu", 0),     # 64-channel blocks, four of them, two-stage ring
     (192, 64, 9, 9, 1, 3, 4, 14, 0, "relu", 0),        # 64-channel blocks, three of them
     (32, 32, 5, 5, 1, 0, 2, 4, 0, "relu", 0),          # tiny tiles: one activation load per block
+    (64, 160, 40, 36, 2, 4, 16, 32, 0, "relu", 0),     # 128 x 512 blocks: ragged tiles and channel groups
+    (128, 128, 32, 32, 1, 4, 16, 32, 1, "relu6", 0),   # 128 x 512 blocks with the folded pool
+    (64, 64, 30, 30, 2, 4, 14, 28, 0, "relu", 1),      # 128 x 512 blocks, 392 pixels, residual, half the channels
 ])
 def test_block3x3_kernel(cin, cout, h, w, batch, shape, th, tw, pool, act, res):
     """The block 3x3 kernel, forced with a given shape, against the layer-by-layer oracle."""
