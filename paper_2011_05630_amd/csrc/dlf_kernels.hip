@@ -1615,13 +1615,14 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
             const int q = 2 * kq + lhi;
             // halo pixel h, part q: h * ACH halfs + 8 * (q ^ f(h))
             auto b_at = [&](int h) __attribute__((always_inline)) { return ab + h * ACH + ((((h >> SH) & (LPP - 1)) ^ q) << 3); };
-            // (the empty asm keeps the compiler from precomputing the tap addresses of a stage
-            // outside the K loop, which costs two registers per tap and pixel block)
+            // (with four pixel blocks the empty asm keeps the compiler from precomputing the tap
+            // addresses of a stage outside the K loop, which costs two registers per tap and pixel
+            // block; with two blocks there is room, and three instructions per address less)
             int h[FP];
 #pragma unroll
             for (int p = 0; p < FP; ++p) {
                 h[p] = hp0[p];
-                asm volatile("" : "+v"(h[p]));
+                if (FP > 2) asm volatile("" : "+v"(h[p]));
             }
             h8 af[2][2], bf[2][FP];
 #pragma unroll
