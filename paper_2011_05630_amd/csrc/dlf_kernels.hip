@@ -1255,6 +1255,22 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
         for (int q = 0; q < 4; ++q) bias[f][q] = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
     }
 
+    // ... and so does the residual operand of the wave's part (8 lanes cover the 64 channels of a
+    // pixel, as in the epilogue): requested here, it has arrived long before the epilogue, where
+    // the round trip to HBM would otherwise be paid in full, twice
+    u4v rvp[2][4];
+    if (resp != nullptr) {
+        const int c = wcg * 64 + (lane & 7) * 8;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int gpix = wpg * 64 + (h * 4 + i) * 8 + (lane >> 3);
+                if (gpix < a.m && c < a.cout)
+                    rvp[h][i] = *(const u4v*)(resp + (unsigned)gpix * (unsigned)a.cout + (unsigned)c);
+            }
+    }
+
     // this wave's loads of a stage: fragments wave, wave + 4, ...
     const half_t* src[LPW];
 #pragma unroll
@@ -1371,7 +1387,7 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
             const int gpix = wpg * 64 + px;
             ok[i] = gpix < a.m && c < a.cout;
             go[i] = (unsigned)gpix * (unsigned)a.cout + (unsigned)c;
-            if (resp != nullptr && ok[i]) rv[i] = *(const u4v*)(resp + go[i]);
+            rv[i] = rvp[h][i];
             val[i] = *(const u4v*)(tb + px * ROW + part * 8);
         }
 #pragma unroll
