@@ -30,8 +30,8 @@ RIDGE = MFMA_FP16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # FLOP per byte
 # Valid only for the kernel sources they were taken with: `csrc_sha1` is checked at run time and
 # `traffic` is reported as null when the sources have changed since.
 TRAFFIC = {
-    "csrc_sha1": "5506a4acab01d9b8fa0d8a421c8c4bfa39f83e38",
-    "bytes_per_launch": {"resnet50_b32": {"k_group<1,2,4>": 67681469, "k_pwb<2,2>": 43018155, "k_pwb<1,4>": 64612450, "k_group<1,2,2>": 23308050, "k_pw_sk": 55616146, "k_group<1,2,2,true>": 19670287, "k_gap": 6574470, "k_fc": 5398517}},
+    "csrc_sha1": "c819194933b19d4000d1d8cdd8a8dd5dae80480e",
+    "bytes_per_launch": {"resnet50_b32": {"k_group<1,2,4>": 67681475, "k_pwb<2,2>": 42970534, "k_pwb<1,4>": 64623002, "k_group<1,2,2>": 23307853, "k_pw_sk": 55612880, "k_group<1,2,2,true>": 19670344, "k_gap": 6574470, "k_fc": 5398517}},
 }
 
 
