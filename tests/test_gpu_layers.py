@@ -365,6 +365,66 @@ def test_block3x3_kernel(cin, cout, h, w, batch, shape, th, tw, pool, act, res):
     compare(got, ref, "block 3x3 %d->%d %dx%d shape %d tile %dx%d" % (cin, cout, h, w, shape, th, tw))
 
 
+def test_block3x3_kernel_random_shapes():
+    """Seeded random layers, block shapes, pixel tiles, budgets, batches, folded pools and residual
+    operands for the block 3x3 kernel (every case one it accepts), against the oracle."""
+    import random
+    from oracle import oracle as o
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    rnd = random.Random(20240611)
+    tile_h, tile_w = (2, 4, 7, 8, 14, 16), (4, 7, 8, 14, 16, 28, 32)
+    wc, ach, fp = (2, 2, 1, 1, 2), (32, 64, 32, 64, 32), (2, 2, 2, 2, 4)
+    done = tries = 0
+    while done < 24 and tries < 2000:
+        tries += 1
+        shape = rnd.randrange(5)
+        cin = rnd.choice((32, 64, 96, 128, 192))
+        cout = rnd.choice((8, 24, 32, 40, 64, 72, 128, 136, 200))
+        h, w = rnd.randint(3, 36), rnd.randint(3, 36)
+        pool = rnd.random() < 0.3
+        res = (not pool) and rnd.random() < 0.25
+        th, tw = rnd.choice(tile_h), rnd.choice(tile_w)
+        batch = rnd.randint(1, 3)
+        act = rnd.choice(("relu", "relu6", "none"))
+        if pool:
+            h, w = h + (h & 1), w + (w & 1)
+        if cin % ach[shape] or th * tw > 32 * fp[shape] * (8 // wc[shape]) or (pool and ((th | tw) & 1)):
+            continue
+        if cin * cout * h * w * batch > 2e8:
+            continue
+        if res:
+            if cout % ach[shape]:
+                continue
+            layers = [nets.conv(cin, cout, 1, 1, 0, "relu"), nets.conv(cout, cout, 3, 1, 1, act, residual_from=0)]
+            lasts = [0, 1]
+        else:
+            layers = [nets.conv(cin, cout, 3, 1, 1, act)]
+            lasts = [0]
+            if pool:
+                layers.append(nets.maxpool(cout, 2, 2, 0))
+                lasts = [1]
+        net = _mk(layers, h, w, cin, dist="normal")
+        x, ws, bs = gen.make_params(net, batch, 100 + done)
+        B.dlf_debug_block3x3_mode(1, shape, th, tw)
+        try:
+            s = Session(net, batch, ws, bs, **_manual(len(layers), lasts, budget=rnd.choice((8, 64, 256))))
+        except B.DlfError:
+            continue                      # the shape does not fit LDS with this tile
+        finally:
+            B.dlf_debug_block3x3_mode(0)
+        try:
+            if B.dlf_plan_group_config(s.plan, len(lasts) - 1)["kind"] != 4:
+                continue
+            announce("block 3x3 random", done, cin, cout, h, w, batch, shape, th, tw, pool, res, act)
+            got = s.run_numpy(x)
+        finally:
+            s.close()
+        compare(got, o.run_net(net, x, ws, bs), "block 3x3 random case %d" % done)
+        done += 1
+    assert done == 24
+
+
 @pytest.mark.parametrize("k_hw,k_c,cout,batch", [(8, 64, 1000, 3), (7, 96, 70, 40), (4, 512, 96, 16)])
 def test_fc_split_k(k_hw, k_c, cout, batch):
     """Long K, few output channels: the planner splits K over workgroups (pairs of 32-channel
