@@ -153,14 +153,24 @@ __device__ __forceinline__ void stage_region(const half_t* in, int n, int H, int
     }
 }
 
+// Pointers with their address space spelled out, for the helpers below that are not inlined: a
+// plain pointer is generic there and every access becomes a flat one, which waits on both memory
+// counters at once and serialises what should be a batch of independent loads.
+typedef const __attribute__((address_space(1))) half_t* gconst_h;
+typedef __attribute__((address_space(3))) half_t* lds_h;
+typedef __attribute__((address_space(3))) u4v* lds_u4v;
+typedef __attribute__((address_space(3))) h4* lds_h4;
+
 // im2col staging for a convolution on a narrow input (3 channels): LDS row p holds the
 // kh*kw*cin inputs of output pixel p in (kh, kw, ci) order, zero padded to kfill halfs, so that the
 // convolution becomes a 1x1 convolution over kfill channels: K = 27 -> 32 for a 3x3 filter on RGB
 // instead of 9 taps x 32 padded channels.
-__device__ __attribute__((noinline)) void stage_im2col(const half_t* in, int n, int H, int W, int C, int oy0,
+__device__ __forceinline__ void stage_im2col_direct(const half_t* in_, int n, int H, int W, int C, int oy0,
                                              int ox0, int rh, int rw, int kh, int kw, int stride,
-                                             int pad, int kfill, int cs, half_t* dst)
+                                             int pad, int kfill, int cs, half_t* dst_)
 {
+    const gconst_h in = (gconst_h)in_;
+    const lds_h dst = (lds_h)dst_;
     const int rowlen = kw * C;                     // contiguous in NHWC
     const int total = rh * rw * kh;
     for (int v = threadIdx.x; v < total; v += DLF_WG_THREADS) {
@@ -168,9 +178,9 @@ __device__ __attribute__((noinline)) void stage_im2col(const half_t* in, int n, 
         const int oy = pix / rw, ox = pix - oy * rw;
         const int iy = (oy0 + oy) * stride - pad + r;
         const int ix0 = (ox0 + ox) * stride - pad;
-        half_t* d = dst + pix * cs + r * rowlen;
+        const lds_h d = dst + pix * cs + r * rowlen;
         const bool rowok = iy >= 0 && iy < H;
-        const half_t* src = in + (((size_t)n * H + (rowok ? iy : 0)) * W) * C;
+        const gconst_h src = in + (((size_t)n * H + (rowok ? iy : 0)) * W) * C;
         for (int j = 0; j < rowlen; ++j) {
             const int ix = ix0 + j / C;
             half_t val = (half_t)0;
@@ -182,6 +192,83 @@ __device__ __attribute__((noinline)) void stage_im2col(const half_t* in, int n, 
     }
 }
 
+// The same in two steps through LDS, where a spare area `tmp` is at hand (the stage's output buffer,
+// not yet in use): the input patch [ih][iw][C] is brought in first, rows of the image being
+// contiguous in memory, zero outside the image; the im2col rows are then copied out of it -- a
+// filter row of an output pixel is kw * C consecutive halfs of a patch row.  No bounds checks, no
+// global access and no division by a run-time value per element in the second step.
+__device__ __forceinline__ void stage_im2col_lds(const half_t* in_, int n, int H, int W, int C, int oy0,
+                                                 int ox0, int rh, int rw, int kh, int kw, int stride,
+                                                 int pad, int kfill, int cs, half_t* tmp_, half_t* dst_)
+{
+    const gconst_h in = (gconst_h)in_;
+    const lds_h tmp = (lds_h)tmp_, dst = (lds_h)dst_;
+    const int ih = (rh - 1) * stride + kh, iw = (rw - 1) * stride + kw;
+    const int iy0 = oy0 * stride - pad, ix0 = ox0 * stride - pad;
+    const int rowh = iw * C;                       // halfs per patch row
+    const unsigned rowh_m = div_magic(rowh), c_m = div_magic(C);
+    // batches of 4 loads per thread are issued before any is stored: the round trip to HBM is paid
+    // once per batch, not once per element
+    constexpr int U = 4;
+    const int ptotal = ih * rowh;
+    for (int v0 = threadIdx.x; v0 < ptotal; v0 += DLF_WG_THREADS * U) {
+        half_t val[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int v = v0 + u * DLF_WG_THREADS;
+            // every lane loads, from element 0 where it has nothing to fetch, and the value is chosen
+            // afterwards: a load under a divergent branch is waited for at the end of its branch
+            const int r = div_by(v, rowh_m), j = v - r * rowh;
+            const int gy = iy0 + r, gx = ix0 + div_by(j, c_m);
+            const bool ok = v < ptotal && gy >= 0 && gy < H && gx >= 0 && gx < W;
+            const half_t x = in[ok ? (unsigned)(((n * H + gy) * W + ix0) * C + j) : 0u];
+            val[u] = ok ? x : (half_t)0;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int v = v0 + u * DLF_WG_THREADS;
+            if (v < ptotal) tmp[v] = val[u];
+        }
+    }
+    __syncthreads();
+    // One task = 8 consecutive k of one output pixel, written with a single 16-byte store.  Along k a
+    // pixel's row is kh runs of kw*C halfs, each contiguous in the patch, so the source index only
+    // steps by one and jumps at the end of a run: a few instructions per element instead of a full
+    // index decomposition (the per-element form is bound by vector ALU issue, not by memory).
+    const int rowlen = kw * C, per_pix = kh * rowlen, nq = kfill >> 3;
+    const unsigned nq_m = div_magic(nq), rowlen_m = div_magic(rowlen), rw_m = div_magic(rw);
+    for (int u = threadIdx.x; u < rh * rw * nq; u += DLF_WG_THREADS) {
+        const int pix = div_by(u, nq_m), j0 = (u - pix * nq) << 3;
+        const int oy = div_by(pix, rw_m), ox = pix - oy * rw;
+        const int r = div_by(j0, rowlen_m);
+        int jj = j0 - r * rowlen;
+        int src = (oy * stride + r) * rowh + ox * stride * C + jj;
+        half_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            v[e] = (j0 + e < per_pix) ? tmp[src] : (half_t)0;
+            ++src;
+            if (++jj == rowlen) {
+                jj = 0;
+                src += rowh - rowlen;
+            }
+        }
+        *(lds_u4v)(dst + pix * cs + j0) = *(const u4v*)v;
+    }
+}
+
+// One entry for both forms, so that the kernel holds a single call: `tmp` is the spare LDS area of the
+// two-step form, or null for the direct one.
+__device__ __attribute__((noinline)) void stage_im2col(const half_t* in, int n, int H, int W, int C, int oy0,
+                                             int ox0, int rh, int rw, int kh, int kw, int stride,
+                                             int pad, int kfill, int cs, half_t* tmp, half_t* dst)
+{
+    if (tmp != nullptr)
+        stage_im2col_lds(in, n, H, W, C, oy0, ox0, rh, rw, kh, kw, stride, pad, kfill, cs, tmp, dst);
+    else
+        stage_im2col_direct(in, n, H, W, C, oy0, ox0, rh, rw, kh, kw, stride, pad, kfill, cs, dst);
+}
+
 // Staging for a convolution on a narrow input (cin <= 4) with an even stride: the input patch goes
 // to LDS as 4-channel pixels [ih][iw][4] (missing channels and pixels outside the image zero).
 // The convolution stage then treats a filter row as one tap over round_up(4 * kw, 32) "channels":
@@ -189,9 +276,11 @@ __device__ __attribute__((noinline)) void stage_im2col(const half_t* in, int n, 
 // exactly the filter columns; the columns beyond kw meet zero weights (so the 32 halfs behind the
 // last pixel only have to be finite: they are zeroed here).  No gather, K = kh * 32 per 7x7 row
 // set instead of kh * kw * cin copies per output pixel.
-__device__ __attribute__((noinline)) void stage_rowfold(const half_t* in, int n, int H, int W, int C, int iy0,
-                                              int ix0, int ih, int iw, half_t* dst)
+__device__ __attribute__((noinline)) void stage_rowfold(const half_t* in_, int n, int H, int W, int C, int iy0,
+                                              int ix0, int ih, int iw, half_t* dst_)
 {
+    const gconst_h in = (gconst_h)in_;
+    const lds_h dst = (lds_h)dst_;
     const int total = ih * iw;
     const unsigned iw_m = div_magic(iw);
     constexpr int U = 4;
@@ -200,30 +289,29 @@ __device__ __attribute__((noinline)) void stage_rowfold(const half_t* in, int n,
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int v = v0 + u * DLF_WG_THREADS;
-            h4 px = {0, 0, 0, 0};
-            if (v < total) {
-                const int py = div_by(v, iw_m), pxx = v - py * iw;
-                const int gy = iy0 + py, gx = ix0 + pxx;
-                if (gy >= 0 && gy < H && gx >= 0 && gx < W) {
-                    const half_t* p = in + (unsigned)(((n * H + gy) * W + gx) * C);
-                    const half_t c0 = p[0];
-                    const half_t c1 = C > 1 ? p[1] : (half_t)0;
-                    const half_t c2 = C > 2 ? p[2] : (half_t)0;
-                    const half_t c3 = C > 3 ? p[3] : (half_t)0;
-                    px = h4{c0, c1, c2, c3};
-                }
-            }
+            // every lane loads, from element 0 where it has nothing to fetch, and the value is chosen
+            // afterwards: a load under a divergent branch is waited for at the end of its branch
+            const int py = div_by(v, iw_m), pxx = v - py * iw;
+            const int gy = iy0 + py, gx = ix0 + pxx;
+            const bool ok = v < total && gy >= 0 && gy < H && gx >= 0 && gx < W;
+            const gconst_h p = in + (ok ? (unsigned)(((n * H + gy) * W + gx) * C) : 0u);
+            const half_t z = (half_t)0;
+            const half_t c0 = p[0];
+            const half_t c1 = C > 1 ? p[1] : z;
+            const half_t c2 = C > 2 ? p[2] : z;
+            const half_t c3 = C > 3 ? p[3] : z;
+            const h4 px = {ok ? c0 : z, ok ? c1 : z, ok ? c2 : z, ok ? c3 : z};
             val[u] = px;
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int v = v0 + u * DLF_WG_THREADS;
-            if (v < total) *(h4*)(dst + v * 4) = val[u];
+            if (v < total) *(lds_h4)(dst + v * 4) = val[u];
         }
     }
     if (threadIdx.x < 4) {
-        const h8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-        *(h8*)(dst + total * 4 + threadIdx.x * 8) = z;
+        const u4v z = {0, 0, 0, 0};
+        *(lds_u4v)(dst + total * 4 + threadIdx.x * 8) = z;
     }
 }
 
@@ -863,11 +951,17 @@ __global__ __launch_bounds__(DLF_WG_THREADS, MINW) void k_group(const DlfGroupAr
             if (s0.kind == DLF_ST_CONV && s0.im2col == 2)
                 stage_rowfold((const half_t*)a.in, n, a.in_h, a.in_w, a.in_c, ty0 * a.iy_mul + a.iy_off,
                               tx0 * a.ix_mul + a.ix_off, s0.ih, s0.iw, lds + s0.in_off);
-            else if (s0.kind == DLF_ST_CONV && s0.im2col)
+            else if (s0.kind == DLF_ST_CONV && s0.im2col) {
+                // through the stage's output buffer where there is one of its own and the patch fits it
+                const int pih = (s0.rh - 1) * s0.im_stride + s0.im_kh, piw = (s0.rw - 1) * s0.im_stride + s0.im_kw;
+                const bool two_step = a.nstages > 1 && !s0.alias_out && s0.out_off != s0.in_off &&
+                                      ((s0.cin_pad | s0.in_cs) & 7) == 0 &&
+                                      pih * piw * a.in_c <= (s0.pool2 ? (s0.rh >> 1) * (s0.rw >> 1) : s0.rh * s0.rw) * s0.out_cs;
                 stage_im2col((const half_t*)a.in, n, a.in_h, a.in_w, a.in_c,
                              ty0 * s0.oy_mul + s0.oy_off, tx0 * s0.ox_mul + s0.ox_off, s0.rh, s0.rw,
                              s0.im_kh, s0.im_kw, s0.im_stride, s0.im_pad, s0.cin_pad, s0.in_cs,
-                             lds + s0.in_off);
+                             two_step ? lds + s0.out_off : nullptr, lds + s0.in_off);
+            }
             else
                 stage_region((const half_t*)a.in, n, a.in_h, a.in_w, a.in_c,
                              ty0 * a.iy_mul + a.iy_off, tx0 * a.ix_mul + a.ix_off, s0.ih, s0.iw, c0,
