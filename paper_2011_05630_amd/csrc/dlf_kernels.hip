@@ -129,8 +129,12 @@ __device__ __forceinline__ void stage_region(const half_t* in, int n, int H, int
     const int nvec = cfill >> 3;
     const int total = ih * iw * nvec;
     const unsigned nvec_m = div_magic(nvec), iw_m = div_magic(iw);
-    // batches of 8 loads per thread are issued before any is stored: the HBM latency is paid
-    // once per batch, not once per 16 bytes
+    // Batches of 8 parts per thread, loaded and then stored.  Each load sits under its own bounds
+    // check, and the compiler waits for it at the end of that branch, so the eight round trips of
+    // a batch follow one another.  A form without branches (every lane loads from a clamped
+    // address, the value is chosen afterwards) does issue all eight at once, and measured 1-2 %
+    // slower on whole networks: with two workgroups per CU the other workgroup's multiply phase
+    // already covers this one's latency, and the burst only adds contention.
     constexpr int U = 8;
     for (int v0 = threadIdx.x; v0 < total; v0 += DLF_WG_THREADS * U) {
         h8 val[U];
@@ -216,12 +220,16 @@ __device__ __forceinline__ void stage_im2col_lds(const half_t* in_, int n, int H
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int v = v0 + u * DLF_WG_THREADS;
-            // every lane loads, from element 0 where it has nothing to fetch, and the value is chosen
-            // afterwards: a load under a divergent branch is waited for at the end of its branch
-            const int r = div_by(v, rowh_m), j = v - r * rowh;
-            const int gy = iy0 + r, gx = ix0 + div_by(j, c_m);
+            // every lane loads, from the nearest element inside the image where it has nothing to
+            // fetch, and the value is chosen afterwards: a load under a divergent branch is waited
+            // for at the end of its branch
+            const int vv = min(v, ptotal - 1);
+            const int r = div_by(vv, rowh_m), j = vv - r * rowh;
+            const int px = div_by(j, c_m), ch = j - px * C;
+            const int gy = iy0 + r, gx = ix0 + px;
             const bool ok = v < ptotal && gy >= 0 && gy < H && gx >= 0 && gx < W;
-            const half_t x = in[ok ? (unsigned)(((n * H + gy) * W + ix0) * C + j) : 0u];
+            const int gyc = min(max(gy, 0), H - 1), gxc = min(max(gx, 0), W - 1);
+            const half_t x = in[(unsigned)(((n * H + gyc) * W + gxc) * C + ch)];
             val[u] = ok ? x : (half_t)0;
         }
 #pragma unroll
@@ -289,12 +297,15 @@ __device__ __attribute__((noinline)) void stage_rowfold(const half_t* in_, int n
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int v = v0 + u * DLF_WG_THREADS;
-            // every lane loads, from element 0 where it has nothing to fetch, and the value is chosen
-            // afterwards: a load under a divergent branch is waited for at the end of its branch
-            const int py = div_by(v, iw_m), pxx = v - py * iw;
+            // every lane loads, from the nearest pixel inside the image where it has nothing to
+            // fetch, and the value is chosen afterwards: a load under a divergent branch is waited
+            // for at the end of its branch
+            const int vv = min(v, total - 1);
+            const int py = div_by(vv, iw_m), pxx = vv - py * iw;
             const int gy = iy0 + py, gx = ix0 + pxx;
             const bool ok = v < total && gy >= 0 && gy < H && gx >= 0 && gx < W;
-            const gconst_h p = in + (ok ? (unsigned)(((n * H + gy) * W + gx) * C) : 0u);
+            const int gyc = min(max(gy, 0), H - 1), gxc = min(max(gx, 0), W - 1);
+            const gconst_h p = in + (unsigned)(((n * H + gyc) * W + gxc) * C);
             const half_t z = (half_t)0;
             const half_t c0 = p[0];
             const half_t c1 = C > 1 ? p[1] : z;
