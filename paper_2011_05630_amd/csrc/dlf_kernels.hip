@@ -197,10 +197,11 @@ __device__ __forceinline__ void stage_im2col_direct(const half_t* in_, int n, in
 }
 
 // The same in two steps through LDS, where a spare area `tmp` is at hand (the stage's output buffer,
-// not yet in use): the input patch [ih][iw][C] is brought in first, rows of the image being
-// contiguous in memory, zero outside the image; the im2col rows are then copied out of it -- a
-// filter row of an output pixel is kw * C consecutive halfs of a patch row.  No bounds checks, no
-// global access and no division by a run-time value per element in the second step.
+// not yet in use; it must hold the patch and one half more): the input patch [ih][iw][C] is
+// brought in first, rows of the image being contiguous in memory, zero outside the image; the
+// im2col rows are then copied out of it -- a filter row of an output pixel is kw * C consecutive
+// halfs of a patch row.  No bounds checks, no global access and no division by a run-time value
+// per element in the second step.
 __device__ __forceinline__ void stage_im2col_lds(const half_t* in_, int n, int H, int W, int C, int oy0,
                                                  int ox0, int rh, int rw, int kh, int kw, int stride,
                                                  int pad, int kfill, int cs, half_t* tmp_, half_t* dst_)
@@ -238,13 +239,37 @@ __device__ __forceinline__ void stage_im2col_lds(const half_t* in_, int n, int H
             if (v < ptotal) tmp[v] = val[u];
         }
     }
+    if (threadIdx.x == 0) tmp[ptotal] = (half_t)0;                 // the zero that row padding reads
     __syncthreads();
     // One task = 8 consecutive k of one output pixel, written with a single 16-byte store.  Along k a
-    // pixel's row is kh runs of kw*C halfs, each contiguous in the patch, so the source index only
-    // steps by one and jumps at the end of a run: a few instructions per element instead of a full
-    // index decomposition (the per-element form is bound by vector ALU issue, not by memory).
+    // pixel's row is kh runs of kw*C halfs, each contiguous in the patch.  This phase is bound by
+    // vector ALU issue (four waves share a SIMD), so what counts is instructions per element.
     const int rowlen = kw * C, per_pix = kh * rowlen, nq = kfill >> 3;
     const unsigned nq_m = div_magic(nq), rowlen_m = div_magic(rowlen), rw_m = div_magic(rw);
+    if (DLF_WG_THREADS % nq == 0) {
+        // The workgroup's stride is a multiple of the parts per row, so a thread serves the same part
+        // of every row it visits: the eight offsets of its elements inside a pixel's window are
+        // found once (padding beyond kh*kw*C points at the zero behind the patch), and an element
+        // costs one addition and one read.
+        const int j0 = (int)(threadIdx.x % (unsigned)nq) << 3;
+        int off[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int j = j0 + e, r = div_by(j, rowlen_m);
+            off[e] = j < per_pix ? r * rowh + (j - r * rowlen) : -1;
+        }
+        for (int u = threadIdx.x; u < rh * rw * nq; u += DLF_WG_THREADS) {
+            const int pix = div_by(u, nq_m);
+            const int oy = div_by(pix, rw_m), ox = pix - oy * rw;
+            const int base = oy * stride * rowh + ox * stride * C;
+            half_t v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = tmp[off[e] < 0 ? ptotal : base + off[e]];
+            *(lds_u4v)(dst + pix * cs + j0) = *(const u4v*)v;
+        }
+        return;
+    }
+    // otherwise the source index is stepped along the row, with a jump at the end of each run
     for (int u = threadIdx.x; u < rh * rw * nq; u += DLF_WG_THREADS) {
         const int pix = div_by(u, nq_m), j0 = (u - pix * nq) << 3;
         const int oy = div_by(pix, rw_m), ox = pix - oy * rw;
@@ -254,7 +279,11 @@ __device__ __forceinline__ void stage_im2col_lds(const half_t* in_, int n, int H
         half_t v[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            v[e] = (j0 + e < per_pix) ? tmp[src] : (half_t)0;
+            // read without a branch (slot 0 where there is nothing to read) and choose afterwards,
+            // so that the eight reads are in flight together
+            const bool ok = j0 + e < per_pix;
+            const half_t x = tmp[ok ? src : 0];
+            v[e] = ok ? x : (half_t)0;
             ++src;
             if (++jj == rowlen) {
                 jj = 0;
@@ -967,7 +996,7 @@ __global__ __launch_bounds__(DLF_WG_THREADS, MINW) void k_group(const DlfGroupAr
                 const int pih = (s0.rh - 1) * s0.im_stride + s0.im_kh, piw = (s0.rw - 1) * s0.im_stride + s0.im_kw;
                 const bool two_step = a.nstages > 1 && !s0.alias_out && s0.out_off != s0.in_off &&
                                       ((s0.cin_pad | s0.in_cs) & 7) == 0 &&
-                                      pih * piw * a.in_c <= (s0.pool2 ? (s0.rh >> 1) * (s0.rw >> 1) : s0.rh * s0.rw) * s0.out_cs;
+                                      pih * piw * a.in_c < (s0.pool2 ? (s0.rh >> 1) * (s0.rw >> 1) : s0.rh * s0.rw) * s0.out_cs;
                 stage_im2col((const half_t*)a.in, n, a.in_h, a.in_w, a.in_c,
                              ty0 * s0.oy_mul + s0.oy_off, tx0 * s0.ox_mul + s0.ox_off, s0.rh, s0.rw,
                              s0.im_kh, s0.im_kw, s0.im_stride, s0.im_pad, s0.cin_pad, s0.in_cs,
