@@ -570,7 +570,14 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
         const int s_total = (st.ih * st.iw) << vshift;
         const unsigned iw_m = div_magic(st.iw);
         const int iy0 = ty0 * a.iy_mul + a.iy_off, ix0 = tx0 * a.ix_mul + a.ix_off;
-        int s_goff[DLF_STAGE_VECS];   // element offset into `in` for round 0, or -1 (zero fill)
+        // Element offset of the pixel each vector comes from -- clamped into the image and into the
+        // region, so that it can always be loaded from -- and whether the vector is real or zero fill.
+        // Every vector of a round is loaded without a branch and the zero chosen afterwards: a load
+        // under a divergent check is waited for at the end of its branch, which would make a round as
+        // many trips to memory, one after the other, as a thread has vectors; the multiplying waves
+        // wait for nothing else.
+        int s_goff[DLF_STAGE_VECS];
+        unsigned s_ok = 0;
         if ((st.cin & 7) != 0) {
             // narrow inputs (e.g. 3 channels): one round, element-wise copy
             for (int v = lt; v < s_total; v += DLF_LOAD_THREADS) {
@@ -586,14 +593,12 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
 #pragma unroll
         for (int i = 0; i < DLF_STAGE_VECS; ++i) {
             const int v = lt + i * DLF_LOAD_THREADS;
-            s_goff[i] = -1;
-            if (v < s_total) {
-                const int pix = v >> vshift, part = v & vmask;
-                const int ry = div_by(pix, iw_m), rx = pix - ry * st.iw;
-                const int gy = iy0 + ry, gx = ix0 + rx;
-                if (gy >= 0 && gy < a.in_h && gx >= 0 && gx < a.in_w)
-                    s_goff[i] = ((n * a.in_h + gy) * a.in_w + gx) * a.in_c + part * 8;
-            }
+            const int pix = min(v, s_total - 1) >> vshift;
+            const int ry = div_by(pix, iw_m), rx = pix - ry * st.iw;
+            const int gy = iy0 + ry, gx = ix0 + rx;
+            if (v < s_total && gy >= 0 && gy < a.in_h && gx >= 0 && gx < a.in_w) s_ok |= 1u << i;
+            const int gyc = min(max(gy, 0), a.in_h - 1), gxc = min(max(gx, 0), a.in_w - 1);
+            s_goff[i] = ((n * a.in_h + gyc) * a.in_w + gxc) * a.in_c;
         }
         for (int round = 0; round <= nrounds; ++round) {
             // round r of this loop fills the buffer that the multiplying waves read in round r
@@ -603,11 +608,10 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
                 h8 s_reg[DLF_STAGE_VECS];
 #pragma unroll
                 for (int i = 0; i < DLF_STAGE_VECS; ++i) {
-                    h8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-                    const int part8 = ((lt + i * DLF_LOAD_THREADS) & vmask) * 8;
-                    if (s_goff[i] >= 0 && coff + part8 < st.cin)
-                        v = *(const h8*)(in + s_goff[i] + coff);
-                    s_reg[i] = v;
+                    const int c = coff + ((lt + i * DLF_LOAD_THREADS) & vmask) * 8;
+                    const h8 x = *(const h8*)(in + s_goff[i] + min(c, st.cin - 8));
+                    const h8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+                    s_reg[i] = ((s_ok >> i) & 1u) != 0 && c < st.cin ? x : z;
                 }
 #pragma unroll
                 for (int i = 0; i < DLF_STAGE_VECS; ++i) {
