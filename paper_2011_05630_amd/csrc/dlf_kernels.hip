@@ -1928,29 +1928,42 @@ __global__ __launch_bounds__(DLF_FC_WAVES * 64) void k_fc(const DlfFcArgs a)
         // 8 KiB of weights in flight per wave, refilled right behind the MFMA that used the slot
         const int per = (a.nsteps + DLF_FC_WAVES - 1) / DLF_FC_WAVES;
         const int t0 = wave * per, t1 = min(a.nsteps, t0 + per);
+        // A load under a condition is waited for where its branch ends, and the compiler cannot
+        // count the loads behind it, so a ring refilled under "if there is a step t+8" drains at
+        // every turn.  Hence: the first fill clamps its step index instead of testing it; while at
+        // least 16 steps remain, every refill exists and is issued without a test; the last one or
+        // two turns of the ring use the tested form.  Beyond K the activation vector is read from
+        // the start of the weights and replaced by zero where it is used.
         h8 av[8], bv[8];
+        const h8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int t = t0 + j;
-            if (t < t1) {
-                av[j] = wbase[(size_t)t * 64];
-                h8 b = {0, 0, 0, 0, 0, 0, 0, 0};
-                if (t * 16 + lhi * 8 + 8 <= a.k) b = *(const h8*)(xr + t * 16);
-                bv[j] = b;
+            const int t = max(min(t0 + j, t1 - 1), 0);
+            av[j] = wbase[(size_t)t * 64];
+            bv[j] = *(const h8*)(t * 16 + lhi * 8 + 8 <= a.k ? xr + t * 16 : (const half_t*)a.w);
+        }
+        int tb = t0;
+        for (; tb + 16 <= t1; tb += 8) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[j], bv[j], acc, 0, 0, 0);
+                const int tn = tb + j + 8;
+                av[j] = wbase[(size_t)tn * 64];
+                bv[j] = *(const h8*)(tn * 16 + lhi * 8 + 8 <= a.k ? xr + tn * 16 : (const half_t*)a.w);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-        for (int tb = t0; tb < t1; tb += 8) {
+        for (; tb < t1; tb += 8) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int t = tb + j;
                 if (t < t1) {
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[j], bv[j], acc, 0, 0, 0);
+                    const h8 bj = t * 16 + lhi * 8 + 8 <= a.k ? bv[j] : zero8;
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[j], bj, acc, 0, 0, 0);
                     const int tn = t + 8;
                     if (tn < t1) {
                         av[j] = wbase[(size_t)tn * 64];
-                        h8 b = {0, 0, 0, 0, 0, 0, 0, 0};
-                        if (tn * 16 + lhi * 8 + 8 <= a.k) b = *(const h8*)(xr + tn * 16);
-                        bv[j] = b;
+                        bv[j] = *(const h8*)(tn * 16 + lhi * 8 + 8 <= a.k ? xr + tn * 16 : (const half_t*)a.w);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -1999,32 +2012,42 @@ __global__ __launch_bounds__(DLF_FC_WAVES * 64) void k_fc_sk(const DlfFcArgs a)
         f16v acc0, acc1;
 #pragma unroll
         for (int i = 0; i < 16; ++i) { acc0[i] = 0.0f; acc1[i] = 0.0f; }
+        // the ring is filled and refilled as in k_fc
         h8 av0[8], av1[8], bv[8];
+        const h8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int t = t0 + j;
-            if (t < t1) {
-                av0[j] = w0[(size_t)t * 64];
-                av1[j] = w1[(size_t)t * 64];
-                h8 b = {0, 0, 0, 0, 0, 0, 0, 0};
-                if (t * 16 + lhi * 8 + 8 <= a.k) b = *(const h8*)(xr + t * 16);
-                bv[j] = b;
+            const int t = max(min(t0 + j, t1 - 1), 0);
+            av0[j] = w0[(size_t)t * 64];
+            av1[j] = w1[(size_t)t * 64];
+            bv[j] = *(const h8*)(t * 16 + lhi * 8 + 8 <= a.k ? xr + t * 16 : (const half_t*)a.w);
+        }
+        int tb = t0;
+        for (; tb + 16 <= t1; tb += 8) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(av0[j], bv[j], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(av1[j], bv[j], acc1, 0, 0, 0);
+                const int tn = tb + j + 8;
+                av0[j] = w0[(size_t)tn * 64];
+                av1[j] = w1[(size_t)tn * 64];
+                bv[j] = *(const h8*)(tn * 16 + lhi * 8 + 8 <= a.k ? xr + tn * 16 : (const half_t*)a.w);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-        for (int tb = t0; tb < t1; tb += 8) {
+        for (; tb < t1; tb += 8) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int t = tb + j;
                 if (t < t1) {
-                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(av0[j], bv[j], acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(av1[j], bv[j], acc1, 0, 0, 0);
+                    const h8 bj = t * 16 + lhi * 8 + 8 <= a.k ? bv[j] : zero8;
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(av0[j], bj, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(av1[j], bj, acc1, 0, 0, 0);
                     const int tn = t + 8;
                     if (tn < t1) {
                         av0[j] = w0[(size_t)tn * 64];
                         av1[j] = w1[(size_t)tn * 64];
-                        h8 b = {0, 0, 0, 0, 0, 0, 0, 0};
-                        if (tn * 16 + lhi * 8 + 8 <= a.k) b = *(const h8*)(xr + tn * 16);
-                        bv[j] = b;
+                        bv[j] = *(const h8*)(tn * 16 + lhi * 8 + 8 <= a.k ? xr + tn * 16 : (const half_t*)a.w);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
