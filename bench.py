@@ -30,8 +30,8 @@ RIDGE = MFMA_FP16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # FLOP per byte
 # Valid only for the kernel sources they were taken with: `csrc_sha1` is checked at run time and
 # `traffic` is reported as null when the sources have changed since.
 TRAFFIC = {
-    "csrc_sha1": "e55b9f508e161dc1bd1b88bb8fb3b07d1cbcbb84",
-    "bytes_per_launch": {"resnet50_b32": {"k_group<1,2,4>": 67699043, "k_pwb<2,2>": 42969279, "k_pwb<1,4>": 64720537, "k_group<1,2,2>": 23286477, "k_pw_sk": 55612092, "k_group<1,2,2,true>": 19670349, "k_gap": 6574472, "k_fc": 5398518}},
+    "csrc_sha1": "a71ba6ee3144bb7bac6faed279538fac9e366d47",
+    "bytes_per_launch": {"resnet50_b32": {"k_group<1,2,4>": 67694105, "k_pwb<2,2>": 42969574, "k_pwb<1,4>": 64614135, "k_group<1,2,2>": 23290917, "k_pw_sk": 55618515, "k_group<1,2,2,true>": 19665184, "k_gap": 6584729, "k_fc": 5406713}},
 }
 
 
