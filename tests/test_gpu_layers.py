@@ -284,6 +284,30 @@ def test_fc_and_global_avgpool():
     compare(got, ref, "fc-fc batch 37")
 
 
+def test_fc_long_ragged_k_in_one_workgroup():
+    """K = 2056: 129 K steps, so each wave's operand ring turns without tests before its last
+    turns, and the last step is half beyond K (its activation vector is read from a stand-in
+    address and replaced by zero).  K slices forced to 1: the plain kernel, not the split one."""
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    from oracle import oracle as o
+    announce("fc K=2056, one slice")
+    net = _mk([nets.fc(2056, 72, "relu")], 1, 1, 2056, dist="normal")
+    x, ws, bs = gen.make_params(net, 5)
+    B.dlf_debug_force_config(1, 1, 0, 1, 0, 0, 32)
+    try:
+        s = Session(net, 5, ws, bs)
+    finally:
+        B.dlf_debug_force_config(0, 0, 0, 1, 0, 0, 32)
+    try:
+        assert B.dlf_plan_group_config(s.plan, 0)["kind"] == 1
+        assert B.dlf_plan_workspace_bytes(s.plan) == 0, "no partial sums: K is not split"
+        got = s.run_numpy(x)
+    finally:
+        s.close()
+    compare(got, o.run_net(net, x, ws, bs), "fc K=2056")
+
+
 @pytest.mark.parametrize("cin,cout,hw,ks,tile,var,nsl,sc,kh,stride,act", [
     (256, 64, 7, 4, (7, 7), 2, 1, 0, 3, 1, "relu"),      # two work items x 4 K slices
     (512, 128, 7, 8, (7, 7), 2, 4, 32, 3, 1, "relu"),    # sliced channels, one item x 8
