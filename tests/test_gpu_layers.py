@@ -110,6 +110,34 @@ def test_narrow_input_stems_fused():
     compare(got, ref, "3x3 s2 stem + dw + pw + dw s2")
 
 
+@pytest.mark.parametrize("k,stride,pad,cin,mid,pool,h,w", [
+    (3, 1, 1, 3, 64, True, 38, 50),     # K = 27 -> 32: 4 parts per row (divides the workgroup)
+    (3, 1, 1, 5, 32, False, 21, 35),    # K = 45 -> 64: 8 parts per row, odd channel count
+    (5, 1, 2, 3, 32, False, 29, 23),    # K = 75 -> 96: 12 parts per row (does not divide it)
+    (7, 1, 3, 3, 32, True, 30, 26),     # K = 147 -> 160: 20 parts per row
+    (3, 3, 0, 3, 32, False, 40, 31),    # odd stride, no padding
+    (3, 1, 1, 1, 16, False, 19, 19),    # one input channel
+])
+def test_narrow_input_gathered_through_lds(k, stride, pad, cin, mid, pool, h, w):
+    """A narrow first layer that is not folded by rows (odd stride or more than 4 channels), fused
+    with a second convolution: the image patch goes through a spare LDS area and the im2col rows
+    are copied out of it.  Tiles forced small enough that borders, ragged tiles and several tiles
+    per image occur; the automatic choice as well."""
+    announce("narrow gathered", k, stride, pad, cin, mid, pool, h, w)
+    layers = [nets.conv(cin, mid, k, stride, pad, "relu"), nets.conv(mid, 32, 3, 1, 1, "relu")]
+    if pool:
+        layers.append(nets.maxpool(32, 2, 2, 0))
+    net = _mk(layers, h, w, cin, dist="normal")
+    last = len(layers) - 1
+    got, ref, g = _run(net, 2, **_manual(len(layers), [last]))
+    assert len(g) == 1
+    compare(got, ref, "narrow gathered k%d s%d cin%d" % (k, stride, cin))
+    for force in ((4, 8, 2, 1, 0, 0), (2, 16, 3, 1, 0, 0), (5, 6, 0, 1, 0, 0)):
+        got, ref, g = _run(net, 2, force=force, **_manual(len(layers), [last]))
+        assert len(g) == 1
+        compare(got, ref, "narrow gathered k%d s%d cin%d force %s" % (k, stride, cin, force))
+
+
 @pytest.mark.parametrize("slices", [(8, 8, 0, 4, 64, 1), (8, 8, 1, 2, 128, 1), (7, 7, 0, 2, 128, 1),
                                     (8, 8, 2, 8, 32, 1), (8, 8, 1, 4, 64, 1, 64)])
 def test_conv_output_channel_slices(slices):
