@@ -42,12 +42,12 @@ FC_BYTES_PER_CYCLE = 1400
 FC_SPLIT_HBM_BYTES_PER_CYCLE = 1900
 GAP_BYTES_PER_CYCLE = 1000
 # FC, FP, items in flight per CU, cycles per K step (alone, per item sharing the CU), K split
-PW_SHAPES = ((2, 2, 8, 470, 64, 1), (1, 1, 16, 300, 100, 1), (2, 2, 2, 470, 256, 4))
+PW_SHAPES = ((2, 2, 8, 470, 64, 1), (1, 1, 16, 300, 100, 1), (2, 2, 1, 470, 256, 4))
 # block forms: (32-channel blocks, 32-pixel blocks) of a workgroup's block, two blocks per CU
 PWB_SHAPES = ((4, 4), (2, 8))
 C_PWB_BLOCK = 4000
 PWB_BYTES_PER_CYCLE = 25
-C_PW_SK = 12000
+C_PW_SK = 2000
 C_PW_ITEM = 2500
 C_PW_RES = 1000
 PW_HBM_BYTES_PER_CYCLE = 2000

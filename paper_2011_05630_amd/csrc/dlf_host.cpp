@@ -213,7 +213,8 @@ const int64_t GAP_BYTES_PER_CYCLE = 1000;
 const int PW_SHAPES = 5;
 const int PW_FC[PW_SHAPES] = {2, 1, 2, 4, 2};          // 32-channel blocks per item
 const int PW_FP[PW_SHAPES] = {2, 1, 2, 4, 8};          // 32-pixel blocks per item
-const int PW_WAVES_PER_CU[PW_SHAPES] = {8, 16, 2, 2, 2};     // items in flight per CU
+const int PW_WAVES_PER_CU[PW_SHAPES] = {8, 16, 1, 2, 2};     // items in flight per CU that cost no more than one
+                                                             // (split-K: a second item on the CU doubles the time)
 const int PW_KSPLIT[PW_SHAPES] = {1, 1, 4, 1, 1};
 const bool PW_BLOCK[PW_SHAPES] = {false, false, false, true, true};
 // fitted to per-launch HIP-event times of 1x1 layers of the ResNet-50 / MobileNet-v1 shapes
@@ -222,7 +223,7 @@ const int64_t C_PW_STEP[PW_SHAPES] = {470, 300, 470, 0, 0};   // per K step of a
 const int64_t C_PW_STEP_WAVE[PW_SHAPES] = {64, 100, 256, 0, 0};   // ... or of a CU whose waves share its vector-memory path
 const int64_t C_PWB_BLOCK = 4000;           // block form, per round of two blocks on a CU: first operands, epilogue
 const int64_t PWB_BYTES_PER_CYCLE = 25;     // rate at which a CU takes operand fragments in (all pointwise forms)
-const int64_t C_PW_SK = 12000;              // split-K: exchange of partial sums through LDS, idle waves of a second round
+const int64_t C_PW_SK = 2000;               // split-K: exchange of partial sums through LDS
 const int64_t C_PW_RES = 1000;              // residual loads
 const int64_t PW_HBM_BYTES_PER_CYCLE = 2000;
 // block 3x3 kernel: per work item (first stages of the ring, epilogue), per LDS stage of 16 input
