@@ -30,8 +30,8 @@ RIDGE = MFMA_FP16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # FLOP per byte
 # Valid only for the kernel sources they were taken with: `csrc_sha1` is checked at run time and
 # `traffic` is reported as null when the sources have changed since.
 TRAFFIC = {
-    "csrc_sha1": "a71ba6ee3144bb7bac6faed279538fac9e366d47",
-    "bytes_per_launch": {"resnet50_b32": {"k_group<1,2,4>": 67694105, "k_pwb<2,2>": 42969574, "k_pwb<1,4>": 64614135, "k_group<1,2,2>": 23290917, "k_pw_sk": 55618515, "k_group<1,2,2,true>": 19665184, "k_gap": 6584729, "k_fc": 5406713}},
+    "csrc_sha1": "51212e24a6a7b06526f443724c7df6ef205eb2f7",
+    "bytes_per_launch": {"resnet50_b32": {"k_group<1,2,4>": 67694276, "k_pwb<2,2>": 42970560, "k_pwb<1,4>": 64615032, "k_group<1,2,2>": 23296506, "k_pw_sk": 55611492, "k_group<1,2,2,true>": 19665227, "k_gap": 6584710, "k_fc": 5406709}},
 }
 
 
