@@ -121,6 +121,41 @@ def test_stride2_is_subsampled_stride1(h, w_):
     assert np.array_equal(y2, y1[:, ::2, ::2, :])
 
 
+@pytest.mark.parametrize("k,stride,pad,groups", [(3, 1, 1, 1), (3, 2, 1, 1), (1, 1, 0, 1), (1, 2, 0, 1),
+                                                 (7, 2, 3, 1), (5, 1, 2, 1), (3, 1, 1, 6), (3, 2, 1, 6),
+                                                 (11, 4, 2, 1)])
+def test_conv2d_agrees_with_torch_cpu_as_a_third_opinion(k, stride, pad, groups):
+    """torch.nn.functional.conv2d on the CPU (NCHW, its own kernels) on random tensors: every
+    filter size, stride and padding the workloads use, dense and depthwise (groups = channels)."""
+    import torch
+    import torch.nn.functional as F
+    cin, cout = 6, 6 if groups > 1 else 5
+    x = rnd(2, 13, 17, cin)
+    w = rnd(cout, k, k, cin // groups)
+    b = rnd(cout)
+    want = F.conv2d(torch.from_numpy(x).permute(0, 3, 1, 2).double(),
+                    torch.from_numpy(w).permute(0, 3, 1, 2).double(), torch.from_numpy(b).double(),
+                    stride=stride, padding=pad, groups=groups).permute(0, 2, 3, 1).numpy()
+    for acc, tol in (("f32", 2e-5), ("f64", 2e-6)):
+        got = o.conv2d(x, w, b, stride, pad, groups=groups, acc=acc)
+        assert got.shape == want.shape
+        assert np.abs(got - want).max() <= tol * max(1.0, np.abs(want).max())
+
+
+def test_maxpool_and_fc_agree_with_torch_cpu():
+    import torch
+    import torch.nn.functional as F
+    x = rnd(2, 9, 11, 4)
+    for k, s, p in ((2, 2, 0), (3, 2, 1), (3, 2, 0)):
+        want = F.max_pool2d(torch.from_numpy(x).permute(0, 3, 1, 2), k, s, p).permute(0, 2, 3, 1).numpy()
+        assert np.array_equal(o.maxpool(x, k, s, p), want)
+    xf = rnd(3, 40)
+    w = rnd(7, 40)
+    b = rnd(7)
+    want = F.linear(torch.from_numpy(xf).double(), torch.from_numpy(w).double(), torch.from_numpy(b).double()).numpy()
+    assert np.abs(o.fc(xf, w, b, acc="f64") - want).max() <= 1e-5
+
+
 def test_stride2_5x5_hand_case():
     # 5x5 ramp, 3x3 box kernel, stride 2, pad 1 -> 3x3 window sums, by hand
     x = np.arange(25, dtype=np.float32).reshape(1, 5, 5, 1)

@@ -215,3 +215,46 @@ def test_algorithm1_invariants_on_real_shapes(builder):
                     avg2 = sum(mp[:-1]) / (len(mp) - 1)
                     assert sum(ops[i] for i in convs[:-1]) / avg2 < crit
             first = last + 1
+
+
+def test_layerwise_budgets_hand_trace():
+    """The no-fusion rows of the table of strategies (Sec. V): strategy 3 gives every layer the MP of
+    Eq. 5 rounded as a one-layer block; strategies 1 and 2 give every layer one fixed MP.  With
+    alpha = 1, beta = 0, k = 1, b = 0 the per-layer MP is log2(min(Cin, Cout))."""
+    layers = [nets.maxpool(16), nets.conv(16, 64, 3), nets.maxpool(64), nets.conv(64, 256, 1),
+              nets.conv(256, 48, 3), nets.gavgpool(48), nets.fc(48, 1000)]
+    ops = [0, 100, 0, 100, 100, 0, 100]
+    # log2 C: conv0 min(16,64) -> 4 ; conv1 min(64,256) -> 6 -> 2^2 = 4 ; conv2 min(256,48) -> 5.58 -> 4
+    # fc min(48,1000) -> 5.58 -> 4.  A leading pool has no convolution before it: smallest allowed MP;
+    # later pools take the MP of the convolution before them.
+    got = po.layerwise_budgets(layers, ops, alpha=1, beta=0, k=1, b=0, allowed=(1, 2, 4, 8))
+    assert got == [1, 4, 4, 4, 4, 4, 4]
+    # k = 2: MPs 8, 12 -> 8, 11.17 -> 8, 11.17 -> 8 clamped to max 8
+    got = po.layerwise_budgets(layers, ops, alpha=1, beta=0, k=2, b=0, allowed=(1, 2, 4, 8))
+    assert got == [1, 8, 8, 8, 8, 8, 8]
+    # an allowed set without 4: 2^floor(log2 x) = 4 falls to the largest allowed value below, 2;
+    # beta = 1 on ops 2^3 / 2^5: MP = log2 ops -> 3 -> 2 ; 5 -> 4 -> 2 ... ; ops 2^7 -> 7 -> 4 -> 2 ; 2^9 -> 9 -> 8
+    layers2 = [nets.conv(16, 16, 3), nets.maxpool(16), nets.conv(16, 16, 3), nets.conv(16, 16, 3)]
+    got = po.layerwise_budgets(layers2, [2 ** 3, 0, 2 ** 7, 2 ** 9], alpha=0, beta=1, k=1, b=0,
+                               allowed=(2, 8, 32))
+    assert got == [2, 2, 2, 8]
+    # one MP for all (strategies 1 and 2), pools included
+    assert po.layerwise_budgets(layers, ops, fixed_budget=16) == [16] * 7
+
+
+def test_max_fusion_hand_trace():
+    """Strategy 4 of the table of strategies (everything fused, maximal MP), as far as a
+    feasibility test lets blocks grow: the longest feasible block from the left, again and again."""
+    # feasible iff the block has at most 3 layers
+    assert po.max_fusion(7, lambda f, l: l - f < 3, 32) == [(0, 2, 32), (3, 5, 32), (6, 6, 32)]
+    # everything feasible: one block
+    assert po.max_fusion(5, lambda f, l: True, 8) == [(0, 4, 8)]
+    # only single layers feasible
+    assert po.max_fusion(3, lambda f, l: f == l, 4) == [(0, 0, 4), (1, 1, 4), (2, 2, 4)]
+    # a feasibility test that is not monotone: [0,3] is infeasible, [0,2] too, [0,1] feasible;
+    # then [2,4] feasible
+    ok = {(0, 1), (2, 4), (0, 0), (1, 1), (2, 2), (3, 3), (4, 4), (2, 3)}
+    assert po.max_fusion(5, lambda f, l: (f, l) in ok, 2) == [(0, 1, 2), (2, 4, 2)]
+    # a layer that cannot run even alone is the caller's error
+    with pytest.raises(AssertionError):
+        po.max_fusion(2, lambda f, l: False, 2)
