@@ -25,21 +25,41 @@ def _manual(lasts, budget):
     return dict(mode=B.TUNER_MANUAL, group_last=list(lasts), group_budget=[budget] * len(lasts))
 
 
-def _check_groups(s, net, x, ws, bs):
-    """Each group's output vs the oracle applied to the GPU's own input of that group."""
+KIND_NAME = {0: "group", 1: "fc", 2: "gap", 3: "pw", 4: "c3b", 5: "dw", 6: "dwpw", 7: "pw2"}
+
+
+def _kinds(s):
+    """(kind name, variant) of every group of the session's plan, as the library reports them."""
+    from paper_2011_05630_amd import binding as B
+    out = []
+    for g in range(len(s.groups)):
+        cfg = B.dlf_plan_group_config(s.plan, g)
+        out.append((KIND_NAME[cfg["kind"]], cfg["variant"]))
+    return out
+
+
+def _check_groups(s, net, x, ws, bs, sample=None):
+    """Each group's output vs the oracle applied to the GPU's own input of that group, on the
+    images `sample` of the batch (all images if None): images are independent, so a sampled
+    image's tensors are exactly those of a full run."""
     from oracle import oracle as o
     n = len(net["layers"])
-    outs = {-1: x.astype(np.float32)}
+    idx = list(range(x.shape[0])) if sample is None else list(sample)
+    tidx = torch.tensor(idx, device="cuda")
+    outs = {-1: x[idx].astype(np.float32)}
     for i in range(n):
         t = s.layer_output(i)
         if t is not None:
-            outs[i] = t.float().cpu().numpy()
+            outs[i] = t.index_select(0, tidx).float().cpu().numpy()
+    checked = 0
     for g in s.groups:
         if g["last"] == n - 1:
             continue
         given = {k: v for k, v in outs.items() if k < g["first"]}
         ref = o.run_net(net, None, ws, bs, first=g["first"], last=g["last"], given=given)
         compare(outs[g["last"]], ref, "  group [%d,%d]" % (g["first"], g["last"]))
+        checked += 1
+    assert checked == len(s.groups) - 1
 
 
 def test_config1_two_layer_block_fused_vs_unfused():
@@ -69,40 +89,45 @@ PARTITIONS = {1: [0, 1, 2, 3], 2: [1, 3], 3: [2, 3], 4: [3]}
 @pytest.mark.parametrize("batch", [1, 8])
 def test_config2_layer_sweep(c, batch):
     from oracle import oracle as o
-    from paper_2011_05630_amd.binding import DlfError, DLF_ERR_INFEASIBLE
     net = nets.chain4(c)
     x, ws, bs = gen.make_params(net, batch)
     ref = o.run_net(net, x, ws, bs)
     ran = 0
+    # every one of the 16 (depth, budget) points of every width fits on-chip memory (with smaller
+    # tiles as the width grows): a point that stops fitting raises here
     for depth, lasts in PARTITIONS.items():
         for budget in (32, 64, 128, 256):
             announce("config2 C", c, "batch", batch, "depth", depth, "budget", budget)
-            try:
-                s = _session(net, batch, ws, bs, **_manual(lasts, budget))
-            except DlfError as e:
-                assert e.status == DLF_ERR_INFEASIBLE, e
-                print("  infeasible (on-chip memory):", e)
-                continue
+            s = _session(net, batch, ws, bs, **_manual(lasts, budget))
+            assert [g["last"] for g in s.groups] == lasts
             got = s.run_numpy(x)
             s.close()
             compare(got, ref, "config2 C=%d b=%d depth=%d budget=%d" % (c, batch, depth, budget))
             ran += 1
-    assert ran >= 4          # depth 1 is always feasible
+    assert ran == 16
 
 
-def _net_case(net, batch, sample, check_groups, plans):
+def _net_case(net, batch, sample, check_groups, plans, expect_kinds=()):
+    """expect_kinds: (kind name, variant or None) pairs the first plan must contain: the kernels the
+    cost model is known to pick for this workload, so that a silent change of the planner's choice
+    (and with it of what this test covers) shows."""
     from oracle import oracle as o
     x, ws, bs = gen.make_params(net, batch)
     xs = x[sample]
     ref = o.run_net(net, xs, ws, bs)
-    for pname, plan in plans:
+    for pi, (pname, plan) in enumerate(plans):
         announce(net["name"], "batch", batch, "plan", pname)
         s = _session(net, batch, ws, bs, **plan)
-        print("  groups:", [(g["first"], g["last"], g["budget"]) for g in s.groups])
+        kinds = _kinds(s)
+        print("  groups:", [(g["first"], g["last"], g["budget"]) + k for g, k in zip(s.groups, kinds)])
+        if pi == 0:
+            for kind, variant in expect_kinds:
+                assert any(k == kind and (variant is None or v == variant) for k, v in kinds), \
+                    "plan holds no %s%s group: %r" % (kind, "" if variant is None else "/%d" % variant, kinds)
         got = s.run_numpy(x)
         compare(got[sample], ref, "%s b=%d %s" % (net["name"], batch, pname))
         if check_groups:
-            _check_groups(s, net, x, ws, bs)
+            _check_groups(s, net, x, ws, bs, sample)
         s.close()
 
 
@@ -120,7 +145,8 @@ def test_config3_vgg16_batch1():
 
 def test_config3_vgg16_batch16_sampled():
     net = nets.vgg16()
-    _net_case(net, 16, [0, 15], False, _plans(net)[:1])
+    # the plan the benchmark times: block 3x3 kernel on the wide layers, split-K FC on 25088 -> 4096
+    _net_case(net, 16, [0, 7, 15], True, _plans(net)[:1], expect_kinds=[("c3b", None), ("group", None), ("fc", None)])
 
 
 def test_config4_resnet50_batch1():
@@ -130,7 +156,9 @@ def test_config4_resnet50_batch1():
 
 def test_config4_resnet50_batch32_sampled():
     net = nets.resnet50()
-    _net_case(net, 32, [0, 17, 31], False, _plans(net)[:1])
+    # image 17: its pixels straddle the 128-pixel blocks of the pointwise block kernel on every map
+    _net_case(net, 32, [0, 17, 31], True, _plans(net)[:1],
+              expect_kinds=[("pw", 3), ("pw", 2), ("group", None)])
 
 
 def test_config5_mobilenet_batch1():
@@ -140,7 +168,7 @@ def test_config5_mobilenet_batch1():
 
 def test_config5_mobilenet_batch64_sampled():
     net = nets.mobilenet_v1()
-    _net_case(net, 64, [0, 33, 63], False, _plans(net)[:1])
+    _net_case(net, 64, [0, 33, 63], True, _plans(net)[:1], expect_kinds=[("pw", None)])
 
 
 def test_other_evaluated_networks_small_batch():
