@@ -132,6 +132,19 @@ dlf_status dlf_plan_bind_workspace(dlf_plan_t* plan, void* dev_ptr, size_t bytes
  * into a HIP graph (tested: replays equal the eager result; on MI355X a replay is no faster than
  * the eager launches, the step being bound on the GPU side). */
 dlf_status dlf_run(const dlf_plan_t* plan, const void* in_dev, void* out_dev, void* hip_stream);
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): dlf_run with the workspace -- the tensors that cross
+ * group boundaries and the partial sums of a split-K FC layer -- in a static device array of
+ * dlf_static_workspace_bytes() (32 MiB) that the library's code object holds on every GPU it runs
+ * on until the process ends; no workspace has to be bound, and a bound one is not used.  in_dev /
+ * out_dev as for dlf_run (DEVICE, caller-owned).  Calls no hipMalloc / hipFree and creates no
+ * stream or event; every group runs in order on hip_stream (dlf_plan_set_overlap is ignored).
+ * DLF_ERR_OOM if dlf_plan_workspace_bytes(plan) exceeds the static size.  All calls on one GPU share
+ * that GPU's array, whatever the plan: two calls whose kernels overlap in time on one GPU (different
+ * streams or threads) race; calls on one stream are ordered and safe.  Nothing in the array has to
+ * start at zero: every byte a kernel reads was written earlier in the same call. */
+dlf_status dlf_run_noalloc(const dlf_plan_t* plan, const void* in_dev, void* out_dev, void* hip_stream);
+size_t dlf_static_workspace_bytes(void);
 /* Branches of the network (the layer graph of a residual network is not a chain): with on != 0 a
  * group that does not read the output of the group in front of it -- the projection shortcut of a
  * residual block, placed behind the block's first layers -- is launched by dlf_run on a second

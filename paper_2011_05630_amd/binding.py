@@ -17,6 +17,9 @@ ACT = {"none": 0, "relu": 1, "relu6": 2}
 TUNER_DP, TUNER_GREEDY, TUNER_MANUAL, TUNER_LAYERWISE, TUNER_MAXFUSE = 0, 1, 2, 3, 4
 DLF_OK = 0
 DLF_ERR_INFEASIBLE = 4
+DLF_ERR_OOM = 5
+DLF_ERR_HIP = 6
+DLF_ERR_NO_WEIGHTS = 7
 
 
 class DlfError(RuntimeError):
@@ -87,6 +90,10 @@ def lib():
     L.dlf_plan_bind_workspace.restype = i32
     L.dlf_run.argtypes = [vp, vp, vp, vp]
     L.dlf_run.restype = i32
+    L.dlf_run_noalloc.argtypes = [vp, vp, vp, vp]
+    L.dlf_run_noalloc.restype = i32
+    L.dlf_static_workspace_bytes.argtypes = []
+    L.dlf_static_workspace_bytes.restype = ctypes.c_size_t
     L.dlf_run_group.argtypes = [vp, i32, vp, vp, vp, vp]
     L.dlf_run_group.restype = i32
     L.dlf_plan_layer_output.argtypes = [vp, i32]
@@ -257,6 +264,14 @@ def dlf_plan_bind_workspace(plan, dev_ptr, nbytes):
 
 def dlf_run(plan, in_ptr, out_ptr, stream=None):
     _check(lib().dlf_run(plan, in_ptr, out_ptr, stream))
+
+
+def dlf_run_noalloc(plan, in_ptr, out_ptr, stream=None):
+    _check(lib().dlf_run_noalloc(plan, in_ptr, out_ptr, stream))
+
+
+def dlf_static_workspace_bytes():
+    return int(lib().dlf_static_workspace_bytes())
 
 
 def dlf_run_profiled(plan, in_ptr, out_ptr, stream, reps):

@@ -8,12 +8,20 @@
 #include <cstdio>
 #include <cstring>
 #include <limits>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
 
 #include "../../include/dlf.h"
 #include "dlf_internal.h"
+
+// Workspace of dlf_run_noalloc: a file-scope device array, one copy per GPU the library runs on, held
+// until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the device address it returns (per device) is what kernels are given.
+#define DLF_STATIC_WS_BYTES ((size_t)32 << 20)
+#define DLF_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char scratch[DLF_STATIC_WS_BYTES];
 
 namespace {
 
@@ -98,8 +106,6 @@ dlf_status upload(const void* host, size_t bytes, void** dev)
     if (e != hipSuccess) return fail(DLF_ERR_HIP, "hipMemcpy: %s", hipGetErrorString(e));
     return DLF_OK;
 }
-
-bool g_kernels_ready = false;
 
 dlf_status pack_and_upload(Layer& L)
 {
@@ -1523,21 +1529,23 @@ const void* dlf_plan_layer_output(const dlf_plan_t* plan, int32_t layer)
     return plan->ws + plan->layer_off[layer];
 }
 
+static std::once_flag g_kernels_once;
+static int g_kernels_rc = 0;
+
+// ws: base of the workspace this run uses (the plan's bound one, or the static array)
 static dlf_status launch_one(const dlf_plan_s* plan, const GroupPlan& G, const void* in, const void* res,
-                             void* out, void* stream)
+                             void* out, void* stream, char* ws)
 {
     int e = 0;
-    if (!g_kernels_ready) {
-        e = dlf_kernels_init();
-        if (e != 0) return fail(DLF_ERR_HIP, "kernel setup failed: %s", hipGetErrorString((hipError_t)e));
-        g_kernels_ready = true;
-    }
+    std::call_once(g_kernels_once, [] { g_kernels_rc = dlf_kernels_init(); });
+    if (g_kernels_rc != 0)
+        return fail(DLF_ERR_HIP, "kernel setup failed: %s", hipGetErrorString((hipError_t)g_kernels_rc));
     if (G.kind == GK_FC) {
         DlfFcArgs fa = G.fa;
         fa.x = in; fa.y = out;
         if (fa.ksplit > 1) {
-            if (!plan->ws) return fail(DLF_ERR_INVALID_ARG, "no workspace bound");
-            fa.part = (float*)(plan->ws + G.scratch_off);
+            if (!ws) return fail(DLF_ERR_INVALID_ARG, "no workspace bound");
+            fa.part = (float*)(ws + G.scratch_off);
         }
         e = dlf_launch_fc(&fa, stream);
     } else if (G.kind == GK_GAP) {
@@ -1581,7 +1589,7 @@ dlf_status dlf_run_group(const dlf_plan_t* plan, int32_t g, const void* in_dev, 
     if (!plan || g < 0 || g >= (int)plan->G.size() || !in_dev || !out_dev)
         return fail(DLF_ERR_INVALID_ARG, "dlf_run_group: bad argument");
     if (!plan->net->has_weights) return fail(DLF_ERR_NO_WEIGHTS, "network was created without weights");
-    return launch_one(plan, plan->G[g], in_dev, res_dev, out_dev, hip_stream);
+    return launch_one(plan, plan->G[g], in_dev, res_dev, out_dev, hip_stream, plan->ws);
 }
 
 static void group_pointers(const dlf_plan_s* plan, size_t g, const void* in_dev, void* out_dev,
@@ -1625,7 +1633,7 @@ dlf_status dlf_plan_refine(dlf_plan_t* plan, const void* in_dev, void* out_dev, 
         dlf_status r = DLF_OK;
         std::vector<double> sum(list.size(), 0.0);
         for (size_t i = 0; i < list.size() && r == DLF_OK; ++i)
-            r = launch_one(plan, list[i], in, res, out, hip_stream);          // warm-up
+            r = launch_one(plan, list[i], in, res, out, hip_stream, plan->ws);          // warm-up
         for (int rep = 0; rep < reps && r == DLF_OK; ++rep)
             for (size_t i = 0; i < list.size() && r == DLF_OK; ++i) {
                 if (scrub) (void)hipMemsetAsync(scrub, rep, scrub_bytes, st);
@@ -1633,11 +1641,11 @@ dlf_status dlf_plan_refine(dlf_plan_t* plan, const void* in_dev, void* out_dev, 
                     const void *pin, *pres;
                     void* pout;
                     group_pointers(plan, g - 1, in_dev, out_dev, &pin, &pres, &pout);
-                    r = launch_one(plan, plan->G[g - 1], pin, pres, pout, hip_stream);
+                    r = launch_one(plan, plan->G[g - 1], pin, pres, pout, hip_stream, plan->ws);
                     if (r != DLF_OK) break;
                 }
                 (void)hipEventRecord(e0, st);
-                r = launch_one(plan, list[i], in, res, out, hip_stream);
+                r = launch_one(plan, list[i], in, res, out, hip_stream, plan->ws);
                 (void)hipEventRecord(e1, st);
                 if (hipEventSynchronize(e1) != hipSuccess && r == DLF_OK)
                     r = fail(DLF_ERR_HIP, "event synchronise failed");
@@ -1759,7 +1767,7 @@ dlf_status dlf_run_profiled(const dlf_plan_t* plan, const void* in_dev, void* ou
             void* out;
             group_pointers(plan, g, in_dev, out_dev, &in, &res, &out);
             dlf_next_launch_events(nullptr, ev[1 + r * ng + g]);
-            rs = launch_one(plan, plan->G[g], in, res, out, hip_stream);
+            rs = launch_one(plan, plan->G[g], in, res, out, hip_stream, plan->ws);
             dlf_next_launch_events(nullptr, nullptr);
             if (rs != DLF_OK) break;
         }
@@ -1829,7 +1837,7 @@ dlf_status dlf_run(const dlf_plan_t* plan, const void* in_dev, void* out_dev, vo
                     hipStreamWaitEvent(st, plan->done[d], 0) != hipSuccess)
                     return fail(DLF_ERR_HIP, "hipStreamWaitEvent failed");
         }
-        dlf_status s = launch_one(plan, G, in, res, out, (void*)st);
+        dlf_status s = launch_one(plan, G, in, res, out, (void*)st, plan->ws);
         if (s != DLF_OK) return s;
         if (any_side && plan->done[g] != nullptr && hipEventRecord(plan->done[g], st) != hipSuccess)
             return fail(DLF_ERR_HIP, "hipEventRecord failed");
@@ -1839,6 +1847,52 @@ dlf_status dlf_run(const dlf_plan_t* plan, const void* in_dev, void* out_dev, vo
         if (hipEventRecord(plan->side_end, plan->side) != hipSuccess ||
             hipStreamWaitEvent(main_s, plan->side_end, 0) != hipSuccess)
             return fail(DLF_ERR_HIP, "stream join failed");
+    }
+    return DLF_OK;
+}
+
+// Device address of this GPU's copy of the static workspace, looked up once per device.
+static dlf_status static_workspace(char** base)
+{
+    static std::mutex mu;
+    static void* ptr[DLF_MAX_DEVICES] = {nullptr};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(DLF_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= DLF_MAX_DEVICES) return fail(DLF_ERR_UNSUPPORTED, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(mu);
+    if (ptr[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || p == nullptr)
+            return fail(DLF_ERR_HIP, "hipGetSymbolAddress(static workspace): %s", hipGetErrorString(e));
+        ptr[dev] = p;
+    }
+    *base = (char*)ptr[dev];
+    return DLF_OK;
+}
+
+size_t dlf_static_workspace_bytes(void) { return DLF_STATIC_WS_BYTES; }
+
+dlf_status dlf_run_noalloc(const dlf_plan_t* plan, const void* in_dev, void* out_dev, void* hip_stream)
+{
+    if (!plan || !in_dev || !out_dev) return fail(DLF_ERR_INVALID_ARG, "dlf_run_noalloc: null argument");
+    if (!plan->net->has_weights) return fail(DLF_ERR_NO_WEIGHTS, "network was created without weights");
+    if (plan->ws_bytes > DLF_STATIC_WS_BYTES)
+        return fail(DLF_ERR_OOM, "dlf_run_noalloc: the plan needs %zu bytes of workspace, the static one holds %zu",
+                    plan->ws_bytes, (size_t)DLF_STATIC_WS_BYTES);
+    char* ws = nullptr;
+    dlf_status s = static_workspace(&ws);
+    if (s != DLF_OK) return s;
+    // every group in order on the caller's stream: nothing here creates a stream or an event
+    const size_t ng = plan->G.size();
+    for (size_t g = 0; g < ng; ++g) {
+        const GroupPlan& G = plan->G[g];
+        const void* in = G.in_layer < 0 ? in_dev : ws + plan->layer_off[G.in_layer];
+        const void* res = G.res_stage >= 0 ? ws + plan->layer_off[G.res_layer] : nullptr;
+        void* out = (g + 1 == ng) ? out_dev : (void*)(ws + plan->layer_off[G.last]);
+        s = launch_one(plan, G, in, res, out, hip_stream, ws);
+        if (s != DLF_OK) return s;
     }
     return DLF_OK;
 }
