@@ -48,6 +48,7 @@ def csrc_sha1():
 VARIANT_NAME = {0: "k_group<2,2,2>", 1: "k_group<1,4,2>", 2: "k_group<1,2,2>", 3: "k_group<1,2,4>"}
 # pointwise kernels by item shape
 PW_NAME = {0: "k_pw<2,2,6,2>", 1: "k_pw<1,1,8,4>", 2: "k_pw_sk", 3: "k_pwb<2,2>", 4: "k_pwb<1,4>"}
+DW_NAME = {0: "k_dw<1>", 1: "k_dw<2>"}
 C3_NAME = {0: "k_c3b<2,32,2>", 1: "k_c3b<2,64,2>", 2: "k_c3b<1,32,2>", 3: "k_c3b<1,64,2>", 4: "k_c3b<2,32,4>"}
 
 
@@ -114,6 +115,10 @@ def group_accounting(net, batch, session):
             kname = "k_gap"
         elif cfg["kind"] == 4:
             kname = C3_NAME[cfg["variant"]]
+        elif cfg["kind"] == 5:
+            kname = DW_NAME[cfg["variant"]]
+        elif cfg["kind"] == 6:
+            kname = "k_dwpw<%d>" % cfg["variant"]
         else:
             kname = VARIANT_NAME[cfg["variant"]]
         out.append(dict(first=f, last=l, budget=info["budget"], flops=flops, bytes=byts,

@@ -181,7 +181,10 @@ const void* dlf_plan_layer_output(const dlf_plan_t* plan, int32_t layer);
  * 3 = 32x64 built for two workgroups per CU), for kind 3 the work-item form (0 = 64x64 and
  * 1 = 32x32 per wave, 2 = 64x64 with K split over four waves, 3 = 128x128 and 4 = 64x256 blocks
  * shared through LDS), for kind 4 the block shape (0 / 1 = 128 channels x 256 pixels, 2 / 3 =
- * 64 x 512, odd: activations 64 input channels at a time, even: 32; 4 = 128 x 512); channel slices, channels
+ * 64 x 512, odd: activations 64 input channels at a time, even: 32; 4 = 128 x 512), 5 streaming
+ * depthwise kernel: a single depthwise 3x3 layer (variant = stride - 1), 6 fused depthwise 3x3 +
+ * 1x1 kernel: a depthwise layer and the pointwise layer behind it, the depthwise result held in
+ * registers (variant = 32-channel blocks of a wave's work item, 2 or 4); channel slices, channels
  * per slice, whether stage 0 streams its input, LDS bytes per workgroup.  Any out pointer may be
  * NULL. */
 dlf_status dlf_plan_group_config(const dlf_plan_t* plan, int32_t g, int32_t* kind, int32_t* variant,
@@ -222,6 +225,12 @@ void dlf_debug_force_ksplit(int32_t ksplit);
  * 6 / 7 = with workgroup blocks of 128 channels x 128 pixels / 64 channels x 256 pixels whose
  * operands are shared through LDS.  Process-wide, not thread-safe. */
 void dlf_debug_pointwise_mode(int32_t mode);
+
+/* Testing hook: how a single depthwise 3x3 layer (pad 1, stride 1 or 2), or such a layer with the 1x1
+ * convolution behind it, chooses between the fused-group kernel and the streaming depthwise kernel /
+ * the fused depthwise + 1x1 kernel: 0 = by modelled cost (default), 1 = the depthwise kernels
+ * wherever they apply, 2 = never.  Process-wide, not thread-safe. */
+void dlf_debug_depthwise_mode(int32_t mode);
 
 /* Testing hook: how a single 3x3 stride-1 pad-1 convolution (with the 2x2 max pool folded behind
  * it, if any) chooses between the fused-group kernel and the block 3x3 kernel: mode 0 = by

@@ -110,6 +110,8 @@ def lib():
     L.dlf_debug_force_ksplit.restype = None
     L.dlf_debug_pointwise_mode.argtypes = [i32]
     L.dlf_debug_pointwise_mode.restype = None
+    L.dlf_debug_depthwise_mode.argtypes = [i32]
+    L.dlf_debug_depthwise_mode.restype = None
     L.dlf_debug_block3x3_mode.argtypes = [i32, i32, i32, i32]
     L.dlf_debug_block3x3_mode.restype = None
     L.dlf_plan_set_overlap.argtypes = [vp, i32]
@@ -305,6 +307,12 @@ def dlf_cost_model_version():
 def dlf_debug_force_ksplit(ksplit=1):
     """Testing hook (after dlf_debug_force_config): K of the forced tiling split over `ksplit` waves."""
     lib().dlf_debug_force_ksplit(ksplit)
+
+
+def dlf_debug_depthwise_mode(mode=0):
+    """Testing hook: 0 = streaming depthwise kernel chosen by modelled cost, 1 = wherever it applies,
+    2 = never."""
+    lib().dlf_debug_depthwise_mode(mode)
 
 
 def dlf_debug_pointwise_mode(mode=0):

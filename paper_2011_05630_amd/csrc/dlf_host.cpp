@@ -153,7 +153,7 @@ dlf_status pack_and_upload(Layer& L)
 // Fusion groups
 // ------------------------------------------------------------------------------------------
 
-enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3, GK_C3 = 4 };
+enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3, GK_C3 = 4, GK_DW = 5, GK_DWPW = 6 };
 
 struct TileCfg {
     int th, tw;      // tile of the group's final output tensor
@@ -179,6 +179,8 @@ struct GroupPlan {
     DlfGapArgs pa;
     DlfPwArgs wa;
     DlfC3Args ca;
+    DlfDwArgs da;
+    DlfDwPwArgs dp;
 };
 
 const int VAR_FC[DLF_NUM_VARIANTS] = {2, 1, 1, 1};
@@ -239,6 +241,26 @@ const int64_t C_C3_SHORT_K = 6000;          // per item when K has fewer than 8 
 const int64_t C3_MMA_TENTHS = 16;
 const int64_t C3_BYTES_PER_CYCLE = 25;
 const int64_t C3_SHALLOW_RING = 300;        // per stage when the weight ring has two stages only
+
+// streaming depthwise kernel: per work item (decode, weights, first rows of the window), per output
+// row of a wave (about a hundred vector instructions; the waves of a SIMD share its issue slots),
+// the rate at which the chip streams the tensors, waves in flight per CU
+const int64_t C_DW_ITEM = 2500;
+const int64_t C_DW_ROW = 420;
+const int64_t DW_HBM_BYTES_PER_CYCLE = 2300;
+const int64_t DW_CU_BYTES_PER_CYCLE = 24;
+const int DW_WAVES_PER_CU = 16;
+
+// fused depthwise + 1x1 kernel: per work item (decode, first loads, epilogue), per K step the vector
+// instructions of a wave (nine taps x 8 channels of mixed-precision multiply-adds and their operands;
+// the two waves of a SIMD share its issue slots), cycles a CU's vector-memory path needs per load
+// instruction of a wave: a K step takes 16 of a pixel's channels, a quarter of a 128-byte line, and
+// with eight waves' lines in flight the CU's cache does not keep a line until the next K step asks
+// for it again, so 1 KiB of operands costs 4 KiB of intake (measured: 800 cycles per K step and item
+// on a CU for 13 loads)
+const int64_t C_DWPW_ITEM = 4000;
+const int64_t C_DWPW_STEP = 470;
+const int64_t C_DWPW_LOAD = 62;
 
 struct StageSpec {   // one stage, before tiling
     int layer;
@@ -830,6 +852,99 @@ bool c3_choose(const Layer& L, int pool2, int batch, int budget, int max_lds, C3
     return found;
 }
 
+// ---- streaming depthwise kernel (one depthwise 3x3 layer, pad 1, stride 1 or 2) ----
+
+// Testing hook: 0 = the streaming kernel competes with the fused-group kernel on modelled cost,
+// 1 = always where it applies, 2 = never.
+int g_dw_mode = 0;
+
+bool dw_eligible(const Layer& L, int batch)
+{
+    const dlf_layer_desc& d = L.d;
+    if (d.op != DLF_DWCONV || d.kh != 3 || d.kw != 3 || d.pad != 1 || (d.stride != 1 && d.stride != 2)) return false;
+    if ((d.cin % 8) != 0 || d.residual_from >= 0) return false;
+    // byte offsets into the input are formed in 31 bits, element offsets into the output in 32
+    if ((int64_t)batch * L.in_h * L.in_w * L.in_c * 2 >= (int64_t)1 << 31) return false;
+    if ((int64_t)batch * L.out_h * L.out_w * L.out_c >= (int64_t)1 << 31) return false;
+    return true;
+}
+
+void dw_fill(const Layer& L, int batch, DlfDwArgs& da)
+{
+    memset(&da, 0, sizeof da);
+    da.w = L.d_w; da.bias = L.d_bias;
+    da.in_bytes = (uint32_t)((int64_t)batch * L.in_h * L.in_w * L.in_c * 2);
+    da.batch = batch; da.h = L.in_h; da.w_ = L.in_w; da.c = L.d.cin; da.cpad = L.cin_pad;
+    da.oh = L.out_h; da.ow = L.out_w; da.stride = L.d.stride; da.act = L.d.act;
+    da.cg = L.d.cin / 8;
+    da.rowv = L.out_w * da.cg;
+    da.nxr = ceil_div(da.rowv, 64);
+    da.nstrips = ceil_div(L.out_h, L.d.stride == 1 ? DLF_DW_ROWS1 : DLF_DW_ROWS2);
+    da.nitems = batch * da.nstrips * da.nxr;
+}
+
+uint64_t dw_cost_ps(const Layer& L, int batch, int budget, const DlfDwArgs& da)
+{
+    const int64_t rows = std::min<int64_t>(L.out_h, L.d.stride == 1 ? DLF_DW_ROWS1 : DLF_DW_ROWS2);
+    // the items of a CU are dealt to its four SIMDs; a SIMD's waves share its instruction issue
+    const int64_t items_simd = ((int64_t)da.nitems + (int64_t)budget * 4 - 1) / ((int64_t)budget * 4);
+    const int64_t compute = C_LAT + items_simd * (C_DW_ITEM / (DW_WAVES_PER_CU / 4) + rows * C_DW_ROW);
+    const int64_t bytes = (int64_t)da.in_bytes + (int64_t)batch * L.out_h * L.out_w * L.out_c * 2 + (int64_t)L.cin_pad * 22;
+    const int64_t mem = bytes / std::min<int64_t>(DW_HBM_BYTES_PER_CYCLE, (int64_t)budget * DW_CU_BYTES_PER_CYCLE);
+    return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
+}
+
+// ---- fused depthwise 3x3 + 1x1 kernel (a depthwise layer and the pointwise layer that reads it) ----
+
+bool dwpw_eligible(const dlf_net_s& net, int first, int last, int batch)
+{
+    if (last != first + 1) return false;
+    const Layer& D = net.L[first];
+    const Layer& P = net.L[last];
+    if (!dw_eligible(D, batch) || (D.d.cin % 32) != 0) return false;
+    const dlf_layer_desc& p = P.d;
+    if (p.op != DLF_CONV || p.kh != 1 || p.kw != 1 || p.pad != 0 || p.stride != 1 || P.src != first) return false;
+    if (p.residual_from >= 0 || (p.cout % 8) != 0 || P.nsteps != D.d.cin / 16) return false;
+    if ((int64_t)batch * P.out_h * P.out_w * P.out_c >= (int64_t)1 << 31) return false;
+    if (DLF_DWPW_LDS_BYTES(D.d.cin, 4) > 64 * 1024) return false;
+    // the depthwise output exists only in registers: nothing else may read it
+    for (size_t k = 0; k < net.L.size(); ++k) {
+        if (net.L[k].d.residual_from == first) return false;
+        if ((int)k != last && net.L[k].src == first) return false;
+    }
+    return true;
+}
+
+void dwpw_fill(const Layer& D, const Layer& P, int batch, int nb, DlfDwPwArgs& dp)
+{
+    memset(&dp, 0, sizeof dp);
+    dp.wdw = D.d_w; dp.bdw = D.d_bias; dp.wpw = P.d_w; dp.bpw = P.d_bias;
+    dp.in_bytes = (uint32_t)((int64_t)batch * D.in_h * D.in_w * D.in_c * 2);
+    dp.batch = batch; dp.h = D.in_h; dp.w_ = D.in_w; dp.c = D.d.cin;
+    dp.oh = D.out_h; dp.ow = D.out_w; dp.stride = D.d.stride; dp.act_dw = D.d.act; dp.act_pw = P.d.act;
+    dp.cout = P.d.cout; dp.ncb = P.ncb; dp.nsteps = P.nsteps;
+    dp.m = batch * D.out_h * D.out_w;
+    dp.n_pg = ceil_div(dp.m, 32);
+    dp.n_cg = ceil_div(P.ncb, nb);
+    dp.nitems = dp.n_pg * dp.n_cg;
+}
+
+uint64_t dwpw_cost_ps(const Layer& D, const Layer& P, int batch, int budget, int nb)
+{
+    const int64_t m = (int64_t)batch * D.out_h * D.out_w;
+    const int64_t items = ((m + 31) / 32) * ceil_div(P.ncb, nb);
+    const int64_t items_simd = (items + (int64_t)budget * 4 - 1) / ((int64_t)budget * 4);
+    const int64_t items_cu = (items + budget - 1) / budget;
+    const int64_t valu = items_simd * (C_DWPW_ITEM / 2 + P.nsteps * C_DWPW_STEP);
+    const int64_t mfma = items_simd * P.nsteps * nb * MFMA_CYCLES;
+    const int64_t loads = items_cu * P.nsteps * (9 + nb) * C_DWPW_LOAD;
+    const int64_t compute = C_LAT + std::max(std::max(valu, mfma), loads);
+    const int64_t bytes = (int64_t)batch * D.in_h * D.in_w * D.in_c * 2 + m * P.d.cout * 2 +
+                          (int64_t)P.ncb * P.nsteps * 1024 + (int64_t)D.d.cin * 22;
+    const int64_t mem = bytes / std::min<int64_t>(DW_HBM_BYTES_PER_CYCLE, (int64_t)budget * DW_CU_BYTES_PER_CYCLE);
+    return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
+}
+
 // force_tc / pw_mode: explicit values for the two testing hooks (null / -1: the process-wide ones)
 // Fully connected layer: one workgroup per 32 output channels streaming all of K, or, where that is
 // cheaper, pairs of channel blocks with K split 2, 4 or 8 ways (at most 256 workgroups), a second
@@ -930,6 +1045,41 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
                           : shape == 4 ? DLF_PWB_LDS_BYTES(1, 4)
                                        : DLF_PW_WAVES * 32 * PW_FP[shape] * (32 * PW_FC[shape] + 8) * 2;
             if (L0.d.residual_from >= 0) { g.res_layer = L0.d.residual_from; g.res_stage = 0; }
+            return DLF_OK;
+        }
+    }
+    if (g_dw_mode != 2 && (force.th <= 0 || g_dw_mode == 1) && dwpw_eligible(net, first, last, batch)) {
+        const Layer& P = net.L[last];
+        int nb = 4;
+        uint64_t dc = dwpw_cost_ps(L0, P, batch, budget, 4);
+        const uint64_t dc2 = dwpw_cost_ps(L0, P, batch, budget, 2);
+        if (dc2 < dc || P.ncb <= 2) { nb = 2; dc = dc2; }
+        if (!tiled || g_dw_mode == 1 || dc < cost) {
+            dwpw_fill(L0, P, batch, nb, g.dp);
+            g.kind = GK_DWPW;
+            g.cost = dc;
+            g.variant = nb;
+            g.occ = 2;
+            g.grid = std::min(budget * g.occ, ceil_div(g.dp.nitems, DLF_DWPW_WAVES));
+            g.th = 1; g.tw = 32;
+            g.lds_bytes = DLF_DWPW_LDS_BYTES(L0.d.cin, nb);
+            return DLF_OK;
+        }
+    }
+    if (first == last && g_dw_mode != 2 && (force.th <= 0 || g_dw_mode == 1) && dw_eligible(L0, batch)) {
+        DlfDwArgs da;
+        dw_fill(L0, batch, da);
+        const uint64_t dc = dw_cost_ps(L0, batch, budget, da);
+        if (!tiled || g_dw_mode == 1 || dc < cost) {
+            g.da = da;
+            g.kind = GK_DW;
+            g.cost = dc;
+            g.variant = L0.d.stride - 1;
+            g.occ = DW_WAVES_PER_CU / DLF_DW_WAVES;
+            g.grid = std::min(budget * g.occ, ceil_div(da.nitems, DLF_DW_WAVES));
+            g.th = L0.d.stride == 1 ? DLF_DW_ROWS1 : DLF_DW_ROWS2;
+            g.tw = 64;
+            g.lds_bytes = 0;
             return DLF_OK;
         }
     }
@@ -1497,6 +1647,8 @@ dlf_status dlf_plan_group_io(const dlf_plan_t* plan, int32_t g, int32_t* in_laye
 
 void dlf_debug_pointwise_mode(int32_t mode) { g_pw_mode = (mode >= 0 && mode <= 7) ? mode : 0; }
 
+void dlf_debug_depthwise_mode(int32_t mode) { g_dw_mode = (mode >= 0 && mode <= 2) ? mode : 0; }
+
 void dlf_debug_block3x3_mode(int32_t mode, int32_t shape, int32_t th, int32_t tw)
 {
     g_c3_force = C3Force{(mode >= 0 && mode <= 2) ? mode : 0, shape, th, tw};
@@ -1560,6 +1712,14 @@ static dlf_status launch_one(const dlf_plan_s* plan, const GroupPlan& G, const v
             wa.res = res;
         }
         e = dlf_launch_pw(&wa, G.variant, G.grid, stream);
+    } else if (G.kind == GK_DW) {
+        DlfDwArgs da = G.da;
+        da.in = in; da.out = out;
+        e = dlf_launch_dw(&da, G.grid, stream);
+    } else if (G.kind == GK_DWPW) {
+        DlfDwPwArgs dp = G.dp;
+        dp.in = in; dp.out = out;
+        e = dlf_launch_dwpw(&dp, G.variant, G.grid, stream);
     } else if (G.kind == GK_C3) {
         DlfC3Args ca = G.ca;
         ca.in = in; ca.out = out;

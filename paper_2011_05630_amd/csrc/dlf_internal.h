@@ -142,6 +142,47 @@ struct DlfC3Args {
     int32_t nst;          // stages in the weight ring (2 .. 4)
 };
 
+// Depthwise 3x3 convolution (pad 1, stride 1 or 2) as a streaming kernel without LDS or barriers:
+// a wave owns 64 consecutive 16-byte vectors (8 channels each) of the output rows of a strip and
+// walks down the strip with a sliding window of input rows in registers.
+#define DLF_DW_WAVES 4               // waves per workgroup
+#define DLF_DW_ROWS1 14              // output rows per strip, stride 1
+#define DLF_DW_ROWS2 7               // output rows per strip, stride 2
+struct DlfDwArgs {
+    const void* in;       // [batch][h][w][c] fp16
+    void* out;            // [batch][oh][ow][c] fp16
+    const void* w;        // [9][cpad] fp16 (tap-major)
+    const float* bias;    // [cpad]
+    uint32_t in_bytes;    // size of the input tensor (below 2 GiB)
+    int32_t batch, h, w_, c, cpad, oh, ow, stride, act;
+    int32_t cg;           // c / 8: 16-byte vectors per pixel
+    int32_t rowv;         // ow * cg: vectors per output row
+    int32_t nxr;          // ceil(rowv / 64): runs of 64 vectors per output row
+    int32_t nstrips;      // ceil(oh / rows per strip)
+    int32_t nitems;       // batch * nstrips * nxr
+};
+
+// Depthwise 3x3 (pad 1, stride 1 or 2) followed by a 1x1 convolution, fused without a tile pipeline:
+// a wave owns work items of 32 output pixels x 32 * NB output channels; per 16-channel K step every
+// lane computes the depthwise result of its pixel and 8 channels in registers -- which is the MFMA
+// "B" operand as it stands -- and the wave multiplies it with NB packed weight fragments.
+#define DLF_DWPW_WAVES 4
+#define DLF_DWPW_LDS_BYTES(C, NB) (22 * (C) + DLF_DWPW_WAVES * 32 * (32 * (NB) + 8) * 2)
+struct DlfDwPwArgs {
+    const void* in;       // [batch][h][w][c] fp16
+    void* out;            // [batch][oh][ow][cout] fp16
+    const void* wdw;      // depthwise weights [9][c] fp16 (tap-major)
+    const float* bdw;     // depthwise bias [c]
+    const void* wpw;      // pointwise weights, packed fragments
+    const float* bpw;     // pointwise bias, padded to ncb * 32
+    uint32_t in_bytes;    // size of the input tensor (below 2 GiB)
+    int32_t batch, h, w_, c, oh, ow, stride, act_dw, act_pw;
+    int32_t cout, ncb, nsteps;
+    int32_t m;            // output pixels = batch * oh * ow
+    int32_t n_pg, n_cg;   // groups of 32 pixels, groups of 32 * NB output channels
+    int32_t nitems;       // n_pg * n_cg (channel group fastest)
+};
+
 struct DlfGapArgs {
     const void* x;        // [batch][hw][c]
     void* y;              // [batch][c]
@@ -160,6 +201,8 @@ int dlf_launch_fc(const DlfFcArgs* a, void* stream);
 int dlf_launch_gap(const DlfGapArgs* a, void* stream);
 int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stream);
 int dlf_launch_c3(const DlfC3Args* a, int shape, int grid, int lds_bytes, void* stream);
+int dlf_launch_dw(const DlfDwArgs* a, int grid, void* stream);
+int dlf_launch_dwpw(const DlfDwPwArgs* a, int nb, int grid, void* stream);
 int dlf_kernels_init(void);
 // Attaches a start / stop event pair (hipEvent_t, either may be null) to this thread's next launch.
 void dlf_next_launch_events(void* start, void* stop);

@@ -1905,6 +1905,262 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
     }
 }
 
+// ---- buffer loads: a tensor behind a buffer resource, so that the hardware's range check turns the
+// loads of padding positions into zeros (an offset beyond the tensor returns 0: no branch, no
+// select).  Offsets are bytes; DLF_OOB is an offset no tensor reaches (the host keeps tensors
+// below 2 GiB on these paths).
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ i32x4 raw_buffer_load_x4(i32x4 rsrc, int voffset, int soffset, int aux) __asm("llvm.amdgcn.raw.buffer.load.v4i32");
+#define DLF_OOB ((int)0x80000000)
+__device__ __forceinline__ i32x4 make_rsrc(const void* p, unsigned bytes)
+{
+    const unsigned long long a = (unsigned long long)p;
+    i32x4 r;
+    r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
+    r.y = __builtin_amdgcn_readfirstlane((int)((unsigned)(a >> 32) & 0xffffu));   // stride 0: raw buffer
+    r.z = __builtin_amdgcn_readfirstlane((int)bytes);                              // bytes that may be read
+    r.w = 0x00020000;                                                              // 32-bit raw data
+    return r;
+}
+
+// Mixed-precision multiply-add on one half of two packed fp16 pairs: c + a.lo * b.lo / c + a.hi * b.hi
+// in fp32.  Written out because the compiler, given (float)a * (float)b + c in a loop that reuses b,
+// converts b to fp32 once and keeps it there: twice the registers and a conversion per operand.
+__device__ __forceinline__ float fma_mix_lo(unsigned a, unsigned b, float c)
+{
+    float d;
+    asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[1,1,0]" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+__device__ __forceinline__ float fma_mix_hi(unsigned a, unsigned b, float c)
+{
+    float d;
+    asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,1,0] op_sel_hi:[1,1,0]" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+// v[0..7] += x[0..7] * w[0..7] (8 channels of one filter tap)
+__device__ __forceinline__ void dw_tap(float (&v)[8], const u4v& x, const u4v& w)
+{
+    v[0] = fma_mix_lo(x.x, w.x, v[0]);
+    v[1] = fma_mix_hi(x.x, w.x, v[1]);
+    v[2] = fma_mix_lo(x.y, w.y, v[2]);
+    v[3] = fma_mix_hi(x.y, w.y, v[3]);
+    v[4] = fma_mix_lo(x.z, w.z, v[4]);
+    v[5] = fma_mix_hi(x.z, w.z, v[5]);
+    v[6] = fma_mix_lo(x.w, w.w, v[6]);
+    v[7] = fma_mix_hi(x.w, w.w, v[7]);
+}
+
+// Depthwise 3x3 convolution, pad 1, stride S, + bias + activation: the layer the paper's evaluation
+// shows to be bound by memory, not arithmetic (Sec. V: layers of low operation count).  No LDS, no
+// barrier: a wave owns 64 consecutive 16-byte vectors of the output rows of a strip (a run of
+// (pixel, 8 channels) pairs, contiguous in NHWC) and walks down the strip.  Each lane keeps a window
+// of input rows in registers -- the three columns x-1, x, x+1 of its 8 channels -- so every input
+// vector is requested once per lane that needs it (three per row instead of nine per output), the
+// rows one iteration ahead of their use; the 9 weight vectors and the bias of the lane's channels
+// stay in registers for the whole strip.  Multiply-adds are mixed precision (fp16 operands, fp32
+// sum).  Loads and stores are whole 1 KiB runs per wave.
+template <int S>
+__global__ __launch_bounds__(DLF_DW_WAVES * 64, 4) void k_dw(const DlfDwArgs a)
+{
+    constexpr int ROWS = S == 1 ? DLF_DW_ROWS1 : DLF_DW_ROWS2;
+    constexpr int RING = S == 1 ? 4 : 5;                  // input rows in registers
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const i32x4 rin = make_rsrc(a.in, a.in_bytes);
+    const unsigned cg_m = div_magic(a.cg);
+    const half_t* wdw = (const half_t*)a.w;
+    half_t* outp = (half_t*)a.out;
+    const unsigned lo = act_lo(a.act), hi = act_hi(a.act);
+    const int rowbytes = a.w_ * a.c * 2;
+    const int nwaves = gridDim.x * DLF_DW_WAVES;
+    for (int item = blockIdx.x * DLF_DW_WAVES + wave; item < a.nitems; item += nwaves) {
+        int t = item;
+        const int xr = t % a.nxr;
+        t /= a.nxr;
+        const int strip = t % a.nstrips, n = t / a.nstrips;
+        const int e = xr * 64 + lane;
+        const bool lv = e < a.rowv;
+        const int ec = lv ? e : 0;
+        const int ox = div_by(ec, cg_m), g = ec - ox * a.cg;
+        u4v w[9];
+#pragma unroll
+        for (int k = 0; k < 9; ++k) w[k] = *(const u4v*)(wdw + k * a.cpad + g * 8);
+        const f4v b0 = *(const f4v*)(a.bias + g * 8), b1 = *(const f4v*)(a.bias + g * 8 + 4);
+        int voff[3];
+#pragma unroll
+        for (int d = 0; d < 3; ++d) {
+            const int ix = ox * S - 1 + d;
+            voff[d] = (lv && ix >= 0 && ix < a.w_) ? (ix * a.cg + g) * 16 : DLF_OOB;
+        }
+        const int oy0 = strip * ROWS;
+        const int iy0 = oy0 * S - 1;                       // input row of window slot 0
+        u4v win[RING][3];
+        auto load_row = [&](int k) __attribute__((always_inline)) {
+            const int iy = iy0 + k;
+            const bool rok = iy >= 0 && iy < a.h;          // uniform; a row of padding reads zeros
+            const int so = rok ? (n * a.h + iy) * rowbytes : 0;
+#pragma unroll
+            for (int d = 0; d < 3; ++d)
+                win[k % RING][d] = __builtin_bit_cast(u4v, raw_buffer_load_x4(rin, rok ? voff[d] : DLF_OOB, so, 0));
+        };
+#pragma unroll
+        for (int k = 0; k < RING - 1; ++k) load_row(k);
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            const int oy = oy0 + r;
+            if (oy >= a.oh) break;
+            // the rows of the next output row are requested before this one is computed
+#pragma unroll
+            for (int k = r * S + RING - S; k < r * S + RING; ++k) load_row(k);
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { v[j] = b0[j]; v[j + 4] = b1[j]; }
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) dw_tap(v, win[(r * S + kh) % RING][kw], w[kh * 3 + kw]);
+            u4v hv;
+            hv.x = pk_min(pk_max(cvt_pk(v[0], v[1]), lo), hi);
+            hv.y = pk_min(pk_max(cvt_pk(v[2], v[3]), lo), hi);
+            hv.z = pk_min(pk_max(cvt_pk(v[4], v[5]), lo), hi);
+            hv.w = pk_min(pk_max(cvt_pk(v[6], v[7]), lo), hi);
+            if (lv) *(u4v*)(outp + ((size_t)((n * a.oh + oy) * a.rowv + e) << 3)) = hv;
+        }
+    }
+}
+
+// Depthwise 3x3 + 1x1 convolution fused (the pair MobileNet-style networks are made of: the
+// depthwise layer has nine multiply-adds per value it reads and writes, so run alone it is pure
+// memory traffic, and its output is read again at once by the 1x1 layer; Sec. V: layers of low
+// operation count gain most from fusion).  The depthwise output never exists in memory: lane
+// (pixel l % 32, K half l / 32) of a wave computes, for each 16-channel K step, the depthwise
+// result of its pixel and its 8 channels from nine 16-byte loads (range-checked buffer loads:
+// padding positions read zero), applies bias and activation, rounds to fp16 -- and holds exactly
+// the MFMA "B" fragment of that K step, which is multiplied at once with the NB weight fragments
+// (32 output channels each) of the wave's channel group.  No LDS between the two layers, no
+// workgroup barrier in the loop; the loads of K step k + 1 are in flight while step k is computed.
+// The depthwise weights and bias sit in LDS (read once per workgroup), the 1x1 fragments stream
+// from L2 as in k_pw.  Waves of a workgroup take consecutive items, channel group fastest, so the
+// channel groups of one pixel group find their inputs in the CU's cache.
+template <int NB>
+__global__ __launch_bounds__(DLF_DWPW_WAVES * 64, 2) void k_dwpw(const DlfDwPwArgs a)
+{
+    constexpr int ROW = 32 * NB + 8;                 // halfs per pixel row of the transpose buffer
+    constexpr int LPP = 4 * NB;                      // lanes (16-byte vectors) per pixel
+    constexpr int NPASS = 2 * NB;                    // read-back passes of 64 vectors
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
+    const int c = a.c;
+    half_t* wl = lds;                                // [9][c] fp16
+    float* bl = (float*)(lds + 9 * c);               // [c] fp32
+    half_t* tb = lds + 11 * c + wave * (32 * ROW);
+    for (int i = threadIdx.x; i < (9 * c) >> 3; i += DLF_DWPW_WAVES * 64) ((u4v*)wl)[i] = ((const u4v*)a.wdw)[i];
+    for (int i = threadIdx.x; i < c >> 2; i += DLF_DWPW_WAVES * 64) ((f4v*)bl)[i] = ((const f4v*)a.bdw)[i];
+    __syncthreads();
+    const i32x4 rin = make_rsrc(a.in, a.in_bytes);
+    half_t* outp = (half_t*)a.out;
+    const unsigned lo_d = act_lo(a.act_dw), hi_d = act_hi(a.act_dw);
+    const unsigned lo_p = act_lo(a.act_pw), hi_p = act_hi(a.act_pw);
+    const int nsteps = a.nsteps;                     // even: c is a multiple of 32
+    const int ohw = a.oh * a.ow;
+    const unsigned ohw_m = div_magic(ohw), ow_m = div_magic(a.ow), ncg_m = div_magic(a.n_cg);
+    const int nwaves = gridDim.x * DLF_DWPW_WAVES;
+    for (int item = blockIdx.x * DLF_DWPW_WAVES + wave; item < a.nitems; item += nwaves) {
+        const int pg = div_by(item, ncg_m), cg = item - pg * a.n_cg;
+        int pix = pg * 32 + l32;
+        pix = pix < a.m ? pix : a.m - 1;             // clamped lanes compute a result nobody stores
+        const int n = div_by(pix, ohw_m), r = pix - n * ohw;
+        const int oy = div_by(r, ow_m), ox = r - oy * a.ow;
+        // byte offsets of the nine taps' 16 bytes (K step 0), or out of range for padding
+        int voff[9];
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) {
+                const int iy = oy * a.stride - 1 + kh, ix = ox * a.stride - 1 + kw;
+                const bool ok = iy >= 0 && iy < a.h && ix >= 0 && ix < a.w_;
+                voff[kh * 3 + kw] = ok ? (((n * a.h + iy) * a.w_ + ix) * c + lhi * 8) * 2 : DLF_OOB;
+            }
+        const h8* wp[NB];
+#pragma unroll
+        for (int f = 0; f < NB; ++f) {
+            const int cb = min(cg * NB + f, a.ncb - 1);
+            wp[f] = (const h8*)a.wpw + (size_t)cb * nsteps * 64 + lane;
+        }
+        f16v acc[NB];
+#pragma unroll
+        for (int f = 0; f < NB; ++f)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[f][q] = 0.0f;
+        u4v x[2][9];
+        h8 ar[2][NB];
+        // K step ks: inputs and weight fragments of step ks + 1 are requested first (the last step
+        // requests a step that does not exist: the loads land in the next pixel's channels or
+        // beyond the tensor, where the range check returns zero, and in the zero steps behind the
+        // packed weights; nothing uses them)
+        auto request = [&](int ks, u4v (&xn)[9], h8 (&an)[NB]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int k = 0; k < 9; ++k)
+                xn[k] = __builtin_bit_cast(u4v, raw_buffer_load_x4(rin, voff[k], ks * 32, 0));
+#pragma unroll
+            for (int f = 0; f < NB; ++f) an[f] = wp[f][ks * 64];
+        };
+        auto step = [&](int ks, const u4v (&xc)[9], u4v (&xn)[9], const h8 (&ac)[NB], h8 (&an)[NB])
+                        __attribute__((always_inline)) {
+            request(ks + 1, xn, an);
+            __builtin_amdgcn_sched_barrier(0);       // all of them before the arithmetic, not sunk into it
+            const int ch = ks * 16 + lhi * 8;
+            const f4v b0 = *(const f4v*)(bl + ch), b1 = *(const f4v*)(bl + ch + 4);
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { v[j] = b0[j]; v[j + 4] = b1[j]; }
+#pragma unroll
+            for (int k = 0; k < 9; ++k) dw_tap(v, xc[k], *(const u4v*)(wl + k * c + ch));
+            u4v hv;
+            hv.x = pk_min(pk_max(cvt_pk(v[0], v[1]), lo_d), hi_d);
+            hv.y = pk_min(pk_max(cvt_pk(v[2], v[3]), lo_d), hi_d);
+            hv.z = pk_min(pk_max(cvt_pk(v[4], v[5]), lo_d), hi_d);
+            hv.w = pk_min(pk_max(cvt_pk(v[6], v[7]), lo_d), hi_d);
+            const h8 b = __builtin_bit_cast(h8, hv);
+#pragma unroll
+            for (int f = 0; f < NB; ++f) acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ac[f], b, acc[f], 0, 0, 0);
+        };
+        request(0, x[0], ar[0]);
+        for (int ks = 0; ks < nsteps; ks += 2) {
+            step(ks, x[0], x[1], ar[0], ar[1]);
+            step(ks + 1, x[1], x[0], ar[1], ar[0]);
+        }
+        // ---- result + bias -> activation -> wave-private transpose buffer [pixel][channel] ----
+#pragma unroll
+        for (int f = 0; f < NB; ++f) {
+            const int cb = min(cg * NB + f, a.ncb - 1);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f4v bv = *(const f4v*)(a.bpw + cb * 32 + q * 8 + lhi * 4);
+                unsigned u0 = cvt_pk(acc[f][q * 4 + 0] + bv[0], acc[f][q * 4 + 1] + bv[1]);
+                unsigned u1 = cvt_pk(acc[f][q * 4 + 2] + bv[2], acc[f][q * 4 + 3] + bv[3]);
+                u0 = pk_min(pk_max(u0, lo_p), hi_p);
+                u1 = pk_min(pk_max(u1, lo_p), hi_p);
+                const u2v uu = {u0, u1};
+                *(u2v*)(tb + l32 * ROW + f * 32 + q * 8 + lhi * 4) = uu;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        // ---- 16 bytes per lane: LPP lanes cover the 32 * NB channels of one pixel ----
+        const int part = lane % LPP;
+        const int cc = cg * (32 * NB) + part * 8;
+#pragma unroll
+        for (int i = 0; i < NPASS; ++i) {
+            const int px = i * (64 / LPP) + lane / LPP;
+            const int gpix = pg * 32 + px;
+            if (gpix < a.m && cc < a.cout)
+                *(u4v*)(outp + (size_t)gpix * a.cout + cc) = *(const u4v*)(tb + px * ROW + part * 8);
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+extern "C" int dlf_launch_dw(const DlfDwArgs* a, int grid, void* stream);
+
 // Fully connected layer (Eq. 2 with M = batch): y[n][co] = act(bias[co] + sum_k x[n][k] w[co][k]).
 // One workgroup per 32 output channels; its 8 waves split K, each streaming a contiguous share
 // of the packed weight fragments from HBM exactly once; partial sums meet in LDS.
@@ -2218,6 +2474,31 @@ extern "C" int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stre
     else if (shape == 4)
         launch(k_pwb<1, 4>, dim3(grid), dim3(DLF_PW_WAVES * 64), (size_t)DLF_PWB_LDS_BYTES(1, 4),
                (hipStream_t)stream, *a);
+    else
+        return (int)hipErrorInvalidValue;
+    return (int)hipGetLastError();
+}
+
+extern "C" int dlf_launch_dw(const DlfDwArgs* a, int grid, void* stream)
+{
+    if (grid <= 0 || (a->stride != 1 && a->stride != 2) || a->in_bytes >= 0x80000000u || (a->c & 7) != 0)
+        return (int)hipErrorInvalidValue;
+    if (a->stride == 1)
+        launch(k_dw<1>, dim3(grid), dim3(DLF_DW_WAVES * 64), 0, (hipStream_t)stream, *a);
+    else
+        launch(k_dw<2>, dim3(grid), dim3(DLF_DW_WAVES * 64), 0, (hipStream_t)stream, *a);
+    return (int)hipGetLastError();
+}
+
+extern "C" int dlf_launch_dwpw(const DlfDwPwArgs* a, int nb, int grid, void* stream)
+{
+    if (grid <= 0 || (a->stride != 1 && a->stride != 2) || a->in_bytes >= 0x80000000u || (a->c & 31) != 0 ||
+        a->nsteps != a->c / 16 || (a->cout & 7) != 0)
+        return (int)hipErrorInvalidValue;
+    if (nb == 2)
+        launch(k_dwpw<2>, dim3(grid), dim3(DLF_DWPW_WAVES * 64), (size_t)DLF_DWPW_LDS_BYTES(a->c, 2), (hipStream_t)stream, *a);
+    else if (nb == 4)
+        launch(k_dwpw<4>, dim3(grid), dim3(DLF_DWPW_WAVES * 64), (size_t)DLF_DWPW_LDS_BYTES(a->c, 4), (hipStream_t)stream, *a);
     else
         return (int)hipErrorInvalidValue;
     return (int)hipGetLastError();

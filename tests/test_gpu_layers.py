@@ -282,6 +282,90 @@ def test_depthwise(stride, c, hw):
     compare(got, ref, "dw s%d c%d" % (stride, c))
 
 
+def _run_dw_mode(net, batch, mode, seed=1, **plan):
+    """_run with the planner's choice between the fused-group kernel and the streaming depthwise
+    kernels fixed (1 = streaming wherever it applies, 2 = never)."""
+    from paper_2011_05630_amd import binding as B
+    B.dlf_debug_depthwise_mode(mode)
+    try:
+        return _run(net, batch, seed=seed, **plan)
+    finally:
+        B.dlf_debug_depthwise_mode(0)
+
+
+# (stride, channels, height, width, batch, activation): maps of one strip and of several with a ragged
+# last one, widths whose rows are not whole runs of 64 vectors, 8 to 1024 channels (one to 128 vectors
+# per pixel), odd and even sizes under stride 2, one-pixel-wide and one-row maps
+DW_CASES = [(1, 32, 20, 21, 2, "relu6"), (2, 64, 21, 22, 2, "relu6"), (1, 128, 9, 10, 2, "relu6"),
+            (2, 8, 12, 13, 2, "none"), (1, 8, 31, 5, 3, "relu"), (1, 24, 30, 17, 1, "relu6"),
+            (2, 40, 29, 30, 2, "relu6"), (1, 512, 14, 14, 3, "relu6"), (2, 512, 14, 14, 2, "relu6"),
+            (1, 1024, 7, 7, 2, "relu6"), (1, 16, 1, 9, 2, "none"), (1, 16, 9, 1, 2, "relu"),
+            (2, 16, 2, 2, 1, "relu"), (1, 64, 57, 56, 1, "relu6"), (2, 32, 112, 112, 1, "relu6")]
+
+
+@pytest.mark.parametrize("stride,c,h,w,batch,act", DW_CASES)
+def test_depthwise_streaming_kernel(stride, c, h, w, batch, act):
+    from paper_2011_05630_amd import binding as B
+    announce("depthwise streaming", stride, c, h, w, batch, act)
+    net = _mk([nets.dwconv(c, 3, stride, act)], h, w, c, dist="normal")
+    B.dlf_debug_depthwise_mode(1)
+    try:
+        from paper_2011_05630_amd.runner import Session
+        from oracle import oracle as o
+        x, ws, bs = gen.make_params(net, batch, 7)
+        s = Session(net, batch, ws, bs)
+    finally:
+        B.dlf_debug_depthwise_mode(0)
+    try:
+        cfg = B.dlf_plan_group_config(s.plan, 0)
+        assert cfg["kind"] == 5 and cfg["variant"] == stride - 1, cfg
+        got = s.run_numpy(x)
+    finally:
+        s.close()
+    compare(got, o.run_net(net, x, ws, bs), "dw stream s%d c%d %dx%d" % (stride, c, h, w))
+
+
+def test_depthwise_streaming_kernel_equals_fused_group_kernel():
+    """The two kernels accumulate the nine taps in the same order in fp32 and round once: same bits."""
+    net = _mk([nets.dwconv(64, 3, 1, "relu6")], 33, 29, 64, dist="normal")
+    a, ref, _ = _run_dw_mode(net, 2, 1)
+    b, _, _ = _run_dw_mode(net, 2, 2)
+    compare(a, ref, "dw streaming")
+    compare(b, ref, "dw in the fused-group kernel")
+    assert np.array_equal(a, b)
+
+
+# (stride, channels in, channels out, height, width, batch): 2 or 4 channel blocks per work item and
+# several channel groups, a ragged last pixel group, maps narrower than a pixel group (rows wrap
+# inside a group), images that end inside a group, one pixel
+DWPW_CASES = [(1, 32, 64, 28, 28, 2), (2, 64, 128, 21, 23, 2), (1, 128, 128, 9, 10, 3), (2, 128, 256, 14, 14, 2),
+              (1, 256, 512, 7, 7, 3), (1, 512, 512, 14, 14, 2), (1, 32, 24, 13, 5, 1), (1, 64, 200, 6, 9, 2),
+              (2, 32, 64, 1, 1, 3), (1, 1024, 1024, 7, 7, 1), (2, 32, 64, 112, 112, 1)]
+
+
+@pytest.mark.parametrize("stride,c,cout,h,w,batch", DWPW_CASES)
+def test_depthwise_pointwise_fused_kernel(stride, c, cout, h, w, batch):
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    from oracle import oracle as o
+    announce("dw+pw fused kernel", stride, c, cout, h, w, batch)
+    layers = [nets.dwconv(c, 3, stride, "relu6"), nets.conv(c, cout, 1, 1, 0, "relu6" if cout != 24 else "none")]
+    net = _mk(layers, h, w, c, dist="normal")
+    x, ws, bs = gen.make_params(net, batch, 9)
+    B.dlf_debug_depthwise_mode(1)
+    try:
+        s = Session(net, batch, ws, bs, **_manual(2, [1]))
+    finally:
+        B.dlf_debug_depthwise_mode(0)
+    try:
+        cfg = B.dlf_plan_group_config(s.plan, 0)
+        assert len(s.groups) == 1 and cfg["kind"] == 6 and cfg["variant"] in (2, 4), cfg
+        got = s.run_numpy(x)
+    finally:
+        s.close()
+    compare(got, o.run_net(net, x, ws, bs), "dw+pw s%d %d->%d %dx%d" % (stride, c, cout, h, w))
+
+
 def test_depthwise_channel_slices():
     announce("depthwise slices")
     net = _mk([nets.dwconv(128, 3, 1, "relu6")], 14, 14, 128, dist="normal")

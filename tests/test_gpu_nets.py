@@ -168,7 +168,7 @@ def test_config5_mobilenet_batch1():
 
 def test_config5_mobilenet_batch64_sampled():
     net = nets.mobilenet_v1()
-    _net_case(net, 64, [0, 33, 63], True, _plans(net)[:1], expect_kinds=[("pw", None)])
+    _net_case(net, 64, [0, 33, 63], True, _plans(net)[:1], expect_kinds=[("pw", None), ("dw", 0), ("dw", 1)])
 
 
 def test_other_evaluated_networks_small_batch():
