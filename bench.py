@@ -119,6 +119,8 @@ def group_accounting(net, batch, session):
             kname = DW_NAME[cfg["variant"]]
         elif cfg["kind"] == 6:
             kname = "k_dwpw<%d>" % cfg["variant"]
+        elif cfg["kind"] == 7:
+            kname = "k_dwt<%d>" % (cfg["variant"] + 1)
         else:
             kname = VARIANT_NAME[cfg["variant"]]
         out.append(dict(first=f, last=l, budget=info["budget"], flops=flops, bytes=byts,

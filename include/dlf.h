@@ -184,7 +184,9 @@ const void* dlf_plan_layer_output(const dlf_plan_t* plan, int32_t layer);
  * 64 x 512, odd: activations 64 input channels at a time, even: 32; 4 = 128 x 512), 5 streaming
  * depthwise kernel: a single depthwise 3x3 layer (variant = stride - 1), 6 fused depthwise 3x3 +
  * 1x1 kernel: a depthwise layer and the pointwise layer behind it, the depthwise result held in
- * registers (variant = 32-channel blocks of a wave's work item, 2 or 4); channel slices, channels
+ * registers (variant = 32-channel blocks of a wave's work item, 2 or 4), 7 depthwise + 1x1 tile
+ * kernel: the same pair, the depthwise result of a pixel tile held in LDS (variant = stride - 1);
+ * channel slices, channels
  * per slice, whether stage 0 streams its input, LDS bytes per workgroup.  Any out pointer may be
  * NULL. */
 dlf_status dlf_plan_group_config(const dlf_plan_t* plan, int32_t g, int32_t* kind, int32_t* variant,
@@ -228,9 +230,15 @@ void dlf_debug_pointwise_mode(int32_t mode);
 
 /* Testing hook: how a single depthwise 3x3 layer (pad 1, stride 1 or 2), or such a layer with the 1x1
  * convolution behind it, chooses between the fused-group kernel and the streaming depthwise kernel /
- * the fused depthwise + 1x1 kernel: 0 = by modelled cost (default), 1 = the depthwise kernels
- * wherever they apply, 2 = never.  Process-wide, not thread-safe. */
+ * the depthwise + 1x1 kernels: 0 = by modelled cost (default), 1 = the depthwise kernels wherever
+ * they apply (a pair: the tile kernel where its shape restrictions allow, else the register kernel),
+ * 2 = never, 3 = as 1 but a pair always on the register kernel.  Process-wide, not thread-safe. */
 void dlf_debug_depthwise_mode(int32_t mode);
+/* Testing hook: wx > 0 fixes the tile of the depthwise + 1x1 tile kernel for groups planned afterwards:
+ * wx (1, 2 or 4) of its four waves side by side, each 512 / (2 * channels) pixels wide, rw output rows
+ * per wave (a shape that does not fit falls back to the other kernels); wx = 0 restores the automatic
+ * choice.  Process-wide, not thread-safe. */
+void dlf_debug_depthwise_tile(int32_t wx, int32_t rw);
 
 /* Testing hook: how a single 3x3 stride-1 pad-1 convolution (with the 2x2 max pool folded behind
  * it, if any) chooses between the fused-group kernel and the block 3x3 kernel: mode 0 = by

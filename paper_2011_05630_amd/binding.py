@@ -112,6 +112,8 @@ def lib():
     L.dlf_debug_pointwise_mode.restype = None
     L.dlf_debug_depthwise_mode.argtypes = [i32]
     L.dlf_debug_depthwise_mode.restype = None
+    L.dlf_debug_depthwise_tile.argtypes = [i32, i32]
+    L.dlf_debug_depthwise_tile.restype = None
     L.dlf_debug_block3x3_mode.argtypes = [i32, i32, i32, i32]
     L.dlf_debug_block3x3_mode.restype = None
     L.dlf_plan_set_overlap.argtypes = [vp, i32]
@@ -310,9 +312,15 @@ def dlf_debug_force_ksplit(ksplit=1):
 
 
 def dlf_debug_depthwise_mode(mode=0):
-    """Testing hook: 0 = streaming depthwise kernel chosen by modelled cost, 1 = wherever it applies,
-    2 = never."""
+    """Testing hook: 0 = depthwise kernels chosen by modelled cost, 1 = wherever they apply, 2 = never,
+    3 = wherever they apply, a depthwise + 1x1 pair always on the register kernel."""
     lib().dlf_debug_depthwise_mode(mode)
+
+
+def dlf_debug_depthwise_tile(wx=0, rw=0):
+    """Testing hook: wx > 0 fixes the tile of the depthwise + 1x1 tile kernel (wx waves side by side, rw
+    rows per wave); 0 restores the automatic choice."""
+    lib().dlf_debug_depthwise_tile(wx, rw)
 
 
 def dlf_debug_pointwise_mode(mode=0):

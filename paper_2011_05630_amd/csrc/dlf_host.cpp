@@ -153,7 +153,7 @@ dlf_status pack_and_upload(Layer& L)
 // Fusion groups
 // ------------------------------------------------------------------------------------------
 
-enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3, GK_C3 = 4, GK_DW = 5, GK_DWPW = 6 };
+enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3, GK_C3 = 4, GK_DW = 5, GK_DWPW = 6, GK_DWT = 7 };
 
 struct TileCfg {
     int th, tw;      // tile of the group's final output tensor
@@ -181,6 +181,7 @@ struct GroupPlan {
     DlfC3Args ca;
     DlfDwArgs da;
     DlfDwPwArgs dp;
+    DlfDwtArgs dt;
 };
 
 const int VAR_FC[DLF_NUM_VARIANTS] = {2, 1, 1, 1};
@@ -261,6 +262,18 @@ const int DW_WAVES_PER_CU = 16;
 const int64_t C_DWPW_ITEM = 4000;
 const int64_t C_DWPW_STEP = 470;
 const int64_t C_DWPW_LOAD = 62;
+
+// depthwise + 1x1 tile kernel: per tile (decode, barriers, first rows of the window in flight), per
+// output row of the depthwise phase, per work unit of the 1x1 phase (first fragments, epilogue
+// set-up), per K step and 32-pixel block of a unit (at least two blocks' worth: below that the
+// operand reads, not the MFMAs, set the pace), per 32-pixel block of a unit's epilogue.  Fitted to
+// the eight depthwise / 1x1 pairs of MobileNet-v1 at batch 64, every tile shape forced in turn; the
+// workgroups that share a CU (two: registers) split its time.
+const int64_t C_DWT_TILE = 6000;
+const int64_t C_DWT_ROW = 630;
+const int64_t C_DWT_UNIT = 2250;
+const int64_t C_DWT_STEP = 48;
+const int64_t C_DWT_EPI = 750;
 
 struct StageSpec {   // one stage, before tiling
     int layer;
@@ -945,6 +958,86 @@ uint64_t dwpw_cost_ps(const Layer& D, const Layer& P, int batch, int budget, int
     return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
 }
 
+// ---- depthwise + 1x1 tile kernel ----
+
+bool dwt_eligible(const dlf_net_s& net, int first, int last, int batch)
+{
+    if (!dwpw_eligible(net, first, last, batch)) return false;
+    const int cg = net.L[first].d.cin / 8;
+    return cg >= 4 && cg <= 64 && (cg & (cg - 1)) == 0;
+}
+
+// One tile shape: wx x wy waves, rw rows per wave.
+bool dwt_build(const Layer& D, const Layer& P, int batch, int wx, int rw, int max_lds, DlfDwtArgs& dt)
+{
+    memset(&dt, 0, sizeof dt);
+    dt.cg = D.d.cin / 8;
+    dt.pxw = 64 / dt.cg;
+    dt.wx = wx; dt.wy = DLF_DWT_WAVES / wx; dt.rw = rw;
+    dt.th = dt.wy * rw; dt.tw = wx * dt.pxw;
+    dt.tp = dt.th * dt.tw;
+    if (dt.tp > 256 || rw < 1) return false;
+    if ((int)DLF_DWT_LDS_BYTES(dt.tp, D.d.cin) > max_lds) return false;
+    dt.npb = ceil_div(dt.tp, 32);
+    dt.npg = ceil_div(dt.npb, 4);
+    dt.wdw = D.d_w; dt.bdw = D.d_bias; dt.wpw = P.d_w; dt.bpw = P.d_bias;
+    dt.in_bytes = (uint32_t)((int64_t)batch * D.in_h * D.in_w * D.in_c * 2);
+    dt.batch = batch; dt.h = D.in_h; dt.w_ = D.in_w; dt.c = D.d.cin;
+    dt.oh = D.out_h; dt.ow = D.out_w; dt.stride = D.d.stride; dt.act_dw = D.d.act; dt.act_pw = P.d.act;
+    dt.cout = P.d.cout; dt.ncb = P.ncb; dt.nsteps = P.nsteps;
+    dt.tiles_y = ceil_div(D.out_h, dt.th); dt.tiles_x = ceil_div(D.out_w, dt.tw);
+    dt.ntiles = batch * dt.tiles_y * dt.tiles_x;
+    return true;
+}
+
+uint64_t dwt_cost_ps(const Layer& D, const Layer& P, int batch, int budget, const DlfDwtArgs& dt, int& occ)
+{
+    const int lds = (int)DLF_DWT_LDS_BYTES(dt.tp, dt.c);
+    occ = std::max(1, std::min(2, (160 * 1024) / lds));
+    const int64_t units_wave = ceil_div(dt.ncb * dt.npg, DLF_DWT_WAVES);
+    const int64_t nb = std::min(4, dt.npb);
+    const int64_t p1 = (int64_t)dt.rw * C_DWT_ROW;
+    const int64_t p2 = units_wave * (C_DWT_UNIT + dt.nsteps * std::max<int64_t>(nb, 2) * C_DWT_STEP + nb * C_DWT_EPI);
+    const int64_t tile = C_DWT_TILE + p1 + p2;
+    const int64_t tiles_cu = ((int64_t)dt.ntiles + budget - 1) / budget;
+    const int64_t conc = std::min<int64_t>(occ, tiles_cu);
+    // ... but not the rate at which the CU takes in the weight fragments every tile streams anew
+    const int64_t intake = tiles_cu * ((int64_t)dt.ncb * dt.npg * dt.nsteps * 1024) / PWB_BYTES_PER_CYCLE;
+    const int64_t compute = C_LAT + std::max(tiles_cu * tile / conc, intake);
+    const int64_t m = (int64_t)batch * D.out_h * D.out_w;
+    const int64_t bytes = (int64_t)batch * D.in_h * D.in_w * D.in_c * 2 + m * P.d.cout * 2 +
+                          (int64_t)P.ncb * P.nsteps * 1024 + (int64_t)D.d.cin * 22;
+    const int64_t mem = bytes / std::min<int64_t>(DW_HBM_BYTES_PER_CYCLE, (int64_t)budget * DW_CU_BYTES_PER_CYCLE);
+    return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
+}
+
+const int DWT_RW[] = {1, 2, 4, 7, 8, 14, 16};
+
+// Cheapest tile shape (ties: the first in the order waves along x 4, 2, 1; rows ascending).
+bool dwt_choose(const Layer& D, const Layer& P, int batch, int budget, int max_lds, DlfDwtArgs& best,
+                uint64_t& cost, int& occ)
+{
+    bool found = false;
+    // tiles that overshoot the map by a whole wave's share are skipped, unless a map is so small that
+    // every shape does
+    for (int pass = 0; pass < 2 && !found; ++pass)
+        for (int wx = 4; wx >= 1; wx /= 2)
+            for (int rw : DWT_RW) {
+                DlfDwtArgs dt;
+                if (!dwt_build(D, P, batch, wx, rw, max_lds, dt)) continue;
+                if (pass == 0 && dt.th - D.out_h >= rw && dt.wy > 1) continue;
+                if (pass == 0 && dt.tw - D.out_w >= dt.pxw && wx > 1) continue;
+                int o = 1;
+                const uint64_t c = dwt_cost_ps(D, P, batch, budget, dt, o);
+                if (!found || c < cost) { found = true; cost = c; best = dt; occ = o; }
+            }
+    return found;
+}
+
+// Testing hook of the tile kernel: wx > 0 forces its shape.
+struct DwtForce { int wx, rw; };
+DwtForce g_dwt_force = {0, 0};
+
 // force_tc / pw_mode: explicit values for the two testing hooks (null / -1: the process-wide ones)
 // Fully connected layer: one workgroup per 32 output channels streaming all of K, or, where that is
 // cheaper, pairs of channel blocks with K split 2, 4 or 8 ways (at most 256 workgroups), a second
@@ -1048,13 +1141,37 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
             return DLF_OK;
         }
     }
-    if (g_dw_mode != 2 && (force.th <= 0 || g_dw_mode == 1) && dwpw_eligible(net, first, last, batch)) {
+    if (g_dw_mode != 2 && g_dw_mode != 3 && (force.th <= 0 || g_dw_mode == 1) && dwt_eligible(net, first, last, batch)) {
+        const Layer& P = net.L[last];
+        DlfDwtArgs dt;
+        uint64_t dc = 0;
+        int occ = 1;
+        bool have;
+        if (g_dwt_force.wx > 0) {
+            have = dwt_build(L0, P, batch, g_dwt_force.wx, g_dwt_force.rw, max_lds, dt);
+            if (have) dc = dwt_cost_ps(L0, P, batch, budget, dt, occ);
+        } else {
+            have = dwt_choose(L0, P, batch, budget, max_lds, dt, dc, occ);
+        }
+        if (have && (!tiled || g_dw_mode == 1 || dc < cost)) {
+            g.dt = dt;
+            g.kind = GK_DWT;
+            g.cost = dc;
+            g.variant = L0.d.stride - 1;
+            g.occ = occ;
+            g.grid = std::min(budget * occ, dt.ntiles);
+            g.th = dt.th; g.tw = dt.tw;
+            g.lds_bytes = (int)DLF_DWT_LDS_BYTES(dt.tp, dt.c);
+            return DLF_OK;
+        }
+    }
+    if (g_dw_mode != 2 && (force.th <= 0 || g_dw_mode == 1 || g_dw_mode == 3) && dwpw_eligible(net, first, last, batch)) {
         const Layer& P = net.L[last];
         int nb = 4;
         uint64_t dc = dwpw_cost_ps(L0, P, batch, budget, 4);
         const uint64_t dc2 = dwpw_cost_ps(L0, P, batch, budget, 2);
         if (dc2 < dc || P.ncb <= 2) { nb = 2; dc = dc2; }
-        if (!tiled || g_dw_mode == 1 || dc < cost) {
+        if (!tiled || g_dw_mode == 1 || g_dw_mode == 3 || dc < cost) {
             dwpw_fill(L0, P, batch, nb, g.dp);
             g.kind = GK_DWPW;
             g.cost = dc;
@@ -1647,7 +1764,9 @@ dlf_status dlf_plan_group_io(const dlf_plan_t* plan, int32_t g, int32_t* in_laye
 
 void dlf_debug_pointwise_mode(int32_t mode) { g_pw_mode = (mode >= 0 && mode <= 7) ? mode : 0; }
 
-void dlf_debug_depthwise_mode(int32_t mode) { g_dw_mode = (mode >= 0 && mode <= 2) ? mode : 0; }
+void dlf_debug_depthwise_mode(int32_t mode) { g_dw_mode = (mode >= 0 && mode <= 3) ? mode : 0; }
+
+void dlf_debug_depthwise_tile(int32_t wx, int32_t rw) { g_dwt_force = DwtForce{wx, rw}; }
 
 void dlf_debug_block3x3_mode(int32_t mode, int32_t shape, int32_t th, int32_t tw)
 {
@@ -1716,6 +1835,10 @@ static dlf_status launch_one(const dlf_plan_s* plan, const GroupPlan& G, const v
         DlfDwArgs da = G.da;
         da.in = in; da.out = out;
         e = dlf_launch_dw(&da, G.grid, stream);
+    } else if (G.kind == GK_DWT) {
+        DlfDwtArgs dt = G.dt;
+        dt.in = in; dt.out = out;
+        e = dlf_launch_dwt(&dt, G.grid, G.lds_bytes, stream);
     } else if (G.kind == GK_DWPW) {
         DlfDwPwArgs dp = G.dp;
         dp.in = in; dp.out = out;

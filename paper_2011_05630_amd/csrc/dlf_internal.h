@@ -183,6 +183,35 @@ struct DlfDwPwArgs {
     int32_t nitems;       // n_pg * n_cg (channel group fastest)
 };
 
+// Depthwise 3x3 + 1x1 as a tile kernel: a workgroup of four waves owns a th x tw tile of output
+// pixels.  Phase 1: the waves (wx x wy of them, each pxw = 512 / (2 c) pixels wide and rw rows high)
+// compute the depthwise layer as k_dw does -- coalesced loads, window of input rows in registers --
+// and leave its result in LDS as [pixel][c + 8].  Phase 2: the 1x1 layer on MFMA, its "B" fragments
+// read from that LDS tile, work units of one 32-channel block x up to four 32-pixel blocks dealt
+// to the waves; results leave through wave-private transpose buffers.
+#define DLF_DWT_WAVES 4
+#define DLF_DWT_EPI_HALFS (32 * (32 + 8))            // transpose buffer of a wave: 32 pixels x 32 channels
+#define DLF_DWT_LDS_BYTES(TP, C) (((TP) * ((C) + 8) + DLF_DWT_WAVES * DLF_DWT_EPI_HALFS) * 2)
+struct DlfDwtArgs {
+    const void* in;       // [batch][h][w][c] fp16
+    void* out;            // [batch][oh][ow][cout] fp16
+    const void* wdw;      // depthwise weights [9][c] fp16 (tap-major)
+    const float* bdw;     // depthwise bias [c]
+    const void* wpw;      // pointwise weights, packed fragments
+    const float* bpw;     // pointwise bias, padded to ncb * 32
+    uint32_t in_bytes;    // size of the input tensor (below 2 GiB)
+    int32_t batch, h, w_, c, oh, ow, stride, act_dw, act_pw;
+    int32_t cout, ncb, nsteps;
+    int32_t cg;           // c / 8 (a power of two, 4 .. 64)
+    int32_t pxw;          // 64 / cg: pixels of a row a wave covers
+    int32_t wx, wy, rw;   // waves along x and y (wx * wy = 4), rows per wave
+    int32_t th, tw;       // tile: wy * rw rows x wx * pxw pixels
+    int32_t tp;           // th * tw tile pixels (at most 256)
+    int32_t npb;          // ceil(tp / 32) pixel blocks
+    int32_t npg;          // ceil(npb / 4) groups of up to four pixel blocks
+    int32_t tiles_y, tiles_x, ntiles;     // ntiles = batch * tiles_y * tiles_x
+};
+
 struct DlfGapArgs {
     const void* x;        // [batch][hw][c]
     void* y;              // [batch][c]
@@ -203,6 +232,7 @@ int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stream);
 int dlf_launch_c3(const DlfC3Args* a, int shape, int grid, int lds_bytes, void* stream);
 int dlf_launch_dw(const DlfDwArgs* a, int grid, void* stream);
 int dlf_launch_dwpw(const DlfDwPwArgs* a, int nb, int grid, void* stream);
+int dlf_launch_dwt(const DlfDwtArgs* a, int grid, int lds_bytes, void* stream);
 int dlf_kernels_init(void);
 // Attaches a start / stop event pair (hipEvent_t, either may be null) to this thread's next launch.
 void dlf_next_launch_events(void* start, void* stop);

@@ -15,6 +15,7 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 #include <stdint.h>
+#include <type_traits>
 #include "dlf_internal.h"
 
 typedef _Float16 half_t;
@@ -2159,6 +2160,228 @@ __global__ __launch_bounds__(DLF_DWPW_WAVES * 64, 2) void k_dwpw(const DlfDwPwAr
     }
 }
 
+// Depthwise 3x3 + 1x1 convolution as a tile kernel.  What k_dwpw gets wrong is its memory access (a
+// K step of 16 channels per pixel uses a quarter of each line); here the depthwise phase reads
+// exactly as k_dw does -- a wave's 64 lanes cover whole pixels' channels, contiguous in memory, a
+// window of input rows slides down in registers -- and hands its result to the 1x1 phase through an
+// LDS tile [pixel][c + 8] (the 8 halfs of padding spread the pixels over the banks).  One barrier
+// between the phases, one before the tile buffer is reused; several workgroups share a CU, so one's
+// vector arithmetic overlaps another's MFMAs and stores.
+//   Phase 2 work units: (32-channel block, group of up to four 32-pixel blocks), dealt round-robin
+// to the four waves; weight fragments stream from L2 through a register ring, "B" fragments come
+// from the tile with one 16-byte LDS read per lane.
+// Phase 1 of k_dwt for a wave: RW output rows of the depthwise layer, stride S, written to the LDS
+// tile.  Everything about the row window is static (RW is a template parameter: the kernel
+// switches once per tile), so the compiler knows at every use how many newer loads may still be
+// outstanding; with a run-time row count the loads sit under conditions and every join waits for
+// all of them.  Input rows of output row r + PF are requested before row r is computed.
+template <int S, int RW>
+__device__ __forceinline__ void dwt_phase1(const i32x4 rin, const int (&voff)[3], int img_row0, int h, int rowbytes,
+                                           int iy0, const u4v (&w)[9], const f4v b0, const f4v b1, unsigned lo_d,
+                                           unsigned hi_d, half_t* dst, int row_halfs)
+{
+    constexpr int NR = (RW - 1) * S + 3;             // input rows the wave needs
+    constexpr int PF = S == 1 ? 3 : 2;
+    constexpr int RING = NR < PF * S + 3 ? NR : PF * S + 3;
+    u4v win[RING][3];
+    auto load_row = [&](int k) __attribute__((always_inline)) {
+        const int iy = iy0 + k;
+        const bool rok = iy >= 0 && iy < h;          // uniform; a row of padding reads zeros
+        const int so = rok ? (img_row0 + iy) * rowbytes : 0;
+#pragma unroll
+        for (int d = 0; d < 3; ++d)
+            win[k % RING][d] = __builtin_bit_cast(u4v, raw_buffer_load_x4(rin, rok ? voff[d] : DLF_OOB, so, 0));
+    };
+    constexpr int FIRST = NR < RING - S + (RING == NR ? S : 0) ? NR : RING - S + (RING == NR ? S : 0);
+#pragma unroll
+    for (int k = 0; k < FIRST; ++k) load_row(k);
+#pragma unroll
+    for (int r = 0; r < RW; ++r) {
+#pragma unroll
+        for (int q = 0; q < S; ++q) {
+            const int k = (r + PF) * S + 3 - S + q;  // a row of output row r + PF not yet requested
+            if (k >= FIRST && k < NR) load_row(k);
+        }
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { v[i] = b0[i]; v[i + 4] = b1[i]; }
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) dw_tap(v, win[(r * S + kh) % RING][kw], w[kh * 3 + kw]);
+        u4v hv;
+        hv.x = pk_min(pk_max(cvt_pk(v[0], v[1]), lo_d), hi_d);
+        hv.y = pk_min(pk_max(cvt_pk(v[2], v[3]), lo_d), hi_d);
+        hv.z = pk_min(pk_max(cvt_pk(v[4], v[5]), lo_d), hi_d);
+        hv.w = pk_min(pk_max(cvt_pk(v[6], v[7]), lo_d), hi_d);
+        *(u4v*)(dst + r * row_halfs) = hv;
+    }
+}
+
+// Phase 2 of k_dwt for a wave: its work units of the 1x1 layer.  The weight fragments of all the
+// wave's units form one stream through a ring of D K steps (D divides the K steps of a unit, so
+// ring slots are static): a fragment is requested D steps before its use, across unit boundaries,
+// and the round trip to L2 is paid once per tile, not once per ring turn.
+template <int D>
+__device__ __forceinline__ void dwt_phase2(const DlfDwtArgs& a, const half_t* tile, half_t* tb, int cs, int wave,
+                                           int lane, int n, int ty0, int tx0, unsigned tw_m, unsigned lo_p,
+                                           unsigned hi_p)
+{
+    constexpr int ROW = 32 + 8;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    half_t* outp = (half_t*)a.out;
+    const int nunits = a.ncb * a.npg;
+    int pf_u = wave, pf_ks = 0;                      // the stream's next fragment: unit, K step
+    const h8* wbase = (const h8*)a.wpw + lane;
+    auto next_frag = [&]() __attribute__((always_inline)) {
+        // past the last unit the stream re-reads the last block's first fragment (never used)
+        const int cbp = min(pf_u, nunits - 1) / a.npg;
+        const h8 f = wbase[((size_t)cbp * a.nsteps + pf_ks) * 64];
+        const bool live = pf_u < nunits;
+        const int nks = live ? pf_ks + 1 : pf_ks;
+        const bool wrap = nks == a.nsteps;
+        pf_ks = wrap ? 0 : nks;
+        pf_u = wrap ? pf_u + DLF_DWT_WAVES : pf_u;
+        return f;
+    };
+    h8 ar[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) ar[j] = next_frag();
+    for (int u = wave; u < nunits; u += DLF_DWT_WAVES) {
+        const int cb = u / a.npg, pgi = u - cb * a.npg;
+        const int pb0 = pgi * 4;
+        const int nb = min(4, a.npb - pb0);          // pixel blocks of this unit (uniform)
+        const half_t* bsrc[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            // blocks beyond the tile repeat its last pixel: multiplied, never stored
+            const int px = min((pb0 + p) * 32 + l32, a.tp - 1);
+            bsrc[p] = tile + px * cs + lhi * 8;
+        }
+        f16v acc[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[p][q] = 0.0f;
+        // the K loop, one copy per number of pixel blocks (a switch per unit, nothing conditional inside)
+        auto kloop = [&](auto nbc) __attribute__((always_inline)) {
+            constexpr int NBK = decltype(nbc)::value;
+            for (int s0 = 0; s0 < a.nsteps; s0 += D) {
+#pragma unroll
+                for (int j = 0; j < D; ++j) {
+                    h8 bf[NBK];
+#pragma unroll
+                    for (int p = 0; p < NBK; ++p) bf[p] = *(const h8*)(bsrc[p] + (s0 + j) * 16);
+#pragma unroll
+                    for (int p = 0; p < NBK; ++p)
+                        acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[j], bf[p], acc[p], 0, 0, 0);
+                    ar[j] = next_frag();
+                }
+            }
+        };
+        if (nb == 4) kloop(std::integral_constant<int, 4>());
+        else if (nb == 3) kloop(std::integral_constant<int, 3>());
+        else if (nb == 2) kloop(std::integral_constant<int, 2>());
+        else kloop(std::integral_constant<int, 1>());
+        // epilogue: bias, activation, fp16; 32 pixels at a time through the wave's transpose buffer
+        f4v bias[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bias[q] = *(const f4v*)(a.bpw + cb * 32 + q * 8 + lhi * 4);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            if (p < nb) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    unsigned u0 = cvt_pk(acc[p][q * 4 + 0] + bias[q][0], acc[p][q * 4 + 1] + bias[q][1]);
+                    unsigned u1 = cvt_pk(acc[p][q * 4 + 2] + bias[q][2], acc[p][q * 4 + 3] + bias[q][3]);
+                    u0 = pk_min(pk_max(u0, lo_p), hi_p);
+                    u1 = pk_min(pk_max(u1, lo_p), hi_p);
+                    const u2v uu = {u0, u1};
+                    *(u2v*)(tb + l32 * ROW + q * 8 + lhi * 4) = uu;
+                }
+                __builtin_amdgcn_wave_barrier();
+                // 4 lanes cover the 32 channels of a pixel: 16 pixels per pass
+                const int part = lane & 3;
+                const int cc = cb * 32 + part * 8;
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int pl = i * 16 + (lane >> 2);
+                    const int px = (pb0 + p) * 32 + pl;
+                    const int row = div_by(px, tw_m), colp = px - row * a.tw;
+                    const int oy = ty0 + row, ox = tx0 + colp;
+                    if (px < a.tp && oy < a.oh && ox < a.ow && cc < a.cout)
+                        *(u4v*)(outp + ((size_t)((n * a.oh + oy) * a.ow + ox) * a.cout + cc)) =
+                            *(const u4v*)(tb + pl * ROW + part * 8);
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+    }
+}
+
+template <int S>
+__global__ __launch_bounds__(DLF_DWT_WAVES * 64, 2) void k_dwt(const DlfDwtArgs a)
+{
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int c = a.c, cs = c + 8;
+    half_t* tile = lds;                              // [tp][c + 8]
+    half_t* tb = lds + a.tp * cs + wave * DLF_DWT_EPI_HALFS;
+    const i32x4 rin = make_rsrc(a.in, a.in_bytes);
+    const half_t* wdw = (const half_t*)a.wdw;
+    const unsigned lo_d = act_lo(a.act_dw), hi_d = act_hi(a.act_dw);
+    const unsigned lo_p = act_lo(a.act_pw), hi_p = act_hi(a.act_pw);
+    const int rowbytes = a.w_ * c * 2;
+    const unsigned tw_m = div_magic(a.tw);
+    // phase 1 role of the lane: column pxl of the wave's pxw pixels, channel group g
+    const int cg_shift = __builtin_ctz(a.cg);
+    const int pxl = lane >> cg_shift, g = lane & (a.cg - 1);
+    const int wxi = wave % a.wx, wyi = wave / a.wx;
+    // the lane's nine weight vectors and bias stay in registers over all tiles
+    u4v w[9];
+#pragma unroll
+    for (int k = 0; k < 9; ++k) w[k] = *(const u4v*)(wdw + k * c + g * 8);
+    const f4v b0 = *(const f4v*)(a.bdw + g * 8), b1 = *(const f4v*)(a.bdw + g * 8 + 4);
+
+    for (int t = blockIdx.x; t < a.ntiles; t += gridDim.x) {
+        int r_ = t;
+        const int tx = r_ % a.tiles_x;
+        r_ /= a.tiles_x;
+        const int ty = r_ % a.tiles_y, n = r_ / a.tiles_y;
+        const int ty0 = ty * a.th, tx0 = tx * a.tw;
+        // ---------------- phase 1: depthwise rows of this wave -> LDS tile ----------------
+        {
+            const int col = wxi * a.pxw + pxl;                 // column inside the tile
+            const int ox = tx0 + col;
+            const bool lv = ox < a.ow;
+            int voff[3];
+#pragma unroll
+            for (int d = 0; d < 3; ++d) {
+                const int ix = ox * S - 1 + d;
+                voff[d] = (lv && ix >= 0 && ix < a.w_) ? (ix * a.cg + g) * 16 : DLF_OOB;
+            }
+            const int oyw = ty0 + wyi * a.rw;                  // first output row of the wave
+            const int iy0 = oyw * S - 1;
+            half_t* dst = tile + ((wyi * a.rw) * a.tw + col) * cs + g * 8;
+            const int rh = a.tw * cs;
+            switch (a.rw) {                                    // the shapes the host offers
+            case 1: dwt_phase1<S, 1>(rin, voff, n * a.h, a.h, rowbytes, iy0, w, b0, b1, lo_d, hi_d, dst, rh); break;
+            case 2: dwt_phase1<S, 2>(rin, voff, n * a.h, a.h, rowbytes, iy0, w, b0, b1, lo_d, hi_d, dst, rh); break;
+            case 4: dwt_phase1<S, 4>(rin, voff, n * a.h, a.h, rowbytes, iy0, w, b0, b1, lo_d, hi_d, dst, rh); break;
+            case 7: dwt_phase1<S, 7>(rin, voff, n * a.h, a.h, rowbytes, iy0, w, b0, b1, lo_d, hi_d, dst, rh); break;
+            case 8: dwt_phase1<S, 8>(rin, voff, n * a.h, a.h, rowbytes, iy0, w, b0, b1, lo_d, hi_d, dst, rh); break;
+            case 14: dwt_phase1<S, 14>(rin, voff, n * a.h, a.h, rowbytes, iy0, w, b0, b1, lo_d, hi_d, dst, rh); break;
+            default: dwt_phase1<S, 16>(rin, voff, n * a.h, a.h, rowbytes, iy0, w, b0, b1, lo_d, hi_d, dst, rh); break;
+            }
+        }
+        __syncthreads();
+        // ---------------- phase 2: 1x1 convolution of the tile ----------------
+        if (a.nsteps >= 8) dwt_phase2<8>(a, tile, tb, cs, wave, lane, n, ty0, tx0, tw_m, lo_p, hi_p);
+        else if (a.nsteps == 4) dwt_phase2<4>(a, tile, tb, cs, wave, lane, n, ty0, tx0, tw_m, lo_p, hi_p);
+        else dwt_phase2<2>(a, tile, tb, cs, wave, lane, n, ty0, tx0, tw_m, lo_p, hi_p);
+        __syncthreads();                 // every wave is done reading the tile
+    }
+}
+
 extern "C" int dlf_launch_dw(const DlfDwArgs* a, int grid, void* stream);
 
 // Fully connected layer (Eq. 2 with M = batch): y[n][co] = act(bias[co] + sum_k x[n][k] w[co][k]).
@@ -2412,6 +2635,12 @@ extern "C" int dlf_kernels_init(void)
                                            160 * 1024);
         if (e != hipSuccess) return (int)e;
     }
+    {
+        hipError_t e = hipFuncSetAttribute((const void*)k_dwt<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void*)k_dwt<2>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return (int)e;
+    }
     for (int sh = 0; sh < DLF_C3_SHAPES; ++sh) {
         hipError_t e = hipFuncSetAttribute((const void*)c3_kernel(sh), hipFuncAttributeMaxDynamicSharedMemorySize,
                                            160 * 1024);
@@ -2501,6 +2730,26 @@ extern "C" int dlf_launch_dwpw(const DlfDwPwArgs* a, int nb, int grid, void* str
         launch(k_dwpw<4>, dim3(grid), dim3(DLF_DWPW_WAVES * 64), (size_t)DLF_DWPW_LDS_BYTES(a->c, 4), (hipStream_t)stream, *a);
     else
         return (int)hipErrorInvalidValue;
+    return (int)hipGetLastError();
+}
+
+extern "C" int dlf_launch_dwt(const DlfDwtArgs* a, int grid, int lds_bytes, void* stream)
+{
+    // what the kernel's indexing assumes
+    if (grid <= 0 || (a->stride != 1 && a->stride != 2) || a->in_bytes >= 0x80000000u) return (int)hipErrorInvalidValue;
+    if (a->cg * 8 != a->c || a->cg < 4 || a->cg > 64 || (a->cg & (a->cg - 1)) != 0 || a->pxw * a->cg != 64)
+        return (int)hipErrorInvalidValue;
+    if (a->rw != 1 && a->rw != 2 && a->rw != 4 && a->rw != 7 && a->rw != 8 && a->rw != 14 && a->rw != 16)
+        return (int)hipErrorInvalidValue;
+    if ((a->nsteps & (a->nsteps - 1)) != 0 || a->nsteps < 2) return (int)hipErrorInvalidValue;
+    if (a->wx * a->wy != DLF_DWT_WAVES || a->th != a->wy * a->rw || a->tw != a->wx * a->pxw || a->tp != a->th * a->tw ||
+        a->tp > 256 || a->npb != (a->tp + 31) / 32 || a->npg != (a->npb + 3) / 4 || a->nsteps != a->c / 16 ||
+        (a->cout & 7) != 0 || lds_bytes != (int)DLF_DWT_LDS_BYTES(a->tp, a->c) || lds_bytes > 160 * 1024)
+        return (int)hipErrorInvalidValue;
+    if (a->stride == 1)
+        launch(k_dwt<1>, dim3(grid), dim3(DLF_DWT_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
+    else
+        launch(k_dwt<2>, dim3(grid), dim3(DLF_DWT_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
     return (int)hipGetLastError();
 }
 

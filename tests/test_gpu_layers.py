@@ -352,7 +352,7 @@ def test_depthwise_pointwise_fused_kernel(stride, c, cout, h, w, batch):
     layers = [nets.dwconv(c, 3, stride, "relu6"), nets.conv(c, cout, 1, 1, 0, "relu6" if cout != 24 else "none")]
     net = _mk(layers, h, w, c, dist="normal")
     x, ws, bs = gen.make_params(net, batch, 9)
-    B.dlf_debug_depthwise_mode(1)
+    B.dlf_debug_depthwise_mode(3)
     try:
         s = Session(net, batch, ws, bs, **_manual(2, [1]))
     finally:
@@ -364,6 +364,45 @@ def test_depthwise_pointwise_fused_kernel(stride, c, cout, h, w, batch):
     finally:
         s.close()
     compare(got, o.run_net(net, x, ws, bs), "dw+pw s%d %d->%d %dx%d" % (stride, c, cout, h, w))
+
+
+# (stride, channels in, channels out, height, width, batch, waves along x, rows per wave; 0, 0 = the
+# planner's choice): every power-of-two channel count the kernel takes, tiles that overhang the map
+# on both sides, one to eight pixel blocks per tile, 1 to 32 channel blocks, more and fewer work
+# units than waves
+DWT_CASES = [(1, 32, 64, 28, 28, 2, 0, 0), (1, 32, 64, 30, 37, 2, 2, 4), (1, 32, 64, 9, 70, 1, 4, 1),
+             (2, 64, 128, 21, 23, 2, 0, 0), (2, 64, 128, 33, 31, 1, 4, 8), (1, 64, 24, 13, 5, 3, 1, 2),
+             (1, 128, 128, 9, 10, 3, 0, 0), (1, 128, 128, 20, 20, 2, 4, 16), (2, 128, 256, 14, 14, 2, 2, 7),
+             (1, 256, 512, 7, 7, 3, 0, 0), (1, 256, 256, 28, 28, 2, 4, 14), (1, 512, 512, 14, 14, 2, 0, 0),
+             (2, 512, 1024, 14, 14, 2, 4, 7), (1, 512, 200, 6, 9, 2, 2, 2), (2, 32, 64, 1, 1, 3, 0, 0),
+             (2, 32, 64, 112, 112, 1, 0, 0)]
+
+
+@pytest.mark.parametrize("stride,c,cout,h,w,batch,wx,rw", DWT_CASES)
+def test_depthwise_pointwise_tile_kernel(stride, c, cout, h, w, batch, wx, rw):
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    from oracle import oracle as o
+    announce("dw+pw tile kernel", stride, c, cout, h, w, batch, wx, rw)
+    layers = [nets.dwconv(c, 3, stride, "relu6"), nets.conv(c, cout, 1, 1, 0, "relu6" if cout != 24 else "none")]
+    net = _mk(layers, h, w, c, dist="normal")
+    x, ws, bs = gen.make_params(net, batch, 10)
+    B.dlf_debug_depthwise_mode(1)
+    B.dlf_debug_depthwise_tile(wx, rw)
+    try:
+        s = Session(net, batch, ws, bs, **_manual(2, [1]))
+    finally:
+        B.dlf_debug_depthwise_mode(0)
+        B.dlf_debug_depthwise_tile(0, 0)
+    try:
+        cfg = B.dlf_plan_group_config(s.plan, 0)
+        assert len(s.groups) == 1 and cfg["kind"] == 7 and cfg["variant"] == stride - 1, cfg
+        if wx:
+            assert (s.groups[0]["tile_h"], s.groups[0]["tile_w"]) == ((4 // wx) * rw, wx * 512 // c)
+        got = s.run_numpy(x)
+    finally:
+        s.close()
+    compare(got, o.run_net(net, x, ws, bs), "dw+pw tile s%d %d->%d %dx%d" % (stride, c, cout, h, w))
 
 
 def test_depthwise_channel_slices():

@@ -25,7 +25,7 @@ def _manual(lasts, budget):
     return dict(mode=B.TUNER_MANUAL, group_last=list(lasts), group_budget=[budget] * len(lasts))
 
 
-KIND_NAME = {0: "group", 1: "fc", 2: "gap", 3: "pw", 4: "c3b", 5: "dw", 6: "dwpw", 7: "pw2"}
+KIND_NAME = {0: "group", 1: "fc", 2: "gap", 3: "pw", 4: "c3b", 5: "dw", 6: "dwpw", 7: "dwt"}
 
 
 def _kinds(s):
@@ -168,7 +168,7 @@ def test_config5_mobilenet_batch1():
 
 def test_config5_mobilenet_batch64_sampled():
     net = nets.mobilenet_v1()
-    _net_case(net, 64, [0, 33, 63], True, _plans(net)[:1], expect_kinds=[("pw", None), ("dw", 0), ("dw", 1)])
+    _net_case(net, 64, [0, 33, 63], True, _plans(net)[:1], expect_kinds=[("pw", None), ("dw", 0), ("dw", 1), ("dwt", 0), ("dwt", 1)])
 
 
 def test_other_evaluated_networks_small_batch():
