@@ -24,15 +24,70 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA
 RIDGE = MFMA_FP16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # FLOP per byte
 
-# HBM bytes per launch of a workload's main kernels, from two `rocprofv3 --pmc` runs of this file
+# HBM bytes per launch of a workload's kernels, from two `rocprofv3 --pmc` runs of this file
 # (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch; `--calib-copy 3` adds plain 256 MiB device copies
-# whose readings give the scale factors: 2.000 for FETCH_SIZE, 1.000 for WRITE_SIZE on this chip).
-# Valid only for the kernel sources they were taken with: `csrc_sha1` is checked at run time and
-# `traffic` is reported as null when the sources have changed since.
-TRAFFIC = {
-    "csrc_sha1": "51212e24a6a7b06526f443724c7df6ef205eb2f7",
-    "bytes_per_launch": {"resnet50_b32": {"k_group<1,2,4>": 67694276, "k_pwb<2,2>": 42970560, "k_pwb<1,4>": 64615032, "k_group<1,2,2>": 23296506, "k_pw_sk": 55611492, "k_group<1,2,2,true>": 19665227, "k_gap": 6584710, "k_fc": 5406709}},
-}
+# whose readings give each counter's scale).  `--traffic-from FETCH_DIR WRITE_DIR` turns the two
+# counter CSVs into profiles/hbm_traffic.json; the figures are valid only for the kernel sources they
+# were taken with (`csrc_sha1`), and `traffic` is reported as null once the sources have changed.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def load_traffic():
+    try:
+        with open(TRAFFIC_FILE) as f:
+            return json.load(f)
+    except (OSError, ValueError):
+        return {"csrc_sha1": "", "bytes_per_launch": {}}
+
+
+def kernel_short_name(k):
+    return k.replace("void ", "").split("(")[0].replace(" ", "").replace(",false>", ">")
+
+
+def traffic_from(fetch_dir, write_dir, workload_key):
+    """Reads rocprofv3's counter_collection CSVs of a FETCH_SIZE and a WRITE_SIZE run of
+    `bench.py --workload W --calib-copy 3`, scales both counters by what they read for the 256 MiB
+    copies, and stores mean HBM bytes per launch of every kernel under `workload_key`.  Prints the
+    table that goes into the profile summary."""
+    import collections
+    import csv
+    import glob
+
+    def load(d):
+        files = glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True)
+        assert files, "no counter_collection.csv under " + d
+        by = collections.defaultdict(list)
+        for fn in files:
+            for r in csv.DictReader(open(fn)):
+                by[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+        return by
+
+    F, W = load(fetch_dir), load(write_dir)
+    copy = [k for k in F if "copyBuffer" in k or "copy" in k.lower()][0]
+    kib = 256 * 1024
+    bf, bw = sorted(F[copy])[-3:], sorted(W[copy])[-3:]
+    ff, fw = kib / (sum(bf) / len(bf)), kib / (sum(bw) / len(bw))
+    rows = []
+    for k in F:
+        n = kernel_short_name(k)
+        if not n.startswith("k_") or k not in W:
+            continue
+        f, w = sum(F[k]) / len(F[k]), sum(W[k]) / len(W[k])
+        rows.append((n, len(F[k]), f, w, int(round((f * ff + w * fw) * 1024))))
+    rows.sort(key=lambda r: -r[1] * r[4])
+    t = load_traffic()
+    if t.get("csrc_sha1") != csrc_sha1():
+        t = {"csrc_sha1": csrc_sha1(), "bytes_per_launch": {}}
+    t["bytes_per_launch"][workload_key] = {r[0]: r[4] for r in rows}
+    t.setdefault("factors", {})[workload_key] = {"FETCH_SIZE": ff, "WRITE_SIZE": fw,
+                                                 "copy_readings_KiB": {"FETCH_SIZE": bf, "WRITE_SIZE": bw}}
+    with open(TRAFFIC_FILE, "w") as f:
+        json.dump(t, f, indent=1, sort_keys=True)
+        f.write("\n")
+    print("factors: FETCH_SIZE %.4f (%s), WRITE_SIZE %.4f (%s)" % (ff, bf, fw, bw))
+    print("| kernel | launches | FETCH_SIZE KiB | WRITE_SIZE KiB | scaled HBM bytes per launch |\n|---|---|---|---|---|")
+    for n, cnt, f, w, tot in rows:
+        print("| `%s` | %d | %.1f | %.1f | %.1f MB |" % (n, cnt, f, w, tot / 1e6))
 
 
 def csrc_sha1():
@@ -86,7 +141,7 @@ def layer_bytes_flops(net, batch):
             wb = L["cin"] * L["cout"] * 2 + 4 * L["cout"]
         else:
             mac, wb = 0, 0
-        rows.append(dict(mac=mac * batch, wbytes=wb,
+        rows.append(dict(mac=mac * batch, wbytes=wb, op=L["op"], k=L["kh"],
                          in_bytes=batch * hin[0] * hin[1] * hin[2] * 2,
                          out_bytes=batch * hout[0] * hout[1] * hout[2] * 2))
     return rows
@@ -101,6 +156,8 @@ def group_accounting(net, batch, session):
     for g, info in enumerate(session.groups):
         f, l = info["first"], info["last"]
         flops = 2 * sum(rows[i]["mac"] for i in range(f, l + 1))
+        flops3x3 = 2 * sum(rows[i]["mac"] for i in range(f, l + 1) if rows[i]["op"] == "conv" and rows[i]["k"] == 3)
+        has_dw = any(rows[i]["op"] == "dwconv" for i in range(f, l + 1))
         wbytes = sum(rows[i]["wbytes"] for i in range(f, l + 1))
         in_layer, res_layer = B.dlf_plan_group_io(session.plan, g)
         byts = rows[f]["in_bytes"] + rows[l]["out_bytes"] + wbytes
@@ -123,10 +180,140 @@ def group_accounting(net, batch, session):
             kname = "k_dwt<%d>" % (cfg["variant"] + 1)
         else:
             kname = VARIANT_NAME[cfg["variant"]]
-        out.append(dict(first=f, last=l, budget=info["budget"], flops=flops, bytes=byts,
+        out.append(dict(first=f, last=l, budget=info["budget"], flops=flops, bytes=byts, flops3x3=flops3x3,
+                        has_dw=has_dw,
                         kernel=kname, tile=(info["tile_h"], info["tile_w"]), cfg=cfg,
                         model_us=info["model_cost"] / 1e6))
     return out
+
+
+def time_plan(net, batch, plan, steps, warmup, x=None, ws=None, bs=None, refine=0, calib_copy=0):
+    """Builds the session, runs `warmup` untimed and exactly `steps` timed passes of dlf_run between
+    two synchronisations, then a profiled pass for per-group durations.  Returns a dict."""
+    import torch
+    from synth import gen
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    if x is None:
+        x, ws, bs = gen.make_params(net, batch)
+    s = Session(net, batch, ws, bs, **plan)
+    xt = torch.from_numpy(x).cuda()
+    out = torch.empty(s.out_shape, dtype=torch.float16, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    if calib_copy > 0:
+        src = torch.ones(128 * 1024 * 1024, dtype=torch.float16, device="cuda")     # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(calib_copy):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    refined = s.refine(xt, top_k=refine, reps=5) if refine > 0 else 0
+    for _ in range(warmup):
+        B.dlf_run(s.plan, xt.data_ptr(), out.data_ptr(), stream)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        B.dlf_run(s.plan, xt.data_ptr(), out.data_ptr(), stream)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps   # wall clock, sync on both sides
+    event_ms_per_step = e0.elapsed_time(e1) / steps
+    # per-group durations: a HIP stop event on every group launch, on the launch stream
+    reps = max(5, min(50, steps))
+    gms = B.dlf_run_profiled(s.plan, xt.data_ptr(), out.data_ptr(), stream, reps)
+    # Events stretch the stream: every launch of the profiled pass carries a constant hand-over
+    # cost that the timed region (no events) does not have.  It is removed uniformly, so that the
+    # group durations add up to the step time measured over the timed region.
+    ev_overhead_ms = max(0.0, (sum(gms) - ms_per_step) / len(gms))
+    gms = [max(g - ev_overhead_ms, 1e-6) for g in gms]
+    acct = group_accounting(net, batch, s)
+    for a, ms in zip(acct, gms):
+        a["ms"] = ms
+    res = dict(ms_per_step=ms_per_step, event_ms_per_step=event_ms_per_step, ev_overhead_ms=ev_overhead_ms,
+               acct=acct, groups=len(s.groups), refined=refined, x=x, ws=ws, bs=bs)
+    s.close()
+    del xt, out
+    return res
+
+
+def class_fractions(net, acct):
+    """Roofline fractions of the two classes of groups the targets are stated on.
+    mfma: groups whose operations are dominated by 3x3 convolutions and whose intensity lies above
+    the ridge -- fraction of the fp16 MFMA peak; depthwise: groups that hold a depthwise layer --
+    fraction of the HBM peak on algorithmic bytes.  Each: best group, and all such groups together
+    (sum of work / sum of time)."""
+    out = {}
+    mf = [a for a in acct if a["flops3x3"] * 2 > a["flops"] and a["flops"] / max(a["bytes"], 1) >= RIDGE]
+    if mf:
+        best = max(mf, key=lambda a: a["flops"] / a["ms"])
+        out["mfma_3x3_groups"] = dict(
+            groups=len(mf), share_of_step=sum(a["ms"] for a in mf) / sum(a["ms"] for a in acct),
+            frac_time_weighted=sum(a["flops"] for a in mf) / (sum(a["ms"] for a in mf) * 1e-3) / 1e12 / MFMA_FP16_PEAK_TFLOPS,
+            frac_best=best["flops"] / (best["ms"] * 1e-3) / 1e12 / MFMA_FP16_PEAK_TFLOPS,
+            best_group="%d-%d %s" % (best["first"], best["last"], best["kernel"]))
+    dw = [a for a in acct if a["has_dw"]]
+    if dw:
+        best = max(dw, key=lambda a: a["bytes"] / a["ms"])
+        out["depthwise_groups"] = dict(
+            groups=len(dw), share_of_step=sum(a["ms"] for a in dw) / sum(a["ms"] for a in acct),
+            frac_time_weighted=sum(a["bytes"] for a in dw) / (sum(a["ms"] for a in dw) * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            frac_best=best["bytes"] / (best["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            best_group="%d-%d %s" % (best["first"], best["last"], best["kernel"]))
+    return out
+
+
+def print_table(acct, gms_sum, ms_per_step):
+    print("%-10s %-13s %6s %-7s %9s %9s %9s %8s %8s %7s %8s" % (
+        "layers", "kernel", "budget", "tile", "us", "model_us", "GFLOP", "MB", "TFLOP/s", "GB/s",
+        "roof%"), file=sys.stderr)
+    for a in acct:
+        t = a["ms"] * 1e-3
+        tf = a["flops"] / t / 1e12
+        gb = a["bytes"] / t / 1e9
+        aig = a["flops"] / max(a["bytes"], 1)
+        frac = tf / MFMA_FP16_PEAK_TFLOPS if aig >= RIDGE else gb / HBM_PEAK_GBS
+        print("%-10s %-13s %6d %-7s %9.2f %9.2f %9.3f %8.2f %8.1f %7.0f %7.1f%s  s%d x%d lds%dk" % (
+            "%d-%d" % (a["first"], a["last"]), a["kernel"], a["budget"],
+            "%dx%d" % a["tile"], a["ms"] * 1e3, a["model_us"], a["flops"] / 1e9,
+            a["bytes"] / 1e6, tf, gb, 100 * frac, "M" if aig >= RIDGE else "H",
+            a["cfg"]["stream0"], a["cfg"]["nslices"], a["cfg"]["lds_bytes"] // 1024),
+            file=sys.stderr)
+    print("sum of groups %.1f us; step %.1f us" % (gms_sum * 1e3, ms_per_step * 1e3), file=sys.stderr)
+
+
+def sweep_chain4(steps, warmup):
+    """The block-size sweep of Sec. III-B on this chip: chains of four 3x3 convolutions at 56 x 56,
+    C -> C for five widths, batch 1 and 8, every fusion depth 1..4 (groups {1,1,1,1}, {2,2}, {3,1},
+    {4}) on every CU budget.  One line per point on stdout: feasible?, measured and modelled us,
+    fraction of the plan's roofline (sum over groups of max(flops / MFMA peak, bytes / HBM peak))."""
+    from synth import nets, gen
+    from paper_2011_05630_amd import binding as B
+    parts = {1: [0, 1, 2, 3], 2: [1, 3], 3: [2, 3], 4: [3]}
+    print("| C | batch | depth | budget | feasible | us | model us | roofline us | fraction |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    for c in (16, 32, 64, 128, 256):
+        net = nets.chain4(c)
+        for batch in (1, 8):
+            x, ws, bs = gen.make_params(net, batch)
+            for depth, lasts in parts.items():
+                for budget in (32, 64, 128, 256):
+                    plan = dict(mode=B.TUNER_MANUAL, group_last=lasts, group_budget=[budget] * len(lasts))
+                    try:
+                        r = time_plan(net, batch, plan, steps, warmup, x, ws, bs)
+                    except B.DlfError as e:
+                        if e.status != B.DLF_ERR_INFEASIBLE:
+                            raise
+                        print("| %d | %d | %d | %d | no | - | - | - | - |" % (c, batch, depth, budget))
+                        continue
+                    roof = sum(max(a["flops"] / (MFMA_FP16_PEAK_TFLOPS * 1e12), a["bytes"] / (HBM_PEAK_GBS * 1e9))
+                               for a in r["acct"]) * 1e6
+                    us = r["ms_per_step"] * 1e3
+                    print("| %d | %d | %d | %d | yes | %.1f | %.1f | %.2f | %.3f |" % (
+                        c, batch, depth, budget, us, sum(a["model_us"] for a in r["acct"]), roof, roof / us))
+                    sys.stdout.flush()
 
 
 def main():
@@ -151,19 +338,21 @@ def main():
                     help="measured refinement of the plan before timing: candidates per group (0 = off)")
     ap.add_argument("--table", action="store_true", help="per-group table on stderr")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the side measurements (VGG-16 b16, MobileNet-v1 b64, ResNet-50 b1) of the default run")
+    ap.add_argument("--sweep", default="", choices=["", "chain4"],
+                    help="chain4: the fusion-depth x budget sweep of the 4-layer chains, a table on stdout")
     ap.add_argument("--calib-copy", type=int, default=0,
                     help="run this many plain 256 MiB device copies first (reference dispatches of "
                          "known size for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"), default=None,
+                    help="no GPU: read the counter CSVs of two rocprofv3 --pmc runs of this workload and "
+                         "store HBM bytes per launch in profiles/hbm_traffic.json")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: the library runs on one GPU; --gpus %d is not supported" % args.gpus,
               file=sys.stderr)
         sys.exit(2)
-
-    import torch
-    from synth import gen
-    from paper_2011_05630_amd import binding as B
-    from paper_2011_05630_amd.runner import Session
 
     wl = workloads()
     if args.workload not in wl:
@@ -173,7 +362,14 @@ def main():
     builder, default_batch = wl[args.workload]
     batch = args.batch or default_batch
     net = builder()
-    x, ws, bs = gen.make_params(net, batch)
+    if args.traffic_from:
+        traffic_from(args.traffic_from[0], args.traffic_from[1], "%s_b%d" % (net["name"], batch))
+        return
+    if args.sweep == "chain4":
+        sweep_chain4(min(args.steps, 50), min(args.warmup, 10))
+        return
+
+    from paper_2011_05630_amd import binding as B
     n = len(net["layers"])
     if args.plan == "dp":
         plan = dict(mode=B.TUNER_DP)
@@ -191,50 +387,15 @@ def main():
             plan.update(alpha=al, beta=be, mp_scale=sc, mp_offset=of)
         if args.opcount_critical > 0:
             plan.update(opcount_critical=args.opcount_critical)
-    s = Session(net, batch, ws, bs, **plan)
-    xt = torch.from_numpy(x).cuda()
-    out = torch.empty(s.out_shape, dtype=torch.float16, device="cuda")
-    stream = torch.cuda.current_stream().cuda_stream
-
-    if args.calib_copy > 0:
-        src = torch.ones(128 * 1024 * 1024, dtype=torch.float16, device="cuda")     # 256 MiB
-        dst = torch.empty_like(src)
-        for _ in range(args.calib_copy):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-    refined = 0
-    if args.refine > 0:
-        refined = s.refine(xt, top_k=args.refine, reps=5)
-    for _ in range(args.warmup):
-        B.dlf_run(s.plan, xt.data_ptr(), out.data_ptr(), stream)
-    torch.cuda.synchronize()
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record()
-    for _ in range(args.steps):
-        B.dlf_run(s.plan, xt.data_ptr(), out.data_ptr(), stream)
-    e1.record()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps   # wall clock, sync on both sides
-    event_ms_per_step = e0.elapsed_time(e1) / args.steps
+    r = time_plan(net, batch, plan, args.steps, args.warmup, refine=args.refine, calib_copy=args.calib_copy)
+    ms_per_step, acct = r["ms_per_step"], r["acct"]
+    x, ws, bs = r["x"], r["ws"], r["bs"]
+    gms = [a["ms"] for a in acct]
     images_per_s = batch / (ms_per_step * 1e-3)
-
-    # per-group durations: HIP event pair around every group launch, on the launch stream
-    reps = max(5, min(50, args.steps))
-    gms = B.dlf_run_profiled(s.plan, xt.data_ptr(), out.data_ptr(), stream, reps)
-    # Events stretch the stream: every launch of the profiled pass carries a constant hand-over
-    # cost that the timed region (no events) does not have.  It is removed uniformly, so that the
-    # group durations add up to the step time measured over the timed region.
-    ev_overhead_ms = max(0.0, (sum(gms) - ms_per_step) / len(gms))
-    gms = [max(g - ev_overhead_ms, 1e-6) for g in gms]
-    acct = group_accounting(net, batch, s)
     by_kernel = {}
-    for a, ms in zip(acct, gms):
-        a["ms"] = ms
+    for a in acct:
         k = by_kernel.setdefault(a["kernel"], dict(ms=0.0, flops=0, bytes=0, launches=0))
-        k["ms"] += ms
+        k["ms"] += a["ms"]
         k["flops"] += a["flops"]
         k["bytes"] += a["bytes"]
         k["launches"] += 1
@@ -251,31 +412,37 @@ def main():
         roof = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=ach / HBM_PEAK_GBS)
     traffic = None
-    if TRAFFIC["csrc_sha1"] == csrc_sha1():
-        traffic = TRAFFIC["bytes_per_launch"].get("%s_b%d" % (net["name"], batch), {}).get(dom)
+    tt = load_traffic()
+    if tt.get("csrc_sha1") == csrc_sha1():
+        traffic = tt["bytes_per_launch"].get("%s_b%d" % (net["name"], batch), {}).get(dom)
     roof.update(traffic=traffic, kernel=dom, launches_per_step=d["launches"],
                 avg_launch_us=avg_ms * 1e3, flops_per_launch=d["flops"] / d["launches"],
                 bytes_per_launch=d["bytes"] / d["launches"],
                 share_of_step=d["ms"] / max(sum(gms), 1e-9))
 
     if args.table:
-        print("%-10s %-13s %6s %-7s %9s %9s %9s %8s %8s %7s %8s" % (
-            "layers", "kernel", "budget", "tile", "us", "model_us", "GFLOP", "MB", "TFLOP/s",
-            "GB/s", "roof%"), file=sys.stderr)
-        for a in acct:
-            t = a["ms"] * 1e-3
-            tf = a["flops"] / t / 1e12
-            gb = a["bytes"] / t / 1e9
-            aig = a["flops"] / max(a["bytes"], 1)
-            frac = tf / MFMA_FP16_PEAK_TFLOPS if aig >= RIDGE else gb / HBM_PEAK_GBS
-            print("%-10s %-13s %6d %-7s %9.2f %9.2f %9.3f %8.2f %8.1f %7.0f %7.1f%s  s%d x%d lds%dk" % (
-                "%d-%d" % (a["first"], a["last"]), a["kernel"], a["budget"],
-                "%dx%d" % a["tile"], a["ms"] * 1e3, a["model_us"], a["flops"] / 1e9,
-                a["bytes"] / 1e6, tf, gb, 100 * frac, "M" if aig >= RIDGE else "H",
-                a["cfg"]["stream0"], a["cfg"]["nslices"], a["cfg"]["lds_bytes"] // 1024),
-                file=sys.stderr)
-        print("sum of groups %.1f us; step %.1f us" % (sum(gms) * 1e3, ms_per_step * 1e3),
-              file=sys.stderr)
+        print_table(acct, sum(gms), ms_per_step)
+
+    # Side measurements of the default run: the classes of groups the targets are stated on, in the
+    # workloads that have them, and the small batch of the headline network (a few ms each).
+    extra = {}
+    if not args.no_extra and args.workload == "resnet50" and args.plan == "dp" and not args.batch:
+        from synth import nets
+        side_steps = max(5, min(args.steps, 50))
+        for name, bld, b in (("vgg16_b16", nets.vgg16, 16), ("mobilenet_v1_b64", nets.mobilenet_v1, 64),
+                             ("resnet50_b1", nets.resnet50, 1)):
+            sn = bld()
+            sr = time_plan(sn, b, dict(mode=B.TUNER_DP), side_steps, min(args.warmup, 10))
+            e = dict(images_per_s=b / (sr["ms_per_step"] * 1e-3), ms_per_step=sr["ms_per_step"], groups=sr["groups"],
+                     steps=side_steps)
+            tot = sum(max(a["flops"] / (MFMA_FP16_PEAK_TFLOPS * 1e12), a["bytes"] / (HBM_PEAK_GBS * 1e9)) for a in sr["acct"])
+            e["whole_step_roofline_frac"] = tot / (sr["ms_per_step"] * 1e-3)
+            e.update(class_fractions(sn, sr["acct"]))
+            extra[name] = e
+            if args.table:
+                print("--- %s" % name, file=sys.stderr)
+                print_table(sr["acct"], sum(a["ms"] for a in sr["acct"]), sr["ms_per_step"])
+            del sr
 
     cpu = None
     if not args.no_cpu:
@@ -296,6 +463,7 @@ def main():
                           % nsample)
 
     total_flops = sum(a["flops"] for a in acct)
+    whole = sum(max(a["flops"] / (MFMA_FP16_PEAK_TFLOPS * 1e12), a["bytes"] / (HBM_PEAK_GBS * 1e9)) for a in acct)
     res = {
         "metric": "images_per_sec", "value": images_per_s, "unit": "images/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -307,14 +475,17 @@ def main():
                    + ("[crit %g]" % args.opcount_critical if args.opcount_critical > 0 and args.plan == "greedy" else "")
                    + ("@%d" % args.budget if args.plan == "unfused" else "")
                    + ("+refine%d" % args.refine if args.refine > 0 else ""),
-                   "groups_refined": refined, "groups": len(s.groups), "layers": n,
+                   "groups_refined": r["refined"], "groups": r["groups"], "layers": n,
                    "input": "%dx%dx%d" % (net["in_h"], net["in_w"], net["in_c"])},
-        "event_ms_per_step": event_ms_per_step,
-        "event_overhead_us_per_launch": ev_overhead_ms * 1e3,
+        "event_ms_per_step": r["event_ms_per_step"],
+        "event_overhead_us_per_launch": r["ev_overhead_ms"] * 1e3,
         "algorithmic_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
+        "whole_step_roofline_frac": whole / (ms_per_step * 1e-3),
         "roofline": roof, "cpu_baseline": cpu,
     }
-    s.close()
+    res.update(class_fractions(net, acct))
+    if extra:
+        res["other_workloads"] = extra
     print(json.dumps(res))
 
 

@@ -54,7 +54,10 @@ typedef struct {
     int32_t has_bias;      /* 1: add bias[cout] (a folded batch-norm shift)                     */
     int32_t act;           /* dlf_act; applied after the residual add if there is one           */
     int32_t input_from;    /* -1: previous layer (net input for layer 0); else a layer index    */
-    int32_t residual_from; /* -1: none; else index of the layer whose output is added           */
+    int32_t residual_from; /* -1: none; else index of the layer whose output is added: the layer's  */
+                           /* own result (convolution + bias, fp32) is rounded to fp16, the fp16    */
+                           /* operand is added and the sum rounded again, then the activation; the  */
+                           /* result before the add must therefore lie in the fp16 range            */
     const void* weight;    /* HOST fp16 [cout][kh][kw][cin] (depthwise: [cout][kh][kw][1];      */
                            /* FC: [cout][cin], cin flattened in h,w,c order); NULL => shape-only */
     const float* bias;     /* HOST fp32 [cout], or NULL                                         */
@@ -209,46 +212,6 @@ dlf_status dlf_plan_group_io(const dlf_plan_t* plan, int32_t g, int32_t* in_laye
  * variable DLF_DEBUG set, one line per group with the measured times goes to stderr. */
 dlf_status dlf_plan_refine(dlf_plan_t* plan, const void* in_dev, void* out_dev, void* hip_stream,
                            int32_t top_k, int32_t reps, int32_t* changed);
-
-/* Testing hook: th > 0 forces tile th x tw, register-tile variant, channel slicing, streaming and
- * channels per streaming round (kc: 32, 64 or 128; 0 = 32) for every group planned afterwards
- * (groups it does not fit become infeasible; for a fully connected layer nslices = 1, 2, 4 or 8
- * is the number of K slices); th = 0 restores the automatic choice.
- * Process-wide, not thread-safe. */
-void dlf_debug_force_config(int32_t th, int32_t tw, int32_t variant, int32_t nslices,
-                            int32_t slice_c, int32_t stream0, int32_t kc);
-/* Testing hook, after dlf_debug_force_config (which resets it to 1): the forced tiling also splits K
- * over `ksplit` waves per work item (2, 4 or 8; single resident convolution, 32x64 register tile). */
-void dlf_debug_force_ksplit(int32_t ksplit);
-
-/* Testing hook: how single 1x1 convolutions choose between the fused-group kernel and the
- * pointwise kernel: 0 = by modelled cost (default), 1 = pointwise wherever it applies, 2 = never,
- * 3 / 4 / 5 = pointwise wherever it applies with 64x64 / 32x32 / split-K 64x64 work items,
- * 6 / 7 = with workgroup blocks of 128 channels x 128 pixels / 64 channels x 256 pixels whose
- * operands are shared through LDS.  Process-wide, not thread-safe. */
-void dlf_debug_pointwise_mode(int32_t mode);
-
-/* Testing hook: how a single depthwise 3x3 layer (pad 1, stride 1 or 2), or such a layer with the 1x1
- * convolution behind it, chooses between the fused-group kernel and the streaming depthwise kernel /
- * the depthwise + 1x1 kernels: 0 = by modelled cost (default), 1 = the depthwise kernels wherever
- * they apply (a pair: the tile kernel where its shape restrictions allow, else the register kernel),
- * 2 = never, 3 = as 1 but a pair always on the register kernel.  Process-wide, not thread-safe. */
-void dlf_debug_depthwise_mode(int32_t mode);
-/* Testing hook: wx > 0 fixes the tile of the depthwise + 1x1 tile kernel for groups planned afterwards:
- * wx (1, 2 or 4) of its four waves side by side, each 512 / (2 * channels) pixels wide, rw output rows
- * per wave (a shape that does not fit falls back to the other kernels); wx = 0 restores the automatic
- * choice.  Process-wide, not thread-safe. */
-void dlf_debug_depthwise_tile(int32_t wx, int32_t rw);
-
-/* Testing hook: how a single 3x3 stride-1 pad-1 convolution (with the 2x2 max pool folded behind
- * it, if any) chooses between the fused-group kernel and the block 3x3 kernel: mode 0 = by
- * modelled cost (default), 1 = the block kernel wherever it applies, 2 = never.  shape >= 0 also
- * fixes the block's shape and its th x tw pixel tile: shape 0 / 1 = 128 channels x up to 256
- * pixels with activations brought in 32 / 64 input channels at a time, 2 / 3 = 64 channels x up to
- * 512 pixels likewise, 4 = 128 channels x up to 512 pixels (32 input channels at a time); a shape
- * that cannot be laid out falls back to the fused-group kernel.
- * Process-wide, not thread-safe. */
-void dlf_debug_block3x3_mode(int32_t mode, int32_t shape, int32_t th, int32_t tw);
 
 const char* dlf_status_string(dlf_status s);
 const char* dlf_last_error(void);

@@ -6,7 +6,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdlf.so")
 SOURCES = ["dlf_kernels.hip", "dlf_host.cpp"]
-HEADERS = ["dlf_internal.h", os.path.join("..", "..", "include", "dlf.h")]
+HEADERS = ["dlf_internal.h", os.path.join("..", "..", "include", "dlf.h"),
+           os.path.join("..", "..", "include", "dlf_debug.h")]
 
 
 def needs_build():

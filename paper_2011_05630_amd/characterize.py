@@ -21,8 +21,16 @@ SMALL_BUDGET = 8          # 1/32 of the chip: the analogue of one of the paper's
 
 
 def conv_ops(cin, cout, hw, k, batch=1):
-    """Eq. 1 with one multiply-add counted as two operations."""
-    return 2 * batch * hw * hw * k * k * cin * cout
+    """Operation count of the layer {cin, cout, hw x hw, k x k} (stride 1, 'same' padding) as the
+    library reports it for a shape-only network (dlf_net_layer_info: Eq. 1), times the batch."""
+    from . import binding as B
+    layer = dict(op="conv", cin=cin, cout=cout, kh=k, kw=k, stride=1, pad=k // 2, has_bias=1,
+                 act="relu", input_from=-1, residual_from=-1)
+    h = B.dlf_net_create([layer], hw, hw, cin)
+    try:
+        return batch * B.dlf_net_layer_info(h, 0)[3]
+    finally:
+        B.dlf_net_destroy(h)
 
 
 # ----------------------------------------------------------------------------------------------

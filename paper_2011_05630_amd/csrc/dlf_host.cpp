@@ -14,6 +14,7 @@
 #include <vector>
 
 #include "../../include/dlf.h"
+#include "../../include/dlf_debug.h"
 #include "dlf_internal.h"
 
 // Workspace of dlf_run_noalloc: a file-scope device array, one copy per GPU the library runs on, held

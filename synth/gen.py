@@ -27,9 +27,10 @@ def weight_shape(L):
     return None
 
 
-def make_params(net, batch, seed=MASTER_SEED):
+def make_params(net, batch, seed=MASTER_SEED, residual_gain=RESIDUAL_BRANCH_GAIN):
     """Returns (x, weights, biases): x fp16 [batch,H,W,C]; weights[i] fp16 or None; biases[i]
-    fp32 or None."""
+    fp32 or None.  residual_gain scales the weights of layers that add a residual (1.0 = plain
+    He-normal)."""
     rng = np.random.Generator(np.random.PCG64(seed))
     shape = (batch, net["in_h"], net["in_w"], net["in_c"])
     if net.get("input_dist", "normal") == "uniform":
@@ -47,7 +48,7 @@ def make_params(net, batch, seed=MASTER_SEED):
         fan_in = ws[1] * ws[2] * ws[3]
         std = np.float32(np.sqrt(2.0 / fan_in))
         if L["residual_from"] >= 0:
-            std = np.float32(std * RESIDUAL_BRANCH_GAIN)
+            std = np.float32(std * residual_gain)
         w = rng.standard_normal(size=ws, dtype=np.float32) * std
         weights.append(w.astype(np.float16))
         if L["has_bias"]:

@@ -177,6 +177,26 @@ def test_other_evaluated_networks_small_batch():
         _net_case(net, 2, [0, 1], False, _plans(net)[:1])
 
 
+def test_residual_network_with_plain_he_normal_branch_weights():
+    """The synthetic residual networks scale the last convolution of every branch by 0.25; here the
+    same network with the plain He-normal draw (activations grow with every block, the residual sums
+    are large against the branch results), where the kernels' order of operations in the residual
+    epilogue -- round the branch result to fp16, add, round -- is furthest from the oracle's single
+    fp32 add."""
+    from oracle import oracle as o
+    net = nets.resnet18()
+    x, ws, bs = gen.make_params(net, 2, residual_gain=1.0)
+    ref = o.run_net(net, x, ws, bs)
+    assert np.abs(ref).max() < 6e4
+    s = _session(net, 2, ws, bs)
+    try:
+        got = s.run_numpy(x)
+        compare(got, ref, "resnet18 b2, residual branch gain 1.0")
+        _check_groups(s, net, x, ws, bs)
+    finally:
+        s.close()
+
+
 def test_run_is_repeatable_and_async_on_a_side_stream():
     from oracle import oracle as o
     net = nets.chain4(32, 28)
