@@ -161,9 +161,14 @@ def group_accounting(net, batch, session):
         wbytes = sum(rows[i]["wbytes"] for i in range(f, l + 1))
         in_layer, res_layer = B.dlf_plan_group_io(session.plan, g)
         byts = rows[f]["in_bytes"] + rows[l]["out_bytes"] + wbytes
-        if res_layer >= -1:
-            byts += rows[l]["out_bytes"] if res_layer < 0 else rows[res_layer]["out_bytes"]
         cfg = B.dlf_plan_group_config(session.plan, g)
+        if cfg["kind"] == 8:
+            # projection + last 1x1 layer of a residual block: both inputs (of a strided projection
+            # the pixels it uses), one output
+            st = net["layers"][f]["stride"]
+            byts = rows[f]["in_bytes"] // (st * st) + rows[l]["in_bytes"] + rows[l]["out_bytes"] + wbytes
+        elif res_layer >= -1:
+            byts += rows[l]["out_bytes"] if res_layer < 0 else rows[res_layer]["out_bytes"]
         if cfg["kind"] == 1:
             kname = "k_fc"
         elif cfg["kind"] == 3:
@@ -178,6 +183,8 @@ def group_accounting(net, batch, session):
             kname = "k_dwpw<%d>" % cfg["variant"]
         elif cfg["kind"] == 7:
             kname = "k_dwt<%d>" % (cfg["variant"] + 1)
+        elif cfg["kind"] == 8:
+            kname = PW_NAME[cfg["variant"]] + "+proj"
         else:
             kname = VARIANT_NAME[cfg["variant"]]
         out.append(dict(first=f, last=l, budget=info["budget"], flops=flops, bytes=byts, flops3x3=flops3x3,

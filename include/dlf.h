@@ -170,7 +170,8 @@ int32_t dlf_plan_group_stream(const dlf_plan_t* plan, int32_t g);
 dlf_status dlf_run_profiled(const dlf_plan_t* plan, const void* in_dev, void* out_dev,
                             void* hip_stream, int32_t reps, float* group_ms);
 /* Runs only group g: in_dev = the group's input tensor, out_dev = its output tensor; a residual
- * operand produced outside the group is read from res_dev (may be NULL if the group has none). */
+ * operand produced outside the group (for a group of kind 8: its second input) is read from
+ * res_dev (may be NULL if the group has none). */
 dlf_status dlf_run_group(const dlf_plan_t* plan, int32_t g, const void* in_dev, const void* res_dev,
                          void* out_dev, void* hip_stream);
 /* Device address inside the bound workspace of the output of layer i, or NULL if that tensor is
@@ -188,7 +189,10 @@ const void* dlf_plan_layer_output(const dlf_plan_t* plan, int32_t layer);
  * depthwise kernel: a single depthwise 3x3 layer (variant = stride - 1), 6 fused depthwise 3x3 +
  * 1x1 kernel: a depthwise layer and the pointwise layer behind it, the depthwise result held in
  * registers (variant = 32-channel blocks of a wave's work item, 2 or 4), 7 depthwise + 1x1 tile
- * kernel: the same pair, the depthwise result of a pixel tile held in LDS (variant = stride - 1);
+ * kernel: the same pair, the depthwise result of a pixel tile held in LDS (variant = stride - 1),
+ * 8 two 1x1 convolutions into one output (the projection shortcut of a residual block and the
+ * block's last layer, variant = block form as for kind 3; the group reads two tensors, reported by
+ * dlf_plan_group_io as input = the last layer's input, residual = the projection's input);
  * channel slices, channels
  * per slice, whether stage 0 streams its input, LDS bytes per workgroup.  Any out pointer may be
  * NULL. */

@@ -154,7 +154,7 @@ dlf_status pack_and_upload(Layer& L)
 // Fusion groups
 // ------------------------------------------------------------------------------------------
 
-enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3, GK_C3 = 4, GK_DW = 5, GK_DWPW = 6, GK_DWT = 7 };
+enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3, GK_C3 = 4, GK_DW = 5, GK_DWPW = 6, GK_DWT = 7, GK_PW2 = 8 };
 
 struct TileCfg {
     int th, tw;      // tile of the group's final output tensor
@@ -784,6 +784,45 @@ uint64_t pw_cost_ps(const Layer& L, int batch, int budget, int& shape)
     return best;
 }
 
+// ---- two 1x1 convolutions into one output: the projection shortcut of a residual block and the
+// block's last 1x1 layer, out = act(conv(y) + conv_proj(x)), as one launch of the block pointwise kernel
+// whose K loop runs over both operand pairs ----
+
+// layers [first, last] = [projection, last 1x1]: the projection (no activation, read by nothing
+// else) is the residual operand of the layer behind it, which reads a tensor from outside
+bool pw2_eligible(const dlf_net_s& net, int first, int last, int batch)
+{
+    if (last != first + 1) return false;
+    const Layer& P = net.L[first];
+    const Layer& Q = net.L[last];
+    if (!pw_eligible(P, batch) || !pw_eligible(Q, batch)) return false;
+    if (Q.d.residual_from != first || Q.src >= first || P.d.residual_from >= 0 || P.d.act != DLF_ACT_NONE) return false;
+    if (P.out_h != Q.out_h || P.out_w != Q.out_w || P.d.cout != Q.d.cout || Q.d.stride != 1) return false;
+    for (size_t k = 0; k < net.L.size(); ++k) {
+        if ((int)k != last && net.L[k].d.residual_from == first) return false;
+        if (net.L[k].src == first) return false;
+    }
+    return true;
+}
+
+uint64_t pw2_cost_ps(const Layer& P, const Layer& Q, int batch, int budget, int shape)
+{
+    const int64_t FCs = PW_FC[shape], FPs = PW_FP[shape], W = PW_WAVES_PER_CU[shape];
+    const int64_t m = (int64_t)batch * Q.out_h * Q.out_w;
+    const int64_t nsteps = P.nsteps + Q.nsteps;
+    const int64_t items = ((m + 32 * FPs - 1) / (32 * FPs)) * ((Q.ncb + FCs - 1) / FCs);
+    const int64_t items_cu = (items + budget - 1) / budget;
+    const int64_t rounds = (items_cu + W - 1) / W;
+    const int64_t frag_bytes = items_cu * nsteps * (FCs + FPs) * 1024;
+    const int64_t compute = rounds * C_PWB_BLOCK + frag_bytes / PWB_BYTES_PER_CYCLE;
+    // a strided projection uses one pixel in stride^2 of its input, but fetches the lines of every
+    // second pixel of every second row
+    const int64_t in2 = (int64_t)batch * P.in_h * P.in_w * P.d.cin * 2 / P.d.stride;
+    const int64_t bytes = m * Q.d.cin * 2 + in2 + m * Q.d.cout * 2 + (int64_t)Q.ncb * nsteps * 1024;
+    const int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
+    return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
+}
+
 // ---- block 3x3 kernel (one 3x3 stride-1 pad-1 convolution, optionally with its folded 2x2 pool) ----
 
 // Testing hook: mode 0 = the block kernel competes with the fused-group kernel on modelled cost,
@@ -1068,6 +1107,34 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
     const C3Force& c3f = c3_force ? *c3_force : g_c3_force;
     if (first < 0 || last >= (int)net.L.size() || first > last || budget <= 0)
         return fail(DLF_ERR_INVALID_ARG, "bad group [%d,%d] budget %d", first, last, budget);
+    if (pwm != 2 && force.th <= 0 && pw2_eligible(net, first, last, batch)) {
+        const Layer& P = net.L[first];
+        const Layer& Q = net.L[last];
+        const int shape = Q.ncb >= 3 ? 3 : 4;
+        g = GroupPlan();
+        g.first = first; g.last = last; g.budget = budget;
+        g.in_layer = Q.src;                  // the 1x1 layer's input ...
+        g.res_layer = P.src; g.res_stage = 0;   // ... and the projection's, handed over like a residual operand
+        DlfPwArgs& wa = g.wa;
+        memset(&wa, 0, sizeof wa);
+        wa.w = Q.d_w; wa.bias = Q.d_bias;
+        wa.m = batch * Q.out_h * Q.out_w;
+        wa.cin = Q.d.cin; wa.cout = Q.d.cout; wa.ncb = Q.ncb; wa.nsteps = Q.nsteps;
+        wa.act = Q.d.act; wa.stride = 1;
+        wa.in_h = Q.in_h; wa.in_w = Q.in_w; wa.out_h = Q.out_h; wa.out_w = Q.out_w;
+        wa.n_pg = ceil_div(wa.m, 32 * PW_FP[shape]); wa.n_cg = ceil_div(Q.ncb, PW_FC[shape]);
+        wa.nitems = wa.n_pg * wa.n_cg;
+        wa.w2 = P.d_w; wa.bias2 = P.d_bias; wa.cin2 = P.d.cin; wa.nsteps2 = P.nsteps; wa.stride2 = P.d.stride;
+        wa.in_h2 = P.in_h; wa.in_w2 = P.in_w;
+        g.kind = GK_PW2;
+        g.cost = pw2_cost_ps(P, Q, batch, budget, shape);
+        g.variant = shape;
+        g.occ = 2;
+        g.grid = std::max(8, std::min(budget * 2, ceil_div(wa.nitems, 8) * 8) / 8 * 8);
+        g.th = 1; g.tw = 32 * PW_FP[shape];
+        g.lds_bytes = shape == 3 ? DLF_PWB_LDS_BYTES(2, 2) : DLF_PWB_LDS_BYTES(1, 4);
+        return DLF_OK;
+    }
     std::vector<StageSpec> specs;
     std::string why;
     int kind;
@@ -1711,7 +1778,7 @@ dlf_status dlf_plan(const dlf_net_t* net, int32_t batch, const dlf_tuner_opts* o
     }
     for (const GroupPlan& G : groups) {
         const bool in_ok = G.in_layer < 0 || plan->layer_off[G.in_layer] != (size_t)-1;
-        const bool res_ok = G.res_stage < 0 || plan->layer_off[G.res_layer] != (size_t)-1;
+        const bool res_ok = G.res_stage < 0 || G.res_layer < 0 || plan->layer_off[G.res_layer] != (size_t)-1;
         if (!in_ok || !res_ok) {
             delete plan;
             return fail(DLF_ERR_INFEASIBLE, "group [%d,%d] reads a tensor that is not the output of an earlier group",
@@ -1824,6 +1891,12 @@ static dlf_status launch_one(const dlf_plan_s* plan, const GroupPlan& G, const v
         DlfGapArgs pa = G.pa;
         pa.x = in; pa.y = out;
         e = dlf_launch_gap(&pa, stream);
+    } else if (G.kind == GK_PW2) {
+        DlfPwArgs wa = G.wa;
+        wa.in = in; wa.out = out;
+        if (!res) return fail(DLF_ERR_INVALID_ARG, "group [%d,%d] needs its second input", G.first, G.last);
+        wa.in2 = res;
+        e = dlf_launch_pw(&wa, G.variant, G.grid, stream);
     } else if (G.kind == GK_PW) {
         DlfPwArgs wa = G.wa;
         wa.in = in; wa.out = out;
@@ -1881,7 +1954,7 @@ static void group_pointers(const dlf_plan_s* plan, size_t g, const void* in_dev,
 {
     const GroupPlan& G = plan->G[g];
     *in = G.in_layer < 0 ? in_dev : plan->ws + plan->layer_off[G.in_layer];
-    *res = G.res_stage >= 0 ? plan->ws + plan->layer_off[G.res_layer] : nullptr;
+    *res = G.res_stage < 0 ? nullptr : G.res_layer < 0 ? in_dev : plan->ws + plan->layer_off[G.res_layer];
     *out = (g + 1 == plan->G.size()) ? out_dev : (void*)(plan->ws + plan->layer_off[G.last]);
 }
 
@@ -1945,7 +2018,7 @@ dlf_status dlf_plan_refine(dlf_plan_t* plan, const void* in_dev, void* out_dev, 
     int nchanged = 0;
     for (size_t g = 0; g < plan->G.size() && rs == DLF_OK; ++g) {
         const GroupPlan cur = plan->G[g];
-        if (cur.kind == GK_FC || cur.kind == GK_GAP) continue;
+        if (cur.kind == GK_FC || cur.kind == GK_GAP || cur.kind == GK_PW2) continue;
         const void *in, *res;
         void* out;
         group_pointers(plan, g, in_dev, out_dev, &in, &res, &out);
@@ -2109,7 +2182,7 @@ dlf_status dlf_run(const dlf_plan_t* plan, const void* in_dev, void* out_dev, vo
         const GroupPlan& G = plan->G[g];
         const void* in = G.in_layer < 0 ? in_dev : plan->ws + plan->layer_off[G.in_layer];
         const void* res = nullptr;
-        if (G.res_stage >= 0) res = plan->ws + plan->layer_off[G.res_layer];
+        if (G.res_stage >= 0) res = G.res_layer < 0 ? in_dev : plan->ws + plan->layer_off[G.res_layer];
         void* out = (g + 1 == ng) ? out_dev : (void*)(plan->ws + plan->layer_off[G.last]);
         hipStream_t st = main_s;
         if (any_side) {
@@ -2173,7 +2246,7 @@ dlf_status dlf_run_noalloc(const dlf_plan_t* plan, const void* in_dev, void* out
     for (size_t g = 0; g < ng; ++g) {
         const GroupPlan& G = plan->G[g];
         const void* in = G.in_layer < 0 ? in_dev : ws + plan->layer_off[G.in_layer];
-        const void* res = G.res_stage >= 0 ? ws + plan->layer_off[G.res_layer] : nullptr;
+        const void* res = G.res_stage < 0 ? nullptr : G.res_layer < 0 ? in_dev : ws + plan->layer_off[G.res_layer];
         void* out = (g + 1 == ng) ? out_dev : (void*)(ws + plan->layer_off[G.last]);
         s = launch_one(plan, G, in, res, out, hip_stream, ws);
         if (s != DLF_OK) return s;

@@ -112,6 +112,14 @@ struct DlfPwArgs {
     int32_t stride, in_h, in_w, out_h, out_w;
     int32_t n_pg, n_cg;   // groups of 64 (32) pixels, groups of 64 (32) output channels
     int32_t nitems;       // n_pg * n_cg
+    // Second operand pair (block forms only; nsteps2 = 0: none): a second 1x1 convolution with the
+    // same output shape whose result is added before the activation -- the projection shortcut of a
+    // residual block run as further K steps of the same accumulators, out = act(w . in + bias +
+    // w2 . in2 + bias2), instead of a tensor written to memory and read back as a residual.
+    const void* in2;      // [batch][in_h2][in_w2][cin2] fp16
+    const void* w2;       // packed fragments
+    const float* bias2;   // padded to ncb*32
+    int32_t cin2, nsteps2, stride2, in_h2, in_w2;
 };
 
 // 3x3 stride-1 pad-1 convolution as a block kernel (one layer, optionally with the 2x2 max pool

@@ -1392,6 +1392,10 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
         const int cb = min(wcg * 2 + f, a.ncb - 1);
 #pragma unroll
         for (int q = 0; q < 4; ++q) bias[f][q] = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
+        if (a.nsteps2 > 0) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) bias[f][q] += *(const f4v*)(a.bias2 + cb * 32 + q * 8 + lhi * 4);
+        }
     }
 
     // ... and so does the residual operand of the wave's part (8 lanes cover the 64 channels of a
@@ -1410,33 +1414,48 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
             }
     }
 
-    // this wave's loads of a stage: fragments wave, wave + 4, ...
+    // this wave's loads of a stage: fragments wave, wave + 4, ...; src2: the same for the second
+    // operand pair, which the stream of stages switches to after the first pair's K steps
     const half_t* src[LPW];
+    const half_t* src2[LPW];
+    auto operand_ptrs = [&](const half_t* wbase, const half_t* ibase, int nsteps, int cin, int stride, int in_h,
+                            int in_w, const half_t* (&sp)[LPW]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < LPW; ++i) {
-        const int f = wave + DLF_PW_WAVES * i;
-        if (DLF_PW_WAVES * i < NA) {
-            const int cbl = f / KS, ks = f - cbl * KS;
-            const int cb = min(cg * (2 * WN) + cbl, a.ncb - 1);
-            src[i] = (const half_t*)a.w + ((size_t)cb * a.nsteps + ks) * 512 + lane * 8;
-        } else {
-            const int j = f - NA;
-            const int pbl = j / KS, ks = j - pbl * KS;
-            int pix = (pg * (2 * WM) + pbl) * 32 + l32;
-            pix = pix < a.m ? pix : a.m - 1;          // clamped lanes compute a result nobody stores
-            unsigned off;
-            if (a.stride == 1) {
-                off = (unsigned)pix * (unsigned)a.cin;
+        for (int i = 0; i < LPW; ++i) {
+            const int f = wave + DLF_PW_WAVES * i;
+            if (DLF_PW_WAVES * i < NA) {
+                const int cbl = f / KS, ks = f - cbl * KS;
+                const int cb = min(cg * (2 * WN) + cbl, a.ncb - 1);
+                sp[i] = wbase + ((size_t)cb * nsteps + ks) * 512 + lane * 8;
             } else {
-                const int hw = a.out_h * a.out_w;
-                const int n = pix / hw, r = pix - n * hw;
-                const int oy = r / a.out_w, ox = r - oy * a.out_w;
-                off = (unsigned)(((n * a.in_h + oy * a.stride) * a.in_w + ox * a.stride) * a.cin);
+                const int j = f - NA;
+                const int pbl = j / KS, ks = j - pbl * KS;
+                int pix = (pg * (2 * WM) + pbl) * 32 + l32;
+                pix = pix < a.m ? pix : a.m - 1;          // clamped lanes compute a result nobody stores
+                unsigned off;
+                if (stride == 1) {
+                    off = (unsigned)pix * (unsigned)cin;
+                } else {
+                    const int hw = a.out_h * a.out_w;
+                    const int n = pix / hw, r = pix - n * hw;
+                    const int oy = r / a.out_w, ox = r - oy * a.out_w;
+                    off = (unsigned)(((n * in_h + oy * stride) * in_w + ox * stride) * cin);
+                }
+                sp[i] = ibase + off + ks * 16 + lhi * 8;
             }
-            src[i] = (const half_t*)a.in + off + ks * 16 + lhi * 8;
         }
-    }
+    };
+    operand_ptrs((const half_t*)a.w, (const half_t*)a.in, a.nsteps, a.cin, a.stride, a.in_h, a.in_w, src);
+    const int KT1 = a.nsteps / KS;
+    if (a.nsteps2 > 0)
+        operand_ptrs((const half_t*)a.w2, (const half_t*)a.in2, a.nsteps2, a.cin2, a.stride2, a.in_h2, a.in_w2, src2);
+    int nissued = 0;
     auto issue = [&](int slot) {
+        if (nissued == KT1) {            // uniform; only pointers move under this condition, no load
+#pragma unroll
+            for (int i = 0; i < LPW; ++i) src[i] = src2[i];
+        }
+        ++nissued;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             half_t* dst = lds + slot * STAGE + (wave + DLF_PW_WAVES * i) * 512;
@@ -1445,7 +1464,7 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
             src[i] += (DLF_PW_WAVES * i < NA) ? KS * 512 : KS * 16;
         }
     };
-    const int KT = a.nsteps / KS;
+    const int KT = (a.nsteps + a.nsteps2) / KS;
 #pragma unroll
     for (int t = 0; t < NST - 1; ++t)
         if (t < KT) issue(t);
@@ -2687,6 +2706,10 @@ extern "C" int dlf_launch_fc(const DlfFcArgs* a, void* stream)
 extern "C" int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stream)
 {
     if (grid <= 0) return (int)hipErrorInvalidValue;
+    // a second operand pair: block forms only, whole stages of K steps, both operands present
+    if (a->nsteps2 != 0 && ((shape != 3 && shape != 4) || a->nsteps2 < 0 || (a->nsteps2 % DLF_PWB_KS) != 0 ||
+                            a->in2 == nullptr || a->w2 == nullptr || a->bias2 == nullptr || a->res != nullptr))
+        return (int)hipErrorInvalidValue;
     if (shape == 0)
         launch(k_pw<2, 2, 6, 2>, dim3(grid), dim3(DLF_PW_WAVES * 64),
                            (size_t)(DLF_PW_WAVES * 64 * (64 + 8) * 2), (hipStream_t)stream, *a);

@@ -423,6 +423,46 @@ def test_dw_pw_fused_and_unfused():
     compare(got, ref, "dw, pw separate")
 
 
+@pytest.mark.parametrize("stride,cin,width,hw,batch", [(1, 64, 64, 28, 2), (2, 256, 128, 28, 3), (2, 64, 32, 15, 2),
+                                                     (1, 32, 32, 9, 5), (2, 512, 256, 14, 2)])
+def test_projection_shortcut_fused_into_the_last_pointwise_layer(stride, cin, width, hw, batch):
+    """A bottleneck block with a projection shortcut: the projection and the block's last 1x1 layer
+    as one group whose K loop runs over both operand pairs (kind 8), against the same block with the
+    projection written to memory and added as a residual."""
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    from oracle import oracle as o
+    announce("projection + 1x1", stride, cin, width, hw, batch)
+    cout = 4 * width
+    layers = [nets.conv(cin, width, 1, 1, 0, "relu"), nets.conv(width, width, 3, stride, 1, "relu"),
+              nets.conv(cin, cout, 1, stride, 0, "none", input_from=-1),
+              nets.conv(width, cout, 1, 1, 0, "relu", input_from=1, residual_from=2)]
+    layers[2]["input_from"] = -1
+    net = _mk([nets.conv(cin, cin, 1, 1, 0, "relu")] + [dict(L) for L in layers], hw, hw + 1, cin, dist="normal")
+    # indices shift by one: the block reads layer 0
+    net["layers"][3]["input_from"] = 0
+    net["layers"][4]["input_from"] = 2
+    net["layers"][4]["residual_from"] = 3
+    x, ws, bs = gen.make_params(net, batch, 12, residual_gain=1.0)
+    ref = o.run_net(net, x, ws, bs)
+    outs = {}
+    for name, lasts, mode in (("fused", [0, 1, 2, 4], 1), ("separate", [0, 1, 2, 3, 4], 2)):
+        B.dlf_debug_pointwise_mode(mode)
+        try:
+            s = Session(net, batch, ws, bs, **_manual(5, lasts))
+        finally:
+            B.dlf_debug_pointwise_mode(0)
+        try:
+            kinds = [B.dlf_plan_group_config(s.plan, g)["kind"] for g in range(len(s.groups))]
+            assert (kinds[-1] == 8) == (name == "fused"), kinds
+            if name == "fused":
+                assert B.dlf_plan_group_io(s.plan, len(s.groups) - 1) == (2, 0)
+            outs[name] = s.run_numpy(x)
+        finally:
+            s.close()
+        compare(outs[name], ref, "projection %s" % name)
+
+
 def test_fc_and_global_avgpool():
     announce("gap + fc")
     layers = [nets.conv(16, 64, 3, 1, 1, "relu"), nets.gavgpool(64), nets.fc(64, 1000, "none")]

@@ -348,9 +348,24 @@ def test_manual_plan_and_workspace():
 
 def test_residual_groups_read_their_operand_from_outside():
     r = nets.resnet50()
-    net = _sub(r, 0, 5)
+    net = _sub(r, 0, 5)              # stem, pool, 1x1, 3x3, projection, 1x1 + projection result
     h = _handle(net)
+    # the projection shortcut and the block's last layer as one group of two 1x1 convolutions that
+    # reads both their inputs (the planner's choice here) ...
     p = B.dlf_plan(h, 2)
+    gs = B.dlf_plan_groups(p)
+    last = len(gs) - 1
+    assert (gs[last]["first"], gs[last]["last"]) == (4, 5)
+    assert B.dlf_plan_group_config(p, last)["kind"] == 8
+    assert B.dlf_plan_group_io(p, last) == (3, 1)       # the 3x3 layer's output, the block input
+    B.dlf_plan_destroy(p)
+    # ... and, with the pointwise kernels switched off, the last layer adding the projection's
+    # result from memory: a residual operand is never produced inside the group that adds it
+    B.dlf_debug_pointwise_mode(2)
+    try:
+        p = B.dlf_plan(h, 2)
+    finally:
+        B.dlf_debug_pointwise_mode(0)
     gs = B.dlf_plan_groups(p)
     last = len(gs) - 1
     assert gs[last]["last"] == 5
