@@ -184,7 +184,7 @@ def group_accounting(net, batch, session):
         elif cfg["kind"] == 7:
             kname = "k_dwt<%d>" % (cfg["variant"] + 1)
         elif cfg["kind"] == 8:
-            kname = PW_NAME[cfg["variant"]] + "+proj"
+            kname = PW_NAME[cfg["variant"]]          # the same kernel, with a second operand pair
         else:
             kname = VARIANT_NAME[cfg["variant"]]
         out.append(dict(first=f, last=l, budget=info["budget"], flops=flops, bytes=byts, flops3x3=flops3x3,
