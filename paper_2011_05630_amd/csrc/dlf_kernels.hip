@@ -1338,9 +1338,11 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 // one-wave-per-item form: a workgroup of four waves computes 64 * WN output channels x 64 * WM
 // pixels (2 x 2 or 1 x 4 waves, each a 64 x 64 part), and the block's operands pass through LDS, so
 // every byte fetched from L2 feeds WM (weights) or WN (activations) waves.
-//   Global -> LDS: 16-byte direct loads (no registers in between); a wave's 64 lanes deposit one
-//     1 KiB MFMA fragment, lane l at byte 16 l -- for weights the packed fragment as it lies in
-//     memory, for activations lane (pixel l % 32, K half l / 32) fetches its own 16 bytes.
+//   Global -> LDS: 16-byte direct loads (no registers in between); a wave's 64 lanes deposit
+//     1 KiB, lane l at byte 16 l -- for weights one packed MFMA fragment as it lies in memory, for
+//     activations 2 KS adjacent lanes fetch the stage's 32 KS bytes of one pixel, so that a request
+//     covers whole runs of memory (16-byte pieces of many different cache lines cost a CU several
+//     times their size in intake).
 //   LDS is a ring of NST stages of KS K steps; stage t + NST - 1 is requested when stage t is
 //     about to be multiplied.  Loads retire in issue order: "at most n x loads-per-stage
 //     outstanding" means that all but the wave's last n requested stages have landed, and the
@@ -1358,6 +1360,8 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
     constexpr int NA = 2 * WN * KS, NB = 2 * WM * KS, NF = NA + NB;   // fragments per stage
     constexpr int LPW = NF / DLF_PW_WAVES;                            // loads per wave per stage
     constexpr int STAGE = NF * 512;                                   // halfs per stage
+    constexpr int LPX = 2 * KS, PPI = 64 / LPX;      // activation loads: lanes per pixel, pixels per instruction
+    static_assert(KS == 2 || KS == 4, "a pixel's part of a stage is 64 or 128 bytes: 4 or 8 lanes");
     static_assert(WN * WM == DLF_PW_WAVES && NA % DLF_PW_WAVES == 0 && NB % DLF_PW_WAVES == 0, "fragment roles are per wave");
     static_assert(KS % 2 == 0 && NST >= 4, "two register sets alternate per K step; one stage is read ahead");
     constexpr int ROW = 64 + 8;
@@ -1428,9 +1432,14 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
                 const int cb = min(cg * (2 * WN) + cbl, a.ncb - 1);
                 sp[i] = wbase + ((size_t)cb * nsteps + ks) * 512 + lane * 8;
             } else {
+                // instruction `sub` of 32-pixel block pbl: PPI pixels, LPX adjacent lanes fetching
+                // the stage's 32 * KS bytes of one pixel (a whole run of memory per pixel, not a
+                // 32-byte piece of it); the 16-byte parts are stored permuted, see actb_off
                 const int j = f - NA;
-                const int pbl = j / KS, ks = j - pbl * KS;
-                int pix = (pg * (2 * WM) + pbl) * 32 + l32;
+                const int pbl = j / KS, sub = j - pbl * KS;
+                const int pl = sub * PPI + lane / LPX;
+                const int q = (lane & (LPX - 1)) ^ ((pl / (16 / LPX)) & (LPX - 1));
+                int pix = (pg * (2 * WM) + pbl) * 32 + pl;
                 pix = pix < a.m ? pix : a.m - 1;          // clamped lanes compute a result nobody stores
                 unsigned off;
                 if (stride == 1) {
@@ -1441,7 +1450,7 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
                     const int oy = r / a.out_w, ox = r - oy * a.out_w;
                     off = (unsigned)(((n * in_h + oy * stride) * in_w + ox * stride) * cin);
                 }
-                sp[i] = ibase + off + ks * 16 + lhi * 8;
+                sp[i] = ibase + off + q * 8;
             }
         }
     };
@@ -1480,16 +1489,24 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
     // Stage t is multiplied while the fragments of the next K step -- the last one of a stage
     // reads ahead into stage t + 1 -- are on their way from LDS, so stage t + 1 must be visible
     // when iteration t starts: NST - 3 requested stages stay in flight behind it.
+    // A 32-pixel block of a stage lies in LDS as [pixel][32 * KS bytes]; part q (16 bytes: K step
+    // q / 2, K half q % 2) of pixel p sits at position q ^ f(p), f(p) = (p / (16 / LPX)) % LPX, so
+    // that the 16 lanes LDS serves per cycle -- 16 consecutive pixels, one part each -- fall into
+    // 16 different 16-byte bank groups.
+    int actb_off[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+        actb_off[ks] = l32 * (KS * 16) + (((2 * ks + lhi) ^ ((l32 / (16 / LPX)) & (LPX - 1))) << 3);
     auto read_frags = [&](const half_t* sb, int ks, h8 (&af)[2], h8 (&bf)[2]) {
 #pragma unroll
-        for (int f = 0; f < 2; ++f) af[f] = *(const h8*)(sb + ((wn * 2 + f) * KS + ks) * 512);
+        for (int f = 0; f < 2; ++f) af[f] = *(const h8*)(sb + ((wn * 2 + f) * KS + ks) * 512 + lane * 8);
 #pragma unroll
-        for (int p = 0; p < 2; ++p) bf[p] = *(const h8*)(sb + (NA + (wm * 2 + p) * KS + ks) * 512);
+        for (int p = 0; p < 2; ++p) bf[p] = *(const h8*)(sb + (NA + (wm * 2 + p) * KS) * 512 + actb_off[ks]);
     };
     h8 af[2][2], bf[2][2];
     if (KT > NST - 2) wait_vmcnt<(NST - 2) * LPW>(); else wait_vmcnt<0>();
     asm volatile("s_barrier" ::: "memory");
-    read_frags(lds + lane * 8, 0, af[0], bf[0]);
+    read_frags(lds, 0, af[0], bf[0]);
     int slot = 0;
     for (int kt = 0; kt < KT; ++kt) {
         const int nslot = slot + 1 == NST ? 0 : slot + 1;
@@ -1499,8 +1516,8 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
         }
         asm volatile("s_barrier" ::: "memory");
         if (kt + NST - 1 < KT) issue(slot == 0 ? NST - 1 : slot - 1);
-        const half_t* sb = lds + slot * STAGE + lane * 8;
-        const half_t* nb = lds + nslot * STAGE + lane * 8;
+        const half_t* sb = lds + slot * STAGE;
+        const half_t* nb = lds + nslot * STAGE;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;
