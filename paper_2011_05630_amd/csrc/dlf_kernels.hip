@@ -1334,6 +1334,28 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// An LDS read issued as an instruction (16 bytes per lane at byte address addr + OFF), invisible to
+// the compiler's own wait insertion: the value may be used only behind an lds_arrive that covers it.
+template <int OFF> __device__ __forceinline__ h8 lds_read16(unsigned addr)
+{
+    h8 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+// Waits until at most N LDS reads of the wave are outstanding (they return in order) and passes the
+// four fragments through, so that their users depend on the wait.
+template <int N> __device__ __forceinline__ void lds_arrive(h8& a, h8& b, h8& c, h8& d)
+{
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+}
+template <int I, int N, typename F> __device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>());
+        static_for<I + 1, N>(f);
+    }
+}
+
 // Block form of the pointwise kernel, for layers whose operand traffic from L2 bounds the
 // one-wave-per-item form: a workgroup of four waves computes 64 * WN output channels x 64 * WM
 // pixels (2 x 2 or 1 x 4 waves, each a 64 x 64 part), and the block's operands pass through LDS, so
@@ -1497,16 +1519,28 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
         actb_off[ks] = l32 * (KS * 16) + (((2 * ks + lhi) ^ ((l32 / (16 / LPX)) & (LPX - 1))) << 3);
-    auto read_frags = [&](const half_t* sb, int ks, h8 (&af)[2], h8 (&bf)[2]) {
+    // The fragment reads are written as instructions, with their waits: while a direct-to-LDS load
+    // is pending the compiler turns every wait for an LDS read into a wait for all of them, the
+    // ones just issued for the next K step included (one full LDS round trip per step).  LDS reads
+    // return in order, so "at most 4 outstanding" behind the 4 requests of the next step means the
+    // current step's fragments have arrived; lds_arrive hands them to the MFMAs (a data dependence:
+    // nothing that uses them can move above the wait).
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) half_t*)lds;
+    const unsigned a_addr = lds0 + (unsigned)(((wn * 2) * KS * 512 + lane * 8) * 2);
+    unsigned b_addr[KS];
 #pragma unroll
-        for (int f = 0; f < 2; ++f) af[f] = *(const h8*)(sb + ((wn * 2 + f) * KS + ks) * 512 + lane * 8);
-#pragma unroll
-        for (int p = 0; p < 2; ++p) bf[p] = *(const h8*)(sb + (NA + (wm * 2 + p) * KS) * 512 + actb_off[ks]);
+    for (int ks = 0; ks < KS; ++ks) b_addr[ks] = lds0 + (unsigned)(((NA + (wm * 2) * KS) * 512 + actb_off[ks]) * 2);
+    auto request = [&](unsigned slot_bytes, auto kc, h8 (&af)[2], h8 (&bf)[2]) __attribute__((always_inline)) {
+        constexpr int K = decltype(kc)::value;
+        af[0] = lds_read16<(0 * KS + K) * 1024>(a_addr + slot_bytes);
+        af[1] = lds_read16<(1 * KS + K) * 1024>(a_addr + slot_bytes);
+        bf[0] = lds_read16<(0 * KS) * 1024>(b_addr[K] + slot_bytes);
+        bf[1] = lds_read16<(1 * KS) * 1024>(b_addr[K] + slot_bytes);
     };
     h8 af[2][2], bf[2][2];
     if (KT > NST - 2) wait_vmcnt<(NST - 2) * LPW>(); else wait_vmcnt<0>();
     asm volatile("s_barrier" ::: "memory");
-    read_frags(lds, 0, af[0], bf[0]);
+    request(0u, std::integral_constant<int, 0>(), af[0], bf[0]);
     int slot = 0;
     for (int kt = 0; kt < KT; ++kt) {
         const int nslot = slot + 1 == NST ? 0 : slot + 1;
@@ -1516,21 +1550,25 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
         }
         asm volatile("s_barrier" ::: "memory");
         if (kt + NST - 1 < KT) issue(slot == 0 ? NST - 1 : slot - 1);
-        const half_t* sb = lds + slot * STAGE;
-        const half_t* nb = lds + nslot * STAGE;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const int cur = ks & 1, nxt = cur ^ 1;
-            if (ks + 1 < KS) read_frags(sb, ks + 1, af[nxt], bf[nxt]);
-            else if (kt + 1 < KT) read_frags(nb, 0, af[nxt], bf[nxt]);
+        const unsigned sb = (unsigned)(slot * STAGE * 2), nb = (unsigned)(nslot * STAGE * 2);
+        static_for<0, KS>([&](auto kc) __attribute__((always_inline)) {
+            constexpr int K = decltype(kc)::value, cur = K & 1, nxt = cur ^ 1;
+            // (behind the last stage the read-ahead takes stale fragments nobody multiplies)
+            if constexpr (K + 1 < KS) request(sb, std::integral_constant<int, K + 1>(), af[nxt], bf[nxt]);
+            else request(nb, std::integral_constant<int, 0>(), af[nxt], bf[nxt]);
+            lds_arrive<4>(af[cur][0], af[cur][1], bf[cur][0], bf[cur][1]);
 #pragma unroll
             for (int f = 0; f < 2; ++f)
 #pragma unroll
                 for (int p = 0; p < 2; ++p)
                     acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][f], bf[cur][p], acc[f][p], 0, 0, 0);
-        }
+            __builtin_amdgcn_sched_barrier(0);
+        });
         slot = nslot;
     }
+    // the read-ahead of the last step lands in registers nobody reads: it must have landed before
+    // they are used for anything else
+    lds_arrive<0>(af[0][0], af[0][1], bf[0][0], bf[0][1]);
     // every wave is done with the ring (all loads were waited for above): reuse it
     asm volatile("s_barrier" ::: "memory");
     half_t* tb = lds + wave * (64 * ROW);
