@@ -842,7 +842,8 @@ bool c3_eligible(const dlf_net_s& net, const std::vector<StageSpec>& specs, int 
     const dlf_layer_desc& d = L.d;
     if (d.op != DLF_CONV || d.kh != 3 || d.kw != 3 || d.stride != 1 || d.pad != 1) return false;
     if (L.im2col || L.rowfold || (d.cin % 32) != 0 || (d.cout % 8) != 0) return false;
-    if ((int64_t)batch * L.in_h * L.in_w * L.in_c >= (int64_t)1 << 31) return false;
+    // the input is read through a buffer resource whose range check supplies the padding: below 2 GiB
+    if ((int64_t)batch * L.in_h * L.in_w * L.in_c * 2 >= (int64_t)1 << 31) return false;
     if ((int64_t)batch * L.out_h * L.out_w * L.out_c >= (int64_t)1 << 31) return false;
     return true;
 }
@@ -860,10 +861,12 @@ bool c3_build(int pool2, int cin, int shape, int th, int tw, int max_lds, C3Cfg&
     c.na_i = ceil_div(c.npxh, 512 / ach);
     c.lpw_a = ceil_div(c.na_i, DLF_C3_LOAD_WAVES);
     if (c.lpw_a > DLF_C3_MAX_ACT_LOADS) return false;
+    // ... and, behind the spare KiB, the requesting waves' table of halo-pixel offsets (4 bytes per pixel)
     const int act = 2 * c.na_i * 1024, wstage = 9 * 2 * wc * 1024;
-    c.nst = std::min(4, (max_lds - 1024 - act) / wstage);
+    const int tab = (c.lpw_a * DLF_C3_LOAD_WAVES * (512 / ach) * 4 + 255) / 256 * 256;
+    c.nst = std::min(4, (max_lds - 1024 - tab - act) / wstage);
     if (c.nst < 2) return false;
-    c.lds_bytes = std::max(act + c.nst * wstage + 1024, (int)DLF_C3_EPI_BYTES);
+    c.lds_bytes = std::max(act + c.nst * wstage + 1024 + tab, (int)DLF_C3_EPI_BYTES);
     return c.lds_bytes <= max_lds;
 }
 

@@ -28,6 +28,33 @@ typedef unsigned u2v __attribute__((ext_vector_type(2)));
 
 extern __shared__ __attribute__((aligned(16))) half_t lds[];
 
+// A byte offset no tensor reaches (the host keeps tensors that are read through buffer resources
+// below 2 GiB): a buffer load at this offset fails the hardware's range check and returns zeros.
+#define DLF_OOB ((int)0x80000000)
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ i32x4 raw_buffer_load_x4(i32x4 rsrc, int voffset, int soffset, int aux) __asm("llvm.amdgcn.raw.buffer.load.v4i32");
+__device__ __forceinline__ i32x4 make_rsrc(const void* p, unsigned bytes)
+{
+    const unsigned long long a = (unsigned long long)p;
+    i32x4 r;
+    r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
+    r.y = __builtin_amdgcn_readfirstlane((int)((unsigned)(a >> 32) & 0xffffu));   // stride 0: raw buffer
+    r.z = __builtin_amdgcn_readfirstlane((int)bytes);                              // bytes that may be read
+    r.w = 0x00020000;                                                              // 32-bit raw data
+    return r;
+}
+
+
+// 16 bytes per lane of the packed weights, read through a buffer resource: address = base +
+// 16 * lane + a uniform byte offset (a scalar register).  The per-lane part never changes, so a
+// wave's walk through its fragments is scalar arithmetic only.  (A per-lane 64-bit pointer would be
+// stepped with 64-bit vector instructions, and those get a slot on a SIMD only when its matrix
+// pipe pauses: under MFMA load the weight stream of such a loop runs at a fraction of its rate.)
+__device__ __forceinline__ h8 wfrag(const i32x4 rw, int lane16, unsigned soff)
+{
+    return __builtin_bit_cast(h8, raw_buffer_load_x4(rw, lane16, (int)soff, 0));
+}
+
 __device__ __forceinline__ float apply_act(float v, int act)
 {
     if (act >= 1) v = fmaxf(v, 0.0f);
@@ -376,8 +403,8 @@ template <int TAPS, int FC, int FP, bool LEAN> struct RingSize {
 };
 
 template <int FC, int FP, int TAPS, int RA>
-__device__ __forceinline__ void mma_chunk(const half_t* src, const int (&pbase)[FP],
-                                          const h8* (&wp)[FC], h8 (&ar)[RA][FC],
+__device__ __forceinline__ void mma_chunk(const half_t* src, const int (&pbase)[FP], const i32x4 rw, int lane16,
+                                          unsigned (&wo)[FC], h8 (&ar)[RA][FC],
                                           f16v (&acc)[FC][FP], int cs, int iw, int kw, int ntaps)
 {
     static_assert(RA == 2 || (TAPS == 9 && 18 % RA == 0), "ring depths this loop is written for");
@@ -418,14 +445,14 @@ __device__ __forceinline__ void mma_chunk(const half_t* src, const int (&pbase)[
                         if (f == FC - 1 && p == FP - 1) {
 #pragma unroll
                             for (int f2 = 0; f2 < FC; ++f2)
-                                ar[sidx][f2] = wp[f2][(2 * t + ks + RA) * 64];
+                                ar[sidx][f2] = wfrag(rw, lane16, wo[f2] + (2 * t + ks + RA) * 1024);
                         }
                         __builtin_amdgcn_sched_barrier(0);
                     }
             }
         }
 #pragma unroll
-        for (int f = 0; f < FC; ++f) wp[f] += 18 * 64;
+        for (int f = 0; f < FC; ++f) wo[f] += 18 * 1024;
     } else {
         h8 b0[FP], b1[FP];
 #pragma unroll
@@ -442,7 +469,7 @@ __device__ __forceinline__ void mma_chunk(const half_t* src, const int (&pbase)[
                 for (int p = 0; p < FP; ++p)
                     acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[0][f], b0[p], acc[f][p], 0, 0, 0);
 #pragma unroll
-            for (int f = 0; f < FC; ++f) ar[0][f] = wp[f][128];
+            for (int f = 0; f < FC; ++f) ar[0][f] = wfrag(rw, lane16, wo[f] + 2 * 1024);
             tapoff += cs;
             if (++kwc == kw) { kwc = 0; tapoff += rowskip; }
             if (t + 1 < nt) {
@@ -455,7 +482,7 @@ __device__ __forceinline__ void mma_chunk(const half_t* src, const int (&pbase)[
                 for (int p = 0; p < FP; ++p)
                     acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[1][f], b1[p], acc[f][p], 0, 0, 0);
 #pragma unroll
-            for (int f = 0; f < FC; ++f) { ar[1][f] = wp[f][192]; wp[f] += 128; }
+            for (int f = 0; f < FC; ++f) { ar[1][f] = wfrag(rw, lane16, wo[f] + 3 * 1024); wo[f] += 2 * 1024; }
         }
     }
 }
@@ -632,6 +659,8 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
     // KSP builds of the kernel carry this form; in the others ksplit is the constant 1.
     const int ksplit = (KSP && !STREAM) ? max(st.ksplit, 1) : 1;    // a power of two
     const int ks_shift = __builtin_ctz(ksplit);
+    const i32x4 rw = make_rsrc(st.w, 0xffffffffu);       // every offset the streams form lies inside the packed weights
+    const int lane16 = lane * 16;
     const int kpart = wave & (ksplit - 1);
     const int iwave = wave >> ks_shift;
     const int items_per_pass = MMA_WAVES >> ks_shift;
@@ -657,11 +686,12 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
         }
         const int rounds_mine = nrounds / ksplit;           // the host guarantees divisibility
         const int round_first = kpart * rounds_mine;
-        const h8* wp[FC];
+        // the wave's weight streams: uniform byte offsets into the packed weights (below 4 GiB)
+        unsigned wo[FC];
 #pragma unroll
         for (int f = 0; f < FC; ++f) {
             const int cb = min(cb_begin + cg * FC + f, cb_end - 1);
-            wp[f] = (const h8*)st.w + ((size_t)cb * st.nsteps + (size_t)round_first * cpr * ntaps * 2) * 64 + lane;
+            wo[f] = (unsigned)__builtin_amdgcn_readfirstlane((cb * st.nsteps + round_first * cpr * ntaps * 2) * 1024);
         }
         // accumulators start at the bias of their output channel (in the item's first wave)
         f16v acc[FC][FP];
@@ -684,7 +714,7 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
 #pragma unroll
         for (int i = 0; i < RA; ++i)
 #pragma unroll
-            for (int f = 0; f < FC; ++f) ar[i][f] = wp[f][i * 64];
+            for (int f = 0; f < FC; ++f) ar[i][f] = wfrag(rw, lane16, wo[f] + i * 1024);
 
         if (STREAM && first_pass) {
             __syncthreads();          // round 0 is in LDS
@@ -697,14 +727,14 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
                 if constexpr (TAPS == 1) {
                     int j = 0;
                     for (; j + 1 < cpr; j += 2) {
-                        mma_chunk<FC, FP, 1, RA>(src + j * 32, pbase, wp, ar, acc, cs, st.iw, 1, 1);
-                        mma_chunk<FC, FP, 1, RA>(src + j * 32 + 32, pbase, wp, ar, acc, cs, st.iw, 1, 1);
+                        mma_chunk<FC, FP, 1, RA>(src + j * 32, pbase, rw, lane16, wo, ar, acc, cs, st.iw, 1, 1);
+                        mma_chunk<FC, FP, 1, RA>(src + j * 32 + 32, pbase, rw, lane16, wo, ar, acc, cs, st.iw, 1, 1);
                     }
                     if (j < cpr)
-                        mma_chunk<FC, FP, 1, RA>(src + j * 32, pbase, wp, ar, acc, cs, st.iw, 1, 1);
+                        mma_chunk<FC, FP, 1, RA>(src + j * 32, pbase, rw, lane16, wo, ar, acc, cs, st.iw, 1, 1);
                 } else {
                     for (int j = 0; j < cpr; ++j)
-                        mma_chunk<FC, FP, TAPS, RA>(src + j * 32, pbase, wp, ar, acc, cs, st.iw, st.kw,
+                        mma_chunk<FC, FP, TAPS, RA>(src + j * 32, pbase, rw, lane16, wo, ar, acc, cs, st.iw, st.kw,
                                                 ntaps);
                 }
             }
@@ -1334,6 +1364,25 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// Direct-to-LDS load of 16 bytes per lane, lane l from base + off into LDS at dst + 16 l, in the
+// instruction's scalar-base form: `base` (uniform) in a scalar register pair, `off` a 32-bit lane
+// offset, `dst` (uniform) through M0.  A request then costs the wave no vector ALU instruction.
+// Written as an instruction because the compiler, given the same address as base + off, folds it
+// into a 64-bit vector-register pointer per request.  Counted by vmcnt like any load; the compiler
+// does not see it.  (The kernels that use it keep their uniform values within the scalar register
+// file: a spilled `base` cannot be named by the instruction.  tests/test_build.py checks the
+// generated code for that.)
+__device__ __forceinline__ void dma16s(const void* base, unsigned off, unsigned dst)
+{
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(dst) : "memory", "m0");
+}
+// The same load through the compiler's own instruction selection (any register class for base).
+__device__ __forceinline__ void dma16(const void* base, unsigned off, half_t* dst)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)((const char*)base + off),
+                                     (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+}
+
 // An LDS read issued as an instruction (16 bytes per lane at byte address addr + OFF), invisible to
 // the compiler's own wait insertion: the value may be used only behind an lds_arrive that covers it.
 template <int OFF> __device__ __forceinline__ h8 lds_read16(unsigned addr)
@@ -1347,6 +1396,14 @@ template <int OFF> __device__ __forceinline__ h8 lds_read16(unsigned addr)
 template <int N> __device__ __forceinline__ void lds_arrive(h8& a, h8& b, h8& c, h8& d)
 {
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+}
+template <int N> __device__ __forceinline__ void lds_arrive1(h8& a)
+{
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N));
+}
+template <int N> __device__ __forceinline__ void lds_arrive2(h8& a, h8& b)
+{
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
 }
 template <int I, int N, typename F> __device__ __forceinline__ void static_for(F&& f)
 {
@@ -1375,7 +1432,7 @@ template <int I, int N, typename F> __device__ __forceinline__ void static_for(F
 //   Epilogue as in k_pw, through a wave-private transpose buffer that reuses the ring.
 // One block per workgroup; consecutive blocks (same pixels, next channels) are dealt to the same
 // XCD so that they meet in its L2.
-template <int WN, int WM>
+template <int WN, int WM, bool P2>
 __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
 {
     constexpr int KS = DLF_PWB_KS, NST = DLF_PWB_STAGES;
@@ -1387,7 +1444,9 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
     static_assert(WN * WM == DLF_PW_WAVES && NA % DLF_PW_WAVES == 0 && NB % DLF_PW_WAVES == 0, "fragment roles are per wave");
     static_assert(KS % 2 == 0 && NST >= 4, "two register sets alternate per K step; one stage is read ahead");
     constexpr int ROW = 64 + 8;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) half_t*)lds;
     // blockIdx.x % 8 is the XCD: give each XCD a contiguous range of blocks (the grid is a
     // multiple of 8; a workgroup takes every (gridDim.x / 8)-th block of its XCD's range)
     const int per_xcd = (a.nitems + 7) >> 3;
@@ -1418,7 +1477,7 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
         const int cb = min(wcg * 2 + f, a.ncb - 1);
 #pragma unroll
         for (int q = 0; q < 4; ++q) bias[f][q] = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
-        if (a.nsteps2 > 0) {
+        if (P2) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) bias[f][q] += *(const f4v*)(a.bias2 + cb * 32 + q * 8 + lhi * 4);
         }
@@ -1440,19 +1499,25 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
             }
     }
 
-    // this wave's loads of a stage: fragments wave, wave + 4, ...; src2: the same for the second
-    // operand pair, which the stream of stages switches to after the first pair's K steps
-    const half_t* src[LPW];
-    const half_t* src2[LPW];
-    auto operand_ptrs = [&](const half_t* wbase, const half_t* ibase, int nsteps, int cin, int stride, int in_h,
-                            int in_w, const half_t* (&sp)[LPW]) __attribute__((always_inline)) {
+    // This wave's loads of a stage: fragments wave, wave + 4, ...  Every load is "uniform base +
+    // 32-bit lane offset" (dma16): the bases live in scalar registers and move by scalar adds, the
+    // lane offsets are fixed for the block, so that a request costs the wave no vector ALU
+    // instruction -- on a SIMD whose matrix pipe another wave keeps busy a wave gets a vector ALU
+    // slot only every few dozen cycles, and requests that need one each arrive at a quarter of
+    // the rate.  Weight fragments: base = the fragment, offset 16 * lane.  Activations: base = the
+    // tensor + the stage's channel offset, offset = the lane's pixel and 16-byte part.  base2 /
+    // off2: the same for the second operand pair, which the stream of stages switches to after the
+    // first pair's K steps.
+    unsigned off[LPW], off2[LPW];
+    auto operand_offsets = [&](int nsteps, int cin, int stride, int in_h, int in_w, unsigned (&op)[LPW])
+                               __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             const int f = wave + DLF_PW_WAVES * i;
             if (DLF_PW_WAVES * i < NA) {
                 const int cbl = f / KS, ks = f - cbl * KS;
                 const int cb = min(cg * (2 * WN) + cbl, a.ncb - 1);
-                sp[i] = wbase + ((size_t)cb * nsteps + ks) * 512 + lane * 8;
+                op[i] = (unsigned)((cb * nsteps + ks) * 1024 + lane * 16);   // packed weights: < 4 GiB
             } else {
                 // instruction `sub` of 32-pixel block pbl: PPI pixels, LPX adjacent lanes fetching
                 // the stage's 32 * KS bytes of one pixel (a whole run of memory per pixel, not a
@@ -1463,39 +1528,48 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
                 const int q = (lane & (LPX - 1)) ^ ((pl / (16 / LPX)) & (LPX - 1));
                 int pix = (pg * (2 * WM) + pbl) * 32 + pl;
                 pix = pix < a.m ? pix : a.m - 1;          // clamped lanes compute a result nobody stores
-                unsigned off;
+                unsigned o;
                 if (stride == 1) {
-                    off = (unsigned)pix * (unsigned)cin;
+                    o = (unsigned)pix * (unsigned)cin;
                 } else {
                     const int hw = a.out_h * a.out_w;
                     const int n = pix / hw, r = pix - n * hw;
                     const int oy = r / a.out_w, ox = r - oy * a.out_w;
-                    off = (unsigned)(((n * in_h + oy * stride) * in_w + ox * stride) * cin);
+                    o = (unsigned)(((n * in_h + oy * stride) * in_w + ox * stride) * cin);
                 }
-                sp[i] = ibase + off + q * 8;
+                op[i] = (o + (unsigned)q * 8u) * 2u;      // bytes; a tensor is smaller than 4 GiB
             }
         }
     };
-    operand_ptrs((const half_t*)a.w, (const half_t*)a.in, a.nsteps, a.cin, a.stride, a.in_h, a.in_w, src);
+    operand_offsets(a.nsteps, a.cin, a.stride, a.in_h, a.in_w, off);
     const int KT1 = a.nsteps / KS;
-    if (a.nsteps2 > 0)
-        operand_ptrs((const half_t*)a.w2, (const half_t*)a.in2, a.nsteps2, a.cin2, a.stride2, a.in_h2, a.in_w2, src2);
+    if (P2) operand_offsets(a.nsteps2, a.cin2, a.stride2, a.in_h2, a.in_w2, off2);
+    // the two bases of the stage being requested (weights, activations), for either operand pair
+    const half_t* wb = (const half_t*)a.w;
+    const half_t* ib = (const half_t*)a.in;
+    const half_t* wb2 = P2 ? (const half_t*)a.w2 : nullptr;
+    const half_t* ib2 = P2 ? (const half_t*)a.in2 : nullptr;
     int nissued = 0;
     auto issue = [&](int slot) {
-        if (nissued == KT1) {            // uniform; only pointers move under this condition, no load
-#pragma unroll
-            for (int i = 0; i < LPW; ++i) src[i] = src2[i];
-        }
-        ++nissued;
+        const bool first = !P2 || nissued < KT1;                   // uniform
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            half_t* dst = lds + slot * STAGE + (wave + DLF_PW_WAVES * i) * 512;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src[i],
-                                             (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
-            src[i] += (DLF_PW_WAVES * i < NA) ? KS * 512 : KS * 16;
+            const half_t* b = (DLF_PW_WAVES * i < NA) ? (first ? wb : wb2) : (first ? ib : ib2);
+            // (with two operand pairs the kernel's uniform values no longer fit the scalar register
+            // file, and the compiler chooses the registers of the address)
+            if constexpr (P2) dma16(b, first ? off[i] : off2[i], lds + slot * STAGE + (wave + DLF_PW_WAVES * i) * 512);
+            else dma16s(b, off[i], lds0 + (unsigned)((slot * STAGE + (wave + DLF_PW_WAVES * i) * 512) * 2));
         }
+        if (first) {
+            wb += KS * 512;
+            ib += KS * 16;
+        } else {
+            wb2 += KS * 512;
+            ib2 += KS * 16;
+        }
+        ++nissued;
     };
-    const int KT = (a.nsteps + a.nsteps2) / KS;
+    const int KT = (a.nsteps + (P2 ? a.nsteps2 : 0)) / KS;
 #pragma unroll
     for (int t = 0; t < NST - 1; ++t)
         if (t < KT) issue(t);
@@ -1525,7 +1599,6 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
     // return in order, so "at most 4 outstanding" behind the 4 requests of the next step means the
     // current step's fragments have arrived; lds_arrive hands them to the MFMAs (a data dependence:
     // nothing that uses them can move above the wait).
-    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) half_t*)lds;
     const unsigned a_addr = lds0 + (unsigned)(((wn * 2) * KS * 512 + lane * 8) * 2);
     unsigned b_addr[KS];
 #pragma unroll
@@ -1691,9 +1764,8 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
     const int act_halfs = na_i * 512;
     half_t* const wring = lds + 2 * act_halfs;
     half_t* const trash = wring + nst * W_HALFS;
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) half_t*)lds;
     const int KT = a.cin >> 4, NB = a.cin / ACH;
-    const half_t* const inp = (const half_t*)a.in;
-    const half_t* const zsrc = (const half_t*)a.w + (size_t)a.ncb * a.nsteps * 512 + lane * 8;
     const unsigned pw_m = div_magic(pw);
     const unsigned tw_m = div_magic(a.pool2 ? a.tw >> 1 : a.tw);
     const half_t* resp = (const half_t*)a.res;
@@ -1722,8 +1794,27 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
 
     // Load side: the item whose operands are being requested.  The first stages of item i + 1 are
     // requested before the epilogue of item i, so that they arrive while it runs.
+    // A request must cost the requesting wave as little vector arithmetic as possible: its SIMD's
+    // matrix pipe is kept busy by the other wave, a vector ALU instruction gets a slot only every
+    // few dozen cycles, and loads that need address arithmetic in vector registers arrive at a
+    // quarter of the rate the memory pipe could take them.
+    //   weights: uniform base (scalar arithmetic) + 16 * lane, the scalar-base form of the load;
+    //   activations: the byte offset of a halo pixel is the same for all of an item's channel
+    //     blocks: it is computed once per item into a table in LDS (wave-private: no barrier), and
+    //     a request is one 4-byte LDS read, one 32-bit add of the lane's 16-byte part, and a buffer
+    //     load (32-bit offsets) whose scalar offset selects the block; pixels outside the image
+    //     hold an offset beyond the tensor, for which the hardware's range check delivers zeros
+    //     (the padding arrives as data, without a source of zeros in memory).  The part a lane
+    //     fetches, (lane % LPP) ^ f(halo pixel), is the same in all of a wave's instructions:
+    //     instruction wave + LW i starts at halo pixel (wave + LW i) PPI, and LW (PPI >> SH) is a
+    //     multiple of LPP.
     int cg = 0, n = 0, ty0 = 0, tx0 = 0;
-    const half_t* wsrc[LPW_W];
+    static_assert(((LW * (PPI >> SH)) % LPP) == 0 && (PPI % (1 << SH)) == 0, "the permuted part of a lane is the same in all of a wave's load instructions");
+    unsigned* const atab = (unsigned*)(trash + 512) + wave * PPI + lane / LPP;   // pixel entry of load i at atab[i * LW * PPI]
+    const unsigned part16 =
+        (unsigned)(((lane & (LPP - 1)) ^ ((wave * (PPI >> SH) + ((lane / LPP) >> SH)) & (LPP - 1))) << 4);
+    const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)a.in, 0, (int)((unsigned)(a.batch * a.h * a.w_) * (unsigned)a.cin * 2u), 0x00020000);
     auto setup = [&](int item) __attribute__((always_inline)) {
         cg = item / a.ntiles;
         int t = item - cg * a.ntiles;
@@ -1733,46 +1824,43 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
         n = t / a.tiles_y;
         ty0 = ty * a.th;
         tx0 = tx * a.tw;
-        // this wave's weight loads of a stage: fragments wave, wave + 8, ... (tap-major)
-#pragma unroll
-        for (int i = 0; i < LPW_W; ++i) {
-            const int fi = wave + LW * i;
-            wsrc[i] = zsrc;
-            if (fi < NWF) {
-                const int tap = fi / NCBW, cbi = fi - tap * NCBW;
-                const int cb = min(cg * NCBW + cbi, a.ncb - 1);
-                wsrc[i] = (const half_t*)a.w + ((size_t)cb * a.nsteps + tap * 2) * 512 + lane * 8;
+        if (wave < LW) {
+            // instruction j = wave + LW * i covers PPI halo pixels x LPP parts
+#pragma unroll 1
+            for (int i = 0; i < lpa; ++i) {
+                const int j = wave + LW * i;
+                const int hpx = j * PPI + lane / LPP;
+                unsigned off = DLF_OOB;
+                if (hpx < npxh) {
+                    const int hy = div_by(hpx, pw_m), hx = hpx - hy * pw;
+                    const int gy = ty0 - 1 + hy, gx = tx0 - 1 + hx;
+                    if (gy >= 0 && gy < a.h && gx >= 0 && gx < a.w_)
+                        off = (unsigned)(((n * a.h + gy) * a.w_ + gx) * a.cin) * 2u;
+                }
+                atab[i * (LW * PPI)] = off;       // (the LPP lanes of a pixel write the same value)
             }
         }
     };
-    // one weight load (the wave's i-th of stage c, into ring slot `slot`) / one activation load
-    // (its i-th of block b)
+    // one weight load (the wave's i-th of stage c, into ring slot `slot`): fragment fi = wave +
+    // LW * i (tap-major) of the block's channels, K chunk c
+    const unsigned lane16 = (unsigned)lane * 16u;
     auto issue_w1 = [&](int i, int c, int slot) __attribute__((always_inline)) {
         const int fi = wave + LW * i;
-        const int woff = ((c >> 1) * 18 + (c & 1)) * 512;    // stage c = 16-channel chunk c
-        half_t* dst = fi < NWF ? wring + slot * W_HALFS + fi * 512 : trash;
-        const half_t* src = fi < NWF ? wsrc[i] + woff : zsrc;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                         (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+        const int tap = fi / NCBW, cbi = fi - tap * NCBW;
+        const int cb = min(cg * NCBW + cbi, a.ncb - 1);
+        const int ks = (c >> 1) * 18 + tap * 2 + (c & 1);       // stage c = 16-channel chunk c of tap `tap`
+        const bool real = fi < NWF;                             // uniform; surplus loads re-read the first fragment
+        const half_t* base = (const half_t*)a.w + (real ? (size_t)(cb * a.nsteps + ks) * 512 : (size_t)0);
+        const unsigned dst = lds0 + (unsigned)((real ? 2 * act_halfs + slot * W_HALFS + fi * 512
+                                                     : 2 * act_halfs + nst * W_HALFS) * 2);
+        dma16s(base, lane16, dst);
     };
-    // activation load i of the wave for block b: instruction j = wave + LW * i covers PPI halo
-    // pixels x LPP parts; the lane's 16 bytes, or zeros for a pixel outside the image (the offsets
-    // are formed anew each time: a wave that requests is waiting on the memory pipe anyway)
+    // one activation load (the wave's i-th of block b)
     auto issue_a1 = [&](int i, int b) __attribute__((always_inline)) {
         const int j = wave + LW * i;
         half_t* dst = j < na_i ? lds + (b & 1) * act_halfs + j * 512 : trash;
-        const half_t* src = zsrc;
-        const int hpx = j * PPI + lane / LPP;
-        if (hpx < npxh) {
-            const int hy = div_by(hpx, pw_m), hx = hpx - hy * pw;
-            const int gy = ty0 - 1 + hy, gx = tx0 - 1 + hx;
-            if (gy >= 0 && gy < a.h && gx >= 0 && gx < a.w_) {
-                const int q = (lane & (LPP - 1)) ^ ((hpx >> SH) & (LPP - 1));
-                src = inp + (unsigned)(((n * a.h + gy) * a.w_ + gx) * a.cin + q * 8 + b * ACH);
-            }
-        }
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                         (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rin, (__attribute__((address_space(3))) void*)dst, 16,
+                                                 atab[i * (LW * PPI)] + part16, b * (ACH * 2), 0, 0);
     };
     auto issue_w = [&](int c, int slot) __attribute__((always_inline)) {
 #pragma unroll
@@ -1839,11 +1927,13 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
                 if (do_w) issue_w(c + nst - 1, nslot);
                 if (do_a) issue_a(blk + 1);
             }
-            const half_t* wf = wring + slot * W_HALFS + (wc * 2) * 512 + lane * 8;
-            const half_t* ab = lds + (blk & 1) * act_halfs;
+            const unsigned wf = lds0 + (unsigned)((2 * act_halfs + slot * W_HALFS + (wc * 2) * 512 + lane * 8) * 2);
+            const unsigned ab = lds0 + (unsigned)(((blk & 1) * act_halfs) * 2);
             const int q = 2 * kq + lhi;
-            // halo pixel h, part q: h * ACH halfs + 8 * (q ^ f(h))
-            auto b_at = [&](int h) __attribute__((always_inline)) { return ab + h * ACH + ((((h >> SH) & (LPP - 1)) ^ q) << 3); };
+            // halo pixel h, part q: byte address of h * ACH halfs + 8 * (q ^ f(h))
+            auto b_at = [&](int h) __attribute__((always_inline)) {
+                return ab + (unsigned)((h * ACH + ((((h >> SH) & (LPP - 1)) ^ q) << 3)) * 2);
+            };
             // (with four pixel blocks the empty asm keeps the compiler from precomputing the tap
             // addresses of a stage outside the K loop, which costs two registers per tap and pixel
             // block; with two blocks there is room, and three instructions per address less)
@@ -1853,43 +1943,47 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
                 h[p] = hp0[p];
                 if (FP > 2) asm volatile("" : "+v"(h[p]));
             }
+            // Fragment reads are issued as instructions and waited for by count (LDS reads return
+            // in order; while a direct-to-LDS load is pending the compiler would turn every wait
+            // into a wait for all reads, the newest included).  Request order of a tap: A0, B0,
+            // B1 .. B(FP-1), A1 -- the order its MFMAs need them -- each request of tap t + 1
+            // placed behind an MFMA of tap t.  Before MFMA (f, p) of tap t the reads that may still
+            // be outstanding are the tap's own later ones plus what has been requested of tap
+            // t + 1 so far: FP before (0, 0); FP + 1 before (0, p > 0) and (1, 0); at the last tap,
+            // with nothing requested behind it, FP - p and 0.
             h8 af[2][2], bf[2][FP];
+            af[0][0] = lds_read16<0>(wf);
 #pragma unroll
-            for (int f = 0; f < 2; ++f) af[0][f] = *(const h8*)(wf + f * 512);
-#pragma unroll
-            for (int p = 0; p < FP; ++p) bf[0][p] = *(const h8*)b_at(h[p]);
-            // A wave issues in order: each LDS read of the next tap's fragments is placed behind an
-            // MFMA of the current tap and is served while that MFMA occupies the matrix pipe; the
-            // scheduling barriers keep exactly this order.
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int tap = 0; tap < 9; ++tap) {
-                const int cur = tap & 1, nxt = cur ^ 1;
+            for (int p = 0; p < FP; ++p) bf[0][p] = lds_read16<0>(b_at(h[p]));
+            af[0][1] = lds_read16<1024>(wf);
+            static_for<0, 9>([&](auto tc) __attribute__((always_inline)) {
+                constexpr int tap = decltype(tc)::value, cur = tap & 1, nxt = cur ^ 1;
+                constexpr bool more = tap + 1 < 9;
                 const int toff = ((tap + 1) / 3) * pw + ((tap + 1) % 3);
-                const half_t* nb[FP];
+                unsigned nb[FP];
 #pragma unroll
-                for (int p = 0; p < FP; ++p) nb[p] = b_at(h[p] + toff);
+                for (int p = 0; p < FP; ++p) nb[p] = more ? b_at(h[p] + toff) : 0u;
                 __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int f = 0; f < 2; ++f)
-#pragma unroll
-                    for (int p = 0; p < FP; ++p) {
-                        acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][f], bf[cur][p], acc[f][p], 0, 0, 0);
-                        if (tap + 1 < 9) {
-                            // behind the first FP + 1 MFMAs, in the order the next tap needs them
-                            const int kk = f * FP + p;
-                            if (kk == 0) {
-                                af[nxt][0] = *(const h8*)(wf + ((tap + 1) * NCBW) * 512);
-                                bf[nxt][0] = *(const h8*)nb[0];
-                            } else if (kk < FP) {
-                                bf[nxt][kk] = *(const h8*)nb[kk];
-                            } else if (kk == FP) {
-                                af[nxt][1] = *(const h8*)(wf + ((tap + 1) * NCBW + 1) * 512);
-                            }
+                lds_arrive2<FP>(af[cur][0], bf[cur][0]);
+                static_for<0, 2 * FP>([&](auto kc) __attribute__((always_inline)) {
+                    constexpr int kk = decltype(kc)::value, f = kk / FP, p = kk % FP;
+                    if constexpr (f == 0 && p > 0) lds_arrive1<more ? FP + 1 : FP - p>(bf[cur][p]);
+                    if constexpr (f == 1 && p == 0) lds_arrive1<more ? FP + 1 : 0>(af[cur][1]);
+                    acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][f], bf[cur][p], acc[f][p], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if constexpr (more) {
+                        if constexpr (kk == 0) {
+                            af[nxt][0] = lds_read16<((tap + 1) * NCBW) * 1024>(wf);
+                            bf[nxt][0] = lds_read16<0>(nb[0]);
+                        } else if constexpr (kk < FP) {
+                            bf[nxt][kk] = lds_read16<0>(nb[kk]);
+                        } else if constexpr (kk == FP) {
+                            af[nxt][1] = lds_read16<((tap + 1) * NCBW + 1) * 1024>(wf);
                         }
-                        __builtin_amdgcn_sched_barrier(0);
                     }
-            }
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+            });
             slot = slot + 1 == nst ? 0 : slot + 1;
         }
         // every wave is done with the ring and the buffers (all loads were waited for above)
@@ -1984,20 +2078,6 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
 // loads of padding positions into zeros (an offset beyond the tensor returns 0: no branch, no
 // select).  Offsets are bytes; DLF_OOB is an offset no tensor reaches (the host keeps tensors
 // below 2 GiB on these paths).
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-__device__ i32x4 raw_buffer_load_x4(i32x4 rsrc, int voffset, int soffset, int aux) __asm("llvm.amdgcn.raw.buffer.load.v4i32");
-#define DLF_OOB ((int)0x80000000)
-__device__ __forceinline__ i32x4 make_rsrc(const void* p, unsigned bytes)
-{
-    const unsigned long long a = (unsigned long long)p;
-    i32x4 r;
-    r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
-    r.y = __builtin_amdgcn_readfirstlane((int)((unsigned)(a >> 32) & 0xffffu));   // stride 0: raw buffer
-    r.z = __builtin_amdgcn_readfirstlane((int)bytes);                              // bytes that may be read
-    r.w = 0x00020000;                                                              // 32-bit raw data
-    return r;
-}
-
 // Mixed-precision multiply-add on one half of two packed fp16 pairs: c + a.lo * b.lo / c + a.hi * b.hi
 // in fp32.  Written out because the compiler, given (float)a * (float)b + c in a loop that reuses b,
 // converts b to fp32 once and keeps it there: twice the registers and a conversion per operand.
@@ -2776,11 +2856,11 @@ extern "C" int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stre
                            (size_t)(DLF_PWSK_PART_BYTES + DLF_PW_WAVES * 32 * (32 + 8) * 2),
                            (hipStream_t)stream, *a);
     else if (shape == 3)
-        launch(k_pwb<2, 2>, dim3(grid), dim3(DLF_PW_WAVES * 64), (size_t)DLF_PWB_LDS_BYTES(2, 2),
-               (hipStream_t)stream, *a);
+        launch(a->nsteps2 != 0 ? k_pwb<2, 2, true> : k_pwb<2, 2, false>, dim3(grid), dim3(DLF_PW_WAVES * 64),
+               (size_t)DLF_PWB_LDS_BYTES(2, 2), (hipStream_t)stream, *a);
     else if (shape == 4)
-        launch(k_pwb<1, 4>, dim3(grid), dim3(DLF_PW_WAVES * 64), (size_t)DLF_PWB_LDS_BYTES(1, 4),
-               (hipStream_t)stream, *a);
+        launch(a->nsteps2 != 0 ? k_pwb<1, 4, true> : k_pwb<1, 4, false>, dim3(grid), dim3(DLF_PW_WAVES * 64),
+               (size_t)DLF_PWB_LDS_BYTES(1, 4), (hipStream_t)stream, *a);
     else
         return (int)hipErrorInvalidValue;
     return (int)hipGetLastError();

@@ -532,14 +532,14 @@ def test_conv_k_split_over_waves(cin, cout, hw, ks, tile, var, nsl, sc, kh, stri
 
 
 @pytest.mark.parametrize("cin,cout,h,w,batch,shape,th,tw,pool,act,res", [
-    (64, 128, 20, 24, 2, 1, 8, 32, 0, "relu", 0),      # ragged tiles in both directions, one activation block
+    (64, 128, 20, 24, 2, 1, 8, 28, 0, "relu", 0),      # ragged tiles in both directions, one activation block
     (32, 64, 16, 16, 1, 2, 16, 32, 0, "none", 0),      # tile wider than the map, two weight stages only
     (128, 72, 14, 14, 3, 0, 14, 16, 0, "relu6", 0),    # ragged channel group, 196 of 256 pixels
     (64, 64, 12, 12, 2, 3, 8, 8, 1, "relu", 0),        # folded 2x2 pool, small tiles
     (96, 200, 28, 28, 2, 0, 8, 28, 1, "relu", 0),      # folded pool, ragged channels and rows, three blocks
     (64, 64, 30, 30, 2, 1, 16, 16, 0, "relu", 1),      # residual operand
     (256, 256, 14, 14, 2, 2, 14, 32, 0, "relu", 1),    # long K: ring and buffers wrap many times
-    (256, 128, 14, 14, 2, 1, 8, 32, 0, "relu", 0),     # 64-channel blocks, four of them, two-stage ring
+    (256, 128, 14, 14, 2, 1, 8, 28, 0, "relu", 0),     # 64-channel blocks, four of them, two-stage ring
     (192, 64, 9, 9, 1, 3, 4, 14, 0, "relu", 0),        # 64-channel blocks, three of them
     (32, 32, 5, 5, 1, 0, 2, 4, 0, "relu", 0),          # tiny tiles: one activation load per block
     (64, 160, 40, 36, 2, 4, 16, 32, 0, "relu", 0),     # 128 x 512 blocks: ragged tiles and channel groups
