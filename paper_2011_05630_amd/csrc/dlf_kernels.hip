@@ -568,7 +568,7 @@ template <int FC, int FP, bool STREAM, int TAPS, bool LEAN, bool KSP>
 __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage& st, int n,
                                            int ty0, int tx0, int slice, bool defer_act)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
     const int npix = st.rh * st.rw;
     const int npb = (npix + 31) >> 5;
@@ -1084,7 +1084,7 @@ __global__ __launch_bounds__(DLF_WG_THREADS, MINW) void k_group(const DlfGroupAr
 // Shapes: (2,2) with D = 4 for large layers (each operand byte feeds two MFMAs); (1,1) with D = 8
 // where the layer has too few 64 x 64 items to occupy the chip (small feature maps, long K).
 template <int FP>
-__device__ __forceinline__ void pw_item_setup(const DlfPwArgs& a, int item, int lane, const half_t* (&bp)[FP],
+__device__ __forceinline__ void pw_item_setup(const DlfPwArgs& a, int item, int lane, int (&bo)[FP],
                                               int& pg, int& cg)
 {
     const int l32 = lane & 31, lhi = lane >> 5;
@@ -1103,7 +1103,7 @@ __device__ __forceinline__ void pw_item_setup(const DlfPwArgs& a, int item, int 
             const int oy = r / a.out_w, ox = r - oy * a.out_w;
             off = (unsigned)(((n * a.in_h + oy * a.stride) * a.in_w + ox * a.stride) * a.cin);
         }
-        bp[p] = (const half_t*)a.in + off + lhi * 8;
+        bo[p] = (int)((off + lhi * 8) * 2u);       // byte offset of the lane's 16 bytes of K step 0
     }
 }
 
@@ -1113,7 +1113,10 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, MINB) void k_pw(const DlfPwArgs 
     constexpr int ROW = 32 * FC + 8;                 // halfs per pixel row of the transpose buffer
     constexpr int LPP = 4 * FC;                      // lanes (16-byte vectors) per pixel
     constexpr int NPASS = 2 * FC * FP;               // read-back passes of 64 vectors
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
+    // (the wave index as a scalar: what is derived from it -- work items, loop exits, weight offsets --
+    // is then uniform for the compiler too)
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
     half_t* tb = lds + wave * (32 * FP * ROW);
     const half_t* resp = (const half_t*)a.res;
     half_t* outp = (half_t*)a.out;
@@ -1125,24 +1128,28 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, MINB) void k_pw(const DlfPwArgs 
 
     int item = blockIdx.x * DLF_PW_WAVES + wave;
     if (item >= a.nitems) return;
-    const half_t* bp[FP];
-    const h8* wp[FC];
+    // operands through buffer resources: 32-bit lane offsets + uniform K-step offsets, so that the
+    // wave's walk along K is scalar arithmetic (see wfrag)
+    const i32x4 rw = make_rsrc(a.w, 0xffffffffu), rin = make_rsrc(a.in, 0xffffffffu);
+    const int lane16 = lane * 16;
+    int bo[FP];
+    unsigned wo[FC];
     int pg, cg;
     h8 ar[D][FC], br[D][FP];
     auto request_first = [&]() {
-        pw_item_setup<FP>(a, item, lane, bp, pg, cg);
+        pw_item_setup<FP>(a, item, lane, bo, pg, cg);
 #pragma unroll
         for (int f = 0; f < FC; ++f) {
             const int cb = min(cg * FC + f, a.ncb - 1);
-            wp[f] = (const h8*)a.w + (size_t)cb * nsteps * 64 + lane;
+            wo[f] = (unsigned)__builtin_amdgcn_readfirstlane(cb * nsteps * 1024);
         }
 #pragma unroll
         for (int j = 0; j < D; ++j) {
             if (j < nsteps) {
 #pragma unroll
-                for (int f = 0; f < FC; ++f) ar[j][f] = wp[f][j * 64];
+                for (int f = 0; f < FC; ++f) ar[j][f] = wfrag(rw, lane16, wo[f] + j * 1024);
 #pragma unroll
-                for (int p = 0; p < FP; ++p) br[j][p] = *(const h8*)(bp[p] + j * 16);
+                for (int p = 0; p < FP; ++p) br[j][p] = wfrag(rin, bo[p], j * 32);
             }
         }
     };
@@ -1166,9 +1173,9 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, MINB) void k_pw(const DlfPwArgs 
                             acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[j][f], br[j][p], acc[f][p], 0, 0, 0);
                     if (s + j + D < nsteps) {       // never read activations beyond the pixel's channels
 #pragma unroll
-                        for (int f = 0; f < FC; ++f) ar[j][f] = wp[f][(s + j + D) * 64];
+                        for (int f = 0; f < FC; ++f) ar[j][f] = wfrag(rw, lane16, wo[f] + (s + j + D) * 1024);
 #pragma unroll
-                        for (int p = 0; p < FP; ++p) br[j][p] = *(const h8*)(bp[p] + (s + j + D) * 16);
+                        for (int p = 0; p < FP; ++p) br[j][p] = wfrag(rin, bo[p], (s + j + D) * 32);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -1247,36 +1254,41 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pw_sk(const DlfPwArgs 
 {
     constexpr int D = 6;
     constexpr int ROW = 32 + 8;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
+    // (the wave index as a scalar: what is derived from it -- work items, loop exits, weight offsets --
+    // is then uniform for the compiler too)
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
     float* part = (float*)lds;                                  // [block][3 senders][16][64] fp32
     half_t* tb = lds + DLF_PWSK_PART_BYTES / 2 + wave * (32 * ROW);
     const half_t* resp = (const half_t*)a.res;
     half_t* outp = (half_t*)a.out;
     const int per = a.nsteps / DLF_PW_WAVES;                    // the host guarantees divisibility
     const int s0 = wave * per;
+    const i32x4 rw = make_rsrc(a.w, 0xffffffffu), rin = make_rsrc(a.in, 0xffffffffu);
+    const int lane16 = lane * 16;
     const int act_epi = resp != nullptr ? 0 : a.act;
     const unsigned lo_e = act_lo(act_epi), hi_e = act_hi(act_epi);
     const unsigned lo_r = act_lo(a.act), hi_r = act_hi(a.act);
     for (int item = blockIdx.x; item < a.nitems; item += gridDim.x) {
-        const half_t* bp[2];
-        const h8* wp[2];
+        int bo[2];
+        unsigned wo[2];
         int pg, cg;
-        pw_item_setup<2>(a, item, lane, bp, pg, cg);
+        pw_item_setup<2>(a, item, lane, bo, pg, cg);
 #pragma unroll
-        for (int p = 0; p < 2; ++p) bp[p] += s0 * 16;
+        for (int p = 0; p < 2; ++p) bo[p] += s0 * 32;
 #pragma unroll
         for (int f = 0; f < 2; ++f) {
             const int cb = min(cg * 2 + f, a.ncb - 1);
-            wp[f] = (const h8*)a.w + ((size_t)cb * a.nsteps + s0) * 64 + lane;
+            wo[f] = (unsigned)__builtin_amdgcn_readfirstlane((cb * a.nsteps + s0) * 1024);
         }
         h8 ar[D][2], br[D][2];
 #pragma unroll
         for (int j = 0; j < D; ++j) {
             if (j < per) {
 #pragma unroll
-                for (int f = 0; f < 2; ++f) ar[j][f] = wp[f][j * 64];
+                for (int f = 0; f < 2; ++f) ar[j][f] = wfrag(rw, lane16, wo[f] + j * 1024);
 #pragma unroll
-                for (int p = 0; p < 2; ++p) br[j][p] = *(const h8*)(bp[p] + j * 16);
+                for (int p = 0; p < 2; ++p) br[j][p] = wfrag(rin, bo[p], j * 32);
             }
         }
         f16v acc[2][2];
@@ -1297,9 +1309,9 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pw_sk(const DlfPwArgs 
                             acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[j][f], br[j][p], acc[f][p], 0, 0, 0);
                     if (s + j + D < per) {          // stays inside this wave's share of the channels
 #pragma unroll
-                        for (int f = 0; f < 2; ++f) ar[j][f] = wp[f][(s + j + D) * 64];
+                        for (int f = 0; f < 2; ++f) ar[j][f] = wfrag(rw, lane16, wo[f] + (s + j + D) * 1024);
 #pragma unroll
-                        for (int p = 0; p < 2; ++p) br[j][p] = *(const h8*)(bp[p] + (s + j + D) * 16);
+                        for (int p = 0; p < 2; ++p) br[j][p] = wfrag(rin, bo[p], (s + j + D) * 32);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -2120,7 +2132,7 @@ __global__ __launch_bounds__(DLF_DW_WAVES * 64, 4) void k_dw(const DlfDwArgs a)
 {
     constexpr int ROWS = S == 1 ? DLF_DW_ROWS1 : DLF_DW_ROWS2;
     constexpr int RING = S == 1 ? 4 : 5;                  // input rows in registers
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const i32x4 rin = make_rsrc(a.in, a.in_bytes);
     const unsigned cg_m = div_magic(a.cg);
     const half_t* wdw = (const half_t*)a.w;
@@ -2203,7 +2215,10 @@ __global__ __launch_bounds__(DLF_DWPW_WAVES * 64, 2) void k_dwpw(const DlfDwPwAr
     constexpr int ROW = 32 * NB + 8;                 // halfs per pixel row of the transpose buffer
     constexpr int LPP = 4 * NB;                      // lanes (16-byte vectors) per pixel
     constexpr int NPASS = 2 * NB;                    // read-back passes of 64 vectors
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
+    // (the wave index as a scalar: what is derived from it -- work items, loop exits, weight offsets --
+    // is then uniform for the compiler too)
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
     const int c = a.c;
     half_t* wl = lds;                                // [9][c] fp16
     float* bl = (float*)(lds + 9 * c);               // [c] fp32
@@ -2386,11 +2401,12 @@ __device__ __forceinline__ void dwt_phase2(const DlfDwtArgs& a, const half_t* ti
     half_t* outp = (half_t*)a.out;
     const int nunits = a.ncb * a.npg;
     int pf_u = wave, pf_ks = 0;                      // the stream's next fragment: unit, K step
-    const h8* wbase = (const h8*)a.wpw + lane;
+    const i32x4 rw = make_rsrc(a.wpw, 0xffffffffu);
+    const int lane16 = lane * 16;
     auto next_frag = [&]() __attribute__((always_inline)) {
         // past the last unit the stream re-reads the last block's first fragment (never used)
         const int cbp = min(pf_u, nunits - 1) / a.npg;
-        const h8 f = wbase[((size_t)cbp * a.nsteps + pf_ks) * 64];
+        const h8 f = wfrag(rw, lane16, (unsigned)__builtin_amdgcn_readfirstlane((cbp * a.nsteps + pf_ks) * 1024));
         const bool live = pf_u < nunits;
         const int nks = live ? pf_ks + 1 : pf_ks;
         const bool wrap = nks == a.nsteps;
@@ -2545,7 +2561,7 @@ extern "C" int dlf_launch_dw(const DlfDwArgs* a, int grid, void* stream);
 __global__ __launch_bounds__(DLF_FC_WAVES * 64) void k_fc(const DlfFcArgs a)
 {
     __shared__ float red[DLF_FC_WAVES][16][64];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
     const int cb = blockIdx.x;
     const half_t* x = (const half_t*)a.x;
@@ -2628,7 +2644,7 @@ __global__ __launch_bounds__(DLF_FC_WAVES * 64) void k_fc(const DlfFcArgs a)
 __global__ __launch_bounds__(DLF_FC_WAVES * 64) void k_fc_sk(const DlfFcArgs a)
 {
     __shared__ float red[DLF_FC_WAVES][16][64];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
     const int ks = blockIdx.x % a.ksplit, cbp = blockIdx.x / a.ksplit;
     const int cb0 = cbp * 2, cb1 = min(cb0 + 1, a.ncb - 1);
