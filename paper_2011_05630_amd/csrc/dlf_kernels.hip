@@ -588,6 +588,7 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
     const int cs = st.in_cs;
     const int ntaps = st.kh * st.kw;
     const half_t* in = (const half_t*)a.in;
+    const i32x4 rin = make_rsrc(a.in, 0xffffffffu);
     constexpr int MMA_WAVES = STREAM ? DLF_MMA_WAVES : DLF_WAVES;
 
     if (STREAM && wave >= DLF_MMA_WAVES) {
@@ -637,7 +638,7 @@ __device__ __forceinline__ void conv_stage(const DlfGroupArgs& a, const DlfStage
 #pragma unroll
                 for (int i = 0; i < DLF_STAGE_VECS; ++i) {
                     const int c = coff + ((lt + i * DLF_LOAD_THREADS) & vmask) * 8;
-                    const h8 x = *(const h8*)(in + s_goff[i] + min(c, st.cin - 8));
+                    const h8 x = wfrag(rin, (s_goff[i] + min(c, st.cin - 8)) * 2, 0);     // 32-bit offsets: the tensor is below 4 GiB
                     const h8 z = {0, 0, 0, 0, 0, 0, 0, 0};
                     s_reg[i] = ((s_ok >> i) & 1u) != 0 && c < st.cin ? x : z;
                 }
