@@ -232,7 +232,8 @@ const int64_t C_PW_ITEM = 2500;             // per work item: address setup, epi
 const int64_t C_PW_STEP[PW_SHAPES] = {470, 300, 470, 0, 0};   // per K step of a latency-bound wave ...
 const int64_t C_PW_STEP_WAVE[PW_SHAPES] = {64, 100, 256, 0, 0};   // ... or of a CU whose waves share its vector-memory path
 const int64_t C_PWB_BLOCK = 4000;           // block form, per round of two blocks on a CU: first operands, epilogue
-const int64_t PWB_BYTES_PER_CYCLE = 25;     // rate at which a CU takes operand fragments in (all pointwise forms)
+const int64_t PWB_BYTES_PER_CYCLE = 28;     // rate at which a CU takes operand fragments in (block form of the pointwise kernel)
+const int64_t PW_BYTES_PER_CYCLE = 25;      // ... the per-wave forms, the 1x1 phase of the depthwise tile kernel, the FC kernel
 const int64_t C_PW_SK = 2000;               // split-K: exchange of partial sums through LDS
 const int64_t C_PW_RES = 1000;              // residual loads
 const int64_t PW_HBM_BYTES_PER_CYCLE = 2000;
@@ -240,8 +241,8 @@ const int64_t PW_HBM_BYTES_PER_CYCLE = 2000;
 // channels (nine taps x four MFMAs on each of two waves per SIMD, in tenths), intake of a stage
 const int64_t C_C3_ITEM = 10000;
 const int64_t C_C3_SHORT_K = 6000;          // per item when K has fewer than 8 stages: the ring never reaches its steady state
-const int64_t C3_MMA_TENTHS = 16;
-const int64_t C3_BYTES_PER_CYCLE = 25;
+const int64_t C3_MMA_TENTHS = 15;
+const int64_t C3_BYTES_PER_CYCLE = 27;
 const int64_t C3_SHALLOW_RING = 300;        // per stage when the weight ring has two stages only
 
 // streaming depthwise kernel: per work item (decode, weights, first rows of the window), per output
@@ -562,10 +563,10 @@ Built build_group(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
             const bool streaming = (s == 0 && tc.stream0);
             const int mma_waves = streaming ? DLF_MMA_WAVES : DLF_WAVES;
             if (streaming && nitems > mma_waves) return b;
-            // items queue up on the 4 SIMDs; measured rounds run at about half the MFMA issue rate
+            // items queue up on the 4 SIMDs; measured rounds run at 1.8 times the MFMA issue time
             // (a 32 x 128 register tile needs half the weight traffic per MFMA and runs closer to
-            //  the issue rate: 1.6 instead of 2)
-            int64_t mma = (int64_t)ceil_div(nitems, 4) * (st.nsteps / tc.ksplit) * FCv * FPv * MFMA_CYCLES * (FPv >= 4 ? 13 : 20) / 10;
+            //  the issue rate: 1.3)
+            int64_t mma = (int64_t)ceil_div(nitems, 4) * (st.nsteps / tc.ksplit) * FCv * FPv * MFMA_CYCLES * (FPv >= 4 ? 13 : 18) / 10;
             if (streaming) {
                 const int64_t nrounds = st.cin_pad / st.kc;
                 const int64_t vecs = ceil_div(st.ih * st.iw * (st.kc / 8), DLF_LOAD_THREADS);
@@ -752,7 +753,7 @@ uint64_t pw_shape_cost_ps(const Layer& L, int batch, int budget, int shape)
     const int64_t ks = PW_KSPLIT[shape];
     const int64_t item = C_PW_ITEM + (L.nsteps / ks) * step + (ks > 1 ? C_PW_SK : 0) + has_res * C_PW_RES;
     // ... and never faster than the CU takes in the operand fragments of its items
-    const int64_t stream = items_cu * L.nsteps * (FCs + FPs) * 1024 / PWB_BYTES_PER_CYCLE;
+    const int64_t stream = items_cu * L.nsteps * (FCs + FPs) * 1024 / PW_BYTES_PER_CYCLE;
     const int64_t compute = std::max(((items_cu + W - 1) / W) * item, stream);
     const int64_t bytes = m * L.d.cin * 2 + m * L.d.cout * 2 * (1 + has_res) + (int64_t)L.ncb * L.nsteps * 1024;
     const int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
@@ -1045,7 +1046,7 @@ uint64_t dwt_cost_ps(const Layer& D, const Layer& P, int batch, int budget, cons
     const int64_t tiles_cu = ((int64_t)dt.ntiles + budget - 1) / budget;
     const int64_t conc = std::min<int64_t>(occ, tiles_cu);
     // ... but not the rate at which the CU takes in the weight fragments every tile streams anew
-    const int64_t intake = tiles_cu * ((int64_t)dt.ncb * dt.npg * dt.nsteps * 1024) / PWB_BYTES_PER_CYCLE;
+    const int64_t intake = tiles_cu * ((int64_t)dt.ncb * dt.npg * dt.nsteps * 1024) / PW_BYTES_PER_CYCLE;
     const int64_t compute = C_LAT + std::max(tiles_cu * tile / conc, intake);
     const int64_t m = (int64_t)batch * D.out_h * D.out_w;
     const int64_t bytes = (int64_t)batch * D.in_h * D.in_w * D.in_c * 2 + m * P.d.cout * 2 +
@@ -1093,7 +1094,7 @@ uint64_t fc_cost_ps(const Layer& L, int batch, int& ksplit)
     ksplit = 1;
     for (int ks = 2; ks <= 8; ks *= 2) {
         if (ceil_div(L.ncb, 2) * ks > 256 || L.nsteps < 64 * ks) continue;
-        const int64_t intake = 3 * (int64_t)ceil_div(L.nsteps, ks) * 1024 * nbb / PWB_BYTES_PER_CYCLE;
+        const int64_t intake = 3 * (int64_t)ceil_div(L.nsteps, ks) * 1024 * nbb / PW_BYTES_PER_CYCLE;
         const int64_t hbm = wbytes / FC_SPLIT_HBM_BYTES_PER_CYCLE;
         const uint64_t c = (uint64_t)((2 * C_LAUNCH + C_LAT + std::max(intake, hbm)) * PS_PER_CYCLE);
         if (c < best) { best = c; ksplit = ks; }
