@@ -102,7 +102,7 @@ def csrc_sha1():
 
 VARIANT_NAME = {0: "k_group<2,2,2>", 1: "k_group<1,4,2>", 2: "k_group<1,2,2>", 3: "k_group<1,2,4>"}
 # pointwise kernels by item shape
-PW_NAME = {0: "k_pw<2,2,6,2>", 1: "k_pw<1,1,8,4>", 2: "k_pw_sk", 3: "k_pwb<2,2,false>", 4: "k_pwb<1,4,false>"}
+PW_NAME = {0: "k_pw<2,2,6,2>", 1: "k_pw<1,1,8,4>", 2: "k_pw_sk", 3: "k_pwb<2,2>", 4: "k_pwb<1,4>"}
 PW2_NAME = {3: "k_pwb<2,2,true>", 4: "k_pwb<1,4,true>"}
 DW_NAME = {0: "k_dw<1>", 1: "k_dw<2>"}
 C3_NAME = {0: "k_c3b<2,32,2>", 1: "k_c3b<2,64,2>", 2: "k_c3b<1,32,2>", 3: "k_c3b<1,64,2>", 4: "k_c3b<2,32,4>"}
