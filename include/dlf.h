@@ -97,7 +97,9 @@ typedef struct {
 /* Builds a network from `n` layers on an in_h x in_w x in_c input.  Validates and infers
  * shapes.  If every conv/depthwise/FC layer has a weight pointer, weights are repacked and
  * uploaded to the current HIP device (needs a GPU); if all weight pointers are NULL the result
- * is a shape-only network that can be planned but not run (works without a GPU). */
+ * is a shape-only network that can be planned but not run (works without a GPU).
+ * Ranges: in_h, in_w, in_c, cin, cout <= 2^20 (FC: cin <= 2^24); kh, kw, stride, pad <= 1024;
+ * anything above is DLF_ERR_INVALID_ARG. */
 dlf_status dlf_net_create(const dlf_layer_desc* layers, int32_t n, int32_t in_h, int32_t in_w,
                           int32_t in_c, dlf_net_t** out);
 void dlf_net_destroy(dlf_net_t* net);

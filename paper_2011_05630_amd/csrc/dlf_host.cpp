@@ -1457,6 +1457,10 @@ dlf_status dlf_net_create(const dlf_layer_desc* layers, int32_t n, int32_t in_h,
 {
     if (!layers || !out || n <= 0 || in_h <= 0 || in_w <= 0 || in_c <= 0)
         return fail(DLF_ERR_INVALID_ARG, "dlf_net_create: null or non-positive argument");
+    // Limits that keep every size computed from these fields inside 32-bit integers.
+    const int32_t MAX_DIM = 1 << 20, MAX_WINDOW = 1 << 10;
+    if (in_h > MAX_DIM || in_w > MAX_DIM || in_c > MAX_DIM)
+        return fail(DLF_ERR_INVALID_ARG, "dlf_net_create: input dimension above %d", MAX_DIM);
     dlf_net_s* net = new (std::nothrow) dlf_net_s;
     if (!net) return fail(DLF_ERR_OOM, "host allocation failed");
     net->in_h = in_h; net->in_w = in_w; net->in_c = in_c;
@@ -1474,6 +1478,9 @@ dlf_status dlf_net_create(const dlf_layer_desc* layers, int32_t n, int32_t in_h,
         if (d.act < DLF_ACT_NONE || d.act > DLF_ACT_RELU6) return bad(DLF_ERR_INVALID_ARG, "bad activation");
         if (d.cin <= 0 || d.cout <= 0 || d.kh <= 0 || d.kw <= 0 || d.stride <= 0 || d.pad < 0)
             return bad(DLF_ERR_INVALID_ARG, "non-positive size");
+        if (d.cin > (d.op == DLF_FC ? (1 << 24) : MAX_DIM) || d.cout > MAX_DIM || d.kh > MAX_WINDOW || d.kw > MAX_WINDOW ||
+            d.stride > MAX_WINDOW || d.pad > MAX_WINDOW)
+            return bad(DLF_ERR_INVALID_ARG, "size above the supported range");
         if (d.input_from < -1 || d.input_from >= i) return bad(DLF_ERR_INVALID_ARG, "input_from must name an earlier layer");
         if (d.residual_from < -1 || d.residual_from >= i) return bad(DLF_ERR_INVALID_ARG, "residual_from must name an earlier layer");
         L.src = d.input_from >= 0 ? d.input_from : i - 1;
@@ -1493,7 +1500,7 @@ dlf_status dlf_net_create(const dlf_layer_desc* layers, int32_t n, int32_t in_h,
             if (d.op == DLF_MAXPOOL && d.has_bias) return bad(DLF_ERR_INVALID_ARG, "pooling has no bias");
             break;
         case DLF_FC:
-            if (d.cin != L.in_h * L.in_w * L.in_c) return bad(DLF_ERR_SHAPE, "FC cin must equal H*W*C of its input");
+            if ((int64_t)d.cin != (int64_t)L.in_h * L.in_w * L.in_c) return bad(DLF_ERR_SHAPE, "FC cin must equal H*W*C of its input");
             if (d.kh != 1 || d.kw != 1) return bad(DLF_ERR_INVALID_ARG, "FC kernel must be 1x1");
             L.out_h = L.out_w = 1; L.out_c = d.cout;
             L.macs = (uint64_t)d.cin * d.cout;

@@ -2050,7 +2050,7 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
                     }
             }
             __builtin_amdgcn_wave_barrier();
-            const int obase = wp * (a.pool2 ? 8 * FP : 32 * FP) + (p * 32 + sub * R >> (a.pool2 ? 2 : 0));
+            const int obase = wp * (a.pool2 ? 8 * FP : 32 * FP) + ((p * 32 + sub * R) >> (a.pool2 ? 2 : 0));
             for (int r0 = 0; r0 < rows_pass; r0 += 16) {
                 u4v val[2], rv[2];
                 bool ok[2];
