@@ -35,12 +35,15 @@ void dlf_debug_pointwise_mode(int32_t mode);
  * convolution behind it, chooses between the fused-group kernel and the streaming depthwise kernel /
  * the depthwise + 1x1 kernels: 0 = by modelled cost (default), 1 = the depthwise kernels wherever
  * they apply (a pair: the tile kernel where its shape restrictions allow, else the register kernel),
- * 2 = never, 3 = as 1 but a pair always on the register kernel.  Process-wide, not thread-safe. */
+ * 2 = never, 3 = as 1 but a pair always on the register kernel, 4 = a pair on the kernel for maps of many
+ * channels and few pixels wherever that applies (channels a multiple of 256).  In mode 1 - 3 that kernel is
+ * not considered.  Process-wide, not thread-safe. */
 void dlf_debug_depthwise_mode(int32_t mode);
 /* Testing hook: wx > 0 fixes the tile of the depthwise + 1x1 tile kernel for groups planned afterwards:
  * wx (1, 2 or 4) of its four waves side by side, each 512 / (2 * channels) pixels wide, rw output rows
  * per wave (a shape that does not fit falls back to the other kernels); wx = 0 restores the automatic
- * choice.  Process-wide, not thread-safe. */
+ * choice.  Under depthwise mode 4 the two values fix the other kernel's configuration instead: wx = channel
+ * blocks per wave (1 or 2), rw = channels per pass (256 or 512).  Process-wide, not thread-safe. */
 void dlf_debug_depthwise_tile(int32_t wx, int32_t rw);
 
 /* Testing hook: how a single 3x3 stride-1 pad-1 convolution (with the 2x2 max pool folded behind

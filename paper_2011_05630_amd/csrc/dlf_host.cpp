@@ -154,7 +154,7 @@ dlf_status pack_and_upload(Layer& L)
 // Fusion groups
 // ------------------------------------------------------------------------------------------
 
-enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3, GK_C3 = 4, GK_DW = 5, GK_DWPW = 6, GK_DWT = 7, GK_PW2 = 8 };
+enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3, GK_C3 = 4, GK_DW = 5, GK_DWPW = 6, GK_DWT = 7, GK_PW2 = 8, GK_DWS = 9 };
 
 struct TileCfg {
     int th, tw;      // tile of the group's final output tensor
@@ -183,6 +183,7 @@ struct GroupPlan {
     DlfDwArgs da;
     DlfDwPwArgs dp;
     DlfDwtArgs dt;
+    DlfDwsArgs ds;
 };
 
 const int VAR_FC[DLF_NUM_VARIANTS] = {2, 1, 1, 1};
@@ -276,6 +277,15 @@ const int64_t C_DWT_ROW = 630;
 const int64_t C_DWT_UNIT = 2250;
 const int64_t C_DWT_STEP = 48;
 const int64_t C_DWT_EPI = 750;
+// small-map depthwise + 1x1 kernel: per work item a fixed part (the first region's trip to memory,
+// barriers, store drain), the trip of every further region that is not resident, per depthwise step
+// of a wave pair, per K step and channel block of a wave, per channel block of a wave in the epilogue
+const int64_t C_DWS_ITEM = 7000;
+const int64_t C_DWS_REGION = 5000;
+const int64_t C_DWS_STEP = 1070;
+const int64_t C_DWS_MMA = 120;
+const int64_t C_DWS_EPI = 2500;
+const int64_t DWS_BYTES_PER_CYCLE = 64;
 
 struct StageSpec {   // one stage, before tiling
     int layer;
@@ -1082,6 +1092,80 @@ bool dwt_choose(const Layer& D, const Layer& P, int batch, int budget, int max_l
 struct DwtForce { int wx, rw; };
 DwtForce g_dwt_force = {0, 0};
 
+// ---- depthwise + 1x1 kernel for maps of many channels and few pixels ----
+
+bool dws_eligible(const dlf_net_s& net, int first, int last, int batch)
+{
+    if (!dwpw_eligible(net, first, last, batch)) return false;
+    return (net.L[first].d.cin % 256) == 0;
+}
+
+// One configuration: kh channels per pass, cbw channel blocks per wave.
+bool dws_build(const Layer& D, const Layer& P, int batch, int kh, int cbw, int max_lds, DlfDwsArgs& ds)
+{
+    memset(&ds, 0, sizeof ds);
+    const int c = D.d.cin, s = D.d.stride;
+    if ((kh != 256 && kh != 512) || (c % kh) != 0 || (cbw != 1 && cbw != 2)) return false;
+    ds.kh = kh; ds.nkh = c / kh;
+    // the map is cut into equal tiles of at most 8 x 8 output pixels
+    ds.th = ceil_div(D.out_h, ceil_div(D.out_h, 8));
+    ds.tw = ceil_div(D.out_w, ceil_div(D.out_w, 8));
+    ds.tp = ds.th * ds.tw;
+    ds.rh = (ds.th - 1) * s + 3; ds.rw = (ds.tw - 1) * s + 3; ds.rp = ds.rh * ds.rw;
+    // all passes' regions in LDS where they fit (and the kernel's counted waits reach), else one
+    ds.nbuf = ds.nkh;
+    if ((int)DLF_DWS_LDS_BYTES(ds.rp, ds.tp, kh, cbw, ds.nbuf) > max_lds ||
+        (ds.nbuf - 1) * ceil_div((int)(DLF_DWS_IN_BYTES(ds.rp, kh) / 1024), DLF_DWS_WAVES) + 16 + 11 > 48)
+        ds.nbuf = 1;
+    if ((int)DLF_DWS_LDS_BYTES(ds.rp, ds.tp, kh, cbw, ds.nbuf) > max_lds) return false;
+    ds.wdw = D.d_w; ds.bdw = D.d_bias; ds.wpw = P.d_w; ds.bpw = P.d_bias;
+    ds.in_bytes = (uint32_t)((int64_t)batch * D.in_h * D.in_w * D.in_c * 2);
+    ds.batch = batch; ds.h = D.in_h; ds.w_ = D.in_w; ds.c = c;
+    ds.oh = D.out_h; ds.ow = D.out_w; ds.stride = s; ds.act_dw = D.d.act; ds.act_pw = P.d.act;
+    ds.cout = P.d.cout; ds.ncb = P.ncb; ds.nsteps = P.nsteps;
+    ds.tiles_y = ceil_div(D.out_h, ds.th); ds.tiles_x = ceil_div(D.out_w, ds.tw);
+    ds.ntiles = batch * ds.tiles_y * ds.tiles_x;
+    ds.cbw = cbw;
+    ds.nsl = ceil_div(P.ncb, DLF_DWS_WAVES * cbw);
+    return true;
+}
+
+uint64_t dws_cost_ps(const Layer& D, const Layer& P, int batch, int budget, const DlfDwsArgs& ds)
+{
+    const int ppi = ds.kh == 512 ? 1 : 2;
+    const int64_t steps = (int64_t)ds.nkh * ceil_div(ds.tp, DLF_DWS_WAVES * ppi);
+    const int64_t dw = steps * C_DWS_STEP;
+    const int64_t mma = (int64_t)ds.nsteps * ds.cbw * C_DWS_MMA;
+    const int64_t blocks = std::min(ds.ncb, DLF_DWS_WAVES * ds.cbw);
+    const int64_t intake = (blocks * ds.nsteps * 1024) / DWS_BYTES_PER_CYCLE;
+    // a region that is not resident is waited for: a trip to memory per pass beyond the first
+    const int64_t exposed = ds.nbuf == ds.nkh ? 0 : (int64_t)(ds.nkh - 1) * C_DWS_REGION;
+    const int64_t item = C_DWS_ITEM + (int64_t)ds.rp * ds.c * 2 / DWS_BYTES_PER_CYCLE + exposed + dw + std::max(mma, intake) +
+                         (int64_t)ds.cbw * C_DWS_EPI;
+    const int64_t nitems = (int64_t)ds.ntiles * ds.nsl;
+    const int64_t compute = C_LAT + ((nitems + budget - 1) / budget) * item;
+    const int64_t m = (int64_t)batch * D.out_h * D.out_w;
+    const int64_t bytes = (int64_t)batch * D.in_h * D.in_w * D.in_c * 2 + m * P.d.cout * 2 +
+                          (int64_t)P.ncb * P.nsteps * 1024 + (int64_t)D.d.cin * 22;
+    const int64_t mem = bytes / std::min<int64_t>(DW_HBM_BYTES_PER_CYCLE, (int64_t)budget * DW_CU_BYTES_PER_CYCLE);
+    return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
+}
+
+// Cheapest configuration (ties: 512 channels per pass before 256, two channel blocks per wave before one).
+bool dws_choose(const Layer& D, const Layer& P, int batch, int budget, int max_lds, DlfDwsArgs& best, uint64_t& cost)
+{
+    bool found = false;
+    for (int kh = 512; kh >= 256; kh /= 2)
+        for (int cbw = 2; cbw >= 1; --cbw) {
+            DlfDwsArgs ds;
+            if (cbw == 2 && P.ncb <= DLF_DWS_WAVES) continue;      // half the waves would have no channel block
+            if (!dws_build(D, P, batch, kh, cbw, max_lds, ds)) continue;
+            const uint64_t c = dws_cost_ps(D, P, batch, budget, ds);
+            if (!found || c < cost) { found = true; cost = c; best = ds; }
+        }
+    return found;
+}
+
 // force_tc / pw_mode: explicit values for the two testing hooks (null / -1: the process-wide ones)
 // Fully connected layer: one workgroup per 32 output channels streaming all of K, or, where that is
 // cheaper, pairs of channel blocks with K split 2, 4 or 8 ways (at most 256 workgroups), a second
@@ -1211,6 +1295,39 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
                                        : DLF_PW_WAVES * 32 * PW_FP[shape] * (32 * PW_FC[shape] + 8) * 2;
             if (L0.d.residual_from >= 0) { g.res_layer = L0.d.residual_from; g.res_stage = 0; }
             return DLF_OK;
+        }
+    }
+    if ((g_dw_mode == 0 || g_dw_mode == 4) && (force.th <= 0 || g_dw_mode == 4) && dws_eligible(net, first, last, batch)) {
+        const Layer& P = net.L[last];
+        DlfDwsArgs ds;
+        uint64_t sc = 0;
+        bool have_s;
+        if (g_dw_mode == 4 && g_dwt_force.wx > 0) {    // testing hook: channel blocks per wave, channels per pass
+            have_s = dws_build(L0, P, batch, g_dwt_force.rw, g_dwt_force.wx, max_lds, ds);
+            if (have_s) sc = dws_cost_ps(L0, P, batch, budget, ds);
+        } else {
+            have_s = dws_choose(L0, P, batch, budget, max_lds, ds, sc);
+        }
+        if (have_s) {
+            // against the fused-group kernel and, where that one applies, the tile kernel
+            uint64_t other = tiled ? cost : UINT64_MAX;
+            if (g_dw_mode == 0 && g_dwt_force.wx <= 0 && dwt_eligible(net, first, last, batch)) {
+                DlfDwtArgs dt;
+                uint64_t dc = 0;
+                int occ = 1;
+                if (dwt_choose(L0, P, batch, budget, max_lds, dt, dc, occ)) other = std::min(other, dc);
+            }
+            if (g_dw_mode == 4 || sc < other) {
+                g.ds = ds;
+                g.kind = GK_DWS;
+                g.cost = sc;
+                g.variant = (L0.d.stride - 1) * 2 + (ds.cbw - 1);
+                g.occ = 1;
+                g.grid = ceil_div(ds.ntiles, 8) * 8 * ds.nsl;
+                g.th = ds.th; g.tw = ds.tw;
+                g.lds_bytes = (int)DLF_DWS_LDS_BYTES(ds.rp, ds.tp, ds.kh, ds.cbw, ds.nbuf);
+                return DLF_OK;
+            }
         }
     }
     if (g_dw_mode != 2 && g_dw_mode != 3 && (force.th <= 0 || g_dw_mode == 1) && dwt_eligible(net, first, last, batch)) {
@@ -1843,7 +1960,7 @@ dlf_status dlf_plan_group_io(const dlf_plan_t* plan, int32_t g, int32_t* in_laye
 
 void dlf_debug_pointwise_mode(int32_t mode) { g_pw_mode = (mode >= 0 && mode <= 7) ? mode : 0; }
 
-void dlf_debug_depthwise_mode(int32_t mode) { g_dw_mode = (mode >= 0 && mode <= 3) ? mode : 0; }
+void dlf_debug_depthwise_mode(int32_t mode) { g_dw_mode = (mode >= 0 && mode <= 4) ? mode : 0; }
 
 void dlf_debug_depthwise_tile(int32_t wx, int32_t rw) { g_dwt_force = DwtForce{wx, rw}; }
 
@@ -1924,6 +2041,10 @@ static dlf_status launch_one(const dlf_plan_s* plan, const GroupPlan& G, const v
         DlfDwtArgs dt = G.dt;
         dt.in = in; dt.out = out;
         e = dlf_launch_dwt(&dt, G.grid, G.lds_bytes, stream);
+    } else if (G.kind == GK_DWS) {
+        DlfDwsArgs ds = G.ds;
+        ds.in = in; ds.out = out;
+        e = dlf_launch_dws(&ds, G.grid, G.lds_bytes, stream);
     } else if (G.kind == GK_DWPW) {
         DlfDwPwArgs dp = G.dp;
         dp.in = in; dp.out = out;

@@ -220,6 +220,40 @@ struct DlfDwtArgs {
     int32_t tiles_y, tiles_x, ntiles;     // ntiles = batch * tiles_y * tiles_x
 };
 
+// Depthwise 3x3 + 1x1 convolution for maps of many channels and few pixels (channels a multiple of
+// 256), where the tile kernel above has no tile to work with: one workgroup of eight waves per work
+// item = (tile of at most 8 x 8 output pixels, slice of 8 * cbw 32-channel blocks of the 1x1 layer).
+// Per pass over kh of the c channels: the tile's input region arrives in LDS by direct loads, the waves compute the depthwise layer from there
+// into an LDS tile [pixel][kh + 8], then multiply it on MFMA, every wave cbw channel blocks x two
+// 32-pixel blocks with its weight fragments streaming through a register ring.
+#define DLF_DWS_WAVES 8
+// a region: whole KiB of pixels, kh channels each
+#define DLF_DWS_IN_BYTES(RP, KH) ((((RP) * (KH) * 2 + 1023) / 1024) * 1024)
+#define DLF_DWS_EPI_BYTES(CBW) (DLF_DWS_WAVES * 32 * (32 * (CBW) + 8) * 2)
+#define DLF_DWS_MID_BYTES(TP, KH) ((TP) * ((KH) + 8) * 2)
+#define DLF_DWS_LDS_BYTES(RP, TP, KH, CBW, NBUF)                                                 \
+    (((NBUF) * DLF_DWS_IN_BYTES(RP, KH) > DLF_DWS_EPI_BYTES(CBW) ? (NBUF) * DLF_DWS_IN_BYTES(RP, KH) \
+                                                               : DLF_DWS_EPI_BYTES(CBW)) +         \
+     DLF_DWS_MID_BYTES(TP, KH))
+struct DlfDwsArgs {
+    const void* in;       // [batch][h][w][c] fp16
+    void* out;            // [batch][oh][ow][cout] fp16
+    const void* wdw;      // depthwise weights [9][c] fp16 (tap-major)
+    const float* bdw;     // depthwise bias [c]
+    const void* wpw;      // pointwise weights, packed fragments
+    const float* bpw;     // pointwise bias, padded to ncb * 32
+    uint32_t in_bytes;    // size of the input tensor (below 2 GiB)
+    int32_t batch, h, w_, c, oh, ow, stride, act_dw, act_pw;
+    int32_t cout, ncb, nsteps;
+    int32_t kh, nkh;      // channels per pass (256 or 512), passes = c / kh
+    int32_t nbuf;         // region buffers in LDS: nkh (every pass's region is requested at the start) or 1
+    int32_t th, tw, tp;   // tile of output pixels (each side <= 8), tp = th * tw
+    int32_t rh, rw, rp;   // its input region: (th - 1) * stride + 3 rows, likewise columns; rp = rh * rw
+    int32_t tiles_y, tiles_x, ntiles;     // ntiles = batch * tiles_y * tiles_x
+    int32_t cbw;          // channel blocks per wave (1 or 2)
+    int32_t nsl;          // slices of the output channels: ceil(ncb / (8 * cbw))
+};
+
 struct DlfGapArgs {
     const void* x;        // [batch][hw][c]
     void* y;              // [batch][c]
@@ -241,6 +275,7 @@ int dlf_launch_c3(const DlfC3Args* a, int shape, int grid, int lds_bytes, void* 
 int dlf_launch_dw(const DlfDwArgs* a, int grid, void* stream);
 int dlf_launch_dwpw(const DlfDwPwArgs* a, int nb, int grid, void* stream);
 int dlf_launch_dwt(const DlfDwtArgs* a, int grid, int lds_bytes, void* stream);
+int dlf_launch_dws(const DlfDwsArgs* a, int grid, int lds_bytes, void* stream);
 int dlf_kernels_init(void);
 // Attaches a start / stop event pair (hipEvent_t, either may be null) to this thread's next launch.
 void dlf_next_launch_events(void* start, void* stop);

@@ -2553,6 +2553,246 @@ __global__ __launch_bounds__(DLF_DWT_WAVES * 64, 2) void k_dwt(const DlfDwtArgs 
     }
 }
 
+
+// Depthwise 3x3 + 1x1 convolution where a map has many channels and few pixels (MobileNet's 14 x 14
+// and 7 x 7 maps of 256 - 1024 channels).  There the layers are small, a launch costs about as much
+// as the arithmetic, and the depthwise result is best never written: Sec. V finds exactly these
+// low-operation-count layers to gain most from fusion.  The tile kernel above cannot take them (a
+// wave's 64 lanes cover one pixel's 512 channels: its tiles degenerate to columns).
+//   Work item = (tile of up to 8 x 8 output pixels, slice of 8 * CBW channel blocks of the 1x1 layer):
+// one workgroup of eight waves, one item, one workgroup per CU.  The slices of a tile run on the same
+// XCD (workgroups i, i + 8, ...), so their common input reaches that L2 once.
+//   The c channels are taken kh = 256 or 512 at a time; per pass
+//     1. region: the tile's input region, kh channels per pixel, global -> LDS by direct loads, one
+//        instruction = 1 KiB = one pixel's 512 channels or two pixels' 256; pixels outside the
+//        image are requested beyond the buffer's range and arrive as zeros (the padding is data,
+//        no branch).  Behind the pixels the same way: the pass's depthwise weights (nine taps,
+//        "pixels" of their own) and bias, so that no lane has loads of its own for them.  Where
+//        LDS holds the regions of all passes they are all requested at the start (a region takes
+//        a trip to memory, 4 - 5 thousand cycles), else one after the other;
+//     2. depthwise: a wave takes every eighth pixel (pair), lane = 8 channels; nine 16-byte LDS reads,
+//        fp32 sums in the order of k_dw (same bits), result to the LDS tile [pixel][kh + 8];
+//     3. 1x1: every wave CBW channel blocks x the tile's two 32-pixel blocks, accumulators kept over
+//        the passes; "B" fragments from the tile, weight fragments through a register ring of 8 K
+//        steps, first requested behind the regions (the ring's trip to L2 hides behind step 2, and
+//        the regions do not share the CU's intake with it).
+//   Steps 2 and 3 were also built as a pipeline over 128-channel passes with half of the waves
+// filtering while the other half multiplies: the two halves slowed each other down by what the
+// overlap should have gained, and the phases' barriers came on top (20 us against 19).
+//   Results leave through wave-private transpose buffers (in the regions' space), 64 * CBW bytes
+// per pixel and instruction group.
+template <int S, int CBW>
+__global__ __launch_bounds__(DLF_DWS_WAVES * 64, 1) void k_dws(const DlfDwsArgs a)
+{
+    constexpr int D = 8;
+    constexpr int ROW = 32 * CBW + 8;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int KH = a.kh, cs = KH + 8;
+    const int ng_shift = KH == 512 ? 6 : 5;                  // lanes per pixel = kh / 8
+    const int ppi = 64 >> ng_shift;                          // pixels per load instruction and per wave step
+    const int g = lane & ((1 << ng_shift) - 1), psub = lane >> ng_shift;
+    const int per8 = blockIdx.x >> 3;
+    const int sl = per8 % a.nsl, tile = (per8 / a.nsl) * 8 + (blockIdx.x & 7);
+    if (tile >= a.ntiles) return;
+    int r_ = tile;
+    const int tx = r_ % a.tiles_x;
+    r_ /= a.tiles_x;
+    const int ty = r_ % a.tiles_y, n = r_ / a.tiles_y;
+    const int oy0 = ty * a.th, ox0 = tx * a.tw;
+    const int iy0 = oy0 * S - 1, ix0 = ox0 * S - 1;
+    const int in_halfs = DLF_DWS_IN_BYTES(a.rp, KH) / 2, epi_halfs = DLF_DWS_EPI_BYTES(CBW) / 2;
+    const bool resident = a.nbuf == a.nkh;                   // every pass has a region buffer of its own
+    half_t* const inb = lds;
+    half_t* const mid = lds + (a.nbuf * in_halfs > epi_halfs ? a.nbuf * in_halfs : epi_halfs);
+    half_t* const tb = lds + wave * (32 * ROW);
+    half_t* outp = (half_t*)a.out;
+    const unsigned lo_d = act_lo(a.act_dw), hi_d = act_hi(a.act_dw);
+    const unsigned lo_p = act_lo(a.act_pw), hi_p = act_hi(a.act_pw);
+    const unsigned tw_m = div_magic(a.tw), rw_m = div_magic(a.rw);
+
+    // ---- the wave's weight stream: CBW fragments per K step, D steps ahead ----
+    const i32x4 rwt = make_rsrc(a.wpw, 0xffffffffu);
+    const int lane16 = lane * 16;
+    const int cb0 = (sl * DLF_DWS_WAVES + wave) * CBW;
+    const bool live = cb0 < a.ncb;                           // uniform: a wave beyond the last block only loads and filters
+    unsigned wo[CBW];
+#pragma unroll
+    for (int j = 0; j < CBW; ++j)
+        wo[j] = (unsigned)__builtin_amdgcn_readfirstlane(min(cb0 + j, a.ncb - 1) * a.nsteps * 1024);
+    int pf_ks = 0;
+    h8 ar[D][CBW];
+    auto request = [&](int slot) __attribute__((always_inline)) {
+        const unsigned so = (unsigned)min(pf_ks, a.nsteps - 1) * 1024u;      // past the end: re-read, never used
+#pragma unroll
+        for (int j = 0; j < CBW; ++j) ar[slot][j] = wfrag(rwt, lane16, wo[j] + so);
+        ++pf_ks;
+    };
+
+    // ---- step 1: this wave's share of a region's load instructions ----
+    // (written as instructions: of a direct-to-LDS load the compiler only knows that it writes LDS
+    // at some time, and it would put a wait for all loads in front of every LDS read that follows;
+    // here the waits are counted by hand)
+    const i32x4 rin = make_rsrc(a.in, a.in_bytes);
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) half_t*)lds;
+    const int ni = (a.rp + ppi - 1) >> (6 - ng_shift);
+    auto issue_in = [&](int pass) __attribute__((always_inline)) {
+        const unsigned dst0 = lds0 + (unsigned)((resident ? pass : 0) * in_halfs) * 2u;
+#pragma unroll 1
+        for (int i = wave; i < ni; i += DLF_DWS_WAVES) {
+            const int rp = i * ppi + psub;
+            unsigned off = (unsigned)DLF_OOB;
+            if (rp < a.rp) {
+                const int ry = div_by(rp, rw_m), rx = rp - ry * a.rw;
+                const int gy = iy0 + ry, gx = ix0 + rx;
+                if (gy >= 0 && gy < a.h && gx >= 0 && gx < a.w_)
+                    off = (unsigned)(((n * a.h + gy) * a.w_ + gx) * a.c + pass * KH + g * 8) * 2u;
+            }
+            asm volatile("s_mov_b32 m0, %2\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(off), "s"(rin),
+                         "s"(dst0 + (unsigned)i * 1024u)
+                         : "memory", "m0");
+        }
+    };
+
+    // the depthwise weights and bias of the lane's 8 channels, for one pass (uniform parts of the
+    // addresses in scalar registers: one lane offset serves all eleven loads)
+    const i32x4 rdw = make_rsrc(a.wdw, (unsigned)(9 * a.c * 2)), rdb = make_rsrc(a.bdw, (unsigned)(a.c * 4));
+    u4v w[9];
+    f4v b0, b1;
+    auto load_dw_weights = [&](int pass) __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < 9; ++k)
+            w[k] = __builtin_bit_cast(u4v, raw_buffer_load_x4(rdw, g * 16, (k * a.c + pass * KH) * 2, 0));
+        b0 = __builtin_bit_cast(f4v, raw_buffer_load_x4(rdb, g * 32, pass * KH * 4, 0));
+        b1 = __builtin_bit_cast(f4v, raw_buffer_load_x4(rdb, g * 32 + 16, pass * KH * 4, 0));
+    };
+
+    f16v acc[CBW][2];
+#pragma unroll
+    for (int j = 0; j < CBW; ++j)
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[j][p][q] = 0.0f;
+
+    // Loads retire in the order of their requests, so "region q has landed" is "at most the requests
+    // behind it are outstanding".
+    const int n_in = (ni - wave + DLF_DWS_WAVES - 1) / DLF_DWS_WAVES;     // this wave's loads per region
+    const int n_ring = live ? D * CBW : 0;
+    const int ahead = resident ? a.nkh : 1;
+    load_dw_weights(0);                                      // (requested first: the oldest loads)
+    asm volatile("" ::: "memory");
+    for (int q = 0; q < ahead; ++q) issue_in(q);
+    // (the ring's first turn behind the regions: requested only when the first region has landed it
+    // slows the depthwise step by what the region gains)
+    if (live) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) request(d);
+    }
+    for (int pass = 0; pass < a.nkh; ++pass) {
+        // behind region `pass`: the later regions (if all were requested at the start) and the ring
+        wait_vmcnt_dyn((resident ? (a.nkh - 1 - pass) * n_in : 0) + n_ring);
+        asm volatile("s_barrier" ::: "memory");      // the region has landed; everyone is done multiplying the previous tile
+        // ---- step 2: depthwise ----
+        {
+            const half_t* const region = inb + (resident ? pass : 0) * in_halfs;
+            if (pass > 0) load_dw_weights(pass);
+#pragma unroll 1
+            for (int p0 = wave * ppi; p0 < a.tp; p0 += DLF_DWS_WAVES * ppi) {
+                const int p = p0 + psub;
+                const int pc = min(p, a.tp - 1);
+                const int py = div_by(pc, tw_m), px = pc - py * a.tw;
+                const half_t* src = region + ((py * S) * a.rw + px * S) * KH + g * 8;
+                float v[8];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { v[i] = b0[i]; v[i + 4] = b1[i]; }
+#pragma unroll
+                for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                    for (int kw = 0; kw < 3; ++kw) {
+                        const u4v x = *(const u4v*)(src + (kh * a.rw + kw) * KH);
+                        dw_tap(v, x, w[kh * 3 + kw]);
+                    }
+                u4v hv;
+                hv.x = pk_min(pk_max(cvt_pk(v[0], v[1]), lo_d), hi_d);
+                hv.y = pk_min(pk_max(cvt_pk(v[2], v[3]), lo_d), hi_d);
+                hv.z = pk_min(pk_max(cvt_pk(v[4], v[5]), lo_d), hi_d);
+                hv.w = pk_min(pk_max(cvt_pk(v[6], v[7]), lo_d), hi_d);
+                if (p < a.tp) *(u4v*)(mid + p * cs + g * 8) = hv;
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // the tile is complete; the region may be overwritten
+        if (!resident && pass + 1 < a.nkh) issue_in(pass + 1);
+        // ---- step 3: 1x1 on MFMA ----
+        if (live) {
+            const half_t* bsrc[2];
+#pragma unroll
+            for (int p = 0; p < 2; ++p) bsrc[p] = mid + min(p * 32 + l32, a.tp - 1) * cs + lhi * 8;
+            // the fragments of step s + 1 are read before step s is multiplied, and the ring slot of
+            // step s is requested again right behind its multiplies (the scheduler would otherwise
+            // gather a turn's requests at its end: one exposed trip to L2 per turn)
+            const int last_s = (KH >> 4) - 1;
+            h8 bf[2][2];
+#pragma unroll
+            for (int p = 0; p < 2; ++p) bf[0][p] = *(const h8*)(bsrc[p]);
+            for (int s0 = 0; s0 <= last_s; s0 += D) {
+#pragma unroll
+                for (int j = 0; j < D; ++j) {
+                    const int sn = min(s0 + j + 1, last_s);
+#pragma unroll
+                    for (int p = 0; p < 2; ++p) bf[(j + 1) & 1][p] = *(const h8*)(bsrc[p] + sn * 16);
+#pragma unroll
+                    for (int c = 0; c < CBW; ++c)
+#pragma unroll
+                        for (int p = 0; p < 2; ++p)
+                            acc[c][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[j][c], bf[j & 1][p], acc[c][p], 0, 0, 0);
+                    request(j);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+    }
+    if (!live) return;
+    // ---- epilogue: bias, activation, fp16; 32 pixels x 32 * CBW channels at a time ----
+    // (the transpose buffers lie in the regions' space: nobody reads a region after the last
+    // barrier, and no load into one is outstanding)
+    constexpr int LPX = 4 * CBW;                             // lanes per pixel in the store phase
+    constexpr int PPP = 64 / LPX;                            // pixels per store instruction
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        if (p * 32 < a.tp) {
+#pragma unroll
+            for (int c = 0; c < CBW; ++c) {
+                const int cbj = min(cb0 + c, a.ncb - 1);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f4v bias = *(const f4v*)(a.bpw + cbj * 32 + q * 8 + lhi * 4);
+                    unsigned u0 = cvt_pk(acc[c][p][q * 4 + 0] + bias[0], acc[c][p][q * 4 + 1] + bias[1]);
+                    unsigned u1 = cvt_pk(acc[c][p][q * 4 + 2] + bias[2], acc[c][p][q * 4 + 3] + bias[3]);
+                    u0 = pk_min(pk_max(u0, lo_p), hi_p);
+                    u1 = pk_min(pk_max(u1, lo_p), hi_p);
+                    const u2v uu = {u0, u1};
+                    *(u2v*)(tb + l32 * ROW + c * 32 + q * 8 + lhi * 4) = uu;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            const int part = lane & (LPX - 1);
+            const int cc = cb0 * 32 + part * 8;
+#pragma unroll
+            for (int i = 0; i < 32 / PPP; ++i) {
+                const int pl = i * PPP + lane / LPX;
+                const int px_ = p * 32 + pl;
+                const int row = div_by(px_, tw_m), colp = px_ - row * a.tw;
+                const int oy = oy0 + row, ox = ox0 + colp;
+                if (px_ < a.tp && oy < a.oh && ox < a.ow && cc < a.cout)
+                    *(u4v*)(outp + ((size_t)((n * a.oh + oy) * a.ow + ox) * a.cout + cc)) =
+                        *(const u4v*)(tb + pl * ROW + part * 8);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+
 extern "C" int dlf_launch_dw(const DlfDwArgs* a, int grid, void* stream);
 
 // Fully connected layer (Eq. 2 with M = batch): y[n][co] = act(bias[co] + sum_k x[n][k] w[co][k]).
@@ -2812,6 +3052,13 @@ extern "C" int dlf_kernels_init(void)
             e = hipFuncSetAttribute((const void*)k_dwt<2>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return (int)e;
     }
+    {
+        const void* ks[4] = {(const void*)k_dws<1, 1>, (const void*)k_dws<1, 2>, (const void*)k_dws<2, 1>, (const void*)k_dws<2, 2>};
+        for (const void* k : ks) {
+            hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return (int)e;
+        }
+    }
     for (int sh = 0; sh < DLF_C3_SHAPES; ++sh) {
         hipError_t e = hipFuncSetAttribute((const void*)c3_kernel(sh), hipFuncAttributeMaxDynamicSharedMemorySize,
                                            160 * 1024);
@@ -2925,6 +3172,34 @@ extern "C" int dlf_launch_dwt(const DlfDwtArgs* a, int grid, int lds_bytes, void
         launch(k_dwt<1>, dim3(grid), dim3(DLF_DWT_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
     else
         launch(k_dwt<2>, dim3(grid), dim3(DLF_DWT_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
+    return (int)hipGetLastError();
+}
+
+extern "C" int dlf_launch_dws(const DlfDwsArgs* a, int grid, int lds_bytes, void* stream)
+{
+    // what the kernel's indexing assumes
+    if (grid <= 0 || (grid & 7) != 0 || (a->stride != 1 && a->stride != 2) || a->in_bytes >= 0x80000000u)
+        return (int)hipErrorInvalidValue;
+    if ((a->kh != 256 && a->kh != 512) || a->nkh < 1 || a->kh * a->nkh != a->c || a->nsteps != a->c / 16 || (a->cout & 7) != 0)
+        return (int)hipErrorInvalidValue;
+    if (a->th < 1 || a->th > 8 || a->tw < 1 || a->tw > 8 || a->tp != a->th * a->tw || a->rh != (a->th - 1) * a->stride + 3 ||
+        a->rw != (a->tw - 1) * a->stride + 3 || a->rp != a->rh * a->rw)
+        return (int)hipErrorInvalidValue;
+    if ((a->cbw != 1 && a->cbw != 2) || a->nsl != (a->ncb + 8 * a->cbw - 1) / (8 * a->cbw) ||
+        a->tiles_y != (a->oh + a->th - 1) / a->th || a->tiles_x != (a->ow + a->tw - 1) / a->tw ||
+        a->ntiles != a->batch * a->tiles_y * a->tiles_x || grid != (a->ntiles + 7) / 8 * 8 * a->nsl)
+        return (int)hipErrorInvalidValue;
+    if ((a->nbuf != a->nkh && a->nbuf != 1) || lds_bytes != (int)DLF_DWS_LDS_BYTES(a->rp, a->tp, a->kh, a->cbw, a->nbuf) ||
+        lds_bytes > 160 * 1024)
+        return (int)hipErrorInvalidValue;
+    // (the counted waits of the kernel go up to 48 outstanding loads)
+    if ((a->nbuf - 1) * ((int)(DLF_DWS_IN_BYTES(a->rp, a->kh) / 1024 + DLF_DWS_WAVES - 1) / DLF_DWS_WAVES) + 16 + 11 > 48)
+        return (int)hipErrorInvalidValue;
+    const dim3 block(DLF_DWS_WAVES * 64);
+    if (a->stride == 1 && a->cbw == 1) launch(k_dws<1, 1>, dim3(grid), block, (size_t)lds_bytes, (hipStream_t)stream, *a);
+    else if (a->stride == 1) launch(k_dws<1, 2>, dim3(grid), block, (size_t)lds_bytes, (hipStream_t)stream, *a);
+    else if (a->cbw == 1) launch(k_dws<2, 1>, dim3(grid), block, (size_t)lds_bytes, (hipStream_t)stream, *a);
+    else launch(k_dws<2, 2>, dim3(grid), block, (size_t)lds_bytes, (hipStream_t)stream, *a);
     return (int)hipGetLastError();
 }
 

@@ -366,6 +366,48 @@ def test_depthwise_pointwise_fused_kernel(stride, c, cout, h, w, batch):
     compare(got, o.run_net(net, x, ws, bs), "dw+pw s%d %d->%d %dx%d" % (stride, c, cout, h, w))
 
 
+# (stride, channels in, channels out, height, width, batch, channel blocks per wave, channels per pass;
+# 0, 0 = the planner's choice): the kernel for maps of many channels and few pixels: one and several
+# passes over the channels (256 .. 1024 in passes of 256 or 512) with all regions resident or one at
+# a time, both strides, one and two channel blocks per wave, several slices of the output channels
+# and a ragged last one, waves without a channel block, maps cut into several tiles with the last
+# row / column of tiles overhanging, tiles of fewer than 32 pixels, one-pixel maps, odd sizes under
+# stride 2
+DWS_CASES = [(1, 512, 512, 14, 14, 3, 2, 512), (1, 512, 512, 14, 14, 2, 1, 256), (1, 256, 256, 7, 7, 2, 0, 0),
+             (2, 256, 512, 28, 28, 2, 2, 256), (2, 512, 1024, 14, 14, 2, 0, 0), (2, 512, 1024, 14, 14, 1, 2, 256),
+             (1, 1024, 1024, 7, 7, 2, 2, 512), (1, 1024, 1024, 7, 7, 2, 1, 256), (1, 768, 200, 9, 11, 2, 0, 0),
+             (1, 512, 96, 3, 5, 3, 1, 512), (2, 512, 640, 13, 11, 1, 2, 256), (1, 256, 1024, 1, 1, 4, 2, 256),
+             (2, 256, 64, 2, 2, 2, 0, 0), (1, 512, 512, 17, 8, 1, 2, 256), (2, 1024, 256, 9, 9, 2, 1, 256),
+             (2, 1024, 512, 9, 11, 1, 2, 256), (1, 1024, 320, 8, 8, 2, 2, 256)]
+
+
+@pytest.mark.parametrize("stride,c,cout,h,w,batch,cbw,kh", DWS_CASES)
+def test_depthwise_pointwise_small_map_kernel(stride, c, cout, h, w, batch, cbw, kh):
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    from oracle import oracle as o
+    announce("dw+pw small-map kernel", stride, c, cout, h, w, batch, cbw, kh)
+    layers = [nets.dwconv(c, 3, stride, "relu6"), nets.conv(c, cout, 1, 1, 0, "relu6" if cout != 200 else "none")]
+    net = _mk(layers, h, w, c, dist="normal")
+    x, ws, bs = gen.make_params(net, batch, 11)
+    B.dlf_debug_depthwise_mode(4)
+    B.dlf_debug_depthwise_tile(cbw, kh)       # under mode 4: channel blocks per wave, channels per pass
+    try:
+        s = Session(net, batch, ws, bs, **_manual(2, [1]))
+    finally:
+        B.dlf_debug_depthwise_mode(0)
+        B.dlf_debug_depthwise_tile(0, 0)
+    try:
+        cfg = B.dlf_plan_group_config(s.plan, 0)
+        assert len(s.groups) == 1 and cfg["kind"] == 9 and cfg["variant"] // 2 == stride - 1, cfg
+        if cbw:
+            assert cfg["variant"] % 2 == cbw - 1, cfg
+        got = s.run_numpy(x)
+    finally:
+        s.close()
+    compare(got, o.run_net(net, x, ws, bs), "dw+pw small map s%d %d->%d %dx%d" % (stride, c, cout, h, w))
+
+
 # (stride, channels in, channels out, height, width, batch, waves along x, rows per wave; 0, 0 = the
 # planner's choice): every power-of-two channel count the kernel takes, tiles that overhang the map
 # on both sides, one to eight pixel blocks per tile, 1 to 32 channel blocks, more and fewer work
