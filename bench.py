@@ -184,6 +184,8 @@ def group_accounting(net, batch, session):
             kname = "k_dwpw<%d>" % cfg["variant"]
         elif cfg["kind"] == 7:
             kname = "k_dwt<%d>" % (cfg["variant"] + 1)
+        elif cfg["kind"] == 10:
+            kname = "k_c3s"
         elif cfg["kind"] == 9:
             kname = "k_dws<%d,%d>" % (cfg["variant"] // 2 + 1, cfg["variant"] % 2 + 1)
         elif cfg["kind"] == 8:

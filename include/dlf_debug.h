@@ -51,8 +51,10 @@ void dlf_debug_depthwise_tile(int32_t wx, int32_t rw);
  * modelled cost (default), 1 = the block kernel wherever it applies, 2 = never.  shape >= 0 also
  * fixes the block's shape and its th x tw pixel tile: shape 0 / 1 = 128 channels x up to 256
  * pixels with activations brought in 32 / 64 input channels at a time, 2 / 3 = 64 channels x up to
- * 512 pixels likewise, 4 = 128 channels x up to 512 pixels (32 input channels at a time); a shape
- * that cannot be laid out falls back to the fused-group kernel.
+ * 512 pixels likewise, 4 = 128 channels x up to 512 pixels (32 input channels at a time), 5 = the kernel
+ * for maps of many channels and few pixels (cin 256, 512 or 1024, no pool, no residual; th > 0 then
+ * fixes the number of waves that share a channel block's K: 1, 2 or 4; tw is not used); a shape that
+ * cannot be laid out falls back to the fused-group kernel.
  * Process-wide, not thread-safe. */
 void dlf_debug_block3x3_mode(int32_t mode, int32_t shape, int32_t th, int32_t tw);
 

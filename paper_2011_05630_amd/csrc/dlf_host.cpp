@@ -154,7 +154,7 @@ dlf_status pack_and_upload(Layer& L)
 // Fusion groups
 // ------------------------------------------------------------------------------------------
 
-enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3, GK_C3 = 4, GK_DW = 5, GK_DWPW = 6, GK_DWT = 7, GK_PW2 = 8, GK_DWS = 9 };
+enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3, GK_C3 = 4, GK_DW = 5, GK_DWPW = 6, GK_DWT = 7, GK_PW2 = 8, GK_DWS = 9, GK_C3S = 10 };
 
 struct TileCfg {
     int th, tw;      // tile of the group's final output tensor
@@ -184,6 +184,7 @@ struct GroupPlan {
     DlfDwPwArgs dp;
     DlfDwtArgs dt;
     DlfDwsArgs ds;
+    DlfC3sArgs cs;
 };
 
 const int VAR_FC[DLF_NUM_VARIANTS] = {2, 1, 1, 1};
@@ -286,6 +287,18 @@ const int64_t C_DWS_STEP = 1070;
 const int64_t C_DWS_MMA = 120;
 const int64_t C_DWS_EPI = 2500;
 const int64_t DWS_BYTES_PER_CYCLE = 64;
+// small-map 3x3 kernel: per work item a fixed part (beyond the launch's own round trip), per K step of a
+// wave two MFMAs beside those of the SIMD's other wave -- or, when the layer's weights do not fit an
+// XCD's L2 (4 MiB) and every CU streams them at once, what the fabric behind it delivers --, the
+// exchange of partial sums, the epilogue; a CU's further items each pay the region's trip to memory
+// and the store drain in full (one workgroup per CU: nothing overlaps them)
+const int64_t C_C3S_ITEM = 3000;
+const int64_t C_C3S_NEXT = 13000;
+const int64_t C_C3S_STEP = 128;
+const int64_t C_C3S_STEP_BIG = 215;
+const int64_t C_C3S_BIG_BYTES = 3 << 20;
+const int64_t C_C3S_RED = 1500;
+const int64_t C_C3S_EPI = 2500;
 
 struct StageSpec {   // one stage, before tiling
     int layer;
@@ -1092,6 +1105,64 @@ bool dwt_choose(const Layer& D, const Layer& P, int batch, int budget, int max_l
 struct DwtForce { int wx, rw; };
 DwtForce g_dwt_force = {0, 0};
 
+// ---- 3x3 kernel for maps of many channels and few pixels ----
+
+bool c3s_eligible(const dlf_net_s& net, const std::vector<StageSpec>& specs, int batch)
+{
+    if (!c3_eligible(net, specs, batch) || specs[0].pool2) return false;
+    const Layer& L = net.L[specs[0].layer];
+    return (L.d.cin == 256 || L.d.cin == 512 || L.d.cin == 1024) && L.d.residual_from < 0 && (L.d.cout % 8) == 0;
+}
+
+bool c3s_build(const Layer& L, int batch, int ksplit, int max_lds, DlfC3sArgs& cs)
+{
+    memset(&cs, 0, sizeof cs);
+    if ((ksplit != 1 && ksplit != 2 && ksplit != 4) || ((L.d.cin / 32) % ksplit) != 0) return false;
+    // the map is cut into equal tiles of at most 8 x 8 output pixels
+    cs.th = ceil_div(L.out_h, ceil_div(L.out_h, 8));
+    cs.tw = ceil_div(L.out_w, ceil_div(L.out_w, 8));
+    cs.tp = cs.th * cs.tw;
+    cs.rw = cs.tw + 2; cs.rp = (cs.th + 2) * (cs.tw + 2);
+    if ((int)DLF_C3S_LDS_BYTES(cs.rp, L.d.cin) > max_lds) return false;
+    cs.w = L.d_w; cs.bias = L.d_bias;
+    cs.in_bytes = (uint32_t)((int64_t)batch * L.in_h * L.in_w * L.in_c * 2);
+    cs.batch = batch; cs.h = L.out_h; cs.w_ = L.out_w; cs.cin = L.d.cin; cs.cout = L.d.cout;
+    cs.ncb = L.ncb; cs.nsteps = L.nsteps; cs.act = L.d.act;
+    cs.tiles_y = ceil_div(L.out_h, cs.th); cs.tiles_x = ceil_div(L.out_w, cs.tw);
+    cs.ntiles = batch * cs.tiles_y * cs.tiles_x;
+    cs.ksplit = ksplit;
+    cs.nsl = ceil_div(L.ncb, DLF_C3S_WAVES / ksplit);
+    return true;
+}
+
+uint64_t c3s_cost_ps(const Layer& L, int batch, int budget, const DlfC3sArgs& cs)
+{
+    const int64_t wbytes = (int64_t)L.ncb * L.nsteps * 1024;
+    const int64_t nitems = (int64_t)cs.ntiles * cs.nsl;
+    const int64_t rounds = (nitems + budget - 1) / budget;
+    const int64_t item = C_C3S_ITEM + (rounds > 1 ? C_C3S_NEXT : 0) + (int64_t)cs.rp * cs.cin * 2 / DWS_BYTES_PER_CYCLE +
+                         (int64_t)(cs.nsteps / cs.ksplit) * (wbytes > C_C3S_BIG_BYTES ? C_C3S_STEP_BIG : C_C3S_STEP) +
+                         (cs.ksplit > 1 ? C_C3S_RED : 0) + C_C3S_EPI;
+    const int64_t compute = C_LAT + rounds * item;
+    const int64_t m = (int64_t)batch * L.out_h * L.out_w;
+    const int64_t bytes = m * L.d.cin * 2 + m * L.d.cout * 2 + (int64_t)L.ncb * L.nsteps * 1024;
+    const int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
+    return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
+}
+
+// Cheapest split of K over the waves (ties: the smaller split).
+bool c3s_choose(const Layer& L, int batch, int budget, int max_lds, DlfC3sArgs& best, uint64_t& cost)
+{
+    bool found = false;
+    for (int ks = 1; ks <= 4; ks *= 2) {
+        DlfC3sArgs cs;
+        if (!c3s_build(L, batch, ks, max_lds, cs)) continue;
+        const uint64_t c = c3s_cost_ps(L, batch, budget, cs);
+        if (!found || c < cost) { found = true; cost = c; best = cs; }
+    }
+    return found;
+}
+
 // ---- depthwise + 1x1 kernel for maps of many channels and few pixels ----
 
 bool dws_eligible(const dlf_net_s& net, int first, int last, int batch)
@@ -1389,7 +1460,20 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
             return DLF_OK;
         }
     }
-    if (c3f.mode != 2 && (force.th <= 0 || c3f.mode == 1) && c3_eligible(net, specs, batch)) {
+    // the small-map 3x3 kernel: shape DLF_C3_SHAPES of the testing hook (its th then fixes the split of K)
+    DlfC3sArgs cs;
+    uint64_t c3sc = 0;
+    bool have_c3s = false;
+    if (c3f.mode != 2 && (force.th <= 0 || c3f.mode == 1) && (c3f.shape < 0 || c3f.shape == DLF_C3_SHAPES) &&
+        c3s_eligible(net, specs, batch)) {
+        if (c3f.shape == DLF_C3_SHAPES && c3f.th > 0) {
+            have_c3s = c3s_build(L0, batch, c3f.th, max_lds, cs);
+            if (have_c3s) c3sc = c3s_cost_ps(L0, batch, budget, cs);
+        } else {
+            have_c3s = c3s_choose(L0, batch, budget, max_lds, cs, c3sc);
+        }
+    }
+    if (c3f.mode != 2 && (force.th <= 0 || c3f.mode == 1) && c3f.shape != DLF_C3_SHAPES && c3_eligible(net, specs, batch)) {
         C3Cfg cc;
         uint64_t c3c = 0;
         const int pool2 = specs[0].pool2;
@@ -1400,6 +1484,7 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
         } else {
             have = c3_choose(L0, pool2, batch, budget, max_lds, cc, c3c);
         }
+        if (have && have_c3s && c3sc < c3c) have = false;       // the small-map kernel is cheaper: decided below
         if (have && (!tiled || c3f.mode == 1 || c3c < cost)) {
             DlfC3Args& ca = g.ca;
             memset(&ca, 0, sizeof ca);
@@ -1422,6 +1507,17 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
             if (L0.d.residual_from >= 0) { g.res_layer = L0.d.residual_from; g.res_stage = 0; }
             return DLF_OK;
         }
+    }
+    if (have_c3s && (!tiled || c3f.mode == 1 || c3sc < cost)) {
+        g.cs = cs;
+        g.kind = GK_C3S;
+        g.cost = c3sc;
+        g.variant = cs.ksplit;
+        g.occ = 1;
+        g.grid = ceil_div(cs.ntiles, 8) * 8 * cs.nsl;
+        g.th = cs.th; g.tw = cs.tw;
+        g.lds_bytes = (int)DLF_C3S_LDS_BYTES(cs.rp, cs.cin);
+        return DLF_OK;
     }
     if (!tiled)
         return fail(DLF_ERR_INFEASIBLE, "layers [%d,%d] do not fit on-chip memory as one group", first, last);
@@ -2041,6 +2137,10 @@ static dlf_status launch_one(const dlf_plan_s* plan, const GroupPlan& G, const v
         DlfDwtArgs dt = G.dt;
         dt.in = in; dt.out = out;
         e = dlf_launch_dwt(&dt, G.grid, G.lds_bytes, stream);
+    } else if (G.kind == GK_C3S) {
+        DlfC3sArgs cs = G.cs;
+        cs.in = in; cs.out = out;
+        e = dlf_launch_c3s(&cs, G.grid, G.lds_bytes, stream);
     } else if (G.kind == GK_DWS) {
         DlfDwsArgs ds = G.ds;
         ds.in = in; ds.out = out;

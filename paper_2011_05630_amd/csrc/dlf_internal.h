@@ -254,6 +254,33 @@ struct DlfDwsArgs {
     int32_t nsl;          // slices of the output channels: ceil(ncb / (8 * cbw))
 };
 
+// 3x3 convolution, stride 1, pad 1, on maps of many channels and few pixels (cin 256, 512 or 1024),
+// where the block kernel has too few blocks for the chip and the fused-group kernel's waves each
+// stream their own weights: one workgroup of eight waves per work item = (tile of at most 8 x 8 output
+// pixels, slice of 8 / ksplit 32-channel blocks); the tile's input region, all cin channels, goes to LDS
+// by direct loads; ksplit waves share a channel block's K (whole 32-channel chunks each) and their
+// partial sums meet in LDS.
+#define DLF_C3S_WAVES 8
+#define DLF_C3S_IN_BYTES(RP, CIN) ((((RP) * (CIN) * 2 + 1023) / 1024) * 1024)
+#define DLF_C3S_RED_BYTES (6 * 2 * 16 * 64 * 4)      // up to six waves' accumulators (2 pixel blocks x 16 registers x 64 lanes)
+#define DLF_C3S_EPI_BYTES (DLF_C3S_WAVES * 32 * (32 + 8) * 2)
+#define DLF_C3S_LDS_BYTES(RP, CIN)                                                      \
+    (DLF_C3S_IN_BYTES(RP, CIN) > DLF_C3S_RED_BYTES + DLF_C3S_EPI_BYTES ? DLF_C3S_IN_BYTES(RP, CIN) \
+                                                                     : DLF_C3S_RED_BYTES + DLF_C3S_EPI_BYTES)
+struct DlfC3sArgs {
+    const void* in;       // [batch][h][w][cin] fp16
+    void* out;            // [batch][h][w][cout] fp16
+    const void* w;        // packed weight fragments, K step = (32-channel chunk, tap, half)
+    const float* bias;    // padded to ncb * 32
+    uint32_t in_bytes;    // size of the input tensor (below 2 GiB)
+    int32_t batch, h, w_, cin, cout, ncb, nsteps, act;
+    int32_t th, tw, tp;   // tile of output pixels (each side <= 8), tp = th * tw
+    int32_t rw, rp;       // its input region: tw + 2 columns, (th + 2) * (tw + 2) pixels
+    int32_t tiles_y, tiles_x, ntiles;     // ntiles = batch * tiles_y * tiles_x
+    int32_t ksplit;       // 1, 2 or 4 waves per channel block; divides cin / 32
+    int32_t nsl;          // slices of the output channels: ceil(ncb / (8 / ksplit))
+};
+
 struct DlfGapArgs {
     const void* x;        // [batch][hw][c]
     void* y;              // [batch][c]
@@ -276,6 +303,7 @@ int dlf_launch_dw(const DlfDwArgs* a, int grid, void* stream);
 int dlf_launch_dwpw(const DlfDwPwArgs* a, int nb, int grid, void* stream);
 int dlf_launch_dwt(const DlfDwtArgs* a, int grid, int lds_bytes, void* stream);
 int dlf_launch_dws(const DlfDwsArgs* a, int grid, int lds_bytes, void* stream);
+int dlf_launch_c3s(const DlfC3sArgs* a, int grid, int lds_bytes, void* stream);
 int dlf_kernels_init(void);
 // Attaches a start / stop event pair (hipEvent_t, either may be null) to this thread's next launch.
 void dlf_next_launch_events(void* start, void* stop);

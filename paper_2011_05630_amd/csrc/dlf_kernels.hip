@@ -2793,6 +2793,191 @@ __global__ __launch_bounds__(DLF_DWS_WAVES * 64, 1) void k_dws(const DlfDwsArgs 
     }
 }
 
+// 3x3 convolution (stride 1, pad 1, bias, activation) where a map has many channels and few pixels:
+// the 14 x 14 and 7 x 7 maps of ResNet-50's and VGG-16's last stages.  The block kernel k_c3b has too
+// few 128-channel x 256-pixel blocks there to fill the chip, and in the fused-group kernel every wave
+// streams weights for one or two pixel blocks of its own.  Built like k_dws:
+//   Work item = (tile of up to 8 x 8 output pixels, slice of 8 / ksplit channel blocks): one workgroup
+// of eight waves, one item, one workgroup per CU; the slices of a tile run on one XCD.
+//   1. The tile's input region, all cin channels, global -> LDS by direct loads with the hardware's
+//      range check supplying the padding (written as instructions, waits counted by hand, as in
+//      k_dws).  Within a pixel the 16-byte parts are stored permuted, part q of region pixel h at
+//      position q ^ (h % 16): an MFMA "B" fragment reads one part of 32 pixels whose region indices
+//      are nearly consecutive, a pixel's cin * 2 bytes are a multiple of all 64 banks, and so the
+//      position alone picks the bank group; 16 pixels with different h % 16 read conflict-free.
+//   2. Every wave one channel block x the tile's two 32-pixel blocks; ksplit waves share a channel
+//      block, each taking whole 32-channel chunks of K (18 K steps a chunk: nine taps x two halves,
+//      the order the weights are packed in, so a wave's fragments are one contiguous stream through
+//      a register ring of 9 K steps).  The tap of a K step is static in the unrolled chunk, so the
+//      lane's nine (tap-shifted pixel, permutation) pairs stay in registers.
+//   3. Partial sums of the waves of a channel block meet in LDS (in the region's space, behind a
+//      barrier); bias, activation, fp16, transpose, 64-byte runs per pixel to memory.
+__global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs a)
+{
+    constexpr int D = 9;
+    constexpr int ROW = 32 + 8;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int pp_shift = __builtin_ctz(a.cin) - 3;           // 16-byte parts per pixel = cin / 8 (32, 64 or 128)
+    const int per8 = blockIdx.x >> 3;
+    const int sl = per8 % a.nsl, tile = (per8 / a.nsl) * 8 + (blockIdx.x & 7);
+    if (tile >= a.ntiles) return;
+    int r_ = tile;
+    const int tx = r_ % a.tiles_x;
+    r_ /= a.tiles_x;
+    const int ty = r_ % a.tiles_y, n = r_ / a.tiles_y;
+    const int oy0 = ty * a.th, ox0 = tx * a.tw;
+    const int ncbw = DLF_C3S_WAVES / a.ksplit;               // channel blocks of the item
+    const int cbw = wave % ncbw, kpart = wave / ncbw;
+    const int cb = sl * ncbw + cbw;
+    const bool live = cb < a.ncb;                            // uniform
+    half_t* outp = (half_t*)a.out;
+    const unsigned lo_e = act_lo(a.act), hi_e = act_hi(a.act);
+    const unsigned tw_m = div_magic(a.tw), rw_m = div_magic(a.rw);
+
+    // ---- step 1: the region ----
+    const i32x4 rin = make_rsrc(a.in, a.in_bytes);
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) half_t*)lds;
+    const int nparts = a.rp << pp_shift;
+    const int ni = (nparts + 63) >> 6;
+#pragma unroll 1
+    for (int i = wave; i < ni; i += DLF_C3S_WAVES) {
+        const int idx = i * 64 + lane;
+        const int hp = idx >> pp_shift, pos = idx & ((1 << pp_shift) - 1);
+        unsigned off = (unsigned)DLF_OOB;
+        if (hp < a.rp) {
+            const int ry = div_by(hp, rw_m), rx = hp - ry * a.rw;
+            const int gy = oy0 - 1 + ry, gx = ox0 - 1 + rx;
+            if (gy >= 0 && gy < a.h && gx >= 0 && gx < a.w_)
+                off = (unsigned)(((n * a.h + gy) * a.w_ + gx) * a.cin + ((pos ^ (hp & 15)) << 3)) * 2u;
+        }
+        asm volatile("s_mov_b32 m0, %2\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(off), "s"(rin),
+                     "s"(lds0 + (unsigned)i * 1024u)
+                     : "memory", "m0");
+    }
+
+    // ---- the wave's weight stream ----
+    const i32x4 rwt = make_rsrc(a.w, 0xffffffffu);
+    const int lane16 = lane * 16;
+    const int nchunk = (a.cin >> 5) / a.ksplit;              // 32-channel chunks of this wave
+    const int c32_0 = kpart * nchunk;
+    const unsigned wo = (unsigned)__builtin_amdgcn_readfirstlane((min(cb, a.ncb - 1) * a.nsteps + c32_0 * 18) * 1024);
+    const int n_mine = nchunk * 18;
+    int pf_ks = 0;
+    h8 ar[D];
+    auto request = [&](int slot) __attribute__((always_inline)) {
+        ar[slot] = wfrag(rwt, lane16, wo + (unsigned)min(pf_ks, n_mine - 1) * 1024u);   // past the end: re-read, never used
+        ++pf_ks;
+    };
+    if (live) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) request(d);
+    }
+
+    // the lane's two pixels under each of the nine taps: byte offset of the region pixel, and the
+    // permutation of that pixel combined with the lane's K half, as a byte offset (16 * (h % 16 ^ lhi))
+    int bt[9][2], ft[9][2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int px_ = min(p * 32 + l32, a.tp - 1);
+        const int py = div_by(px_, tw_m), pxx = px_ - py * a.tw;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const int hp = (py + t / 3) * a.rw + pxx + t % 3;
+            bt[t][p] = hp * a.cin * 2;
+            ft[t][p] = ((hp & 15) ^ lhi) << 4;
+        }
+    }
+    f16v acc[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[p][q] = 0.0f;
+
+    if (live) wait_vmcnt<D>(); else wait_vmcnt<0>();         // the region has landed: only the ring's requests are behind it
+    asm volatile("s_barrier" ::: "memory");
+
+    // ---- step 2: K loop ----
+    if (live) {
+        const char* const region = (const char*)lds;
+        // (the fragments of step s + 1 are read before step s is multiplied; a ring slot is requested
+        // again right behind its multiplies)
+        h8 bf[2][2];
+#pragma unroll
+        for (int p = 0; p < 2; ++p) bf[0][p] = *(const h8*)(region + bt[0][p] + ((c32_0 * 64) ^ ft[0][p]));
+#pragma unroll 1
+        for (int c = 0; c < nchunk; ++c) {
+            const int q16 = (c32_0 + c) * 64;                // byte offset of the chunk's first part, before the permutation
+            const int q16n = (c32_0 + min(c + 1, nchunk - 1)) * 64;
+#pragma unroll
+            for (int j = 0; j < 18; ++j) {
+                const int jn = (j + 1) % 18, tn = jn >> 1;
+                const int qn = (j == 17 ? q16n : q16) + (jn & 1) * 32;
+#pragma unroll
+                for (int p = 0; p < 2; ++p) bf[(j + 1) & 1][p] = *(const h8*)(region + bt[tn][p] + (qn ^ ft[tn][p]));
+#pragma unroll
+                for (int p = 0; p < 2; ++p)
+                    acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[j % D], bf[j & 1][p], acc[p], 0, 0, 0);
+                request(j % D);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+    // ---- step 3: partial sums, epilogue ----
+    float* const red = (float*)lds;
+    half_t* const tb = lds + DLF_C3S_RED_BYTES / 2 + wave * (32 * ROW);
+    if (a.ksplit > 1) {
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // everyone is done reading the region
+        if (kpart > 0 && live) {
+            float* dst = red + (wave - ncbw) * (2 * 16 * 64) + lane;
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) dst[(p * 16 + q) * 64] = acc[p][q];
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        if (kpart > 0 || !live) return;
+        for (int k = 1; k < a.ksplit; ++k) {
+            const float* src = red + (k * ncbw + cbw - ncbw) * (2 * 16 * 64) + lane;
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) acc[p][q] += src[(p * 16 + q) * 64];
+        }
+    } else {
+        if (!live) return;
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // the transpose buffers lie in the region's space
+    }
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        if (p * 32 < a.tp) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f4v bias = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
+                unsigned u0 = cvt_pk(acc[p][q * 4 + 0] + bias[0], acc[p][q * 4 + 1] + bias[1]);
+                unsigned u1 = cvt_pk(acc[p][q * 4 + 2] + bias[2], acc[p][q * 4 + 3] + bias[3]);
+                u0 = pk_min(pk_max(u0, lo_e), hi_e);
+                u1 = pk_min(pk_max(u1, lo_e), hi_e);
+                const u2v uu = {u0, u1};
+                *(u2v*)(tb + l32 * ROW + q * 8 + lhi * 4) = uu;
+            }
+            __builtin_amdgcn_wave_barrier();
+            const int part = lane & 3;
+            const int cc = cb * 32 + part * 8;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int pl = i * 16 + (lane >> 2);
+                const int px_ = p * 32 + pl;
+                const int row = div_by(px_, tw_m), colp = px_ - row * a.tw;
+                const int oy = oy0 + row, ox = ox0 + colp;
+                if (px_ < a.tp && oy < a.h && ox < a.w_ && cc < a.cout)
+                    *(u4v*)(outp + ((size_t)((n * a.h + oy) * a.w_ + ox) * a.cout + cc)) = *(const u4v*)(tb + pl * ROW + part * 8);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+
 extern "C" int dlf_launch_dw(const DlfDwArgs* a, int grid, void* stream);
 
 // Fully connected layer (Eq. 2 with M = batch): y[n][co] = act(bias[co] + sum_k x[n][k] w[co][k]).
@@ -3053,6 +3238,10 @@ extern "C" int dlf_kernels_init(void)
         if (e != hipSuccess) return (int)e;
     }
     {
+        hipError_t e = hipFuncSetAttribute((const void*)k_c3s, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return (int)e;
+    }
+    {
         const void* ks[4] = {(const void*)k_dws<1, 1>, (const void*)k_dws<1, 2>, (const void*)k_dws<2, 1>, (const void*)k_dws<2, 2>};
         for (const void* k : ks) {
             hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -3200,6 +3389,25 @@ extern "C" int dlf_launch_dws(const DlfDwsArgs* a, int grid, int lds_bytes, void
     else if (a->stride == 1) launch(k_dws<1, 2>, dim3(grid), block, (size_t)lds_bytes, (hipStream_t)stream, *a);
     else if (a->cbw == 1) launch(k_dws<2, 1>, dim3(grid), block, (size_t)lds_bytes, (hipStream_t)stream, *a);
     else launch(k_dws<2, 2>, dim3(grid), block, (size_t)lds_bytes, (hipStream_t)stream, *a);
+    return (int)hipGetLastError();
+}
+
+extern "C" int dlf_launch_c3s(const DlfC3sArgs* a, int grid, int lds_bytes, void* stream)
+{
+    // what the kernel's indexing assumes
+    if (grid <= 0 || (grid & 7) != 0 || a->in_bytes >= 0x80000000u) return (int)hipErrorInvalidValue;
+    if ((a->cin != 256 && a->cin != 512 && a->cin != 1024) || a->nsteps != (a->cin / 32) * 18 || (a->cout & 7) != 0)
+        return (int)hipErrorInvalidValue;
+    if ((a->ksplit != 1 && a->ksplit != 2 && a->ksplit != 4) || ((a->cin / 32) % a->ksplit) != 0 ||
+        a->nsl != (a->ncb + DLF_C3S_WAVES / a->ksplit - 1) / (DLF_C3S_WAVES / a->ksplit))
+        return (int)hipErrorInvalidValue;
+    if (a->th < 1 || a->th > 8 || a->tw < 1 || a->tw > 8 || a->tp != a->th * a->tw || a->rw != a->tw + 2 ||
+        a->rp != (a->th + 2) * (a->tw + 2) || a->tiles_y != (a->h + a->th - 1) / a->th ||
+        a->tiles_x != (a->w_ + a->tw - 1) / a->tw || a->ntiles != a->batch * a->tiles_y * a->tiles_x ||
+        grid != (a->ntiles + 7) / 8 * 8 * a->nsl)
+        return (int)hipErrorInvalidValue;
+    if (lds_bytes != (int)DLF_C3S_LDS_BYTES(a->rp, a->cin) || lds_bytes > 160 * 1024) return (int)hipErrorInvalidValue;
+    launch(k_c3s, dim3(grid), dim3(DLF_C3S_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
     return (int)hipGetLastError();
 }
 

@@ -622,6 +622,41 @@ def test_block3x3_kernel(cin, cout, h, w, batch, shape, th, tw, pool, act, res):
     compare(got, ref, "block 3x3 %d->%d %dx%d shape %d tile %dx%d" % (cin, cout, h, w, shape, th, tw))
 
 
+# (channels in, channels out, height, width, batch, waves per channel block (0 = the planner's choice),
+# activation): the 3x3 kernel for maps of many channels and few pixels: 32, 64 and 128 sixteen-byte
+# parts per pixel, K whole or split over 2 or 4 waves, several slices of the output channels and a
+# ragged last one, waves without a channel block, maps of one tile and of several with the last row /
+# column of tiles overhanging, tiles of fewer than 32 pixels, a one-pixel map
+C3S_CASES = [(256, 256, 14, 14, 2, 2, "relu"), (256, 256, 14, 14, 3, 1, "relu"), (512, 512, 7, 7, 2, 4, "relu"),
+             (512, 512, 14, 14, 1, 2, "relu6"), (1024, 256, 5, 6, 2, 1, "relu"), (256, 200, 9, 11, 2, 4, "none"),
+             (512, 96, 3, 5, 3, 2, "relu"), (256, 1024, 1, 1, 4, 0, "relu"), (512, 640, 17, 8, 1, 0, "relu"),
+             (256, 64, 7, 7, 4, 0, "relu"), (1024, 1024, 4, 4, 1, 4, "relu")]
+
+
+@pytest.mark.parametrize("cin,cout,h,w,batch,ksplit,act", C3S_CASES)
+def test_small_map_3x3_kernel(cin, cout, h, w, batch, ksplit, act):
+    from oracle import oracle as o
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    announce("small-map 3x3", cin, cout, h, w, batch, ksplit, act)
+    net = _mk([nets.conv(cin, cout, 3, 1, 1, act)], h, w, cin, dist="normal")
+    x, ws, bs = gen.make_params(net, batch, 12)
+    B.dlf_debug_block3x3_mode(1, 5, ksplit, 0)        # shape 5: this kernel; th = waves per channel block
+    try:
+        s = Session(net, batch, ws, bs, **_manual(1, [0]))
+    finally:
+        B.dlf_debug_block3x3_mode(0)
+    try:
+        cfg = B.dlf_plan_group_config(s.plan, 0)
+        assert cfg["kind"] == 10, cfg
+        if ksplit:
+            assert cfg["variant"] == ksplit, cfg
+        got = s.run_numpy(x)
+    finally:
+        s.close()
+    compare(got, o.run_net(net, x, ws, bs), "small-map 3x3 %d->%d %dx%d" % (cin, cout, h, w))
+
+
 def test_block3x3_kernel_random_shapes():
     """Seeded random layers, block shapes, pixel tiles, budgets, batches, folded pools and residual
     operands for the block 3x3 kernel (every case one it accepts), against the oracle."""

@@ -25,7 +25,7 @@ def _manual(lasts, budget):
     return dict(mode=B.TUNER_MANUAL, group_last=list(lasts), group_budget=[budget] * len(lasts))
 
 
-KIND_NAME = {0: "group", 1: "fc", 2: "gap", 3: "pw", 4: "c3b", 5: "dw", 6: "dwpw", 7: "dwt", 8: "pw2", 9: "dws"}
+KIND_NAME = {0: "group", 1: "fc", 2: "gap", 3: "pw", 4: "c3b", 5: "dw", 6: "dwpw", 7: "dwt", 8: "pw2", 9: "dws", 10: "c3s"}
 
 
 def _kinds(s):
