@@ -288,9 +288,10 @@ const int64_t C_DWS_MMA = 120;
 const int64_t C_DWS_EPI = 2500;
 const int64_t DWS_BYTES_PER_CYCLE = 64;
 // small-map 3x3 kernel: per work item a fixed part (beyond the launch's own round trip), per K step of a
-// wave two MFMAs beside those of the SIMD's other wave -- or, when the layer's weights do not fit an
-// XCD's L2 (4 MiB) and every CU streams them at once, what the fabric behind it delivers --, the
-// exchange of partial sums, the epilogue; a CU's further items each pay the region's trip to memory
+// wave two MFMAs beside those of the SIMD's other wave -- 128 cycles at the pipe's rate, measured on the
+// 256-channel layers; the 512-channel layers (weights above 3 MiB, K loops of 30 thousand cycles) run at
+// 215 whether an XCD's L2 holds all of its weights or not: the rate the matrix pipes sustain on such
+// operands --, the exchange of partial sums, the epilogue; a CU's further items each pay the region's trip to memory
 // and the store drain in full (one workgroup per CU: nothing overlaps them)
 const int64_t C_C3S_ITEM = 3000;
 const int64_t C_C3S_NEXT = 13000;
@@ -1132,6 +1133,8 @@ bool c3s_build(const Layer& L, int batch, int ksplit, int max_lds, DlfC3sArgs& c
     cs.ntiles = batch * cs.tiles_y * cs.tiles_x;
     cs.ksplit = ksplit;
     cs.nsl = ceil_div(L.ncb, DLF_C3S_WAVES / ksplit);
+    // weights that do not fit an XCD's L2: let every XCD keep to one slice of them
+    cs.slice_major = ((int64_t)L.ncb * L.nsteps * 1024 > C_C3S_BIG_BYTES && (cs.nsl == 2 || cs.nsl == 4 || cs.nsl == 8)) ? 1 : 0;
     return true;
 }
 
@@ -1514,7 +1517,7 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
         g.cost = c3sc;
         g.variant = cs.ksplit;
         g.occ = 1;
-        g.grid = ceil_div(cs.ntiles, 8) * 8 * cs.nsl;
+        g.grid = cs.slice_major ? ceil_div(cs.ntiles, 8 / cs.nsl) * 8 : ceil_div(cs.ntiles, 8) * 8 * cs.nsl;
         g.th = cs.th; g.tw = cs.tw;
         g.lds_bytes = (int)DLF_C3S_LDS_BYTES(cs.rp, cs.cin);
         return DLF_OK;

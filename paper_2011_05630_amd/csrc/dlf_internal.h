@@ -279,6 +279,7 @@ struct DlfC3sArgs {
     int32_t tiles_y, tiles_x, ntiles;     // ntiles = batch * tiles_y * tiles_x
     int32_t ksplit;       // 1, 2 or 4 waves per channel block; divides cin / 32
     int32_t nsl;          // slices of the output channels: ceil(ncb / (8 / ksplit))
+    int32_t slice_major;  // 1: an XCD keeps to one slice (nsl 2, 4 or 8); 0: the slices of a tile share an XCD
 };
 
 struct DlfGapArgs {

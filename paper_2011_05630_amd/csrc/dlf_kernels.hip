@@ -2801,10 +2801,13 @@ __global__ __launch_bounds__(DLF_DWS_WAVES * 64, 1) void k_dws(const DlfDwsArgs 
 // of eight waves, one item, one workgroup per CU; the slices of a tile run on one XCD.
 //   1. The tile's input region, all cin channels, global -> LDS by direct loads with the hardware's
 //      range check supplying the padding (written as instructions, waits counted by hand, as in
-//      k_dws).  Within a pixel the 16-byte parts are stored permuted, part q of region pixel h at
-//      position q ^ (h % 16): an MFMA "B" fragment reads one part of 32 pixels whose region indices
-//      are nearly consecutive, a pixel's cin * 2 bytes are a multiple of all 64 banks, and so the
-//      position alone picks the bank group; 16 pixels with different h % 16 read conflict-free.
+//      k_dws).  Within a pixel the 16-byte parts are stored permuted, part q of the region pixel in
+//      row r, column c at position q ^ ((r * tw + c) % 16): a pixel's cin * 2 bytes are a multiple
+//      of all 64 banks, so the position alone picks the bank group; an MFMA "B" fragment reads one
+//      part of 32 consecutive tile pixels shifted by a tap, for which r * tw + c runs through
+//      consecutive integers (tile pixel + a constant): any 16 of them read conflict-free.  (With
+//      the region's own pixel index in its place the row breaks of a 7-wide tile in a 9-wide
+//      region repeat two of 16 values: SQ_LDS_BANK_CONFLICT at 48 % of the LDS cycles.)
 //   2. Every wave one channel block x the tile's two 32-pixel blocks; ksplit waves share a channel
 //      block, each taking whole 32-channel chunks of K (18 K steps a chunk: nine taps x two halves,
 //      the order the weights are packed in, so a wave's fragments are one contiguous stream through
@@ -2819,8 +2822,19 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
     const int pp_shift = __builtin_ctz(a.cin) - 3;           // 16-byte parts per pixel = cin / 8 (32, 64 or 128)
-    const int per8 = blockIdx.x >> 3;
-    const int sl = per8 % a.nsl, tile = (per8 / a.nsl) * 8 + (blockIdx.x & 7);
+    // Work item of the workgroup.  Workgroup i runs on XCD i % 8.  Either the slices of a tile share an
+    // XCD (its L2 fetches the tile's region once, and every XCD fetches all the weights), or an XCD
+    // keeps to one slice (8 / nsl XCDs share the tiles of a slice: each L2 holds 1 / nsl of the weights
+    // and fetches every region its tiles need) -- the host chooses by which of the two is larger.
+    const int per8 = blockIdx.x >> 3, xcd = blockIdx.x & 7;
+    int sl, tile;
+    if (a.slice_major) {
+        sl = xcd % a.nsl;
+        tile = per8 * (8 / a.nsl) + xcd / a.nsl;
+    } else {
+        sl = per8 % a.nsl;
+        tile = (per8 / a.nsl) * 8 + xcd;
+    }
     if (tile >= a.ntiles) return;
     int r_ = tile;
     const int tx = r_ % a.tiles_x;
@@ -2849,7 +2863,7 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
             const int ry = div_by(hp, rw_m), rx = hp - ry * a.rw;
             const int gy = oy0 - 1 + ry, gx = ox0 - 1 + rx;
             if (gy >= 0 && gy < a.h && gx >= 0 && gx < a.w_)
-                off = (unsigned)(((n * a.h + gy) * a.w_ + gx) * a.cin + ((pos ^ (hp & 15)) << 3)) * 2u;
+                off = (unsigned)(((n * a.h + gy) * a.w_ + gx) * a.cin + ((pos ^ ((ry * a.tw + rx) & 15)) << 3)) * 2u;
         }
         asm volatile("s_mov_b32 m0, %2\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(off), "s"(rin),
                      "s"(lds0 + (unsigned)i * 1024u)
@@ -2883,9 +2897,9 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
         const int py = div_by(px_, tw_m), pxx = px_ - py * a.tw;
 #pragma unroll
         for (int t = 0; t < 9; ++t) {
-            const int hp = (py + t / 3) * a.rw + pxx + t % 3;
-            bt[t][p] = hp * a.cin * 2;
-            ft[t][p] = ((hp & 15) ^ lhi) << 4;
+            const int ry = py + t / 3, rx = pxx + t % 3;
+            bt[t][p] = (ry * a.rw + rx) * a.cin * 2;
+            ft[t][p] = (((ry * a.tw + rx) & 15) ^ lhi) << 4;
         }
     }
     f16v acc[2];
@@ -3404,7 +3418,9 @@ extern "C" int dlf_launch_c3s(const DlfC3sArgs* a, int grid, int lds_bytes, void
     if (a->th < 1 || a->th > 8 || a->tw < 1 || a->tw > 8 || a->tp != a->th * a->tw || a->rw != a->tw + 2 ||
         a->rp != (a->th + 2) * (a->tw + 2) || a->tiles_y != (a->h + a->th - 1) / a->th ||
         a->tiles_x != (a->w_ + a->tw - 1) / a->tw || a->ntiles != a->batch * a->tiles_y * a->tiles_x ||
-        grid != (a->ntiles + 7) / 8 * 8 * a->nsl)
+        (a->slice_major != 0 && a->slice_major != 1) ||
+        (a->slice_major && (a->nsl != 2 && a->nsl != 4 && a->nsl != 8)) ||
+        grid != (a->slice_major ? (a->ntiles + 8 / a->nsl - 1) / (8 / a->nsl) * 8 : (a->ntiles + 7) / 8 * 8 * a->nsl))
         return (int)hipErrorInvalidValue;
     if (lds_bytes != (int)DLF_C3S_LDS_BYTES(a->rp, a->cin) || lds_bytes > 160 * 1024) return (int)hipErrorInvalidValue;
     launch(k_c3s, dim3(grid), dim3(DLF_C3S_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
