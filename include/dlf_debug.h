@@ -28,7 +28,8 @@ void dlf_debug_force_ksplit(int32_t ksplit);
  * pointwise kernel: 0 = by modelled cost (default), 1 = pointwise wherever it applies, 2 = never,
  * 3 / 4 / 5 = pointwise wherever it applies with 64x64 / 32x32 / split-K 64x64 work items,
  * 6 / 7 = with workgroup blocks of 128 channels x 128 pixels / 64 channels x 256 pixels whose
- * operands are shared through LDS.  Process-wide, not thread-safe. */
+ * operands are shared through LDS, 8 = on the kernel for maps of many channels and few pixels (cin 256,
+ * 512 or 1024, stride 1, no residual) wherever that applies.  Process-wide, not thread-safe. */
 void dlf_debug_pointwise_mode(int32_t mode);
 
 /* Testing hook: how a single depthwise 3x3 layer (pad 1, stride 1 or 2), or such a layer with the 1x1

@@ -1115,15 +1115,25 @@ bool c3s_eligible(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
     return (L.d.cin == 256 || L.d.cin == 512 || L.d.cin == 1024) && L.d.residual_from < 0 && (L.d.cout % 8) == 0;
 }
 
+// The same kernel takes 1x1 layers (stride 1, no residual) of those channel counts.
+bool c3s_pw_eligible(const Layer& L, int batch)
+{
+    if (!pw_eligible(L, batch) || L.d.stride != 1 || L.d.residual_from >= 0) return false;
+    if ((int64_t)batch * L.in_h * L.in_w * L.in_c * 2 >= (int64_t)1 << 31) return false;
+    return L.d.cin == 256 || L.d.cin == 512 || L.d.cin == 1024;
+}
+
 bool c3s_build(const Layer& L, int batch, int ksplit, int max_lds, DlfC3sArgs& cs)
 {
     memset(&cs, 0, sizeof cs);
-    if ((ksplit != 1 && ksplit != 2 && ksplit != 4) || ((L.d.cin / 32) % ksplit) != 0) return false;
+    cs.taps = L.d.kh * L.d.kw;
+    const int halo = cs.taps == 9 ? 1 : 0, chunks = L.d.cin / (cs.taps == 9 ? 32 : 128);
+    if ((cs.taps != 9 && cs.taps != 1) || (ksplit != 1 && ksplit != 2 && ksplit != 4) || (chunks % ksplit) != 0) return false;
     // the map is cut into equal tiles of at most 8 x 8 output pixels
     cs.th = ceil_div(L.out_h, ceil_div(L.out_h, 8));
     cs.tw = ceil_div(L.out_w, ceil_div(L.out_w, 8));
     cs.tp = cs.th * cs.tw;
-    cs.rw = cs.tw + 2; cs.rp = (cs.th + 2) * (cs.tw + 2);
+    cs.rw = cs.tw + 2 * halo; cs.rp = (cs.th + 2 * halo) * (cs.tw + 2 * halo);
     if ((int)DLF_C3S_LDS_BYTES(cs.rp, L.d.cin) > max_lds) return false;
     cs.w = L.d_w; cs.bias = L.d_bias;
     cs.in_bytes = (uint32_t)((int64_t)batch * L.in_h * L.in_w * L.in_c * 2);
@@ -1338,9 +1348,27 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
     const bool tiled = choose_group(net, specs, batch, budget, max_lds, b, tc, cost, force);
     const bool pw_ok = first == last && pw_eligible(L0, batch) && pwm != 2 &&
                        (force.th <= 0 || pwm == 1 || pwm >= 3);
-    if (pw_ok) {
+    // a 1x1 layer on the small-map kernel: pointwise mode 8 of the testing hook forces it
+    DlfC3sArgs pcs;
+    uint64_t pcsc = 0;
+    const bool have_pcs = first == last && (pwm == 0 || pwm == 8) && (force.th <= 0 || pwm == 8) &&
+                          c3s_pw_eligible(L0, batch) && c3s_choose(L0, batch, budget, max_lds, pcs, pcsc);
+    auto take_pcs = [&]() {
+        g.cs = pcs;
+        g.kind = GK_C3S;
+        g.cost = pcsc;
+        g.variant = 8 + pcs.ksplit;
+        g.occ = 1;
+        g.grid = pcs.slice_major ? ceil_div(pcs.ntiles, 8 / pcs.nsl) * 8 : ceil_div(pcs.ntiles, 8) * 8 * pcs.nsl;
+        g.th = pcs.th; g.tw = pcs.tw;
+        g.lds_bytes = (int)DLF_C3S_LDS_BYTES(pcs.rp, pcs.cin);
+        return DLF_OK;
+    };
+    if (have_pcs && pwm == 8) return take_pcs();
+    if (pw_ok && pwm != 8) {
         int shape = 0;
         uint64_t pc = pw_cost_ps(L0, batch, budget, shape);
+        if (have_pcs && pcsc < pc && (!tiled || pcsc < cost)) return take_pcs();
         if (pwm >= 3) {
             shape = pwm - 3;
             if (PW_KSPLIT[shape] > 1 && !pw_shape_ok(L0, shape)) shape = 0;
@@ -2057,7 +2085,7 @@ dlf_status dlf_plan_group_io(const dlf_plan_t* plan, int32_t g, int32_t* in_laye
     return DLF_OK;
 }
 
-void dlf_debug_pointwise_mode(int32_t mode) { g_pw_mode = (mode >= 0 && mode <= 7) ? mode : 0; }
+void dlf_debug_pointwise_mode(int32_t mode) { g_pw_mode = (mode >= 0 && mode <= 8) ? mode : 0; }
 
 void dlf_debug_depthwise_mode(int32_t mode) { g_dw_mode = (mode >= 0 && mode <= 4) ? mode : 0; }
 

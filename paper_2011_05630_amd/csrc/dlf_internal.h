@@ -254,7 +254,7 @@ struct DlfDwsArgs {
     int32_t nsl;          // slices of the output channels: ceil(ncb / (8 * cbw))
 };
 
-// 3x3 convolution, stride 1, pad 1, on maps of many channels and few pixels (cin 256, 512 or 1024),
+// 3x3 convolution, stride 1, pad 1 (or 1x1, stride 1) on maps of many channels and few pixels (cin 256, 512 or 1024),
 // where the block kernel has too few blocks for the chip and the fused-group kernel's waves each
 // stream their own weights: one workgroup of eight waves per work item = (tile of at most 8 x 8 output
 // pixels, slice of 8 / ksplit 32-channel blocks); the tile's input region, all cin channels, goes to LDS
@@ -274,10 +274,11 @@ struct DlfC3sArgs {
     const float* bias;    // padded to ncb * 32
     uint32_t in_bytes;    // size of the input tensor (below 2 GiB)
     int32_t batch, h, w_, cin, cout, ncb, nsteps, act;
+    int32_t taps;         // 9: 3x3, pad 1; 1: 1x1
     int32_t th, tw, tp;   // tile of output pixels (each side <= 8), tp = th * tw
-    int32_t rw, rp;       // its input region: tw + 2 columns, (th + 2) * (tw + 2) pixels
+    int32_t rw, rp;       // its input region: tw + 2 columns, (th + 2) * (tw + 2) pixels (1x1: the tile itself)
     int32_t tiles_y, tiles_x, ntiles;     // ntiles = batch * tiles_y * tiles_x
-    int32_t ksplit;       // 1, 2 or 4 waves per channel block; divides cin / 32
+    int32_t ksplit;       // 1, 2 or 4 waves per channel block; divides cin / 32 (1x1: cin / 128)
     int32_t nsl;          // slices of the output channels: ceil(ncb / (8 / ksplit))
     int32_t slice_major;  // 1: an XCD keeps to one slice (nsl 2, 4 or 8); 0: the slices of a tile share an XCD
 };

@@ -2793,8 +2793,8 @@ __global__ __launch_bounds__(DLF_DWS_WAVES * 64, 1) void k_dws(const DlfDwsArgs 
     }
 }
 
-// 3x3 convolution (stride 1, pad 1, bias, activation) where a map has many channels and few pixels:
-// the 14 x 14 and 7 x 7 maps of ResNet-50's and VGG-16's last stages.  The block kernel k_c3b has too
+// 3x3 convolution (stride 1, pad 1) or 1x1 convolution (stride 1), + bias + activation, where a map has
+// many channels and few pixels: the 14 x 14 and 7 x 7 maps of ResNet-50's and VGG-16's last stages.  The block kernel k_c3b has too
 // few 128-channel x 256-pixel blocks there to fill the chip, and in the fused-group kernel every wave
 // streams weights for one or two pixel blocks of its own.  Built like k_dws:
 //   Work item = (tile of up to 8 x 8 output pixels, slice of 8 / ksplit channel blocks): one workgroup
@@ -2815,9 +2815,14 @@ __global__ __launch_bounds__(DLF_DWS_WAVES * 64, 1) void k_dws(const DlfDwsArgs 
 //      lane's nine (tap-shifted pixel, permutation) pairs stay in registers.
 //   3. Partial sums of the waves of a channel block meet in LDS (in the region's space, behind a
 //      barrier); bias, activation, fp16, transpose, 64-byte runs per pixel to memory.
+template <int TAPS>
 __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs a)
 {
-    constexpr int D = 9;
+    static_assert(TAPS == 9 || TAPS == 1, "3x3 (pad 1) or 1x1 (pad 0)");
+    constexpr int HALO = TAPS == 9 ? 1 : 0;
+    constexpr int CH = TAPS == 9 ? 32 : 128;                 // channels of a chunk of K
+    constexpr int STEPS = TAPS * CH / 16;                    // its K steps: 18 or 8, in the order the weights are packed
+    constexpr int D = TAPS == 9 ? 9 : 8;                     // ring depth: divides STEPS
     constexpr int ROW = 32 + 8;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
@@ -2861,7 +2866,7 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
         unsigned off = (unsigned)DLF_OOB;
         if (hp < a.rp) {
             const int ry = div_by(hp, rw_m), rx = hp - ry * a.rw;
-            const int gy = oy0 - 1 + ry, gx = ox0 - 1 + rx;
+            const int gy = oy0 - HALO + ry, gx = ox0 - HALO + rx;
             if (gy >= 0 && gy < a.h && gx >= 0 && gx < a.w_)
                 off = (unsigned)(((n * a.h + gy) * a.w_ + gx) * a.cin + ((pos ^ ((ry * a.tw + rx) & 15)) << 3)) * 2u;
         }
@@ -2873,10 +2878,10 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
     // ---- the wave's weight stream ----
     const i32x4 rwt = make_rsrc(a.w, 0xffffffffu);
     const int lane16 = lane * 16;
-    const int nchunk = (a.cin >> 5) / a.ksplit;              // 32-channel chunks of this wave
+    const int nchunk = (a.cin / CH) / a.ksplit;              // chunks of this wave
     const int c32_0 = kpart * nchunk;
-    const unsigned wo = (unsigned)__builtin_amdgcn_readfirstlane((min(cb, a.ncb - 1) * a.nsteps + c32_0 * 18) * 1024);
-    const int n_mine = nchunk * 18;
+    const unsigned wo = (unsigned)__builtin_amdgcn_readfirstlane((min(cb, a.ncb - 1) * a.nsteps + c32_0 * STEPS) * 1024);
+    const int n_mine = nchunk * STEPS;
     int pf_ks = 0;
     h8 ar[D];
     auto request = [&](int slot) __attribute__((always_inline)) {
@@ -2890,13 +2895,13 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
 
     // the lane's two pixels under each of the nine taps: byte offset of the region pixel, and the
     // permutation of that pixel combined with the lane's K half, as a byte offset (16 * (h % 16 ^ lhi))
-    int bt[9][2], ft[9][2];
+    int bt[TAPS][2], ft[TAPS][2];
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
         const int px_ = min(p * 32 + l32, a.tp - 1);
         const int py = div_by(px_, tw_m), pxx = px_ - py * a.tw;
 #pragma unroll
-        for (int t = 0; t < 9; ++t) {
+        for (int t = 0; t < TAPS; ++t) {
             const int ry = py + t / 3, rx = pxx + t % 3;
             bt[t][p] = (ry * a.rw + rx) * a.cin * 2;
             ft[t][p] = (((ry * a.tw + rx) & 15) ^ lhi) << 4;
@@ -2918,15 +2923,16 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
         // again right behind its multiplies)
         h8 bf[2][2];
 #pragma unroll
-        for (int p = 0; p < 2; ++p) bf[0][p] = *(const h8*)(region + bt[0][p] + ((c32_0 * 64) ^ ft[0][p]));
+        for (int p = 0; p < 2; ++p) bf[0][p] = *(const h8*)(region + bt[0][p] + ((c32_0 * (CH * 2)) ^ ft[0][p]));
 #pragma unroll 1
         for (int c = 0; c < nchunk; ++c) {
-            const int q16 = (c32_0 + c) * 64;                // byte offset of the chunk's first part, before the permutation
-            const int q16n = (c32_0 + min(c + 1, nchunk - 1)) * 64;
+            const int q16 = (c32_0 + c) * (CH * 2);          // byte offset of the chunk's first part, before the permutation
+            const int q16n = (c32_0 + min(c + 1, nchunk - 1)) * (CH * 2);
 #pragma unroll
-            for (int j = 0; j < 18; ++j) {
-                const int jn = (j + 1) % 18, tn = jn >> 1;
-                const int qn = (j == 17 ? q16n : q16) + (jn & 1) * 32;
+            for (int j = 0; j < STEPS; ++j) {
+                // step j of a chunk: 3x3: tap j / 2, channels (j % 2) * 16 ..; 1x1: channels j * 16 ..
+                const int jn = (j + 1) % STEPS, tn = TAPS == 9 ? jn >> 1 : 0;
+                const int qn = (j == STEPS - 1 ? q16n : q16) + (TAPS == 9 ? (jn & 1) : jn) * 32;
 #pragma unroll
                 for (int p = 0; p < 2; ++p) bf[(j + 1) & 1][p] = *(const h8*)(region + bt[tn][p] + (qn ^ ft[tn][p]));
 #pragma unroll
@@ -3252,7 +3258,8 @@ extern "C" int dlf_kernels_init(void)
         if (e != hipSuccess) return (int)e;
     }
     {
-        hipError_t e = hipFuncSetAttribute((const void*)k_c3s, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        hipError_t e = hipFuncSetAttribute((const void*)k_c3s<9>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_c3s<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return (int)e;
     }
     {
@@ -3410,20 +3417,23 @@ extern "C" int dlf_launch_c3s(const DlfC3sArgs* a, int grid, int lds_bytes, void
 {
     // what the kernel's indexing assumes
     if (grid <= 0 || (grid & 7) != 0 || a->in_bytes >= 0x80000000u) return (int)hipErrorInvalidValue;
-    if ((a->cin != 256 && a->cin != 512 && a->cin != 1024) || a->nsteps != (a->cin / 32) * 18 || (a->cout & 7) != 0)
+    if ((a->taps != 9 && a->taps != 1) || (a->cin != 256 && a->cin != 512 && a->cin != 1024) ||
+        a->nsteps != a->taps * a->cin / 16 || (a->cout & 7) != 0)
         return (int)hipErrorInvalidValue;
-    if ((a->ksplit != 1 && a->ksplit != 2 && a->ksplit != 4) || ((a->cin / 32) % a->ksplit) != 0 ||
+    const int halo = a->taps == 9 ? 1 : 0, chunks = a->cin / (a->taps == 9 ? 32 : 128);
+    if ((a->ksplit != 1 && a->ksplit != 2 && a->ksplit != 4) || (chunks % a->ksplit) != 0 ||
         a->nsl != (a->ncb + DLF_C3S_WAVES / a->ksplit - 1) / (DLF_C3S_WAVES / a->ksplit))
         return (int)hipErrorInvalidValue;
-    if (a->th < 1 || a->th > 8 || a->tw < 1 || a->tw > 8 || a->tp != a->th * a->tw || a->rw != a->tw + 2 ||
-        a->rp != (a->th + 2) * (a->tw + 2) || a->tiles_y != (a->h + a->th - 1) / a->th ||
+    if (a->th < 1 || a->th > 8 || a->tw < 1 || a->tw > 8 || a->tp != a->th * a->tw || a->rw != a->tw + 2 * halo ||
+        a->rp != (a->th + 2 * halo) * (a->tw + 2 * halo) || a->tiles_y != (a->h + a->th - 1) / a->th ||
         a->tiles_x != (a->w_ + a->tw - 1) / a->tw || a->ntiles != a->batch * a->tiles_y * a->tiles_x ||
         (a->slice_major != 0 && a->slice_major != 1) ||
         (a->slice_major && (a->nsl != 2 && a->nsl != 4 && a->nsl != 8)) ||
         grid != (a->slice_major ? (a->ntiles + 8 / a->nsl - 1) / (8 / a->nsl) * 8 : (a->ntiles + 7) / 8 * 8 * a->nsl))
         return (int)hipErrorInvalidValue;
     if (lds_bytes != (int)DLF_C3S_LDS_BYTES(a->rp, a->cin) || lds_bytes > 160 * 1024) return (int)hipErrorInvalidValue;
-    launch(k_c3s, dim3(grid), dim3(DLF_C3S_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
+    if (a->taps == 9) launch(k_c3s<9>, dim3(grid), dim3(DLF_C3S_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
+    else launch(k_c3s<1>, dim3(grid), dim3(DLF_C3S_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
     return (int)hipGetLastError();
 }
 

@@ -657,6 +657,36 @@ def test_small_map_3x3_kernel(cin, cout, h, w, batch, ksplit, act):
     compare(got, o.run_net(net, x, ws, bs), "small-map 3x3 %d->%d %dx%d" % (cin, cout, h, w))
 
 
+# (channels in, channels out, height, width, batch, activation): 1x1 layers on the same kernel (pointwise
+# mode 8): chunks of 128 channels whole or split over the waves, 2 to 64 channel blocks, ragged last
+# slices, tiles of fewer than 32 pixels, several tiles per map, a one-pixel map
+C3S_PW_CASES = [(1024, 256, 14, 14, 2, "relu"), (512, 2048, 7, 7, 2, "relu"), (256, 64, 9, 11, 3, "none"),
+                (1024, 1024, 7, 7, 1, "relu6"), (512, 200, 3, 5, 2, "relu"), (256, 1024, 1, 1, 4, "relu"),
+                (1024, 96, 17, 8, 1, "relu")]
+
+
+@pytest.mark.parametrize("cin,cout,h,w,batch,act", C3S_PW_CASES)
+def test_small_map_kernel_pointwise(cin, cout, h, w, batch, act):
+    from oracle import oracle as o
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    announce("small-map 1x1", cin, cout, h, w, batch, act)
+    net = _mk([nets.conv(cin, cout, 1, 1, 0, act)], h, w, cin, dist="normal")
+    x, ws, bs = gen.make_params(net, batch, 13)
+    B.dlf_debug_pointwise_mode(8)
+    try:
+        s = Session(net, batch, ws, bs, **_manual(1, [0]))
+    finally:
+        B.dlf_debug_pointwise_mode(0)
+    try:
+        cfg = B.dlf_plan_group_config(s.plan, 0)
+        assert cfg["kind"] == 10 and cfg["variant"] >= 8, cfg
+        got = s.run_numpy(x)
+    finally:
+        s.close()
+    compare(got, o.run_net(net, x, ws, bs), "small-map 1x1 %d->%d %dx%d" % (cin, cout, h, w))
+
+
 def test_block3x3_kernel_random_shapes():
     """Seeded random layers, block shapes, pixel tiles, budgets, batches, folded pools and residual
     operands for the block 3x3 kernel (every case one it accepts), against the oracle."""
