@@ -1108,11 +1108,19 @@ DwtForce g_dwt_force = {0, 0};
 
 // ---- 3x3 kernel for maps of many channels and few pixels ----
 
+bool c3s_cin_ok(int cin) { return cin == 256 || cin == 512 || cin == 1024 || cin == 2048; }
+
 bool c3s_eligible(const dlf_net_s& net, const std::vector<StageSpec>& specs, int batch)
 {
-    if (!c3_eligible(net, specs, batch) || specs[0].pool2) return false;
+    if (specs.size() != 1 || specs[0].kind != DLF_ST_CONV || specs[0].pool2) return false;
     const Layer& L = net.L[specs[0].layer];
-    return (L.d.cin == 256 || L.d.cin == 512 || L.d.cin == 1024) && L.d.residual_from < 0 && (L.d.cout % 8) == 0;
+    const dlf_layer_desc& d = L.d;
+    if (d.op != DLF_CONV || d.kh != 3 || d.kw != 3 || (d.stride != 1 && d.stride != 2) || d.pad != 1) return false;
+    if (L.im2col || L.rowfold || !c3s_cin_ok(d.cin) || (d.cout % 8) != 0 || d.residual_from >= 0) return false;
+    // the input is read through a buffer resource whose range check supplies the padding: below 2 GiB
+    if ((int64_t)batch * L.in_h * L.in_w * L.in_c * 2 >= (int64_t)1 << 31) return false;
+    if ((int64_t)batch * L.out_h * L.out_w * L.out_c >= (int64_t)1 << 31) return false;
+    return true;
 }
 
 // The same kernel takes 1x1 layers (stride 1, no residual) of those channel counts.
@@ -1120,24 +1128,31 @@ bool c3s_pw_eligible(const Layer& L, int batch)
 {
     if (!pw_eligible(L, batch) || L.d.stride != 1 || L.d.residual_from >= 0) return false;
     if ((int64_t)batch * L.in_h * L.in_w * L.in_c * 2 >= (int64_t)1 << 31) return false;
-    return L.d.cin == 256 || L.d.cin == 512 || L.d.cin == 1024;
+    return c3s_cin_ok(L.d.cin);
 }
 
-bool c3s_build(const Layer& L, int batch, int ksplit, int max_lds, DlfC3sArgs& cs)
+// One configuration: ksplit waves per channel block, the map cut into `rows` x `cols` equal tiles
+// (0: as few as tiles of at most 8 x 8 output pixels allow).
+bool c3s_build(const Layer& L, int batch, int ksplit, int rows, int cols, int max_lds, DlfC3sArgs& cs)
 {
     memset(&cs, 0, sizeof cs);
     cs.taps = L.d.kh * L.d.kw;
+    cs.stride = L.d.stride;
     const int halo = cs.taps == 9 ? 1 : 0, chunks = L.d.cin / (cs.taps == 9 ? 32 : 128);
     if ((cs.taps != 9 && cs.taps != 1) || (ksplit != 1 && ksplit != 2 && ksplit != 4) || (chunks % ksplit) != 0) return false;
-    // the map is cut into equal tiles of at most 8 x 8 output pixels
-    cs.th = ceil_div(L.out_h, ceil_div(L.out_h, 8));
-    cs.tw = ceil_div(L.out_w, ceil_div(L.out_w, 8));
+    if (rows <= 0) rows = ceil_div(L.out_h, 8);
+    if (cols <= 0) cols = ceil_div(L.out_w, 8);
+    cs.th = ceil_div(L.out_h, rows);
+    cs.tw = ceil_div(L.out_w, cols);
+    if (cs.th > 8 || cs.tw > 8) return false;
     cs.tp = cs.th * cs.tw;
-    cs.rw = cs.tw + 2 * halo; cs.rp = (cs.th + 2 * halo) * (cs.tw + 2 * halo);
+    cs.rw = (cs.tw - 1) * cs.stride + 1 + 2 * halo;
+    cs.rp = ((cs.th - 1) * cs.stride + 1 + 2 * halo) * cs.rw;
     if ((int)DLF_C3S_LDS_BYTES(cs.rp, L.d.cin) > max_lds) return false;
     cs.w = L.d_w; cs.bias = L.d_bias;
     cs.in_bytes = (uint32_t)((int64_t)batch * L.in_h * L.in_w * L.in_c * 2);
-    cs.batch = batch; cs.h = L.out_h; cs.w_ = L.out_w; cs.cin = L.d.cin; cs.cout = L.d.cout;
+    cs.batch = batch; cs.h = L.in_h; cs.w_ = L.in_w; cs.oh = L.out_h; cs.ow = L.out_w;
+    cs.cin = L.d.cin; cs.cout = L.d.cout;
     cs.ncb = L.ncb; cs.nsteps = L.nsteps; cs.act = L.d.act;
     cs.tiles_y = ceil_div(L.out_h, cs.th); cs.tiles_x = ceil_div(L.out_w, cs.tw);
     cs.ntiles = batch * cs.tiles_y * cs.tiles_x;
@@ -1154,25 +1169,31 @@ uint64_t c3s_cost_ps(const Layer& L, int batch, int budget, const DlfC3sArgs& cs
     const int64_t nitems = (int64_t)cs.ntiles * cs.nsl;
     const int64_t rounds = (nitems + budget - 1) / budget;
     const int64_t item = C_C3S_ITEM + (rounds > 1 ? C_C3S_NEXT : 0) + (int64_t)cs.rp * cs.cin * 2 / DWS_BYTES_PER_CYCLE +
-                         (int64_t)(cs.nsteps / cs.ksplit) * (wbytes > C_C3S_BIG_BYTES ? C_C3S_STEP_BIG : C_C3S_STEP) +
+                         (int64_t)(cs.nsteps / cs.ksplit) * (wbytes > C_C3S_BIG_BYTES ? C_C3S_STEP_BIG : C_C3S_STEP) *
+                             (cs.tp > 32 ? 4 : 3) / 4 +        // one pixel block: half the MFMAs, the same weights
+
                          (cs.ksplit > 1 ? C_C3S_RED : 0) + C_C3S_EPI;
     const int64_t compute = C_LAT + rounds * item;
     const int64_t m = (int64_t)batch * L.out_h * L.out_w;
-    const int64_t bytes = m * L.d.cin * 2 + m * L.d.cout * 2 + (int64_t)L.ncb * L.nsteps * 1024;
+    const int64_t bytes = (int64_t)batch * L.in_h * L.in_w * L.d.cin * 2 + m * L.d.cout * 2 + (int64_t)L.ncb * L.nsteps * 1024;
     const int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
     return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
 }
 
-// Cheapest split of K over the waves (ties: the smaller split).
+// Cheapest split of K over the waves and cut of the map (ties: the smaller split, the fewer tiles):
+// the largest tiles first, then one more row or column of tiles while a region does not fit LDS.
 bool c3s_choose(const Layer& L, int batch, int budget, int max_lds, DlfC3sArgs& best, uint64_t& cost)
 {
     bool found = false;
-    for (int ks = 1; ks <= 4; ks *= 2) {
-        DlfC3sArgs cs;
-        if (!c3s_build(L, batch, ks, max_lds, cs)) continue;
-        const uint64_t c = c3s_cost_ps(L, batch, budget, cs);
-        if (!found || c < cost) { found = true; cost = c; best = cs; }
-    }
+    const int r0 = ceil_div(L.out_h, 8), c0 = ceil_div(L.out_w, 8);
+    for (int extra = 0; extra <= 6 && !found; ++extra)
+        for (int er = 0; er <= extra; ++er)
+            for (int ks = 1; ks <= 4; ks *= 2) {
+                DlfC3sArgs cs;
+                if (!c3s_build(L, batch, ks, r0 + er, c0 + extra - er, max_lds, cs)) continue;
+                const uint64_t c = c3s_cost_ps(L, batch, budget, cs);
+                if (!found || c < cost) { found = true; cost = c; best = cs; }
+            }
     return found;
 }
 
@@ -1498,7 +1519,7 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
     if (c3f.mode != 2 && (force.th <= 0 || c3f.mode == 1) && (c3f.shape < 0 || c3f.shape == DLF_C3_SHAPES) &&
         c3s_eligible(net, specs, batch)) {
         if (c3f.shape == DLF_C3_SHAPES && c3f.th > 0) {
-            have_c3s = c3s_build(L0, batch, c3f.th, max_lds, cs);
+            have_c3s = c3s_build(L0, batch, c3f.th, 0, 0, max_lds, cs);
             if (have_c3s) c3sc = c3s_cost_ps(L0, batch, budget, cs);
         } else {
             have_c3s = c3s_choose(L0, batch, budget, max_lds, cs, c3sc);

@@ -254,7 +254,7 @@ struct DlfDwsArgs {
     int32_t nsl;          // slices of the output channels: ceil(ncb / (8 * cbw))
 };
 
-// 3x3 convolution, stride 1, pad 1 (or 1x1, stride 1) on maps of many channels and few pixels (cin 256, 512 or 1024),
+// 3x3 convolution, pad 1, stride 1 or 2 (or 1x1, stride 1) on maps of many channels and few pixels (cin 256 .. 2048),
 // where the block kernel has too few blocks for the chip and the fused-group kernel's waves each
 // stream their own weights: one workgroup of eight waves per work item = (tile of at most 8 x 8 output
 // pixels, slice of 8 / ksplit 32-channel blocks); the tile's input region, all cin channels, goes to LDS
@@ -269,14 +269,15 @@ struct DlfDwsArgs {
                                                                      : DLF_C3S_RED_BYTES + DLF_C3S_EPI_BYTES)
 struct DlfC3sArgs {
     const void* in;       // [batch][h][w][cin] fp16
-    void* out;            // [batch][h][w][cout] fp16
+    void* out;            // [batch][oh][ow][cout] fp16
     const void* w;        // packed weight fragments, K step = (32-channel chunk, tap, half)
     const float* bias;    // padded to ncb * 32
     uint32_t in_bytes;    // size of the input tensor (below 2 GiB)
-    int32_t batch, h, w_, cin, cout, ncb, nsteps, act;
+    int32_t batch, h, w_, oh, ow, cin, cout, ncb, nsteps, act;
     int32_t taps;         // 9: 3x3, pad 1; 1: 1x1
+    int32_t stride;       // 1, or 2 (3x3 only)
     int32_t th, tw, tp;   // tile of output pixels (each side <= 8), tp = th * tw
-    int32_t rw, rp;       // its input region: tw + 2 columns, (th + 2) * (tw + 2) pixels (1x1: the tile itself)
+    int32_t rw, rp;       // its input region: (tw - 1) * stride + 3 columns (1x1: tw), rows likewise, rp pixels
     int32_t tiles_y, tiles_x, ntiles;     // ntiles = batch * tiles_y * tiles_x
     int32_t ksplit;       // 1, 2 or 4 waves per channel block; divides cin / 32 (1x1: cin / 128)
     int32_t nsl;          // slices of the output channels: ceil(ncb / (8 / ksplit))

@@ -2793,7 +2793,7 @@ __global__ __launch_bounds__(DLF_DWS_WAVES * 64, 1) void k_dws(const DlfDwsArgs 
     }
 }
 
-// 3x3 convolution (stride 1, pad 1) or 1x1 convolution (stride 1), + bias + activation, where a map has
+// 3x3 convolution (pad 1, stride 1 or 2) or 1x1 convolution (stride 1), + bias + activation, where a map has
 // many channels and few pixels: the 14 x 14 and 7 x 7 maps of ResNet-50's and VGG-16's last stages.  The block kernel k_c3b has too
 // few 128-channel x 256-pixel blocks there to fill the chip, and in the fused-group kernel every wave
 // streams weights for one or two pixel blocks of its own.  Built like k_dws:
@@ -2815,10 +2815,12 @@ __global__ __launch_bounds__(DLF_DWS_WAVES * 64, 1) void k_dws(const DlfDwsArgs 
 //      lane's nine (tap-shifted pixel, permutation) pairs stay in registers.
 //   3. Partial sums of the waves of a channel block meet in LDS (in the region's space, behind a
 //      barrier); bias, activation, fp16, transpose, 64-byte runs per pixel to memory.
-template <int TAPS>
+template <int TAPS, int S, int FP>
 __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs a)
 {
-    static_assert(TAPS == 9 || TAPS == 1, "3x3 (pad 1) or 1x1 (pad 0)");
+    static_assert(TAPS == 9 || (TAPS == 1 && S == 1), "3x3 (pad 1, stride 1 or 2) or 1x1 (pad 0, stride 1)");
+    static_assert(S == 1 || S == 2, "stride");
+    static_assert(FP == 1 || FP == 2, "32-pixel blocks of a tile");
     constexpr int HALO = TAPS == 9 ? 1 : 0;
     constexpr int CH = TAPS == 9 ? 32 : 128;                 // channels of a chunk of K
     constexpr int STEPS = TAPS * CH / 16;                    // its K steps: 18 or 8, in the order the weights are packed
@@ -2826,7 +2828,7 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
     constexpr int ROW = 32 + 8;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
-    const int pp_shift = __builtin_ctz(a.cin) - 3;           // 16-byte parts per pixel = cin / 8 (32, 64 or 128)
+    const int pp_shift = __builtin_ctz(a.cin) - 3;           // 16-byte parts per pixel = cin / 8 (32 .. 256)
     // Work item of the workgroup.  Workgroup i runs on XCD i % 8.  Either the slices of a tile share an
     // XCD (its L2 fetches the tile's region once, and every XCD fetches all the weights), or an XCD
     // keeps to one slice (8 / nsl XCDs share the tiles of a slice: each L2 holds 1 / nsl of the weights
@@ -2866,9 +2868,9 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
         unsigned off = (unsigned)DLF_OOB;
         if (hp < a.rp) {
             const int ry = div_by(hp, rw_m), rx = hp - ry * a.rw;
-            const int gy = oy0 - HALO + ry, gx = ox0 - HALO + rx;
+            const int gy = oy0 * S - HALO + ry, gx = ox0 * S - HALO + rx;
             if (gy >= 0 && gy < a.h && gx >= 0 && gx < a.w_)
-                off = (unsigned)(((n * a.h + gy) * a.w_ + gx) * a.cin + ((pos ^ ((ry * a.tw + rx) & 15)) << 3)) * 2u;
+                off = (unsigned)(((n * a.h + gy) * a.w_ + gx) * a.cin + ((pos ^ (((ry / S) * a.tw + rx / S) & 15)) << 3)) * 2u;
         }
         asm volatile("s_mov_b32 m0, %2\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(off), "s"(rin),
                      "s"(lds0 + (unsigned)i * 1024u)
@@ -2895,21 +2897,21 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
 
     // the lane's two pixels under each of the nine taps: byte offset of the region pixel, and the
     // permutation of that pixel combined with the lane's K half, as a byte offset (16 * (h % 16 ^ lhi))
-    int bt[TAPS][2], ft[TAPS][2];
+    int bt[TAPS][FP], ft[TAPS][FP];
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
+    for (int p = 0; p < FP; ++p) {
         const int px_ = min(p * 32 + l32, a.tp - 1);
         const int py = div_by(px_, tw_m), pxx = px_ - py * a.tw;
 #pragma unroll
         for (int t = 0; t < TAPS; ++t) {
-            const int ry = py + t / 3, rx = pxx + t % 3;
+            const int ry = py * S + t / 3, rx = pxx * S + t % 3;
             bt[t][p] = (ry * a.rw + rx) * a.cin * 2;
-            ft[t][p] = (((ry * a.tw + rx) & 15) ^ lhi) << 4;
+            ft[t][p] = ((((ry / S) * a.tw + rx / S) & 15) ^ lhi) << 4;
         }
     }
-    f16v acc[2];
+    f16v acc[FP];
 #pragma unroll
-    for (int p = 0; p < 2; ++p)
+    for (int p = 0; p < FP; ++p)
 #pragma unroll
         for (int q = 0; q < 16; ++q) acc[p][q] = 0.0f;
 
@@ -2921,9 +2923,9 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
         const char* const region = (const char*)lds;
         // (the fragments of step s + 1 are read before step s is multiplied; a ring slot is requested
         // again right behind its multiplies)
-        h8 bf[2][2];
+        h8 bf[2][FP];
 #pragma unroll
-        for (int p = 0; p < 2; ++p) bf[0][p] = *(const h8*)(region + bt[0][p] + ((c32_0 * (CH * 2)) ^ ft[0][p]));
+        for (int p = 0; p < FP; ++p) bf[0][p] = *(const h8*)(region + bt[0][p] + ((c32_0 * (CH * 2)) ^ ft[0][p]));
 #pragma unroll 1
         for (int c = 0; c < nchunk; ++c) {
             const int q16 = (c32_0 + c) * (CH * 2);          // byte offset of the chunk's first part, before the permutation
@@ -2934,9 +2936,9 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
                 const int jn = (j + 1) % STEPS, tn = TAPS == 9 ? jn >> 1 : 0;
                 const int qn = (j == STEPS - 1 ? q16n : q16) + (TAPS == 9 ? (jn & 1) : jn) * 32;
 #pragma unroll
-                for (int p = 0; p < 2; ++p) bf[(j + 1) & 1][p] = *(const h8*)(region + bt[tn][p] + (qn ^ ft[tn][p]));
+                for (int p = 0; p < FP; ++p) bf[(j + 1) & 1][p] = *(const h8*)(region + bt[tn][p] + (qn ^ ft[tn][p]));
 #pragma unroll
-                for (int p = 0; p < 2; ++p)
+                for (int p = 0; p < FP; ++p)
                     acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[j % D], bf[j & 1][p], acc[p], 0, 0, 0);
                 request(j % D);
                 __builtin_amdgcn_sched_barrier(0);
@@ -2951,7 +2953,7 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
         if (kpart > 0 && live) {
             float* dst = red + (wave - ncbw) * (2 * 16 * 64) + lane;
 #pragma unroll
-            for (int p = 0; p < 2; ++p)
+            for (int p = 0; p < FP; ++p)
 #pragma unroll
                 for (int q = 0; q < 16; ++q) dst[(p * 16 + q) * 64] = acc[p][q];
         }
@@ -2960,7 +2962,7 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
         for (int k = 1; k < a.ksplit; ++k) {
             const float* src = red + (k * ncbw + cbw - ncbw) * (2 * 16 * 64) + lane;
 #pragma unroll
-            for (int p = 0; p < 2; ++p)
+            for (int p = 0; p < FP; ++p)
 #pragma unroll
                 for (int q = 0; q < 16; ++q) acc[p][q] += src[(p * 16 + q) * 64];
         }
@@ -2969,7 +2971,7 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // the transpose buffers lie in the region's space
     }
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
+    for (int p = 0; p < FP; ++p) {
         if (p * 32 < a.tp) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -2990,8 +2992,8 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
                 const int px_ = p * 32 + pl;
                 const int row = div_by(px_, tw_m), colp = px_ - row * a.tw;
                 const int oy = oy0 + row, ox = ox0 + colp;
-                if (px_ < a.tp && oy < a.h && ox < a.w_ && cc < a.cout)
-                    *(u4v*)(outp + ((size_t)((n * a.h + oy) * a.w_ + ox) * a.cout + cc)) = *(const u4v*)(tb + pl * ROW + part * 8);
+                if (px_ < a.tp && oy < a.oh && ox < a.ow && cc < a.cout)
+                    *(u4v*)(outp + ((size_t)((n * a.oh + oy) * a.ow + ox) * a.cout + cc)) = *(const u4v*)(tb + pl * ROW + part * 8);
             }
             __builtin_amdgcn_wave_barrier();
         }
@@ -3229,6 +3231,15 @@ static group_kernel_t group_kernel(int variant, bool ksplit)
     }
 }
 
+typedef void (*c3s_kernel_t)(const DlfC3sArgs);
+static c3s_kernel_t c3s_kernel(int taps, int stride, int fp)
+{
+    if (taps == 9 && stride == 1) return fp == 2 ? k_c3s<9, 1, 2> : k_c3s<9, 1, 1>;
+    if (taps == 9 && stride == 2) return fp == 2 ? k_c3s<9, 2, 2> : k_c3s<9, 2, 1>;
+    if (taps == 1 && stride == 1) return fp == 2 ? k_c3s<1, 1, 2> : k_c3s<1, 1, 1>;
+    return nullptr;
+}
+
 typedef void (*c3_kernel_t)(const DlfC3Args);
 static c3_kernel_t c3_kernel(int shape)
 {
@@ -3258,9 +3269,11 @@ extern "C" int dlf_kernels_init(void)
         if (e != hipSuccess) return (int)e;
     }
     {
-        hipError_t e = hipFuncSetAttribute((const void*)k_c3s<9>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_c3s<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return (int)e;
+        for (int v = 0; v < 6; ++v) {
+            hipError_t e = hipFuncSetAttribute((const void*)c3s_kernel(v < 4 ? 9 : 1, (v >> 1) == 1 ? 2 : 1, (v & 1) + 1),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return (int)e;
+        }
     }
     {
         const void* ks[4] = {(const void*)k_dws<1, 1>, (const void*)k_dws<1, 2>, (const void*)k_dws<2, 1>, (const void*)k_dws<2, 2>};
@@ -3417,23 +3430,26 @@ extern "C" int dlf_launch_c3s(const DlfC3sArgs* a, int grid, int lds_bytes, void
 {
     // what the kernel's indexing assumes
     if (grid <= 0 || (grid & 7) != 0 || a->in_bytes >= 0x80000000u) return (int)hipErrorInvalidValue;
-    if ((a->taps != 9 && a->taps != 1) || (a->cin != 256 && a->cin != 512 && a->cin != 1024) ||
-        a->nsteps != a->taps * a->cin / 16 || (a->cout & 7) != 0)
+    if ((a->taps != 9 && a->taps != 1) || (a->stride != 1 && a->stride != 2) || (a->taps == 1 && a->stride != 1) ||
+        (a->cin != 256 && a->cin != 512 && a->cin != 1024 && a->cin != 2048) || a->nsteps != a->taps * a->cin / 16 ||
+        (a->cout & 7) != 0)
         return (int)hipErrorInvalidValue;
-    const int halo = a->taps == 9 ? 1 : 0, chunks = a->cin / (a->taps == 9 ? 32 : 128);
+    const int halo = a->taps == 9 ? 1 : 0, chunks = a->cin / (a->taps == 9 ? 32 : 128), s = a->stride;
     if ((a->ksplit != 1 && a->ksplit != 2 && a->ksplit != 4) || (chunks % a->ksplit) != 0 ||
         a->nsl != (a->ncb + DLF_C3S_WAVES / a->ksplit - 1) / (DLF_C3S_WAVES / a->ksplit))
         return (int)hipErrorInvalidValue;
-    if (a->th < 1 || a->th > 8 || a->tw < 1 || a->tw > 8 || a->tp != a->th * a->tw || a->rw != a->tw + 2 * halo ||
-        a->rp != (a->th + 2 * halo) * (a->tw + 2 * halo) || a->tiles_y != (a->h + a->th - 1) / a->th ||
-        a->tiles_x != (a->w_ + a->tw - 1) / a->tw || a->ntiles != a->batch * a->tiles_y * a->tiles_x ||
+    if (a->th < 1 || a->th > 8 || a->tw < 1 || a->tw > 8 || a->tp != a->th * a->tw ||
+        a->rw != (a->tw - 1) * s + 1 + 2 * halo || a->rp != ((a->th - 1) * s + 1 + 2 * halo) * a->rw ||
+        a->oh != (a->h + 2 * halo - (a->taps == 9 ? 3 : 1)) / s + 1 || a->ow != (a->w_ + 2 * halo - (a->taps == 9 ? 3 : 1)) / s + 1 ||
+        a->tiles_y != (a->oh + a->th - 1) / a->th || a->tiles_x != (a->ow + a->tw - 1) / a->tw ||
+        a->ntiles != a->batch * a->tiles_y * a->tiles_x ||
         (a->slice_major != 0 && a->slice_major != 1) ||
         (a->slice_major && (a->nsl != 2 && a->nsl != 4 && a->nsl != 8)) ||
         grid != (a->slice_major ? (a->ntiles + 8 / a->nsl - 1) / (8 / a->nsl) * 8 : (a->ntiles + 7) / 8 * 8 * a->nsl))
         return (int)hipErrorInvalidValue;
     if (lds_bytes != (int)DLF_C3S_LDS_BYTES(a->rp, a->cin) || lds_bytes > 160 * 1024) return (int)hipErrorInvalidValue;
-    if (a->taps == 9) launch(k_c3s<9>, dim3(grid), dim3(DLF_C3S_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
-    else launch(k_c3s<1>, dim3(grid), dim3(DLF_C3S_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
+    launch(c3s_kernel(a->taps, s, a->tp > 32 ? 2 : 1), dim3(grid), dim3(DLF_C3S_WAVES * 64), (size_t)lds_bytes,
+           (hipStream_t)stream, *a);
     return (int)hipGetLastError();
 }
 

@@ -627,19 +627,23 @@ def test_block3x3_kernel(cin, cout, h, w, batch, shape, th, tw, pool, act, res):
 # parts per pixel, K whole or split over 2 or 4 waves, several slices of the output channels and a
 # ragged last one, waves without a channel block, maps of one tile and of several with the last row /
 # column of tiles overhanging, tiles of fewer than 32 pixels, a one-pixel map
-C3S_CASES = [(256, 256, 14, 14, 2, 2, "relu"), (256, 256, 14, 14, 3, 1, "relu"), (512, 512, 7, 7, 2, 4, "relu"),
-             (512, 512, 14, 14, 1, 2, "relu6"), (1024, 256, 5, 6, 2, 1, "relu"), (256, 200, 9, 11, 2, 4, "none"),
-             (512, 96, 3, 5, 3, 2, "relu"), (256, 1024, 1, 1, 4, 0, "relu"), (512, 640, 17, 8, 1, 0, "relu"),
-             (256, 64, 7, 7, 4, 0, "relu"), (1024, 1024, 4, 4, 1, 4, "relu")]
+C3S_CASES = [(256, 256, 14, 14, 2, 2, "relu", 1), (256, 256, 14, 14, 3, 1, "relu", 1), (512, 512, 7, 7, 2, 4, "relu", 1),
+             (512, 512, 14, 14, 1, 2, "relu6", 1), (1024, 256, 5, 6, 2, 1, "relu", 1), (256, 200, 9, 11, 2, 4, "none", 1),
+             (512, 96, 3, 5, 3, 2, "relu", 1), (256, 1024, 1, 1, 4, 0, "relu", 1), (512, 640, 17, 8, 1, 0, "relu", 1),
+             (256, 64, 7, 7, 4, 0, "relu", 1), (1024, 1024, 4, 4, 1, 4, "relu", 1),
+             # stride 2: even and odd maps, regions that only fit LDS for smaller tiles (the planner's cut), one
+             # 32-pixel block per tile, a map that shrinks to one pixel
+             (256, 256, 28, 28, 2, 0, "relu", 2), (512, 512, 14, 14, 2, 0, "relu", 2), (256, 96, 13, 15, 2, 2, "relu6", 2),
+             (1024, 128, 9, 7, 1, 0, "relu", 2), (256, 64, 2, 2, 3, 4, "none", 2), (2048, 64, 6, 6, 1, 0, "relu", 1)]
 
 
-@pytest.mark.parametrize("cin,cout,h,w,batch,ksplit,act", C3S_CASES)
-def test_small_map_3x3_kernel(cin, cout, h, w, batch, ksplit, act):
+@pytest.mark.parametrize("cin,cout,h,w,batch,ksplit,act,stride", C3S_CASES)
+def test_small_map_3x3_kernel(cin, cout, h, w, batch, ksplit, act, stride):
     from oracle import oracle as o
     from paper_2011_05630_amd import binding as B
     from paper_2011_05630_amd.runner import Session
-    announce("small-map 3x3", cin, cout, h, w, batch, ksplit, act)
-    net = _mk([nets.conv(cin, cout, 3, 1, 1, act)], h, w, cin, dist="normal")
+    announce("small-map 3x3", cin, cout, h, w, batch, ksplit, act, stride)
+    net = _mk([nets.conv(cin, cout, 3, stride, 1, act)], h, w, cin, dist="normal")
     x, ws, bs = gen.make_params(net, batch, 12)
     B.dlf_debug_block3x3_mode(1, 5, ksplit, 0)        # shape 5: this kernel; th = waves per channel block
     try:
@@ -654,7 +658,7 @@ def test_small_map_3x3_kernel(cin, cout, h, w, batch, ksplit, act):
         got = s.run_numpy(x)
     finally:
         s.close()
-    compare(got, o.run_net(net, x, ws, bs), "small-map 3x3 %d->%d %dx%d" % (cin, cout, h, w))
+    compare(got, o.run_net(net, x, ws, bs), "small-map 3x3 s%d %d->%d %dx%d" % (stride, cin, cout, h, w))
 
 
 # (channels in, channels out, height, width, batch, activation): 1x1 layers on the same kernel (pointwise
@@ -662,7 +666,7 @@ def test_small_map_3x3_kernel(cin, cout, h, w, batch, ksplit, act):
 # slices, tiles of fewer than 32 pixels, several tiles per map, a one-pixel map
 C3S_PW_CASES = [(1024, 256, 14, 14, 2, "relu"), (512, 2048, 7, 7, 2, "relu"), (256, 64, 9, 11, 3, "none"),
                 (1024, 1024, 7, 7, 1, "relu6"), (512, 200, 3, 5, 2, "relu"), (256, 1024, 1, 1, 4, "relu"),
-                (1024, 96, 17, 8, 1, "relu")]
+                (1024, 96, 17, 8, 1, "relu"), (2048, 512, 7, 7, 2, "relu"), (2048, 72, 5, 3, 1, "none")]
 
 
 @pytest.mark.parametrize("cin,cout,h,w,batch,act", C3S_PW_CASES)

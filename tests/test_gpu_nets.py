@@ -146,7 +146,7 @@ def test_config3_vgg16_batch1():
 def test_config3_vgg16_batch16_sampled():
     net = nets.vgg16()
     # the plan the benchmark times: block 3x3 kernel on the wide layers, split-K FC on 25088 -> 4096
-    _net_case(net, 16, [0, 7, 15], True, _plans(net)[:1], expect_kinds=[("c3b", None), ("group", None), ("fc", None)])
+    _net_case(net, 16, [0, 7, 15], True, _plans(net)[:1], expect_kinds=[("c3b", None), ("c3s", None), ("group", None), ("fc", None)])
 
 
 def test_config4_resnet50_batch1():
@@ -156,9 +156,10 @@ def test_config4_resnet50_batch1():
 
 def test_config4_resnet50_batch32_sampled():
     net = nets.resnet50()
-    # image 17: its pixels straddle the 128-pixel blocks of the pointwise block kernel on every map
+    # image 17: its pixels straddle the 128-pixel blocks of the pointwise block kernel on every map;
+    # the small-map kernel on the 3x3 (variant = waves per channel block) and 1x1 (8 + that) layers of the last two stages
     _net_case(net, 32, [0, 17, 31], True, _plans(net)[:1],
-              expect_kinds=[("pw", 3), ("pw", 2), ("group", None)])
+              expect_kinds=[("pw", 3), ("pw2", None), ("group", None), ("c3s", 2), ("c3s", 10)])
 
 
 def test_config5_mobilenet_batch1():
@@ -168,7 +169,7 @@ def test_config5_mobilenet_batch1():
 
 def test_config5_mobilenet_batch64_sampled():
     net = nets.mobilenet_v1()
-    _net_case(net, 64, [0, 33, 63], True, _plans(net)[:1], expect_kinds=[("pw", None), ("dw", 0), ("dw", 1), ("dwt", 0), ("dwt", 1)])
+    _net_case(net, 64, [0, 33, 63], True, _plans(net)[:1], expect_kinds=[("pw", None), ("dw", 0), ("dw", 1), ("dwt", 0), ("dwt", 1), ("dws", None), ("c3s", None)])
 
 
 def test_other_evaluated_networks_small_batch():
