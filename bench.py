@@ -185,7 +185,8 @@ def group_accounting(net, batch, session):
         elif cfg["kind"] == 7:
             kname = "k_dwt<%d>" % (cfg["variant"] + 1)
         elif cfg["kind"] == 10:
-            kname = "k_c3s<1>" if cfg["variant"] >= 8 else "k_c3s<9>"
+            kname = "k_c3s<%d,%d,%d>" % (1 if cfg["variant"] >= 8 else 9, net["layers"][f]["stride"],
+                                         2 if info["tile_h"] * info["tile_w"] > 32 else 1)
         elif cfg["kind"] == 9:
             kname = "k_dws<%d,%d>" % (cfg["variant"] // 2 + 1, cfg["variant"] % 2 + 1)
         elif cfg["kind"] == 8:
