@@ -154,7 +154,7 @@ dlf_status pack_and_upload(Layer& L)
 // Fusion groups
 // ------------------------------------------------------------------------------------------
 
-enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3, GK_C3 = 4, GK_DW = 5, GK_DWPW = 6, GK_DWT = 7, GK_PW2 = 8, GK_DWS = 9, GK_C3S = 10 };
+enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3, GK_C3 = 4, GK_DW = 5, GK_DWPW = 6, GK_DWT = 7, GK_PW2 = 8, GK_DWS = 9, GK_C3S = 10, GK_C3PW = 11 };
 
 struct TileCfg {
     int th, tw;      // tile of the group's final output tensor
@@ -184,7 +184,7 @@ struct GroupPlan {
     DlfDwPwArgs dp;
     DlfDwtArgs dt;
     DlfDwsArgs ds;
-    DlfC3sArgs cs;
+    DlfC3sArgs cs; DlfC3PwArgs cp;
 };
 
 const int VAR_FC[DLF_NUM_VARIANTS] = {2, 1, 1, 1};
@@ -300,6 +300,18 @@ const int64_t C_C3S_STEP_BIG = 215;
 const int64_t C_C3S_BIG_BYTES = 3 << 20;
 const int64_t C_C3S_RED = 1500;
 const int64_t C_C3S_EPI = 2500;
+// the fused 3x3 -> 1x1 kernel for small maps: per work item (decode, first loads), bytes per cycle of
+// its LDS intake, cycles per MFMA of a SIMD, per K step of the first layer's weight ring (requests
+// nine steps ahead against the L2's latency), per channel block of the first layer for the hand-over
+// of its result, per item for the second layer's start, and the rate at which the chip takes the
+// stores of all items of a round, which run their last phase together
+const int64_t C_C3PW_ITEM = 3500;
+const int64_t C3PW_BYTES_PER_CYCLE = 16;
+const int64_t C_C3PW_MMA = 38;
+const int64_t C_C3PW_STEP = 125;
+const int64_t C_C3PW_MID = 600;
+const int64_t C_C3PW_SECOND = 1000;
+const int64_t C3PW_STORE_BYTES_PER_CYCLE = 2300;
 
 struct StageSpec {   // one stage, before tiling
     int layer;
@@ -1197,6 +1209,84 @@ bool c3s_choose(const Layer& L, int batch, int budget, int max_lds, DlfC3sArgs& 
     return found;
 }
 
+// ---- fused 3x3 -> 1x1 (+ residual) kernel for maps with no more tiles than CUs ----
+
+bool c3pw_eligible(const dlf_net_s& net, const std::vector<StageSpec>& specs, int batch)
+{
+    if (specs.size() != 2 || specs[0].kind != DLF_ST_CONV || specs[1].kind != DLF_ST_CONV || specs[0].pool2 || specs[1].pool2)
+        return false;
+    const Layer& A = net.L[specs[0].layer];
+    const Layer& P = net.L[specs[1].layer];
+    const dlf_layer_desc& a = A.d;
+    const dlf_layer_desc& p = P.d;
+    if (a.kh != 3 || a.kw != 3 || a.stride != 1 || a.pad != 1 || A.im2col || A.rowfold || a.residual_from >= 0) return false;
+    if ((a.cin != 128 && a.cin != 256) || a.cout != a.cin) return false;
+    if (p.kh != 1 || p.kw != 1 || p.stride != 1 || p.pad != 0 || P.im2col || P.rowfold || (p.cout % 8) != 0) return false;
+    if ((int64_t)batch * A.in_h * A.in_w * a.cin * 2 >= (int64_t)1 << 31) return false;
+    if ((int64_t)batch * P.out_h * P.out_w * p.cout * 2 >= (int64_t)1 << 31) return false;
+    return true;
+}
+
+// One configuration: the map cut into rows x cols equal tiles.
+bool c3pw_build(const Layer& A, const Layer& P, int batch, int rows, int cols, int max_lds, DlfC3PwArgs& cp)
+{
+    memset(&cp, 0, sizeof cp);
+    if (rows <= 0 || cols <= 0) return false;
+    cp.th = ceil_div(A.out_h, rows);
+    cp.tw = ceil_div(A.out_w, cols);
+    if (cp.th > 8 || cp.tw > 16 || cp.th * cp.tw > 128) return false;
+    cp.tp = cp.th * cp.tw;
+    cp.rw = cp.tw + 2;
+    cp.rp = (cp.th + 2) * cp.rw;
+    if ((int)DLF_C3PW_LDS_BYTES(cp.rp, cp.tp, A.d.cin, P.d.residual_from >= 0) > max_lds) return false;
+    cp.w1 = A.d_w; cp.b1 = A.d_bias; cp.w2 = P.d_w; cp.b2 = P.d_bias;
+    cp.in_bytes = (uint32_t)((int64_t)batch * A.in_h * A.in_w * A.in_c * 2);
+    cp.res_bytes = (uint32_t)((int64_t)batch * P.out_h * P.out_w * P.d.cout * 2);
+    cp.batch = batch; cp.h = A.in_h; cp.w_ = A.in_w; cp.c = A.d.cin; cp.cout = P.d.cout;
+    cp.ncb2 = P.ncb; cp.act1 = A.d.act; cp.act2 = P.d.act;
+    cp.tiles_y = ceil_div(A.out_h, cp.th); cp.tiles_x = ceil_div(A.out_w, cp.tw);
+    cp.ntiles = batch * cp.tiles_y * cp.tiles_x;
+    cp.nsl = ceil_div(P.ncb, 2 * DLF_C3PW_WAVES);
+    return true;
+}
+
+uint64_t c3pw_cost_ps(const Layer& A, const Layer& P, int batch, int budget, const DlfC3PwArgs& cp)
+{
+    const int64_t nitems = (int64_t)cp.ntiles * cp.nsl;
+    const int64_t rounds = (nitems + budget - 1) / budget;
+    const int64_t fp = cp.tp > 64 ? 4 : 2, ncb1 = cp.c / 32;
+    const bool res = P.d.residual_from >= 0;
+    const int64_t intake = (int64_t)cp.rp * cp.c * 2 + (res && ncb1 == DLF_C3PW_WAVES ? (int64_t)cp.tp * 1024 : 0);
+    const int64_t mma1 = (int64_t)A.nsteps * std::max(fp * C_C3PW_MMA * (ncb1 > 4 ? 2 : 1), C_C3PW_STEP);
+    const int64_t pbs = ceil_div(cp.tp, 32);
+    const int64_t cb_item = std::min<int64_t>(P.ncb, 2 * DLF_C3PW_WAVES);
+    const int64_t mma2 = pbs * P.nsteps * ceil_div(cb_item, 4) * C_C3PW_MMA;     // a SIMD's two waves, two blocks each
+    const int64_t stores = std::min<int64_t>(nitems, budget) * cp.tp * cb_item * 64 / C3PW_STORE_BYTES_PER_CYCLE;
+    const int64_t item = C_C3PW_ITEM + intake / C3PW_BYTES_PER_CYCLE + mma1 + ncb1 * C_C3PW_MID + C_C3PW_SECOND +
+                         std::max(mma2, stores);
+    const int64_t compute = C_LAT + rounds * item;
+    const int64_t m = (int64_t)batch * P.out_h * P.out_w;
+    const int64_t bytes = (int64_t)batch * A.in_h * A.in_w * cp.c * 2 + m * cp.cout * 2 * (res ? 2 : 1) +
+                          ((int64_t)A.ncb * A.nsteps + (int64_t)P.ncb * P.nsteps) * 1024;
+    const int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
+    return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
+}
+
+// Cheapest cut of the map (ties: the fewer tiles).
+bool c3pw_choose(const Layer& A, const Layer& P, int batch, int budget, int max_lds, DlfC3PwArgs& best, uint64_t& cost)
+{
+    bool found = false;
+    const int r0 = ceil_div(A.out_h, 8), c0 = ceil_div(A.out_w, 16);
+    for (int rows = r0; rows <= r0 + 3; ++rows)
+        for (int cols = c0; cols <= c0 + 3; ++cols) {
+            DlfC3PwArgs cp;
+            if (!c3pw_build(A, P, batch, rows, cols, max_lds, cp)) continue;
+            const uint64_t c = c3pw_cost_ps(A, P, batch, budget, cp);
+            if (!found || c < cost) { found = true; cost = c; best = cp; }
+        }
+    return found;
+}
+
 // ---- depthwise + 1x1 kernel for maps of many channels and few pixels ----
 
 bool dws_eligible(const dlf_net_s& net, int first, int last, int batch)
@@ -1509,6 +1599,32 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
             g.th = L0.d.stride == 1 ? DLF_DW_ROWS1 : DLF_DW_ROWS2;
             g.tw = 64;
             g.lds_bytes = 0;
+            return DLF_OK;
+        }
+    }
+    // the fused 3x3 -> 1x1 kernel: shape DLF_C3_SHAPES + 1 of the testing hook (its th x tw then fix the tile)
+    if (first + 1 == last && c3f.mode != 2 && (force.th <= 0 || c3f.mode == 1) &&
+        (c3f.shape < 0 || c3f.shape == DLF_C3_SHAPES + 1) && c3pw_eligible(net, specs, batch)) {
+        const Layer& P = net.L[last];
+        DlfC3PwArgs cp;
+        uint64_t pc = 0;
+        bool have;
+        if (c3f.shape == DLF_C3_SHAPES + 1 && c3f.th > 0 && c3f.tw > 0) {
+            have = c3pw_build(L0, P, batch, ceil_div(L0.out_h, c3f.th), ceil_div(L0.out_w, c3f.tw), max_lds, cp);
+            if (have) pc = c3pw_cost_ps(L0, P, batch, budget, cp);
+        } else {
+            have = c3pw_choose(L0, P, batch, budget, max_lds, cp, pc);
+        }
+        if (have && (!tiled || c3f.mode == 1 || pc < cost)) {
+            g.cp = cp;
+            g.kind = GK_C3PW;
+            g.cost = pc;
+            g.variant = cp.tp > 64 ? 4 : 2;
+            g.occ = 1;
+            g.grid = ceil_div(cp.ntiles, 8) * 8 * cp.nsl;
+            g.th = cp.th; g.tw = cp.tw;
+            g.lds_bytes = (int)DLF_C3PW_LDS_BYTES(cp.rp, cp.tp, cp.c, P.d.residual_from >= 0);
+            if (P.d.residual_from >= 0) { g.res_layer = P.d.residual_from; g.res_stage = 1; }
             return DLF_OK;
         }
     }
@@ -2193,6 +2309,14 @@ static dlf_status launch_one(const dlf_plan_s* plan, const GroupPlan& G, const v
         DlfC3sArgs cs = G.cs;
         cs.in = in; cs.out = out;
         e = dlf_launch_c3s(&cs, G.grid, G.lds_bytes, stream);
+    } else if (G.kind == GK_C3PW) {
+        DlfC3PwArgs cp = G.cp;
+        cp.in = in; cp.out = out;
+        if (G.res_stage >= 0) {
+            if (!res) return fail(DLF_ERR_INVALID_ARG, "group [%d,%d] needs its residual operand", G.first, G.last);
+            cp.res = res;
+        }
+        e = dlf_launch_c3pw(&cp, G.grid, G.lds_bytes, stream);
     } else if (G.kind == GK_DWS) {
         DlfDwsArgs ds = G.ds;
         ds.in = in; ds.out = out;

@@ -161,7 +161,7 @@ struct DlfDwArgs {
     void* out;            // [batch][oh][ow][c] fp16
     const void* w;        // [9][cpad] fp16 (tap-major)
     const float* bias;    // [cpad]
-    uint32_t in_bytes;    // size of the input tensor (below 2 GiB)
+    uint32_t in_bytes, res_bytes;    // size of the input tensor (below 2 GiB)
     int32_t batch, h, w_, c, cpad, oh, ow, stride, act;
     int32_t cg;           // c / 8: 16-byte vectors per pixel
     int32_t rowv;         // ow * cg: vectors per output row
@@ -284,6 +284,42 @@ struct DlfC3sArgs {
     int32_t slice_major;  // 1: an XCD keeps to one slice (nsl 2, 4 or 8); 0: the slices of a tile share an XCD
 };
 
+// 3x3 convolution (stride 1, pad 1, cin = cout = c: 128 or 256) and the 1x1 convolution behind it, with
+// a residual operand added to the second layer's result: the second half of a bottleneck block, where
+// the batch's tiles are no more than the chip's CUs (ResNet-50's 28 x 28 stage at batch 32).  One
+// workgroup of eight waves per work item = (tile of up to 128 output pixels, slice of 16 channel
+// blocks of the second layer); the input region goes to LDS by direct loads, the first layer's
+// result stays in LDS as [pixel][c + 8].
+#define DLF_C3PW_WAVES 8
+#define DLF_C3PW_IN_BYTES(RP, C) ((((RP) * (C) * 2 + 1023) / 1024) * 1024)
+#define DLF_C3PW_EPI_BYTES (DLF_C3PW_WAVES * 32 * (32 + 8) * 2)
+#define DLF_C3PW_MID_BYTES(TP, C) ((TP) * ((C) + 8) * 2)
+#define DLF_C3PW_RES_STRIDE (1024 + 64)
+// the first layer's result takes the region's place; behind it the waves' transpose buffers, then
+// (past the region's end) the residual operand
+#define DLF_C3PW_TB_OFF(TP, C) (((DLF_C3PW_MID_BYTES(TP, C) + 63) / 64) * 64)
+#define DLF_C3PW_RES_OFF(RP, TP, C)                                                      \
+    (DLF_C3PW_IN_BYTES(RP, C) > DLF_C3PW_TB_OFF(TP, C) + DLF_C3PW_EPI_BYTES ? DLF_C3PW_IN_BYTES(RP, C) \
+                                                                             : DLF_C3PW_TB_OFF(TP, C) + DLF_C3PW_EPI_BYTES)
+#define DLF_C3PW_BIAS_OFF(RP, TP, C, RES) (DLF_C3PW_RES_OFF(RP, TP, C) + ((RES) ? (TP) * DLF_C3PW_RES_STRIDE : 0))
+#define DLF_C3PW_LDS_BYTES(RP, TP, C, RES) (DLF_C3PW_BIAS_OFF(RP, TP, C, RES) + DLF_C3PW_WAVES * 64 * 4)
+struct DlfC3PwArgs {
+    const void* in;       // [batch][h][w][c] fp16
+    const void* res;      // residual operand [batch][h][w][cout] fp16, or null
+    void* out;            // [batch][h][w][cout] fp16
+    const void* w1;       // 3x3 weights, packed fragments (K step = 32-channel chunk, tap, half)
+    const float* b1;      // padded to c
+    const void* w2;       // 1x1 weights, packed fragments
+    const float* b2;      // padded to ncb2 * 32
+    uint32_t in_bytes;    // size of the input tensor (below 2 GiB)
+    uint32_t res_bytes;   // size of the residual operand = of the output (below 2 GiB)
+    int32_t batch, h, w_, c, cout, ncb2, act1, act2;
+    int32_t th, tw, tp;   // tile of output pixels: th <= 8, tw <= 16, tp = th * tw <= 128
+    int32_t rw, rp;       // its input region: tw + 2 columns, (th + 2) * (tw + 2) pixels
+    int32_t tiles_y, tiles_x, ntiles;     // ntiles = batch * tiles_y * tiles_x
+    int32_t nsl;          // slices of the second layer's channels: ceil(ncb2 / 16)
+};
+
 struct DlfGapArgs {
     const void* x;        // [batch][hw][c]
     void* y;              // [batch][c]
@@ -307,6 +343,7 @@ int dlf_launch_dwpw(const DlfDwPwArgs* a, int nb, int grid, void* stream);
 int dlf_launch_dwt(const DlfDwtArgs* a, int grid, int lds_bytes, void* stream);
 int dlf_launch_dws(const DlfDwsArgs* a, int grid, int lds_bytes, void* stream);
 int dlf_launch_c3s(const DlfC3sArgs* a, int grid, int lds_bytes, void* stream);
+int dlf_launch_c3pw(const DlfC3PwArgs* a, int grid, int lds_bytes, void* stream);
 int dlf_kernels_init(void);
 // Attaches a start / stop event pair (hipEvent_t, either may be null) to this thread's next launch.
 void dlf_next_launch_events(void* start, void* stop);

@@ -3000,6 +3000,276 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
     }
 }
 
+// 3x3 convolution (stride 1, pad 1, c -> c channels, c = 128 or 256) + bias + activation, and the 1x1
+// convolution behind it + bias + residual operand + activation: the second half of a bottleneck block
+// (Sec. III-B: the intermediate tensor never leaves the chip), for the case that the batch has no
+// more tiles than the chip has CUs, where the fused-group kernel's tile pipeline is bound by the
+// latency of its steps.  One workgroup of eight waves per work item = (tile of up to 8 x 16 output
+// pixels, slice of 16 channel blocks of the second layer); one item per workgroup.  Every workgroup
+// of the chip is in the same phase at the same time, so the phases are arranged for memory and
+// matrix pipes to work side by side: the residual operand comes in while the first layer multiplies.
+//   1. The tile's input region, all c channels, global -> LDS by direct loads, as in k_c3s (range
+//      check as padding, parts permuted by (r * tw + c) % 16).  Behind it the residual operand of the
+//      item's pixels x 512 channels, likewise to LDS (one load per pixel, rows of 1024 + 64 bytes), by
+//      the waves that have no part in the first layer, once the region has landed (requested beside
+//      it, it doubles the time until the first layer can start); with eight channel blocks in the
+//      first layer every wave has one, and they all request it before they start.
+//   2. First layer: waves 0 .. c / 32 - 1 take one channel block x all FP 32-pixel blocks each, K in the
+//      packed order through a register ring of 9 steps.  (With four channel blocks the other four
+//      waves have nothing to multiply here: two waves of a SIMD would take turns on its matrix pipe
+//      anyway.)  Once every wave is done with the region: result (bias included), activation, fp16 to an LDS
+//      tile [pixel][c + 8] in the region's place.
+//   3. Second layer: every wave two channel blocks, one after the other, all of K (c / 16 steps)
+//      with both blocks' weight fragments in registers (requested as early as the wave has room for
+//      them), 32 pixels at a time: the MFMAs run, the results go through the wave's transpose
+//      buffer, the residual is added to the rounded sum (fp16 + fp16, as in the other kernels),
+//      activation, and a pixel's 2 x 64 bytes go to memory in adjacent instructions.
+template <int FP, int C>
+__global__ __launch_bounds__(DLF_C3PW_WAVES * 64, 1) void k_c3pw(const DlfC3PwArgs a)
+{
+    constexpr int D = 9;
+    constexpr int ROW = 32 + 8;
+    static_assert(FP == 2 || FP == 4, "32-pixel blocks of a tile");
+    static_assert(C == 128 || C == 256, "channels of the first layer");
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    constexpr int pp_shift = C == 128 ? 4 : 5;               // 16-byte parts per pixel: 16 or 32
+    constexpr int cs = C + 8;
+    const int per8 = blockIdx.x >> 3;
+    const int sl = per8 % a.nsl, tile = (per8 / a.nsl) * 8 + (blockIdx.x & 7);
+    if (tile >= a.ntiles) return;
+    int r_ = tile;
+    const int tx = r_ % a.tiles_x;
+    r_ /= a.tiles_x;
+    const int ty = r_ % a.tiles_y, n = r_ / a.tiles_y;
+    const int oy0 = ty * a.th, ox0 = tx * a.tw;
+    half_t* const mid = lds;                                 // takes the region's place
+    half_t* const tb = lds + DLF_C3PW_TB_OFF(a.tp, C) / 2 + wave * (32 * ROW);
+    const int res_off = DLF_C3PW_RES_OFF(a.rp, a.tp, C);
+    half_t* outp = (half_t*)a.out;
+    const bool has_res = a.res != nullptr;
+    const unsigned lo1 = act_lo(a.act1), hi1 = act_hi(a.act1);
+    const unsigned lo2 = act_lo(a.act2), hi2 = act_hi(a.act2);
+    const unsigned tw_m = div_magic(a.tw), rw_m = div_magic(a.rw);
+
+    // ---- step 1: the region, the residual operand ----
+    const i32x4 rin = make_rsrc(a.in, a.in_bytes);
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) half_t*)lds;
+    const int ni = ((a.rp << pp_shift) + 63) >> 6;
+#pragma unroll 1
+    for (int i = wave; i < ni; i += DLF_C3PW_WAVES) {
+        const int idx = i * 64 + lane;
+        const int hp = idx >> pp_shift, pos = idx & ((1 << pp_shift) - 1);
+        unsigned off = (unsigned)DLF_OOB;
+        if (hp < a.rp) {
+            const int ry = div_by(hp, rw_m), rx = hp - ry * a.rw;
+            const int gy = oy0 - 1 + ry, gx = ox0 - 1 + rx;
+            if (gy >= 0 && gy < a.h && gx >= 0 && gx < a.w_)
+                off = (unsigned)(((n * a.h + gy) * a.w_ + gx) * C + ((pos ^ ((ry * a.tw + rx) & 15)) << 3)) * 2u;
+        }
+        asm volatile("s_mov_b32 m0, %2\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(off), "s"(rin),
+                     "s"(lds0 + (unsigned)i * 1024u)
+                     : "memory", "m0");
+    }
+    const int lane16 = lane * 16;
+    constexpr int ncb1 = C / 32, nsteps1 = ncb1 * 18, nsteps2 = C / 16;
+    const bool conv1 = wave < ncb1;                          // uniform
+    // the residual operand of pixels first, first + every, ..: one load per pixel
+    auto request_res = [&](int first, int every) __attribute__((always_inline)) {
+        const i32x4 rres = make_rsrc(a.res, a.res_bytes);
+        const int ch = sl * (2 * DLF_C3PW_WAVES * 32) + lane * 8;
+#pragma unroll 1
+        for (int p = first; p < a.tp; p += every) {
+            const int row = div_by(p, tw_m), colp = p - row * a.tw;
+            const int oy = oy0 + row, ox = ox0 + colp;
+            unsigned off = (unsigned)DLF_OOB;
+            if (oy < a.h && ox < a.w_ && ch < a.cout) off = (unsigned)(((n * a.h + oy) * a.w_ + ox) * a.cout + ch) * 2u;
+            asm volatile("s_mov_b32 m0, %2\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(off), "s"(rres),
+                         "s"(lds0 + (unsigned)(res_off + p * DLF_C3PW_RES_STRIDE))
+                         : "memory", "m0");
+        }
+    };
+    if (ncb1 == DLF_C3PW_WAVES && has_res) request_res(wave, DLF_C3PW_WAVES);
+
+    // the second layer's weights of this wave: both channel blocks, all of K
+    const int cb0 = (sl * DLF_C3PW_WAVES + wave) * 2;
+    const bool live = cb0 < a.ncb2;                          // uniform
+    const i32x4 rw2 = make_rsrc(a.w2, 0xffffffffu);
+    h8 a2[2][nsteps2];
+    auto load_a2 = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const unsigned wo2 = (unsigned)__builtin_amdgcn_readfirstlane(min(cb0 + j, a.ncb2 - 1) * nsteps2 * 1024);
+#pragma unroll
+            for (int k = 0; k < nsteps2; ++k) a2[j][k] = wfrag(rw2, lane16, wo2 + (unsigned)k * 1024u);
+        }
+    };
+
+    // its bias values, to a wave-private place in LDS (they start the accumulators below)
+    float* const bl = (float*)((char*)lds + DLF_C3PW_BIAS_OFF(a.rp, a.tp, C, has_res)) + wave * 64;
+    bl[lane] = a.b2[min(cb0 * 32 + lane, a.ncb2 * 32 - 1)];
+
+    // ---- step 2: the first layer ----
+    f16v acc[FP];
+    if (conv1) {
+        const i32x4 rw1 = make_rsrc(a.w1, 0xffffffffu);
+        const unsigned wo = (unsigned)__builtin_amdgcn_readfirstlane(wave * nsteps1 * 1024);
+        // the accumulators start from the bias
+        f4v bias1[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bias1[q] = *(const f4v*)(a.b1 + wave * 32 + q * 8 + lhi * 4);
+        int pf_ks = 0;
+        h8 ar[D];
+        auto request = [&](int slot) __attribute__((always_inline)) {
+            ar[slot] = wfrag(rw1, lane16, wo + (unsigned)min(pf_ks, nsteps1 - 1) * 1024u);   // past the end: re-read, never used
+            ++pf_ks;
+        };
+#pragma unroll
+        for (int d = 0; d < D; ++d) request(d);
+        int bt[9][FP], ft[9][FP];
+#pragma unroll
+        for (int p = 0; p < FP; ++p) {
+            const int px_ = min(p * 32 + l32, a.tp - 1);
+            const int py = div_by(px_, tw_m), pxx = px_ - py * a.tw;
+#pragma unroll
+            for (int t = 0; t < 9; ++t) {
+                const int ry = py + t / 3, rx = pxx + t % 3;
+                bt[t][p] = (ry * a.rw + rx) * C * 2;
+                ft[t][p] = (((ry * a.tw + rx) & 15) ^ lhi) << 4;
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < FP; ++p)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[p][q] = bias1[q >> 2][q & 3];
+        wait_vmcnt<D>();                                     // the region has landed: only the ring's requests are behind it
+        asm volatile("s_barrier" ::: "memory");
+        const char* const region = (const char*)lds;
+        h8 bf[2][FP];
+#pragma unroll
+        for (int p = 0; p < FP; ++p) bf[0][p] = *(const h8*)(region + bt[0][p] + ft[0][p]);
+#pragma unroll 1
+        for (int c = 0; c < ncb1; ++c) {
+            const int q16 = c * 64, q16n = min(c + 1, ncb1 - 1) * 64;
+#pragma unroll
+            for (int j = 0; j < 18; ++j) {
+                const int jn = (j + 1) % 18, tn = jn >> 1;
+                const int qn = (j == 17 ? q16n : q16) + (jn & 1) * 32;
+#pragma unroll
+                for (int p = 0; p < FP; ++p) bf[(j + 1) & 1][p] = *(const h8*)(region + bt[tn][p] + (qn ^ ft[tn][p]));
+#pragma unroll
+                for (int p = 0; p < FP; ++p)
+                    acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[j % D], bf[j & 1][p], acc[p], 0, 0, 0);
+                request(j % D);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    } else {
+        wait_vmcnt<0>();
+        asm volatile("s_barrier" ::: "memory");              // the region has landed
+        if (has_res) request_res(wave - ncb1, DLF_C3PW_WAVES - ncb1);
+        if (live) load_a2();
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // nobody reads the region any more
+    if (conv1) {
+        // activation, fp16, to the tile: the accumulator holds channels q * 8 + lhi * 4 .. + 3 of pixel l32
+#pragma unroll
+        for (int p = 0; p < FP; ++p) {
+            const int px_ = p * 32 + l32;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                unsigned u0 = cvt_pk(acc[p][q * 4 + 0], acc[p][q * 4 + 1]);
+                unsigned u1 = cvt_pk(acc[p][q * 4 + 2], acc[p][q * 4 + 3]);
+                u0 = pk_min(pk_max(u0, lo1), hi1);
+                u1 = pk_min(pk_max(u1, lo1), hi1);
+                const u2v uu = {u0, u1};
+                if (px_ < a.tp) *(u2v*)(mid + px_ * cs + wave * 32 + q * 8 + lhi * 4) = uu;
+            }
+        }
+        if (live) load_a2();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    } else {
+        wait_vmcnt<0>();                                     // this wave's part of the residual operand has landed
+    }
+    asm volatile("s_barrier" ::: "memory");                  // the tile and the residual operand are complete
+    if (!live) return;
+
+    // everything this wave has asked memory for is in its registers from here on: the loop below
+    // issues stores only and never waits for them
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int k = 0; k < nsteps2; ++k) asm volatile("" : "+v"(a2[j][k]));
+
+    // ---- step 3: the second layer ----
+    constexpr int LPX = 4, PPP = 64 / LPX;                   // store phase: 4 lanes per pixel and channel block, 16 pixels per instruction
+    const int part = lane & (LPX - 1);
+    const char* const resl = (const char*)lds + res_off + (wave * 2 * LPX + part) * 16;
+    const int cc = cb0 * 32 + part * 8;                      // of the first block; the second one's are 32 further
+#pragma unroll 1
+    for (int pb = 0; pb * 32 < a.tp; ++pb) {
+        f16v acc2[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f4v bias = *(const f4v*)(bl + j * 32 + q * 8 + lhi * 4);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc2[j][q * 4 + i] = bias[i];
+            }
+        const half_t* const bsrc = mid + min(pb * 32 + l32, a.tp - 1) * cs + lhi * 8;
+#pragma unroll
+        for (int k = 0; k < nsteps2; ++k) {
+            const h8 b = *(const h8*)(bsrc + k * 16);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc2[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2[j][k], b, acc2[j], 0, 0, 0);
+        }
+        // both blocks through the transpose buffer, then each pixel's 2 x 64 bytes to memory back to back
+        u4v val[2][32 / PPP];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const unsigned u0 = cvt_pk(acc2[j][q * 4 + 0], acc2[j][q * 4 + 1]);
+                const unsigned u1 = cvt_pk(acc2[j][q * 4 + 2], acc2[j][q * 4 + 3]);
+                const u2v uu = {u0, u1};
+                *(u2v*)(tb + l32 * ROW + q * 8 + lhi * 4) = uu;
+            }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int i = 0; i < 32 / PPP; ++i) val[j][i] = *(const u4v*)(tb + (i * PPP + lane / LPX) * ROW + part * 8);
+            __builtin_amdgcn_wave_barrier();
+        }
+#pragma unroll
+        for (int i = 0; i < 32 / PPP; ++i) {
+            const int px_ = pb * 32 + i * PPP + lane / LPX;
+            const int pc = min(px_, a.tp - 1);
+            const int row = div_by(pc, tw_m), colp = pc - row * a.tw;
+            const int oy = oy0 + row, ox = ox0 + colp;
+            const bool inside = px_ < a.tp && oy < a.h && ox < a.w_;
+            half_t* const dst = outp + ((size_t)((n * a.h + oy) * a.w_ + ox) * a.cout + cc);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                if (inside && cc + j * 32 < a.cout) {
+                    u4v v = val[j][i];
+                    if (has_res) {
+                        const u4v rv = *(const u4v*)(resl + pc * DLF_C3PW_RES_STRIDE + j * (LPX * 16));
+                        v.x = pk_add(v.x, rv.x);
+                        v.y = pk_add(v.y, rv.y);
+                        v.z = pk_add(v.z, rv.z);
+                        v.w = pk_add(v.w, rv.w);
+                    }
+                    v.x = pk_min(pk_max(v.x, lo2), hi2);
+                    v.y = pk_min(pk_max(v.y, lo2), hi2);
+                    v.z = pk_min(pk_max(v.z, lo2), hi2);
+                    v.w = pk_min(pk_max(v.w, lo2), hi2);
+                    *(u4v*)(dst + j * 32) = v;
+                }
+            }
+        }
+    }
+}
+
 extern "C" int dlf_launch_dw(const DlfDwArgs* a, int grid, void* stream);
 
 // Fully connected layer (Eq. 2 with M = batch): y[n][co] = act(bias[co] + sum_k x[n][k] w[co][k]).
@@ -3269,6 +3539,11 @@ extern "C" int dlf_kernels_init(void)
         if (e != hipSuccess) return (int)e;
     }
     {
+        hipError_t e2 = hipFuncSetAttribute((const void*)k_c3pw<2, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_c3pw<4, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_c3pw<2, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_c3pw<4, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e2 != hipSuccess) return (int)e2;
         for (int v = 0; v < 6; ++v) {
             hipError_t e = hipFuncSetAttribute((const void*)c3s_kernel(v < 4 ? 9 : 1, (v >> 1) == 1 ? 2 : 1, (v & 1) + 1),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -3450,6 +3725,25 @@ extern "C" int dlf_launch_c3s(const DlfC3sArgs* a, int grid, int lds_bytes, void
     if (lds_bytes != (int)DLF_C3S_LDS_BYTES(a->rp, a->cin) || lds_bytes > 160 * 1024) return (int)hipErrorInvalidValue;
     launch(c3s_kernel(a->taps, s, a->tp > 32 ? 2 : 1), dim3(grid), dim3(DLF_C3S_WAVES * 64), (size_t)lds_bytes,
            (hipStream_t)stream, *a);
+    return (int)hipGetLastError();
+}
+
+extern "C" int dlf_launch_c3pw(const DlfC3PwArgs* a, int grid, int lds_bytes, void* stream)
+{
+    // what the kernel's indexing assumes
+    if (grid <= 0 || (grid & 7) != 0 || a->in_bytes >= 0x80000000u || a->res_bytes >= 0x80000000u) return (int)hipErrorInvalidValue;
+    if ((a->c != 128 && a->c != 256) || (a->cout & 7) != 0 || a->ncb2 != (a->cout + 31) / 32 || a->nsl != (a->ncb2 + 15) / 16)
+        return (int)hipErrorInvalidValue;
+    if (a->th < 1 || a->th > 8 || a->tw < 1 || a->tw > 16 || a->tp != a->th * a->tw || a->tp > 128 || a->rw != a->tw + 2 ||
+        a->rp != (a->th + 2) * (a->tw + 2) || a->tiles_y != (a->h + a->th - 1) / a->th ||
+        a->tiles_x != (a->w_ + a->tw - 1) / a->tw || a->ntiles != a->batch * a->tiles_y * a->tiles_x ||
+        grid != (a->ntiles + 7) / 8 * 8 * a->nsl)
+        return (int)hipErrorInvalidValue;
+    if (lds_bytes != (int)DLF_C3PW_LDS_BYTES(a->rp, a->tp, a->c, a->res != nullptr) || lds_bytes > 160 * 1024)
+        return (int)hipErrorInvalidValue;
+    void (*const kern)(DlfC3PwArgs) = a->c == 128 ? (a->tp > 64 ? k_c3pw<4, 128> : k_c3pw<2, 128>)
+                                                  : (a->tp > 64 ? k_c3pw<4, 256> : k_c3pw<2, 256>);
+    launch(kern, dim3(grid), dim3(DLF_C3PW_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
     return (int)hipGetLastError();
 }
 

@@ -661,6 +661,45 @@ def test_small_map_3x3_kernel(cin, cout, h, w, batch, ksplit, act, stride):
     compare(got, o.run_net(net, x, ws, bs), "small-map 3x3 s%d %d->%d %dx%d" % (stride, cin, cout, h, w))
 
 
+# (c, cout, height, width, batch, tile th, tile tw, act of the 3x3, act of the 1x1, residual): the fused
+# 3x3 -> 1x1 kernel (shape 6 of the hook; th = 0: the planner's cut): two and four 32-pixel blocks per
+# tile, ragged tiles at the map's edges, tiles of one row or one column, 128 and 256 channels, one and two slices of
+# the second layer's channel blocks, a ragged last channel block, fewer channel blocks than waves, with
+# and without the residual operand (which shares LDS with the region: 256 channels x 98 pixels go without)
+C3PW_CASES = [(128, 512, 28, 28, 2, 7, 14, "relu", "relu", True), (128, 512, 28, 28, 1, 0, 0, "relu", "relu", True),
+              (256, 1024, 14, 14, 2, 7, 7, "relu", "relu", True), (128, 512, 13, 17, 2, 8, 16, "relu6", "none", True),
+              (128, 200, 9, 11, 3, 5, 6, "relu", "relu6", False), (256, 1024, 14, 14, 1, 7, 14, "relu", "relu", False),
+              (128, 96, 5, 40, 1, 1, 16, "none", "relu", True), (256, 72, 19, 3, 2, 8, 1, "relu", "relu", False),
+              (128, 1024, 7, 7, 2, 0, 0, "relu", "relu", True), (256, 520, 6, 6, 3, 3, 6, "relu", "relu", True)]
+
+
+@pytest.mark.parametrize("c,cout,h,w,batch,th,tw,act1,act2,residual", C3PW_CASES)
+def test_fused_3x3_pointwise_kernel(c, cout, h, w, batch, th, tw, act1, act2, residual):
+    from oracle import oracle as o
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    announce("fused 3x3 -> 1x1", c, cout, h, w, batch, th, tw, act1, act2, residual)
+    layers = [nets.conv(64, cout, 1, 1, 0, "relu"), nets.conv(cout, c, 1, 1, 0, "relu"), nets.conv(c, c, 3, 1, 1, act1),
+              nets.conv(c, cout, 1, 1, 0, act2, **(dict(residual_from=0) if residual else {}))]
+    net = _mk(layers, h, w, 64, dist="normal")
+    x, ws, bs = gen.make_params(net, batch, 14)
+    B.dlf_debug_block3x3_mode(1, 6, th, tw)        # shape 6: this kernel; th x tw: its tile
+    try:
+        s = Session(net, batch, ws, bs, **_manual(4, [0, 1, 3]))
+    finally:
+        B.dlf_debug_block3x3_mode(0)
+    try:
+        cfg = B.dlf_plan_group_config(s.plan, 2)
+        assert cfg["kind"] == 11, cfg
+        if th:      # the map is cut into equal tiles, as many as tiles of th x tw need
+            gp = B.dlf_plan_groups(s.plan)[2]
+            assert (gp["tile_h"], gp["tile_w"]) == (-(-h // -(-h // th)), -(-w // -(-w // tw))), gp
+        got = s.run_numpy(x)
+    finally:
+        s.close()
+    compare(got, o.run_net(net, x, ws, bs), "fused 3x3 -> 1x1 %d->%d %dx%d" % (c, cout, h, w))
+
+
 # (channels in, channels out, height, width, batch, activation): 1x1 layers on the same kernel (pointwise
 # mode 8): chunks of 128 channels whole or split over the waves, 2 to 64 channel blocks, ragged last
 # slices, tiles of fewer than 32 pixels, several tiles per map, a one-pixel map
