@@ -2758,15 +2758,20 @@ __global__ __launch_bounds__(DLF_DWS_WAVES * 64, 1) void k_dws(const DlfDwsArgs 
     // barrier, and no load into one is outstanding)
     constexpr int LPX = 4 * CBW;                             // lanes per pixel in the store phase
     constexpr int PPP = 64 / LPX;                            // pixels per store instruction
+    // (the bias before the first store: a load behind a store waits for the store as well)
+    f4v biasv[CBW][4];
+#pragma unroll
+    for (int c = 0; c < CBW; ++c)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) biasv[c][q] = *(const f4v*)(a.bpw + min(cb0 + c, a.ncb - 1) * 32 + q * 8 + lhi * 4);
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
         if (p * 32 < a.tp) {
 #pragma unroll
             for (int c = 0; c < CBW; ++c) {
-                const int cbj = min(cb0 + c, a.ncb - 1);
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const f4v bias = *(const f4v*)(a.bpw + cbj * 32 + q * 8 + lhi * 4);
+                    const f4v bias = biasv[c][q];
                     unsigned u0 = cvt_pk(acc[c][p][q * 4 + 0] + bias[0], acc[c][p][q * 4 + 1] + bias[1]);
                     unsigned u1 = cvt_pk(acc[c][p][q * 4 + 2] + bias[2], acc[c][p][q * 4 + 3] + bias[3]);
                     u0 = pk_min(pk_max(u0, lo_p), hi_p);
@@ -2970,12 +2975,16 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
         if (!live) return;
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // the transpose buffers lie in the region's space
     }
+    // (the bias before the first store: a load behind a store waits for the store as well)
+    f4v biasv[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) biasv[q] = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
 #pragma unroll
     for (int p = 0; p < FP; ++p) {
         if (p * 32 < a.tp) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const f4v bias = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
+                const f4v bias = biasv[q];
                 unsigned u0 = cvt_pk(acc[p][q * 4 + 0] + bias[0], acc[p][q * 4 + 1] + bias[1]);
                 unsigned u1 = cvt_pk(acc[p][q * 4 + 2] + bias[2], acc[p][q * 4 + 3] + bias[3]);
                 u0 = pk_min(pk_max(u0, lo_e), hi_e);
