@@ -3285,68 +3285,121 @@ extern "C" int dlf_launch_dw(const DlfDwArgs* a, int grid, void* stream);
 // One workgroup per 32 output channels; its 8 waves split K, each streaming a contiguous share
 // of the packed weight fragments from HBM exactly once; partial sums meet in LDS.
 #define DLF_FC_WAVES 8
-__global__ __launch_bounds__(DLF_FC_WAVES * 64) void k_fc(const DlfFcArgs a)
+#define DLF_FC_BROW 144                                      // bytes of an activation row in LDS: 4 K steps + 16
+#define DLF_FC_BBYTES (32 * DLF_FC_BROW)                     // per wave
+
+// K steps [t0, t1) of one block of 32 images for NA streams of weight fragments, on one wave.
+//   Weights: an 8-deep ring of fragments per stream (8 KiB in flight per wave and stream), a slot
+// refilled right behind the MFMA that used it.  A load under a condition is waited for where its
+// branch ends, and the compiler cannot count the loads behind it, so a ring refilled under "if
+// there is a step t + 8" drains at every turn.  Hence: the first fill clamps its step index instead
+// of testing it; while at least 16 steps remain, every refill exists and is issued without a test;
+// the last one or two turns of the ring use the tested form.
+//   Activations: the "B" fragment of a step is 16 bytes of each of 32 rows of x, a row per image:
+// read as it is used, one load touches 32 lines for a quarter of a line each, and with 8 waves at
+// their own places of K the CU's vector cache does not keep those lines for the next three steps
+// (VGG-16's 25088 -> 4096 layer: 45 us at batch 1, 67 us at batch 16 for the same weights).  So a
+// wave fetches the rows' 128 bytes of four steps at once, 8 lanes to a row, four loads for 32 rows,
+// two such groups ahead; the lanes exchange them through the wave's own LDS rows (144 bytes apart:
+// the fragment reads of 32 rows are conflict-free) into the fragments of the four steps.  Beyond K
+// a piece is read from the start of the weights and written as zero.
+template <int NA>
+__device__ __forceinline__ void fc_steps(const DlfFcArgs& a, const h8* const (&wp)[NA], int nb, int t0, int t1,
+                                         char* bb, int lane, f16v (&acc)[NA])
 {
-    __shared__ float red[DLF_FC_WAVES][16][64];
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int l32 = lane & 31, lhi = lane >> 5;
-    const int cb = blockIdx.x;
-    const half_t* x = (const half_t*)a.x;
-    half_t* y = (half_t*)a.y;
-    const h8* wbase = (const h8*)a.w + (size_t)cb * a.nsteps * 64 + lane;
-    for (int nb = 0; nb < a.batch; nb += 32) {
-        const int img = min(nb + l32, a.batch - 1);
-        const half_t* xr = x + (size_t)img * a.k + lhi * 8;
-        f16v acc;
+    const int l32 = lane & 31, lhi = lane >> 5, rrow = lane >> 3, piece = lane & 7;
+    const half_t* xrow[4];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
-        // each wave streams a contiguous eighth of the K steps through an 8-deep operand ring:
-        // 8 KiB of weights in flight per wave, refilled right behind the MFMA that used the slot
-        const int per = (a.nsteps + DLF_FC_WAVES - 1) / DLF_FC_WAVES;
-        const int t0 = wave * per, t1 = min(a.nsteps, t0 + per);
-        // A load under a condition is waited for where its branch ends, and the compiler cannot
-        // count the loads behind it, so a ring refilled under "if there is a step t+8" drains at
-        // every turn.  Hence: the first fill clamps its step index instead of testing it; while at
-        // least 16 steps remain, every refill exists and is issued without a test; the last one or
-        // two turns of the ring use the tested form.  Beyond K the activation vector is read from
-        // the start of the weights and replaced by zero where it is used.
-        h8 av[8], bv[8];
-        const h8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int i = 0; i < 4; ++i)
+        xrow[i] = (const half_t*)a.x + (size_t)min(nb + i * 8 + rrow, a.batch - 1) * a.k + piece * 8;
+    char* const wr = bb + rrow * DLF_FC_BROW + piece * 16;
+    const char* const rd = bb + l32 * DLF_FC_BROW + lhi * 16;
+    h8 av[NA][8], raw[2][4], bv[4];
+    const h8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    auto fetch = [&](int slot, int tg) __attribute__((always_inline)) {      // the group of steps tg .. tg + 3
+        const bool ok = tg * 16 + piece * 8 + 8 <= a.k;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) raw[slot][i] = *(const h8*)(ok ? xrow[i] + tg * 16 : (const half_t*)a.w);
+    };
+    auto exchange = [&](int slot, int tg) __attribute__((always_inline)) {
+        const bool ok = tg * 16 + piece * 8 + 8 <= a.k;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *(h8*)(wr + i * 8 * DLF_FC_BROW) = ok ? raw[slot][i] : zero8;
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int s_ = 0; s_ < 4; ++s_) bv[s_] = *(const h8*)(rd + s_ * 32);
+        __builtin_amdgcn_wave_barrier();
+    };
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int t = max(min(t0 + j, t1 - 1), 0);
+#pragma unroll
+        for (int n = 0; n < NA; ++n) av[n][j] = wp[n][(size_t)t * 64];
+    }
+    fetch(0, t0);
+    fetch(1, t0 + 4);
+    int tb = t0;
+    for (; tb + 16 <= t1; tb += 8) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int t = max(min(t0 + j, t1 - 1), 0);
-            av[j] = wbase[(size_t)t * 64];
-            bv[j] = *(const h8*)(t * 16 + lhi * 8 + 8 <= a.k ? xr + t * 16 : (const half_t*)a.w);
-        }
-        int tb = t0;
-        for (; tb + 16 <= t1; tb += 8) {
+            if (j == 0) { exchange(0, tb); fetch(0, tb + 8); }
+            if (j == 4) { exchange(1, tb + 4); fetch(1, tb + 12); }
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[j], bv[j], acc, 0, 0, 0);
-                const int tn = tb + j + 8;
-                av[j] = wbase[(size_t)tn * 64];
-                bv[j] = *(const h8*)(tn * 16 + lhi * 8 + 8 <= a.k ? xr + tn * 16 : (const half_t*)a.w);
+            for (int n = 0; n < NA; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[n][j], bv[j & 3], acc[n], 0, 0, 0);
+            const int tn = tb + j + 8;
+#pragma unroll
+            for (int n = 0; n < NA; ++n) av[n][j] = wp[n][(size_t)tn * 64];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    for (; tb < t1; tb += 8) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (j == 0) {
+                exchange(0, tb);
+                if (tb + 8 < t1) fetch(0, tb + 8);
+            }
+            if (j == 4) {
+                exchange(1, tb + 4);
+                if (tb + 12 < t1) fetch(1, tb + 12);
+            }
+            const int t = tb + j;
+            if (t < t1) {
+#pragma unroll
+                for (int n = 0; n < NA; ++n)
+                    acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[n][j], bv[j & 3], acc[n], 0, 0, 0);
+                const int tn = t + 8;
+                if (tn < t1) {
+#pragma unroll
+                    for (int n = 0; n < NA; ++n) av[n][j] = wp[n][(size_t)tn * 64];
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        for (; tb < t1; tb += 8) {
+    }
+}
+
+__global__ __launch_bounds__(DLF_FC_WAVES * 64) void k_fc(const DlfFcArgs a)
+{
+    // the waves' activation rows during the K loop, their partial sums behind it
+    __shared__ __align__(16) char smem[DLF_FC_WAVES * DLF_FC_BBYTES];
+    static_assert(sizeof(smem) >= DLF_FC_WAVES * 16 * 64 * 4, "partial sums");
+    float (*const red)[16][64] = (float (*)[16][64])smem;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cb = blockIdx.x;
+    half_t* y = (half_t*)a.y;
+    const h8* const wp[1] = {(const h8*)a.w + (size_t)cb * a.nsteps * 64 + lane};
+    // each wave a contiguous eighth of the K steps, whole groups of four
+    const int per = ((a.nsteps + DLF_FC_WAVES - 1) / DLF_FC_WAVES + 3) & ~3;
+    const int t0 = min(wave * per, a.nsteps), t1 = min(a.nsteps, t0 + per);
+    for (int nb = 0; nb < a.batch; nb += 32) {
+        f16v acc[1];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int t = tb + j;
-                if (t < t1) {
-                    const h8 bj = t * 16 + lhi * 8 + 8 <= a.k ? bv[j] : zero8;
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[j], bj, acc, 0, 0, 0);
-                    const int tn = t + 8;
-                    if (tn < t1) {
-                        av[j] = wbase[(size_t)tn * 64];
-                        bv[j] = *(const h8*)(tn * 16 + lhi * 8 + 8 <= a.k ? xr + tn * 16 : (const half_t*)a.w);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-        }
+        for (int i = 0; i < 16; ++i) acc[0][i] = 0.0f;
+        fc_steps<1>(a, wp, nb, t0, t1, smem + wave * DLF_FC_BBYTES, lane, acc);
+        __syncthreads();                                     // the sums take the rows' place
 #pragma unroll
-        for (int i = 0; i < 16; ++i) red[wave][i][lane] = acc[i];
+        for (int i = 0; i < 16; ++i) red[wave][i][lane] = acc[0][i];
         __syncthreads();
         for (int e = tid; e < 16 * 64; e += DLF_FC_WAVES * 64) {
             const int i = e >> 6, ln = e & 63;
@@ -3370,71 +3423,30 @@ __global__ __launch_bounds__(DLF_FC_WAVES * 64) void k_fc(const DlfFcArgs a)
 // order, the bias and the activation.
 __global__ __launch_bounds__(DLF_FC_WAVES * 64) void k_fc_sk(const DlfFcArgs a)
 {
-    __shared__ float red[DLF_FC_WAVES][16][64];
+    __shared__ __align__(16) char smem[DLF_FC_WAVES * DLF_FC_BBYTES];
+    float (*const red)[16][64] = (float (*)[16][64])smem;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int l32 = lane & 31, lhi = lane >> 5;
     const int ks = blockIdx.x % a.ksplit, cbp = blockIdx.x / a.ksplit;
     const int cb0 = cbp * 2, cb1 = min(cb0 + 1, a.ncb - 1);
-    const half_t* x = (const half_t*)a.x;
-    const h8* w0 = (const h8*)a.w + (size_t)cb0 * a.nsteps * 64 + lane;
-    const h8* w1 = (const h8*)a.w + (size_t)cb1 * a.nsteps * 64 + lane;
-    const int per_ks = (a.nsteps + a.ksplit - 1) / a.ksplit;
-    const int s0 = ks * per_ks, s1 = min(a.nsteps, s0 + per_ks);
-    const int per = (max(s1 - s0, 0) + DLF_FC_WAVES - 1) / DLF_FC_WAVES;
-    const int t0 = s0 + wave * per, t1 = min(s1, t0 + per);
+    const h8* const wp[2] = {(const h8*)a.w + (size_t)cb0 * a.nsteps * 64 + lane,
+                             (const h8*)a.w + (size_t)cb1 * a.nsteps * 64 + lane};
+    // slices and the waves' shares of a slice: whole groups of four K steps
+    const int per_ks = ((a.nsteps + a.ksplit - 1) / a.ksplit + 3) & ~3;
+    const int s0 = min(ks * per_ks, a.nsteps), s1 = min(a.nsteps, s0 + per_ks);
+    const int per = ((s1 - s0 + DLF_FC_WAVES - 1) / DLF_FC_WAVES + 3) & ~3;
+    const int t0 = min(s0 + wave * per, s1), t1 = min(s1, t0 + per);
     for (int nb = 0; nb < a.batch; nb += 32) {
-        const int img = min(nb + l32, a.batch - 1);
-        const half_t* xr = x + (size_t)img * a.k + lhi * 8;
-        f16v acc0, acc1;
+        f16v acc[2];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) { acc0[i] = 0.0f; acc1[i] = 0.0f; }
-        // the ring is filled and refilled as in k_fc
-        h8 av0[8], av1[8], bv[8];
-        const h8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int t = max(min(t0 + j, t1 - 1), 0);
-            av0[j] = w0[(size_t)t * 64];
-            av1[j] = w1[(size_t)t * 64];
-            bv[j] = *(const h8*)(t * 16 + lhi * 8 + 8 <= a.k ? xr + t * 16 : (const half_t*)a.w);
-        }
-        int tb = t0;
-        for (; tb + 16 <= t1; tb += 8) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(av0[j], bv[j], acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(av1[j], bv[j], acc1, 0, 0, 0);
-                const int tn = tb + j + 8;
-                av0[j] = w0[(size_t)tn * 64];
-                av1[j] = w1[(size_t)tn * 64];
-                bv[j] = *(const h8*)(tn * 16 + lhi * 8 + 8 <= a.k ? xr + tn * 16 : (const half_t*)a.w);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        for (; tb < t1; tb += 8) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int t = tb + j;
-                if (t < t1) {
-                    const h8 bj = t * 16 + lhi * 8 + 8 <= a.k ? bv[j] : zero8;
-                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(av0[j], bj, acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(av1[j], bj, acc1, 0, 0, 0);
-                    const int tn = t + 8;
-                    if (tn < t1) {
-                        av0[j] = w0[(size_t)tn * 64];
-                        av1[j] = w1[(size_t)tn * 64];
-                        bv[j] = *(const h8*)(tn * 16 + lhi * 8 + 8 <= a.k ? xr + tn * 16 : (const half_t*)a.w);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-        }
+        for (int i = 0; i < 16; ++i) { acc[0][i] = 0.0f; acc[1][i] = 0.0f; }
+        fc_steps<2>(a, wp, nb, t0, t1, smem + wave * DLF_FC_BBYTES, lane, acc);
+        __syncthreads();                                     // the sums take the rows' place
         float* pbase = a.part + (size_t)((nb >> 5) * a.ksplit + ks) * a.ncb * 1024;
 #pragma unroll
         for (int f = 0; f < 2; ++f) {
             if (f == 1 && cb0 + 1 >= a.ncb) break;          // uniform: an odd number of blocks
 #pragma unroll
-            for (int i = 0; i < 16; ++i) red[wave][i][lane] = f == 0 ? acc0[i] : acc1[i];
+            for (int i = 0; i < 16; ++i) red[wave][i][lane] = acc[f][i];
             __syncthreads();
             for (int e = tid; e < 16 * 64; e += DLF_FC_WAVES * 64) {
                 const int i = e >> 6, ln = e & 63;
