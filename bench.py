@@ -188,7 +188,7 @@ def group_accounting(net, batch, session):
             kname = "k_c3s<%d,%d,%d>" % (1 if cfg["variant"] >= 8 else 9, net["layers"][f]["stride"],
                                          2 if info["tile_h"] * info["tile_w"] > 32 else 1)
         elif cfg["kind"] == 11:
-            kname = "k_c3pw<%d>" % cfg["variant"]
+            kname = "k_c3pw<%d,%d>" % (cfg["variant"], net["layers"][f]["cin"])
         elif cfg["kind"] == 9:
             kname = "k_dws<%d,%d>" % (cfg["variant"] // 2 + 1, cfg["variant"] % 2 + 1)
         elif cfg["kind"] == 8:

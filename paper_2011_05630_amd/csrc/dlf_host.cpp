@@ -1128,7 +1128,7 @@ bool c3s_eligible(const dlf_net_s& net, const std::vector<StageSpec>& specs, int
     const Layer& L = net.L[specs[0].layer];
     const dlf_layer_desc& d = L.d;
     if (d.op != DLF_CONV || d.kh != 3 || d.kw != 3 || (d.stride != 1 && d.stride != 2) || d.pad != 1) return false;
-    if (L.im2col || L.rowfold || !c3s_cin_ok(d.cin) || (d.cout % 8) != 0 || d.residual_from >= 0) return false;
+    if (L.im2col || L.rowfold || !c3s_cin_ok(d.cin) || (d.cout % 8) != 0) return false;
     // the input is read through a buffer resource whose range check supplies the padding: below 2 GiB
     if ((int64_t)batch * L.in_h * L.in_w * L.in_c * 2 >= (int64_t)1 << 31) return false;
     if ((int64_t)batch * L.out_h * L.out_w * L.out_c >= (int64_t)1 << 31) return false;
@@ -1184,10 +1184,11 @@ uint64_t c3s_cost_ps(const Layer& L, int batch, int budget, const DlfC3sArgs& cs
                          (int64_t)(cs.nsteps / cs.ksplit) * (wbytes > C_C3S_BIG_BYTES ? C_C3S_STEP_BIG : C_C3S_STEP) *
                              (cs.tp > 32 ? 4 : 3) / 4 +        // one pixel block: half the MFMAs, the same weights
 
-                         (cs.ksplit > 1 ? C_C3S_RED : 0) + C_C3S_EPI;
+                         (cs.ksplit > 1 ? C_C3S_RED : 0) + C_C3S_EPI + (L.d.residual_from >= 0 ? C_PW_RES : 0);
     const int64_t compute = C_LAT + rounds * item;
     const int64_t m = (int64_t)batch * L.out_h * L.out_w;
-    const int64_t bytes = (int64_t)batch * L.in_h * L.in_w * L.d.cin * 2 + m * L.d.cout * 2 + (int64_t)L.ncb * L.nsteps * 1024;
+    const int64_t bytes = (int64_t)batch * L.in_h * L.in_w * L.d.cin * 2 + m * L.d.cout * 2 * (L.d.residual_from >= 0 ? 2 : 1) +
+                          (int64_t)L.ncb * L.nsteps * 1024;
     const int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
     return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
 }
@@ -1685,6 +1686,7 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
         g.grid = cs.slice_major ? ceil_div(cs.ntiles, 8 / cs.nsl) * 8 : ceil_div(cs.ntiles, 8) * 8 * cs.nsl;
         g.th = cs.th; g.tw = cs.tw;
         g.lds_bytes = (int)DLF_C3S_LDS_BYTES(cs.rp, cs.cin);
+        if (L0.d.residual_from >= 0) { g.res_layer = L0.d.residual_from; g.res_stage = 0; }
         return DLF_OK;
     }
     if (!tiled)
@@ -2308,6 +2310,10 @@ static dlf_status launch_one(const dlf_plan_s* plan, const GroupPlan& G, const v
     } else if (G.kind == GK_C3S) {
         DlfC3sArgs cs = G.cs;
         cs.in = in; cs.out = out;
+        if (G.res_stage >= 0) {
+            if (!res) return fail(DLF_ERR_INVALID_ARG, "group [%d,%d] needs its residual operand", G.first, G.last);
+            cs.res = res;
+        }
         e = dlf_launch_c3s(&cs, G.grid, G.lds_bytes, stream);
     } else if (G.kind == GK_C3PW) {
         DlfC3PwArgs cp = G.cp;

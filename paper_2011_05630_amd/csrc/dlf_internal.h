@@ -270,6 +270,7 @@ struct DlfDwsArgs {
 struct DlfC3sArgs {
     const void* in;       // [batch][h][w][cin] fp16
     void* out;            // [batch][oh][ow][cout] fp16
+    const void* res;      // residual operand [batch][oh][ow][cout] fp16, or null
     const void* w;        // packed weight fragments, K step = (32-channel chunk, tap, half)
     const float* bias;    // padded to ncb * 32
     uint32_t in_bytes;    // size of the input tensor (below 2 GiB)

@@ -2953,6 +2953,28 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
     // ---- step 3: partial sums, epilogue ----
     float* const red = (float*)lds;
     half_t* const tb = lds + DLF_C3S_RED_BYTES / 2 + wave * (32 * ROW);
+    // the residual vectors of the pixels and channels this lane will store, and the bias: requested
+    // here, ahead of the exchange of partial sums and of the first store (a load behind a store
+    // waits for the store as well)
+    const half_t* const resp = (const half_t*)a.res;
+    u4v rv[FP][2];
+    f4v biasv[4];
+    if (live && kpart == 0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) biasv[q] = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
+        if (resp != nullptr) {
+            const int cc = cb * 32 + (lane & 3) * 8;
+#pragma unroll
+            for (int p = 0; p < FP; ++p)
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int px_ = min(p * 32 + i * 16 + (lane >> 2), a.tp - 1);
+                    const int row = div_by(px_, tw_m), colp = px_ - row * a.tw;
+                    const int oy = min(oy0 + row, a.oh - 1), ox = min(ox0 + colp, a.ow - 1);
+                    rv[p][i] = *(const u4v*)(resp + ((size_t)((n * a.oh + oy) * a.ow + ox) * a.cout + min(cc, a.cout - 8)));
+                }
+        }
+    }
     if (a.ksplit > 1) {
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // everyone is done reading the region
         if (kpart > 0 && live) {
@@ -2975,10 +2997,8 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
         if (!live) return;
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // the transpose buffers lie in the region's space
     }
-    // (the bias before the first store: a load behind a store waits for the store as well)
-    f4v biasv[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) biasv[q] = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
+    // with a residual operand the activation follows the add (fp16 + fp16, as in the other kernels)
+    const unsigned lo_t = resp != nullptr ? act_lo(0) : lo_e, hi_t = resp != nullptr ? act_hi(0) : hi_e;
 #pragma unroll
     for (int p = 0; p < FP; ++p) {
         if (p * 32 < a.tp) {
@@ -2987,8 +3007,8 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
                 const f4v bias = biasv[q];
                 unsigned u0 = cvt_pk(acc[p][q * 4 + 0] + bias[0], acc[p][q * 4 + 1] + bias[1]);
                 unsigned u1 = cvt_pk(acc[p][q * 4 + 2] + bias[2], acc[p][q * 4 + 3] + bias[3]);
-                u0 = pk_min(pk_max(u0, lo_e), hi_e);
-                u1 = pk_min(pk_max(u1, lo_e), hi_e);
+                u0 = pk_min(pk_max(u0, lo_t), hi_t);
+                u1 = pk_min(pk_max(u1, lo_t), hi_t);
                 const u2v uu = {u0, u1};
                 *(u2v*)(tb + l32 * ROW + q * 8 + lhi * 4) = uu;
             }
@@ -3001,8 +3021,16 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
                 const int px_ = p * 32 + pl;
                 const int row = div_by(px_, tw_m), colp = px_ - row * a.tw;
                 const int oy = oy0 + row, ox = ox0 + colp;
-                if (px_ < a.tp && oy < a.oh && ox < a.ow && cc < a.cout)
-                    *(u4v*)(outp + ((size_t)((n * a.oh + oy) * a.ow + ox) * a.cout + cc)) = *(const u4v*)(tb + pl * ROW + part * 8);
+                if (px_ < a.tp && oy < a.oh && ox < a.ow && cc < a.cout) {
+                    u4v v = *(const u4v*)(tb + pl * ROW + part * 8);
+                    if (resp != nullptr) {
+                        v.x = pk_min(pk_max(pk_add(v.x, rv[p][i].x), lo_e), hi_e);
+                        v.y = pk_min(pk_max(pk_add(v.y, rv[p][i].y), lo_e), hi_e);
+                        v.z = pk_min(pk_max(pk_add(v.z, rv[p][i].z), lo_e), hi_e);
+                        v.w = pk_min(pk_max(pk_add(v.w, rv[p][i].w), lo_e), hi_e);
+                    }
+                    *(u4v*)(outp + ((size_t)((n * a.oh + oy) * a.ow + ox) * a.cout + cc)) = v;
+                }
             }
             __builtin_amdgcn_wave_barrier();
         }

@@ -661,6 +661,39 @@ def test_small_map_3x3_kernel(cin, cout, h, w, batch, ksplit, act, stride):
     compare(got, o.run_net(net, x, ws, bs), "small-map 3x3 s%d %d->%d %dx%d" % (stride, cin, cout, h, w))
 
 
+# (cin, cout, height, width, batch, waves per channel block, activation, stride): the same kernel with a residual
+# operand added before the activation (the second 3x3 layer of a basic residual block): one and two 32-pixel
+# blocks, K shared by 1, 2 and 4 waves, a ragged last channel block, ragged tiles, stride 2
+C3S_RES_CASES = [(256, 256, 14, 14, 2, 2, "relu", 1), (512, 512, 7, 7, 3, 4, "relu", 1), (256, 200, 9, 11, 2, 1, "relu6", 1),
+                 (512, 96, 3, 5, 3, 0, "none", 1), (256, 256, 13, 15, 2, 0, "relu", 2), (1024, 128, 4, 4, 2, 2, "relu", 1)]
+
+
+@pytest.mark.parametrize("cin,cout,h,w,batch,ksplit,act,stride", C3S_RES_CASES)
+def test_small_map_3x3_kernel_residual(cin, cout, h, w, batch, ksplit, act, stride):
+    from oracle import oracle as o
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    announce("small-map 3x3 + residual", cin, cout, h, w, batch, ksplit, act, stride)
+    # layer 0 makes the input of the layer under test, layer 1 the residual operand (at the output's size)
+    layers = [nets.conv(64, cin, 1, 1, 0, "relu"), nets.conv(cin, cout, 3, stride, 1, "relu"),
+              nets.conv(cin, cout, 3, stride, 1, act, input_from=0, residual_from=1)]
+    net = _mk(layers, h, w, 64, dist="normal")
+    x, ws, bs = gen.make_params(net, batch, 15)
+    B.dlf_debug_block3x3_mode(1, 5, ksplit, 0)
+    try:
+        s = Session(net, batch, ws, bs, **_manual(3, [0, 1, 2]))
+    finally:
+        B.dlf_debug_block3x3_mode(0)
+    try:
+        cfg = B.dlf_plan_group_config(s.plan, 2)
+        assert cfg["kind"] == 10, cfg
+        assert B.dlf_plan_group_io(s.plan, 2) == (0, 1)
+        got = s.run_numpy(x)
+    finally:
+        s.close()
+    compare(got, o.run_net(net, x, ws, bs), "small-map 3x3 + residual s%d %d->%d %dx%d" % (stride, cin, cout, h, w))
+
+
 # (c, cout, height, width, batch, tile th, tile tw, act of the 3x3, act of the 1x1, residual): the fused
 # 3x3 -> 1x1 kernel (shape 6 of the hook; th = 0: the planner's cut): two and four 32-pixel blocks per
 # tile, ragged tiles at the map's edges, tiles of one row or one column, 128 and 256 channels, one and two slices of
