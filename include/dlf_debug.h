@@ -53,7 +53,7 @@ void dlf_debug_depthwise_tile(int32_t wx, int32_t rw);
  * fixes the block's shape and its th x tw pixel tile: shape 0 / 1 = 128 channels x up to 256
  * pixels with activations brought in 32 / 64 input channels at a time, 2 / 3 = 64 channels x up to
  * 512 pixels likewise, 4 = 128 channels x up to 512 pixels (32 input channels at a time), 5 = the kernel
- * for maps of many channels and few pixels (cin 256, 512, 1024 or 2048, no pool, no residual; th > 0 then
+ * for maps of many channels and few pixels (cin 256, 512, 1024 or 2048, no pool; th > 0 then
  * fixes the number of waves that share a channel block's K: 1, 2 or 4; tw is not used), 6 = the
  * kernel for a 3x3 layer (128 or 256 channels in and out) with a 1x1 layer behind it as one group
  * (th, tw > 0 then fix the tile the map is cut into equal parts for: at most 8 x 16 pixels); a shape

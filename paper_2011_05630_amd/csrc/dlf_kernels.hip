@@ -2798,7 +2798,7 @@ __global__ __launch_bounds__(DLF_DWS_WAVES * 64, 1) void k_dws(const DlfDwsArgs 
     }
 }
 
-// 3x3 convolution (pad 1, stride 1 or 2) or 1x1 convolution (stride 1), + bias + activation, where a map has
+// 3x3 convolution (pad 1, stride 1 or 2; + residual operand) or 1x1 convolution (stride 1), + bias + activation, where a map has
 // many channels and few pixels: the 14 x 14 and 7 x 7 maps of ResNet-50's and VGG-16's last stages.  The block kernel k_c3b has too
 // few 128-channel x 256-pixel blocks there to fill the chip, and in the fused-group kernel every wave
 // streams weights for one or two pixel blocks of its own.  Built like k_dws:
@@ -2819,7 +2819,8 @@ __global__ __launch_bounds__(DLF_DWS_WAVES * 64, 1) void k_dws(const DlfDwsArgs 
 //      a register ring of 9 K steps).  The tap of a K step is static in the unrolled chunk, so the
 //      lane's nine (tap-shifted pixel, permutation) pairs stay in registers.
 //   3. Partial sums of the waves of a channel block meet in LDS (in the region's space, behind a
-//      barrier); bias, activation, fp16, transpose, 64-byte runs per pixel to memory.
+//      barrier); bias, fp16, residual operand if there is one (its vectors requested right behind
+//      the K loop), activation, transpose, 64-byte runs per pixel to memory.
 template <int TAPS, int S, int FP>
 __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs a)
 {
