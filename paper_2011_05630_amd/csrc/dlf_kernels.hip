@@ -3363,7 +3363,7 @@ __device__ __forceinline__ void fc_steps(const DlfFcArgs& a, const h8* const (&w
     for (int j = 0; j < 8; ++j) {
         const int t = max(min(t0 + j, t1 - 1), 0);
 #pragma unroll
-        for (int n = 0; n < NA; ++n) av[n][j] = wp[n][(size_t)t * 64];
+        for (int n = 0; n < NA; ++n) av[n][j] = __builtin_nontemporal_load(wp[n] + (size_t)t * 64);
     }
     fetch(0, t0);
     fetch(1, t0 + 4);
@@ -3377,7 +3377,7 @@ __device__ __forceinline__ void fc_steps(const DlfFcArgs& a, const h8* const (&w
             for (int n = 0; n < NA; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[n][j], bv[j & 3], acc[n], 0, 0, 0);
             const int tn = tb + j + 8;
 #pragma unroll
-            for (int n = 0; n < NA; ++n) av[n][j] = wp[n][(size_t)tn * 64];
+            for (int n = 0; n < NA; ++n) av[n][j] = __builtin_nontemporal_load(wp[n] + (size_t)tn * 64);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -3400,7 +3400,7 @@ __device__ __forceinline__ void fc_steps(const DlfFcArgs& a, const h8* const (&w
                 const int tn = t + 8;
                 if (tn < t1) {
 #pragma unroll
-                    for (int n = 0; n < NA; ++n) av[n][j] = wp[n][(size_t)tn * 64];
+                    for (int n = 0; n < NA; ++n) av[n][j] = __builtin_nontemporal_load(wp[n] + (size_t)tn * 64);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
