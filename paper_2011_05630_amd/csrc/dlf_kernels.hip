@@ -121,6 +121,11 @@ __device__ __forceinline__ unsigned cvt_pk(float a, float b)
 __device__ __forceinline__ unsigned act_lo(int act) { return act == 0 ? 0xFC00FC00u : 0u; }
 __device__ __forceinline__ unsigned act_hi(int act) { return act == 2 ? 0x46004600u : 0x7C007C00u; }
 
+// Output of the block pointwise kernel: to memory with the streaming hint (nothing in the same
+// launch reads it again).  Measured per kernel: it shortens k_pwb's launches by 1 - 3 us; on the
+// outputs of the other kernels the next layer loses what the storing one gains.
+__device__ __forceinline__ void store_out(half_t* p, u4v v) { __builtin_nontemporal_store(v, (u4v*)p); }
+
 __device__ __forceinline__ unsigned quad_max_pk(unsigned v)
 {
     // max over the 4 lanes of a quad with two DPP quad permutes: [1,0,3,2] then [2,3,0,1]
@@ -1698,7 +1703,7 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
                     val[i].z = pk_min(pk_max(pk_add(val[i].z, rv[i].z), lo_r), hi_r);
                     val[i].w = pk_min(pk_max(pk_add(val[i].w, rv[i].w), lo_r), hi_r);
                 }
-                *(u4v*)(outp + go[i]) = val[i];
+                store_out(outp + go[i], val[i]);
             }
         }
     }
