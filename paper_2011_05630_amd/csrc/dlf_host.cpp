@@ -312,6 +312,7 @@ const int64_t C_C3PW_STEP = 125;
 const int64_t C_C3PW_MID = 600;
 const int64_t C_C3PW_SECOND = 1000;
 const int64_t C3PW_STORE_BYTES_PER_CYCLE = 2300;
+const int64_t C3PW_OVERLAP_PCT = 60;         // two workgroups per CU: what a further round of items adds, in per cent of an item
 
 struct StageSpec {   // one stage, before tiling
     int layer;
@@ -1221,7 +1222,7 @@ bool c3pw_eligible(const dlf_net_s& net, const std::vector<StageSpec>& specs, in
     const dlf_layer_desc& a = A.d;
     const dlf_layer_desc& p = P.d;
     if (a.kh != 3 || a.kw != 3 || a.stride != 1 || a.pad != 1 || A.im2col || A.rowfold || a.residual_from >= 0) return false;
-    if ((a.cin != 128 && a.cin != 256) || a.cout != a.cin) return false;
+    if ((a.cin != 64 && a.cin != 128 && a.cin != 256) || a.cout != a.cin) return false;
     if (p.kh != 1 || p.kw != 1 || p.stride != 1 || p.pad != 0 || P.im2col || P.rowfold || (p.cout % 8) != 0) return false;
     if ((int64_t)batch * A.in_h * A.in_w * a.cin * 2 >= (int64_t)1 << 31) return false;
     if ((int64_t)batch * P.out_h * P.out_w * p.cout * 2 >= (int64_t)1 << 31) return false;
@@ -1239,7 +1240,9 @@ bool c3pw_build(const Layer& A, const Layer& P, int batch, int rows, int cols, i
     cp.tp = cp.th * cp.tw;
     cp.rw = cp.tw + 2;
     cp.rp = (cp.th + 2) * cp.rw;
-    if ((int)DLF_C3PW_LDS_BYTES(cp.rp, cp.tp, A.d.cin, P.d.residual_from >= 0) > max_lds) return false;
+    // 64 channels: items of four waves, two of them to a CU
+    if ((int)DLF_C3PW_LDS_BYTES(cp.rp, cp.tp, A.d.cin, P.d.residual_from >= 0) > (A.d.cin == 64 ? std::min(max_lds, 80 * 1024) : max_lds))
+        return false;
     cp.w1 = A.d_w; cp.b1 = A.d_bias; cp.w2 = P.d_w; cp.b2 = P.d_bias;
     cp.in_bytes = (uint32_t)((int64_t)batch * A.in_h * A.in_w * A.in_c * 2);
     cp.res_bytes = (uint32_t)((int64_t)batch * P.out_h * P.out_w * P.d.cout * 2);
@@ -1247,29 +1250,49 @@ bool c3pw_build(const Layer& A, const Layer& P, int batch, int rows, int cols, i
     cp.ncb2 = P.ncb; cp.act1 = A.d.act; cp.act2 = P.d.act;
     cp.tiles_y = ceil_div(A.out_h, cp.th); cp.tiles_x = ceil_div(A.out_w, cp.tw);
     cp.ntiles = batch * cp.tiles_y * cp.tiles_x;
-    cp.nsl = ceil_div(P.ncb, 2 * DLF_C3PW_WAVES);
+    cp.nsl = ceil_div(P.ncb, 2 * DLF_C3PW_WAVES(A.d.cin));
     return true;
+}
+
+// Workgroups of the kernel a CU holds: one of eight waves; of four waves as many as LDS and
+// registers take (two with four 32-pixel blocks per wave, else three).
+int c3pw_per_cu(const DlfC3PwArgs& cp, bool res)
+{
+    if (cp.c != 64) return 1;
+    const int lds = (int)DLF_C3PW_LDS_BYTES(cp.rp, cp.tp, cp.c, res);
+    return std::max(1, std::min(cp.tp > 64 ? 2 : 3, (160 * 1024) / lds));
 }
 
 uint64_t c3pw_cost_ps(const Layer& A, const Layer& P, int batch, int budget, const DlfC3PwArgs& cp)
 {
+    const int waves = DLF_C3PW_WAVES(cp.c), per_cu = c3pw_per_cu(cp, P.d.residual_from >= 0);
     const int64_t nitems = (int64_t)cp.ntiles * cp.nsl;
-    const int64_t rounds = (nitems + budget - 1) / budget;
+    const int64_t slots = (int64_t)budget * per_cu;
+    const int64_t rounds = (nitems + slots - 1) / slots;
     const int64_t fp = cp.tp > 64 ? 4 : 2, ncb1 = cp.c / 32;
     const bool res = P.d.residual_from >= 0;
-    const int64_t intake = (int64_t)cp.rp * cp.c * 2 + (res && ncb1 == DLF_C3PW_WAVES ? (int64_t)cp.tp * 1024 : 0);
+    const int64_t intake = (int64_t)cp.rp * cp.c * 2 + (res && ncb1 == waves ? (int64_t)cp.tp * 1024 : 0);
     const int64_t mma1 = (int64_t)A.nsteps * std::max(fp * C_C3PW_MMA * (ncb1 > 4 ? 2 : 1), C_C3PW_STEP);
     const int64_t pbs = ceil_div(cp.tp, 32);
-    const int64_t cb_item = std::min<int64_t>(P.ncb, 2 * DLF_C3PW_WAVES);
-    const int64_t mma2 = pbs * P.nsteps * ceil_div(cb_item, 4) * C_C3PW_MMA;     // a SIMD's two waves, two blocks each
-    const int64_t stores = std::min<int64_t>(nitems, budget) * cp.tp * cb_item * 64 / C3PW_STORE_BYTES_PER_CYCLE;
+    const int64_t cb_item = std::min<int64_t>(P.ncb, 2 * waves);
+    const int64_t mma2 = pbs * P.nsteps * ceil_div(cb_item, 4) * C_C3PW_MMA;     // the waves of a SIMD, two blocks each
+    const int64_t stores = std::min<int64_t>(nitems, slots) * cp.tp * cb_item * 64 / C3PW_STORE_BYTES_PER_CYCLE;
     const int64_t item = C_C3PW_ITEM + intake / C3PW_BYTES_PER_CYCLE + mma1 + ncb1 * C_C3PW_MID + C_C3PW_SECOND +
                          std::max(mma2, stores);
-    const int64_t compute = C_LAT + rounds * item;
+    // one workgroup per CU: a further item of a CU repeats every phase behind the first; two per
+    // CU: their phases interleave, and the rounds cost what the chip's memory takes for them
+    const int64_t compute = C_LAT + (per_cu == 1 ? rounds * item + (rounds > 1 ? (rounds - 1) * C_C3S_NEXT : 0)
+                                                 : item + (rounds - 1) * item * C3PW_OVERLAP_PCT / 100);
     const int64_t m = (int64_t)batch * P.out_h * P.out_w;
     const int64_t bytes = (int64_t)batch * A.in_h * A.in_w * cp.c * 2 + m * cp.cout * 2 * (res ? 2 : 1) +
                           ((int64_t)A.ncb * A.nsteps + (int64_t)P.ncb * P.nsteps) * 1024;
-    const int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
+    int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
+    if (per_cu > 1) {
+        // measured on the 56 x 56 pair of ResNet-50 (tiles 7x8, 4x14: 31.6 us; 7x14: 32.9; 8x8: 36.7;
+        // 8x12: 36.9): three workgroups per CU hold the memory rate, two lose some of it, and
+        // pixels of tiles that hang over the map's edge cost like real ones
+        mem = mem * (per_cu >= 3 ? 100 : 104) / 100 * ((int64_t)cp.ntiles * cp.tp) / m;
+    }
     return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
 }
 
@@ -1621,7 +1644,7 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
             g.kind = GK_C3PW;
             g.cost = pc;
             g.variant = cp.tp > 64 ? 4 : 2;
-            g.occ = 1;
+            g.occ = c3pw_per_cu(cp, P.d.residual_from >= 0);
             g.grid = ceil_div(cp.ntiles, 8) * 8 * cp.nsl;
             g.th = cp.th; g.tw = cp.tw;
             g.lds_bytes = (int)DLF_C3PW_LDS_BYTES(cp.rp, cp.tp, cp.c, P.d.residual_from >= 0);

@@ -285,25 +285,25 @@ struct DlfC3sArgs {
     int32_t slice_major;  // 1: an XCD keeps to one slice (nsl 2, 4 or 8); 0: the slices of a tile share an XCD
 };
 
-// 3x3 convolution (stride 1, pad 1, cin = cout = c: 128 or 256) and the 1x1 convolution behind it, with
+// 3x3 convolution (stride 1, pad 1, cin = cout = c: 64, 128 or 256) and the 1x1 convolution behind it, with
 // a residual operand added to the second layer's result: the second half of a bottleneck block, where
 // the batch's tiles are no more than the chip's CUs (ResNet-50's 28 x 28 stage at batch 32).  One
 // workgroup of eight waves per work item = (tile of up to 128 output pixels, slice of 16 channel
 // blocks of the second layer); the input region goes to LDS by direct loads, the first layer's
 // result stays in LDS as [pixel][c + 8].
-#define DLF_C3PW_WAVES 8
+#define DLF_C3PW_WAVES(C) ((C) == 64 ? 4 : 8)             /* 64 channels: four waves, two workgroups per CU */
 #define DLF_C3PW_IN_BYTES(RP, C) ((((RP) * (C) * 2 + 1023) / 1024) * 1024)
-#define DLF_C3PW_EPI_BYTES (DLF_C3PW_WAVES * 32 * (32 + 8) * 2)
+#define DLF_C3PW_EPI_BYTES(C) (DLF_C3PW_WAVES(C) * 32 * (32 + 8) * 2)
 #define DLF_C3PW_MID_BYTES(TP, C) ((TP) * ((C) + 8) * 2)
-#define DLF_C3PW_RES_STRIDE (1024 + 64)
+#define DLF_C3PW_RES_STRIDE(C) (DLF_C3PW_WAVES(C) * 128 + 64)   /* a pixel's residual row: the item's channels + 64 bytes */
 // the first layer's result takes the region's place; behind it the waves' transpose buffers, then
 // (past the region's end) the residual operand
 #define DLF_C3PW_TB_OFF(TP, C) (((DLF_C3PW_MID_BYTES(TP, C) + 63) / 64) * 64)
-#define DLF_C3PW_RES_OFF(RP, TP, C)                                                      \
-    (DLF_C3PW_IN_BYTES(RP, C) > DLF_C3PW_TB_OFF(TP, C) + DLF_C3PW_EPI_BYTES ? DLF_C3PW_IN_BYTES(RP, C) \
-                                                                             : DLF_C3PW_TB_OFF(TP, C) + DLF_C3PW_EPI_BYTES)
-#define DLF_C3PW_BIAS_OFF(RP, TP, C, RES) (DLF_C3PW_RES_OFF(RP, TP, C) + ((RES) ? (TP) * DLF_C3PW_RES_STRIDE : 0))
-#define DLF_C3PW_LDS_BYTES(RP, TP, C, RES) (DLF_C3PW_BIAS_OFF(RP, TP, C, RES) + DLF_C3PW_WAVES * 64 * 4)
+#define DLF_C3PW_RES_OFF(RP, TP, C)                                                                        \
+    (DLF_C3PW_IN_BYTES(RP, C) > DLF_C3PW_TB_OFF(TP, C) + DLF_C3PW_EPI_BYTES(C) ? DLF_C3PW_IN_BYTES(RP, C) \
+                                                                                : DLF_C3PW_TB_OFF(TP, C) + DLF_C3PW_EPI_BYTES(C))
+#define DLF_C3PW_BIAS_OFF(RP, TP, C, RES) (DLF_C3PW_RES_OFF(RP, TP, C) + ((RES) ? (TP) * DLF_C3PW_RES_STRIDE(C) : 0))
+#define DLF_C3PW_LDS_BYTES(RP, TP, C, RES) (DLF_C3PW_BIAS_OFF(RP, TP, C, RES) + DLF_C3PW_WAVES(C) * 64 * 4)
 struct DlfC3PwArgs {
     const void* in;       // [batch][h][w][c] fp16
     const void* res;      // residual operand [batch][h][w][cout] fp16, or null
@@ -318,7 +318,7 @@ struct DlfC3PwArgs {
     int32_t th, tw, tp;   // tile of output pixels: th <= 8, tw <= 16, tp = th * tw <= 128
     int32_t rw, rp;       // its input region: tw + 2 columns, (th + 2) * (tw + 2) pixels
     int32_t tiles_y, tiles_x, ntiles;     // ntiles = batch * tiles_y * tiles_x
-    int32_t nsl;          // slices of the second layer's channels: ceil(ncb2 / 16)
+    int32_t nsl;          // slices of the second layer's channels: ceil(ncb2 / (2 * waves))
 };
 
 struct DlfGapArgs {

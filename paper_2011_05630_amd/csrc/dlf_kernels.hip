@@ -3068,15 +3068,19 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
 //      buffer, the residual is added to the rounded sum (fp16 + fp16, as in the other kernels),
 //      activation, and a pixel's 2 x 64 bytes go to memory in adjacent instructions.
 template <int FP, int C>
-__global__ __launch_bounds__(DLF_C3PW_WAVES * 64, 1) void k_c3pw(const DlfC3PwArgs a)
+__global__ __launch_bounds__(DLF_C3PW_WAVES(C) * 64, C == 64 ? 2 : 1) void k_c3pw(const DlfC3PwArgs a)
 {
     constexpr int D = 9;
     constexpr int ROW = 32 + 8;
     static_assert(FP == 2 || FP == 4, "32-pixel blocks of a tile");
-    static_assert(C == 128 || C == 256, "channels of the first layer");
+    static_assert(C == 64 || C == 128 || C == 256, "channels of the first layer");
+    constexpr int W = DLF_C3PW_WAVES(C);
+    constexpr int PP = C / 8;                                // 16-byte parts per pixel: 8, 16 or 32
+    constexpr int RES_STRIDE = DLF_C3PW_RES_STRIDE(C);
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
-    constexpr int pp_shift = C == 128 ? 4 : 5;               // 16-byte parts per pixel: 16 or 32
+    constexpr int pp_shift = C == 64 ? 3 : (C == 128 ? 4 : 5);
+    constexpr int PERM = PP < 16 ? PP - 1 : 15;              // the permutation stays inside a pixel
     constexpr int cs = C + 8;
     const int per8 = blockIdx.x >> 3;
     const int sl = per8 % a.nsl, tile = (per8 / a.nsl) * 8 + (blockIdx.x & 7);
@@ -3100,7 +3104,7 @@ __global__ __launch_bounds__(DLF_C3PW_WAVES * 64, 1) void k_c3pw(const DlfC3PwAr
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) half_t*)lds;
     const int ni = ((a.rp << pp_shift) + 63) >> 6;
 #pragma unroll 1
-    for (int i = wave; i < ni; i += DLF_C3PW_WAVES) {
+    for (int i = wave; i < ni; i += W) {
         const int idx = i * 64 + lane;
         const int hp = idx >> pp_shift, pos = idx & ((1 << pp_shift) - 1);
         unsigned off = (unsigned)DLF_OOB;
@@ -3108,7 +3112,7 @@ __global__ __launch_bounds__(DLF_C3PW_WAVES * 64, 1) void k_c3pw(const DlfC3PwAr
             const int ry = div_by(hp, rw_m), rx = hp - ry * a.rw;
             const int gy = oy0 - 1 + ry, gx = ox0 - 1 + rx;
             if (gy >= 0 && gy < a.h && gx >= 0 && gx < a.w_)
-                off = (unsigned)(((n * a.h + gy) * a.w_ + gx) * C + ((pos ^ ((ry * a.tw + rx) & 15)) << 3)) * 2u;
+                off = (unsigned)(((n * a.h + gy) * a.w_ + gx) * C + ((pos ^ ((ry * a.tw + rx) & PERM)) << 3)) * 2u;
         }
         asm volatile("s_mov_b32 m0, %2\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(off), "s"(rin),
                      "s"(lds0 + (unsigned)i * 1024u)
@@ -3120,22 +3124,24 @@ __global__ __launch_bounds__(DLF_C3PW_WAVES * 64, 1) void k_c3pw(const DlfC3PwAr
     // the residual operand of pixels first, first + every, ..: one load per pixel
     auto request_res = [&](int first, int every) __attribute__((always_inline)) {
         const i32x4 rres = make_rsrc(a.res, a.res_bytes);
-        const int ch = sl * (2 * DLF_C3PW_WAVES * 32) + lane * 8;
+        const int ch = sl * (2 * W * 32) + lane * 8;
 #pragma unroll 1
         for (int p = first; p < a.tp; p += every) {
             const int row = div_by(p, tw_m), colp = p - row * a.tw;
             const int oy = oy0 + row, ox = ox0 + colp;
             unsigned off = (unsigned)DLF_OOB;
             if (oy < a.h && ox < a.w_ && ch < a.cout) off = (unsigned)(((n * a.h + oy) * a.w_ + ox) * a.cout + ch) * 2u;
-            asm volatile("s_mov_b32 m0, %2\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(off), "s"(rres),
-                         "s"(lds0 + (unsigned)(res_off + p * DLF_C3PW_RES_STRIDE))
-                         : "memory", "m0");
+            // (an item of four waves has 256 channels: the upper lanes take no part and write nothing)
+            if (W == 8 || lane < W * 8)
+                asm volatile("s_mov_b32 m0, %2\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(off), "s"(rres),
+                             "s"(lds0 + (unsigned)(res_off + p * RES_STRIDE))
+                             : "memory", "m0");
         }
     };
-    if (ncb1 == DLF_C3PW_WAVES && has_res) request_res(wave, DLF_C3PW_WAVES);
+    if (ncb1 == W && has_res) request_res(wave, W);
 
     // the second layer's weights of this wave: both channel blocks, all of K
-    const int cb0 = (sl * DLF_C3PW_WAVES + wave) * 2;
+    const int cb0 = (sl * W + wave) * 2;
     const bool live = cb0 < a.ncb2;                          // uniform
     const i32x4 rw2 = make_rsrc(a.w2, 0xffffffffu);
     h8 a2[2][nsteps2];
@@ -3178,7 +3184,7 @@ __global__ __launch_bounds__(DLF_C3PW_WAVES * 64, 1) void k_c3pw(const DlfC3PwAr
             for (int t = 0; t < 9; ++t) {
                 const int ry = py + t / 3, rx = pxx + t % 3;
                 bt[t][p] = (ry * a.rw + rx) * C * 2;
-                ft[t][p] = (((ry * a.tw + rx) & 15) ^ lhi) << 4;
+                ft[t][p] = (((ry * a.tw + rx) & PERM) ^ lhi) << 4;
             }
         }
 #pragma unroll
@@ -3210,7 +3216,7 @@ __global__ __launch_bounds__(DLF_C3PW_WAVES * 64, 1) void k_c3pw(const DlfC3PwAr
     } else {
         wait_vmcnt<0>();
         asm volatile("s_barrier" ::: "memory");              // the region has landed
-        if (has_res) request_res(wave - ncb1, DLF_C3PW_WAVES - ncb1);
+        if (has_res) request_res(wave - ncb1, W - ncb1);
         if (live) load_a2();
     }
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // nobody reads the region any more
@@ -3296,7 +3302,7 @@ __global__ __launch_bounds__(DLF_C3PW_WAVES * 64, 1) void k_c3pw(const DlfC3PwAr
                 if (inside && cc + j * 32 < a.cout) {
                     u4v v = val[j][i];
                     if (has_res) {
-                        const u4v rv = *(const u4v*)(resl + pc * DLF_C3PW_RES_STRIDE + j * (LPX * 16));
+                        const u4v rv = *(const u4v*)(resl + pc * RES_STRIDE + j * (LPX * 16));
                         v.x = pk_add(v.x, rv.x);
                         v.y = pk_add(v.y, rv.y);
                         v.z = pk_add(v.z, rv.z);
@@ -3598,6 +3604,8 @@ extern "C" int dlf_kernels_init(void)
         if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_c3pw<4, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_c3pw<2, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_c3pw<4, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_c3pw<2, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_c3pw<4, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e2 != hipSuccess) return (int)e2;
         for (int v = 0; v < 6; ++v) {
             hipError_t e = hipFuncSetAttribute((const void*)c3s_kernel(v < 4 ? 9 : 1, (v >> 1) == 1 ? 2 : 1, (v & 1) + 1),
@@ -3787,7 +3795,9 @@ extern "C" int dlf_launch_c3pw(const DlfC3PwArgs* a, int grid, int lds_bytes, vo
 {
     // what the kernel's indexing assumes
     if (grid <= 0 || (grid & 7) != 0 || a->in_bytes >= 0x80000000u || a->res_bytes >= 0x80000000u) return (int)hipErrorInvalidValue;
-    if ((a->c != 128 && a->c != 256) || (a->cout & 7) != 0 || a->ncb2 != (a->cout + 31) / 32 || a->nsl != (a->ncb2 + 15) / 16)
+    if (a->c != 64 && a->c != 128 && a->c != 256) return (int)hipErrorInvalidValue;
+    const int waves = DLF_C3PW_WAVES(a->c);
+    if ((a->cout & 7) != 0 || a->ncb2 != (a->cout + 31) / 32 || a->nsl != (a->ncb2 + 2 * waves - 1) / (2 * waves))
         return (int)hipErrorInvalidValue;
     if (a->th < 1 || a->th > 8 || a->tw < 1 || a->tw > 16 || a->tp != a->th * a->tw || a->tp > 128 || a->rw != a->tw + 2 ||
         a->rp != (a->th + 2) * (a->tw + 2) || a->tiles_y != (a->h + a->th - 1) / a->th ||
@@ -3796,9 +3806,10 @@ extern "C" int dlf_launch_c3pw(const DlfC3PwArgs* a, int grid, int lds_bytes, vo
         return (int)hipErrorInvalidValue;
     if (lds_bytes != (int)DLF_C3PW_LDS_BYTES(a->rp, a->tp, a->c, a->res != nullptr) || lds_bytes > 160 * 1024)
         return (int)hipErrorInvalidValue;
-    void (*const kern)(DlfC3PwArgs) = a->c == 128 ? (a->tp > 64 ? k_c3pw<4, 128> : k_c3pw<2, 128>)
-                                                  : (a->tp > 64 ? k_c3pw<4, 256> : k_c3pw<2, 256>);
-    launch(kern, dim3(grid), dim3(DLF_C3PW_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
+    void (*const kern)(DlfC3PwArgs) = a->c == 64    ? (a->tp > 64 ? k_c3pw<4, 64> : k_c3pw<2, 64>)
+                                      : a->c == 128 ? (a->tp > 64 ? k_c3pw<4, 128> : k_c3pw<2, 128>)
+                                                    : (a->tp > 64 ? k_c3pw<4, 256> : k_c3pw<2, 256>);
+    launch(kern, dim3(grid), dim3(waves * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
     return (int)hipGetLastError();
 }
 

@@ -703,7 +703,11 @@ C3PW_CASES = [(128, 512, 28, 28, 2, 7, 14, "relu", "relu", True), (128, 512, 28,
               (256, 1024, 14, 14, 2, 7, 7, "relu", "relu", True), (128, 512, 13, 17, 2, 8, 16, "relu6", "none", True),
               (128, 200, 9, 11, 3, 5, 6, "relu", "relu6", False), (256, 1024, 14, 14, 1, 7, 14, "relu", "relu", False),
               (128, 96, 5, 40, 1, 1, 16, "none", "relu", True), (256, 72, 19, 3, 2, 8, 1, "relu", "relu", False),
-              (128, 1024, 7, 7, 2, 0, 0, "relu", "relu", True), (256, 520, 6, 6, 3, 3, 6, "relu", "relu", True)]
+              (128, 1024, 7, 7, 2, 0, 0, "relu", "relu", True), (256, 520, 6, 6, 3, 3, 6, "relu", "relu", True),
+              # 64 channels: workgroups of four waves, two to a CU; 256 and more output channels (two slices), a ragged block
+              (64, 256, 56, 56, 1, 7, 14, "relu", "relu", True), (64, 256, 28, 28, 2, 0, 0, "relu", "relu", True),
+              (64, 256, 13, 17, 2, 7, 8, "relu6", "none", True), (64, 520, 9, 11, 3, 5, 6, "relu", "relu", True),
+              (64, 72, 5, 40, 1, 1, 16, "none", "relu", False), (64, 256, 19, 3, 2, 8, 1, "relu", "relu6", True)]
 
 
 @pytest.mark.parametrize("c,cout,h,w,batch,th,tw,act1,act2,residual", C3PW_CASES)
