@@ -187,6 +187,8 @@ def group_accounting(net, batch, session):
         elif cfg["kind"] == 10:
             kname = "k_c3s<%d,%d,%d>" % (1 if cfg["variant"] >= 8 else 9, net["layers"][f]["stride"],
                                          2 if info["tile_h"] * info["tile_w"] > 32 else 1)
+        elif cfg["kind"] == 12:
+            kname = "k_bneck<%d>" % cfg["variant"]
         elif cfg["kind"] == 11:
             kname = "k_c3pw<%d,%d>" % (cfg["variant"], net["layers"][f]["cin"])
         elif cfg["kind"] == 9:

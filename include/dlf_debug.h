@@ -56,7 +56,9 @@ void dlf_debug_depthwise_tile(int32_t wx, int32_t rw);
  * for maps of many channels and few pixels (cin 256, 512, 1024 or 2048, no pool; th > 0 then
  * fixes the number of waves that share a channel block's K: 1, 2 or 4; tw is not used), 6 = the
  * kernel for a 3x3 layer (128 or 256 channels in and out) with a 1x1 layer behind it as one group
- * (th, tw > 0 then fix the tile the map is cut into equal parts for: at most 8 x 16 pixels); a shape
+ * (th, tw > 0 then fix the tile the map is cut into equal parts for: at most 8 x 16 pixels), 7 = the
+ * kernel for a whole bottleneck block (1x1 to 64 channels, 3x3, 1x1; th, tw as for 6, at most 64
+ * pixels); a shape
  * that cannot be laid out falls back to the fused-group kernel.  Mode 2 keeps such a pair of layers
  * on the fused-group kernel as well.
  * Process-wide, not thread-safe. */

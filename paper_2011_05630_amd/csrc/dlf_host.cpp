@@ -154,7 +154,7 @@ dlf_status pack_and_upload(Layer& L)
 // Fusion groups
 // ------------------------------------------------------------------------------------------
 
-enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3, GK_C3 = 4, GK_DW = 5, GK_DWPW = 6, GK_DWT = 7, GK_PW2 = 8, GK_DWS = 9, GK_C3S = 10, GK_C3PW = 11 };
+enum { GK_GROUP = 0, GK_FC = 1, GK_GAP = 2, GK_PW = 3, GK_C3 = 4, GK_DW = 5, GK_DWPW = 6, GK_DWT = 7, GK_PW2 = 8, GK_DWS = 9, GK_C3S = 10, GK_C3PW = 11, GK_BNECK = 12 };
 
 struct TileCfg {
     int th, tw;      // tile of the group's final output tensor
@@ -184,7 +184,7 @@ struct GroupPlan {
     DlfDwPwArgs dp;
     DlfDwtArgs dt;
     DlfDwsArgs ds;
-    DlfC3sArgs cs; DlfC3PwArgs cp;
+    DlfC3sArgs cs; DlfC3PwArgs cp; DlfBnArgs bn;
 };
 
 const int VAR_FC[DLF_NUM_VARIANTS] = {2, 1, 1, 1};
@@ -312,6 +312,9 @@ const int64_t C_C3PW_STEP = 125;
 const int64_t C_C3PW_MID = 600;
 const int64_t C_C3PW_SECOND = 1000;
 const int64_t C3PW_STORE_BYTES_PER_CYCLE = 2300;
+const int64_t C_BN_ITEM = 14000;              // bottleneck kernel: per item, per tile pixel, per 16 input channels beyond 256
+const int64_t C_BN_PIXEL = 245;
+const int64_t C_BN_CHANNEL = 150;
 const int64_t C3PW_OVERLAP_PCT = 60;         // two workgroups per CU: what a further round of items adds, in per cent of an item
 
 struct StageSpec {   // one stage, before tiling
@@ -1311,6 +1314,87 @@ bool c3pw_choose(const Layer& A, const Layer& P, int batch, int budget, int max_
     return found;
 }
 
+// ---- a whole bottleneck block (1x1 -> 3x3 -> 1x1, identity shortcut or none) as one group ----
+
+bool bneck_eligible(const dlf_net_s& net, const std::vector<StageSpec>& specs, int batch)
+{
+    if (specs.size() != 3) return false;
+    for (const StageSpec& sp : specs)
+        if (sp.kind != DLF_ST_CONV || sp.pool2) return false;
+    const Layer& A = net.L[specs[0].layer];
+    const Layer& B = net.L[specs[1].layer];
+    const Layer& P = net.L[specs[2].layer];
+    const dlf_layer_desc& a = A.d;
+    const dlf_layer_desc& b = B.d;
+    const dlf_layer_desc& p = P.d;
+    if (A.im2col || A.rowfold || B.im2col || B.rowfold || P.im2col || P.rowfold) return false;
+    if (a.kh != 1 || a.kw != 1 || a.stride != 1 || a.pad != 0 || a.residual_from >= 0) return false;
+    if ((a.cin != 128 && a.cin != 256 && a.cin != 512) || a.cout != 64) return false;
+    if (b.kh != 3 || b.kw != 3 || b.stride != 1 || b.pad != 1 || b.cin != 64 || b.cout != 64 || b.residual_from >= 0) return false;
+    if (p.kh != 1 || p.kw != 1 || p.stride != 1 || p.pad != 0 || p.cin != 64 || (p.cout % 8) != 0) return false;
+    // the shortcut, if any, is the block's own input
+    if (p.residual_from >= 0 && (p.residual_from != A.src || p.cout != a.cin)) return false;
+    if ((int64_t)batch * A.in_h * A.in_w * a.cin * 2 >= (int64_t)1 << 31) return false;
+    if ((int64_t)batch * P.out_h * P.out_w * p.cout * 2 >= (int64_t)1 << 31) return false;
+    return true;
+}
+
+// One configuration: the map cut into rows x cols equal tiles of at most 64 pixels.
+bool bneck_build(const Layer& A, const Layer& B, const Layer& P, int batch, int rows, int cols, int max_lds, DlfBnArgs& bn)
+{
+    memset(&bn, 0, sizeof bn);
+    if (rows <= 0 || cols <= 0) return false;
+    bn.th = ceil_div(A.out_h, rows);
+    bn.tw = ceil_div(A.out_w, cols);
+    if (bn.th > 8 || bn.tw > 16 || bn.th * bn.tw > 64) return false;
+    bn.tp = bn.th * bn.tw;
+    bn.rw = bn.tw + 2;
+    bn.rp = (bn.th + 2) * bn.rw;
+    if ((int)DLF_BN_LDS_BYTES(bn.rp, bn.tp, A.d.cin) > std::min(max_lds, 80 * 1024)) return false;   // two to a CU
+    bn.w0 = A.d_w; bn.b0 = A.d_bias; bn.w1 = B.d_w; bn.b1 = B.d_bias; bn.w2 = P.d_w; bn.b2 = P.d_bias;
+    bn.in_bytes = (uint32_t)((int64_t)batch * A.in_h * A.in_w * A.in_c * 2);
+    bn.batch = batch; bn.h = A.in_h; bn.w_ = A.in_w; bn.cin0 = A.d.cin; bn.cout = P.d.cout;
+    bn.ncb2 = P.ncb; bn.act0 = A.d.act; bn.act1 = B.d.act; bn.act2 = P.d.act;
+    bn.identity = P.d.residual_from >= 0 ? 1 : 0;
+    bn.tiles_y = ceil_div(A.out_h, bn.th); bn.tiles_x = ceil_div(A.out_w, bn.tw);
+    bn.ntiles = batch * bn.tiles_y * bn.tiles_x;
+    bn.nsl = ceil_div(P.ncb, 2 * DLF_BN_WAVES);
+    return true;
+}
+
+// An item is a chain of waits (region, first layer with one accumulator per wave, the 3x3 ring, the
+// transposes of the last layer) that two workgroups per CU do not hide: C_BN_ITEM + C_BN_PIXEL per
+// tile pixel, half of it where the chip is not full; the items of a CU's two places follow one
+// another.  Fitted to seven forced tile shapes of ResNet-50's 56 x 56 block at batch 32 (49 - 72 us)
+// and two at batch 1 (8.3, 10.1 us): modelled / measured 0.97 - 1.05.
+uint64_t bneck_cost_ps(const Layer& A, const Layer& B, const Layer& P, int batch, int budget, const DlfBnArgs& bn)
+{
+    const int64_t nitems = (int64_t)bn.ntiles * bn.nsl;
+    const int64_t slots = (int64_t)budget * 2;
+    int64_t item = C_BN_ITEM + C_BN_PIXEL * bn.tp + (bn.cin0 - 256) * C_BN_CHANNEL / 16;
+    if (nitems <= budget) item /= 2;
+    const int64_t compute = nitems <= slots ? item : item * nitems / slots;
+    const int64_t m = (int64_t)batch * P.out_h * P.out_w;
+    const int64_t bytes = (int64_t)bn.ntiles * bn.rp * bn.cin0 * 2 + m * bn.cout * 2 +
+                          ((int64_t)A.ncb * A.nsteps + (int64_t)B.ncb * B.nsteps + (int64_t)P.ncb * P.nsteps) * 1024;
+    const int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
+    return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
+}
+
+bool bneck_choose(const Layer& A, const Layer& B, const Layer& P, int batch, int budget, int max_lds, DlfBnArgs& best, uint64_t& cost)
+{
+    bool found = false;
+    const int r0 = ceil_div(A.out_h, 8), c0 = ceil_div(A.out_w, 16);
+    for (int rows = r0; rows <= r0 + 8; ++rows)
+        for (int cols = c0; cols <= c0 + 8; ++cols) {
+            DlfBnArgs bn;
+            if (!bneck_build(A, B, P, batch, rows, cols, max_lds, bn)) continue;
+            const uint64_t c = bneck_cost_ps(A, B, P, batch, budget, bn);
+            if (!found || c < cost) { found = true; cost = c; best = bn; }
+        }
+    return found;
+}
+
 // ---- depthwise + 1x1 kernel for maps of many channels and few pixels ----
 
 bool dws_eligible(const dlf_net_s& net, int first, int last, int batch)
@@ -1623,6 +1707,33 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
             g.th = L0.d.stride == 1 ? DLF_DW_ROWS1 : DLF_DW_ROWS2;
             g.tw = 64;
             g.lds_bytes = 0;
+            return DLF_OK;
+        }
+    }
+    // a whole bottleneck block: shape DLF_C3_SHAPES + 2 of the testing hook (its th x tw then fix the tile)
+    if (first + 2 == last && c3f.mode != 2 && (force.th <= 0 || c3f.mode == 1) &&
+        (c3f.shape < 0 || c3f.shape == DLF_C3_SHAPES + 2) && bneck_eligible(net, specs, batch)) {
+        const Layer& Bm = net.L[first + 1];
+        const Layer& P = net.L[last];
+        DlfBnArgs bn;
+        uint64_t bc = 0;
+        bool have;
+        if (c3f.shape == DLF_C3_SHAPES + 2 && c3f.th > 0 && c3f.tw > 0) {
+            have = bneck_build(L0, Bm, P, batch, ceil_div(L0.out_h, c3f.th), ceil_div(L0.out_w, c3f.tw), max_lds, bn);
+            if (have) bc = bneck_cost_ps(L0, Bm, P, batch, budget, bn);
+        } else {
+            have = bneck_choose(L0, Bm, P, batch, budget, max_lds, bn, bc);
+        }
+        if (have && (!tiled || c3f.mode == 1 || bc < cost)) {
+            g.bn = bn;
+            g.kind = GK_BNECK;
+            g.cost = bc;
+            g.variant = bn.cin0;
+            g.occ = 2;
+            g.grid = ceil_div(bn.ntiles, 8) * 8 * bn.nsl;
+            g.th = bn.th; g.tw = bn.tw;
+            g.lds_bytes = (int)DLF_BN_LDS_BYTES(bn.rp, bn.tp, bn.cin0);
+            // (the shortcut is the group's own input: no second operand)
             return DLF_OK;
         }
     }
@@ -2346,6 +2457,10 @@ static dlf_status launch_one(const dlf_plan_s* plan, const GroupPlan& G, const v
             cp.res = res;
         }
         e = dlf_launch_c3pw(&cp, G.grid, G.lds_bytes, stream);
+    } else if (G.kind == GK_BNECK) {
+        DlfBnArgs bn = G.bn;
+        bn.in = in; bn.out = out;
+        e = dlf_launch_bneck(&bn, G.grid, G.lds_bytes, stream);
     } else if (G.kind == GK_DWS) {
         DlfDwsArgs ds = G.ds;
         ds.in = in; ds.out = out;

@@ -321,6 +321,40 @@ struct DlfC3PwArgs {
     int32_t nsl;          // slices of the second layer's channels: ceil(ncb2 / (2 * waves))
 };
 
+// A whole bottleneck block as one group: 1x1 (cin0 -> 64), 3x3 (64 -> 64, stride 1, pad 1), 1x1 (64 ->
+// cout), the block's input added to the last layer's result where the block has an identity
+// shortcut (then cout = cin0).  One workgroup of four waves per work item = (tile of up to 64 output
+// pixels, slice of 8 channel blocks of the last layer), two workgroups to a CU.  LDS: the input
+// region with all cin0 channels, the first layer's result on the region, the second layer's on the
+// tile, the waves' transpose buffers, the last layer's bias.
+#define DLF_BN_WAVES 4
+#define DLF_BN_IN_BYTES(RP, CIN0) ((((RP) * (CIN0) * 2 + 1023) / 1024) * 1024)
+#define DLF_BN_MA_BYTES(RP) ((((RP) * 128 + 1023) / 1024) * 1024)
+#define DLF_BN_MB_BYTES(TP) ((((TP) * (64 + 8) * 2 + 63) / 64) * 64)
+#define DLF_BN_EPI_BYTES (DLF_BN_WAVES * 32 * (32 + 8) * 2)
+#define DLF_BN_MA_OFF(RP, CIN0) DLF_BN_IN_BYTES(RP, CIN0)
+#define DLF_BN_MB_OFF(RP, CIN0) (DLF_BN_MA_OFF(RP, CIN0) + DLF_BN_MA_BYTES(RP))
+#define DLF_BN_TB_OFF(RP, TP, CIN0) (DLF_BN_MB_OFF(RP, CIN0) + DLF_BN_MB_BYTES(TP))
+#define DLF_BN_BIAS_OFF(RP, TP, CIN0) (DLF_BN_TB_OFF(RP, TP, CIN0) + DLF_BN_EPI_BYTES)
+#define DLF_BN_LDS_BYTES(RP, TP, CIN0) (DLF_BN_BIAS_OFF(RP, TP, CIN0) + DLF_BN_WAVES * 64 * 4)
+struct DlfBnArgs {
+    const void* in;       // [batch][h][w][cin0] fp16: the block's input (and its residual operand)
+    void* out;            // [batch][h][w][cout] fp16
+    const void* w0;       // 1x1 weights cin0 -> 64, packed fragments
+    const float* b0;
+    const void* w1;       // 3x3 weights 64 -> 64, packed fragments (K step = 32-channel chunk, tap, half)
+    const float* b1;
+    const void* w2;       // 1x1 weights 64 -> cout, packed fragments
+    const float* b2;      // padded to ncb2 * 32
+    uint32_t in_bytes;    // size of the input tensor (below 2 GiB)
+    int32_t batch, h, w_, cin0, cout, ncb2, act0, act1, act2;
+    int32_t identity;     // 1: the input is added to the last layer's result (cout == cin0)
+    int32_t th, tw, tp;   // tile of output pixels: th <= 8, tw <= 16, tp = th * tw <= 64
+    int32_t rw, rp;       // its input region: tw + 2 columns, (th + 2) * (tw + 2) pixels
+    int32_t tiles_y, tiles_x, ntiles;     // ntiles = batch * tiles_y * tiles_x
+    int32_t nsl;          // slices of the last layer's channels: ceil(ncb2 / 8)
+};
+
 struct DlfGapArgs {
     const void* x;        // [batch][hw][c]
     void* y;              // [batch][c]
@@ -345,6 +379,7 @@ int dlf_launch_dwt(const DlfDwtArgs* a, int grid, int lds_bytes, void* stream);
 int dlf_launch_dws(const DlfDwsArgs* a, int grid, int lds_bytes, void* stream);
 int dlf_launch_c3s(const DlfC3sArgs* a, int grid, int lds_bytes, void* stream);
 int dlf_launch_c3pw(const DlfC3PwArgs* a, int grid, int lds_bytes, void* stream);
+int dlf_launch_bneck(const DlfBnArgs* a, int grid, int lds_bytes, void* stream);
 int dlf_kernels_init(void);
 // Attaches a start / stop event pair (hipEvent_t, either may be null) to this thread's next launch.
 void dlf_next_launch_events(void* start, void* stop);

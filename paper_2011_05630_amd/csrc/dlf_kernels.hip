@@ -3319,6 +3319,285 @@ __global__ __launch_bounds__(DLF_C3PW_WAVES(C) * 64, C == 64 ? 2 : 1) void k_c3p
     }
 }
 
+// A bottleneck block as one group: 1x1 (cin0 -> 64) + 3x3 (64 -> 64, stride 1, pad 1) + 1x1 (64 -> cout),
+// each with bias and activation, and the block's input added before the last activation where the
+// block has an identity shortcut (Sec. III-B: neither intermediate tensor leaves the chip, and the
+// residual operand is the input region that is in LDS already).  Built from the parts of k_c3pw's
+// 64-channel form: one workgroup of four waves per work item = (tile of up to 64 output pixels,
+// slice of 8 channel blocks of the last layer), two workgroups to a CU, more items than places, so
+// that the load, multiply and store phases of neighbouring items overlap.
+//   1. The tile's input region, all cin0 channels, global -> LDS by direct loads (range check as
+//      padding, parts permuted by (r * tw + c) % 16).
+//   2. First layer on every pixel of the region (the halo is computed again by the neighbouring
+//      tiles): wave w takes channel block w % 2 and every second 32-pixel block, all of K with the
+//      weight fragments in registers; bias, activation, zero for pixels outside the map (they are
+//      the second layer's padding), fp16 into a second region [pixel][64] with the permutation the
+//      3x3 loop reads by.
+//   3. Second layer: waves 0 and 1 one channel block x the tile's two pixel blocks each, K through a
+//      register ring of 9 steps, as in k_c3pw; result to an LDS tile [pixel][64 + 8].
+//   4. Last layer: every wave two channel blocks, all of K in registers, 32 pixels at a time through
+//      the wave's transpose buffer; + the input's centre pixels from the first region (fp16 + fp16),
+//      activation, a pixel's 2 x 64 bytes stored by adjacent instructions.
+template <int CIN0>
+__global__ __launch_bounds__(DLF_BN_WAVES * 64, 2) void k_bneck(const DlfBnArgs a)
+{
+    constexpr int D = 9, ROW = 32 + 8, C = 64, W = DLF_BN_WAVES, FP = 2, cs = C + 8;
+    static_assert(CIN0 == 128 || CIN0 == 256 || CIN0 == 512, "channels of the block's input");
+    constexpr int pp0 = CIN0 == 128 ? 4 : (CIN0 == 256 ? 5 : 6);       // log2 of the input's 16-byte parts per pixel
+    constexpr int NS0 = CIN0 / 16;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    // Workgroup i runs on XCD i % 8: an XCD takes a contiguous eighth of the tiles (whole rows of
+    // tiles, whole images), in order, so that the halo a tile shares with its neighbours is in that
+    // XCD's L2 when the neighbour asks for it
+    const int per8 = blockIdx.x >> 3;
+    const int sl = per8 % a.nsl, tile = (blockIdx.x & 7) * ((a.ntiles + 7) >> 3) + per8 / a.nsl;
+    if (tile >= a.ntiles) return;
+    int r_ = tile;
+    const int tx = r_ % a.tiles_x;
+    r_ /= a.tiles_x;
+    const int ty = r_ % a.tiles_y, n = r_ / a.tiles_y;
+    const int oy0 = ty * a.th, ox0 = tx * a.tw;
+    char* const r0 = (char*)lds;
+    char* const ma = r0 + DLF_BN_MA_OFF(a.rp, CIN0);
+    half_t* const mid = (half_t*)(r0 + DLF_BN_MB_OFF(a.rp, CIN0));
+    half_t* const tb = (half_t*)(r0 + DLF_BN_TB_OFF(a.rp, a.tp, CIN0)) + wave * (32 * ROW);
+    float* const bl = (float*)(r0 + DLF_BN_BIAS_OFF(a.rp, a.tp, CIN0)) + wave * 64;
+    half_t* outp = (half_t*)a.out;
+    const unsigned lo0 = act_lo(a.act0), hi0 = act_hi(a.act0);
+    const unsigned lo1 = act_lo(a.act1), hi1 = act_hi(a.act1);
+    const unsigned lo2 = act_lo(a.act2), hi2 = act_hi(a.act2);
+    const unsigned tw_m = div_magic(a.tw), rw_m = div_magic(a.rw);
+    const int lane16 = lane * 16;
+
+    // ---- step 1: the region ----
+    const i32x4 rin = make_rsrc(a.in, a.in_bytes);
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) half_t*)lds;
+    const int ni = ((a.rp << pp0) + 63) >> 6;
+#pragma unroll 1
+    for (int i = wave; i < ni; i += W) {
+        const int idx = i * 64 + lane;
+        const int hp = idx >> pp0, pos = idx & ((1 << pp0) - 1);
+        unsigned off = (unsigned)DLF_OOB;
+        if (hp < a.rp) {
+            const int ry = div_by(hp, rw_m), rx = hp - ry * a.rw;
+            const int gy = oy0 - 1 + ry, gx = ox0 - 1 + rx;
+            if (gy >= 0 && gy < a.h && gx >= 0 && gx < a.w_)
+                off = (unsigned)(((n * a.h + gy) * a.w_ + gx) * CIN0 + ((pos ^ ((ry * a.tw + rx) & 15)) << 3)) * 2u;
+        }
+        asm volatile("s_mov_b32 m0, %2\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(off), "s"(rin),
+                     "s"(lds0 + (unsigned)i * 1024u)
+                     : "memory", "m0");
+    }
+    // the first layer's weights of this wave's channel block, all of K; the last layer's bias to LDS
+    const int cb_a = wave & 1;
+    h8 a0[NS0];
+    {
+        const i32x4 rw0 = make_rsrc(a.w0, 0xffffffffu);
+        const unsigned wo0 = (unsigned)(cb_a * NS0 * 1024);
+#pragma unroll
+        for (int k = 0; k < NS0; ++k) a0[k] = wfrag(rw0, lane16, wo0 + (unsigned)k * 1024u);
+    }
+    f4v bias0[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) bias0[q] = *(const f4v*)(a.b0 + cb_a * 32 + q * 8 + lhi * 4);
+    const int cb0 = (sl * W + wave) * 2;
+    const bool live = cb0 < a.ncb2;                          // uniform
+    bl[lane] = a.b2[min(cb0 * 32 + lane, a.ncb2 * 32 - 1)];
+    // the last layer's weights of this wave (both channel blocks, all of K) and, on the two waves of
+    // the second layer, the first turn of its ring: everything is requested before the first wait
+    constexpr int nsteps1 = 2 * 18, nsteps2 = C / 16;
+    h8 a2[2][nsteps2];
+    {
+        const i32x4 rw2 = make_rsrc(a.w2, 0xffffffffu);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const unsigned wo2 = (unsigned)__builtin_amdgcn_readfirstlane(min(cb0 + j, a.ncb2 - 1) * nsteps2 * 1024);
+#pragma unroll
+            for (int k = 0; k < nsteps2; ++k) a2[j][k] = wfrag(rw2, lane16, wo2 + (unsigned)k * 1024u);
+        }
+    }
+    const i32x4 rw1 = make_rsrc(a.w1, 0xffffffffu);
+    const unsigned wo = (unsigned)__builtin_amdgcn_readfirstlane((wave & 1) * nsteps1 * 1024);
+    int pf_ks = 0;
+    h8 ar[D];
+    auto request = [&](int slot) __attribute__((always_inline)) {
+        ar[slot] = wfrag(rw1, lane16, wo + (unsigned)min(pf_ks, nsteps1 - 1) * 1024u);   // past the end: re-read, never used
+        ++pf_ks;
+    };
+    if (wave < 2) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) request(d);
+    }
+    wait_vmcnt<0>();
+    asm volatile("s_barrier" ::: "memory");                  // the region has landed
+
+    // ---- step 2: the first layer, on the region ----
+    {
+        const int npb = (a.rp + 31) >> 5;
+#pragma unroll 1
+        for (int pb = wave >> 1; pb < npb; pb += W / 2) {
+            const int px_ = pb * 32 + l32, pc = min(px_, a.rp - 1);
+            const int ry = div_by(pc, rw_m), rx = pc - ry * a.rw;
+            const int perm = (ry * a.tw + rx) & 15;
+            const char* const src = r0 + pc * (CIN0 * 2);
+            f16v acc;
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[q] = bias0[q >> 2][q & 3];
+#pragma unroll
+            for (int k = 0; k < NS0; ++k)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0[k], *(const h8*)(src + (((2 * k + lhi) ^ perm) << 4)), acc, 0, 0, 0);
+            const int gy = oy0 - 1 + ry, gx = ox0 - 1 + rx;
+            const bool inside = gy >= 0 && gy < a.h && gx >= 0 && gx < a.w_;
+            char* const dst = ma + pc * (C * 2) + lhi * 8;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                unsigned u0 = cvt_pk(acc[q * 4 + 0], acc[q * 4 + 1]);
+                unsigned u1 = cvt_pk(acc[q * 4 + 2], acc[q * 4 + 3]);
+                u0 = inside ? pk_min(pk_max(u0, lo0), hi0) : 0u;
+                u1 = inside ? pk_min(pk_max(u1, lo0), hi0) : 0u;
+                const u2v uu = {u0, u1};
+                if (px_ < a.rp) *(u2v*)(dst + (((cb_a * 4 + q) ^ (perm & 7)) << 4)) = uu;
+            }
+        }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // the second region is complete
+
+    // ---- step 3: the second layer ----
+    if (wave < 2) {
+        f4v bias1[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bias1[q] = *(const f4v*)(a.b1 + wave * 32 + q * 8 + lhi * 4);
+        int bt[9][FP], ft[9][FP];
+#pragma unroll
+        for (int p = 0; p < FP; ++p) {
+            const int px_ = min(p * 32 + l32, a.tp - 1);
+            const int py = div_by(px_, tw_m), pxx = px_ - py * a.tw;
+#pragma unroll
+            for (int t = 0; t < 9; ++t) {
+                const int ry = py + t / 3, rx = pxx + t % 3;
+                bt[t][p] = (ry * a.rw + rx) * C * 2;
+                ft[t][p] = (((ry * a.tw + rx) & 7) ^ lhi) << 4;
+            }
+        }
+        f16v acc[FP];
+#pragma unroll
+        for (int p = 0; p < FP; ++p)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[p][q] = bias1[q >> 2][q & 3];
+        const char* const region = ma;
+        h8 bf[2][FP];
+#pragma unroll
+        for (int p = 0; p < FP; ++p) bf[0][p] = *(const h8*)(region + bt[0][p] + ft[0][p]);
+#pragma unroll 1
+        for (int c = 0; c < 2; ++c) {
+            const int q16 = c * 64, q16n = min(c + 1, 1) * 64;
+#pragma unroll
+            for (int j = 0; j < 18; ++j) {
+                const int jn = (j + 1) % 18, tn = jn >> 1;
+                const int qn = (j == 17 ? q16n : q16) + (jn & 1) * 32;
+#pragma unroll
+                for (int p = 0; p < FP; ++p) bf[(j + 1) & 1][p] = *(const h8*)(region + bt[tn][p] + (qn ^ ft[tn][p]));
+#pragma unroll
+                for (int p = 0; p < FP; ++p)
+                    acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[j % D], bf[j & 1][p], acc[p], 0, 0, 0);
+                request(j % D);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < FP; ++p) {
+            const int px_ = p * 32 + l32;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                unsigned u0 = cvt_pk(acc[p][q * 4 + 0], acc[p][q * 4 + 1]);
+                unsigned u1 = cvt_pk(acc[p][q * 4 + 2], acc[p][q * 4 + 3]);
+                u0 = pk_min(pk_max(u0, lo1), hi1);
+                u1 = pk_min(pk_max(u1, lo1), hi1);
+                const u2v uu = {u0, u1};
+                if (px_ < a.tp) *(u2v*)(mid + px_ * cs + wave * 32 + q * 8 + lhi * 4) = uu;
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    }
+    asm volatile("s_barrier" ::: "memory");                  // the tile is complete
+    if (!live) return;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int k = 0; k < nsteps2; ++k) asm volatile("" : "+v"(a2[j][k]));
+
+    // ---- step 4: the last layer ----
+    constexpr int LPX = 4, PPP = 64 / LPX;
+    const int part = lane & (LPX - 1);
+    const int cc = cb0 * 32 + part * 8;
+#pragma unroll 1
+    for (int pb = 0; pb * 32 < a.tp; ++pb) {
+        f16v acc2[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f4v bias = *(const f4v*)(bl + j * 32 + q * 8 + lhi * 4);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc2[j][q * 4 + i] = bias[i];
+            }
+        const half_t* const bsrc = mid + min(pb * 32 + l32, a.tp - 1) * cs + lhi * 8;
+#pragma unroll
+        for (int k = 0; k < nsteps2; ++k) {
+            const h8 b = *(const h8*)(bsrc + k * 16);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc2[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2[j][k], b, acc2[j], 0, 0, 0);
+        }
+        u4v val[2][32 / PPP];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const unsigned u0 = cvt_pk(acc2[j][q * 4 + 0], acc2[j][q * 4 + 1]);
+                const unsigned u1 = cvt_pk(acc2[j][q * 4 + 2], acc2[j][q * 4 + 3]);
+                const u2v uu = {u0, u1};
+                *(u2v*)(tb + l32 * ROW + q * 8 + lhi * 4) = uu;
+            }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int i = 0; i < 32 / PPP; ++i) val[j][i] = *(const u4v*)(tb + (i * PPP + lane / LPX) * ROW + part * 8);
+            __builtin_amdgcn_wave_barrier();
+        }
+#pragma unroll
+        for (int i = 0; i < 32 / PPP; ++i) {
+            const int px_ = pb * 32 + i * PPP + lane / LPX;
+            const int pc = min(px_, a.tp - 1);
+            const int row = div_by(pc, tw_m), colp = pc - row * a.tw;
+            const int oy = oy0 + row, ox = ox0 + colp;
+            const bool inside = px_ < a.tp && oy < a.h && ox < a.w_;
+            half_t* const dst = outp + ((size_t)((n * a.h + oy) * a.w_ + ox) * a.cout + cc);
+            // the same pixel of the input region: one row and one column in
+            const int rpx = (row + 1) * a.rw + colp + 1;
+            const int rperm = ((row + 1) * a.tw + colp + 1) & 15;
+            const char* const rsrc = r0 + rpx * (CIN0 * 2);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                if (inside && cc + j * 32 < a.cout) {
+                    u4v v = val[j][i];
+                    if (a.identity) {
+                        const u4v rv = *(const u4v*)(rsrc + ((((cb0 + j) * 4 + part) ^ rperm) << 4));
+                        v.x = pk_add(v.x, rv.x);
+                        v.y = pk_add(v.y, rv.y);
+                        v.z = pk_add(v.z, rv.z);
+                        v.w = pk_add(v.w, rv.w);
+                    }
+                    v.x = pk_min(pk_max(v.x, lo2), hi2);
+                    v.y = pk_min(pk_max(v.y, lo2), hi2);
+                    v.z = pk_min(pk_max(v.z, lo2), hi2);
+                    v.w = pk_min(pk_max(v.w, lo2), hi2);
+                    *(u4v*)(dst + j * 32) = v;
+                }
+            }
+        }
+    }
+}
+
 extern "C" int dlf_launch_dw(const DlfDwArgs* a, int grid, void* stream);
 
 // Fully connected layer (Eq. 2 with M = batch): y[n][co] = act(bias[co] + sum_k x[n][k] w[co][k]).
@@ -3606,6 +3885,9 @@ extern "C" int dlf_kernels_init(void)
         if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_c3pw<4, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_c3pw<2, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_c3pw<4, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_bneck<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_bneck<256>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_bneck<512>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e2 != hipSuccess) return (int)e2;
         for (int v = 0; v < 6; ++v) {
             hipError_t e = hipFuncSetAttribute((const void*)c3s_kernel(v < 4 ? 9 : 1, (v >> 1) == 1 ? 2 : 1, (v & 1) + 1),
@@ -3810,6 +4092,25 @@ extern "C" int dlf_launch_c3pw(const DlfC3PwArgs* a, int grid, int lds_bytes, vo
                                       : a->c == 128 ? (a->tp > 64 ? k_c3pw<4, 128> : k_c3pw<2, 128>)
                                                     : (a->tp > 64 ? k_c3pw<4, 256> : k_c3pw<2, 256>);
     launch(kern, dim3(grid), dim3(waves * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
+    return (int)hipGetLastError();
+}
+
+extern "C" int dlf_launch_bneck(const DlfBnArgs* a, int grid, int lds_bytes, void* stream)
+{
+    // what the kernel's indexing assumes
+    if (grid <= 0 || (grid & 7) != 0 || a->in_bytes >= 0x80000000u) return (int)hipErrorInvalidValue;
+    if (a->cin0 != 128 && a->cin0 != 256 && a->cin0 != 512) return (int)hipErrorInvalidValue;
+    if ((a->cout & 7) != 0 || a->ncb2 != (a->cout + 31) / 32 || a->nsl != (a->ncb2 + 2 * DLF_BN_WAVES - 1) / (2 * DLF_BN_WAVES) ||
+        (a->identity && a->cout != a->cin0))
+        return (int)hipErrorInvalidValue;
+    if (a->th < 1 || a->th > 8 || a->tw < 1 || a->tw > 16 || a->tp != a->th * a->tw || a->tp > 64 || a->rw != a->tw + 2 ||
+        a->rp != (a->th + 2) * (a->tw + 2) || a->tiles_y != (a->h + a->th - 1) / a->th ||
+        a->tiles_x != (a->w_ + a->tw - 1) / a->tw || a->ntiles != a->batch * a->tiles_y * a->tiles_x ||
+        grid != (a->ntiles + 7) / 8 * 8 * a->nsl)
+        return (int)hipErrorInvalidValue;
+    if (lds_bytes != (int)DLF_BN_LDS_BYTES(a->rp, a->tp, a->cin0) || lds_bytes > 160 * 1024) return (int)hipErrorInvalidValue;
+    void (*const kern)(DlfBnArgs) = a->cin0 == 128 ? k_bneck<128> : (a->cin0 == 256 ? k_bneck<256> : k_bneck<512>);
+    launch(kern, dim3(grid), dim3(DLF_BN_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
     return (int)hipGetLastError();
 }
 

@@ -40,6 +40,7 @@ int dlf_launch_dwt(const DlfDwtArgs*, int, int, void*) { return unreachable_laun
 int dlf_launch_dws(const DlfDwsArgs*, int, int, void*) { return unreachable_launch("dws"); }
 int dlf_launch_c3s(const DlfC3sArgs*, int, int, void*) { return unreachable_launch("c3s"); }
 int dlf_launch_c3pw(const DlfC3PwArgs*, int, int, void*) { return unreachable_launch("c3pw"); }
+int dlf_launch_bneck(const DlfBnArgs*, int, int, void*) { return unreachable_launch("bneck"); }
 int dlf_kernels_init(void) { return unreachable_launch("init"); }
 void dlf_next_launch_events(void*, void*) { (void)unreachable_launch("events"); }
 }

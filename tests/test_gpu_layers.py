@@ -737,6 +737,45 @@ def test_fused_3x3_pointwise_kernel(c, cout, h, w, batch, th, tw, act1, act2, re
     compare(got, o.run_net(net, x, ws, bs), "fused 3x3 -> 1x1 %d->%d %dx%d" % (c, cout, h, w))
 
 
+# (cin0, cout, height, width, batch, tile th, tile tw, identity shortcut, activations of the three layers): a
+# whole bottleneck block 1x1 -> 3x3 -> 1x1 on one kernel (shape 7 of the hook; th = 0: the planner's cut):
+# tiles that divide the map and ragged ones, one-row and one-column tiles, 128 / 256 / 512 input
+# channels, one and two slices of the last layer's channel blocks, a ragged last block, with the block's
+# input as the residual operand and without
+BNECK_CASES = [(256, 256, 56, 56, 1, 7, 8, True, ("relu", "relu", "relu")), (256, 256, 28, 28, 2, 0, 0, True, ("relu", "relu", "relu")),
+               (128, 128, 13, 17, 2, 7, 8, True, ("relu6", "relu", "none")), (512, 512, 9, 11, 2, 5, 6, True, ("relu", "relu6", "relu")),
+               (256, 520, 9, 11, 3, 4, 14, False, ("relu", "relu", "relu")), (128, 72, 5, 40, 1, 1, 16, False, ("none", "relu", "relu")),
+               (256, 256, 19, 3, 2, 8, 1, True, ("relu", "none", "relu6")), (512, 200, 6, 6, 3, 3, 6, False, ("relu", "relu", "relu"))]
+
+
+@pytest.mark.parametrize("cin0,cout,h,w,batch,th,tw,identity,acts", BNECK_CASES)
+def test_bottleneck_kernel(cin0, cout, h, w, batch, th, tw, identity, acts):
+    from oracle import oracle as o
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    announce("bottleneck", cin0, cout, h, w, batch, th, tw, identity, acts)
+    layers = [nets.conv(32, cin0, 1, 1, 0, "relu"), nets.conv(cin0, 64, 1, 1, 0, acts[0]), nets.conv(64, 64, 3, 1, 1, acts[1]),
+              nets.conv(64, cout, 1, 1, 0, acts[2], **(dict(residual_from=0) if identity else {}))]
+    net = _mk(layers, h, w, 32, dist="normal")
+    x, ws, bs = gen.make_params(net, batch, 16)
+    B.dlf_debug_block3x3_mode(1, 7, th, tw)        # shape 7: this kernel; th x tw: its tile
+    try:
+        s = Session(net, batch, ws, bs, **_manual(4, [0, 3]))
+    finally:
+        B.dlf_debug_block3x3_mode(0)
+    try:
+        cfg = B.dlf_plan_group_config(s.plan, 1)
+        assert cfg["kind"] == 12 and cfg["variant"] == cin0, cfg
+        assert B.dlf_plan_group_io(s.plan, 1) == (0, -2)      # the shortcut is the group's own input
+        if th:
+            gp = B.dlf_plan_groups(s.plan)[1]
+            assert (gp["tile_h"], gp["tile_w"]) == (-(-h // -(-h // th)), -(-w // -(-w // tw))), gp
+        got = s.run_numpy(x)
+    finally:
+        s.close()
+    compare(got, o.run_net(net, x, ws, bs), "bottleneck %d->64->64->%d %dx%d" % (cin0, cout, h, w))
+
+
 # (channels in, channels out, height, width, batch, activation): 1x1 layers on the same kernel (pointwise
 # mode 8): chunks of 128 channels whole or split over the waves, 2 to 64 channel blocks, ragged last
 # slices, tiles of fewer than 32 pixels, several tiles per map, a one-pixel map

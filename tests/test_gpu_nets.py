@@ -25,7 +25,7 @@ def _manual(lasts, budget):
     return dict(mode=B.TUNER_MANUAL, group_last=list(lasts), group_budget=[budget] * len(lasts))
 
 
-KIND_NAME = {0: "group", 1: "fc", 2: "gap", 3: "pw", 4: "c3b", 5: "dw", 6: "dwpw", 7: "dwt", 8: "pw2", 9: "dws", 10: "c3s", 11: "c3pw"}
+KIND_NAME = {0: "group", 1: "fc", 2: "gap", 3: "pw", 4: "c3b", 5: "dw", 6: "dwpw", 7: "dwt", 8: "pw2", 9: "dws", 10: "c3s", 11: "c3pw", 12: "bneck"}
 
 
 def _kinds(s):
@@ -159,7 +159,7 @@ def test_config4_resnet50_batch32_sampled():
     # image 17: its pixels straddle the 128-pixel blocks of the pointwise block kernel on every map;
     # the small-map kernel on the 3x3 (variant = waves per channel block) and 1x1 (8 + that) layers of the last two stages
     _net_case(net, 32, [0, 17, 31], True, _plans(net)[:1],
-              expect_kinds=[("pw", 3), ("pw2", None), ("group", None), ("c3s", 2), ("c3s", 10), ("c3pw", 4), ("c3pw", 2)])
+              expect_kinds=[("pw", 3), ("pw2", None), ("group", None), ("c3s", 2), ("c3s", 10), ("c3pw", 4), ("bneck", 256)])
 
 
 def test_config5_mobilenet_batch1():
