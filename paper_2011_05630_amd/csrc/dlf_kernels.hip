@@ -3043,17 +3043,21 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
     }
 }
 
-// 3x3 convolution (stride 1, pad 1, c -> c channels, c = 128 or 256) + bias + activation, and the 1x1
+// 3x3 convolution (stride 1, pad 1, c -> c channels, c = 64, 128 or 256) + bias + activation, and the 1x1
 // convolution behind it + bias + residual operand + activation: the second half of a bottleneck block
-// (Sec. III-B: the intermediate tensor never leaves the chip), for the case that the batch has no
-// more tiles than the chip has CUs, where the fused-group kernel's tile pipeline is bound by the
-// latency of its steps.  One workgroup of eight waves per work item = (tile of up to 8 x 16 output
-// pixels, slice of 16 channel blocks of the second layer); one item per workgroup.  Every workgroup
-// of the chip is in the same phase at the same time, so the phases are arranged for memory and
-// matrix pipes to work side by side: the residual operand comes in while the first layer multiplies.
+// (Sec. III-B: the intermediate tensor never leaves the chip), where the fused-group kernel's tile
+// pipeline is bound by the latency of its steps.  Work item = (tile of up to 8 x 16 output pixels,
+// slice of the second layer's channel blocks, two per wave); one item per workgroup.
+//   c = 128, 256: workgroups of eight waves, one to a CU, for batches with no more tiles than CUs.
+// Every workgroup of the chip is then in the same phase at the same time, so the phases are
+// arranged for memory and matrix pipes to work side by side: the residual operand comes in while
+// the first layer multiplies.
+//   c = 64: workgroups of four waves, two or three to a CU and more items than places: the phases
+// of neighbouring items overlap by themselves (ResNet-50's 56 x 56 groups: 116 MB in 31 us).
 //   1. The tile's input region, all c channels, global -> LDS by direct loads, as in k_c3s (range
 //      check as padding, parts permuted by (r * tw + c) % 16).  Behind it the residual operand of the
-//      item's pixels x 512 channels, likewise to LDS (one load per pixel, rows of 1024 + 64 bytes), by
+//      item's pixels x 512 (four waves: 256) channels, likewise to LDS (one load per pixel, rows of
+//      1024 + 64 (512 + 64) bytes; of an item of four waves the upper lanes take no part), by
 //      the waves that have no part in the first layer, once the region has landed (requested beside
 //      it, it doubles the time until the first layer can start); with eight channel blocks in the
 //      first layer every wave has one, and they all request it before they start.
