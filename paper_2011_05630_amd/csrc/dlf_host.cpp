@@ -315,6 +315,7 @@ const int64_t C3PW_STORE_BYTES_PER_CYCLE = 2300;
 const int64_t C_BN_ITEM = 14000;              // bottleneck kernel: per item, per tile pixel, per 16 input channels beyond 256
 const int64_t C_BN_PIXEL = 245;
 const int64_t C_BN_CHANNEL = 150;
+const int64_t C_BN_LAST = 5000;              // ... less without the last layer
 const int64_t C3PW_OVERLAP_PCT = 60;         // two workgroups per CU: what a further round of items adds, in per cent of an item
 
 struct StageSpec {   // one stage, before tiling
@@ -1316,30 +1317,35 @@ bool c3pw_choose(const Layer& A, const Layer& P, int batch, int budget, int max_
 
 // ---- a whole bottleneck block (1x1 -> 3x3 -> 1x1, identity shortcut or none) as one group ----
 
+// (two stages: the pair 1x1 -> 3x3, which the kernel runs without its last layer)
 bool bneck_eligible(const dlf_net_s& net, const std::vector<StageSpec>& specs, int batch)
 {
-    if (specs.size() != 3) return false;
+    if (specs.size() != 3 && specs.size() != 2) return false;
     for (const StageSpec& sp : specs)
         if (sp.kind != DLF_ST_CONV || sp.pool2) return false;
     const Layer& A = net.L[specs[0].layer];
     const Layer& B = net.L[specs[1].layer];
-    const Layer& P = net.L[specs[2].layer];
     const dlf_layer_desc& a = A.d;
     const dlf_layer_desc& b = B.d;
-    const dlf_layer_desc& p = P.d;
-    if (A.im2col || A.rowfold || B.im2col || B.rowfold || P.im2col || P.rowfold) return false;
+    if (A.im2col || A.rowfold || B.im2col || B.rowfold) return false;
     if (a.kh != 1 || a.kw != 1 || a.stride != 1 || a.pad != 0 || a.residual_from >= 0) return false;
-    if ((a.cin != 128 && a.cin != 256 && a.cin != 512) || a.cout != 64) return false;
+    if ((a.cin != 64 && a.cin != 128 && a.cin != 256 && a.cin != 512) || a.cout != 64) return false;
     if (b.kh != 3 || b.kw != 3 || b.stride != 1 || b.pad != 1 || b.cin != 64 || b.cout != 64 || b.residual_from >= 0) return false;
+    if ((int64_t)batch * A.in_h * A.in_w * a.cin * 2 >= (int64_t)1 << 31) return false;
+    if (specs.size() == 2) return true;
+    if (a.cin == 64) return false;
+    const Layer& P = net.L[specs[2].layer];
+    const dlf_layer_desc& p = P.d;
+    if (P.im2col || P.rowfold) return false;
     if (p.kh != 1 || p.kw != 1 || p.stride != 1 || p.pad != 0 || p.cin != 64 || (p.cout % 8) != 0) return false;
     // the shortcut, if any, is the block's own input
     if (p.residual_from >= 0 && (p.residual_from != A.src || p.cout != a.cin)) return false;
-    if ((int64_t)batch * A.in_h * A.in_w * a.cin * 2 >= (int64_t)1 << 31) return false;
     if ((int64_t)batch * P.out_h * P.out_w * p.cout * 2 >= (int64_t)1 << 31) return false;
     return true;
 }
 
-// One configuration: the map cut into rows x cols equal tiles of at most 64 pixels.
+// One configuration: the map cut into rows x cols equal tiles of at most 64 pixels.  P is the last
+// layer, or the second one again where there are only two.
 bool bneck_build(const Layer& A, const Layer& B, const Layer& P, int batch, int rows, int cols, int max_lds, DlfBnArgs& bn)
 {
     memset(&bn, 0, sizeof bn);
@@ -1351,15 +1357,22 @@ bool bneck_build(const Layer& A, const Layer& B, const Layer& P, int batch, int 
     bn.rw = bn.tw + 2;
     bn.rp = (bn.th + 2) * bn.rw;
     if ((int)DLF_BN_LDS_BYTES(bn.rp, bn.tp, A.d.cin) > std::min(max_lds, 80 * 1024)) return false;   // two to a CU
-    bn.w0 = A.d_w; bn.b0 = A.d_bias; bn.w1 = B.d_w; bn.b1 = B.d_bias; bn.w2 = P.d_w; bn.b2 = P.d_bias;
+    const bool two = &P == &B;
+    bn.w0 = A.d_w; bn.b0 = A.d_bias; bn.w1 = B.d_w; bn.b1 = B.d_bias; bn.w2 = two ? nullptr : P.d_w; bn.b2 = two ? nullptr : P.d_bias;
     bn.in_bytes = (uint32_t)((int64_t)batch * A.in_h * A.in_w * A.in_c * 2);
     bn.batch = batch; bn.h = A.in_h; bn.w_ = A.in_w; bn.cin0 = A.d.cin; bn.cout = P.d.cout;
-    bn.ncb2 = P.ncb; bn.act0 = A.d.act; bn.act1 = B.d.act; bn.act2 = P.d.act;
-    bn.identity = P.d.residual_from >= 0 ? 1 : 0;
+    bn.ncb2 = two ? 0 : P.ncb; bn.act0 = A.d.act; bn.act1 = B.d.act; bn.act2 = P.d.act;
+    bn.identity = !two && P.d.residual_from >= 0 ? 1 : 0;
     bn.tiles_y = ceil_div(A.out_h, bn.th); bn.tiles_x = ceil_div(A.out_w, bn.tw);
     bn.ntiles = batch * bn.tiles_y * bn.tiles_x;
-    bn.nsl = ceil_div(P.ncb, 2 * DLF_BN_WAVES);
+    bn.nsl = two ? 1 : ceil_div(P.ncb, 2 * DLF_BN_WAVES);
     return true;
+}
+
+// Workgroups a CU holds: two or three, as LDS allows (182 - 256 registers for four waves: three fit).
+int bneck_per_cu(const DlfBnArgs& bn)
+{
+    return std::max(1, std::min(bn.cin0 == 512 ? 2 : 3, (160 * 1024) / (int)DLF_BN_LDS_BYTES(bn.rp, bn.tp, bn.cin0)));
 }
 
 // An item is a chain of waits (region, first layer with one accumulator per wave, the 3x3 ring, the
@@ -1370,13 +1383,15 @@ bool bneck_build(const Layer& A, const Layer& B, const Layer& P, int batch, int 
 uint64_t bneck_cost_ps(const Layer& A, const Layer& B, const Layer& P, int batch, int budget, const DlfBnArgs& bn)
 {
     const int64_t nitems = (int64_t)bn.ntiles * bn.nsl;
+    // (a third workgroup on a CU, where LDS has room for one, does not shorten the chains: priced as two)
     const int64_t slots = (int64_t)budget * 2;
-    int64_t item = C_BN_ITEM + C_BN_PIXEL * bn.tp + (bn.cin0 - 256) * C_BN_CHANNEL / 16;
+    const bool two = bn.ncb2 == 0;
+    int64_t item = C_BN_ITEM + C_BN_PIXEL * bn.tp + (bn.cin0 - 256) * C_BN_CHANNEL / 16 - (two ? C_BN_LAST : 0);
     if (nitems <= budget) item /= 2;
     const int64_t compute = nitems <= slots ? item : item * nitems / slots;
     const int64_t m = (int64_t)batch * P.out_h * P.out_w;
     const int64_t bytes = (int64_t)bn.ntiles * bn.rp * bn.cin0 * 2 + m * bn.cout * 2 +
-                          ((int64_t)A.ncb * A.nsteps + (int64_t)B.ncb * B.nsteps + (int64_t)P.ncb * P.nsteps) * 1024;
+                          ((int64_t)A.ncb * A.nsteps + (int64_t)B.ncb * B.nsteps + (two ? 0 : (int64_t)P.ncb * P.nsteps)) * 1024;
     const int64_t mem = bytes / std::min<int64_t>(PW_HBM_BYTES_PER_CYCLE, (int64_t)budget * CU_BYTES_PER_CYCLE);
     return (uint64_t)((C_LAUNCH + std::max(compute, mem)) * PS_PER_CYCLE);
 }
@@ -1711,10 +1726,10 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
         }
     }
     // a whole bottleneck block: shape DLF_C3_SHAPES + 2 of the testing hook (its th x tw then fix the tile)
-    if (first + 2 == last && c3f.mode != 2 && (force.th <= 0 || c3f.mode == 1) &&
+    if ((first + 2 == last || first + 1 == last) && c3f.mode != 2 && (force.th <= 0 || c3f.mode == 1) &&
         (c3f.shape < 0 || c3f.shape == DLF_C3_SHAPES + 2) && bneck_eligible(net, specs, batch)) {
         const Layer& Bm = net.L[first + 1];
-        const Layer& P = net.L[last];
+        const Layer& P = net.L[last];            // (two layers: the second one again)
         DlfBnArgs bn;
         uint64_t bc = 0;
         bool have;
@@ -1729,7 +1744,7 @@ dlf_status make_group(const dlf_net_s& net, int batch, int first, int last, int 
             g.kind = GK_BNECK;
             g.cost = bc;
             g.variant = bn.cin0;
-            g.occ = 2;
+            g.occ = bneck_per_cu(bn);
             g.grid = ceil_div(bn.ntiles, 8) * 8 * bn.nsl;
             g.th = bn.th; g.tw = bn.tw;
             g.lds_bytes = (int)DLF_BN_LDS_BYTES(bn.rp, bn.tp, bn.cin0);

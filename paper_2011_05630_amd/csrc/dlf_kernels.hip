@@ -3323,6 +3323,7 @@ __global__ __launch_bounds__(DLF_C3PW_WAVES(C) * 64, C == 64 ? 2 : 1) void k_c3p
     }
 }
 
+// (With ncb2 = 0 the kernel stops after the second layer and stores its tile: the pair 1x1 -> 3x3.)
 // A bottleneck block as one group: 1x1 (cin0 -> 64) + 3x3 (64 -> 64, stride 1, pad 1) + 1x1 (64 -> cout),
 // each with bias and activation, and the block's input added before the last activation where the
 // block has an identity shortcut (Sec. III-B: neither intermediate tensor leaves the chip, and the
@@ -3346,8 +3347,9 @@ template <int CIN0>
 __global__ __launch_bounds__(DLF_BN_WAVES * 64, 2) void k_bneck(const DlfBnArgs a)
 {
     constexpr int D = 9, ROW = 32 + 8, C = 64, W = DLF_BN_WAVES, FP = 2, cs = C + 8;
-    static_assert(CIN0 == 128 || CIN0 == 256 || CIN0 == 512, "channels of the block's input");
-    constexpr int pp0 = CIN0 == 128 ? 4 : (CIN0 == 256 ? 5 : 6);       // log2 of the input's 16-byte parts per pixel
+    static_assert(CIN0 == 64 || CIN0 == 128 || CIN0 == 256 || CIN0 == 512, "channels of the block's input");
+    constexpr int pp0 = CIN0 == 64 ? 3 : (CIN0 == 128 ? 4 : (CIN0 == 256 ? 5 : 6));   // log2 of the input's 16-byte parts per pixel
+    constexpr int PERM0 = CIN0 == 64 ? 7 : 15;               // the permutation stays inside a pixel
     constexpr int NS0 = CIN0 / 16;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
@@ -3387,7 +3389,7 @@ __global__ __launch_bounds__(DLF_BN_WAVES * 64, 2) void k_bneck(const DlfBnArgs 
             const int ry = div_by(hp, rw_m), rx = hp - ry * a.rw;
             const int gy = oy0 - 1 + ry, gx = ox0 - 1 + rx;
             if (gy >= 0 && gy < a.h && gx >= 0 && gx < a.w_)
-                off = (unsigned)(((n * a.h + gy) * a.w_ + gx) * CIN0 + ((pos ^ ((ry * a.tw + rx) & 15)) << 3)) * 2u;
+                off = (unsigned)(((n * a.h + gy) * a.w_ + gx) * CIN0 + ((pos ^ ((ry * a.tw + rx) & PERM0)) << 3)) * 2u;
         }
         asm volatile("s_mov_b32 m0, %2\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(off), "s"(rin),
                      "s"(lds0 + (unsigned)i * 1024u)
@@ -3405,14 +3407,15 @@ __global__ __launch_bounds__(DLF_BN_WAVES * 64, 2) void k_bneck(const DlfBnArgs 
     f4v bias0[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) bias0[q] = *(const f4v*)(a.b0 + cb_a * 32 + q * 8 + lhi * 4);
+    const bool last = a.ncb2 > 0;                            // uniform: is there a third layer
     const int cb0 = (sl * W + wave) * 2;
     const bool live = cb0 < a.ncb2;                          // uniform
-    bl[lane] = a.b2[min(cb0 * 32 + lane, a.ncb2 * 32 - 1)];
+    if (last) bl[lane] = a.b2[min(cb0 * 32 + lane, a.ncb2 * 32 - 1)];
     // the last layer's weights of this wave (both channel blocks, all of K) and, on the two waves of
     // the second layer, the first turn of its ring: everything is requested before the first wait
     constexpr int nsteps1 = 2 * 18, nsteps2 = C / 16;
     h8 a2[2][nsteps2];
-    {
+    if (last) {
         const i32x4 rw2 = make_rsrc(a.w2, 0xffffffffu);
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
@@ -3443,14 +3446,14 @@ __global__ __launch_bounds__(DLF_BN_WAVES * 64, 2) void k_bneck(const DlfBnArgs 
         for (int pb = wave >> 1; pb < npb; pb += W / 2) {
             const int px_ = pb * 32 + l32, pc = min(px_, a.rp - 1);
             const int ry = div_by(pc, rw_m), rx = pc - ry * a.rw;
-            const int perm = (ry * a.tw + rx) & 15;
+            const int perm = (ry * a.tw + rx) & 15;          // (the first region uses PERM0 of its bits, the second 7)
             const char* const src = r0 + pc * (CIN0 * 2);
             f16v acc;
 #pragma unroll
             for (int q = 0; q < 16; ++q) acc[q] = bias0[q >> 2][q & 3];
 #pragma unroll
             for (int k = 0; k < NS0; ++k)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0[k], *(const h8*)(src + (((2 * k + lhi) ^ perm) << 4)), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0[k], *(const h8*)(src + (((2 * k + lhi) ^ (perm & PERM0)) << 4)), acc, 0, 0, 0);
             const int gy = oy0 - 1 + ry, gx = ox0 - 1 + rx;
             const bool inside = gy >= 0 && gy < a.h && gx >= 0 && gx < a.w_;
             char* const dst = ma + pc * (C * 2) + lhi * 8;
@@ -3525,6 +3528,17 @@ __global__ __launch_bounds__(DLF_BN_WAVES * 64, 2) void k_bneck(const DlfBnArgs 
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     }
     asm volatile("s_barrier" ::: "memory");                  // the tile is complete
+    if (!last) {
+        // two layers only: the tile goes to memory as it is, 16 bytes per lane
+        for (int idx = threadIdx.x; idx < a.tp * (C / 8); idx += W * 64) {
+            const int px_ = idx >> 3, q = idx & 7;
+            const int row = div_by(px_, tw_m), colp = px_ - row * a.tw;
+            const int oy = oy0 + row, ox = ox0 + colp;
+            if (oy < a.h && ox < a.w_)
+                *(u4v*)(outp + ((size_t)((n * a.h + oy) * a.w_ + ox) * C + q * 8)) = *(const u4v*)(mid + px_ * cs + q * 8);
+        }
+        return;
+    }
     if (!live) return;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
@@ -3578,7 +3592,7 @@ __global__ __launch_bounds__(DLF_BN_WAVES * 64, 2) void k_bneck(const DlfBnArgs 
             half_t* const dst = outp + ((size_t)((n * a.h + oy) * a.w_ + ox) * a.cout + cc);
             // the same pixel of the input region: one row and one column in
             const int rpx = (row + 1) * a.rw + colp + 1;
-            const int rperm = ((row + 1) * a.tw + colp + 1) & 15;
+            const int rperm = ((row + 1) * a.tw + colp + 1) & PERM0;
             const char* const rsrc = r0 + rpx * (CIN0 * 2);
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -3889,6 +3903,7 @@ extern "C" int dlf_kernels_init(void)
         if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_c3pw<4, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_c3pw<2, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_c3pw<4, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_bneck<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_bneck<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_bneck<256>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e2 == hipSuccess) e2 = hipFuncSetAttribute((const void*)k_bneck<512>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -4103,17 +4118,20 @@ extern "C" int dlf_launch_bneck(const DlfBnArgs* a, int grid, int lds_bytes, voi
 {
     // what the kernel's indexing assumes
     if (grid <= 0 || (grid & 7) != 0 || a->in_bytes >= 0x80000000u) return (int)hipErrorInvalidValue;
-    if (a->cin0 != 128 && a->cin0 != 256 && a->cin0 != 512) return (int)hipErrorInvalidValue;
-    if ((a->cout & 7) != 0 || a->ncb2 != (a->cout + 31) / 32 || a->nsl != (a->ncb2 + 2 * DLF_BN_WAVES - 1) / (2 * DLF_BN_WAVES) ||
-        (a->identity && a->cout != a->cin0))
+    if (a->cin0 != 64 && a->cin0 != 128 && a->cin0 != 256 && a->cin0 != 512) return (int)hipErrorInvalidValue;
+    if (a->ncb2 == 0) {                                      // two layers: the output is the second layer's
+        if (a->cout != 64 || a->nsl != 1 || a->identity) return (int)hipErrorInvalidValue;
+    } else if (a->cin0 == 64 || (a->cout & 7) != 0 || a->ncb2 != (a->cout + 31) / 32 ||
+               a->nsl != (a->ncb2 + 2 * DLF_BN_WAVES - 1) / (2 * DLF_BN_WAVES) || (a->identity && a->cout != a->cin0)) {
         return (int)hipErrorInvalidValue;
+    }
     if (a->th < 1 || a->th > 8 || a->tw < 1 || a->tw > 16 || a->tp != a->th * a->tw || a->tp > 64 || a->rw != a->tw + 2 ||
         a->rp != (a->th + 2) * (a->tw + 2) || a->tiles_y != (a->h + a->th - 1) / a->th ||
         a->tiles_x != (a->w_ + a->tw - 1) / a->tw || a->ntiles != a->batch * a->tiles_y * a->tiles_x ||
         grid != (a->ntiles + 7) / 8 * 8 * a->nsl)
         return (int)hipErrorInvalidValue;
     if (lds_bytes != (int)DLF_BN_LDS_BYTES(a->rp, a->tp, a->cin0) || lds_bytes > 160 * 1024) return (int)hipErrorInvalidValue;
-    void (*const kern)(DlfBnArgs) = a->cin0 == 128 ? k_bneck<128> : (a->cin0 == 256 ? k_bneck<256> : k_bneck<512>);
+    void (*const kern)(DlfBnArgs) = a->cin0 == 64 ? k_bneck<64> : (a->cin0 == 128 ? k_bneck<128> : (a->cin0 == 256 ? k_bneck<256> : k_bneck<512>));
     launch(kern, dim3(grid), dim3(DLF_BN_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
     return (int)hipGetLastError();
 }

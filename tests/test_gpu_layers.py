@@ -776,6 +776,35 @@ def test_bottleneck_kernel(cin0, cout, h, w, batch, th, tw, identity, acts):
     compare(got, o.run_net(net, x, ws, bs), "bottleneck %d->64->64->%d %dx%d" % (cin0, cout, h, w))
 
 
+# (cin0, height, width, batch, tile th, tile tw, activations): the same kernel without its last layer, the
+# pair 1x1 -> 3x3 (64 channels out)
+BNECK2_CASES = [(64, 56, 56, 1, 7, 8, ("relu", "relu")), (64, 28, 28, 2, 0, 0, ("relu", "relu")), (256, 13, 17, 2, 7, 8, ("relu6", "none")),
+                (128, 9, 11, 3, 5, 6, ("none", "relu")), (512, 5, 40, 1, 1, 16, ("relu", "relu6")), (64, 19, 3, 2, 8, 1, ("relu", "relu"))]
+
+
+@pytest.mark.parametrize("cin0,h,w,batch,th,tw,acts", BNECK2_CASES)
+def test_bottleneck_kernel_two_layers(cin0, h, w, batch, th, tw, acts):
+    from oracle import oracle as o
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    announce("bottleneck, two layers", cin0, h, w, batch, th, tw, acts)
+    layers = [nets.conv(32, cin0, 1, 1, 0, "relu"), nets.conv(cin0, 64, 1, 1, 0, acts[0]), nets.conv(64, 64, 3, 1, 1, acts[1])]
+    net = _mk(layers, h, w, 32, dist="normal")
+    x, ws, bs = gen.make_params(net, batch, 17)
+    B.dlf_debug_block3x3_mode(1, 7, th, tw)
+    try:
+        s = Session(net, batch, ws, bs, **_manual(3, [0, 2]))
+    finally:
+        B.dlf_debug_block3x3_mode(0)
+    try:
+        cfg = B.dlf_plan_group_config(s.plan, 1)
+        assert cfg["kind"] == 12 and cfg["variant"] == cin0, cfg
+        got = s.run_numpy(x)
+    finally:
+        s.close()
+    compare(got, o.run_net(net, x, ws, bs), "1x1 -> 3x3 %d->64->64 %dx%d" % (cin0, h, w))
+
+
 # (channels in, channels out, height, width, batch, activation): 1x1 layers on the same kernel (pointwise
 # mode 8): chunks of 128 channels whole or split over the waves, 2 to 64 channel blocks, ragged last
 # slices, tiles of fewer than 32 pixels, several tiles per map, a one-pixel map
