@@ -2556,8 +2556,15 @@ dlf_status dlf_plan_refine(dlf_plan_t* plan, const void* in_dev, void* out_dev, 
                            void* out, std::vector<float>& ms) {
         dlf_status r = DLF_OK;
         std::vector<double> sum(list.size(), 0.0);
+        // a candidate's residual operand is its own: the kernel for a whole bottleneck block takes it
+        // from its input, the fused-group kernel on the same layers as a second tensor
+        (void)res;
+        auto res_of = [&](const GroupPlan& c) -> const void* {
+            if (c.res_stage < 0) return nullptr;
+            return c.res_layer < 0 ? in_dev : (const void*)(plan->ws + plan->layer_off[c.res_layer]);
+        };
         for (size_t i = 0; i < list.size() && r == DLF_OK; ++i)
-            r = launch_one(plan, list[i], in, res, out, hip_stream, plan->ws);          // warm-up
+            r = launch_one(plan, list[i], in, res_of(list[i]), out, hip_stream, plan->ws);          // warm-up
         for (int rep = 0; rep < reps && r == DLF_OK; ++rep)
             for (size_t i = 0; i < list.size() && r == DLF_OK; ++i) {
                 if (scrub) (void)hipMemsetAsync(scrub, rep, scrub_bytes, st);
@@ -2569,7 +2576,7 @@ dlf_status dlf_plan_refine(dlf_plan_t* plan, const void* in_dev, void* out_dev, 
                     if (r != DLF_OK) break;
                 }
                 (void)hipEventRecord(e0, st);
-                r = launch_one(plan, list[i], in, res, out, hip_stream, plan->ws);
+                r = launch_one(plan, list[i], in, res_of(list[i]), out, hip_stream, plan->ws);
                 (void)hipEventRecord(e1, st);
                 if (hipEventSynchronize(e1) != hipSuccess && r == DLF_OK)
                     r = fail(DLF_ERR_HIP, "event synchronise failed");

@@ -260,6 +260,28 @@ def test_measured_refinement_keeps_the_results():
     s.close()
 
 
+def test_measured_refinement_of_a_bottleneck_block():
+    """A whole bottleneck block as one group takes its residual operand from its input; the
+    fused-group candidates that dlf_plan_refine times on the same layers take it as a second
+    tensor: every candidate must get its own."""
+    from oracle import oracle as o
+    from paper_2011_05630_amd import binding as B
+    layers = [nets.conv(16, 256, 1, 1, 0, "relu"), nets.conv(256, 64, 1, 1, 0, "relu"), nets.conv(64, 64, 3, 1, 1, "relu"),
+              nets.conv(64, 256, 1, 1, 0, "relu", residual_from=0), nets.conv(256, 64, 1, 1, 0, "relu")]
+    net = dict(name="refine_bneck", layers=layers, in_h=28, in_w=28, in_c=16, input_dist="normal")
+    x, ws, bs = gen.make_params(net, 2)
+    ref = o.run_net(net, x, ws, bs)
+    s = _session(net, 2, ws, bs, mode=B.TUNER_MANUAL, group_last=[0, 3, 4], group_budget=[256] * 3)
+    assert B.dlf_plan_group_config(s.plan, 1)["kind"] == 12
+    xt = torch.from_numpy(x).cuda()
+    changed = s.refine(xt, top_k=4, reps=2)
+    assert 0 <= changed <= 3
+    y1 = s.run(xt)
+    torch.cuda.synchronize()
+    compare(y1.cpu().numpy(), ref, "bottleneck block after refinement")
+    s.close()
+
+
 def test_error_paths_return_status_not_crash():
     from paper_2011_05630_amd import binding as B
     net = nets.chain4(256)
