@@ -194,7 +194,15 @@ const void* dlf_plan_layer_output(const dlf_plan_t* plan, int32_t layer);
  * kernel: the same pair, the depthwise result of a pixel tile held in LDS (variant = stride - 1),
  * 8 two 1x1 convolutions into one output (the projection shortcut of a residual block and the
  * block's last layer, variant = block form as for kind 3; the group reads two tensors, reported by
- * dlf_plan_group_io as input = the last layer's input, residual = the projection's input);
+ * dlf_plan_group_io as input = the last layer's input, residual = the projection's input),
+ * 9 depthwise + 1x1 kernel for maps of 256 and more channels and few pixels (variant = 2 * (stride
+ * - 1) + channel blocks per wave - 1), 10 small-map kernel: a single 3x3 layer (stride 1 or 2,
+ * residual or not) or 1x1 layer on 256 .. 2048 input channels (variant = waves that share a channel
+ * block's K: 1, 2 or 4; + 8 for a 1x1 layer), 11 a 3x3 layer of 64, 128 or 256 channels and the 1x1
+ * layer behind it (variant = 32-pixel blocks of a tile: 2 or 4), 12 a whole bottleneck block, 1x1 to
+ * 64 channels -> 3x3 -> 1x1 with the block's input as residual operand, or its first two layers
+ * (variant = the block's input channels; dlf_plan_group_io reports no residual tensor: the kernel
+ * takes it from its input);
  * channel slices, channels
  * per slice, whether stage 0 streams its input, LDS bytes per workgroup.  Any out pointer may be
  * NULL. */
