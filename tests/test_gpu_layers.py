@@ -805,6 +805,68 @@ def test_bottleneck_kernel_two_layers(cin0, h, w, batch, th, tw, acts):
     compare(got, o.run_net(net, x, ws, bs), "1x1 -> 3x3 %d->64->64 %dx%d" % (cin0, h, w))
 
 
+def test_pair_and_bottleneck_kernels_random_shapes():
+    """Seeded random shapes for the 3x3 -> 1x1 pair kernel (64 / 128 / 256 channels) and the bottleneck
+    kernel (two and three layers): maps that the tile does not divide, every tile size the hook lets
+    through, odd output channel counts (multiples of 8), with and without the residual operand."""
+    import random
+    from oracle import oracle as o
+    from paper_2011_05630_amd import binding as B
+    from paper_2011_05630_amd.runner import Session
+    rnd = random.Random(20252)
+    done = 0
+    tries = 0
+    while done < 30 and tries < 400:
+        tries += 1
+        which = rnd.choice(("pair", "pair", "bneck3", "bneck2"))
+        h, w = rnd.randint(1, 20), rnd.randint(1, 20)
+        batch = rnd.randint(1, 3)
+        th, tw = rnd.randint(1, 8), rnd.randint(1, 16)
+        acts = [rnd.choice(("relu", "relu6", "none")) for _ in range(3)]
+        residual = rnd.random() < 0.6
+        if which == "pair":
+            c = rnd.choice((64, 128, 256))
+            cout = 8 * rnd.randint(1, 80)
+            if th * tw > 128:
+                continue
+            layers = [nets.conv(16, cout, 1, 1, 0, "relu"), nets.conv(cout, c, 1, 1, 0, "relu"), nets.conv(c, c, 3, 1, 1, acts[0]),
+                      nets.conv(c, cout, 1, 1, 0, acts[1], **(dict(residual_from=0) if residual else {}))]
+            lasts, shape, kind, target = [0, 1, 3], 6, 11, 2
+        elif which == "bneck3":
+            cin0 = rnd.choice((128, 256, 512))
+            cout = cin0 if residual else 8 * rnd.randint(1, 80)
+            if th * tw > 64:
+                continue
+            layers = [nets.conv(16, cin0, 1, 1, 0, "relu"), nets.conv(cin0, 64, 1, 1, 0, acts[0]), nets.conv(64, 64, 3, 1, 1, acts[1]),
+                      nets.conv(64, cout, 1, 1, 0, acts[2], **(dict(residual_from=0) if residual else {}))]
+            lasts, shape, kind, target = [0, 3], 7, 12, 1
+        else:
+            cin0 = rnd.choice((64, 128, 256, 512))
+            if th * tw > 64:
+                continue
+            layers = [nets.conv(16, cin0, 1, 1, 0, "relu"), nets.conv(cin0, 64, 1, 1, 0, acts[0]), nets.conv(64, 64, 3, 1, 1, acts[1])]
+            lasts, shape, kind, target = [0, 2], 7, 12, 1
+        net = _mk(layers, h, w, 16, dist="normal")
+        x, ws, bs = gen.make_params(net, batch, 300 + done)
+        B.dlf_debug_block3x3_mode(1, shape, th, tw)
+        try:
+            s = Session(net, batch, ws, bs, **_manual(len(layers), lasts, budget=rnd.choice((32, 256))))
+        except B.DlfError:
+            continue
+        finally:
+            B.dlf_debug_block3x3_mode(0)
+        try:
+            if B.dlf_plan_group_config(s.plan, target)["kind"] != kind:
+                continue                  # the tile does not fit LDS: another kernel took the group
+            announce("pair / bottleneck random", done, which, [L["cout"] for L in layers], h, w, batch, th, tw, acts, residual)
+            got = s.run_numpy(x)
+        finally:
+            s.close()
+        compare(got, o.run_net(net, x, ws, bs), "pair / bottleneck random case %d (%s)" % (done, which))
+        done += 1
+    assert done == 30
+
+
 # (channels in, channels out, height, width, batch, activation): 1x1 layers on the same kernel (pointwise
 # mode 8): chunks of 128 channels whole or split over the waves, 2 to 64 channel blocks, ragged last
 # slices, tiles of fewer than 32 pixels, several tiles per map, a one-pixel map
