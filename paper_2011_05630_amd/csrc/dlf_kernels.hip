@@ -2598,7 +2598,8 @@ __global__ __launch_bounds__(DLF_DWS_WAVES * 64, 1) void k_dws(const DlfDwsArgs 
     const int ppi = 64 >> ng_shift;                          // pixels per load instruction and per wave step
     const int g = lane & ((1 << ng_shift) - 1), psub = lane >> ng_shift;
     const int per8 = blockIdx.x >> 3;
-    const int sl = per8 % a.nsl, tile = (per8 / a.nsl) * 8 + (blockIdx.x & 7);
+    // (an XCD takes a contiguous eighth of the tiles: the halo a tile shares with its neighbours is in that XCD's L2)
+    const int sl = per8 % a.nsl, tile = (blockIdx.x & 7) * ((a.ntiles + 7) >> 3) + per8 / a.nsl;
     if (tile >= a.ntiles) return;
     int r_ = tile;
     const int tx = r_ % a.tiles_x;
@@ -2851,7 +2852,7 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
         tile = per8 * (8 / a.nsl) + xcd / a.nsl;
     } else {
         sl = per8 % a.nsl;
-        tile = (per8 / a.nsl) * 8 + xcd;
+        tile = xcd * ((a.ntiles + 7) >> 3) + per8 / a.nsl;     // a contiguous eighth of the tiles: halos meet in the XCD's L2
     }
     if (tile >= a.ntiles) return;
     int r_ = tile;
@@ -3087,7 +3088,8 @@ __global__ __launch_bounds__(DLF_C3PW_WAVES(C) * 64, C == 64 ? 2 : 1) void k_c3p
     constexpr int PERM = PP < 16 ? PP - 1 : 15;              // the permutation stays inside a pixel
     constexpr int cs = C + 8;
     const int per8 = blockIdx.x >> 3;
-    const int sl = per8 % a.nsl, tile = (per8 / a.nsl) * 8 + (blockIdx.x & 7);
+    // (an XCD takes a contiguous eighth of the tiles: the halo a tile shares with its neighbours is in that XCD's L2)
+    const int sl = per8 % a.nsl, tile = (blockIdx.x & 7) * ((a.ntiles + 7) >> 3) + per8 / a.nsl;
     if (tile >= a.ntiles) return;
     int r_ = tile;
     const int tx = r_ % a.tiles_x;
