@@ -2518,7 +2518,12 @@ __global__ __launch_bounds__(DLF_DWT_WAVES * 64, 2) void k_dwt(const DlfDwtArgs 
     for (int k = 0; k < 9; ++k) w[k] = *(const u4v*)(wdw + k * c + g * 8);
     const f4v b0 = *(const f4v*)(a.bdw + g * 8), b1 = *(const f4v*)(a.bdw + g * 8 + 4);
 
-    for (int t = blockIdx.x; t < a.ntiles; t += gridDim.x) {
+    // (work item i goes to XCD i % 8 when the grid is a multiple of 8: an XCD's items are a
+    // contiguous eighth of the tiles, so the rows neighbouring tiles share are in its L2)
+    const int per_xcd = (a.ntiles + 7) >> 3;
+    for (int i = blockIdx.x; i < 8 * per_xcd; i += gridDim.x) {
+        const int t = (i & 7) * per_xcd + (i >> 3);
+        if (t >= a.ntiles) continue;
         int r_ = t;
         const int tx = r_ % a.tiles_x;
         r_ /= a.tiles_x;
