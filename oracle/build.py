@@ -3,16 +3,16 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "dlf_oracle.c")
+SRCS = [os.path.join(HERE, "dlf_oracle.c"), os.path.join(HERE, "dlf_oracle_i8.c")]
 LIB = os.path.join(HERE, "liboracle.so")
 
 
 def build(force=False):
     if (not force and os.path.exists(LIB)
-            and os.path.getmtime(LIB) >= os.path.getmtime(SRC)):
+            and all(os.path.getmtime(LIB) >= os.path.getmtime(s) for s in SRCS)):
         return LIB
     tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-o", tmp, SRC, "-lm"]
+    cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-o", tmp] + SRCS + ["-lm"]
     subprocess.check_call(cmd)
     os.replace(tmp, LIB)
     return LIB

@@ -10,7 +10,10 @@ where intermediates live).
 Pins (tests/test_oracle_*.py): tap-count closed form, delta/shift kernels, linearity, 1x1 conv and
 FC against numpy.matmul, single-channel conv against scipy.signal.correlate2d, stride-2 against
 subsampled stride-1, depthwise against per-channel correlate2d, pooling against reshape/max and
-mean, hand-computed values, and tile-wise fused == whole-layer unfused bit equality.
+mean, hand-computed values, and tile-wise fused == whole-layer unfused bit equality.  The quantised
+convolution (tests/test_oracle_i8.py): accumulators against the fp64 convolution above, numpy
+integer matmul and scipy correlate2d; the requantisation against exact rational arithmetic on
+hand-made ties, saturation and a case where a two-rounding multiply-add would differ.
 """
 import ctypes
 import os
@@ -34,6 +37,10 @@ def lib():
                                                            i, _F]
             getattr(_lib, "orc_fc_" + sfx).argtypes = [_F, i, i, _F, _F, i, _F]
             getattr(_lib, "orc_global_avgpool_" + sfx).argtypes = [_F, i, i, i, i, _F]
+        _I8 = ctypes.POINTER(ctypes.c_int8)
+        _lib.orc_conv2d_i8.argtypes = [_I8, i, i, i, i, _I8, _F, _F, i, i, i, i, i, i, _I8,
+                                       ctypes.POINTER(ctypes.c_int32)]
+        _lib.orc_conv2d_i8.restype = ctypes.c_int
         _lib.orc_maxpool.argtypes = [_F, i, i, i, i, i, i, i, i, _F]
         _lib.orc_add.argtypes = [_F, _F, ctypes.c_size_t, _F]
         _lib.orc_act.argtypes = [_F, ctypes.c_size_t, i]
@@ -71,6 +78,28 @@ def conv2d(x, w, b=None, stride=1, pad=0, groups=1, acc="f32"):
     getattr(lib(), "orc_conv2d_" + acc)(_p(x), N, H, W, Cin, _p(w), _p(b), Cout, Kh, Kw, stride,
                                         pad, groups, _p(out))
     return out
+
+
+def conv2d_i8(x, w, scale, bias, stride=1, pad=0, relu=False, return_acc=False):
+    """Quantised convolution (see dlf_oracle_i8.c): x int8 [N,H,W,Cin], w int8 [Cout,Kh,Kw,Cin],
+    scale / bias fp32 [Cout] -> int8 [N,Ho,Wo,Cout] (and the int32 accumulators on request)."""
+    x = np.ascontiguousarray(x, dtype=np.int8)
+    w = np.ascontiguousarray(w, dtype=np.int8)
+    scale, bias = _f32(scale), _f32(bias)
+    N, H, W, Cin = x.shape
+    Cout, Kh, Kw, ci = w.shape
+    assert ci == Cin and scale.shape == (Cout,) and bias.shape == (Cout,)
+    Ho = (H + 2 * pad - Kh) // stride + 1
+    Wo = (W + 2 * pad - Kw) // stride + 1
+    out = np.empty((N, Ho, Wo, Cout), dtype=np.int8)
+    acc = np.empty((N, Ho, Wo, Cout), dtype=np.int32)
+    p8 = ctypes.POINTER(ctypes.c_int8)
+    rc = lib().orc_conv2d_i8(x.ctypes.data_as(p8), N, H, W, Cin, w.ctypes.data_as(p8), _p(scale),
+                             _p(bias), Cout, Kh, Kw, stride, pad, int(bool(relu)),
+                             out.ctypes.data_as(p8), acc.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    if rc != 0:
+        raise OverflowError("an accumulator left the 32-bit range")
+    return (out, acc) if return_acc else out
 
 
 def fc(x, w, b=None, acc="f32"):

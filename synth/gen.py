@@ -56,3 +56,28 @@ def make_params(net, batch, seed=MASTER_SEED, residual_gain=RESIDUAL_BRANCH_GAIN
         else:
             biases.append(None)
     return x, weights, biases
+
+
+def make_i8_layer(batch, h, w, cin, cout, k=3, seed=MASTER_SEED, full_range=False):
+    """Seeded operands of one quantised convolution layer: (x int8 [batch,h,w,cin], weight int8
+    [cout,k,k,cin], scale fp32 [cout], bias fp32 [cout]).
+
+    Recipe: activations round(16 * N(0,1)) and weights round(24 * N(0,1)), clipped to [-127, 127]
+    (`full_range`: both uniform over [-128, 127], the largest accumulators the format allows);
+    the per-channel scale brings the accumulator's spread (sqrt(k*k*cin) * 16 * 24) to about 48
+    output steps, times U(0.5, 1.5), so that outputs use the int8 range and a few per cent
+    saturate; bias ~U(-8, 8)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    if full_range:
+        x = rng.integers(-128, 128, size=(batch, h, w, cin), dtype=np.int64).astype(np.int8)
+        wt = rng.integers(-128, 128, size=(cout, k, k, cin), dtype=np.int64).astype(np.int8)
+        spread = np.sqrt(k * k * cin) * 74.0 * 74.0
+    else:
+        x = np.clip(np.rint(rng.standard_normal(size=(batch, h, w, cin), dtype=np.float32) * 16.0),
+                    -127, 127).astype(np.int8)
+        wt = np.clip(np.rint(rng.standard_normal(size=(cout, k, k, cin), dtype=np.float32) * 24.0),
+                     -127, 127).astype(np.int8)
+        spread = np.sqrt(k * k * cin) * 16.0 * 24.0
+    scale = (48.0 / spread * rng.uniform(0.5, 1.5, size=(cout,))).astype(np.float32)
+    bias = rng.uniform(-8.0, 8.0, size=(cout,)).astype(np.float32)
+    return x, wt, scale, bias
