@@ -16,6 +16,9 @@ OP = {"conv": 0, "dwconv": 1, "fc": 2, "maxpool": 3, "gavgpool": 4}
 ACT = {"none": 0, "relu": 1, "relu6": 2}
 TUNER_DP, TUNER_GREEDY, TUNER_MANUAL, TUNER_LAYERWISE, TUNER_MAXFUSE = 0, 1, 2, 3, 4
 DLF_OK = 0
+DLF_ERR_INVALID_ARG = 1
+DLF_ERR_SHAPE = 2
+DLF_ERR_UNSUPPORTED = 3
 DLF_ERR_INFEASIBLE = 4
 DLF_ERR_OOM = 5
 DLF_ERR_HIP = 6
@@ -128,6 +131,14 @@ def lib():
     L.dlf_plan_refine.restype = i32
     L.dlf_plan_group_io.argtypes = [vp, i32, i32p, i32p]
     L.dlf_plan_group_io.restype = i32
+    L.dlf_i8conv_create.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, i32, ctypes.POINTER(vp)]
+    L.dlf_i8conv_create.restype = i32
+    L.dlf_i8conv_destroy.argtypes = [vp]
+    L.dlf_i8conv_destroy.restype = None
+    L.dlf_i8conv_info.argtypes = [vp, i32p, i32p, i32p, i32p, u64p]
+    L.dlf_i8conv_info.restype = i32
+    L.dlf_i8conv_run.argtypes = [vp, vp, vp, vp]
+    L.dlf_i8conv_run.restype = i32
     _lib = L
     return L
 
@@ -300,6 +311,39 @@ def dlf_run_group(plan, g, in_ptr, res_ptr, out_ptr, stream=None):
 
 def dlf_plan_layer_output(plan, layer):
     return lib().dlf_plan_layer_output(plan, layer)
+
+
+def dlf_i8conv_create(batch, h, w, cin, cout, relu, weight=None, scale=None, bias=None, budget=0):
+    """weight: numpy int8 [cout,3,3,cin] (None: shape-only layer), scale / bias: numpy fp32 [cout]."""
+    out = ctypes.c_void_p()
+    wp = sp = bp = None
+    if weight is not None:
+        weight = np.ascontiguousarray(weight, dtype=np.int8)
+        scale = np.ascontiguousarray(scale, dtype=np.float32)
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+        if weight.shape != (cout, 3, 3, cin) or scale.shape != (cout,) or bias.shape != (cout,):
+            raise ValueError("weight [cout,3,3,cin], scale [cout], bias [cout] expected")
+        wp, sp, bp = weight.ctypes.data, scale.ctypes.data, bias.ctypes.data
+    _check(lib().dlf_i8conv_create(batch, h, w, cin, cout, int(bool(relu)), wp, sp, bp, budget,
+                                   ctypes.byref(out)))
+    return out
+
+
+def dlf_i8conv_destroy(layer):
+    lib().dlf_i8conv_destroy(layer)
+
+
+def dlf_i8conv_info(layer):
+    """-> dict(th, tw, shape, grid, op_count)."""
+    th, tw, sh, gr = (ctypes.c_int32() for _ in range(4))
+    ops = ctypes.c_uint64()
+    _check(lib().dlf_i8conv_info(layer, ctypes.byref(th), ctypes.byref(tw), ctypes.byref(sh),
+                                 ctypes.byref(gr), ctypes.byref(ops)))
+    return dict(th=th.value, tw=tw.value, shape=sh.value, grid=gr.value, op_count=ops.value)
+
+
+def dlf_i8conv_run(layer, in_ptr, out_ptr, stream=None):
+    _check(lib().dlf_i8conv_run(layer, in_ptr, out_ptr, stream))
 
 
 def dlf_cost_model_version():

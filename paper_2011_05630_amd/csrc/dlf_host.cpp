@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstring>
 #include <limits>
+#include <memory>
 #include <mutex>
 #include <new>
 #include <string>
@@ -2800,6 +2801,116 @@ static dlf_status static_workspace(char** base)
         ptr[dev] = p;
     }
     *base = (char*)ptr[dev];
+    return DLF_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Quantised (int8) 3x3 convolution layer on the block kernel
+// ------------------------------------------------------------------------------------------
+
+struct dlf_i8conv_s {
+    DlfC3Args ca;
+    int shape = 0, grid = 0, lds_bytes = 0;
+    uint64_t ops = 0;
+    void* d_w = nullptr;
+    float* d_scale = nullptr;
+    float* d_bias = nullptr;
+};
+
+void dlf_i8conv_destroy(dlf_i8conv_t* l)
+{
+    if (!l) return;
+    if (l->d_w) (void)hipFree(l->d_w);
+    if (l->d_scale) (void)hipFree(l->d_scale);
+    if (l->d_bias) (void)hipFree(l->d_bias);
+    delete l;
+}
+
+dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, int32_t cout, int32_t relu,
+                             const int8_t* weight, const float* scale, const float* bias, int32_t budget,
+                             dlf_i8conv_t** out)
+{
+    if (!out) return fail(DLF_ERR_INVALID_ARG, "dlf_i8conv_create: null out pointer");
+    if (batch < 1 || h < 1 || w < 1 || cin < 1 || cout < 1 || h > (1 << 20) || w > (1 << 20) || cin > (1 << 20) ||
+        cout > (1 << 20))
+        return fail(DLF_ERR_INVALID_ARG, "dlf_i8conv_create: sizes out of range");
+    if (weight && (!scale || !bias)) return fail(DLF_ERR_INVALID_ARG, "dlf_i8conv_create: weights without scale / bias");
+    if ((cin % 64) != 0 || (cout % 16) != 0)
+        return fail(DLF_ERR_UNSUPPORTED, "the int8 layer needs cin %% 64 == 0 and cout %% 16 == 0");
+    if ((int64_t)batch * h * w * cin >= (int64_t)1 << 31 || (int64_t)batch * h * w * cout >= (int64_t)1 << 31)
+        return fail(DLF_ERR_UNSUPPORTED, "the int8 layer needs tensors below 2 GiB");
+    if (budget <= 0 || budget > 256) budget = 256;
+    // to the operand path an int8 tensor of cin channels is an fp16 tensor of cin / 2
+    Layer L;
+    memset(&L.d, 0, sizeof L.d);
+    L.d.op = DLF_CONV; L.d.cin = cin / 2; L.d.cout = cout; L.d.kh = L.d.kw = 3; L.d.stride = 1; L.d.pad = 1;
+    L.d.residual_from = -1; L.d.input_from = -1;
+    L.in_h = L.out_h = h; L.in_w = L.out_w = w; L.in_c = cin / 2; L.out_c = cout;
+    L.kc = 32; L.cin_pad = cin / 2; L.ncb = ceil_div(cout, 32); L.nsteps = (L.cin_pad / 32) * 9 * 2;
+    C3Cfg cc;
+    uint64_t cost = 0;
+    if (g_c3_force.shape >= 0 && g_c3_force.shape < DLF_C3_SHAPES) {      // testing hook: shape and tile as given
+        if (!c3_build(0, L.d.cin, g_c3_force.shape, g_c3_force.th, g_c3_force.tw, 160 * 1024, cc))
+            return fail(DLF_ERR_INFEASIBLE, "the forced shape and tile do not fit this layer");
+    } else if (!c3_choose(L, 0, batch, budget, 160 * 1024, cc, cost))
+        return fail(DLF_ERR_INFEASIBLE, "no tile of the block kernel fits this layer");
+    std::unique_ptr<dlf_i8conv_s> l(new dlf_i8conv_s);
+    DlfC3Args& ca = l->ca;
+    memset(&ca, 0, sizeof ca);
+    ca.batch = batch; ca.h = h; ca.w_ = w; ca.cin = cin / 2; ca.cout = cout;
+    ca.ncb = L.ncb; ca.nsteps = L.nsteps; ca.act = relu ? 1 : 0; ca.pool2 = 0;
+    ca.th = cc.th; ca.tw = cc.tw;
+    ca.tiles_y = ceil_div(h, cc.th); ca.tiles_x = ceil_div(w, cc.tw);
+    ca.n_cg = ceil_div(L.ncb, 2 * C3_WC[cc.shape]);
+    ca.ntiles = batch * ca.tiles_y * ca.tiles_x;
+    ca.nitems = ca.n_cg * ca.ntiles;
+    ca.npxh = cc.npxh; ca.na_i = cc.na_i; ca.lpw_a = cc.lpw_a; ca.nst = cc.nst;
+    l->shape = cc.shape;
+    l->grid = std::max(8, std::min(budget, ceil_div(ca.nitems, 8) * 8) / 8 * 8);
+    l->lds_bytes = cc.lds_bytes;
+    l->ops = (uint64_t)2 * batch * h * w * 9 * (uint64_t)cin * cout;
+    if (weight) {
+        std::vector<uint16_t> packed;
+        pack_conv_weights((const uint16_t*)weight, cout, 9, cin / 2, 32, cin / 2, packed);
+        dlf_status s = upload(packed.data(), packed.size() * 2, &l->d_w);
+        if (s != DLF_OK) { dlf_i8conv_destroy(l.release()); return s; }
+        std::vector<float> sc((size_t)L.ncb * 32, 0.0f), bi((size_t)L.ncb * 32, 0.0f);
+        std::copy(scale, scale + cout, sc.begin());
+        std::copy(bias, bias + cout, bi.begin());
+        s = upload(sc.data(), sc.size() * 4, (void**)&l->d_scale);
+        if (s == DLF_OK) s = upload(bi.data(), bi.size() * 4, (void**)&l->d_bias);
+        if (s != DLF_OK) { dlf_i8conv_destroy(l.release()); return s; }
+        ca.w = l->d_w; ca.scale = l->d_scale; ca.bias = l->d_bias;
+    }
+    *out = l.release();
+    return DLF_OK;
+}
+
+dlf_status dlf_i8conv_info(const dlf_i8conv_t* l, int32_t* th, int32_t* tw, int32_t* shape, int32_t* grid,
+                           uint64_t* op_count)
+{
+    if (!l) return fail(DLF_ERR_INVALID_ARG, "dlf_i8conv_info: null layer");
+    if (th) *th = l->ca.th;
+    if (tw) *tw = l->ca.tw;
+    if (shape) *shape = l->shape;
+    if (grid) *grid = l->grid;
+    if (op_count) *op_count = l->ops;
+    return DLF_OK;
+}
+
+dlf_status dlf_i8conv_run(const dlf_i8conv_t* l, const void* in_dev, void* out_dev, void* hip_stream)
+{
+    if (!l || !in_dev || !out_dev) return fail(DLF_ERR_INVALID_ARG, "dlf_i8conv_run: null argument");
+    if (!l->d_w) return fail(DLF_ERR_NO_WEIGHTS, "the layer was created without weights");
+    if ((((uintptr_t)in_dev | (uintptr_t)out_dev) & 15) != 0)
+        return fail(DLF_ERR_INVALID_ARG, "dlf_i8conv_run: tensors must be 16-byte aligned");
+    std::call_once(g_kernels_once, [] { g_kernels_rc = dlf_kernels_init(); });
+    if (g_kernels_rc != 0)
+        return fail(DLF_ERR_HIP, "kernel setup failed: %s", hipGetErrorString((hipError_t)g_kernels_rc));
+    DlfC3Args ca = l->ca;
+    ca.in = in_dev; ca.out = out_dev;
+    const int e = dlf_launch_c3_i8(&ca, l->shape, l->grid, l->lds_bytes, hip_stream);
+    if (e != 0) return fail(DLF_ERR_HIP, "launch of the int8 layer failed: %s", hipGetErrorString((hipError_t)e));
     return DLF_OK;
 }
 

@@ -148,6 +148,8 @@ struct DlfC3Args {
     int32_t na_i;         // ceil(npxh / (512 / ACH)): activation load instructions per block (1 KiB each)
     int32_t lpw_a;        // ceil(na_i / DLF_C3_LOAD_WAVES): ... per requesting wave
     int32_t nst;          // stages in the weight ring (2 .. 4)
+    // quantised form only (int8 tensors, `cin` = byte pairs per pixel, `act` != 0 = ReLU):
+    const float* scale;   // requantisation scale per output channel, padded to ncb*32
 };
 
 // Depthwise 3x3 convolution (pad 1, stride 1 or 2) as a streaming kernel without LDS or barriers:
@@ -373,6 +375,7 @@ int dlf_launch_fc(const DlfFcArgs* a, void* stream);
 int dlf_launch_gap(const DlfGapArgs* a, void* stream);
 int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stream);
 int dlf_launch_c3(const DlfC3Args* a, int shape, int grid, int lds_bytes, void* stream);
+int dlf_launch_c3_i8(const DlfC3Args* a, int shape, int grid, int lds_bytes, void* stream);
 int dlf_launch_dw(const DlfDwArgs* a, int grid, void* stream);
 int dlf_launch_dwpw(const DlfDwPwArgs* a, int nb, int grid, void* stream);
 int dlf_launch_dwt(const DlfDwtArgs* a, int grid, int lds_bytes, void* stream);

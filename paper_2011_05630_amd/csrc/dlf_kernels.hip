@@ -32,6 +32,9 @@ extern __shared__ __attribute__((aligned(16))) half_t lds[];
 // below 2 GiB): a buffer load at this offset fails the hardware's range check and returns zeros.
 #define DLF_OOB ((int)0x80000000)
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i16v __attribute__((ext_vector_type(16)));
+template <bool I8> struct AccOf { typedef f16v type; };
+template <> struct AccOf<true> { typedef i16v type; };
 __device__ i32x4 raw_buffer_load_x4(i32x4 rsrc, int voffset, int soffset, int aux) __asm("llvm.amdgcn.raw.buffer.load.v4i32");
 __device__ __forceinline__ i32x4 make_rsrc(const void* p, unsigned bytes)
 {
@@ -1756,9 +1759,19 @@ __device__ __forceinline__ void wait_vmcnt_dyn(int n)
 // 1 byte per ~200 FLOP, against ~50-100 for the per-wave weight streams of the fused-group kernel.
 // Work items: channel group slowest, so that the workgroups running at one time share weights; each
 // XCD gets a contiguous range of items.
-template <int WC, int ACH, int FP>
+//
+// I8: the quantised form of the same layer.  An int8 tensor of C channels has the bytes of an fp16
+// tensor of C / 2 channels, and v_mfma_i32_32x32x32_i8 takes its operands as the fp16 instruction
+// does (16 bytes per lane, the two halves of the wave the two halves of a K step), so the operand
+// path above serves as it stands with `cin` counting byte pairs: one K step is 32 int8 channels.
+// What differs: exact int32 accumulators that start at zero, and an epilogue that requantises --
+// (float)acc, one fused multiply-add with the channel's scale and bias, round half to even, clamp
+// to [-128 or 0, 127] -- and stores int8, four lanes of 16 bytes covering a wave's 64 channels of
+// a pixel.  No pool, no residual operand in this form.
+template <int WC, int ACH, int FP, bool I8 = false>
 __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
 {
+    using acc_t = typename AccOf<I8>::type;
     constexpr int NCBW = 2 * WC;                     // 32-channel blocks of the workgroup
     constexpr int NWF = 9 * NCBW;                    // weight fragments per stage
     constexpr int LW = DLF_C3_LOAD_WAVES;              // waves that request operands (one per SIMD)
@@ -1902,17 +1915,24 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
 
     for (;;) {
         // accumulators start at the bias
-        f16v acc[2][FP];
+        acc_t acc[2][FP];
 #pragma unroll
         for (int f = 0; f < 2; ++f) {
             const int cb = min(cg * NCBW + wc * 2 + f, a.ncb - 1);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const f4v bv = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
+                if constexpr (I8) {
 #pragma unroll
-                for (int p = 0; p < FP; ++p)
+                    for (int p = 0; p < FP; ++p)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[f][p][q * 4 + r] = bv[r];
+                        for (int r = 0; r < 4; ++r) acc[f][p][q * 4 + r] = 0;
+                } else {
+                    const f4v bv = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
+#pragma unroll
+                    for (int p = 0; p < FP; ++p)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) acc[f][p][q * 4 + r] = bv[r];
+                }
             }
         }
 
@@ -1987,7 +2007,11 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
                     constexpr int kk = decltype(kc)::value, f = kk / FP, p = kk % FP;
                     if constexpr (f == 0 && p > 0) lds_arrive1<more ? FP + 1 : FP - p>(bf[cur][p]);
                     if constexpr (f == 1 && p == 0) lds_arrive1<more ? FP + 1 : 0>(af[cur][1]);
-                    acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][f], bf[cur][p], acc[f][p], 0, 0, 0);
+                    if constexpr (I8)
+                        acc[f][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4, af[cur][f]),
+                                                                          __builtin_bit_cast(i32x4, bf[cur][p]), acc[f][p], 0, 0, 0);
+                    else
+                        acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][f], bf[cur][p], acc[f][p], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
                     if constexpr (more) {
                         if constexpr (kk == 0) {
@@ -2018,6 +2042,52 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
         // Epilogue, in passes of R pixels per wave through a transpose buffer in the last slot of
         // the weight ring, which the first stages of the next item do not touch: fp16, (pool),
         // activation; then 16 bytes per lane, 8 lanes covering the wave's 64 channels of a pixel.
+        if constexpr (I8) {
+            // Quantised form: a pass per 32-pixel block.  A lane holds, per channel block f and q, four
+            // consecutive channels of its pixel: one dword of the pixel's 64-byte row in the wave's
+            // transpose buffer (rows of 64 bytes, the 16-byte part c of row r at c ^ (r % 4)); then lane
+            // 4 r + c stores part c of row r.
+            static_assert(DLF_C3_WAVES * 32 * 64 <= W_HALFS * 2, "the transpose buffers fit one slot of the ring");
+            unsigned char* tb8 = (unsigned char*)(wring + (nst - 1) * W_HALFS) + wave * (32 * 64);
+            signed char* out8 = (signed char*)a.out;
+            const float lo = a.act != 0 ? 0.0f : -128.0f;
+            const int part = lane & 3;
+            const int cch = (e_cg * NCBW + wc * 2) * 32 + part * 16;
+#pragma unroll
+            for (int p = 0; p < FP; ++p) {
+#pragma unroll
+                for (int f = 0; f < 2; ++f) {
+                    const int cb = min(e_cg * NCBW + wc * 2 + f, a.ncb - 1);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f4v sv = *(const f4v*)(a.scale + cb * 32 + q * 8 + lhi * 4);
+                        const f4v bv = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
+                        unsigned u = 0;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            float t = __builtin_fmaf((float)acc[f][p][q * 4 + r], sv[r], bv[r]);
+                            t = __builtin_rintf(t);
+                            t = __builtin_fminf(__builtin_fmaxf(t, lo), 127.0f);
+                            u |= ((unsigned)(int)t & 255u) << (8 * r);
+                        }
+                        const int c16 = f * 2 + (q >> 1);
+                        *(unsigned*)(tb8 + l32 * 64 + ((c16 ^ (l32 & 3)) << 4) + (q & 1) * 8 + lhi * 4) = u;
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int it = 0; it < 2; ++it) {
+                    const int row = it * 16 + (lane >> 2);
+                    const int opix = wp * (32 * FP) + p * 32 + row;
+                    const int ry = div_by(opix, tw_m), rx = opix - ry * a.tw;
+                    const int gy = e_ty0 + ry, gx = e_tx0 + rx;
+                    const bool ok = opix < npix && gy < a.h && gx < a.w_ && cch < a.cout;
+                    const u4v v = *(const u4v*)(tb8 + row * 64 + ((part ^ (row & 3)) << 4));
+                    if (ok) *(u4v*)(out8 + (size_t)((e_n * a.h + gy) * a.w_ + gx) * (size_t)a.cout + cch) = v;
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        } else {
         constexpr int R = (W_HALFS / (DLF_C3_WAVES * ROW)) >= 32 ? 32 : 16;
         static_assert(DLF_C3_WAVES * R * ROW <= W_HALFS, "the transpose buffers fit one slot of the ring");
         half_t* tb = wring + (nst - 1) * W_HALFS + wave * (R * ROW);
@@ -2085,6 +2155,7 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
                 }
             }
             __builtin_amdgcn_wave_barrier();
+        }
         }
         if (!more) break;
         // this item's stores must not be counted among the loads of the next item's ring
@@ -3887,6 +3958,17 @@ static c3_kernel_t c3_kernel(int shape)
     default: return nullptr;
     }
 }
+static c3_kernel_t c3_kernel_i8(int shape)
+{
+    switch (shape) {
+    case 0: return k_c3b<2, 32, 2, true>;
+    case 1: return k_c3b<2, 64, 2, true>;
+    case 2: return k_c3b<1, 32, 2, true>;
+    case 3: return k_c3b<1, 64, 2, true>;
+    case 4: return k_c3b<2, 32, 4, true>;
+    default: return nullptr;
+    }
+}
 
 extern "C" int dlf_kernels_init(void)
 {
@@ -3928,9 +4010,9 @@ extern "C" int dlf_kernels_init(void)
             if (e != hipSuccess) return (int)e;
         }
     }
-    for (int sh = 0; sh < DLF_C3_SHAPES; ++sh) {
-        hipError_t e = hipFuncSetAttribute((const void*)c3_kernel(sh), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           160 * 1024);
+    for (int sh = 0; sh < 2 * DLF_C3_SHAPES; ++sh) {
+        const c3_kernel_t k = sh < DLF_C3_SHAPES ? c3_kernel(sh) : c3_kernel_i8(sh - DLF_C3_SHAPES);
+        hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return (int)e;
     }
     return 0;
@@ -3940,6 +4022,16 @@ extern "C" int dlf_launch_c3(const DlfC3Args* a, int shape, int grid, int lds_by
 {
     c3_kernel_t k = c3_kernel(shape);
     if (k == nullptr || grid < 8 || (grid & 7) != 0 || lds_bytes <= 0) return (int)hipErrorInvalidValue;
+    launch(k, dim3(grid), dim3(DLF_C3_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
+    return (int)hipGetLastError();
+}
+
+extern "C" int dlf_launch_c3_i8(const DlfC3Args* a, int shape, int grid, int lds_bytes, void* stream)
+{
+    c3_kernel_t k = c3_kernel_i8(shape);
+    if (k == nullptr || grid < 8 || (grid & 7) != 0 || lds_bytes <= 0 || a->scale == nullptr || a->res != nullptr ||
+        a->pool2 != 0 || (a->cout & 15) != 0)
+        return (int)hipErrorInvalidValue;
     launch(k, dim3(grid), dim3(DLF_C3_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
     return (int)hipGetLastError();
 }

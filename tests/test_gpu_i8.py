@@ -1,0 +1,95 @@
+"""The quantised (int8) 3x3 convolution layer of libdlf against the integer oracle, bit for bit:
+the library's own choice of kernel shape and tile on maps that span several tiles with ragged
+edges and ragged channel blocks, every kernel shape forced, operands over the whole int8 range,
+and a chain of four layers each fed the previous one's int8 output."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import announce
+from synth import gen
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(x, wt, sc, b, relu, budget=0):
+    from paper_2011_05630_amd import binding as B
+    n, h, w, cin = x.shape
+    cout = wt.shape[0]
+    layer = B.dlf_i8conv_create(n, h, w, cin, cout, relu, wt, sc, b, budget)
+    try:
+        info = B.dlf_i8conv_info(layer)
+        xt = torch.from_numpy(x).cuda()
+        out = torch.full((n, h, w, cout), 0x55, dtype=torch.int8, device="cuda")
+        guard = out.clone()
+        B.dlf_i8conv_run(layer, xt.data_ptr(), out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        return out.cpu().numpy(), info
+    finally:
+        B.dlf_i8conv_destroy(layer)
+
+
+def _check(case, x, wt, sc, b, relu, budget=0):
+    from oracle import oracle
+    announce("i8conv", case, x.shape, "cout", wt.shape[0], "relu", relu)
+    got, info = _run(x, wt, sc, b, relu, budget)
+    ref = oracle.conv2d_i8(x, wt, sc, b, 1, 1, relu)
+    bad = np.argwhere(got != ref)
+    assert bad.size == 0, (case, info, len(bad), bad[:5].tolist(),
+                           [(int(got[tuple(i)]), int(ref[tuple(i)])) for i in bad[:5]])
+    if ref.size >= 4096:
+        assert ref.min() <= (0 if relu else -100) and ref.max() >= 100      # the case exercises the range
+    return info
+
+
+CASES = [  # batch, h, w, cin, cout, relu
+    (2, 20, 27, 64, 48, False),
+    (1, 14, 14, 128, 128, True),
+    (3, 9, 33, 64, 80, True),
+    (1, 56, 56, 256, 256, True),
+    (2, 28, 28, 192, 144, False),
+    (1, 7, 7, 512, 512, True),
+    (1, 1, 1, 64, 16, False),
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_i8conv_equals_oracle(case):
+    n, h, w, cin, cout, relu = case
+    x, wt, sc, b = gen.make_i8_layer(n, h, w, cin, cout, 3, seed=1000 + h * w + cin)
+    _check(case, x, wt, sc, b, relu)
+
+
+def test_i8conv_full_range_operands():
+    x, wt, sc, b = gen.make_i8_layer(2, 12, 18, 128, 96, 3, seed=31, full_range=True)
+    x[0, :2] = -128
+    wt[:4] = -128                     # the largest products the format allows, accumulators above 2^24
+    _check("full range", x, wt, sc, b, False)
+    _check("full range relu", x, wt, sc, b, True)
+
+
+@pytest.mark.parametrize("shape,th,tw,cin", [(0, 8, 16, 64), (1, 14, 14, 128), (2, 16, 28, 64), (3, 14, 28, 128),
+                                             (4, 16, 32, 64), (0, 7, 7, 192), (4, 14, 28, 128)])
+def test_i8conv_every_kernel_shape(shape, th, tw, cin):
+    from paper_2011_05630_amd import binding as B
+    x, wt, sc, b = gen.make_i8_layer(2, 30, 37, cin, 160, 3, seed=50 + shape)
+    B.dlf_debug_block3x3_mode(0, shape, th, tw)
+    try:
+        info = _check(("shape", shape, th, tw), x, wt, sc, b, True, budget=64)
+    finally:
+        B.dlf_debug_block3x3_mode(0, -1, 0, 0)
+    assert (info["shape"], info["th"], info["tw"]) == (shape, th, tw)
+
+
+def test_i8_chain_of_four_layers():
+    from oracle import oracle
+    n, hw, c = 2, 28, 256
+    x, _, _, _ = gen.make_i8_layer(n, hw, hw, c, c, 3, seed=7)
+    got, ref = x, x
+    for i in range(4):
+        _, wt, sc, b = gen.make_i8_layer(1, 1, 1, c, c, 3, seed=70 + i)
+        announce("i8 chain layer", i)
+        got, _ = _run(got, wt, sc, b, True)
+        ref = oracle.conv2d_i8(ref, wt, sc, b, 1, 1, True)
+        assert np.array_equal(got, ref), "layer %d" % i
+    assert ref.max() > 50
