@@ -22,6 +22,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA
+MFMA_INT8_PEAK_TOPS = 5000.0    # MI355X dense int8 MFMA
 RIDGE = MFMA_FP16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # FLOP per byte
 
 # HBM bytes per launch of a workload's kernels, from two `rocprofv3 --pmc` runs of this file
@@ -333,6 +334,61 @@ def sweep_chain4(steps, warmup):
                     sys.stdout.flush()
 
 
+I8_LAYERS = [  # name, batch, h = w, cin = cout: the 3x3 layers of VGG-16 (from 64 channels on) and of the chain of configuration 2
+    ("vgg_conv1_2", 16, 224, 64), ("vgg_conv2_2", 16, 112, 128), ("vgg_conv3_2", 16, 56, 256),
+    ("vgg_conv4_2", 16, 28, 512), ("vgg_conv5_2", 16, 14, 512), ("chain4_c256", 8, 56, 256),
+]
+
+
+def bench_i8(steps, warmup, cpu=True, layers=None):
+    """The quantised (int8) 3x3 layer: us per launch (events on the launch stream around `steps`
+    launches back to back), TOP/s by Eq. 1, fraction of the int8 MFMA peak, the same layer in
+    fp16 on the block kernel beside it, and the integer oracle on a bounded sample of one layer."""
+    import torch
+    from synth import gen, nets
+    from paper_2011_05630_amd import binding as B
+    out = {}
+    stream = torch.cuda.current_stream().cuda_stream
+    for name, batch, hw, c in (layers or I8_LAYERS):
+        x, wt, sc, b = gen.make_i8_layer(batch, hw, hw, c, c, 3)
+        layer = B.dlf_i8conv_create(batch, hw, hw, c, c, 3, True, wt, sc, b, 0)
+        info = B.dlf_i8conv_info(layer)
+        xt = torch.from_numpy(x).cuda()
+        yt = torch.empty((batch, hw, hw, c), dtype=torch.int8, device="cuda")
+        for _ in range(warmup):
+            B.dlf_i8conv_run(layer, xt.data_ptr(), yt.data_ptr(), stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            B.dlf_i8conv_run(layer, xt.data_ptr(), yt.data_ptr(), stream)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / steps
+        B.dlf_i8conv_destroy(layer)
+        tops = info["op_count"] / (us * 1e-6) / 1e12
+        nbytes = 2 * batch * hw * hw * c + 9 * c * c
+        rec = dict(batch=batch, hw=hw, channels=c, us=us, tops=tops, frac_int8_mfma_peak=tops / MFMA_INT8_PEAK_TOPS,
+                   gbs=nbytes / (us * 1e-6) / 1e9, tile="%dx%d" % (info["th"], info["tw"]), kernel_shape=info["shape"])
+        # the same layer in fp16 (one group, the library's own choice of kernel)
+        net = dict(name=name, layers=[nets.conv(c, c, 3, 1, 1, "relu")], in_h=hw, in_w=hw, in_c=c, input_dist="normal")
+        r = time_plan(net, batch, dict(mode=B.TUNER_DP), steps, warmup)
+        rec["fp16_us"] = r["ms_per_step"] * 1e3
+        rec["fp16_kernel"] = r["acct"][0]["kernel"]
+        rec["speedup_over_fp16"] = rec["fp16_us"] / us
+        out[name] = rec
+        del r
+    if cpu:
+        from oracle import oracle as o
+        x, wt, sc, b = gen.make_i8_layer(1, 56, 56, 256, 256, 3)
+        t = time.perf_counter()
+        o.conv2d_i8(x, wt, sc, b, 1, 1, True)
+        dt = time.perf_counter() - t
+        out["cpu_baseline"] = dict(value=2 * 56 * 56 * 9 * 256 * 256 / dt / 1e12, unit="TOP/s", cores=o.num_threads(),
+                                   kind="oracle", sample="one image of the 56 x 56 x 256 -> 256 layer")
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -359,6 +415,9 @@ def main():
                     help="skip the side measurements (VGG-16 b16, MobileNet-v1 b64, ResNet-50 b1) of the default run")
     ap.add_argument("--sweep", default="", choices=["", "chain4"],
                     help="chain4: the fusion-depth x budget sweep of the 4-layer chains, a table on stdout")
+    ap.add_argument("--i8", action="store_true",
+                    help="the quantised (int8) 3x3 layer on VGG-16's layer shapes: one JSON line")
+    ap.add_argument("--i8-layer", default="", help="with --i8: only this layer (a name of I8_LAYERS)")
     ap.add_argument("--calib-copy", type=int, default=0,
                     help="run this many plain 256 MiB device copies first (reference dispatches of "
                          "known size for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -384,6 +443,12 @@ def main():
         return
     if args.sweep == "chain4":
         sweep_chain4(min(args.steps, 50), min(args.warmup, 10))
+        return
+    if args.i8:
+        print(json.dumps({"metric": "int8_conv3x3_tops", "unit": "TOP/s", "dtype": "i8", "data": "synthetic",
+                          "peak_tops": MFMA_INT8_PEAK_TOPS, "steps": min(args.steps, 100),
+                          "layers": bench_i8(min(args.steps, 100), min(args.warmup, 10), cpu=not args.no_cpu,
+                                             layers=[l for l in I8_LAYERS if l[0] == args.i8_layer] or None)}))
         return
 
     from paper_2011_05630_amd import binding as B
@@ -460,6 +525,8 @@ def main():
                 print("--- %s" % name, file=sys.stderr)
                 print_table(sr["acct"], sum(a["ms"] for a in sr["acct"]), sr["ms_per_step"])
             del sr
+        i8 = bench_i8(side_steps, min(args.warmup, 10), cpu=False, layers=[I8_LAYERS[2]])
+        extra["i8_conv3x3_256_56x56_b16"] = i8[I8_LAYERS[2][0]]
 
     cpu = None
     if not args.no_cpu:

@@ -229,24 +229,24 @@ dlf_status dlf_plan_refine(dlf_plan_t* plan, const void* in_dev, void* out_dev, 
 
 /* ---- Quantised (int8) convolution layer ------------------------------------------------------
  * The paper's chip offers an INT8 mode beside FP16 (table of the MLU100's specification); the paper
- * fixes no quantisation scheme.  This is one 3x3 convolution layer (stride 1, zero padding 1) on the
- * int8 matrix instructions, with the usual integer scheme:
+ * fixes no quantisation scheme.  This is one convolution layer, ksize = 3 (stride 1, zero padding 1)
+ * or ksize = 1 (stride 1, no padding), on the int8 matrix instructions, with the usual integer scheme:
  *   acc = sum over taps and input channels of in * w, exact, in 32-bit integers;
  *   out = clamp(round_half_even(fma((float)acc, scale[co], bias[co])), relu ? 0 : -128, 127)
  * with one fp32 fused multiply-add per output ((float) rounds to nearest even above 2^24).  The
  * caller guarantees |acc| < 2^31 (always true for cin <= 14000).
  * Tensors: in_dev int8 [batch][h][w][cin], out_dev int8 [batch][h][w][cout], DEVICE, caller-owned,
- * 16-byte aligned, below 2 GiB each.  weight: HOST int8 [cout][3][3][cin]; scale, bias: HOST fp32
+ * 16-byte aligned, below 2 GiB each.  weight: HOST int8 [cout][ksize][ksize][cin]; scale, bias: HOST fp32
  * [cout]; all three borrowed for the call only (repacked into device buffers the layer owns).  With
  * weight == NULL (then scale and bias are ignored) the layer is shape-only: it can be queried but not
  * run, and needs no GPU.  cin % 64 == 0 and cout % 16 == 0, else DLF_ERR_UNSUPPORTED.
  * budget: compute units the layer may use (<= 0: all 256). */
 typedef struct dlf_i8conv_s dlf_i8conv_t;
-dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, int32_t cout, int32_t relu,
-                             const int8_t* weight, const float* scale, const float* bias, int32_t budget,
+dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, int32_t cout, int32_t ksize,
+                             int32_t relu, const int8_t* weight, const float* scale, const float* bias, int32_t budget,
                              dlf_i8conv_t** out);
 void dlf_i8conv_destroy(dlf_i8conv_t* layer);
-/* Tile (th x tw output pixels per work item), kernel shape index, workgroups launched, and the
+/* Tile (th x tw output pixels per work item; 1 x pixels for ksize = 1), kernel shape index, workgroups launched, and the
  * operation count of Eq. 1 for the whole batch.  Any out pointer may be NULL. */
 dlf_status dlf_i8conv_info(const dlf_i8conv_t* layer, int32_t* th, int32_t* tw, int32_t* shape, int32_t* grid,
                            uint64_t* op_count);

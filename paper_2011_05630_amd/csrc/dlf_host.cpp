@@ -2805,11 +2805,14 @@ static dlf_status static_workspace(char** base)
 }
 
 // ------------------------------------------------------------------------------------------
-// Quantised (int8) 3x3 convolution layer on the block kernel
+// Quantised (int8) convolution layer on the block kernels (3x3: k_c3b, 1x1: k_pwb)
 // ------------------------------------------------------------------------------------------
 
 struct dlf_i8conv_s {
+    int ksize = 3;
     DlfC3Args ca;
+    DlfPwArgs wa;
+    int th = 0, tw = 0;
     int shape = 0, grid = 0, lds_bytes = 0;
     uint64_t ops = 0;
     void* d_w = nullptr;
@@ -2826,8 +2829,8 @@ void dlf_i8conv_destroy(dlf_i8conv_t* l)
     delete l;
 }
 
-dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, int32_t cout, int32_t relu,
-                             const int8_t* weight, const float* scale, const float* bias, int32_t budget,
+dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, int32_t cout, int32_t ksize,
+                             int32_t relu, const int8_t* weight, const float* scale, const float* bias, int32_t budget,
                              dlf_i8conv_t** out)
 {
     if (!out) return fail(DLF_ERR_INVALID_ARG, "dlf_i8conv_create: null out pointer");
@@ -2835,6 +2838,7 @@ dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, i
         cout > (1 << 20))
         return fail(DLF_ERR_INVALID_ARG, "dlf_i8conv_create: sizes out of range");
     if (weight && (!scale || !bias)) return fail(DLF_ERR_INVALID_ARG, "dlf_i8conv_create: weights without scale / bias");
+    if (ksize != 1 && ksize != 3) return fail(DLF_ERR_UNSUPPORTED, "the int8 layer is a 1x1 or a 3x3 convolution");
     if ((cin % 64) != 0 || (cout % 16) != 0)
         return fail(DLF_ERR_UNSUPPORTED, "the int8 layer needs cin %% 64 == 0 and cout %% 16 == 0");
     if ((int64_t)batch * h * w * cin >= (int64_t)1 << 31 || (int64_t)batch * h * w * cout >= (int64_t)1 << 31)
@@ -2843,20 +2847,38 @@ dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, i
     // to the operand path an int8 tensor of cin channels is an fp16 tensor of cin / 2
     Layer L;
     memset(&L.d, 0, sizeof L.d);
-    L.d.op = DLF_CONV; L.d.cin = cin / 2; L.d.cout = cout; L.d.kh = L.d.kw = 3; L.d.stride = 1; L.d.pad = 1;
+    const int taps = ksize * ksize;
+    L.d.op = DLF_CONV; L.d.cin = cin / 2; L.d.cout = cout; L.d.kh = L.d.kw = ksize; L.d.stride = 1; L.d.pad = ksize / 2;
     L.d.residual_from = -1; L.d.input_from = -1;
     L.in_h = L.out_h = h; L.in_w = L.out_w = w; L.in_c = cin / 2; L.out_c = cout;
-    L.kc = 32; L.cin_pad = cin / 2; L.ncb = ceil_div(cout, 32); L.nsteps = (L.cin_pad / 32) * 9 * 2;
+    L.kc = 32; L.cin_pad = cin / 2; L.ncb = ceil_div(cout, 32); L.nsteps = (L.cin_pad / 32) * taps * 2;
+    std::unique_ptr<dlf_i8conv_s> l(new dlf_i8conv_s);
+    l->ksize = ksize;
+    l->ops = (uint64_t)2 * batch * h * w * taps * (uint64_t)cin * cout;
+    memset(&l->ca, 0, sizeof l->ca);
+    memset(&l->wa, 0, sizeof l->wa);
     C3Cfg cc;
     uint64_t cost = 0;
+    if (ksize == 1) {
+        // the block pointwise kernel: 128 channels x 128 pixels per workgroup, or 64 x 256 for few channels
+        const int shape = pw_shape_ok(L, 3) ? 3 : 4;
+        DlfPwArgs& wa = l->wa;
+        wa.m = batch * h * w;
+        wa.cin = cin / 2; wa.cout = cout; wa.ncb = L.ncb; wa.nsteps = L.nsteps;
+        wa.act = relu ? 1 : 0; wa.stride = 1;
+        wa.in_h = wa.out_h = h; wa.in_w = wa.out_w = w;
+        wa.n_pg = ceil_div(wa.m, 32 * PW_FP[shape]); wa.n_cg = ceil_div(L.ncb, PW_FC[shape]);
+        wa.nitems = wa.n_pg * wa.n_cg;
+        l->shape = shape;
+        l->grid = std::max(8, std::min(budget * 2, ceil_div(wa.nitems, 8) * 8) / 8 * 8);
+        l->th = 1; l->tw = 32 * PW_FP[shape];
+    } else {
     if (g_c3_force.shape >= 0 && g_c3_force.shape < DLF_C3_SHAPES) {      // testing hook: shape and tile as given
         if (!c3_build(0, L.d.cin, g_c3_force.shape, g_c3_force.th, g_c3_force.tw, 160 * 1024, cc))
             return fail(DLF_ERR_INFEASIBLE, "the forced shape and tile do not fit this layer");
     } else if (!c3_choose(L, 0, batch, budget, 160 * 1024, cc, cost))
         return fail(DLF_ERR_INFEASIBLE, "no tile of the block kernel fits this layer");
-    std::unique_ptr<dlf_i8conv_s> l(new dlf_i8conv_s);
     DlfC3Args& ca = l->ca;
-    memset(&ca, 0, sizeof ca);
     ca.batch = batch; ca.h = h; ca.w_ = w; ca.cin = cin / 2; ca.cout = cout;
     ca.ncb = L.ncb; ca.nsteps = L.nsteps; ca.act = relu ? 1 : 0; ca.pool2 = 0;
     ca.th = cc.th; ca.tw = cc.tw;
@@ -2868,10 +2890,11 @@ dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, i
     l->shape = cc.shape;
     l->grid = std::max(8, std::min(budget, ceil_div(ca.nitems, 8) * 8) / 8 * 8);
     l->lds_bytes = cc.lds_bytes;
-    l->ops = (uint64_t)2 * batch * h * w * 9 * (uint64_t)cin * cout;
+    l->th = cc.th; l->tw = cc.tw;
+    }
     if (weight) {
         std::vector<uint16_t> packed;
-        pack_conv_weights((const uint16_t*)weight, cout, 9, cin / 2, 32, cin / 2, packed);
+        pack_conv_weights((const uint16_t*)weight, cout, taps, cin / 2, 32, cin / 2, packed);
         dlf_status s = upload(packed.data(), packed.size() * 2, &l->d_w);
         if (s != DLF_OK) { dlf_i8conv_destroy(l.release()); return s; }
         std::vector<float> sc((size_t)L.ncb * 32, 0.0f), bi((size_t)L.ncb * 32, 0.0f);
@@ -2880,7 +2903,9 @@ dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, i
         s = upload(sc.data(), sc.size() * 4, (void**)&l->d_scale);
         if (s == DLF_OK) s = upload(bi.data(), bi.size() * 4, (void**)&l->d_bias);
         if (s != DLF_OK) { dlf_i8conv_destroy(l.release()); return s; }
-        ca.w = l->d_w; ca.scale = l->d_scale; ca.bias = l->d_bias;
+        l->ca.w = l->wa.w = l->d_w;
+        l->ca.scale = l->wa.scale = l->d_scale;
+        l->ca.bias = l->wa.bias = l->d_bias;
     }
     *out = l.release();
     return DLF_OK;
@@ -2890,8 +2915,8 @@ dlf_status dlf_i8conv_info(const dlf_i8conv_t* l, int32_t* th, int32_t* tw, int3
                            uint64_t* op_count)
 {
     if (!l) return fail(DLF_ERR_INVALID_ARG, "dlf_i8conv_info: null layer");
-    if (th) *th = l->ca.th;
-    if (tw) *tw = l->ca.tw;
+    if (th) *th = l->th;
+    if (tw) *tw = l->tw;
     if (shape) *shape = l->shape;
     if (grid) *grid = l->grid;
     if (op_count) *op_count = l->ops;
@@ -2907,9 +2932,16 @@ dlf_status dlf_i8conv_run(const dlf_i8conv_t* l, const void* in_dev, void* out_d
     std::call_once(g_kernels_once, [] { g_kernels_rc = dlf_kernels_init(); });
     if (g_kernels_rc != 0)
         return fail(DLF_ERR_HIP, "kernel setup failed: %s", hipGetErrorString((hipError_t)g_kernels_rc));
-    DlfC3Args ca = l->ca;
-    ca.in = in_dev; ca.out = out_dev;
-    const int e = dlf_launch_c3_i8(&ca, l->shape, l->grid, l->lds_bytes, hip_stream);
+    int e;
+    if (l->ksize == 1) {
+        DlfPwArgs wa = l->wa;
+        wa.in = in_dev; wa.out = out_dev;
+        e = dlf_launch_pw_i8(&wa, l->shape, l->grid, hip_stream);
+    } else {
+        DlfC3Args ca = l->ca;
+        ca.in = in_dev; ca.out = out_dev;
+        e = dlf_launch_c3_i8(&ca, l->shape, l->grid, l->lds_bytes, hip_stream);
+    }
     if (e != 0) return fail(DLF_ERR_HIP, "launch of the int8 layer failed: %s", hipGetErrorString((hipError_t)e));
     return DLF_OK;
 }

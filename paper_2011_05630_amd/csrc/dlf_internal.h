@@ -120,6 +120,8 @@ struct DlfPwArgs {
     const void* w2;       // packed fragments
     const float* bias2;   // padded to ncb*32
     int32_t cin2, nsteps2, stride2, in_h2, in_w2;
+    // quantised form only (int8 tensors, `cin` = byte pairs per pixel, `act` != 0 = ReLU):
+    const float* scale;   // requantisation scale per output channel, padded to ncb*32
 };
 
 // 3x3 stride-1 pad-1 convolution as a block kernel (one layer, optionally with the 2x2 max pool
@@ -375,6 +377,7 @@ int dlf_launch_fc(const DlfFcArgs* a, void* stream);
 int dlf_launch_gap(const DlfGapArgs* a, void* stream);
 int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stream);
 int dlf_launch_c3(const DlfC3Args* a, int shape, int grid, int lds_bytes, void* stream);
+int dlf_launch_pw_i8(const DlfPwArgs* a, int shape, int grid, void* stream);
 int dlf_launch_c3_i8(const DlfC3Args* a, int shape, int grid, int lds_bytes, void* stream);
 int dlf_launch_dw(const DlfDwArgs* a, int grid, void* stream);
 int dlf_launch_dwpw(const DlfDwPwArgs* a, int nb, int grid, void* stream);

@@ -1453,9 +1453,13 @@ template <int I, int N, typename F> __device__ __forceinline__ void static_for(F
 //   Epilogue as in k_pw, through a wave-private transpose buffer that reuses the ring.
 // One block per workgroup; consecutive blocks (same pixels, next channels) are dealt to the same
 // XCD so that they meet in its L2.
-template <int WN, int WM, bool P2>
+// I8: the quantised form (int8 tensors seen as fp16 tensors of half the channels, int32
+// accumulators on v_mfma_i32_32x32x32_i8, requantising epilogue; see k_c3b).  No residual operand
+// and no second operand pair in this form.
+template <int WN, int WM, bool P2, bool I8 = false>
 __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
 {
+    static_assert(!(I8 && P2), "the quantised form takes one operand pair");
     constexpr int KS = DLF_PWB_KS, NST = DLF_PWB_STAGES;
     constexpr int NA = 2 * WN * KS, NB = 2 * WM * KS, NF = NA + NB;   // fragments per stage
     constexpr int LPW = NF / DLF_PW_WAVES;                            // loads per wave per stage
@@ -1595,13 +1599,13 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
     for (int t = 0; t < NST - 1; ++t)
         if (t < KT) issue(t);
 
-    f16v acc[2][2];
+    typename AccOf<I8>::type acc[2][2];
 #pragma unroll
     for (int f = 0; f < 2; ++f)
 #pragma unroll
         for (int p = 0; p < 2; ++p)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[f][p][r] = 0.0f;
+            for (int r = 0; r < 16; ++r) acc[f][p][r] = 0;
 
     // Stage t is multiplied while the fragments of the next K step -- the last one of a stage
     // reads ahead into stage t + 1 -- are on their way from LDS, so stage t + 1 must be visible
@@ -1654,8 +1658,13 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
 #pragma unroll
             for (int f = 0; f < 2; ++f)
 #pragma unroll
-                for (int p = 0; p < 2; ++p)
-                    acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][f], bf[cur][p], acc[f][p], 0, 0, 0);
+                for (int p = 0; p < 2; ++p) {
+                    if constexpr (I8)
+                        acc[f][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4, af[cur][f]),
+                                                                          __builtin_bit_cast(i32x4, bf[cur][p]), acc[f][p], 0, 0, 0);
+                    else
+                        acc[f][p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][f], bf[cur][p], acc[f][p], 0, 0, 0);
+                }
             __builtin_amdgcn_sched_barrier(0);
         });
         slot = nslot;
@@ -1665,6 +1674,45 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
     lds_arrive<0>(af[0][0], af[0][1], bf[0][0], bf[0][1]);
     // every wave is done with the ring (all loads were waited for above): reuse it
     asm volatile("s_barrier" ::: "memory");
+    if constexpr (I8) {
+        // requantise, transpose through 64-byte rows (16-byte part c of row r at c ^ (r % 4)), and
+        // store 16 bytes per lane: 4 lanes cover the wave's 64 channels of a pixel, 16 pixels per pass
+        unsigned char* tb8 = (unsigned char*)lds + wave * (64 * 64);
+        signed char* out8 = (signed char*)a.out;
+        const float lo = a.act != 0 ? 0.0f : -128.0f;
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+            const int cb = min(wcg * 2 + f, a.ncb - 1);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f4v sv = *(const f4v*)(a.scale + cb * 32 + q * 8 + lhi * 4);
+#pragma unroll
+                for (int p = 0; p < 2; ++p) {
+                    unsigned u = 0;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float t = __builtin_fmaf((float)acc[f][p][q * 4 + r], sv[r], bias[f][q][r]);
+                        t = __builtin_rintf(t);
+                        t = __builtin_fminf(__builtin_fmaxf(t, lo), 127.0f);
+                        u |= ((unsigned)(int)t & 255u) << (8 * r);
+                    }
+                    const int row = p * 32 + l32, c16 = f * 2 + (q >> 1);
+                    *(unsigned*)(tb8 + row * 64 + ((c16 ^ (row & 3)) << 4) + (q & 1) * 8 + lhi * 4) = u;
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        const int part = lane & 3;
+        const int c = wcg * 64 + part * 16;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int px = it * 16 + (lane >> 2);
+            const int gpix = wpg * 64 + px;
+            const u4v v = *(const u4v*)(tb8 + px * 64 + ((part ^ (px & 3)) << 4));
+            if (gpix < a.m && c < a.cout)
+                __builtin_nontemporal_store(v, (u4v*)(out8 + (size_t)gpix * (size_t)a.cout + (size_t)c));
+        }
+    } else {
     half_t* tb = lds + wave * (64 * ROW);
 #pragma unroll
     for (int p = 0; p < 2; ++p)
@@ -1709,6 +1757,7 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
                 store_out(outp + go[i], val[i]);
             }
         }
+    }
     }
     }
 }
@@ -4086,6 +4135,20 @@ extern "C" int dlf_launch_pw(const DlfPwArgs* a, int shape, int grid, void* stre
     else if (shape == 4)
         launch(a->nsteps2 != 0 ? k_pwb<1, 4, true> : k_pwb<1, 4, false>, dim3(grid), dim3(DLF_PW_WAVES * 64),
                (size_t)DLF_PWB_LDS_BYTES(1, 4), (hipStream_t)stream, *a);
+    else
+        return (int)hipErrorInvalidValue;
+    return (int)hipGetLastError();
+}
+
+extern "C" int dlf_launch_pw_i8(const DlfPwArgs* a, int shape, int grid, void* stream)
+{
+    if (grid < 8 || (grid & 7) != 0 || a->scale == nullptr || a->res != nullptr || a->nsteps2 != 0 || a->stride != 1 ||
+        (a->nsteps % DLF_PWB_KS) != 0 || (a->cout & 15) != 0)
+        return (int)hipErrorInvalidValue;
+    if (shape == 3)
+        launch(k_pwb<2, 2, false, true>, dim3(grid), dim3(DLF_PW_WAVES * 64), (size_t)DLF_PWB_LDS_BYTES(2, 2), (hipStream_t)stream, *a);
+    else if (shape == 4)
+        launch(k_pwb<1, 4, false, true>, dim3(grid), dim3(DLF_PW_WAVES * 64), (size_t)DLF_PWB_LDS_BYTES(1, 4), (hipStream_t)stream, *a);
     else
         return (int)hipErrorInvalidValue;
     return (int)hipGetLastError();

@@ -15,8 +15,8 @@ pytestmark = pytest.mark.gpu
 def _run(x, wt, sc, b, relu, budget=0):
     from paper_2011_05630_amd import binding as B
     n, h, w, cin = x.shape
-    cout = wt.shape[0]
-    layer = B.dlf_i8conv_create(n, h, w, cin, cout, relu, wt, sc, b, budget)
+    cout, ksize = wt.shape[0], wt.shape[1]
+    layer = B.dlf_i8conv_create(n, h, w, cin, cout, ksize, relu, wt, sc, b, budget)
     try:
         info = B.dlf_i8conv_info(layer)
         xt = torch.from_numpy(x).cuda()
@@ -33,7 +33,7 @@ def _check(case, x, wt, sc, b, relu, budget=0):
     from oracle import oracle
     announce("i8conv", case, x.shape, "cout", wt.shape[0], "relu", relu)
     got, info = _run(x, wt, sc, b, relu, budget)
-    ref = oracle.conv2d_i8(x, wt, sc, b, 1, 1, relu)
+    ref = oracle.conv2d_i8(x, wt, sc, b, 1, wt.shape[1] // 2, relu)
     bad = np.argwhere(got != ref)
     assert bad.size == 0, (case, info, len(bad), bad[:5].tolist(),
                            [(int(got[tuple(i)]), int(ref[tuple(i)])) for i in bad[:5]])
@@ -58,6 +58,29 @@ def test_i8conv_equals_oracle(case):
     n, h, w, cin, cout, relu = case
     x, wt, sc, b = gen.make_i8_layer(n, h, w, cin, cout, 3, seed=1000 + h * w + cin)
     _check(case, x, wt, sc, b, relu)
+
+
+CASES_1X1 = [  # batch, h, w, cin, cout, relu: both block shapes (cout <= 64: 64 x 256), ragged pixel and channel blocks
+    (2, 28, 28, 256, 128, True),
+    (3, 7, 9, 64, 48, False),
+    (1, 56, 56, 64, 256, True),
+    (5, 13, 11, 512, 208, False),
+    (1, 1, 1, 64, 16, True),
+    (2, 14, 14, 1024, 64, True),
+]
+
+
+@pytest.mark.parametrize("case", CASES_1X1)
+def test_i8conv_1x1_equals_oracle(case):
+    n, h, w, cin, cout, relu = case
+    x, wt, sc, b = gen.make_i8_layer(n, h, w, cin, cout, 1, seed=2000 + h * w + cin)
+    _check(("1x1",) + case, x, wt, sc, b, relu)
+
+
+def test_i8conv_1x1_full_range_and_small_budget():
+    x, wt, sc, b = gen.make_i8_layer(2, 20, 20, 128, 160, 1, seed=32, full_range=True)
+    _check("1x1 full range", x, wt, sc, b, False)
+    _check("1x1 full range, 8 CUs (several blocks per workgroup)", x, wt, sc, b, True, budget=8)
 
 
 def test_i8conv_full_range_operands():
@@ -86,10 +109,10 @@ def test_i8_chain_of_four_layers():
     n, hw, c = 2, 28, 256
     x, _, _, _ = gen.make_i8_layer(n, hw, hw, c, c, 3, seed=7)
     got, ref = x, x
-    for i in range(4):
-        _, wt, sc, b = gen.make_i8_layer(1, 1, 1, c, c, 3, seed=70 + i)
+    for i, k in enumerate((3, 1, 3, 3)):
+        _, wt, sc, b = gen.make_i8_layer(1, 1, 1, c, c, k, seed=70 + i)
         announce("i8 chain layer", i)
         got, _ = _run(got, wt, sc, b, True)
-        ref = oracle.conv2d_i8(ref, wt, sc, b, 1, 1, True)
+        ref = oracle.conv2d_i8(ref, wt, sc, b, 1, k // 2, True)
         assert np.array_equal(got, ref), "layer %d" % i
     assert ref.max() > 50

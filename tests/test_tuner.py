@@ -415,7 +415,7 @@ def test_error_paths_on_the_host():
 def test_i8conv_shape_only_layer_and_argument_checks():
     """The quantised layer's host side without a GPU: a shape-only layer reports its tile, refuses
     to run, and unsupported or invalid sizes come back as statuses."""
-    l = B.dlf_i8conv_create(16, 56, 56, 256, 256, True)
+    l = B.dlf_i8conv_create(16, 56, 56, 256, 256, 3, True)
     info = B.dlf_i8conv_info(l)
     assert info["op_count"] == 2 * 16 * 56 * 56 * 9 * 256 * 256        # Eq. 1 over the batch
     assert info["th"] * info["tw"] <= 512 and info["grid"] % 8 == 0 and 8 <= info["grid"] <= 256
@@ -423,9 +423,16 @@ def test_i8conv_shape_only_layer_and_argument_checks():
         B.dlf_i8conv_run(l, 16, 16, None)
     assert e.value.status == B.DLF_ERR_NO_WEIGHTS
     B.dlf_i8conv_destroy(l)
+    l = B.dlf_i8conv_create(32, 28, 28, 512, 128, 1, False)
+    info = B.dlf_i8conv_info(l)
+    assert info["op_count"] == 2 * 32 * 28 * 28 * 512 * 128 and info["th"] == 1 and info["tw"] in (128, 256)
+    B.dlf_i8conv_destroy(l)
+    with pytest.raises(B.DlfError) as e:
+        B.dlf_i8conv_create(1, 8, 8, 64, 64, 5, False)
+    assert e.value.status == B.DLF_ERR_UNSUPPORTED
     for bad, st in (((1, 8, 8, 48, 64), B.DLF_ERR_UNSUPPORTED), ((1, 8, 8, 64, 24), B.DLF_ERR_UNSUPPORTED),
                     ((0, 8, 8, 64, 64), B.DLF_ERR_INVALID_ARG), ((1, 8, 8, 64, -16), B.DLF_ERR_INVALID_ARG),
                     ((64, 1024, 1024, 64, 64), B.DLF_ERR_UNSUPPORTED)):
         with pytest.raises(B.DlfError) as e:
-            B.dlf_i8conv_create(*bad, False)
+            B.dlf_i8conv_create(*bad, 3, False)
         assert e.value.status == st, bad
