@@ -42,7 +42,10 @@ def load_traffic():
 
 
 def kernel_short_name(k):
-    return k.replace("void ", "").split("(")[0].replace(" ", "").replace(",false>", ">")
+    k = k.replace("void ", "").split("(")[0].replace(" ", "")
+    while k.endswith(",false>"):          # trailing template defaults (second operand pair, quantised form)
+        k = k[:-len(",false>")] + ">"
+    return k
 
 
 def traffic_from(fetch_dir, write_dir, workload_key):
@@ -334,9 +337,12 @@ def sweep_chain4(steps, warmup):
                     sys.stdout.flush()
 
 
-I8_LAYERS = [  # name, batch, h = w, cin = cout: the 3x3 layers of VGG-16 (from 64 channels on) and of the chain of configuration 2
-    ("vgg_conv1_2", 16, 224, 64), ("vgg_conv2_2", 16, 112, 128), ("vgg_conv3_2", 16, 56, 256),
-    ("vgg_conv4_2", 16, 28, 512), ("vgg_conv5_2", 16, 14, 512), ("chain4_c256", 8, 56, 256),
+I8_LAYERS = [  # name, batch, h = w, cin, cout, filter: the 3x3 layers of VGG-16 (from 64 channels on) and of the
+    # chain of configuration 2, and the 1x1 layers of ResNet-50's bottleneck blocks
+    ("vgg_conv1_2", 16, 224, 64, 64, 3), ("vgg_conv2_2", 16, 112, 128, 128, 3), ("vgg_conv3_2", 16, 56, 256, 256, 3),
+    ("vgg_conv4_2", 16, 28, 512, 512, 3), ("vgg_conv5_2", 16, 14, 512, 512, 3), ("chain4_c256", 8, 56, 256, 256, 3),
+    ("res2_reduce", 32, 56, 256, 64, 1), ("res2_expand", 32, 56, 64, 256, 1), ("res3_reduce", 32, 28, 512, 128, 1),
+    ("res3_expand", 32, 28, 128, 512, 1), ("res4_reduce", 32, 14, 1024, 256, 1), ("res4_expand", 32, 14, 256, 1024, 1),
 ]
 
 
@@ -349,12 +355,12 @@ def bench_i8(steps, warmup, cpu=True, layers=None):
     from paper_2011_05630_amd import binding as B
     out = {}
     stream = torch.cuda.current_stream().cuda_stream
-    for name, batch, hw, c in (layers or I8_LAYERS):
-        x, wt, sc, b = gen.make_i8_layer(batch, hw, hw, c, c, 3)
-        layer = B.dlf_i8conv_create(batch, hw, hw, c, c, 3, True, wt, sc, b, 0)
+    for name, batch, hw, c, co, k in (layers or I8_LAYERS):
+        x, wt, sc, b = gen.make_i8_layer(batch, hw, hw, c, co, k)
+        layer = B.dlf_i8conv_create(batch, hw, hw, c, co, k, True, wt, sc, b, 0)
         info = B.dlf_i8conv_info(layer)
         xt = torch.from_numpy(x).cuda()
-        yt = torch.empty((batch, hw, hw, c), dtype=torch.int8, device="cuda")
+        yt = torch.empty((batch, hw, hw, co), dtype=torch.int8, device="cuda")
         for _ in range(warmup):
             B.dlf_i8conv_run(layer, xt.data_ptr(), yt.data_ptr(), stream)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -367,11 +373,13 @@ def bench_i8(steps, warmup, cpu=True, layers=None):
         us = e0.elapsed_time(e1) * 1e3 / steps
         B.dlf_i8conv_destroy(layer)
         tops = info["op_count"] / (us * 1e-6) / 1e12
-        nbytes = 2 * batch * hw * hw * c + 9 * c * c
-        rec = dict(batch=batch, hw=hw, channels=c, us=us, tops=tops, frac_int8_mfma_peak=tops / MFMA_INT8_PEAK_TOPS,
-                   gbs=nbytes / (us * 1e-6) / 1e9, tile="%dx%d" % (info["th"], info["tw"]), kernel_shape=info["shape"])
+        nbytes = batch * hw * hw * (c + co) + k * k * c * co            # input + output + weights, once each
+        rec = dict(batch=batch, hw=hw, cin=c, cout=co, filter=k, us=us, tops=tops,
+                   frac_int8_mfma_peak=tops / MFMA_INT8_PEAK_TOPS, gbs=nbytes / (us * 1e-6) / 1e9,
+                   frac_hbm_peak=nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                   tile="%dx%d" % (info["th"], info["tw"]), kernel_shape=info["shape"])
         # the same layer in fp16 (one group, the library's own choice of kernel)
-        net = dict(name=name, layers=[nets.conv(c, c, 3, 1, 1, "relu")], in_h=hw, in_w=hw, in_c=c, input_dist="normal")
+        net = dict(name=name, layers=[nets.conv(c, co, k, 1, k // 2, "relu")], in_h=hw, in_w=hw, in_c=c, input_dist="normal")
         r = time_plan(net, batch, dict(mode=B.TUNER_DP), steps, warmup)
         rec["fp16_us"] = r["ms_per_step"] * 1e3
         rec["fp16_kernel"] = r["acct"][0]["kernel"]

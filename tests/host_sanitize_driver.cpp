@@ -34,6 +34,8 @@ int dlf_launch_fc(const DlfFcArgs*, void*) { return unreachable_launch("fc"); }
 int dlf_launch_gap(const DlfGapArgs*, void*) { return unreachable_launch("gap"); }
 int dlf_launch_pw(const DlfPwArgs*, int, int, void*) { return unreachable_launch("pw"); }
 int dlf_launch_c3(const DlfC3Args*, int, int, int, void*) { return unreachable_launch("c3"); }
+int dlf_launch_c3_i8(const DlfC3Args*, int, int, int, void*) { return unreachable_launch("c3_i8"); }
+int dlf_launch_pw_i8(const DlfPwArgs*, int, int, void*) { return unreachable_launch("pw_i8"); }
 int dlf_launch_dw(const DlfDwArgs*, int, void*) { return unreachable_launch("dw"); }
 int dlf_launch_dwpw(const DlfDwPwArgs*, int, int, void*) { return unreachable_launch("dwpw"); }
 int dlf_launch_dwt(const DlfDwtArgs*, int, int, void*) { return unreachable_launch("dwt"); }
@@ -197,6 +199,31 @@ int main()
             o.budgets = neg;
             o.n_budgets = 2;
             bad += dlf_plan(net, 1, &o, &plan) == DLF_OK;
+            // the quantised layer: shape-only layers of both filter sizes over a range of maps, and rejected sizes
+            for (int32_t k = 1; k <= 3; k += 2)
+                for (int32_t hw : {1, 7, 14, 28, 56, 112})
+                    for (int32_t ch : {64, 128, 512}) {
+                        dlf_i8conv_t* q = nullptr;
+                        if (dlf_i8conv_create(3, hw, hw + 1, ch, ch + 16, k, 1, nullptr, nullptr, nullptr, 0, &q) != DLF_OK)
+                            die("dlf_i8conv_create");
+                        int32_t th, tw, sh, gr;
+                        uint64_t ops;
+                        if (dlf_i8conv_info(q, &th, &tw, &sh, &gr, &ops) != DLF_OK || gr < 8 || (gr & 7) || th < 1 || tw < 1)
+                            die("dlf_i8conv_info");
+                        bad += dlf_i8conv_run(q, layers.data(), layers.data(), nullptr) == DLF_OK;     // no weights
+                        dlf_i8conv_destroy(q);
+                    }
+            {
+                dlf_i8conv_t* q = nullptr;
+                bad += dlf_i8conv_create(1, 8, 8, 64, 64, 3, 0, nullptr, nullptr, nullptr, 0, nullptr) == DLF_OK;
+                bad += dlf_i8conv_create(1, 8, 8, 32, 64, 3, 0, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;
+                bad += dlf_i8conv_create(1, 8, 8, 64, 8, 1, 0, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;
+                bad += dlf_i8conv_create(1, 8, 8, 64, 64, 2, 0, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;
+                bad += dlf_i8conv_create(1, -8, 8, 64, 64, 3, 0, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;
+                bad += dlf_i8conv_create(1 << 20, 1 << 10, 1 << 10, 64, 64, 3, 0, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;
+                bad += dlf_i8conv_info(nullptr, nullptr, nullptr, nullptr, nullptr, nullptr) == DLF_OK;
+                dlf_i8conv_destroy(nullptr);
+            }
             dlf_net_destroy(nullptr);
             dlf_plan_destroy(nullptr);
             if (bad) die("a bad argument was accepted");
