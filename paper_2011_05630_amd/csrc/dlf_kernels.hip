@@ -35,6 +35,22 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i16v __attribute__((ext_vector_type(16)));
 template <bool I8> struct AccOf { typedef f16v type; };
 template <> struct AccOf<true> { typedef i16v type; };
+// Transpose buffer of the quantised epilogues: rows of 64 bytes (a wave's 64 int8 channels of one
+// pixel), written one dword per lane by 32 lanes that hold 32 consecutive rows, read 16 bytes per
+// lane.  Row r keeps its 16-byte part c at position c ^ (r / 2) % 4 and, inside a part, dword d at
+// d ^ (r / 8) % 4: with bit 4 of the bank number being r % 2, the 32 rows of a write fall into 32
+// different banks.  A reader takes the part as it lies and undoes the dword permutation in registers.
+__device__ __forceinline__ int i8t_write_off(int row, int c16, int d)
+{
+    return row * 64 + (((c16 ^ (row >> 1)) & 3) << 4) + (((d ^ (row >> 3)) & 3) << 2);
+}
+__device__ __forceinline__ u4v i8t_read(const unsigned char* tb, int row, int part)
+{
+    const u4v v = *(const u4v*)(tb + row * 64 + (((part ^ (row >> 1)) & 3) << 4));
+    const int k = row >> 3;
+    const u4v a = (k & 1) ? u4v{v.y, v.x, v.w, v.z} : v;
+    return (k & 2) ? u4v{a.z, a.w, a.x, a.y} : a;
+}
 __device__ i32x4 raw_buffer_load_x4(i32x4 rsrc, int voffset, int soffset, int aux) __asm("llvm.amdgcn.raw.buffer.load.v4i32");
 __device__ __forceinline__ i32x4 make_rsrc(const void* p, unsigned bytes)
 {
@@ -1675,7 +1691,7 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
     // every wave is done with the ring (all loads were waited for above): reuse it
     asm volatile("s_barrier" ::: "memory");
     if constexpr (I8) {
-        // requantise, transpose through 64-byte rows (16-byte part c of row r at c ^ (r % 4)), and
+        // requantise, transpose through 64-byte rows (i8t_write_off), and
         // store 16 bytes per lane: 4 lanes cover the wave's 64 channels of a pixel, 16 pixels per pass
         unsigned char* tb8 = (unsigned char*)lds + wave * (64 * 64);
         signed char* out8 = (signed char*)a.out;
@@ -1696,8 +1712,7 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
                         t = __builtin_fminf(__builtin_fmaxf(t, lo), 127.0f);
                         u |= ((unsigned)(int)t & 255u) << (8 * r);
                     }
-                    const int row = p * 32 + l32, c16 = f * 2 + (q >> 1);
-                    *(unsigned*)(tb8 + row * 64 + ((c16 ^ (row & 3)) << 4) + (q & 1) * 8 + lhi * 4) = u;
+                    *(unsigned*)(tb8 + i8t_write_off(p * 32 + l32, f * 2 + (q >> 1), (q & 1) * 2 + lhi)) = u;
                 }
             }
         }
@@ -1708,7 +1723,7 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
         for (int it = 0; it < 4; ++it) {
             const int px = it * 16 + (lane >> 2);
             const int gpix = wpg * 64 + px;
-            const u4v v = *(const u4v*)(tb8 + px * 64 + ((part ^ (px & 3)) << 4));
+            const u4v v = i8t_read(tb8, px, part);
             if (gpix < a.m && c < a.cout)
                 __builtin_nontemporal_store(v, (u4v*)(out8 + (size_t)gpix * (size_t)a.cout + (size_t)c));
         }
@@ -2094,8 +2109,7 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
         if constexpr (I8) {
             // Quantised form: a pass per 32-pixel block.  A lane holds, per channel block f and q, four
             // consecutive channels of its pixel: one dword of the pixel's 64-byte row in the wave's
-            // transpose buffer (rows of 64 bytes, the 16-byte part c of row r at c ^ (r % 4)); then lane
-            // 4 r + c stores part c of row r.
+            // transpose buffer (i8t_write_off); then lane 4 r + c stores part c of row r.
             static_assert(DLF_C3_WAVES * 32 * 64 <= W_HALFS * 2, "the transpose buffers fit one slot of the ring");
             unsigned char* tb8 = (unsigned char*)(wring + (nst - 1) * W_HALFS) + wave * (32 * 64);
             signed char* out8 = (signed char*)a.out;
@@ -2119,8 +2133,7 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
                             t = __builtin_fminf(__builtin_fmaxf(t, lo), 127.0f);
                             u |= ((unsigned)(int)t & 255u) << (8 * r);
                         }
-                        const int c16 = f * 2 + (q >> 1);
-                        *(unsigned*)(tb8 + l32 * 64 + ((c16 ^ (l32 & 3)) << 4) + (q & 1) * 8 + lhi * 4) = u;
+                        *(unsigned*)(tb8 + i8t_write_off(l32, f * 2 + (q >> 1), (q & 1) * 2 + lhi)) = u;
                     }
                 }
                 __builtin_amdgcn_wave_barrier();
@@ -2131,7 +2144,7 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
                     const int ry = div_by(opix, tw_m), rx = opix - ry * a.tw;
                     const int gy = e_ty0 + ry, gx = e_tx0 + rx;
                     const bool ok = opix < npix && gy < a.h && gx < a.w_ && cch < a.cout;
-                    const u4v v = *(const u4v*)(tb8 + row * 64 + ((part ^ (row & 3)) << 4));
+                    const u4v v = i8t_read(tb8, row, part);
                     if (ok) *(u4v*)(out8 + (size_t)((e_n * a.h + gy) * a.w_ + gx) * (size_t)a.cout + cch) = v;
                 }
                 __builtin_amdgcn_wave_barrier();
