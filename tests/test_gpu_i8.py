@@ -116,3 +116,19 @@ def test_i8_chain_of_four_layers():
         ref = oracle.conv2d_i8(ref, wt, sc, b, 1, k // 2, True)
         assert np.array_equal(got, ref), "layer %d" % i
     assert ref.max() > 50
+
+
+@pytest.mark.parametrize("name", ["vgg_conv3_2", "vgg_conv4_2", "vgg_conv1_2", "res2_reduce", "res4_expand"])
+def test_i8conv_benchmarked_layers_sampled_images(name):
+    """The layers `bench.py --i8` times, at their full size and in the launch configuration it uses:
+    the first, a middle and the last image of the batch against the oracle (images are independent)."""
+    import bench
+    from oracle import oracle
+    _, batch, hw, c, co, k = [l for l in bench.I8_LAYERS if l[0] == name][0]
+    x, wt, sc, b = gen.make_i8_layer(batch, hw, hw, c, co, k)
+    announce("i8conv", name, x.shape, "cout", co)
+    got, info = _run(x, wt, sc, b, True)
+    pick = [0, batch // 2 - 1, batch - 1] if hw <= 56 else [batch - 1]
+    ref = oracle.conv2d_i8(x[pick], wt, sc, b, 1, k // 2, True)
+    assert np.array_equal(got[pick], ref), (name, info)
+    assert got.max() == 127 and (got == 0).mean() > 0.2
