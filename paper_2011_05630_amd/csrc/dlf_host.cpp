@@ -2810,8 +2810,10 @@ static dlf_status static_workspace(char** base)
 
 struct dlf_i8conv_s {
     int ksize = 3;
+    bool small_map = false;      // runs on the small-map kernel (cs), else on a block kernel (ca / wa)
     DlfC3Args ca;
     DlfPwArgs wa;
+    DlfC3sArgs cs;
     int th = 0, tw = 0;
     int shape = 0, grid = 0, lds_bytes = 0;
     uint64_t ops = 0;
@@ -2857,9 +2859,41 @@ dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, i
     l->ops = (uint64_t)2 * batch * h * w * taps * (uint64_t)cin * cout;
     memset(&l->ca, 0, sizeof l->ca);
     memset(&l->wa, 0, sizeof l->wa);
+    memset(&l->cs, 0, sizeof l->cs);
     C3Cfg cc;
     uint64_t cost = 0;
-    if (ksize == 1) {
+    // Maps of many channels and few pixels: the small-map kernel, where it applies (512 .. 4096 int8
+    // channels) and its modelled cost is below the block kernel's.  Testing hook: shape DLF_C3_SHAPES
+    // forces it (th > 0: the split of K), a block shape excludes it.
+    DlfC3sArgs cs;
+    uint64_t cost_s = 0;
+    bool have_s = false;
+    if (c3s_cin_ok(L.d.cin) && !(g_c3_force.shape >= 0 && g_c3_force.shape < DLF_C3_SHAPES)) {
+        if (g_c3_force.shape == DLF_C3_SHAPES && g_c3_force.th > 0) {
+            have_s = c3s_build(L, batch, g_c3_force.th, 0, 0, 160 * 1024, cs);
+            if (!have_s) return fail(DLF_ERR_INFEASIBLE, "the forced split of K does not fit this layer");
+        } else {
+            have_s = c3s_choose(L, batch, budget, 160 * 1024, cs, cost_s);
+        }
+        if (have_s && g_c3_force.shape != DLF_C3_SHAPES) {
+            uint64_t other = UINT64_MAX;
+            C3Cfg c2;
+            if (ksize == 1) other = pw_shape_cost_ps(L, batch, budget, pw_shape_ok(L, 3) ? 3 : 4);
+            else if (!c3_choose(L, 0, batch, budget, 160 * 1024, c2, other)) other = UINT64_MAX;
+            if (other <= cost_s) have_s = false;
+        }
+    } else if (g_c3_force.shape == DLF_C3_SHAPES) {
+        return fail(DLF_ERR_INFEASIBLE, "the small-map kernel does not take this channel count");
+    }
+    if (have_s) {
+        l->small_map = true;
+        l->cs = cs;
+        l->cs.act = relu ? 1 : 0;
+        l->shape = DLF_C3_SHAPES;
+        l->grid = cs.slice_major ? ceil_div(cs.ntiles, 8 / cs.nsl) * 8 : ceil_div(cs.ntiles, 8) * 8 * cs.nsl;
+        l->lds_bytes = (int)DLF_C3S_LDS_BYTES(cs.rp, cs.cin);
+        l->th = cs.th; l->tw = cs.tw;
+    } else if (ksize == 1) {
         // the block pointwise kernel: 128 channels x 128 pixels per workgroup, or 64 x 256 for few channels
         const int shape = pw_shape_ok(L, 3) ? 3 : 4;
         DlfPwArgs& wa = l->wa;
@@ -2903,9 +2937,9 @@ dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, i
         s = upload(sc.data(), sc.size() * 4, (void**)&l->d_scale);
         if (s == DLF_OK) s = upload(bi.data(), bi.size() * 4, (void**)&l->d_bias);
         if (s != DLF_OK) { dlf_i8conv_destroy(l.release()); return s; }
-        l->ca.w = l->wa.w = l->d_w;
-        l->ca.scale = l->wa.scale = l->d_scale;
-        l->ca.bias = l->wa.bias = l->d_bias;
+        l->ca.w = l->wa.w = l->cs.w = l->d_w;
+        l->ca.scale = l->wa.scale = l->cs.scale = l->d_scale;
+        l->ca.bias = l->wa.bias = l->cs.bias = l->d_bias;
     }
     *out = l.release();
     return DLF_OK;
@@ -2933,7 +2967,11 @@ dlf_status dlf_i8conv_run(const dlf_i8conv_t* l, const void* in_dev, void* out_d
     if (g_kernels_rc != 0)
         return fail(DLF_ERR_HIP, "kernel setup failed: %s", hipGetErrorString((hipError_t)g_kernels_rc));
     int e;
-    if (l->ksize == 1) {
+    if (l->small_map) {
+        DlfC3sArgs cs = l->cs;
+        cs.in = in_dev; cs.out = out_dev;
+        e = dlf_launch_c3s(&cs, l->grid, l->lds_bytes, hip_stream);
+    } else if (l->ksize == 1) {
         DlfPwArgs wa = l->wa;
         wa.in = in_dev; wa.out = out_dev;
         e = dlf_launch_pw_i8(&wa, l->shape, l->grid, hip_stream);

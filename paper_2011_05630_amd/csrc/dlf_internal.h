@@ -287,6 +287,8 @@ struct DlfC3sArgs {
     int32_t ksplit;       // 1, 2 or 4 waves per channel block; divides cin / 32 (1x1: cin / 128)
     int32_t nsl;          // slices of the output channels: ceil(ncb / (8 / ksplit))
     int32_t slice_major;  // 1: an XCD keeps to one slice (nsl 2, 4 or 8); 0: the slices of a tile share an XCD
+    // quantised form (int8 tensors, `cin` = byte pairs per pixel, `act` != 0 = ReLU) if not null:
+    const float* scale;   // requantisation scale per output channel, padded to ncb * 32
 };
 
 // 3x3 convolution (stride 1, pad 1, cin = cout = c: 64, 128 or 256) and the 1x1 convolution behind it, with

@@ -2965,9 +2965,15 @@ __global__ __launch_bounds__(DLF_DWS_WAVES * 64, 1) void k_dws(const DlfDwsArgs 
 //   3. Partial sums of the waves of a channel block meet in LDS (in the region's space, behind a
 //      barrier); bias, fp16, residual operand if there is one (its vectors requested right behind
 //      the K loop), activation, transpose, 64-byte runs per pixel to memory.
-template <int TAPS, int S, int FP>
+// I8: the quantised form (int8 tensors seen as fp16 tensors of half the channels, int32 accumulators on
+// v_mfma_i32_32x32x32_i8 -- the partial sums that meet in LDS are integers, so the split of K changes no
+// bit -- and a requantising epilogue, see k_c3b); stride 1, no residual operand.
+template <int TAPS, int S, int FP, bool I8 = false>
 __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs a)
 {
+    static_assert(!I8 || S == 1, "the quantised form has stride 1");
+    typedef typename AccOf<I8>::type acc_t;
+    typedef decltype(acc_t{}[0] + 0) red_t;            // float, or int in the quantised form
     static_assert(TAPS == 9 || (TAPS == 1 && S == 1), "3x3 (pad 1, stride 1 or 2) or 1x1 (pad 0, stride 1)");
     static_assert(S == 1 || S == 2, "stride");
     static_assert(FP == 1 || FP == 2, "32-pixel blocks of a tile");
@@ -3059,11 +3065,11 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
             ft[t][p] = ((((ry / S) * a.tw + rx / S) & 15) ^ lhi) << 4;
         }
     }
-    f16v acc[FP];
+    acc_t acc[FP];
 #pragma unroll
     for (int p = 0; p < FP; ++p)
 #pragma unroll
-        for (int q = 0; q < 16; ++q) acc[p][q] = 0.0f;
+        for (int q = 0; q < 16; ++q) acc[p][q] = 0;
 
     if (live) wait_vmcnt<D>(); else wait_vmcnt<0>();         // the region has landed: only the ring's requests are behind it
     asm volatile("s_barrier" ::: "memory");
@@ -3088,15 +3094,20 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
 #pragma unroll
                 for (int p = 0; p < FP; ++p) bf[(j + 1) & 1][p] = *(const h8*)(region + bt[tn][p] + (qn ^ ft[tn][p]));
 #pragma unroll
-                for (int p = 0; p < FP; ++p)
-                    acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[j % D], bf[j & 1][p], acc[p], 0, 0, 0);
+                for (int p = 0; p < FP; ++p) {
+                    if constexpr (I8)
+                        acc[p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4, ar[j % D]),
+                                                                       __builtin_bit_cast(i32x4, bf[j & 1][p]), acc[p], 0, 0, 0);
+                    else
+                        acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[j % D], bf[j & 1][p], acc[p], 0, 0, 0);
+                }
                 request(j % D);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
     // ---- step 3: partial sums, epilogue ----
-    float* const red = (float*)lds;
+    red_t* const red = (red_t*)lds;
     half_t* const tb = lds + DLF_C3S_RED_BYTES / 2 + wave * (32 * ROW);
     // the residual vectors of the pixels and channels this lane will store, and the bias: requested
     // here, ahead of the exchange of partial sums and of the first store (a load behind a store
@@ -3123,7 +3134,7 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
     if (a.ksplit > 1) {
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // everyone is done reading the region
         if (kpart > 0 && live) {
-            float* dst = red + (wave - ncbw) * (2 * 16 * 64) + lane;
+            red_t* dst = red + (wave - ncbw) * (2 * 16 * 64) + lane;
 #pragma unroll
             for (int p = 0; p < FP; ++p)
 #pragma unroll
@@ -3132,7 +3143,7 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         if (kpart > 0 || !live) return;
         for (int k = 1; k < a.ksplit; ++k) {
-            const float* src = red + (k * ncbw + cbw - ncbw) * (2 * 16 * 64) + lane;
+            const red_t* src = red + (k * ncbw + cbw - ncbw) * (2 * 16 * 64) + lane;
 #pragma unroll
             for (int p = 0; p < FP; ++p)
 #pragma unroll
@@ -3141,6 +3152,48 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
     } else {
         if (!live) return;
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // the transpose buffers lie in the region's space
+    }
+    if constexpr (I8) {
+        // requantise; the wave's 32 channels of a pixel are a row of 32 bytes in its transpose buffer
+        // (16-byte part c of row r at c ^ (r / 4) % 2, dword d of a part at d ^ (r / 8) % 4: the 32 rows
+        // of a write fall into 32 banks); then lane 2 r + c stores part c of row r
+        unsigned char* const tb8 = (unsigned char*)tb;
+        signed char* const out8 = (signed char*)a.out;
+        const float lo = a.act != 0 ? 0.0f : -128.0f;
+        f4v scv[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) scv[q] = *(const f4v*)(a.scale + cb * 32 + q * 8 + lhi * 4);
+#pragma unroll
+        for (int p = 0; p < FP; ++p) {
+            if (p * 32 < a.tp) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    unsigned u = 0;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float t = __builtin_fmaf((float)acc[p][q * 4 + r], scv[q][r], biasv[q][r]);
+                        t = __builtin_rintf(t);
+                        t = __builtin_fminf(__builtin_fmaxf(t, lo), 127.0f);
+                        u |= ((unsigned)(int)t & 255u) << (8 * r);
+                    }
+                    *(unsigned*)(tb8 + l32 * 32 + ((((q >> 1) ^ (l32 >> 2)) & 1) << 4) + (((((q & 1) * 2 + lhi) ^ (l32 >> 3)) & 3) << 2)) = u;
+                }
+                __builtin_amdgcn_wave_barrier();
+                const int part = lane & 1, pl = lane >> 1;
+                const int cc = cb * 32 + part * 16;
+                const int px_ = p * 32 + pl;
+                const int row = div_by(px_, tw_m), colp = px_ - row * a.tw;
+                const int oy = oy0 + row, ox = ox0 + colp;
+                const u4v v = *(const u4v*)(tb8 + pl * 32 + (((part ^ (pl >> 2)) & 1) << 4));
+                const int k = pl >> 3;
+                const u4v v1 = (k & 1) ? u4v{v.y, v.x, v.w, v.z} : v;
+                const u4v v2 = (k & 2) ? u4v{v1.z, v1.w, v1.x, v1.y} : v1;
+                if (px_ < a.tp && oy < a.oh && ox < a.ow && cc < a.cout)
+                    *(u4v*)(out8 + ((size_t)((n * a.oh + oy) * a.ow + ox) * a.cout + cc)) = v2;
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+        return;
     }
     // with a residual operand the activation follows the add (fp16 + fp16, as in the other kernels)
     const unsigned lo_t = resp != nullptr ? act_lo(0) : lo_e, hi_t = resp != nullptr ? act_hi(0) : hi_e;
@@ -4007,6 +4060,12 @@ static c3s_kernel_t c3s_kernel(int taps, int stride, int fp)
     if (taps == 1 && stride == 1) return fp == 2 ? k_c3s<1, 1, 2> : k_c3s<1, 1, 1>;
     return nullptr;
 }
+static c3s_kernel_t c3s_kernel_i8(int taps, int fp)
+{
+    if (taps == 9) return fp == 2 ? k_c3s<9, 1, 2, true> : k_c3s<9, 1, 1, true>;
+    if (taps == 1) return fp == 2 ? k_c3s<1, 1, 2, true> : k_c3s<1, 1, 1, true>;
+    return nullptr;
+}
 
 typedef void (*c3_kernel_t)(const DlfC3Args);
 static c3_kernel_t c3_kernel(int shape)
@@ -4061,6 +4120,11 @@ extern "C" int dlf_kernels_init(void)
         if (e2 != hipSuccess) return (int)e2;
         for (int v = 0; v < 6; ++v) {
             hipError_t e = hipFuncSetAttribute((const void*)c3s_kernel(v < 4 ? 9 : 1, (v >> 1) == 1 ? 2 : 1, (v & 1) + 1),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return (int)e;
+        }
+        for (int v = 0; v < 4; ++v) {
+            hipError_t e = hipFuncSetAttribute((const void*)c3s_kernel_i8(v < 2 ? 9 : 1, (v & 1) + 1),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
             if (e != hipSuccess) return (int)e;
         }
@@ -4262,6 +4326,12 @@ extern "C" int dlf_launch_c3s(const DlfC3sArgs* a, int grid, int lds_bytes, void
         grid != (a->slice_major ? (a->ntiles + 8 / a->nsl - 1) / (8 / a->nsl) * 8 : (a->ntiles + 7) / 8 * 8 * a->nsl))
         return (int)hipErrorInvalidValue;
     if (lds_bytes != (int)DLF_C3S_LDS_BYTES(a->rp, a->cin) || lds_bytes > 160 * 1024) return (int)hipErrorInvalidValue;
+    if (a->scale != nullptr) {       // the quantised form
+        if (s != 1 || a->res != nullptr || (a->cout & 15) != 0) return (int)hipErrorInvalidValue;
+        launch(c3s_kernel_i8(a->taps, a->tp > 32 ? 2 : 1), dim3(grid), dim3(DLF_C3S_WAVES * 64), (size_t)lds_bytes,
+               (hipStream_t)stream, *a);
+        return (int)hipGetLastError();
+    }
     launch(c3s_kernel(a->taps, s, a->tp > 32 ? 2 : 1), dim3(grid), dim3(DLF_C3S_WAVES * 64), (size_t)lds_bytes,
            (hipStream_t)stream, *a);
     return (int)hipGetLastError();

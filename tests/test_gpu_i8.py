@@ -104,6 +104,33 @@ def test_i8conv_every_kernel_shape(shape, th, tw, cin):
     assert (info["shape"], info["th"], info["tw"]) == (shape, th, tw)
 
 
+@pytest.mark.parametrize("k,ksplit,n,h,w,cin,cout", [
+    (3, 1, 2, 14, 14, 512, 512), (3, 2, 3, 7, 7, 512, 80), (3, 4, 1, 9, 11, 1024, 272), (3, 2, 2, 13, 5, 512, 48),
+    (1, 1, 2, 14, 14, 1024, 256), (1, 2, 5, 7, 7, 2048, 512), (1, 4, 1, 10, 9, 1024, 144), (1, 2, 3, 5, 8, 512, 96), (3, 4, 4, 6, 6, 2048, 64)])
+def test_i8conv_small_map_kernel(k, ksplit, n, h, w, cin, cout):
+    """The kernel for maps of many channels and few pixels, forced, with K split over 1, 2 and 4 waves
+    (integer partial sums: the split changes no bit), ragged tiles and ragged channel slices."""
+    from paper_2011_05630_amd import binding as B
+    x, wt, sc, b = gen.make_i8_layer(n, h, w, cin, cout, k, seed=300 + ksplit + k + h)
+    B.dlf_debug_block3x3_mode(0, 5, ksplit, 0)
+    try:
+        info = _check(("small map", k, ksplit), x, wt, sc, b, True)
+    finally:
+        B.dlf_debug_block3x3_mode(0, -1, 0, 0)
+    assert info["shape"] == 5 and info["th"] <= 8 and info["tw"] <= 8
+
+
+def test_i8conv_small_map_kernel_is_chosen_where_it_pays():
+    from paper_2011_05630_amd import binding as B
+    for (n, hw, c, k), want in (((16, 14, 512, 3), 5), ((16, 56, 256, 3), None), ((16, 28, 512, 3), None)):
+        l = B.dlf_i8conv_create(n, hw, hw, c, c, k, True)
+        info = B.dlf_i8conv_info(l)
+        B.dlf_i8conv_destroy(l)
+        assert (info["shape"] == 5) == (want == 5), (n, hw, c, k, info)
+    x, wt, sc, b = gen.make_i8_layer(16, 14, 14, 512, 512, 3, seed=9)
+    _check("14x14 x 512, the library's choice", x, wt, sc, b, True)
+
+
 def test_i8_chain_of_four_layers():
     from oracle import oracle
     n, hw, c = 2, 28, 256
