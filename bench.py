@@ -343,6 +343,7 @@ I8_LAYERS = [  # name, batch, h = w, cin, cout, filter: the 3x3 layers of VGG-16
     ("vgg_conv4_2", 16, 28, 512, 512, 3), ("vgg_conv5_2", 16, 14, 512, 512, 3), ("chain4_c256", 8, 56, 256, 256, 3),
     ("res2_reduce", 32, 56, 256, 64, 1), ("res2_expand", 32, 56, 64, 256, 1), ("res3_reduce", 32, 28, 512, 128, 1),
     ("res3_expand", 32, 28, 128, 512, 1), ("res4_reduce", 32, 14, 1024, 256, 1), ("res4_expand", 32, 14, 256, 1024, 1),
+    ("res5_3x3", 32, 7, 512, 512, 3), ("res5_reduce", 32, 7, 2048, 512, 1),
 ]
 
 
