@@ -159,3 +159,51 @@ def test_i8conv_benchmarked_layers_sampled_images(name):
     ref = oracle.conv2d_i8(x[pick], wt, sc, b, 1, k // 2, True)
     assert np.array_equal(got[pick], ref), (name, info)
     assert got.max() == 127 and (got == 0).mean() > 0.2
+
+
+def test_i8_layers_captured_in_a_hip_graph_replay_to_the_oracle():
+    """dlf_i8conv_run only launches a kernel, so a chain of layers (block 3x3, block 1x1, small-map
+    kernel) can be captured; every replay, with eager work and synchronisations between the replays,
+    must equal the oracle's chain."""
+    from oracle import oracle
+    from paper_2011_05630_amd import binding as B
+    n, hw = 2, 14
+    specs = [(3, 128, 512), (1, 512, 512), (3, 512, 64)]
+    x, _, _, _ = gen.make_i8_layer(n, hw, hw, 128, 16, 3, seed=91)
+    ref, layers, bufs = x, [], [torch.from_numpy(x).cuda()]
+    for i, (k, ci, co) in enumerate(specs):
+        _, wt, sc, b = gen.make_i8_layer(1, 1, 1, ci, co, k, seed=92 + i)
+        ref = oracle.conv2d_i8(ref, wt, sc, b, 1, k // 2, True)
+        layers.append(B.dlf_i8conv_create(n, hw, hw, ci, co, k, True, wt, sc, b))
+        bufs.append(torch.zeros((n, hw, hw, co), dtype=torch.int8, device="cuda"))
+    kinds = [B.dlf_i8conv_info(l)["shape"] for l in layers]
+    assert kinds[1] == 5 or kinds[2] == 5, kinds          # the small-map kernel takes part
+    try:
+        side = torch.cuda.Stream()
+
+        def chain():
+            for l, src, dst in zip(layers, bufs[:-1], bufs[1:]):
+                B.dlf_i8conv_run(l, src.data_ptr(), dst.data_ptr(), side.cuda_stream)
+
+        with torch.cuda.stream(side):
+            chain()                              # first run: one-time kernel set-up, outside the capture
+        torch.cuda.synchronize()
+        assert np.array_equal(bufs[-1].cpu().numpy(), ref)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            chain()
+        torch.cuda.synchronize()
+        for _ in range(3):
+            for t in bufs[1:]:
+                t.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(bufs[-1].cpu().numpy(), ref)
+            with torch.cuda.stream(side):
+                chain()
+            torch.cuda.synchronize()
+            assert np.array_equal(bufs[-1].cpu().numpy(), ref)
+    finally:
+        for l in layers:
+            B.dlf_i8conv_destroy(l)
