@@ -235,6 +235,9 @@ dlf_status dlf_plan_refine(dlf_plan_t* plan, const void* in_dev, void* out_dev, 
  *   out = clamp(round_half_even(fma((float)acc, scale[co], bias[co])), relu ? 0 : -128, 127)
  * with one fp32 fused multiply-add per output ((float) rounds to nearest even above 2^24).  The
  * caller guarantees |acc| < 2^31 (always true for cin <= 14000).
+ * pool = 1 (ksize = 3 only) folds the 2x2 stride-2 max pool behind the layer into it -- a fused block of
+ * two layers in the sense of Sec. III-B: out[y][x] = max of the four requantised values of its window,
+ * the output map is [h/2][w/2] (a last odd row or column is dropped, as by the pooling layer).
  * Tensors: in_dev int8 [batch][h][w][cin], out_dev int8 [batch][h][w][cout], DEVICE, caller-owned,
  * 16-byte aligned, below 2 GiB each.  weight: HOST int8 [cout][ksize][ksize][cin]; scale, bias: HOST fp32
  * [cout]; all three borrowed for the call only (repacked into device buffers the layer owns).  With
@@ -243,7 +246,7 @@ dlf_status dlf_plan_refine(dlf_plan_t* plan, const void* in_dev, void* out_dev, 
  * budget: compute units the layer may use (<= 0: all 256). */
 typedef struct dlf_i8conv_s dlf_i8conv_t;
 dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, int32_t cout, int32_t ksize,
-                             int32_t relu, const int8_t* weight, const float* scale, const float* bias, int32_t budget,
+                             int32_t relu, int32_t pool, const int8_t* weight, const float* scale, const float* bias, int32_t budget,
                              dlf_i8conv_t** out);
 void dlf_i8conv_destroy(dlf_i8conv_t* layer);
 /* Tile (th x tw output pixels per work item; 1 x pixels for a 1x1 layer on the block kernel), kernel shape

@@ -102,6 +102,14 @@ def conv2d_i8(x, w, scale, bias, stride=1, pad=0, relu=False, return_acc=False):
     return (out, acc) if return_acc else out
 
 
+def maxpool2x2_i8(x):
+    """2x2 stride-2 max pool without padding on an int8 map [N,H,W,C] (a last odd row or column is
+    dropped): the plain definition, by reshaping."""
+    x = np.asarray(x)
+    N, H, W, C = x.shape
+    return x[:, :H // 2 * 2, :W // 2 * 2].reshape(N, H // 2, 2, W // 2, 2, C).max(axis=(2, 4))
+
+
 def fc(x, w, b=None, acc="f32"):
     """x [N,K], w [Cout,K] -> [N,Cout] (Eq. 2 with M = batch)."""
     x, w = _f32(x), _f32(w)

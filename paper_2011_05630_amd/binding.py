@@ -131,7 +131,7 @@ def lib():
     L.dlf_plan_refine.restype = i32
     L.dlf_plan_group_io.argtypes = [vp, i32, i32p, i32p]
     L.dlf_plan_group_io.restype = i32
-    L.dlf_i8conv_create.argtypes = [i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, i32, ctypes.POINTER(vp)]
+    L.dlf_i8conv_create.argtypes = [i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, i32, ctypes.POINTER(vp)]
     L.dlf_i8conv_create.restype = i32
     L.dlf_i8conv_destroy.argtypes = [vp]
     L.dlf_i8conv_destroy.restype = None
@@ -313,7 +313,7 @@ def dlf_plan_layer_output(plan, layer):
     return lib().dlf_plan_layer_output(plan, layer)
 
 
-def dlf_i8conv_create(batch, h, w, cin, cout, ksize, relu, weight=None, scale=None, bias=None, budget=0):
+def dlf_i8conv_create(batch, h, w, cin, cout, ksize, relu, weight=None, scale=None, bias=None, budget=0, pool=False):
     """weight: numpy int8 [cout,ksize,ksize,cin] (None: shape-only layer), scale / bias: numpy fp32 [cout]."""
     out = ctypes.c_void_p()
     wp = sp = bp = None
@@ -324,7 +324,7 @@ def dlf_i8conv_create(batch, h, w, cin, cout, ksize, relu, weight=None, scale=No
         if weight.shape != (cout, ksize, ksize, cin) or scale.shape != (cout,) or bias.shape != (cout,):
             raise ValueError("weight [cout,ksize,ksize,cin], scale [cout], bias [cout] expected")
         wp, sp, bp = weight.ctypes.data, scale.ctypes.data, bias.ctypes.data
-    _check(lib().dlf_i8conv_create(batch, h, w, cin, cout, ksize, int(bool(relu)), wp, sp, bp, budget,
+    _check(lib().dlf_i8conv_create(batch, h, w, cin, cout, ksize, int(bool(relu)), int(bool(pool)), wp, sp, bp, budget,
                                    ctypes.byref(out)))
     return out
 

@@ -2832,7 +2832,7 @@ void dlf_i8conv_destroy(dlf_i8conv_t* l)
 }
 
 dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, int32_t cout, int32_t ksize,
-                             int32_t relu, const int8_t* weight, const float* scale, const float* bias, int32_t budget,
+                             int32_t relu, int32_t pool, const int8_t* weight, const float* scale, const float* bias, int32_t budget,
                              dlf_i8conv_t** out)
 {
     if (!out) return fail(DLF_ERR_INVALID_ARG, "dlf_i8conv_create: null out pointer");
@@ -2841,6 +2841,9 @@ dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, i
         return fail(DLF_ERR_INVALID_ARG, "dlf_i8conv_create: sizes out of range");
     if (weight && (!scale || !bias)) return fail(DLF_ERR_INVALID_ARG, "dlf_i8conv_create: weights without scale / bias");
     if (ksize != 1 && ksize != 3) return fail(DLF_ERR_UNSUPPORTED, "the int8 layer is a 1x1 or a 3x3 convolution");
+    if (pool != 0 && pool != 1) return fail(DLF_ERR_INVALID_ARG, "dlf_i8conv_create: pool is 0 or 1");
+    if (pool && (ksize != 3 || h < 2 || w < 2))
+        return fail(DLF_ERR_UNSUPPORTED, "the 2x2 max pool folds into the 3x3 layer only, on maps of at least 2 x 2");
     if ((cin % 64) != 0 || (cout % 16) != 0)
         return fail(DLF_ERR_UNSUPPORTED, "the int8 layer needs cin %% 64 == 0 and cout %% 16 == 0");
     if ((int64_t)batch * h * w * cin >= (int64_t)1 << 31 || (int64_t)batch * h * w * cout >= (int64_t)1 << 31)
@@ -2868,7 +2871,9 @@ dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, i
     DlfC3sArgs cs;
     uint64_t cost_s = 0;
     bool have_s = false;
-    if (c3s_cin_ok(L.d.cin) && !(g_c3_force.shape >= 0 && g_c3_force.shape < DLF_C3_SHAPES)) {
+    if (pool) {
+        if (g_c3_force.shape == DLF_C3_SHAPES) return fail(DLF_ERR_INFEASIBLE, "the small-map kernel folds no pool");
+    } else if (c3s_cin_ok(L.d.cin) && !(g_c3_force.shape >= 0 && g_c3_force.shape < DLF_C3_SHAPES)) {
         if (g_c3_force.shape == DLF_C3_SHAPES && g_c3_force.th > 0) {
             have_s = c3s_build(L, batch, g_c3_force.th, 0, 0, 160 * 1024, cs);
             if (!have_s) return fail(DLF_ERR_INFEASIBLE, "the forced split of K does not fit this layer");
@@ -2908,13 +2913,13 @@ dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, i
         l->th = 1; l->tw = 32 * PW_FP[shape];
     } else {
     if (g_c3_force.shape >= 0 && g_c3_force.shape < DLF_C3_SHAPES) {      // testing hook: shape and tile as given
-        if (!c3_build(0, L.d.cin, g_c3_force.shape, g_c3_force.th, g_c3_force.tw, 160 * 1024, cc))
+        if (!c3_build(pool, L.d.cin, g_c3_force.shape, g_c3_force.th, g_c3_force.tw, 160 * 1024, cc))
             return fail(DLF_ERR_INFEASIBLE, "the forced shape and tile do not fit this layer");
-    } else if (!c3_choose(L, 0, batch, budget, 160 * 1024, cc, cost))
+    } else if (!c3_choose(L, pool, batch, budget, 160 * 1024, cc, cost))
         return fail(DLF_ERR_INFEASIBLE, "no tile of the block kernel fits this layer");
     DlfC3Args& ca = l->ca;
     ca.batch = batch; ca.h = h; ca.w_ = w; ca.cin = cin / 2; ca.cout = cout;
-    ca.ncb = L.ncb; ca.nsteps = L.nsteps; ca.act = relu ? 1 : 0; ca.pool2 = 0;
+    ca.ncb = L.ncb; ca.nsteps = L.nsteps; ca.act = relu ? 1 : 0; ca.pool2 = pool;
     ca.th = cc.th; ca.tw = cc.tw;
     ca.tiles_y = ceil_div(h, cc.th); ca.tiles_x = ceil_div(w, cc.tw);
     ca.n_cg = ceil_div(L.ncb, 2 * C3_WC[cc.shape]);

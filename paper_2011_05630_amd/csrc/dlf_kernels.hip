@@ -1831,7 +1831,8 @@ __device__ __forceinline__ void wait_vmcnt_dyn(int n)
 // What differs: exact int32 accumulators that start at zero, and an epilogue that requantises --
 // (float)acc, one fused multiply-add with the channel's scale and bias, round half to even, clamp
 // to [-128 or 0, 127] -- and stores int8, four lanes of 16 bytes covering a wave's 64 channels of
-// a pixel.  No pool, no residual operand in this form.
+// a pixel.  The 2x2 max pool behind the layer can be folded in (on the requantised values); no residual
+// operand in this form.
 template <int WC, int ACH, int FP, bool I8 = false>
 __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
 {
@@ -2116,6 +2117,13 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
             const float lo = a.act != 0 ? 0.0f : -128.0f;
             const int part = lane & 3;
             const int cch = (e_cg * NCBW + wc * 2) * 32 + part * 16;
+            // with the 2x2 max pool folded in, the window is the 4 lanes of a quad (pix_to_rc): the maximum
+            // is taken on the requantised values (the pooled layer's definition), lane 0 of a quad writes
+            // row l32 / 4, and a pass stores 8 pooled pixels
+            const bool pool = a.pool2 != 0;
+            const int oh = pool ? a.h >> 1 : a.h, ow = pool ? a.w_ >> 1 : a.w_, otw = pool ? a.tw >> 1 : a.tw;
+            const int oy0 = pool ? e_ty0 >> 1 : e_ty0, ox0 = pool ? e_tx0 >> 1 : e_tx0;
+            const int onpix = pool ? npix >> 2 : npix;
 #pragma unroll
             for (int p = 0; p < FP; ++p) {
 #pragma unroll
@@ -2131,21 +2139,26 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
                             float t = __builtin_fmaf((float)acc[f][p][q * 4 + r], sv[r], bv[r]);
                             t = __builtin_rintf(t);
                             t = __builtin_fminf(__builtin_fmaxf(t, lo), 127.0f);
+                            if (pool) {
+                                t = __builtin_fmaxf(t, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, t), 0xB1, 0xF, 0xF, true)));
+                                t = __builtin_fmaxf(t, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, t), 0x4E, 0xF, 0xF, true)));
+                            }
                             u |= ((unsigned)(int)t & 255u) << (8 * r);
                         }
-                        *(unsigned*)(tb8 + i8t_write_off(l32, f * 2 + (q >> 1), (q & 1) * 2 + lhi)) = u;
+                        if (!pool || (l32 & 3) == 0)
+                            *(unsigned*)(tb8 + i8t_write_off(pool ? l32 >> 2 : l32, f * 2 + (q >> 1), (q & 1) * 2 + lhi)) = u;
                     }
                 }
                 __builtin_amdgcn_wave_barrier();
 #pragma unroll
                 for (int it = 0; it < 2; ++it) {
                     const int row = it * 16 + (lane >> 2);
-                    const int opix = wp * (32 * FP) + p * 32 + row;
-                    const int ry = div_by(opix, tw_m), rx = opix - ry * a.tw;
-                    const int gy = e_ty0 + ry, gx = e_tx0 + rx;
-                    const bool ok = opix < npix && gy < a.h && gx < a.w_ && cch < a.cout;
+                    const int opix = pool ? wp * (8 * FP) + p * 8 + row : wp * (32 * FP) + p * 32 + row;
+                    const int ry = div_by(opix, tw_m), rx = opix - ry * otw;
+                    const int gy = oy0 + ry, gx = ox0 + rx;
+                    const bool ok = (!pool || row < 8) && opix < onpix && gy < oh && gx < ow && cch < a.cout;
                     const u4v v = i8t_read(tb8, row, part);
-                    if (ok) *(u4v*)(out8 + (size_t)((e_n * a.h + gy) * a.w_ + gx) * (size_t)a.cout + cch) = v;
+                    if (ok) *(u4v*)(out8 + (size_t)((e_n * oh + gy) * ow + gx) * (size_t)a.cout + cch) = v;
                 }
                 __builtin_amdgcn_wave_barrier();
             }
@@ -4156,7 +4169,7 @@ extern "C" int dlf_launch_c3_i8(const DlfC3Args* a, int shape, int grid, int lds
 {
     c3_kernel_t k = c3_kernel_i8(shape);
     if (k == nullptr || grid < 8 || (grid & 7) != 0 || lds_bytes <= 0 || a->scale == nullptr || a->res != nullptr ||
-        a->pool2 != 0 || (a->cout & 15) != 0)
+        (a->cout & 15) != 0 || (a->pool2 != 0 && (((a->th | a->tw) & 1) != 0 || a->h < 2 || a->w_ < 2)))
         return (int)hipErrorInvalidValue;
     launch(k, dim3(grid), dim3(DLF_C3_WAVES * 64), (size_t)lds_bytes, (hipStream_t)stream, *a);
     return (int)hipGetLastError();

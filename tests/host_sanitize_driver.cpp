@@ -204,7 +204,7 @@ int main()
                 for (int32_t hw : {1, 7, 14, 28, 56, 112})
                     for (int32_t ch : {64, 128, 512}) {
                         dlf_i8conv_t* q = nullptr;
-                        if (dlf_i8conv_create(3, hw, hw + 1, ch, ch + 16, k, 1, nullptr, nullptr, nullptr, 0, &q) != DLF_OK)
+                        if (dlf_i8conv_create(3, hw, hw + 1, ch, ch + 16, k, 1, (k == 3 && hw > 1) ? 1 : 0, nullptr, nullptr, nullptr, 0, &q) != DLF_OK)
                             die("dlf_i8conv_create");
                         int32_t th, tw, sh, gr;
                         uint64_t ops;
@@ -215,12 +215,14 @@ int main()
                     }
             {
                 dlf_i8conv_t* q = nullptr;
-                bad += dlf_i8conv_create(1, 8, 8, 64, 64, 3, 0, nullptr, nullptr, nullptr, 0, nullptr) == DLF_OK;
-                bad += dlf_i8conv_create(1, 8, 8, 32, 64, 3, 0, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;
-                bad += dlf_i8conv_create(1, 8, 8, 64, 8, 1, 0, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;
-                bad += dlf_i8conv_create(1, 8, 8, 64, 64, 2, 0, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;
-                bad += dlf_i8conv_create(1, -8, 8, 64, 64, 3, 0, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;
-                bad += dlf_i8conv_create(1 << 20, 1 << 10, 1 << 10, 64, 64, 3, 0, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;
+                bad += dlf_i8conv_create(1, 8, 8, 64, 64, 3, 0, 0, nullptr, nullptr, nullptr, 0, nullptr) == DLF_OK;
+                bad += dlf_i8conv_create(1, 8, 8, 32, 64, 3, 0, 0, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;
+                bad += dlf_i8conv_create(1, 8, 8, 64, 8, 1, 0, 0, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;
+                bad += dlf_i8conv_create(1, 8, 8, 64, 64, 2, 0, 0, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;
+                bad += dlf_i8conv_create(1, -8, 8, 64, 64, 3, 0, 0, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;
+                bad += dlf_i8conv_create(1 << 20, 1 << 10, 1 << 10, 64, 64, 3, 0, 0, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;
+                bad += dlf_i8conv_create(1, 8, 8, 64, 64, 1, 0, 1, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;     // pool behind a 1x1
+                bad += dlf_i8conv_create(1, 8, 8, 64, 64, 3, 0, 2, nullptr, nullptr, nullptr, 0, &q) == DLF_OK;
                 bad += dlf_i8conv_info(nullptr, nullptr, nullptr, nullptr, nullptr, nullptr) == DLF_OK;
                 dlf_i8conv_destroy(nullptr);
             }

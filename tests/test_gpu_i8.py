@@ -12,11 +12,13 @@ from synth import gen
 pytestmark = pytest.mark.gpu
 
 
-def _run(x, wt, sc, b, relu, budget=0):
+def _run(x, wt, sc, b, relu, budget=0, pool=False):
     from paper_2011_05630_amd import binding as B
     n, h, w, cin = x.shape
     cout, ksize = wt.shape[0], wt.shape[1]
-    layer = B.dlf_i8conv_create(n, h, w, cin, cout, ksize, relu, wt, sc, b, budget)
+    layer = B.dlf_i8conv_create(n, h, w, cin, cout, ksize, relu, wt, sc, b, budget, pool)
+    if pool:
+        h, w = h // 2, w // 2
     try:
         info = B.dlf_i8conv_info(layer)
         xt = torch.from_numpy(x).cuda()
@@ -29,16 +31,18 @@ def _run(x, wt, sc, b, relu, budget=0):
         B.dlf_i8conv_destroy(layer)
 
 
-def _check(case, x, wt, sc, b, relu, budget=0):
+def _check(case, x, wt, sc, b, relu, budget=0, pool=False):
     from oracle import oracle
-    announce("i8conv", case, x.shape, "cout", wt.shape[0], "relu", relu)
-    got, info = _run(x, wt, sc, b, relu, budget)
+    announce("i8conv", case, x.shape, "cout", wt.shape[0], "relu", relu, "pool", pool)
+    got, info = _run(x, wt, sc, b, relu, budget, pool)
     ref = oracle.conv2d_i8(x, wt, sc, b, 1, wt.shape[1] // 2, relu)
+    if pool:
+        ref = oracle.maxpool2x2_i8(ref)
     bad = np.argwhere(got != ref)
     assert bad.size == 0, (case, info, len(bad), bad[:5].tolist(),
                            [(int(got[tuple(i)]), int(ref[tuple(i)])) for i in bad[:5]])
     if ref.size >= 4096:
-        assert ref.min() <= (0 if relu else -100) and ref.max() >= 100      # the case exercises the range
+        assert ref.min() <= (0 if relu else (-50 if pool else -100)) and ref.max() >= 100      # the case exercises the range
     return info
 
 
@@ -81,6 +85,28 @@ def test_i8conv_1x1_full_range_and_small_budget():
     x, wt, sc, b = gen.make_i8_layer(2, 20, 20, 128, 160, 1, seed=32, full_range=True)
     _check("1x1 full range", x, wt, sc, b, False)
     _check("1x1 full range, 8 CUs (several blocks per workgroup)", x, wt, sc, b, True, budget=8)
+
+
+@pytest.mark.parametrize("case", [(2, 20, 28, 64, 48, False), (1, 56, 56, 128, 128, True), (3, 9, 33, 64, 80, True),
+                                  (1, 14, 14, 512, 512, True), (2, 2, 2, 64, 16, False), (1, 30, 6, 256, 96, True)])
+def test_i8conv_with_folded_pool_equals_oracle(case):
+    """conv 3x3 + 2x2 max pool as one launch against conv then pool in the oracle; odd maps drop their
+    last row / column."""
+    n, h, w, cin, cout, relu = case
+    x, wt, sc, b = gen.make_i8_layer(n, h, w, cin, cout, 3, seed=4000 + h * w + cin)
+    _check(("pool",) + case, x, wt, sc, b, relu, pool=True)
+
+
+@pytest.mark.parametrize("shape,th,tw", [(0, 8, 16), (1, 14, 14), (2, 16, 28), (3, 14, 28), (4, 16, 32), (4, 14, 28)])
+def test_i8conv_with_folded_pool_every_kernel_shape(shape, th, tw):
+    from paper_2011_05630_amd import binding as B
+    x, wt, sc, b = gen.make_i8_layer(2, 30, 37, 128, 160, 3, seed=60 + shape)
+    B.dlf_debug_block3x3_mode(0, shape, th, tw)
+    try:
+        info = _check(("pool shape", shape, th, tw), x, wt, sc, b, True, budget=64, pool=True)
+    finally:
+        B.dlf_debug_block3x3_mode(0, -1, 0, 0)
+    assert (info["shape"], info["th"], info["tw"]) == (shape, th, tw)
 
 
 def test_i8conv_full_range_operands():

@@ -172,6 +172,17 @@ def test_random_requantisation_against_rationals():
         assert int(out2.flat[i]) == requant_exact(int(acc.flat[i]), sc[co], b[co], False)
 
 
+def test_int8_pool_equals_the_float_pooling_routine():
+    rng = np.random.default_rng(41)
+    for shape in ((2, 6, 8, 5), (1, 7, 9, 3), (1, 2, 2, 1)):
+        x = rng.integers(-128, 128, size=shape).astype(np.int8)
+        got = oracle.maxpool2x2_i8(x)
+        ref = oracle.maxpool(x.astype(np.float32), 2, 2, 0)
+        assert got.dtype == np.int8 and np.array_equal(got.astype(np.float32), ref)
+    x = np.array([[[[-128], [-5]], [[-7], [-100]]]], np.int8)           # all negative: no padding value leaks in
+    assert oracle.maxpool2x2_i8(x).tolist() == [[[[-5]]]]
+
+
 def test_overflow_is_reported():
     cin = 140000
     x = np.full((1, 1, 1, cin), 127, np.int8)
