@@ -344,6 +344,8 @@ I8_LAYERS = [  # name, batch, h = w, cin, cout, filter: the 3x3 layers of VGG-16
     ("res2_reduce", 32, 56, 256, 64, 1), ("res2_expand", 32, 56, 64, 256, 1), ("res3_reduce", 32, 28, 512, 128, 1),
     ("res3_expand", 32, 28, 128, 512, 1), ("res4_reduce", 32, 14, 1024, 256, 1), ("res4_expand", 32, 14, 256, 1024, 1),
     ("res5_3x3", 32, 7, 512, 512, 3), ("res5_reduce", 32, 7, 2048, 512, 1),
+    # a 3x3 layer and the 2x2 max pool behind it as one launch (the last layers of VGG-16's stages 3 and 4)
+    ("vgg_conv3_3_pool", 16, 56, 256, 256, 3, True), ("vgg_conv4_3_pool", 16, 28, 512, 512, 3, True),
 ]
 
 
@@ -356,12 +358,14 @@ def bench_i8(steps, warmup, cpu=True, layers=None):
     from paper_2011_05630_amd import binding as B
     out = {}
     stream = torch.cuda.current_stream().cuda_stream
-    for name, batch, hw, c, co, k in (layers or I8_LAYERS):
+    for name, batch, hw, c, co, k, *rest in (layers or I8_LAYERS):
+        pool = bool(rest and rest[0])
+        ohw = hw // 2 if pool else hw
         x, wt, sc, b = gen.make_i8_layer(batch, hw, hw, c, co, k)
-        layer = B.dlf_i8conv_create(batch, hw, hw, c, co, k, True, wt, sc, b, 0)
+        layer = B.dlf_i8conv_create(batch, hw, hw, c, co, k, True, wt, sc, b, 0, pool)
         info = B.dlf_i8conv_info(layer)
         xt = torch.from_numpy(x).cuda()
-        yt = torch.empty((batch, hw, hw, co), dtype=torch.int8, device="cuda")
+        yt = torch.empty((batch, ohw, ohw, co), dtype=torch.int8, device="cuda")
         for _ in range(warmup):
             B.dlf_i8conv_run(layer, xt.data_ptr(), yt.data_ptr(), stream)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -374,14 +378,16 @@ def bench_i8(steps, warmup, cpu=True, layers=None):
         us = e0.elapsed_time(e1) * 1e3 / steps
         B.dlf_i8conv_destroy(layer)
         tops = info["op_count"] / (us * 1e-6) / 1e12
-        nbytes = batch * hw * hw * (c + co) + k * k * c * co            # input + output + weights, once each
-        rec = dict(batch=batch, hw=hw, cin=c, cout=co, filter=k, us=us, tops=tops,
+        nbytes = batch * (hw * hw * c + ohw * ohw * co) + k * k * c * co            # input + output + weights, once each
+        rec = dict(batch=batch, hw=hw, cin=c, cout=co, filter=k, pool=pool, us=us, tops=tops,
                    frac_int8_mfma_peak=tops / MFMA_INT8_PEAK_TOPS, gbs=nbytes / (us * 1e-6) / 1e9,
                    frac_hbm_peak=nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                    tile="%dx%d" % (info["th"], info["tw"]), kernel_shape=info["shape"])
         # the same layer in fp16 (one group, the library's own choice of kernel)
-        net = dict(name=name, layers=[nets.conv(c, co, k, 1, k // 2, "relu")], in_h=hw, in_w=hw, in_c=c, input_dist="normal")
+        net = dict(name=name, layers=[nets.conv(c, co, k, 1, k // 2, "relu")] + ([nets.maxpool(co, 2, 2, 0)] if pool else []),
+                   in_h=hw, in_w=hw, in_c=c, input_dist="normal")
         r = time_plan(net, batch, dict(mode=B.TUNER_DP), steps, warmup)
+        assert r["groups"] == 1
         rec["fp16_us"] = r["ms_per_step"] * 1e3
         rec["fp16_kernel"] = r["acct"][0]["kernel"]
         rec["speedup_over_fp16"] = rec["fp16_us"] / us
