@@ -404,6 +404,51 @@ def bench_i8(steps, warmup, cpu=True, layers=None):
     return out
 
 
+def bench_i8_vgg_body(steps, warmup, batch=16, hw=224):
+    """VGG-16's convolutional body behind its first layer (12 quantised 3x3 layers, the five pools folded
+    into the layers in front of them) as a chain of dlf_i8conv_run launches, and the same layers in fp16
+    under the DP plan."""
+    import torch
+    from synth import gen, nets
+    from paper_2011_05630_amd import binding as B
+    x, params = gen.make_i8_chain(batch, hw)
+    stream = torch.cuda.current_stream().cuda_stream
+    layers, bufs, ops, h = [], [torch.from_numpy(x).cuda()], 0, hw
+    for (wt, sc, b, pool) in params:
+        co, ci = wt.shape[0], wt.shape[3]
+        layers.append(B.dlf_i8conv_create(batch, h, h, ci, co, 3, True, wt, sc, b, 0, pool))
+        ops += B.dlf_i8conv_info(layers[-1])["op_count"]
+        h = h // 2 if pool else h
+        bufs.append(torch.empty((batch, h, h, co), dtype=torch.int8, device="cuda"))
+
+    def step():
+        for l, src, dst in zip(layers, bufs[:-1], bufs[1:]):
+            B.dlf_i8conv_run(l, src.data_ptr(), dst.data_ptr(), stream)
+
+    for _ in range(warmup):
+        step()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    for l in layers:
+        B.dlf_i8conv_destroy(l)
+    fl = []
+    for (ci, co, pool) in gen.VGG16_BODY:
+        fl.append(nets.conv(ci, co, 3, 1, 1, "relu"))
+        if pool:
+            fl.append(nets.maxpool(co, 2, 2, 0))
+    net = dict(name="vgg16_body", layers=fl, in_h=hw, in_w=hw, in_c=64, input_dist="normal")
+    r = time_plan(net, batch, dict(mode=B.TUNER_DP), steps, warmup)
+    return dict(batch=batch, input="%dx%dx64" % (hw, hw), launches=len(layers), ms_per_step=ms, images_per_s=batch / (ms * 1e-3),
+                tops=ops / (ms * 1e-3) / 1e12, frac_int8_mfma_peak=ops / (ms * 1e-3) / 1e12 / MFMA_INT8_PEAK_TOPS,
+                fp16_ms_per_step=r["ms_per_step"], fp16_groups=r["groups"], speedup_over_fp16=r["ms_per_step"] / ms)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -460,10 +505,13 @@ def main():
         sweep_chain4(min(args.steps, 50), min(args.warmup, 10))
         return
     if args.i8:
-        print(json.dumps({"metric": "int8_conv3x3_tops", "unit": "TOP/s", "dtype": "i8", "data": "synthetic",
-                          "peak_tops": MFMA_INT8_PEAK_TOPS, "steps": min(args.steps, 100),
-                          "layers": bench_i8(min(args.steps, 100), min(args.warmup, 10), cpu=not args.no_cpu,
-                                             layers=[l for l in I8_LAYERS if l[0] == args.i8_layer] or None)}))
+        res = {"metric": "int8_conv3x3_tops", "unit": "TOP/s", "dtype": "i8", "data": "synthetic",
+               "peak_tops": MFMA_INT8_PEAK_TOPS, "steps": min(args.steps, 100),
+               "layers": bench_i8(min(args.steps, 100), min(args.warmup, 10), cpu=not args.no_cpu,
+                                  layers=[l for l in I8_LAYERS if l[0] == args.i8_layer] or None)}
+        if not args.i8_layer:
+            res["vgg16_body_b16"] = bench_i8_vgg_body(min(args.steps, 50), min(args.warmup, 10))
+        print(json.dumps(res))
         return
 
     from paper_2011_05630_amd import binding as B

@@ -58,6 +58,18 @@ def make_params(net, batch, seed=MASTER_SEED, residual_gain=RESIDUAL_BRANCH_GAIN
     return x, weights, biases
 
 
+VGG16_BODY = [  # VGG-16's convolutions behind its first layer: (cin, cout, a 2x2 max pool follows), input 64 channels
+    (64, 64, True), (64, 128, False), (128, 128, True), (128, 256, False), (256, 256, False), (256, 256, True),
+    (256, 512, False), (512, 512, False), (512, 512, True), (512, 512, False), (512, 512, False), (512, 512, True)]
+
+
+def make_i8_chain(batch, hw, specs=VGG16_BODY, seed=MASTER_SEED):
+    """Seeded operands of a chain of quantised 3x3 layers (ReLU behind each): (x int8 [batch,hw,hw,cin0],
+    [(weight, scale, bias, pool), ...]); each layer drawn by make_i8_layer with its own seed."""
+    x = make_i8_layer(batch, hw, hw, specs[0][0], 16, 3, seed)[0]
+    return x, [make_i8_layer(1, 1, 1, ci, co, 3, seed + 1 + i)[1:] + (pool,) for i, (ci, co, pool) in enumerate(specs)]
+
+
 def make_i8_layer(batch, h, w, cin, cout, k=3, seed=MASTER_SEED, full_range=False):
     """Seeded operands of one quantised convolution layer: (x int8 [batch,h,w,cin], weight int8
     [cout,k,k,cin], scale fp32 [cout], bias fp32 [cout]).

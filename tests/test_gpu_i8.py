@@ -187,6 +187,26 @@ def test_i8conv_benchmarked_layers_sampled_images(name):
     assert got.max() == 127 and (got == 0).mean() > 0.2
 
 
+def test_i8_vgg16_body_equals_oracle_chain():
+    """VGG-16's twelve convolutions behind its first layer with their five pools folded in, each layer fed
+    the previous one's int8 output, on a 64 x 64 input (maps of 64 .. 4 pixels a side, 2 x 2 after the last
+    pool): the chain `bench.py --i8` times at 224 x 224."""
+    from oracle import oracle
+    x, params = gen.make_i8_chain(2, 64)
+    got, ref = x, x
+    kinds = []
+    for i, (wt, sc, b, pool) in enumerate(params):
+        announce("i8 vgg body layer", i, wt.shape, "pool", pool)
+        got, info = _run(got, wt, sc, b, True, 0, pool)
+        kinds.append(info["shape"])
+        ref = oracle.conv2d_i8(ref, wt, sc, b, 1, 1, True)
+        if pool:
+            ref = oracle.maxpool2x2_i8(ref)
+        assert np.array_equal(got, ref), "layer %d" % i
+    assert got.shape == (2, 2, 2, 512) and got.max() > 20, (got.shape, int(got.max()))
+    assert 5 in kinds and any(k < 5 for k in kinds), kinds         # small-map and block kernels both take part
+
+
 def test_i8_layers_captured_in_a_hip_graph_replay_to_the_oracle():
     """dlf_i8conv_run only launches a kernel, so a chain of layers (block 3x3, block 1x1, small-map
     kernel) can be captured; every replay, with eager work and synchronisations between the replays,
