@@ -1151,7 +1151,9 @@ bool c3s_pw_eligible(const Layer& L, int batch)
 
 // One configuration: ksplit waves per channel block, the map cut into `rows` x `cols` equal tiles
 // (0: as few as tiles of at most 8 x 8 output pixels allow).
-bool c3s_build(const Layer& L, int batch, int ksplit, int rows, int cols, int max_lds, DlfC3sArgs& cs)
+// pool2 (quantised 3x3 form only): the 2x2 max pool behind the layer folded in, which needs tiles 8 pixels
+// wide and of even height.
+bool c3s_build(const Layer& L, int batch, int ksplit, int rows, int cols, int max_lds, DlfC3sArgs& cs, int pool2 = 0)
 {
     memset(&cs, 0, sizeof cs);
     cs.taps = L.d.kh * L.d.kw;
@@ -1162,6 +1164,12 @@ bool c3s_build(const Layer& L, int batch, int ksplit, int rows, int cols, int ma
     if (cols <= 0) cols = ceil_div(L.out_w, 8);
     cs.th = ceil_div(L.out_h, rows);
     cs.tw = ceil_div(L.out_w, cols);
+    if (pool2) {
+        if (L.d.kh != 3 || L.d.stride != 1 || L.out_h < 2 || L.out_w < 2) return false;
+        cs.th = round_up(cs.th, 2);
+        cs.tw = 8;
+        cs.pool2 = 1;
+    }
     if (cs.th > 8 || cs.tw > 8) return false;
     cs.tp = cs.th * cs.tw;
     cs.rw = (cs.tw - 1) * cs.stride + 1 + 2 * halo;
@@ -1201,7 +1209,7 @@ uint64_t c3s_cost_ps(const Layer& L, int batch, int budget, const DlfC3sArgs& cs
 
 // Cheapest split of K over the waves and cut of the map (ties: the smaller split, the fewer tiles):
 // the largest tiles first, then one more row or column of tiles while a region does not fit LDS.
-bool c3s_choose(const Layer& L, int batch, int budget, int max_lds, DlfC3sArgs& best, uint64_t& cost)
+bool c3s_choose(const Layer& L, int batch, int budget, int max_lds, DlfC3sArgs& best, uint64_t& cost, int pool2 = 0)
 {
     bool found = false;
     const int r0 = ceil_div(L.out_h, 8), c0 = ceil_div(L.out_w, 8);
@@ -1209,7 +1217,7 @@ bool c3s_choose(const Layer& L, int batch, int budget, int max_lds, DlfC3sArgs& 
         for (int er = 0; er <= extra; ++er)
             for (int ks = 1; ks <= 4; ks *= 2) {
                 DlfC3sArgs cs;
-                if (!c3s_build(L, batch, ks, r0 + er, c0 + extra - er, max_lds, cs)) continue;
+                if (!c3s_build(L, batch, ks, r0 + er, c0 + extra - er, max_lds, cs, pool2)) continue;
                 const uint64_t c = c3s_cost_ps(L, batch, budget, cs);
                 if (!found || c < cost) { found = true; cost = c; best = cs; }
             }
@@ -2871,20 +2879,18 @@ dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, i
     DlfC3sArgs cs;
     uint64_t cost_s = 0;
     bool have_s = false;
-    if (pool) {
-        if (g_c3_force.shape == DLF_C3_SHAPES) return fail(DLF_ERR_INFEASIBLE, "the small-map kernel folds no pool");
-    } else if (c3s_cin_ok(L.d.cin) && !(g_c3_force.shape >= 0 && g_c3_force.shape < DLF_C3_SHAPES)) {
+    if (c3s_cin_ok(L.d.cin) && !(g_c3_force.shape >= 0 && g_c3_force.shape < DLF_C3_SHAPES)) {
         if (g_c3_force.shape == DLF_C3_SHAPES && g_c3_force.th > 0) {
-            have_s = c3s_build(L, batch, g_c3_force.th, 0, 0, 160 * 1024, cs);
+            have_s = c3s_build(L, batch, g_c3_force.th, 0, 0, 160 * 1024, cs, pool);
             if (!have_s) return fail(DLF_ERR_INFEASIBLE, "the forced split of K does not fit this layer");
         } else {
-            have_s = c3s_choose(L, batch, budget, 160 * 1024, cs, cost_s);
+            have_s = c3s_choose(L, batch, budget, 160 * 1024, cs, cost_s, pool);
         }
         if (have_s && g_c3_force.shape != DLF_C3_SHAPES) {
             uint64_t other = UINT64_MAX;
             C3Cfg c2;
             if (ksize == 1) other = pw_shape_cost_ps(L, batch, budget, pw_shape_ok(L, 3) ? 3 : 4);
-            else if (!c3_choose(L, 0, batch, budget, 160 * 1024, c2, other)) other = UINT64_MAX;
+            else if (!c3_choose(L, pool, batch, budget, 160 * 1024, c2, other)) other = UINT64_MAX;
             if (other <= cost_s) have_s = false;
         }
     } else if (g_c3_force.shape == DLF_C3_SHAPES) {

@@ -289,6 +289,8 @@ struct DlfC3sArgs {
     int32_t slice_major;  // 1: an XCD keeps to one slice (nsl 2, 4 or 8); 0: the slices of a tile share an XCD
     // quantised form (int8 tensors, `cin` = byte pairs per pixel, `act` != 0 = ReLU) if not null:
     const float* scale;   // requantisation scale per output channel, padded to ncb * 32
+    int32_t pool2;        // quantised 3x3 form: the 2x2 max pool behind the layer folded in (tw = 8, th even;
+                          // oh, ow, th, tw count convolution pixels, the output map is [oh / 2][ow / 2])
 };
 
 // 3x3 convolution (stride 1, pad 1, cin = cout = c: 64, 128 or 256) and the 1x1 convolution behind it, with

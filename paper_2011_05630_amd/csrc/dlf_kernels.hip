@@ -3176,9 +3176,16 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
         f4v scv[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) scv[q] = *(const f4v*)(a.scale + cb * 32 + q * 8 + lhi * 4);
+        // With the 2x2 max pool folded in (tiles 8 pixels wide and of even height): a 32-pixel block is four
+        // tile rows, lane l32 holds tile pixel (l32 / 8, l32 % 8) of them, so a window is the lanes
+        // {l, l ^ 1, l ^ 8, l ^ 9}: one quad permute and one rotation by 8 inside the row of 16 lanes; the
+        // lane of the window's first pixel writes pooled pixel (l32 / 16) * 4 + (l32 % 8) / 2 of the block's 8.
+        const bool pool = a.pool2 != 0;
+        const int poh = a.oh >> 1, pow_ = a.ow >> 1;
 #pragma unroll
         for (int p = 0; p < FP; ++p) {
             if (p * 32 < a.tp) {
+                const int wrow = pool ? ((l32 >> 4) << 2) + ((l32 & 7) >> 1) : l32;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     unsigned u = 0;
@@ -3187,22 +3194,35 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
                         float t = __builtin_fmaf((float)acc[p][q * 4 + r], scv[q][r], biasv[q][r]);
                         t = __builtin_rintf(t);
                         t = __builtin_fminf(__builtin_fmaxf(t, lo), 127.0f);
+                        if (pool) {
+                            t = __builtin_fmaxf(t, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, t), 0xB1, 0xF, 0xF, true)));
+                            t = __builtin_fmaxf(t, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, t), 0x128, 0xF, 0xF, true)));
+                        }
                         u |= ((unsigned)(int)t & 255u) << (8 * r);
                     }
-                    *(unsigned*)(tb8 + l32 * 32 + ((((q >> 1) ^ (l32 >> 2)) & 1) << 4) + (((((q & 1) * 2 + lhi) ^ (l32 >> 3)) & 3) << 2)) = u;
+                    if (!pool || (l32 & 9) == 0)
+                        *(unsigned*)(tb8 + wrow * 32 + ((((q >> 1) ^ (wrow >> 2)) & 1) << 4) + (((((q & 1) * 2 + lhi) ^ (wrow >> 3)) & 3) << 2)) = u;
                 }
                 __builtin_amdgcn_wave_barrier();
                 const int part = lane & 1, pl = lane >> 1;
                 const int cc = cb * 32 + part * 16;
-                const int px_ = p * 32 + pl;
-                const int row = div_by(px_, tw_m), colp = px_ - row * a.tw;
-                const int oy = oy0 + row, ox = ox0 + colp;
                 const u4v v = *(const u4v*)(tb8 + pl * 32 + (((part ^ (pl >> 2)) & 1) << 4));
                 const int k = pl >> 3;
                 const u4v v1 = (k & 1) ? u4v{v.y, v.x, v.w, v.z} : v;
                 const u4v v2 = (k & 2) ? u4v{v1.z, v1.w, v1.x, v1.y} : v1;
-                if (px_ < a.tp && oy < a.oh && ox < a.ow && cc < a.cout)
-                    *(u4v*)(out8 + ((size_t)((n * a.oh + oy) * a.ow + ox) * a.cout + cc)) = v2;
+                if (pool) {
+                    // pooled pixel pl (< 8) of the block: pooled tile row 2 p + pl / 4, column pl % 4
+                    const int qy = 2 * p + (pl >> 2), qx = pl & 3;
+                    const int oy = (oy0 >> 1) + qy, ox = (ox0 >> 1) + qx;
+                    if (pl < 8 && 2 * qy < a.th && oy < poh && ox < pow_ && cc < a.cout)
+                        *(u4v*)(out8 + ((size_t)((n * poh + oy) * pow_ + ox) * a.cout + cc)) = v2;
+                } else {
+                    const int px_ = p * 32 + pl;
+                    const int row = div_by(px_, tw_m), colp = px_ - row * a.tw;
+                    const int oy = oy0 + row, ox = ox0 + colp;
+                    if (px_ < a.tp && oy < a.oh && ox < a.ow && cc < a.cout)
+                        *(u4v*)(out8 + ((size_t)((n * a.oh + oy) * a.ow + ox) * a.cout + cc)) = v2;
+                }
                 __builtin_amdgcn_wave_barrier();
             }
         }
@@ -4341,10 +4361,13 @@ extern "C" int dlf_launch_c3s(const DlfC3sArgs* a, int grid, int lds_bytes, void
     if (lds_bytes != (int)DLF_C3S_LDS_BYTES(a->rp, a->cin) || lds_bytes > 160 * 1024) return (int)hipErrorInvalidValue;
     if (a->scale != nullptr) {       // the quantised form
         if (s != 1 || a->res != nullptr || (a->cout & 15) != 0) return (int)hipErrorInvalidValue;
+        if (a->pool2 != 0 && (a->pool2 != 1 || a->taps != 9 || a->tw != 8 || (a->th & 1) != 0 || a->oh < 2 || a->ow < 2))
+            return (int)hipErrorInvalidValue;
         launch(c3s_kernel_i8(a->taps, a->tp > 32 ? 2 : 1), dim3(grid), dim3(DLF_C3S_WAVES * 64), (size_t)lds_bytes,
                (hipStream_t)stream, *a);
         return (int)hipGetLastError();
     }
+    if (a->pool2 != 0) return (int)hipErrorInvalidValue;
     launch(c3s_kernel(a->taps, s, a->tp > 32 ? 2 : 1), dim3(grid), dim3(DLF_C3S_WAVES * 64), (size_t)lds_bytes,
            (hipStream_t)stream, *a);
     return (int)hipGetLastError();

@@ -146,6 +146,22 @@ def test_i8conv_small_map_kernel(k, ksplit, n, h, w, cin, cout):
     assert info["shape"] == 5 and info["th"] <= 8 and info["tw"] <= 8
 
 
+@pytest.mark.parametrize("ksplit,n,h,w,cin,cout", [(1, 2, 14, 14, 512, 512), (2, 3, 7, 7, 512, 80), (4, 1, 9, 11, 1024, 272),
+                                                   (2, 2, 13, 5, 512, 48), (1, 2, 2, 2, 512, 16), (4, 2, 16, 24, 512, 96),
+                                                   (1, 1, 4, 30, 1024, 64)])
+def test_i8conv_small_map_kernel_with_folded_pool(ksplit, n, h, w, cin, cout):
+    """The small-map kernel with the 2x2 max pool folded in (tiles 8 wide, of even height): one- and
+    two-block tiles, ragged tiles, odd maps, K split over 1, 2 and 4 waves."""
+    from paper_2011_05630_amd import binding as B
+    x, wt, sc, b = gen.make_i8_layer(n, h, w, cin, cout, 3, seed=500 + ksplit + h)
+    B.dlf_debug_block3x3_mode(0, 5, ksplit, 0)
+    try:
+        info = _check(("small map + pool", ksplit), x, wt, sc, b, True, pool=True)
+    finally:
+        B.dlf_debug_block3x3_mode(0, -1, 0, 0)
+    assert info["shape"] == 5 and info["tw"] == 8 and info["th"] % 2 == 0
+
+
 def test_i8conv_small_map_kernel_is_chosen_where_it_pays():
     from paper_2011_05630_amd import binding as B
     for (n, hw, c, k), want in (((16, 14, 512, 3), 5), ((16, 56, 256, 3), None), ((16, 28, 512, 3), None)):
@@ -155,6 +171,8 @@ def test_i8conv_small_map_kernel_is_chosen_where_it_pays():
         assert (info["shape"] == 5) == (want == 5), (n, hw, c, k, info)
     x, wt, sc, b = gen.make_i8_layer(16, 14, 14, 512, 512, 3, seed=9)
     _check("14x14 x 512, the library's choice", x, wt, sc, b, True)
+    info = _check("14x14 x 512 + pool, the library's choice", x, wt, sc, b, True, pool=True)
+    assert info["shape"] == 5, info
 
 
 def test_i8_chain_of_four_layers():
