@@ -249,9 +249,11 @@ dlf_status dlf_i8conv_create(int32_t batch, int32_t h, int32_t w, int32_t cin, i
                              int32_t relu, int32_t pool, const int8_t* weight, const float* scale, const float* bias, int32_t budget,
                              dlf_i8conv_t** out);
 void dlf_i8conv_destroy(dlf_i8conv_t* layer);
-/* Tile (th x tw output pixels per work item; 1 x pixels for a 1x1 layer on the block kernel), kernel shape
- * index (5: the kernel for maps of many channels and few pixels), workgroups launched, and the
- * operation count of Eq. 1 for the whole batch.  Any out pointer may be NULL. */
+/* Tile (th x tw convolution pixels per work item; 1 x pixels for a 1x1 layer on the block kernel), kernel
+ * shape index (5: the kernel for maps of many channels and few pixels; else ksize = 3: 0 .. 4, the block
+ * kernel's shapes -- output channels x pixels per workgroup 128 x 256, 128 x 256 with 128-byte activation
+ * blocks, 64 x 512, 64 x 512 with 128-byte blocks, 128 x 512 --, ksize = 1: 3 = 128 x 128, 4 = 64 x 256),
+ * workgroups launched, and the operation count of Eq. 1 for the whole batch.  Any out pointer may be NULL. */
 dlf_status dlf_i8conv_info(const dlf_i8conv_t* layer, int32_t* th, int32_t* tw, int32_t* shape, int32_t* grid,
                            uint64_t* op_count);
 /* One launch on hip_stream; asynchronous, allocates nothing.  DLF_ERR_NO_WEIGHTS on a shape-only layer. */
