@@ -35,6 +35,24 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i16v __attribute__((ext_vector_type(16)));
 template <bool I8> struct AccOf { typedef f16v type; };
 template <> struct AccOf<true> { typedef i16v type; };
+// Requantisation of one accumulator: (float)acc, one fused multiply-add with the channel's scale and bias,
+// clamp, round half to even.  The clamp comes first (the bounds are integers and rounding is monotone, so
+// the result is that of rounding first), and the rounding is the addition of 1.5 * 2^23, whose fp32 sum has
+// a unit in the last place of 1: the sum is the rounded value, and the low byte of its bit pattern is the
+// result as a two's-complement int8.  Four vector instructions per output, and the maximum of a pooling
+// window can be taken on the sums as they are.
+__device__ __forceinline__ float requant_biased(int acc, float sc, float bi, float lo)
+{
+    const float t = __builtin_fmaf((float)acc, sc, bi);
+    return __builtin_amdgcn_fmed3f(t, lo, 127.0f) + 12582912.0f;
+}
+// ... and the low bytes of four such sums as one dword (three byte permutes)
+__device__ __forceinline__ unsigned pack_low_bytes(float a, float b, float c, float d)
+{
+    const unsigned ab = __builtin_amdgcn_perm(__builtin_bit_cast(unsigned, b), __builtin_bit_cast(unsigned, a), 0x0c0c0400u);
+    const unsigned cd = __builtin_amdgcn_perm(__builtin_bit_cast(unsigned, d), __builtin_bit_cast(unsigned, c), 0x0c0c0400u);
+    return __builtin_amdgcn_perm(cd, ab, 0x05040100u);
+}
 // Transpose buffer of the quantised epilogues: rows of 64 bytes (a wave's 64 int8 channels of one
 // pixel), written one dword per lane by 32 lanes that hold 32 consecutive rows, read 16 bytes per
 // lane.  Row r keeps its 16-byte part c at position c ^ (r / 2) % 4 and, inside a part, dword d at
@@ -1704,14 +1722,10 @@ __global__ __launch_bounds__(DLF_PW_WAVES * 64, 2) void k_pwb(const DlfPwArgs a)
                 const f4v sv = *(const f4v*)(a.scale + cb * 32 + q * 8 + lhi * 4);
 #pragma unroll
                 for (int p = 0; p < 2; ++p) {
-                    unsigned u = 0;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        float t = __builtin_fmaf((float)acc[f][p][q * 4 + r], sv[r], bias[f][q][r]);
-                        t = __builtin_rintf(t);
-                        t = __builtin_fminf(__builtin_fmaxf(t, lo), 127.0f);
-                        u |= ((unsigned)(int)t & 255u) << (8 * r);
-                    }
+                    const unsigned u = pack_low_bytes(requant_biased(acc[f][p][q * 4 + 0], sv[0], bias[f][q][0], lo),
+                                                      requant_biased(acc[f][p][q * 4 + 1], sv[1], bias[f][q][1], lo),
+                                                      requant_biased(acc[f][p][q * 4 + 2], sv[2], bias[f][q][2], lo),
+                                                      requant_biased(acc[f][p][q * 4 + 3], sv[3], bias[f][q][3], lo));
                     *(unsigned*)(tb8 + i8t_write_off(p * 32 + l32, f * 2 + (q >> 1), (q & 1) * 2 + lhi)) = u;
                 }
             }
@@ -2133,18 +2147,17 @@ __global__ __launch_bounds__(DLF_C3_WAVES * 64, 1) void k_c3b(const DlfC3Args a)
                     for (int q = 0; q < 4; ++q) {
                         const f4v sv = *(const f4v*)(a.scale + cb * 32 + q * 8 + lhi * 4);
                         const f4v bv = *(const f4v*)(a.bias + cb * 32 + q * 8 + lhi * 4);
-                        unsigned u = 0;
+                        float tv[4];
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            float t = __builtin_fmaf((float)acc[f][p][q * 4 + r], sv[r], bv[r]);
-                            t = __builtin_rintf(t);
-                            t = __builtin_fminf(__builtin_fmaxf(t, lo), 127.0f);
+                            float t = requant_biased(acc[f][p][q * 4 + r], sv[r], bv[r], lo);
                             if (pool) {
                                 t = __builtin_fmaxf(t, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, t), 0xB1, 0xF, 0xF, true)));
                                 t = __builtin_fmaxf(t, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, t), 0x4E, 0xF, 0xF, true)));
                             }
-                            u |= ((unsigned)(int)t & 255u) << (8 * r);
+                            tv[r] = t;
                         }
+                        const unsigned u = pack_low_bytes(tv[0], tv[1], tv[2], tv[3]);
                         if (!pool || (l32 & 3) == 0)
                             *(unsigned*)(tb8 + i8t_write_off(pool ? l32 >> 2 : l32, f * 2 + (q >> 1), (q & 1) * 2 + lhi)) = u;
                     }
@@ -3188,18 +3201,17 @@ __global__ __launch_bounds__(DLF_C3S_WAVES * 64, 1) void k_c3s(const DlfC3sArgs 
                 const int wrow = pool ? ((l32 >> 4) << 2) + ((l32 & 7) >> 1) : l32;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    unsigned u = 0;
+                    float tv[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        float t = __builtin_fmaf((float)acc[p][q * 4 + r], scv[q][r], biasv[q][r]);
-                        t = __builtin_rintf(t);
-                        t = __builtin_fminf(__builtin_fmaxf(t, lo), 127.0f);
+                        float t = requant_biased(acc[p][q * 4 + r], scv[q][r], biasv[q][r], lo);
                         if (pool) {
                             t = __builtin_fmaxf(t, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, t), 0xB1, 0xF, 0xF, true)));
                             t = __builtin_fmaxf(t, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, t), 0x128, 0xF, 0xF, true)));
                         }
-                        u |= ((unsigned)(int)t & 255u) << (8 * r);
+                        tv[r] = t;
                     }
+                    const unsigned u = pack_low_bytes(tv[0], tv[1], tv[2], tv[3]);
                     if (!pool || (l32 & 9) == 0)
                         *(unsigned*)(tb8 + wrow * 32 + ((((q >> 1) ^ (wrow >> 2)) & 1) << 4) + (((((q & 1) * 2 + lhi) ^ (wrow >> 3)) & 3) << 2)) = u;
                 }
