@@ -590,6 +590,7 @@ def main():
             del sr
         i8 = bench_i8(side_steps, min(args.warmup, 10), cpu=False, layers=[I8_LAYERS[2]])
         extra["i8_conv3x3_256_56x56_b16"] = i8[I8_LAYERS[2][0]]
+        extra["i8_vgg16_body_b16"] = bench_i8_vgg_body(side_steps, min(args.warmup, 10))
 
     cpu = None
     if not args.no_cpu:
