@@ -34,7 +34,8 @@ def _kernels(asm):
     names = re.findall(r"^\s*\.amdhsa_kernel\s+(\S+)", asm, flags=re.M)
     out = {}
     for n in names:
-        m = re.search(r"^%s:.*?s_endpgm" % re.escape(n), asm, flags=re.M | re.S)
+        # the whole function: a kernel with early exits has more than one s_endpgm
+        m = re.search(r"^%s:.*?^\.Lfunc_end\d+:" % re.escape(n), asm, flags=re.M | re.S)
         assert m is not None, n
         out[n] = m.group(0)
     return out
@@ -61,3 +62,17 @@ def test_no_kernel_spills_to_scratch(kernel_asm):
     assert sizes
     for name, size in sizes:
         assert int(size) == 0, "%s uses %s bytes of scratch memory per lane" % (name, size)
+
+
+def test_quantised_kernels_multiply_on_the_int8_matrix_instruction(kernel_asm):
+    """The quantised forms of the block, pointwise-block and small-map kernels issue
+    v_mfma_i32_32x32x32_i8 and no fp16 matrix instruction; their fp16 twins the reverse."""
+    ks = _kernels(kernel_asm)
+    quant = [n for n in ks if re.search(r"k_c3bILi\d+ELi\d+ELi\d+ELb1E|k_pwbILi\d+ELi\d+ELb0ELb1E|k_c3sILi\d+ELi\d+ELi\d+ELb1E", n)]
+    assert len(quant) == 5 + 2 + 4, quant
+    for n in quant:
+        assert "v_mfma_i32_32x32x32_i8" in ks[n] and "v_mfma_f32_32x32x16_f16" not in ks[n], n
+    twins = [n for n in ks if re.search(r"k_c3bILi\d+ELi\d+ELi\d+ELb0E|k_pwbILi\d+ELi\d+ELb\dELb0E|k_c3sILi\d+ELi\d+ELi\d+ELb0E", n)]
+    assert len(twins) == 5 + 4 + 6, twins
+    for n in twins:
+        assert "v_mfma_f32_32x32x16_f16" in ks[n] and "v_mfma_i32" not in ks[n], n
